@@ -1,0 +1,278 @@
+"""Pins for the CPU oracle: closed-form spectra, invariants, brute force and mutual agreement.
+
+No value here comes from the HIP path.  Closed forms (normalized Laplacian L = I - D^-1/2 W D^-1/2):
+  ring C_n (unit weights):        lambda_j = 1 - cos(2 pi j / n), j = 0..n-1
+  path P_n:                       lambda_j = 1 - cos(pi j / (n-1)), eigenvector D^1/2 u, u_i = cos(pi j i/(n-1))
+  complete K_n:                   {0, n/(n-1) x (n-1)}
+  complete bipartite K_{a,b}:     {0, 1 x (n-2), 2}
+  hypercube Q_d:                  2 i / d with multiplicity C(d, i)
+  disjoint union:                 multiset union; c components -> c zeros with eigenvectors
+                                  D^1/2 1_C / sqrt(vol C)   (vol as in Section II)
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import laplacian, dense, lanczos, components, compare
+from paper_1802_04450_amd import workloads as wl
+
+
+def ring_spectrum(n):
+    return np.sort(1.0 - np.cos(2.0 * np.pi * np.arange(n) / n))
+
+
+def path_spectrum(n):
+    return np.sort(1.0 - np.cos(np.pi * np.arange(n) / (n - 1)))
+
+
+def hypercube_spectrum(d):
+    out = []
+    for i in range(d + 1):
+        out += [2.0 * i / d] * math.comb(d, i)
+    return np.array(sorted(out))
+
+
+# ------------------------------------------------------------------ operator / definitions
+def test_degrees_and_operator_by_hand():
+    # triangle 0-1 (w=1), 1-2 (w=2), 0-2 (w=3): d = (4, 3, 5)
+    g = wl.symmetric_from_edges([0, 1, 0], [1, 2, 2], [1.0, 2.0, 3.0], 3)
+    rp, c, v, n = g
+    assert np.allclose(laplacian.degrees(rp, c, v), [4.0, 3.0, 5.0])
+    s = laplacian.inv_sqrt_degrees(rp, c, v)
+    assert np.allclose(s, [0.5, 1 / math.sqrt(3), 1 / math.sqrt(5)])
+    x = np.array([1.0, -2.0, 0.5])
+    w = np.array([[0, 1, 3], [1, 0, 2], [3, 2, 0]], dtype=float)
+    expect = s * (w @ (s * x))
+    assert np.allclose(laplacian.apply_s(rp, c, v, x), expect, rtol=0, atol=1e-15)
+    op = laplacian.NormalizedOperator(rp, c, v)
+    assert np.allclose(op(x), expect, rtol=0, atol=1e-15)
+    lap = laplacian.dense_laplacian(rp, c, v)
+    assert np.allclose(lap, np.eye(3) - np.diag(s) @ w @ np.diag(s), atol=1e-15)
+    # a transposed operand or a dropped scaling breaks symmetry / the unit diagonal
+    assert np.allclose(lap, lap.T, atol=1e-15) and np.allclose(np.diag(lap), 1.0)
+
+
+def test_operator_matches_dense_on_random_graph_and_blocks():
+    rp, c, v, n = wl.random_weighted_connected(200, 600, seed=3)
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((n, 5))
+    sd = laplacian.dense_s(rp, c, v)
+    assert np.allclose(laplacian.apply_s(rp, c, v, x), sd @ x, atol=1e-13)
+    assert np.allclose(laplacian.NormalizedOperator(rp, c, v)(x), sd @ x, atol=1e-13)
+
+
+def test_zero_degree_rejected():
+    rp = np.array([0, 1, 1, 2], dtype=np.int64)  # node 1 has no entries
+    c = np.array([2, 0], dtype=np.int32)
+    v = np.array([1.0, 1.0])
+    with pytest.raises(ValueError):
+        laplacian.inv_sqrt_degrees(rp, c, v)
+
+
+# ------------------------------------------------------------------ dense oracle vs closed forms
+@pytest.mark.parametrize("n", [5, 12, 31])
+def test_dense_ring(n):
+    lam, _ = dense.full_spectrum(*wl.ring(n)[:3])
+    assert np.allclose(lam, ring_spectrum(n), atol=1e-13)
+
+
+@pytest.mark.parametrize("n", [2, 7, 40])
+def test_dense_path_values_and_vectors(n):
+    rp, c, v, _ = wl.path(n)
+    lam, vec = dense.full_spectrum(rp, c, v)
+    assert np.allclose(lam, path_spectrum(n), atol=1e-13)
+    d = laplacian.degrees(rp, c, v)
+    i = np.arange(n)
+    for j in range(n):                      # all simple: per-vector check up to sign
+        u = np.sqrt(d) * np.cos(np.pi * j * i / (n - 1))
+        u /= np.linalg.norm(u)
+        assert abs(abs(u @ vec[:, j]) - 1.0) < 1e-10
+
+
+def test_dense_complete_and_bipartite_and_hypercube():
+    lam, _ = dense.full_spectrum(*wl.complete(9)[:3])
+    assert np.allclose(lam, [0.0] + [9.0 / 8.0] * 8, atol=1e-13)
+    lam, _ = dense.full_spectrum(*wl.complete_bipartite(3, 5)[:3])
+    assert np.allclose(lam, [0.0] + [1.0] * 6 + [2.0], atol=1e-13)
+    lam, _ = dense.full_spectrum(*wl.hypercube(4)[:3])
+    assert np.allclose(lam, hypercube_spectrum(4), atol=1e-13)
+
+
+def test_dense_invariants_trace_frobenius_range_scaling_relabel():
+    g = wl.random_weighted_connected(150, 500, seed=11)
+    rp, c, v, n = g
+    lam, vec = dense.full_spectrum(rp, c, v)
+    assert lam.min() > -1e-13 and lam.max() < 2.0 + 1e-13
+    assert abs(lam.sum() - n) < 1e-10                         # trace(L) = n without self loops
+    d = laplacian.degrees(rp, c, v)
+    rows = laplacian.row_index(rp)
+    fro = n + np.sum(v * v / (d[rows] * d[c]))
+    assert abs(np.sum(lam * lam) - fro) < 1e-9                 # ||L||_F^2
+    assert compare.orthonormality_defect(vec) < 1e-12
+    lam2, _ = dense.full_spectrum(rp, c, 37.5 * v)             # W -> cW leaves L unchanged
+    assert np.allclose(lam, lam2, atol=1e-13)
+    perm = np.random.default_rng(5).permutation(n)
+    lam3, _ = dense.full_spectrum(*wl.relabel(g, perm)[:3])
+    assert np.allclose(lam, lam3, atol=1e-12)
+
+
+def test_dense_disjoint_union_null_space():
+    g = wl.disjoint_union(wl.ring(7), wl.path(5), wl.complete(4), wl.random_weighted_connected(30, 60, 2))
+    rp, c, v, n = g
+    lam, vec = dense.smallest_eigenpairs(rp, c, v, 4)
+    assert np.allclose(lam, 0.0, atol=1e-13)
+    basis = components.null_space(rp, c, v)
+    assert basis.shape == (n, 4)
+    assert compare.orthonormality_defect(basis) < 1e-14
+    assert np.max(compare.principal_angles(vec, basis)) < 1e-7
+    # the closed-form vectors really are null vectors of L
+    assert np.max(compare.residual_norms(rp, c, v, np.zeros(4), basis)) < 1e-14
+    full, _ = dense.full_spectrum(rp, c, v)
+    expect = np.sort(np.concatenate([ring_spectrum(7), path_spectrum(5), [0.0] + [4 / 3] * 3,
+                                     dense.full_spectrum(*wl.random_weighted_connected(30, 60, 2)[:3])[0]]))
+    assert np.allclose(full, expect, atol=1e-12)
+
+
+# ------------------------------------------------------------------ Lanczos oracle
+def _check_pairs(g, lam, vec, lam_true, tol_val=1e-9, tol_res=1e-7):
+    rp, c, v, n = g
+    assert np.allclose(lam, lam_true[: lam.size], atol=tol_val), (lam, lam_true[: lam.size])
+    assert compare.orthonormality_defect(vec) < 1e-10
+    assert np.max(compare.residual_norms(rp, c, v, lam, vec)) < tol_res
+
+
+def test_lanczos_path_simple_spectrum():
+    g = wl.path(60)
+    lam, vec, info = lanczos.lanczos_smallest(*g[:3], k=5, tol=1e-10, seed=1, return_info=True)
+    _check_pairs(g, lam, vec, path_spectrum(60))
+    assert info["converged"]
+
+
+def test_lanczos_ring_multiplicity_two():
+    g = wl.ring(50)
+    lam, vec = lanczos.lanczos_smallest(*g[:3], k=5, tol=1e-10, seed=2)
+    _check_pairs(g, lam, vec, ring_spectrum(50))                # 0, then two double eigenvalues
+
+
+def test_lanczos_hypercube_high_multiplicity():
+    d = 6
+    g = wl.hypercube(d)
+    lam, vec = lanczos.lanczos_smallest(*g[:3], k=1 + d, tol=1e-10, seed=3)
+    _check_pairs(g, lam, vec, hypercube_spectrum(d))            # 0 and 2/d with multiplicity d
+
+
+def test_lanczos_complete_and_bipartite_breakdown_and_negative_end():
+    g = wl.complete(12)
+    lam, vec = lanczos.lanczos_smallest(*g[:3], k=4, tol=1e-10, seed=4)
+    _check_pairs(g, lam, vec, np.array([0.0] + [12 / 11] * 11))
+    g = wl.complete_bipartite(4, 7)
+    lam, vec = lanczos.lanczos_smallest(*g[:3], k=3, tol=1e-10, seed=5)
+    _check_pairs(g, lam, vec, np.array([0.0] + [1.0] * 9 + [2.0]))   # theta = -1 must not be picked
+
+
+def test_lanczos_components_give_zeros_with_indicator_vectors():
+    parts = [wl.ring(9), wl.ring(14), wl.path(11), wl.random_weighted_connected(40, 80, 7), wl.complete(6)]
+    g = wl.disjoint_union(*parts)
+    rp, c, v, n = g
+    lam, vec = lanczos.lanczos_smallest(rp, c, v, k=5, tol=1e-10, seed=6)
+    assert np.max(np.abs(lam)) < 1e-12
+    basis = components.null_space(rp, c, v)
+    assert np.max(compare.principal_angles(vec, basis)) < 1e-8
+    # one more than the number of components: the sixth is the smallest nonzero of any part
+    lam6, vec6 = lanczos.lanczos_smallest(rp, c, v, k=7, tol=1e-10, seed=6)
+    full, _ = dense.full_spectrum(rp, c, v)
+    _check_pairs(g, lam6, vec6, full)
+
+
+def test_lanczos_matches_dense_on_mixture_graph_and_is_seed_independent():
+    cfg = wl.reduced(wl.CONFIGS[1], n=600, components=5, k=8, m=24)
+    g, label, _ = wl.build_config_graph(cfg, device="cpu")
+    rp, c, v, n = g
+    ncomp, _ = components.component_labels(rp, c, v)
+    full, fvec = dense.full_spectrum(rp, c, v)
+    assert np.sum(full < 1e-12) == ncomp
+    for seed in (0, 1):
+        lam, vec, info = lanczos.lanczos_smallest(rp, c, v, k=8, tol=1e-10, m=24, seed=seed, return_info=True)
+        _check_pairs(g, lam, vec, full)
+        assert info["converged"]
+    # thick restarts were exercised (basis budget 24 is far below the steps needed)
+    assert info["cycles"] > info["phases"]
+
+
+def test_lanczos_maxiter_reports_not_converged():
+    g = wl.random_weighted_connected(300, 900, seed=9)
+    lam, vec, info = lanczos.lanczos_smallest(*g[:3], k=6, tol=1e-12, m=12, seed=0, maxiter=1, return_info=True)
+    assert not info["converged"]
+
+
+# ------------------------------------------------------------------ component oracle
+def test_component_oracle_matches_dense_beyond_the_zeros():
+    parts = [wl.ring(9), wl.path(11), wl.random_weighted_connected(40, 80, 7), wl.hypercube(3)]
+    g = wl.disjoint_union(*parts)
+    perm = np.random.default_rng(1).permutation(g[3])
+    g = wl.relabel(g, perm)                                       # components interleaved
+    rp, c, v, n = g
+    full, _ = dense.full_spectrum(rp, c, v)
+    for k in (3, 4, 9):
+        lam, vec = components.smallest_eigenpairs(rp, c, v, k)
+        assert np.allclose(lam, full[:k], atol=1e-12)
+        assert compare.orthonormality_defect(vec) < 1e-10
+        assert np.max(compare.residual_norms(rp, c, v, lam, vec)) < 1e-10
+    lam, vec = components.smallest_eigenpairs(rp, c, v, 6, dense_limit=20)   # forces the Lanczos branch
+    assert np.allclose(lam, full[:6], atol=1e-9)
+
+
+def test_planted_mistake_is_caught_by_the_pins():
+    """The pins are sharp enough: dropping the second scaling (S -> D^-1 W D^0 ... i.e. the
+    random-walk matrix applied as if symmetric) or the shift lambda = 1 - theta changes the ring /
+    path numbers by far more than the tolerances used above."""
+    rp, c, v, n = wl.path(7)
+    s = laplacian.inv_sqrt_degrees(rp, c, v)
+    w = np.zeros((n, n))
+    w[laplacian.row_index(rp), c] = v
+    wrong = np.eye(n) - (s * s)[:, None] * w                       # D^-1 W: not symmetric
+    lam_wrong = np.sort(np.linalg.eigvalsh(0.5 * (wrong + wrong.T)))
+    assert np.max(np.abs(lam_wrong - path_spectrum(n))) > 1e-3
+
+
+# ------------------------------------------------------------------ comparison utilities
+def test_principal_angles_and_containment_known_values():
+    e = np.eye(4)
+    a = e[:, :2]
+    t = 1e-6
+    b = np.stack([e[:, 0], math.cos(t) * e[:, 1] + math.sin(t) * e[:, 2]], axis=1)
+    ang = compare.principal_angles(a, b)
+    assert abs(ang[-1] - t) < 1e-12 and ang[0] < 1e-12
+    assert np.allclose(compare.containment_defect(b, e[:, :3]), 0.0, atol=1e-15)
+    assert abs(compare.containment_defect(b, a)[1] - math.sin(t)) < 1e-15
+
+
+def test_separated_clusters():
+    lam = np.array([0.0, 0.0, 1e-12, 0.3, 0.3000001, 0.5])
+    runs = compare.separated_clusters(lam, 5, r_sum=1e-9)
+    assert runs == [(0, 3), (3, 5)]
+    runs = compare.separated_clusters(lam, 4, r_sum=1e-9)          # k cuts the (0.3, 0.3000001) pair
+    assert runs == [(0, 3)]
+
+
+# ------------------------------------------------------------------ the tiny benchmark workload
+def test_config1_full_size_three_oracles_agree():
+    """n = 2000, 8 mixture components: 8 zero eigenvalues (union-find count), indicator null space,
+    Lanczos oracle == dense definition == component oracle."""
+    cfg = wl.CONFIGS[1]
+    g, label, _ = wl.build_config_graph(cfg, device="cpu")
+    rp, c, v, n = g
+    ncomp, _ = components.component_labels(rp, c, v)
+    assert ncomp == cfg.components == 8
+    full, fvec = dense.full_spectrum(rp, c, v)
+    assert np.sum(np.abs(full) < 1e-12) == 8 and full[8] > 0.05
+    lam, vec, info = lanczos.lanczos_smallest(rp, c, v, k=8, tol=cfg.tol, seed=0, return_info=True)
+    assert info["converged"] and np.max(np.abs(lam)) < 1e-12
+    basis = components.null_space(rp, c, v)
+    assert np.max(compare.principal_angles(vec, basis)) < 1e-7
+    assert np.max(compare.principal_angles(fvec[:, :8], basis)) < 1e-7
+    lam10, vec10 = lanczos.lanczos_smallest(rp, c, v, k=10, tol=cfg.tol, seed=1)
+    assert np.allclose(lam10, full[:10], atol=1e-10)
+    lamc, vecc = components.smallest_eigenpairs(rp, c, v, 10)
+    assert np.allclose(lamc, full[:10], atol=1e-11)
