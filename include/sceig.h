@@ -1,0 +1,172 @@
+/*
+ * sceig - eigensolver for the symmetric normalized Laplacian of a sparse similarity graph,
+ *         single AMD MI355X (gfx950), C ABI.
+ *
+ * Problem (paper Section II Steps 2-3, Section IV-B first paragraph): given a sparse symmetric
+ * similarity matrix W (w_ij >= 0) with degrees D_ii = sum_j W_ij > 0 and a number k, return the k
+ * eigenvectors belonging to the k smallest eigenvalues of the normalized Laplacian.  Section IV-B
+ * switches to the k largest eigenvalues of the degree-normalized matrix; this library does the
+ * same with the symmetric form S = D^-1/2 W D^-1/2 (similar to D^-1 W, so the eigenvalues are the
+ * same) and reports lambda = 1 - theta for L = I - S.
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device memory of the current device, owned by the caller; the library
+ *     never frees or keeps them.  Inputs are const and never modified.  "host" pointers are ordinary
+ *     host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device work is
+ *     enqueued on it; every call returns after that work has completed (stream synchronised).
+ *   - Return value: 0 = SC_OK; > 0 = soft condition, outputs are valid as described; < 0 = error,
+ *     outputs are unspecified.  No C++ exception crosses this boundary.
+ *   - CSR: rowptr int64[n+1] with rowptr[0] = 0, non-decreasing, rowptr[n] = nnz; col int32[nnz] in
+ *     [0, n); val fp64[nnz].  Columns need not be sorted; duplicate entries add up.  W must be
+ *     symmetric (not checked).  Self loops are allowed and count towards the degree.
+ *   - Dense blocks handed to the kernel-level entry points are ROW-MAJOR: element (i, c) of an
+ *     n x ncols block with leading dimension ld lives at base[i * ld + c].  The final eigenvector
+ *     output of sc_laplacian_eigsh is COLUMN-MAJOR (vector t contiguous at evecs_out + t * n).
+ *   - Calls that use the same stream or the same buffers must not overlap.
+ */
+#ifndef SCEIG_H
+#define SCEIG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SC_OK 0
+#define SC_NOT_CONVERGED 1 /* maxiter reached; outputs hold the best k Ritz pairs, stats->nconv met tol */
+#define SC_EINVAL (-1)     /* null pointer, negative size */
+#define SC_EDOMAIN (-2)    /* k < 1, k >= n, m out of range, block not supported, tol < 0 */
+#define SC_ECSR (-3)       /* malformed CSR (rowptr not monotone, rowptr[0] != 0, column out of range) */
+#define SC_EZERODEG (-4)   /* a row whose degree is <= 0 or not finite (Section IV-B: remove isolated nodes first) */
+#define SC_ENOMEM (-5)     /* device or host allocation failed */
+#define SC_EHIP (-6)       /* a HIP runtime call failed */
+
+#define SC_FLAG_NO_VERIFY 1u /* skip the final deflated check phase (see sc_laplacian_eigsh) */
+
+/* Options; every field 0 = default. */
+typedef struct sc_options {
+  int32_t m;      /* budget of basis columns (locked + active Krylov vectors), the "number m of Lanczos
+                     vectors" of Section IV-B; default min(n, max(2k, k + 24)); needs k + 3*block <= m <= n
+                     (the library lowers `block` to fit when block is defaulted) */
+  int32_t block;  /* Lanczos block size b in {1,2,4,8,16,32}; default chosen from k and m */
+  int32_t check_every; /* block steps between convergence checks of the projected problem; default 2 */
+  uint32_t flags; /* SC_FLAG_* */
+  uint64_t seed;  /* seed of the start / re-injection blocks */
+} sc_options;
+
+typedef struct sc_stats {
+  int32_t nconv;      /* wanted pairs whose residual estimate met tol */
+  int32_t phases;     /* random (re-)starts */
+  int32_t restarts;   /* thick restarts */
+  int32_t block;      /* block size used */
+  int32_t m;          /* basis budget used */
+  int32_t host_eigs;  /* projected eigenproblems solved on the host */
+  int64_t block_steps;
+  int64_t spmv_cols;  /* columns multiplied by S in total */
+  double t_total;     /* seconds, whole call */
+  double t_host_eig;  /* seconds in the host projected eigenproblems */
+  double t_setup;     /* seconds: validation, degrees, allocation */
+  double max_residual_est; /* largest residual estimate among the returned pairs */
+} sc_stats;
+
+/*
+ * The hot path (Algorithm 3 re-designed GPU-resident): k smallest eigenpairs of
+ * L = I - D^-1/2 W D^-1/2, counted with multiplicity.
+ *
+ *   csr_rowptr, csr_col, csr_val  device, CSR of W as described above
+ *   n, k                          1 <= k < n
+ *   tol                           a Ritz pair counts as converged when its residual estimate
+ *                                 ||S x - theta x||_2 <= tol   (||S||_2 = 1); tol >= 0
+ *   maxiter                       upper bound on restart cycles (phase starts + thick restarts); >= 1
+ *   evals_out                     device, fp64[k], ascending eigenvalues of L
+ *   evecs_out                     device, fp64[n*k], column-major, orthonormal eigenvectors of L
+ *                                 (v = D^1/2 u for the eigenvectors u of the paper's D^-1 L)
+ *   opt, stats                    host, may be NULL
+ *
+ * Method: block Lanczos with full reorthogonalization (classical Gram-Schmidt applied twice against
+ * all locked and active basis vectors), thick restart, locking, and re-injection of a fresh random
+ * block after every lock so that multiple eigenvalues are found with their multiplicity; once k pairs
+ * are locked one further deflated phase must find nothing better (skipped under SC_FLAG_NO_VERIFY);
+ * a final Rayleigh-Ritz step over the locked vectors produces the outputs.  Only the projected
+ * eigenproblems (size <= m) run on the host.
+ *
+ * Returns SC_OK, SC_NOT_CONVERGED, or an error (< 0).
+ */
+int sc_laplacian_eigsh(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n, int32_t k,
+                       double tol, int32_t maxiter, double* evals_out, double* evecs_out, void* stream,
+                       const sc_options* opt, sc_stats* stats);
+
+/*
+ * Setup step (Algorithm 2 steps 1-2, with the scaling kept as a vector instead of a scaled copy of W):
+ * d_i = sum_j W_ij and s_i = d_i^-1/2.   d_out, s_out: device fp64[n] (d_out may be NULL).
+ * Returns SC_EZERODEG if some d_i is <= 0 or not finite (outputs then hold what was computed).
+ */
+int sc_degree_scaling(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n,
+                      double* d_out, double* s_out, void* stream);
+
+/*
+ * The sparse product of Algorithm 3's loop body with the degree scaling fused in:
+ *   Y = diag(s) W diag(s) X   for an n x ncols block, ncols in {1,2,4,8,16,32}.
+ *   s     device fp64[n] (from sc_degree_scaling)
+ *   x     device, row-major n x ncols, leading dimension ldx >= ncols
+ *   y     device, row-major n x ncols, leading dimension ldy >= ncols; must not alias x
+ *   work  device fp64[n*ncols] scratch (holds diag(s) X packed); may be NULL, then it is allocated
+ *         and freed inside the call
+ * CSR columns are NOT range-checked here (sc_validate_csr does that).
+ */
+int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, const double* s,
+                       int64_t n, const double* x, int64_t ldx, double* y, int64_t ldy, int32_t ncols, double* work,
+                       void* stream);
+
+/* Structural check of a device CSR: SC_OK or SC_ECSR. */
+int sc_validate_csr(const int64_t* csr_rowptr, const int32_t* csr_col, int64_t n, void* stream);
+
+/*
+ * One reorthogonalization of the Lanczos recurrence (inside TakeStep of Algorithm 3): classical
+ * Gram-Schmidt applied twice to the block W = basis[:, j : j+b] against Q = basis[:, 0 : j]:
+ *   H1 = Q^T W, W -= Q H1, H2 = Q^T W, W -= Q H2, h_out = H1 + H2.
+ *   basis  device, row-major n x ld, ld >= j + b; columns j..j+b-1 are updated in place
+ *   h_out  device fp64[j*b], row-major j x b (may be NULL)
+ *   1 <= b <= 32, j >= 0.
+ */
+int sc_cgs2(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, double* h_out, void* stream);
+
+/*
+ * Orthonormalization of the block W = basis[:, j : j+b] by Cholesky QR applied twice: W = Q R.
+ * Columns that are numerically dependent on the columns before them (or zero) become exactly
+ * zero columns of Q and zero rows of R.
+ *   r_out  device fp64[b*b] row-major upper triangular R (may be NULL)
+ *   g_out  device fp64[b*b] Gram matrix W^T W of the block before orthonormalization (may be NULL)
+ */
+int sc_block_qr(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, double* r_out, double* g_out,
+                void* stream);
+
+/*
+ * Restart rotation / Ritz vectors (FindEigenvectors of Algorithm 3): out = basis[:, j0 : j0+ja] * Y.
+ *   y       device fp64[ja*l], row-major ja x l
+ *   out     device; if out_colmajor == 0 row-major n x l with leading dimension ldo >= l,
+ *           else column-major (column t contiguous at out + t*ldo, ldo >= n); must not alias basis
+ */
+int sc_rotate(const double* basis, int64_t n, int64_t ld, int32_t j0, int32_t ja, const double* y, int32_t l,
+              double* out, int64_t ldo, int32_t out_colmajor, void* stream);
+
+/*
+ * Projected eigenproblem (the m x m eigendecomposition of Section IV-B), HOST ONLY, no GPU needed:
+ * all eigenpairs of a dense symmetric matrix.
+ *   a     host fp64[n*n], symmetric, row-major (only read)
+ *   w     host fp64[n], eigenvalues ascending
+ *   z     host fp64[n*n], row-major, column t (z[i*n+t]) is the eigenvector of w[t]; may be NULL
+ * Returns SC_OK, SC_EINVAL, SC_ENOMEM, or SC_NOT_CONVERGED if the QL iteration failed.
+ */
+int sc_sym_eig(const double* a, int32_t n, double* w, double* z);
+
+const char* sc_strerror(int code);
+int sc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCEIG_H */

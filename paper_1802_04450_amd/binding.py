@@ -1,0 +1,210 @@
+"""ctypes binding of libsceig.so (include/sceig.h): argument marshalling only.
+
+Device buffers are torch CUDA(HIP) tensors; their ``data_ptr()`` and the current torch stream are
+handed to the library.  Nothing here computes: if the library is missing, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsceig.so")
+
+SC_OK, SC_NOT_CONVERGED = 0, 1
+SC_EINVAL, SC_EDOMAIN, SC_ECSR, SC_EZERODEG, SC_ENOMEM, SC_EHIP = -1, -2, -3, -4, -5, -6
+SC_FLAG_NO_VERIFY = 1
+
+EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_cgs2",
+           "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_strerror", "sc_version"]
+
+
+class ScOptions(ctypes.Structure):
+    _fields_ = [("m", ctypes.c_int32), ("block", ctypes.c_int32), ("check_every", ctypes.c_int32),
+                ("flags", ctypes.c_uint32), ("seed", ctypes.c_uint64)]
+
+
+class ScStats(ctypes.Structure):
+    _fields_ = [("nconv", ctypes.c_int32), ("phases", ctypes.c_int32), ("restarts", ctypes.c_int32),
+                ("block", ctypes.c_int32), ("m", ctypes.c_int32), ("host_eigs", ctypes.c_int32),
+                ("block_steps", ctypes.c_int64), ("spmv_cols", ctypes.c_int64), ("t_total", ctypes.c_double),
+                ("t_host_eig", ctypes.c_double), ("t_setup", ctypes.c_double), ("max_residual_est", ctypes.c_double)]
+
+    def as_dict(self) -> dict:
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
+class ScError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"sceig error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the built library (build it first with ``python -m paper_1802_04450_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_1802_04450_amd.build`")
+        _lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
+        _lib.sc_laplacian_eigsh.argtypes = [vp, vp, vp, i64, i32, dbl, i32, vp, vp, vp, ctypes.POINTER(ScOptions),
+                                            ctypes.POINTER(ScStats)]
+        _lib.sc_degree_scaling.argtypes = [vp, vp, vp, i64, vp, vp, vp]
+        _lib.sc_spmm_normalized.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, i64, i32, vp, vp]
+        _lib.sc_validate_csr.argtypes = [vp, vp, i64, vp]
+        _lib.sc_cgs2.argtypes = [vp, i64, i64, i32, i32, vp, vp]
+        _lib.sc_block_qr.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
+        _lib.sc_rotate.argtypes = [vp, i64, i64, i32, i32, vp, i32, vp, i64, i32, vp]
+        _lib.sc_sym_eig.argtypes = [vp, i32, vp, vp]
+        for name in EXPORTS:
+            getattr(_lib, name).restype = ctypes.c_int
+        _lib.sc_strerror.restype = ctypes.c_char_p
+        _lib.sc_strerror.argtypes = [ctypes.c_int]
+        _lib.sc_version.argtypes = []
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().sc_strerror(code).decode()
+
+
+def _check(code: int, soft_ok: bool = True) -> int:
+    if code < 0 or (code > 0 and not soft_ok):
+        raise ScError(code, strerror(code))
+    return code
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _dev(t, dtype):
+    import torch
+    assert t.is_cuda and t.is_contiguous() and t.dtype == dtype, (t.device, t.dtype, t.is_contiguous())
+    return t
+
+
+def csr_to_device(rowptr: np.ndarray, col: np.ndarray, val: np.ndarray, device="cuda:0"):
+    """Host CSR arrays -> (rowptr int64, col int32, val fp64) device tensors."""
+    import torch
+    return (torch.from_numpy(np.ascontiguousarray(rowptr, dtype=np.int64)).to(device),
+            torch.from_numpy(np.ascontiguousarray(col, dtype=np.int32)).to(device),
+            torch.from_numpy(np.ascontiguousarray(val, dtype=np.float64)).to(device))
+
+
+# ----------------------------------------------------------------------------------------------
+def sc_laplacian_eigsh(rowptr, col, val, k: int, tol: float, maxiter: int = 100000, m: int = 0, block: int = 0,
+                       check_every: int = 0, flags: int = 0, seed: int = 0):
+    """Returns (evals[k] device, evecs (k, n) device - row t is eigenvector t, i.e. the library's
+    column-major n x k output -, status code, stats dict)."""
+    import torch
+    n = rowptr.numel() - 1
+    _dev(rowptr, torch.int64), _dev(col, torch.int32), _dev(val, torch.float64)
+    evals = torch.empty(max(k, 0), dtype=torch.float64, device=rowptr.device)
+    evecs = torch.empty((max(k, 0), n), dtype=torch.float64, device=rowptr.device)
+    opt = ScOptions(m=m, block=block, check_every=check_every, flags=flags, seed=seed)
+    stats = ScStats()
+    with torch.cuda.device(rowptr.device):
+        code = lib().sc_laplacian_eigsh(_ptr(rowptr), _ptr(col), _ptr(val), n, k, tol, maxiter, _ptr(evals),
+                                        _ptr(evecs), _stream(), ctypes.byref(opt), ctypes.byref(stats))
+    _check(code)
+    return evals, evecs, code, stats.as_dict()
+
+
+def sc_degree_scaling(rowptr, col, val, want_degrees: bool = True):
+    import torch
+    n = rowptr.numel() - 1
+    d = torch.empty(n, dtype=torch.float64, device=rowptr.device) if want_degrees else None
+    s = torch.empty(n, dtype=torch.float64, device=rowptr.device)
+    with torch.cuda.device(rowptr.device):
+        code = lib().sc_degree_scaling(_ptr(rowptr), _ptr(col), _ptr(val), n, _ptr(d), _ptr(s), _stream())
+    _check(code)
+    return d, s
+
+
+def sc_validate_csr(rowptr, col) -> int:
+    import torch
+    n = rowptr.numel() - 1
+    with torch.cuda.device(rowptr.device):
+        return lib().sc_validate_csr(_ptr(rowptr), _ptr(col), n, _stream())
+
+
+def sc_spmm_normalized(rowptr, col, val, s, x, y=None, work=None):
+    """x: (n, ncols) row-major device tensor (a 1-D tensor is one column).  Returns y of the same shape."""
+    import torch
+    n = rowptr.numel() - 1
+    x2 = x.reshape(n, -1)
+    ncols = x2.shape[1]
+    if y is None:
+        y = torch.empty_like(x2)
+    y2 = y.reshape(n, -1)
+    with torch.cuda.device(rowptr.device):
+        code = lib().sc_spmm_normalized(_ptr(rowptr), _ptr(col), _ptr(val), _ptr(s), n, _ptr(x2), x2.stride(0),
+                                        _ptr(y2), y2.stride(0), ncols, _ptr(work), _stream())
+    _check(code)
+    return y.reshape(x.shape)
+
+
+def sc_cgs2(basis, j: int, b: int, want_h: bool = True):
+    """basis: (n, ld) row-major device tensor, columns j..j+b-1 updated in place.  Returns H (j, b) or None."""
+    import torch
+    n, ld = basis.shape
+    h = torch.zeros((j, b), dtype=torch.float64, device=basis.device) if want_h else None
+    with torch.cuda.device(basis.device):
+        code = lib().sc_cgs2(_ptr(basis), n, basis.stride(0), j, b, _ptr(h), _stream())
+    _check(code)
+    return h
+
+
+def sc_block_qr(basis, j: int, b: int):
+    """In-place Cholesky-QR (twice) of columns j..j+b-1.  Returns (R (b, b), G (b, b))."""
+    import torch
+    n, ld = basis.shape
+    r = torch.zeros((b, b), dtype=torch.float64, device=basis.device)
+    g = torch.zeros((b, b), dtype=torch.float64, device=basis.device)
+    with torch.cuda.device(basis.device):
+        code = lib().sc_block_qr(_ptr(basis), n, basis.stride(0), j, b, _ptr(r), _ptr(g), _stream())
+    _check(code)
+    return r, g
+
+
+def sc_rotate(basis, j0: int, ja: int, y, out_colmajor: bool = False):
+    """basis[:, j0:j0+ja] @ y  with y (ja, l) row-major.  Returns (n, l) row-major, or (l, n) if out_colmajor."""
+    import torch
+    n, ld = basis.shape
+    l = y.shape[1]
+    yc = y.contiguous()
+    if out_colmajor:
+        out = torch.empty((l, n), dtype=torch.float64, device=basis.device)
+        ldo = n
+    else:
+        out = torch.empty((n, l), dtype=torch.float64, device=basis.device)
+        ldo = l
+    with torch.cuda.device(basis.device):
+        code = lib().sc_rotate(_ptr(basis), n, basis.stride(0), j0, ja, _ptr(yc), l, _ptr(out), ldo,
+                               1 if out_colmajor else 0, _stream())
+    _check(code)
+    return out
+
+
+def sc_sym_eig(a: np.ndarray, vectors: bool = True) -> Tuple[np.ndarray, Optional[np.ndarray]]:
+    """Host projected eigenproblem: eigenvalues ascending and eigenvectors (columns) of a symmetric matrix."""
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    n = a.shape[0]
+    w = np.empty(n)
+    z = np.empty((n, n)) if vectors else None
+    code = lib().sc_sym_eig(a.ctypes.data, n, w.ctypes.data, z.ctypes.data if vectors else 0)
+    _check(code, soft_ok=False)
+    return w, z

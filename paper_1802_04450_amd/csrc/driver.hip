@@ -1,0 +1,825 @@
+// Host driver and C ABI (see include/sceig.h).
+//
+// Block Lanczos with full reorthogonalization, thick restart, locking and random re-injection for the
+// largest eigenvalues of S = D^-1/2 W D^-1/2 (Section IV-B / Algorithm 3 of the paper, moved onto the
+// GPU).  Everything of size n runs in the kernels of kernels.hip; this file only sequences them and
+// solves the small projected eigenproblems (sym_eig.cpp).
+//
+// Basis layout: one row-major buffer of n rows and ld >= m + b columns.  Columns [0, nl) hold locked
+// Ritz vectors, [nl, nl + ja) the active block-Krylov basis of the current phase, [nl + ja, nl + ja + b)
+// the block being built.  A block step never leaves the device:
+//   W = S V_last (SpMM) -> CGS2 against columns [0, nl + ja) (two MFMA projections + two MFMA updates)
+//   -> Cholesky QR twice (Gram by MFMA, b x b factorisation in one workgroup) -> next block + its
+//   scaled packed copy for the next SpMM.
+// Per step the b x b diagonal block, the QR factor R and the Gram matrix of the residual block are
+// kept in device "slots" and fetched only when the host inspects convergence.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <vector>
+
+#include "../../include/sceig.h"
+#include "kernels.h"
+#include "sym_eig.h"
+
+namespace sceig {
+namespace {
+
+struct ScError {
+  int code;
+};
+
+#define HIP_TRY(expr)                                   \
+  do {                                                  \
+    hipError_t e__ = (expr);                            \
+    if (e__ != hipSuccess) {                            \
+      (void)hipGetLastError();                          \
+      throw ScError{e__ == hipErrorOutOfMemory ? SC_ENOMEM : SC_EHIP}; \
+    }                                                   \
+  } while (0)
+
+double now_s() {
+  return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+template <typename T>
+struct DevBuf {
+  T* p = nullptr;
+  DevBuf() = default;
+  DevBuf(const DevBuf&) = delete;
+  DevBuf& operator=(const DevBuf&) = delete;
+  void alloc(size_t count) {
+    release();
+    if (count == 0) count = 1;
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p), count * sizeof(T)));
+  }
+  void release() {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+  }
+  ~DevBuf() { release(); }
+};
+
+template <typename T>
+struct PinnedBuf {
+  T* p = nullptr;
+  PinnedBuf() = default;
+  PinnedBuf(const PinnedBuf&) = delete;
+  PinnedBuf& operator=(const PinnedBuf&) = delete;
+  void alloc(size_t count) {
+    release();
+    if (count == 0) count = 1;
+    HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&p), count * sizeof(T), hipHostMallocDefault));
+  }
+  void release() {
+    if (p) (void)hipHostFree(p);
+    p = nullptr;
+  }
+  ~PinnedBuf() { release(); }
+};
+
+constexpr int kPP = kPartialPad;
+constexpr int kSlotDoubles = 3 * kPP * kPP;  // A, R, G
+constexpr int kMaxPartials = 1024;
+constexpr double kAbsDrop2 = 1e-24;  // squared norm below which a residual column counts as zero
+constexpr double kRelDrop = 1e-12;   // squared sine below which a column counts as dependent
+
+int pow2_floor(int x) {
+  int p = 1;
+  while (p * 2 <= x) p *= 2;
+  return p;
+}
+
+// CGS2 of basis[:, wcol : wcol+b] against basis[:, 0 : j]; hsum (j x b, stride kPP) = H1 + H2.
+// slot_a (may be null) receives rows [slot_row0, j) of hsum.
+void enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, double* part, double* h1, double* hsum,
+                  double* slot_a, int slot_row0, hipStream_t st) {
+  if (j <= 0) return;
+  const ProjectPlan plan = plan_project(n, j, kMaxPartials);
+  for (int pass = 0; pass < 2; ++pass) {
+    HIP_TRY(launch_project(basis, n, ld, 0, j, wcol, b, plan, part, st));
+    HIP_TRY(launch_reduce_partials(part, plan.npart, j, b, h1, hsum, pass, pass == 1 ? slot_a : nullptr, slot_row0, st));
+    HIP_TRY(launch_row_gemm(basis, n, ld, 0, j, h1, kPP, b, 0, wcol, nullptr, 0, st));
+  }
+}
+
+// Cholesky QR twice on basis[:, col : col+b].  r_out / g_out: device b x b (stride kPP) or null.
+// z (may be null): packed s-scaled copy of the orthonormalised block.
+void enqueue_block_qr(double* basis, int64_t n, int64_t ld, int col, int b, double* part, double* rinv, double* r1,
+                      double* r_out, double* g_out, double* z, const double* s, hipStream_t st) {
+  const ProjectPlan plan = plan_project(n, b, kMaxPartials);
+  HIP_TRY(launch_project(basis, n, ld, col, b, col, b, plan, part, st));
+  HIP_TRY(launch_gram_cholesky(part, plan.npart, b, g_out, rinv, r1, nullptr, kAbsDrop2, kRelDrop, st));
+  HIP_TRY(launch_apply_rinv(basis, n, ld, col, b, rinv, nullptr, nullptr, st));
+  HIP_TRY(launch_project(basis, n, ld, col, b, col, b, plan, part, st));
+  // second pass: a column that survived the first pass has unit norm, so only exact zeros are dropped
+  HIP_TRY(launch_gram_cholesky(part, plan.npart, b, nullptr, rinv, r_out, r1, 0.25, 1e-8, st));
+  HIP_TRY(launch_apply_rinv(basis, n, ld, col, b, rinv, z, s, st));
+}
+
+struct Solver {
+  // problem
+  const int64_t* rowptr;
+  const int32_t* col;
+  const double* val;
+  int64_t n, nnz;
+  int k;
+  double tol;
+  int maxiter;
+  // options
+  int m, b, check_every;
+  uint32_t flags;
+  uint64_t seed;
+  hipStream_t st;
+  // device
+  DevBuf<double> basis, s, z, part, h1, hsum, small, slots, yd, rot;
+  DevBuf<int> flag;
+  PinnedBuf<double> slots_host;
+  int64_t ld = 0;
+  int max_slots = 0;
+  size_t yd_cap = 0, rot_cols = 0;
+  double avg_deg = 0;
+  // state
+  int nl = 0;
+  std::vector<double> theta_locked, rho_locked;
+  sc_stats stats{};
+
+  double* rinv() { return small.p; }
+  double* r1() { return small.p + kPP * kPP; }
+  double* slot(int i) { return slots.p + (size_t)i * kSlotDoubles; }
+  const double* hslot(int i) const { return slots_host.p + (size_t)i * kSlotDoubles; }
+
+  void setup() {
+    const double t0 = now_s();
+    flag.alloc(1);
+    HIP_TRY(hipMemsetAsync(flag.p, 0, sizeof(int), st));
+    HIP_TRY(hipMemcpyAsync(&nnz, rowptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (nnz < 0) throw ScError{SC_ECSR};
+    HIP_TRY(launch_validate_csr(rowptr, col, n, nnz, flag.p, st));
+    int hflag = 0;
+    HIP_TRY(hipMemcpyAsync(&hflag, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (hflag & 3) throw ScError{SC_ECSR};
+    s.alloc((size_t)n);
+    HIP_TRY(launch_degree_scaling(rowptr, val, n, nullptr, s.p, flag.p, st));
+    HIP_TRY(hipMemcpyAsync(&hflag, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (hflag & 4) throw ScError{SC_EZERODEG};
+    avg_deg = (double)nnz / (double)n;
+
+    ld = ((int64_t)m + b + 15) / 16 * 16;
+    basis.alloc((size_t)n * ld);
+    z.alloc((size_t)n * b);
+    const int jmax = m + b;
+    part.alloc((size_t)kMaxPartials * jmax * kPP);
+    h1.alloc((size_t)jmax * kPP);
+    hsum.alloc((size_t)jmax * kPP);
+    small.alloc(2 * kPP * kPP);
+    max_slots = m / b + 4;
+    slots.alloc((size_t)max_slots * kSlotDoubles);
+    slots_host.alloc((size_t)max_slots * kSlotDoubles);
+    rot_cols = (size_t)std::min(m, std::max(m / 2 + b, 2 * b));
+    rot.alloc((size_t)n * rot_cols);
+    yd_cap = (size_t)(m + b) * std::max<size_t>(rot_cols, (size_t)k);
+    yd.alloc(yd_cap);
+    stats.t_setup = now_s() - t0;
+  }
+
+  // ---- one block step on the last active block (columns [nl+ja-b, nl+ja)), results into slot si
+  void enqueue_step(int ja, int si) {
+    const int jt = nl + ja;
+    HIP_TRY(launch_spmm(rowptr, col, val, s.p, n, z.p, b, basis.p + jt, ld, avg_deg, st));
+    double* sl = slot(si);
+    enqueue_cgs2(basis.p, n, ld, jt, jt, b, part.p, h1.p, hsum.p, sl, jt - b, st);
+    enqueue_block_qr(basis.p, n, ld, jt, b, part.p, rinv(), r1(), sl + kPP * kPP, sl + 2 * kPP * kPP, z.p, s.p, st);
+    stats.block_steps += 1;
+    stats.spmv_cols += b;
+  }
+
+  void fetch_slots(int first, int count) {
+    if (count <= 0) return;
+    HIP_TRY(hipMemcpyAsync(slots_host.p + (size_t)first * kSlotDoubles, slots.p + (size_t)first * kSlotDoubles,
+                           (size_t)count * kSlotDoubles * sizeof(double), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+  }
+
+  // out (n x l row-major in rot) = basis[:, nl : nl+ja] * Y[:, sel]; then copied to basis[:, dst : dst+l]
+  void rotate_into(int ja, const std::vector<double>& ymat, int ycols, const std::vector<int>& sel, int dst) {
+    const int l = (int)sel.size();
+    if (l == 0) return;
+    std::vector<double> yl((size_t)ja * l);
+    for (int r = 0; r < ja; ++r)
+      for (int t = 0; t < l; ++t) yl[(size_t)r * l + t] = ymat[(size_t)r * ycols + sel[t]];
+    if ((size_t)ja * l > yd_cap || (size_t)l > rot_cols) throw ScError{SC_EDOMAIN};
+    HIP_TRY(hipMemcpyAsync(yd.p, yl.data(), yl.size() * sizeof(double), hipMemcpyHostToDevice, st));
+    HIP_TRY(launch_row_gemm(basis.p, n, ld, nl, ja, yd.p, l, l, 1, 0, rot.p, l, st));
+    HIP_TRY(launch_copy_cols(rot.p, l, 0, basis.p, ld, dst, l, n, st));
+    HIP_TRY(hipStreamSynchronize(st));  // yl (pageable host memory) must stay alive until the copy is done
+  }
+
+  // drop locked column `idx` by moving the last locked column into its place
+  void drop_locked(int idx) {
+    const int last = nl - 1;
+    if (idx != last) {
+      HIP_TRY(launch_copy_cols(basis.p, ld, last, rot.p, 1, 0, 1, n, st));
+      HIP_TRY(launch_copy_cols(rot.p, 1, 0, basis.p, ld, idx, 1, n, st));
+      theta_locked[idx] = theta_locked[last];
+      rho_locked[idx] = rho_locked[last];
+    }
+    theta_locked.pop_back();
+    rho_locked.pop_back();
+    nl -= 1;
+  }
+
+  double kth_locked_theta() const {
+    std::vector<double> t(theta_locked);
+    std::sort(t.begin(), t.end(), std::greater<double>());
+    return t[k - 1];
+  }
+
+  int run(double* evals_out, double* evecs_out) {
+    const double t_begin = now_s();
+    setup();
+    int cycles = 0;
+    bool not_converged = false;
+    bool finished = false;
+    int prev_phase_steps = 0;
+    uint64_t stream_id = 0;
+
+    std::vector<double> T, Tsub, theta, Y;
+    std::vector<char> ghost;
+
+    while (!finished) {
+      const bool verifying = nl >= k;
+      if (verifying && (flags & SC_FLAG_NO_VERIFY)) break;
+      if ((int64_t)nl >= n) break;
+      const bool last_cycle_phase = cycles >= maxiter;  // out of budget: only build enough Ritz vectors to answer
+      if (last_cycle_phase && verifying) {
+        break;  // k pairs are locked, the check phase could not be afforded
+      }
+      const int cap = m - nl;  // active columns allowed (excluding the block under construction)
+      const int want = verifying ? 1 : std::min(b, k - nl);
+      cycles += last_cycle_phase ? 0 : 1;
+      stats.phases += 1;
+
+      // ---- start block
+      HIP_TRY(launch_random_block(basis.p, n, ld, nl, b, seed, stream_id++, st));
+      enqueue_cgs2(basis.p, n, ld, nl, nl, b, part.p, h1.p, hsum.p, nullptr, 0, st);
+      enqueue_block_qr(basis.p, n, ld, nl, b, part.p, rinv(), r1(), slot(0) + kPP * kPP, slot(0) + 2 * kPP * kPP, z.p,
+                       s.p, st);
+      int ja = b;            // active columns whose coupling is (or will be) assembled
+      int assembled = 0;     // active columns of T that are final (their block has been multiplied by S)
+      int next_slot = 1;     // slot 0 = start block QR
+      int fetched = 0;       // slots already on the host
+      int steps_in_phase = 0;
+      T.assign((size_t)cap * cap, 0.0);
+      ghost.assign((size_t)cap + b, 0);
+      bool start_block_seen = false;
+      int pending = 0;
+      int next_check = prev_phase_steps > 1 ? prev_phase_steps - 1 : 4;
+      double last_rho = -1.0;
+      int last_rho_step = 0;
+      bool phase_over = false;
+
+      while (!phase_over) {
+        if (next_slot >= max_slots) throw ScError{SC_EDOMAIN};  // cannot happen: a cycle has at most m/b steps
+        enqueue_step(ja, next_slot);
+        ++next_slot;
+        ++pending;
+        ++steps_in_phase;
+        const bool full = ja + b > cap;  // the block just built cannot join the active basis
+        bool check = full || pending >= next_check;
+        if (last_cycle_phase && !verifying && ja >= std::min(k - nl, cap - b)) check = true;
+        if (!check) {
+          ja += b;
+          continue;
+        }
+        // ---- inspect: bring the slots over and assemble T
+        fetch_slots(fetched, next_slot - fetched);
+        fetched = next_slot;
+        if (!start_block_seen) {
+          const double* r0 = hslot(0) + kPP * kPP;
+          for (int x = 0; x < b; ++x) ghost[x] = (r0[x * kPP + x] == 0.0);
+          start_block_seen = true;
+        }
+        // steps (next_slot - pending) .. (next_slot - 1); step with slot q worked on the block that
+        // ends at active column  e_q = ja - (next_slot - 1 - q) * b
+        for (int q = next_slot - pending; q < next_slot; ++q) {
+          const int e = ja - (next_slot - 1 - q) * b;
+          const int c0 = e - b;
+          const double* A = hslot(q);
+          for (int x = 0; x < b; ++x)
+            for (int y = 0; y < b; ++y)
+              T[(size_t)(c0 + x) * cap + c0 + y] = 0.5 * (A[x * kPP + y] + A[y * kPP + x]);
+          for (int x = 0; x < b; ++x)
+            if (ghost[c0 + x]) {
+              for (int y = 0; y < e; ++y) T[(size_t)(c0 + x) * cap + y] = T[(size_t)y * cap + c0 + x] = 0.0;
+              T[(size_t)(c0 + x) * cap + c0 + x] = -2.0;
+            }
+          assembled = e;
+          if (q + 1 < next_slot) {
+            // the block built by step q joined the basis: coupling R and ghost flags
+            const double* R = hslot(q) + kPP * kPP;
+            for (int x = 0; x < b; ++x) {
+              ghost[e + x] = (R[x * kPP + x] == 0.0);
+              for (int y = 0; y < b; ++y) {
+                T[(size_t)(e + x) * cap + c0 + y] = R[x * kPP + y];
+                T[(size_t)(c0 + y) * cap + e + x] = R[x * kPP + y];
+              }
+            }
+          }
+        }
+        pending = 0;
+        // ---- Ritz pairs of T[0:ja, 0:ja]
+        const double te0 = now_s();
+        Tsub.resize((size_t)ja * ja);
+        for (int x = 0; x < ja; ++x) std::memcpy(&Tsub[(size_t)x * ja], &T[(size_t)x * cap], sizeof(double) * ja);
+        theta.resize(ja);
+        Y.resize((size_t)ja * ja);
+        if (sym_eig(Tsub.data(), ja, theta.data(), Y.data()) != 0) throw ScError{SC_EHIP};
+        stats.t_host_eig += now_s() - te0;
+        stats.host_eigs += 1;
+        const double* Rl = hslot(next_slot - 1) + kPP * kPP;
+        const double* Gl = hslot(next_slot - 1) + 2 * kPP * kPP;
+        int nreal = 0;
+        for (int x = 0; x < ja; ++x) nreal += ghost[x] ? 0 : 1;
+        bool exhausted = true;
+        for (int x = 0; x < b; ++x) exhausted = exhausted && (Rl[x * kPP + x] == 0.0);
+        // descending non-ghost Ritz pairs: indices ja-1, ja-2, ... (ghosts sit at -2, i.e. at the bottom)
+        std::vector<double> rho(nreal);
+        for (int t = 0; t < nreal; ++t) {
+          const int ci = ja - 1 - t;
+          double acc = 0.0;
+          for (int x = 0; x < b; ++x) {
+            double gx = 0.0;
+            for (int y = 0; y < b; ++y) gx += Gl[x * kPP + y] * Y[(size_t)(ja - b + y) * ja + ci];
+            acc += gx * Y[(size_t)(ja - b + x) * ja + ci];
+          }
+          rho[t] = std::sqrt(std::max(acc, 0.0));
+        }
+        int lead = 0;
+        while (lead < nreal && rho[lead] <= tol) ++lead;
+
+        if (nreal == 0) {  // the deflated space is empty: nothing more exists
+          finished = true;
+          if (nl < k) not_converged = true;
+          break;
+        }
+        const bool stop_now = last_cycle_phase && !verifying;
+        if ((lead >= want || exhausted) && !stop_now) {
+          int nlock = std::min(lead, verifying ? b : want);
+          if (exhausted && nlock == 0) nlock = std::min(nreal, want);
+          if (verifying) {
+            const double kth = kth_locked_theta();
+            int better = 0;
+            while (better < nlock && theta[ja - 1 - better] > kth + tol) ++better;
+            nlock = better;
+            if (nlock == 0) {
+              finished = true;
+              break;
+            }
+          }
+          std::vector<int> sel(nlock);
+          for (int t = 0; t < nlock; ++t) sel[t] = ja - 1 - t;
+          rotate_into(ja, Y, ja, sel, nl);
+          for (int t = 0; t < nlock; ++t) {
+            theta_locked.push_back(theta[ja - 1 - t]);
+            rho_locked.push_back(rho[t]);
+          }
+          nl += nlock;
+          while (nl > k) {  // keep the k best
+            int worst = 0;
+            for (int t = 1; t < nl; ++t)
+              if (theta_locked[t] < theta_locked[worst]) worst = t;
+            drop_locked(worst);
+          }
+          phase_over = true;
+          prev_phase_steps = steps_in_phase;
+          break;
+        }
+        if (stop_now || (full && cycles >= maxiter)) {
+          // out of cycles: take the best unconverged Ritz vectors to fill up the answer
+          const int take = std::min({nreal, std::max(0, k - nl), (int)rot_cols});
+          std::vector<int> sel(take);
+          for (int t = 0; t < take; ++t) sel[t] = ja - 1 - t;
+          rotate_into(ja, Y, ja, sel, nl);
+          for (int t = 0; t < take; ++t) {
+            theta_locked.push_back(theta[ja - 1 - t]);
+            rho_locked.push_back(rho[t]);
+          }
+          nl += take;
+          not_converged = true;
+          finished = true;
+          break;
+        }
+        if (full) {
+          // ---- thick restart: keep the leading Ritz vectors and the residual block
+          cycles += 1;
+          stats.restarts += 1;
+          int l = std::max(want + b, ja / 2);
+          l = std::min({l, ja - b, nreal, (int)rot_cols});
+          if (l < 1) throw ScError{SC_EDOMAIN};
+          std::vector<int> sel(l);
+          for (int t = 0; t < l; ++t) sel[t] = ja - 1 - t;
+          rotate_into(ja, Y, ja, sel, nl);
+          HIP_TRY(launch_copy_cols(basis.p, ld, nl + ja, rot.p, b, 0, b, n, st));
+          HIP_TRY(launch_copy_cols(rot.p, b, 0, basis.p, ld, nl + l, b, n, st));
+          std::fill(T.begin(), T.end(), 0.0);
+          std::fill(ghost.begin(), ghost.end(), 0);
+          for (int t = 0; t < l; ++t) T[(size_t)t * cap + t] = theta[sel[t]];
+          for (int x = 0; x < b; ++x) {
+            ghost[l + x] = (Rl[x * kPP + x] == 0.0);
+            for (int t = 0; t < l; ++t) {
+              double c = 0.0;
+              for (int y = 0; y < b; ++y) c += Rl[x * kPP + y] * Y[(size_t)(ja - b + y) * ja + sel[t]];
+              T[(size_t)(l + x) * cap + t] = c;
+              T[(size_t)t * cap + l + x] = c;
+            }
+          }
+          ja = l + b;
+          assembled = l;
+          next_slot = 1;
+          fetched = 1;
+          next_check = std::max(1, check_every);
+          last_rho = -1.0;
+          continue;
+        }
+        // ---- continue: the new block joins; schedule the next inspection from the observed decay
+        {
+          const double* R = Rl;
+          const int e = ja, c0 = ja - b;
+          for (int x = 0; x < b; ++x) {
+            ghost[e + x] = (R[x * kPP + x] == 0.0);
+            for (int y = 0; y < b; ++y) {
+              T[(size_t)(e + x) * cap + c0 + y] = R[x * kPP + y];
+              T[(size_t)(c0 + y) * cap + e + x] = R[x * kPP + y];
+            }
+          }
+          ja += b;
+          const double r_now = rho[std::min(want, nreal) - 1];
+          next_check = std::max(1, check_every);
+          if (last_rho > 0.0 && r_now > 0.0 && r_now < last_rho && steps_in_phase > last_rho_step) {
+            const double rate = std::log(last_rho / r_now) / (steps_in_phase - last_rho_step);
+            const double need = std::log(r_now / std::max(tol, 1e-300)) / rate;
+            int guess = (int)std::floor(0.85 * need);
+            next_check = std::min(std::max(guess, 1), 12);
+          }
+          last_rho = r_now;
+          last_rho_step = steps_in_phase;
+        }
+        (void)assembled;
+      }
+    }
+
+    // ---- Rayleigh-Ritz over the locked vectors (the Ritz-vector step of Algorithm 3)
+    const int nx = nl;
+    std::vector<double> evals_host(k, std::numeric_limits<double>::quiet_NaN());
+    HIP_TRY(hipMemsetAsync(evecs_out, 0, (size_t)n * k * sizeof(double), st));
+    int nfound = std::min(nx, k);
+    if (nx > 0) {
+      std::vector<double> G((size_t)nx * nx, 0.0), hbuf((size_t)nx * kPP);
+      const ProjectPlan plan = plan_project(n, nx, kMaxPartials);
+      // columns [nx, nx+b) are zeroed so that a last chunk narrower than b is padded with zeros;
+      // the products land in columns [nx+b, nx+2b)
+      HIP_TRY(hipMemsetAsync(z.p, 0, (size_t)n * b * sizeof(double), st));
+      HIP_TRY(launch_copy_cols(z.p, b, 0, basis.p, ld, nx, b, n, st));
+      for (int c0 = 0; c0 < nx; c0 += b) {
+        const int w = std::min(b, nx - c0);
+        HIP_TRY(launch_pack_scaled(basis.p + c0, ld, s.p, n, b, z.p, st));
+        HIP_TRY(launch_spmm(rowptr, col, val, s.p, n, z.p, b, basis.p + nx + b, ld, avg_deg, st));
+        HIP_TRY(launch_project(basis.p, n, ld, 0, nx, nx + b, b, plan, part.p, st));
+        HIP_TRY(launch_reduce_partials(part.p, plan.npart, nx, b, h1.p, nullptr, 0, nullptr, 0, st));
+        HIP_TRY(hipMemcpyAsync(hbuf.data(), h1.p, (size_t)nx * kPP * sizeof(double), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        for (int r = 0; r < nx; ++r)
+          for (int t = 0; t < w; ++t) G[(size_t)r * nx + c0 + t] = hbuf[(size_t)r * kPP + t];
+        stats.spmv_cols += w;
+      }
+      const double te0 = now_s();
+      std::vector<double> th(nx), Yx((size_t)nx * nx);
+      if (sym_eig(G.data(), nx, th.data(), Yx.data()) != 0) throw ScError{SC_EHIP};
+      stats.t_host_eig += now_s() - te0;
+      stats.host_eigs += 1;
+      std::vector<double> yk((size_t)nx * nfound);
+      for (int r = 0; r < nx; ++r)
+        for (int t = 0; t < nfound; ++t) yk[(size_t)r * nfound + t] = Yx[(size_t)r * nx + (nx - 1 - t)];
+      for (int t = 0; t < nfound; ++t) evals_host[t] = 1.0 - th[nx - 1 - t];
+      if ((size_t)nx * nfound > yd_cap) throw ScError{SC_EDOMAIN};
+      HIP_TRY(hipMemcpyAsync(yd.p, yk.data(), yk.size() * sizeof(double), hipMemcpyHostToDevice, st));
+      HIP_TRY(launch_row_gemm(basis.p, n, ld, 0, nx, yd.p, nfound, nfound, 2, 0, evecs_out, n, st));
+      HIP_TRY(hipStreamSynchronize(st));
+    }
+    HIP_TRY(hipMemcpyAsync(evals_out, evals_host.data(), (size_t)k * sizeof(double), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));
+
+    int nconv = 0;
+    double maxr = 0.0;
+    for (size_t t = 0; t < rho_locked.size(); ++t) {
+      if (rho_locked[t] <= tol) ++nconv;
+      maxr = std::max(maxr, rho_locked[t]);
+    }
+    stats.nconv = std::min(nconv, k);
+    stats.max_residual_est = maxr;
+    stats.block = b;
+    stats.m = m;
+    stats.t_total = now_s() - t_begin;
+    if (nfound < k) not_converged = true;
+    return not_converged ? SC_NOT_CONVERGED : SC_OK;
+  }
+};
+
+int guarded(int (*fn)(void*), void* ctx) {
+  try {
+    return fn(ctx);
+  } catch (const ScError& e) {
+    return e.code;
+  } catch (const std::bad_alloc&) {
+    return SC_ENOMEM;
+  } catch (...) {
+    return SC_EHIP;
+  }
+}
+
+bool supported_block(int b) { return b == 1 || b == 2 || b == 4 || b == 8 || b == 16 || b == 32; }
+
+}  // namespace
+}  // namespace sceig
+
+using namespace sceig;
+
+extern "C" {
+
+int sc_version(void) { return 100; }
+
+const char* sc_strerror(int code) {
+  switch (code) {
+    case SC_OK: return "ok";
+    case SC_NOT_CONVERGED: return "not converged within maxiter restart cycles";
+    case SC_EINVAL: return "invalid argument (null pointer or negative size)";
+    case SC_EDOMAIN: return "argument out of domain (k, m, block or tol)";
+    case SC_ECSR: return "malformed CSR";
+    case SC_EZERODEG: return "a node has a non-positive or non-finite degree";
+    case SC_ENOMEM: return "out of memory";
+    case SC_EHIP: return "HIP runtime failure";
+    default: return "unknown code";
+  }
+}
+
+int sc_laplacian_eigsh(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n, int32_t k,
+                       double tol, int32_t maxiter, double* evals_out, double* evecs_out, void* stream,
+                       const sc_options* opt, sc_stats* stats) {
+  if (!csr_rowptr || !csr_col || !csr_val || !evals_out || !evecs_out || n < 0) return SC_EINVAL;
+  if (k < 1 || (int64_t)k >= n || !(tol >= 0.0) || maxiter < 1) return SC_EDOMAIN;
+  if (n > (int64_t)0x7fffffff) return SC_EDOMAIN;
+  sc_options o{};
+  if (opt) o = *opt;
+  Solver sv;
+  sv.rowptr = csr_rowptr;
+  sv.col = csr_col;
+  sv.val = csr_val;
+  sv.n = n;
+  sv.nnz = 0;
+  sv.k = k;
+  sv.tol = tol;
+  sv.maxiter = maxiter;
+  sv.flags = o.flags;
+  sv.seed = o.seed;
+  sv.check_every = o.check_every > 0 ? o.check_every : 2;
+  sv.st = reinterpret_cast<hipStream_t>(stream);
+  int64_t m = o.m;
+  if (m == 0) m = std::min<int64_t>(n, std::max<int64_t>(2 * (int64_t)k, (int64_t)k + 56));
+  if (m > n || m < (int64_t)k + 3) return SC_EDOMAIN;
+  int b = o.block;
+  if (b == 0) {
+    b = pow2_floor((int)std::max<int64_t>(1, (m - k) / 3));
+    b = std::min(b, 16);
+    int kb = 1;
+    while (kb < k) kb *= 2;
+    b = std::min(b, kb);
+  }
+  if (!supported_block(b) || (int64_t)k + 3 * (int64_t)b > m) return SC_EDOMAIN;
+  sv.m = (int)m;
+  sv.b = b;
+  struct Ctx {
+    Solver* sv;
+    double* ev;
+    double* evec;
+  } ctx{&sv, evals_out, evecs_out};
+  const int rc = guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        return c->sv->run(c->ev, c->evec);
+      },
+      &ctx);
+  if (stats) *stats = sv.stats;
+  if (rc < 0) (void)hipStreamSynchronize(sv.st);
+  return rc;
+}
+
+int sc_degree_scaling(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n,
+                      double* d_out, double* s_out, void* stream) {
+  (void)csr_col;
+  if (!csr_rowptr || !csr_val || !s_out || n < 0) return SC_EINVAL;
+  if (n == 0) return SC_OK;
+  struct Ctx {
+    const int64_t* rp;
+    const double* v;
+    int64_t n;
+    double *d, *s;
+    hipStream_t st;
+  } ctx{csr_rowptr, csr_val, n, d_out, s_out, reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        DevBuf<int> flag;
+        flag.alloc(1);
+        HIP_TRY(hipMemsetAsync(flag.p, 0, sizeof(int), c->st));
+        HIP_TRY(launch_degree_scaling(c->rp, c->v, c->n, c->d, c->s, flag.p, c->st));
+        int h = 0;
+        HIP_TRY(hipMemcpyAsync(&h, flag.p, sizeof(int), hipMemcpyDeviceToHost, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        return (h & 4) ? SC_EZERODEG : SC_OK;
+      },
+      &ctx);
+}
+
+int sc_validate_csr(const int64_t* csr_rowptr, const int32_t* csr_col, int64_t n, void* stream) {
+  if (!csr_rowptr || !csr_col || n < 0) return SC_EINVAL;
+  if (n == 0) return SC_OK;
+  struct Ctx {
+    const int64_t* rp;
+    const int32_t* c;
+    int64_t n;
+    hipStream_t st;
+  } ctx{csr_rowptr, csr_col, n, reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        int64_t nnz = 0;
+        HIP_TRY(hipMemcpyAsync(&nnz, c->rp + c->n, sizeof(int64_t), hipMemcpyDeviceToHost, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        if (nnz < 0) return SC_ECSR;
+        DevBuf<int> flag;
+        flag.alloc(1);
+        HIP_TRY(hipMemsetAsync(flag.p, 0, sizeof(int), c->st));
+        HIP_TRY(launch_validate_csr(c->rp, c->c, c->n, nnz, flag.p, c->st));
+        int h = 0;
+        HIP_TRY(hipMemcpyAsync(&h, flag.p, sizeof(int), hipMemcpyDeviceToHost, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        return (h & 3) ? SC_ECSR : SC_OK;
+      },
+      &ctx);
+}
+
+int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, const double* s,
+                       int64_t n, const double* x, int64_t ldx, double* y, int64_t ldy, int32_t ncols, double* work,
+                       void* stream) {
+  if (!csr_rowptr || !csr_col || !csr_val || !s || !x || !y || n < 0) return SC_EINVAL;
+  if (!supported_block(ncols) || ldx < ncols || ldy < ncols) return SC_EDOMAIN;
+  if (n == 0) return SC_OK;
+  struct Ctx {
+    const int64_t* rp;
+    const int32_t* c;
+    const double* v;
+    const double* s;
+    int64_t n;
+    const double* x;
+    int64_t ldx;
+    double* y;
+    int64_t ldy;
+    int b;
+    double* work;
+    hipStream_t st;
+  } ctx{csr_rowptr, csr_col, csr_val, s, n, x, ldx, y, ldy, ncols, work, reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        DevBuf<double> own;
+        double* z = c->work;
+        if (!z) {
+          own.alloc((size_t)c->n * c->b);
+          z = own.p;
+        }
+        int64_t nnz = 0;
+        HIP_TRY(hipMemcpyAsync(&nnz, c->rp + c->n, sizeof(int64_t), hipMemcpyDeviceToHost, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        HIP_TRY(launch_pack_scaled(c->x, c->ldx, c->s, c->n, c->b, z, c->st));
+        HIP_TRY(launch_spmm(c->rp, c->c, c->v, c->s, c->n, z, c->b, c->y, c->ldy, (double)nnz / (double)c->n, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        return SC_OK;
+      },
+      &ctx);
+}
+
+int sc_cgs2(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, double* h_out, void* stream) {
+  if (!basis || n < 0) return SC_EINVAL;
+  if (b < 1 || b > kMaxBlock || j < 0 || ld < (int64_t)j + b) return SC_EDOMAIN;
+  if (n == 0 || j == 0) return SC_OK;
+  struct Ctx {
+    double* basis;
+    int64_t n, ld;
+    int j, b;
+    double* h;
+    hipStream_t st;
+  } ctx{basis, n, ld, j, b, h_out, reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        DevBuf<double> part, h1, hsum;
+        part.alloc((size_t)kMaxPartials * c->j * kPP);
+        h1.alloc((size_t)c->j * kPP);
+        hsum.alloc((size_t)c->j * kPP);
+        enqueue_cgs2(c->basis, c->n, c->ld, c->j, c->j, c->b, part.p, h1.p, hsum.p, nullptr, 0, c->st);
+        if (c->h)
+          HIP_TRY(hipMemcpy2DAsync(c->h, (size_t)c->b * sizeof(double), hsum.p, (size_t)kPP * sizeof(double),
+                                   (size_t)c->b * sizeof(double), (size_t)c->j, hipMemcpyDeviceToDevice, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        return SC_OK;
+      },
+      &ctx);
+}
+
+int sc_block_qr(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, double* r_out, double* g_out,
+                void* stream) {
+  if (!basis || n < 0) return SC_EINVAL;
+  if (!supported_block(b) || j < 0 || ld < (int64_t)j + b) return SC_EDOMAIN;
+  if (n == 0) return SC_OK;
+  struct Ctx {
+    double* basis;
+    int64_t n, ld;
+    int j, b;
+    double *r, *g;
+    hipStream_t st;
+  } ctx{basis, n, ld, j, b, r_out, g_out, reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        DevBuf<double> part, small;
+        part.alloc((size_t)kMaxPartials * c->b * kPP);
+        small.alloc(4 * kPP * kPP);
+        double* rinv = small.p;
+        double* r1 = small.p + kPP * kPP;
+        double* rr = small.p + 2 * kPP * kPP;
+        double* gg = small.p + 3 * kPP * kPP;
+        enqueue_block_qr(c->basis, c->n, c->ld, c->j, c->b, part.p, rinv, r1, rr, gg, nullptr, nullptr, c->st);
+        const size_t w = (size_t)c->b * sizeof(double);
+        if (c->r)
+          HIP_TRY(hipMemcpy2DAsync(c->r, w, rr, (size_t)kPP * sizeof(double), w, (size_t)c->b, hipMemcpyDeviceToDevice,
+                                   c->st));
+        if (c->g)
+          HIP_TRY(hipMemcpy2DAsync(c->g, w, gg, (size_t)kPP * sizeof(double), w, (size_t)c->b, hipMemcpyDeviceToDevice,
+                                   c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        return SC_OK;
+      },
+      &ctx);
+}
+
+int sc_rotate(const double* basis, int64_t n, int64_t ld, int32_t j0, int32_t ja, const double* y, int32_t l,
+              double* out, int64_t ldo, int32_t out_colmajor, void* stream) {
+  if (!basis || !y || !out || n < 0) return SC_EINVAL;
+  if (j0 < 0 || ja < 1 || l < 1 || ld < (int64_t)j0 + ja) return SC_EDOMAIN;
+  if (out_colmajor ? (ldo < n) : (ldo < l)) return SC_EDOMAIN;
+  if (n == 0) return SC_OK;
+  struct Ctx {
+    const double* basis;
+    int64_t n, ld;
+    int j0, ja;
+    const double* y;
+    int l;
+    double* out;
+    int64_t ldo;
+    int cm;
+    hipStream_t st;
+  } ctx{basis, n, ld, j0, ja, y, l, out, ldo, out_colmajor, reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        HIP_TRY(launch_row_gemm(const_cast<double*>(c->basis), c->n, c->ld, c->j0, c->ja, c->y, c->l, c->l,
+                                c->cm ? 2 : 1, 0, c->out, c->ldo, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        return SC_OK;
+      },
+      &ctx);
+}
+
+int sc_sym_eig(const double* a, int32_t n, double* w, double* z) {
+  if (!a || !w || n < 0) return SC_EINVAL;
+  if (n == 0) return SC_OK;
+  try {
+    return sym_eig(a, n, w, z) == 0 ? SC_OK : SC_NOT_CONVERGED;
+  } catch (const std::bad_alloc&) {
+    return SC_ENOMEM;
+  } catch (...) {
+    return SC_EHIP;
+  }
+}
+
+}  // extern "C"

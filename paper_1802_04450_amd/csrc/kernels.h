@@ -1,0 +1,76 @@
+// Launch wrappers of the gfx950 kernels.  All pointers are device pointers unless said otherwise;
+// every wrapper only enqueues work on `st` and returns hipGetLastError().
+//
+// Dense blocks are row-major: element (i, c) of a block with leading dimension ld is p[i*ld + c].
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sceig {
+
+constexpr int kMaxBlock = 32;      // largest Lanczos block size
+constexpr int kPartialPad = 32;    // column stride of partial / coefficient blocks (>= kMaxBlock)
+
+// ---- setup ---------------------------------------------------------------------------------
+// flag[0] |= 1 if rowptr is not monotone / rowptr[0] != 0, |= 2 if a column is out of range.
+hipError_t launch_validate_csr(const int64_t* rowptr, const int32_t* col, int64_t n, int64_t nnz, int* flag,
+                               hipStream_t st);
+// d_i = sum of row i, s_i = d_i^-1/2; flag[0] |= 4 if some d_i is <= 0 or not finite.  d may be null.
+hipError_t launch_degree_scaling(const int64_t* rowptr, const double* val, int64_t n, double* d, double* s, int* flag,
+                                 hipStream_t st);
+
+// ---- sparse product ------------------------------------------------------------------------
+// z[i*b + t] = s[i] * x[i*ldx + t]   (packed scaled copy of an n x b block)
+hipError_t launch_pack_scaled(const double* x, int64_t ldx, const double* s, int64_t n, int b, double* z,
+                              hipStream_t st);
+// y[i*ldy + t] = s[i] * sum_e val[e] * z[col[e]*b + t]  over the entries e of row i; b in {1,2,4,8,16,32}.
+// avg_deg steers the lanes-per-row choice of the b <= 4 kernels.
+hipError_t launch_spmm(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
+                       const double* z, int b, double* y, int64_t ldy, double avg_deg, hipStream_t st);
+
+// ---- tall-skinny projections (fp64 MFMA) ---------------------------------------------------
+struct ProjectPlan {
+  int rows_per_panel;  // multiple of 4
+  int nwc;             // waves of a workgroup laid along the columns (1, 2 or 4)
+  int npart;           // number of partial blocks produced = panels * (4 / nwc)
+};
+ProjectPlan plan_project(int64_t n, int ja, int max_partials);
+// part[p][c][t] (c < ja, t < kPartialPad) = sum over the rows of partial p of A[i, acol0 + c] * B[i, bcol0 + t]
+// with A and B both columns of `basis` (row-major n x ld); t >= b entries are written as 0.
+hipError_t launch_project(const double* basis, int64_t n, int64_t ld, int acol0, int ja, int bcol0, int b,
+                          const ProjectPlan& plan, double* part, hipStream_t st);
+// h[c*kPartialPad + t] = sum_p part[p][c][t] in the fixed order p = 0..npart-1 (t < b, else 0);
+// if hsum != null: hsum = (accumulate ? hsum : 0) + h.
+// if slot != null: rows [slot_row0, ja) of the resulting hsum (or h) are copied to slot[(c-slot_row0)*kPartialPad + t].
+hipError_t launch_reduce_partials(const double* part, int npart, int ja, int b, double* h, double* hsum,
+                                  int accumulate, double* slot, int slot_row0, hipStream_t st);
+
+// C = A * B row GEMM:  A = basis[:, acol0 : acol0+kdim] (n x kdim), B = bmat (kdim x ncols, row-major, ldb).
+// mode 0: basis[:, ccol0 + t] -= C[:, t]          (in place update, ncols <= 32, out unused)
+// mode 1: out[i*ldo + t]  = C[i, t]                (row-major)
+// mode 2: out[t*ldo + i]  = C[i, t]                (column-major)
+hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int ldb,
+                           int ncols, int mode, int ccol0, double* out, int64_t ldo, hipStream_t st);
+
+// ---- block orthonormalization --------------------------------------------------------------
+// One Cholesky-QR pass bookkeeping on the summed Gram partials (single workgroup):
+//   g = sum_p part[p] (b x b);  Cholesky g = r^T r with dependent columns dropped (zero row in r,
+//   zero row+column in rinv);  rinv = r^-1 on the kept columns.
+//   If rprev != null: rout = r * rprev (composition of two passes) else rout = r.  Any output may be null.
+hipError_t launch_gram_cholesky(const double* part, int npart, int b, double* g_out, double* rinv, double* rout,
+                                const double* rprev, double abs_tol2, double rel_tol, hipStream_t st);
+// basis[:, col0 : col0+b] = basis[:, col0 : col0+b] * rinv  (rinv b x b row-major stride kPartialPad);
+// if z != null also z[i*b + t] = s[i] * new value.
+hipError_t launch_apply_rinv(double* basis, int64_t n, int64_t ld, int col0, int b, const double* rinv, double* z,
+                             const double* s, hipStream_t st);
+
+// ---- misc ----------------------------------------------------------------------------------
+// basis[i, col0 + t] = uniform(-1, 1) from a counter-based hash of (seed, stream_id, i, t)
+hipError_t launch_random_block(double* basis, int64_t n, int64_t ld, int col0, int b, uint64_t seed,
+                               uint64_t stream_id, hipStream_t st);
+// dst[i*ldd + dcol0 + t] = src[i*lds + scol0 + t], t < w (regions must not overlap)
+hipError_t launch_copy_cols(const double* src, int64_t lds, int scol0, double* dst, int64_t ldd, int dcol0, int w,
+                            int64_t n, hipStream_t st);
+
+}  // namespace sceig

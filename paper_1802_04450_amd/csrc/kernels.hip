@@ -1,0 +1,627 @@
+// HIP kernels for gfx950 (CDNA4, wave64).  See kernels.h for the contracts.
+//
+// fp64 MFMA operand layout used below (v_mfma_f64_16x16x4_f64, one wave):
+//   A (16 x 4):  lane l holds A[l % 16][l / 16]
+//   B (4 x 16):  lane l holds B[l / 16][l % 16]
+//   D (16 x 16): lane l, register r (0..3) holds D[4*r + l / 16][l % 16]
+#include "kernels.h"
+
+namespace sceig {
+
+typedef double d4 __attribute__((ext_vector_type(4)));
+
+#define MFMA_F64(a, b, c) __builtin_amdgcn_mfma_f64_16x16x4f64((a), (b), (c), 0, 0, 0)
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__host__ __device__ inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// --------------------------------------------------------------------------------------------
+// setup
+// --------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void validate_rowptr_kernel(const int64_t* __restrict__ rowptr, int64_t n,
+                                                                   int64_t nnz, int* __restrict__ flag) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= n) return;
+  const int64_t a = rowptr[i], b = rowptr[i + 1];
+  bool bad = a > b || a < 0 || b > nnz;
+  if (i == 0 && a != 0) bad = true;
+  if (bad) atomicOr(flag, 1);
+}
+
+__global__ __launch_bounds__(kThreads) void validate_col_kernel(const int32_t* __restrict__ col, int64_t nnz, int64_t n,
+                                                                int* __restrict__ flag) {
+  int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  bool bad = false;
+  for (; e < nnz; e += stride) {
+    const int32_t c = col[e];
+    bad |= (c < 0) | ((int64_t)c >= n);
+  }
+  if (bad) atomicOr(flag, 2);
+}
+
+// 16 lanes per row
+__global__ __launch_bounds__(kThreads) void degree_kernel(const int64_t* __restrict__ rowptr,
+                                                          const double* __restrict__ val, int64_t n,
+                                                          double* __restrict__ d, double* __restrict__ s,
+                                                          int* __restrict__ flag) {
+  const int64_t row = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 4;
+  const int lane = threadIdx.x & 15;
+  if (row >= n) return;  // uniform over the 16-lane group
+  const int64_t e1 = rowptr[row + 1];
+  double acc = 0.0;
+  for (int64_t e = rowptr[row] + lane; e < e1; e += 16) acc += val[e];
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 16);
+  if (lane == 0) {
+    if (d) d[row] = acc;
+    s[row] = 1.0 / sqrt(acc);
+    if (!(acc > 0.0) || isinf(acc)) atomicOr(flag, 4);
+  }
+}
+
+// --------------------------------------------------------------------------------------------
+// sparse product
+// --------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void pack_scaled_kernel(const double* __restrict__ x, int64_t ldx,
+                                                               const double* __restrict__ s, int64_t n, int b,
+                                                               double* __restrict__ z) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= n * b) return;
+  const int64_t i = idx / b;
+  const int t = (int)(idx - i * b);
+  z[idx] = s[i] * x[i * ldx + t];
+}
+
+// B lanes per row, one lane per column of the block (B = 8, 16, 32).  The B lanes of a row load B
+// consecutive (col, val) pairs at once and broadcast them to each other.
+template <int B>
+__global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __restrict__ rowptr,
+                                                             const int32_t* __restrict__ col,
+                                                             const double* __restrict__ val,
+                                                             const double* __restrict__ s,
+                                                             const double* __restrict__ z, double* __restrict__ y,
+                                                             int64_t ldy, int64_t n) {
+  constexpr int G = kThreads / B;
+  const int t = threadIdx.x % B;
+  const int64_t row = (int64_t)blockIdx.x * G + threadIdx.x / B;
+  if (row >= n) return;  // uniform over the B-lane group
+  const int64_t e1 = rowptr[row + 1];
+  double acc0 = 0.0, acc1 = 0.0;
+  for (int64_t e = rowptr[row]; e < e1; e += B) {
+    int32_t c = 0;
+    double a = 0.0;
+    if (e + t < e1) {
+      c = col[e + t];
+      a = val[e + t];
+    }
+    const int cnt = (int)((e1 - e) < (int64_t)B ? (e1 - e) : (int64_t)B);
+    int u = 0;
+    for (; u + 1 < cnt; u += 2) {
+      const int32_t cu0 = __shfl(c, u, B), cu1 = __shfl(c, u + 1, B);
+      const double au0 = __shfl(a, u, B), au1 = __shfl(a, u + 1, B);
+      acc0 += au0 * z[(int64_t)cu0 * B + t];
+      acc1 += au1 * z[(int64_t)cu1 * B + t];
+    }
+    if (u < cnt) {
+      const int32_t cu = __shfl(c, u, B);
+      const double au = __shfl(a, u, B);
+      acc0 += au * z[(int64_t)cu * B + t];
+    }
+  }
+  y[row * ldy + t] = s[row] * (acc0 + acc1);
+}
+
+// L lanes per row, each lane walks the entries of the row with stride L and keeps B accumulators
+// (B = 1, 2, 4); the L partial sums are combined by a shuffle tree.
+template <int B, int L>
+__global__ __launch_bounds__(kThreads) void spmm_nz_kernel(const int64_t* __restrict__ rowptr,
+                                                           const int32_t* __restrict__ col,
+                                                           const double* __restrict__ val,
+                                                           const double* __restrict__ s,
+                                                           const double* __restrict__ z, double* __restrict__ y,
+                                                           int64_t ldy, int64_t n) {
+  constexpr int G = kThreads / L;
+  const int t = threadIdx.x % L;
+  const int64_t row = (int64_t)blockIdx.x * G + threadIdx.x / L;
+  if (row >= n) return;  // uniform over the L-lane group
+  const int64_t e1 = rowptr[row + 1];
+  double acc[B];
+#pragma unroll
+  for (int q = 0; q < B; ++q) acc[q] = 0.0;
+  for (int64_t e = rowptr[row] + t; e < e1; e += L) {
+    const int64_t c = col[e];
+    const double a = val[e];
+#pragma unroll
+    for (int q = 0; q < B; ++q) acc[q] += a * z[c * B + q];
+  }
+#pragma unroll
+  for (int o = L / 2; o > 0; o >>= 1) {
+#pragma unroll
+    for (int q = 0; q < B; ++q) acc[q] += __shfl_xor(acc[q], o, L);
+  }
+  if (t == 0) {
+    const double sr = s[row];
+#pragma unroll
+    for (int q = 0; q < B; ++q) y[row * ldy + q] = sr * acc[q];
+  }
+}
+
+template <int B>
+hipError_t launch_spmm_nz(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
+                          const double* z, double* y, int64_t ldy, double avg_deg, hipStream_t st) {
+  int lanes = 4;
+  while (lanes < 64 && lanes * 2 <= avg_deg) lanes *= 2;  // largest power of two <= avg_deg, in [4, 64]
+#define SC_LAUNCH_NZ(LL)                                                                                       \
+  hipLaunchKernelGGL((spmm_nz_kernel<B, LL>), dim3((unsigned)ceil_div64(n, kThreads / LL)), dim3(kThreads), 0, \
+                     st, rowptr, col, val, s, z, y, ldy, n)
+  switch (lanes) {
+    case 4: SC_LAUNCH_NZ(4); break;
+    case 8: SC_LAUNCH_NZ(8); break;
+    case 16: SC_LAUNCH_NZ(16); break;
+    case 32: SC_LAUNCH_NZ(32); break;
+    default: SC_LAUNCH_NZ(64); break;
+  }
+#undef SC_LAUNCH_NZ
+  return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------
+// tall-skinny projection  part = A^T B  (contraction over rows), fp64 MFMA
+// --------------------------------------------------------------------------------------------
+// A wave owns 64 consecutive A columns and a slice of rows.  Per step of 4 rows lane (i, g) loads
+// A[row+g][c0 + 4i .. 4i+3] (32 contiguous bytes) and B[row+g][i (+16)].  MFMA q multiplies the q-th
+// of the four A values, so its output row M stands for A column c0 + 4M + q.
+template <int NT>
+__global__ __launch_bounds__(kThreads) void project_kernel(const double* __restrict__ basis, int64_t n, int64_t ld,
+                                                           int acol0, int ja, int bcol0, int b, int rows_per_panel,
+                                                           int nwc, int vec_ok, double* __restrict__ part) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i = lane & 15, g = lane >> 4;
+  const int nwr = 4 / nwc;
+  const int wc = wave % nwc, wr = wave / nwc;
+  const int c0 = ((int)blockIdx.y * nwc + wc) * 64;
+  if (c0 >= ja) return;  // wave-uniform; no barriers in this kernel
+  const int pidx = (int)blockIdx.x * nwr + wr;
+  const int sub = rows_per_panel / nwr;
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_panel + (int64_t)wr * sub;
+  int64_t r1 = r0 + sub;
+  if (r1 > n) r1 = n;
+
+  d4 acc[NT][4];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[nt][q] = (d4){0.0, 0.0, 0.0, 0.0};
+
+  const int cbase = c0 + 4 * i;
+  const bool full = vec_ok && (cbase + 3 < ja);
+#pragma unroll 2
+  for (int64_t r = r0; r < r1; r += 4) {
+    const int64_t row = r + g;
+    double a[4] = {0.0, 0.0, 0.0, 0.0};
+    double bv[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) bv[nt] = 0.0;
+    if (row < r1) {
+      const double* rp = basis + row * ld;
+      const double* ap = rp + acol0 + cbase;
+      if (full) {
+        const d4 v = *reinterpret_cast<const d4*>(ap);
+        a[0] = v[0]; a[1] = v[1]; a[2] = v[2]; a[3] = v[3];
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (cbase + q < ja) a[q] = ap[q];
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        if (i + 16 * nt < b) bv[nt] = rp[bcol0 + i + 16 * nt];
+    }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[nt][q] = MFMA_F64(a[q], bv[nt], acc[nt][q]);
+  }
+
+  double* out = part + (int64_t)pidx * ja * kPartialPad;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int c = c0 + 4 * (4 * rr + g) + q;
+        if (c < ja) out[(int64_t)c * kPartialPad + i + 16 * nt] = acc[nt][q][rr];
+      }
+}
+
+__global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double* __restrict__ part, int npart, int ja,
+                                                                   int ncol, double* __restrict__ h,
+                                                                   double* __restrict__ hsum, int accumulate,
+                                                                   double* __restrict__ slot, int slot_row0) {
+  const int idx = blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= ja * kPartialPad) return;
+  const int t = idx % kPartialPad;
+  double acc = 0.0;
+  if (t < ncol) {
+    const int64_t stride = (int64_t)ja * kPartialPad;
+    const double* p = part + idx;
+    for (int q = 0; q < npart; ++q) acc += p[q * stride];
+  }
+  if (h) h[idx] = acc;
+  double tot = acc;
+  if (hsum) {
+    if (accumulate) tot += hsum[idx];
+    hsum[idx] = tot;
+  }
+  if (slot) {
+    const int c = idx / kPartialPad;
+    if (c >= slot_row0) slot[(c - slot_row0) * kPartialPad + t] = tot;
+  }
+}
+
+// --------------------------------------------------------------------------------------------
+// row GEMM  C = A * Bm  (contraction over basis columns), fp64 MFMA, Bm staged through LDS
+// --------------------------------------------------------------------------------------------
+// A wave owns MT*16 rows and NT*16 output columns.  Per step of 16 contraction indices lane (i, g)
+// loads A[row0+i][k + 4g .. 4g+3]; MFMA q contracts over the indices k + 4g + q, g = 0..3.  The Bm
+// chunk sits in LDS permuted so that the 64 lanes of one MFMA read 64 consecutive doubles.
+template <int NT, int MT>
+__global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
+                                                            int acol0, int kdim, const double* __restrict__ bmat,
+                                                            int ldb, int ncols, int mode, int ccol0,
+                                                            double* __restrict__ out, int64_t ldo, int vec_ok) {
+  constexpr int KC = 4096 / (NT * 16);  // contraction indices per LDS chunk (32 KB)
+  __shared__ double lds[KC * NT * 16];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i = lane & 15, g = lane >> 4;
+  const int n0 = (int)blockIdx.y * NT * 16;
+  const int64_t row0 = ((int64_t)blockIdx.x * 4 + wave) * (16 * MT);
+
+  d4 acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (d4){0.0, 0.0, 0.0, 0.0};
+
+  for (int k0 = 0; k0 < kdim; k0 += KC) {
+    const int kc = (kdim - k0) < KC ? (kdim - k0) : KC;
+    const int kc16 = (kc + 15) & ~15;
+    __syncthreads();
+    for (int e = threadIdx.x; e < kc16 * NT * 16; e += kThreads) {
+      const int kk = e / (NT * 16), t = e % (NT * 16);
+      double v = 0.0;
+      if (kk < kc && n0 + t < ncols) v = bmat[(int64_t)(k0 + kk) * ldb + n0 + t];
+      const int kt = kk >> 4, rem = kk & 15, gg = rem >> 2, q = rem & 3;
+      const int nt = t >> 4, ii = t & 15;
+      lds[((((kt * 4 + q) * NT + nt) * 4 + gg) << 4) + ii] = v;
+    }
+    __syncthreads();
+    for (int kk = 0; kk < kc16; kk += 16) {
+      double a[MT][4];
+      const int kcol = k0 + kk + 4 * g;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int64_t row = row0 + mt * 16 + i;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) a[mt][q] = 0.0;
+        if (row < n) {
+          const double* ap = basis + row * ld + acol0 + kcol;
+          if (vec_ok && kcol + 3 < kdim) {
+            const d4 v = *reinterpret_cast<const d4*>(ap);
+            a[mt][0] = v[0]; a[mt][1] = v[1]; a[mt][2] = v[2]; a[mt][3] = v[3];
+          } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+              if (kcol + q < kdim) a[mt][q] = ap[q];
+          }
+        }
+      }
+      const int kt = kk >> 4;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          const double bq = lds[((((kt * 4 + q) * NT + nt) * 4 + g) << 4) + i];
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = MFMA_F64(a[mt][q], bq, acc[mt][nt]);
+        }
+    }
+  }
+
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int64_t row = row0 + mt * 16 + 4 * rr + g;
+        const int t = n0 + nt * 16 + i;
+        if (row < n && t < ncols) {
+          const double v = acc[mt][nt][rr];
+          if (mode == 0) {
+            basis[row * ld + ccol0 + t] -= v;
+          } else if (mode == 1) {
+            out[row * ldo + t] = v;
+          } else {
+            out[(int64_t)t * ldo + row] = v;
+          }
+        }
+      }
+}
+
+// --------------------------------------------------------------------------------------------
+// block orthonormalization helpers
+// --------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void gram_cholesky_kernel(const double* __restrict__ part, int npart, int b,
+                                                                 double* __restrict__ g_out,
+                                                                 double* __restrict__ rinv_out,
+                                                                 double* __restrict__ r_out,
+                                                                 const double* __restrict__ rprev, double abs_tol2,
+                                                                 double rel_tol) {
+  __shared__ double G[kMaxBlock][kMaxBlock + 1];
+  __shared__ double R[kMaxBlock][kMaxBlock + 1];
+  __shared__ double Ri[kMaxBlock][kMaxBlock + 1];
+  __shared__ int dropped;
+  const int tid = threadIdx.x;
+  for (int e = tid; e < b * b; e += kThreads) {
+    const int c = e / b, t = e % b;
+    double acc = 0.0;
+    const double* p = part + (int64_t)c * kPartialPad + t;
+    const int64_t stride = (int64_t)b * kPartialPad;
+    for (int q = 0; q < npart; ++q) acc += p[q * stride];
+    G[c][t] = acc;
+    R[c][t] = 0.0;
+    Ri[c][t] = 0.0;
+  }
+  __syncthreads();
+  if (g_out)
+    for (int e = tid; e < b * b; e += kThreads) {
+      const int c = e / b, t = e % b;
+      g_out[c * kPartialPad + t] = c <= t ? G[c][t] : G[t][c];  // mirror the upper triangle
+    }
+  // Cholesky G = R^T R on the upper triangle, dropping dependent columns
+  for (int k = 0; k < b; ++k) {
+    if (tid == 0) {
+      double p = G[k][k];
+      for (int q = 0; q < k; ++q) p -= R[q][k] * R[q][k];
+      const bool drop = !(G[k][k] > abs_tol2) || !(p > rel_tol * G[k][k]);
+      dropped = drop ? 1 : 0;
+      R[k][k] = drop ? 0.0 : sqrt(p);
+    }
+    __syncthreads();
+    if (tid > k && tid < b && !dropped) {
+      double v = G[k][tid];
+      for (int q = 0; q < k; ++q) v -= R[q][k] * R[q][tid];
+      R[k][tid] = v / R[k][k];
+    }
+    __syncthreads();
+  }
+  // inverse of R on the kept columns, one thread per column
+  if (tid < b) {
+    const int c = tid;
+    if (R[c][c] != 0.0) {
+      Ri[c][c] = 1.0 / R[c][c];
+      for (int r = c - 1; r >= 0; --r) {
+        if (R[r][r] == 0.0) continue;
+        double v = 0.0;
+        for (int t = r + 1; t <= c; ++t) v += R[r][t] * Ri[t][c];
+        Ri[r][c] = -v / R[r][r];
+      }
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < b * b; e += kThreads) {
+    const int c = e / b, t = e % b;
+    if (rinv_out) rinv_out[c * kPartialPad + t] = Ri[c][t];
+    if (r_out) {
+      double v = R[c][t];
+      if (rprev) {
+        v = 0.0;
+        for (int q = c; q < b; ++q) v += R[c][q] * rprev[q * kPartialPad + t];
+      }
+      r_out[c * kPartialPad + t] = v;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void apply_rinv_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
+                                                              int col0, int b, const double* __restrict__ rinv,
+                                                              double* __restrict__ z, const double* __restrict__ s) {
+  __shared__ double Ri[kMaxBlock][kMaxBlock + 1];
+  for (int e = threadIdx.x; e < b * b; e += kThreads) Ri[e / b][e % b] = rinv[(e / b) * kPartialPad + (e % b)];
+  __syncthreads();
+  const int rows_per_block = kThreads / b;
+  const int t = threadIdx.x % b;
+  const int64_t row = (int64_t)blockIdx.x * rows_per_block + threadIdx.x / b;
+  double acc = 0.0;
+  if (row < n) {
+    const double* w = basis + row * ld + col0;
+    for (int q = 0; q <= t; ++q) acc += w[q] * Ri[q][t];
+  }
+  __syncthreads();  // every thread of the block has read its row before anyone overwrites it
+  if (row < n) {
+    basis[row * ld + col0 + t] = acc;
+    if (z) z[row * b + t] = s[row] * acc;
+  }
+}
+
+// --------------------------------------------------------------------------------------------
+// misc
+// --------------------------------------------------------------------------------------------
+__device__ inline uint64_t mix64(uint64_t x) {
+  x += 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+
+__global__ __launch_bounds__(kThreads) void random_block_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
+                                                                int col0, int b, uint64_t seed, uint64_t stream_id) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= n * b) return;
+  const int64_t i = idx / b;
+  const int t = (int)(idx - i * b);
+  const uint64_t h = mix64(mix64(seed ^ (stream_id * 0xD1B54A32D192ED03ull)) + (uint64_t)idx);
+  const double u = (double)(h >> 11) * (1.0 / 9007199254740992.0);  // [0, 1)
+  basis[i * ld + col0 + t] = 2.0 * u - 1.0;
+}
+
+__global__ __launch_bounds__(kThreads) void copy_cols_kernel(const double* __restrict__ src, int64_t lds, int scol0,
+                                                             double* __restrict__ dst, int64_t ldd, int dcol0, int w,
+                                                             int64_t n) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= n * w) return;
+  const int64_t i = idx / w;
+  const int t = (int)(idx - i * w);
+  dst[i * ldd + dcol0 + t] = src[i * lds + scol0 + t];
+}
+
+}  // namespace
+
+// ============================================================================================
+// launch wrappers
+// ============================================================================================
+hipError_t launch_validate_csr(const int64_t* rowptr, const int32_t* col, int64_t n, int64_t nnz, int* flag,
+                               hipStream_t st) {
+  hipLaunchKernelGGL(validate_rowptr_kernel, dim3((unsigned)ceil_div64(n, kThreads)), dim3(kThreads), 0, st, rowptr,
+                     n, nnz, flag);
+  if (nnz > 0) {
+    int64_t blocks = ceil_div64(nnz, kThreads);
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(validate_col_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, col, nnz, n, flag);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_degree_scaling(const int64_t* rowptr, const double* val, int64_t n, double* d, double* s, int* flag,
+                                 hipStream_t st) {
+  hipLaunchKernelGGL(degree_kernel, dim3((unsigned)ceil_div64(n * 16, kThreads)), dim3(kThreads), 0, st, rowptr, val,
+                     n, d, s, flag);
+  return hipGetLastError();
+}
+
+hipError_t launch_pack_scaled(const double* x, int64_t ldx, const double* s, int64_t n, int b, double* z,
+                              hipStream_t st) {
+  hipLaunchKernelGGL(pack_scaled_kernel, dim3((unsigned)ceil_div64(n * b, kThreads)), dim3(kThreads), 0, st, x, ldx,
+                     s, n, b, z);
+  return hipGetLastError();
+}
+
+hipError_t launch_spmm(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
+                       const double* z, int b, double* y, int64_t ldy, double avg_deg, hipStream_t st) {
+  switch (b) {
+    case 1: return launch_spmm_nz<1>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
+    case 2: return launch_spmm_nz<2>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
+    case 4: return launch_spmm_nz<4>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
+    case 8:
+      hipLaunchKernelGGL((spmm_cols_kernel<8>), dim3((unsigned)ceil_div64(n, kThreads / 8)), dim3(kThreads), 0, st,
+                         rowptr, col, val, s, z, y, ldy, n);
+      break;
+    case 16:
+      hipLaunchKernelGGL((spmm_cols_kernel<16>), dim3((unsigned)ceil_div64(n, kThreads / 16)), dim3(kThreads), 0, st,
+                         rowptr, col, val, s, z, y, ldy, n);
+      break;
+    case 32:
+      hipLaunchKernelGGL((spmm_cols_kernel<32>), dim3((unsigned)ceil_div64(n, kThreads / 32)), dim3(kThreads), 0, st,
+                         rowptr, col, val, s, z, y, ldy, n);
+      break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+ProjectPlan plan_project(int64_t n, int ja, int max_partials) {
+  ProjectPlan p;
+  p.nwc = ja <= 64 ? 1 : (ja <= 128 ? 2 : 4);
+  const int nwr = 4 / p.nwc;
+  // aim at ~1024 workgroups' worth of row panels, at least 64 rows per wave slice
+  int64_t rows = ceil_div64(n, 1024);
+  const int64_t min_rows = 64 * nwr;
+  if (rows < min_rows) rows = min_rows;
+  rows = ceil_div64(rows, 16 * nwr) * 16 * nwr;
+  while (ceil_div64(n, rows) * nwr > max_partials) rows *= 2;
+  p.rows_per_panel = (int)rows;
+  p.npart = (int)(ceil_div64(n, rows) * nwr);
+  return p;
+}
+
+hipError_t launch_project(const double* basis, int64_t n, int64_t ld, int acol0, int ja, int bcol0, int b,
+                          const ProjectPlan& plan, double* part, hipStream_t st) {
+  if (ja <= 0) return hipSuccess;
+  const int panels = plan.npart / (4 / plan.nwc);
+  const dim3 grid((unsigned)panels, (unsigned)((ja + 64 * plan.nwc - 1) / (64 * plan.nwc)));
+  const int vec_ok = (ld % 4 == 0 && acol0 % 4 == 0 && (reinterpret_cast<uintptr_t>(basis) % 32 == 0)) ? 1 : 0;
+  if (b <= 16) {
+    hipLaunchKernelGGL((project_kernel<1>), grid, dim3(kThreads), 0, st, basis, n, ld, acol0, ja, bcol0, b,
+                       plan.rows_per_panel, plan.nwc, vec_ok, part);
+  } else {
+    hipLaunchKernelGGL((project_kernel<2>), grid, dim3(kThreads), 0, st, basis, n, ld, acol0, ja, bcol0, b,
+                       plan.rows_per_panel, plan.nwc, vec_ok, part);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_partials(const double* part, int npart, int ja, int b, double* h, double* hsum,
+                                  int accumulate, double* slot, int slot_row0, hipStream_t st) {
+  if (ja <= 0) return hipSuccess;
+  const int total = ja * kPartialPad;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
+                     part, npart, ja, b, h, hsum, accumulate, slot, slot_row0);
+  return hipGetLastError();
+}
+
+hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int ldb,
+                           int ncols, int mode, int ccol0, double* out, int64_t ldo, hipStream_t st) {
+  if (kdim <= 0 || ncols <= 0) return hipSuccess;
+  const int vec_ok = (ld % 4 == 0 && acol0 % 4 == 0 && (reinterpret_cast<uintptr_t>(basis) % 32 == 0)) ? 1 : 0;
+  constexpr int MT = 2;
+  const unsigned gx = (unsigned)ceil_div64(n, 4 * 16 * MT);
+  if (ncols <= 16) {
+    hipLaunchKernelGGL((row_gemm_kernel<1, MT>), dim3(gx, 1), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, bmat,
+                       ldb, ncols, mode, ccol0, out, ldo, vec_ok);
+  } else if (ncols <= 32) {
+    hipLaunchKernelGGL((row_gemm_kernel<2, MT>), dim3(gx, 1), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, bmat,
+                       ldb, ncols, mode, ccol0, out, ldo, vec_ok);
+  } else {
+    if (mode == 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((row_gemm_kernel<4, MT>), dim3(gx, (unsigned)((ncols + 63) / 64)), dim3(kThreads), 0, st, basis,
+                       n, ld, acol0, kdim, bmat, ldb, ncols, mode, ccol0, out, ldo, vec_ok);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_gram_cholesky(const double* part, int npart, int b, double* g_out, double* rinv, double* rout,
+                                const double* rprev, double abs_tol2, double rel_tol, hipStream_t st) {
+  hipLaunchKernelGGL(gram_cholesky_kernel, dim3(1), dim3(kThreads), 0, st, part, npart, b, g_out, rinv, rout, rprev,
+                     abs_tol2, rel_tol);
+  return hipGetLastError();
+}
+
+hipError_t launch_apply_rinv(double* basis, int64_t n, int64_t ld, int col0, int b, const double* rinv, double* z,
+                             const double* s, hipStream_t st) {
+  hipLaunchKernelGGL(apply_rinv_kernel, dim3((unsigned)ceil_div64(n, kThreads / b)), dim3(kThreads), 0, st, basis, n,
+                     ld, col0, b, rinv, z, s);
+  return hipGetLastError();
+}
+
+hipError_t launch_random_block(double* basis, int64_t n, int64_t ld, int col0, int b, uint64_t seed,
+                               uint64_t stream_id, hipStream_t st) {
+  hipLaunchKernelGGL(random_block_kernel, dim3((unsigned)ceil_div64(n * b, kThreads)), dim3(kThreads), 0, st, basis, n,
+                     ld, col0, b, seed, stream_id);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_cols(const double* src, int64_t lds, int scol0, double* dst, int64_t ldd, int dcol0, int w,
+                            int64_t n, hipStream_t st) {
+  if (w <= 0) return hipSuccess;
+  hipLaunchKernelGGL(copy_cols_kernel, dim3((unsigned)ceil_div64(n * w, kThreads)), dim3(kThreads), 0, st, src, lds,
+                     scol0, dst, ldd, dcol0, w, n);
+  return hipGetLastError();
+}
+
+}  // namespace sceig

@@ -1,0 +1,205 @@
+// Dense symmetric eigensolver for the projected Lanczos problem (the m x m eigendecomposition
+// of the paper's Section IV-B complexity discussion).  Host code, no GPU, no external LAPACK.
+//
+// Method (textbook): Householder reduction to tridiagonal form, accumulation of the orthogonal
+// factor, implicit QL iteration with Wilkinson shifts.  The plane rotations of one QL sweep are
+// recorded and then applied to all rows of the eigenvector matrix at once, which makes the
+// O(n^3) part row-parallel (OpenMP) and contiguous in memory.
+#include "sym_eig.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+namespace sceig {
+
+namespace {
+
+constexpr int kParallelMin = 160;  // below this size the OpenMP fork/join costs more than it saves
+
+// Reduce the symmetric matrix held in q (row-major n x n, full storage) to tridiagonal form
+// (diagonal d, sub-diagonal e with e[i] coupling i and i+1) and overwrite q with the orthogonal
+// matrix Q such that A = Q T Q^T.
+void tridiagonalize(int n, std::vector<double>& q, std::vector<double>& d, std::vector<double>& e) {
+  std::vector<double> vs((size_t)n * n, 0.0);  // Householder vectors, vector k in row k (entries k+1..n-1)
+  std::vector<double> betas(n, 0.0);
+  std::vector<double> p(n), w(n);
+  double* a = q.data();
+  for (int k = 0; k + 2 < n; ++k) {
+    // x = A[k+1:n, k]
+    double* v = &vs[(size_t)k * n];
+    double xnorm2 = 0.0;
+    for (int i = k + 2; i < n; ++i) xnorm2 += a[(size_t)i * n + k] * a[(size_t)i * n + k];
+    const double x0 = a[(size_t)(k + 1) * n + k];
+    if (xnorm2 == 0.0) {
+      betas[k] = 0.0;  // already tridiagonal in this column
+      e[k] = x0;
+      d[k] = a[(size_t)k * n + k];
+      continue;
+    }
+    const double alpha = -std::copysign(std::sqrt(x0 * x0 + xnorm2), x0);
+    // v = x - alpha e1, normalised so that v[0] = 1
+    const double v0 = x0 - alpha;
+    v[k + 1] = 1.0;
+    for (int i = k + 2; i < n; ++i) v[i] = a[(size_t)i * n + k] / v0;
+    const double beta = -v0 / alpha;  // H = I - beta v v^T
+    betas[k] = beta;
+    e[k] = alpha;
+    d[k] = a[(size_t)k * n + k];
+    // p = beta * A22 v
+    const int lo = k + 1;
+#pragma omp parallel for schedule(static) if (n - lo >= kParallelMin)
+    for (int i = lo; i < n; ++i) {
+      const double* row = a + (size_t)i * n;
+      double s = 0.0;
+      for (int j = lo; j < n; ++j) s += row[j] * v[j];
+      p[i] = beta * s;
+    }
+    double pv = 0.0;
+    for (int i = lo; i < n; ++i) pv += p[i] * v[i];
+    const double half = 0.5 * beta * pv;
+    for (int i = lo; i < n; ++i) w[i] = p[i] - half * v[i];
+    // A22 -= v w^T + w v^T
+#pragma omp parallel for schedule(static) if (n - lo >= kParallelMin)
+    for (int i = lo; i < n; ++i) {
+      double* row = a + (size_t)i * n;
+      const double vi = v[i], wi = w[i];
+      for (int j = lo; j < n; ++j) row[j] -= vi * w[j] + wi * v[j];
+    }
+  }
+  if (n >= 2) {
+    d[n - 2] = a[(size_t)(n - 2) * n + (n - 2)];
+    e[n - 2] = a[(size_t)(n - 1) * n + (n - 2)];
+  }
+  d[n - 1] = a[(size_t)(n - 1) * n + (n - 1)];
+  if (n >= 1) e[n - 1] = 0.0;
+  // Q = H_0 H_1 ... H_{n-3}, accumulated backwards into q (row-major)
+  std::fill(q.begin(), q.end(), 0.0);
+  for (int i = 0; i < n; ++i) a[(size_t)i * n + i] = 1.0;
+  std::vector<double> t(n);
+  for (int k = n - 3; k >= 0; --k) {
+    const double beta = betas[k];
+    if (beta == 0.0) continue;
+    const double* v = &vs[(size_t)k * n];
+    const int lo = k + 1;
+    // Q[lo:, lo:] -= beta v (v^T Q[lo:, lo:])
+    std::fill(t.begin(), t.end(), 0.0);
+    for (int i = lo; i < n; ++i) {
+      const double vi = v[i];
+      const double* row = a + (size_t)i * n;
+      for (int j = lo; j < n; ++j) t[j] += vi * row[j];
+    }
+#pragma omp parallel for schedule(static) if (n - lo >= kParallelMin)
+    for (int i = lo; i < n; ++i) {
+      const double bv = beta * v[i];
+      double* row = a + (size_t)i * n;
+      for (int j = lo; j < n; ++j) row[j] -= bv * t[j];
+    }
+  }
+}
+
+struct Rot {
+  double c, s;
+};
+
+// Implicit QL on (d, e); z (row-major n x n, may be null) is multiplied from the right by the
+// accumulated rotations.  Returns false if some eigenvalue needs more than 60 iterations.
+bool ql_implicit(int n, std::vector<double>& d, std::vector<double>& e, double* z) {
+  std::vector<Rot> rots(n);
+  for (int l = 0; l < n; ++l) {
+    int iter = 0;
+    while (true) {
+      int m = l;
+      for (; m + 1 < n; ++m) {
+        const double dd = std::fabs(d[m]) + std::fabs(d[m + 1]);
+        if (std::fabs(e[m]) <= 2.220446049250313e-16 * dd) break;
+      }
+      if (m == l) break;
+      if (++iter > 60) return false;
+      // Wilkinson shift from the leading 2x2 of the unreduced block
+      double g = (d[l + 1] - d[l]) / (2.0 * e[l]);
+      double r = std::hypot(g, 1.0);
+      g = d[m] - d[l] + e[l] / (g + std::copysign(r, g));
+      double s = 1.0, c = 1.0, p = 0.0;
+      int i = m - 1;
+      bool underflow = false;
+      for (; i >= l; --i) {
+        double f = s * e[i];
+        const double b = c * e[i];
+        r = std::hypot(f, g);
+        e[i + 1] = r;
+        if (r == 0.0) {
+          d[i + 1] -= p;
+          e[m] = 0.0;
+          underflow = true;
+          break;
+        }
+        s = f / r;
+        c = g / r;
+        g = d[i + 1] - p;
+        r = (d[i] - g) * s + 2.0 * c * b;
+        p = s * r;
+        d[i + 1] = g + p;
+        g = c * r - b;
+        rots[i] = {c, s};
+      }
+      const int first = underflow ? i + 1 : l;  // rotations recorded for indices first..m-1
+      if (z) {
+        const int cnt = m - first;
+        if (cnt > 0) {
+#pragma omp parallel for schedule(static) if (n >= kParallelMin && (long)n * cnt >= 20000)
+          for (int row = 0; row < n; ++row) {
+            double* zr = z + (size_t)row * n;
+            for (int t = m - 1; t >= first; --t) {
+              const double cc = rots[t].c, ss = rots[t].s;
+              const double f = zr[t + 1];
+              zr[t + 1] = ss * zr[t] + cc * f;
+              zr[t] = cc * zr[t] - ss * f;
+            }
+          }
+        }
+      }
+      if (underflow) continue;
+      d[l] -= p;
+      e[l] = g;
+      e[m] = 0.0;
+    }
+  }
+  return true;
+}
+
+}  // namespace
+
+int sym_eig(const double* a_in, int n, double* w, double* z_out) {
+  if (n <= 0) return 0;
+  std::vector<double> q((size_t)n * n);
+  // symmetrise on the way in (callers fill both triangles, this removes rounding asymmetry)
+  for (int i = 0; i < n; ++i)
+    for (int j = 0; j < n; ++j) q[(size_t)i * n + j] = 0.5 * (a_in[(size_t)i * n + j] + a_in[(size_t)j * n + i]);
+  std::vector<double> d(n), e(n);
+  if (n == 1) {
+    w[0] = q[0];
+    if (z_out) z_out[0] = 1.0;
+    return 0;
+  }
+  tridiagonalize(n, q, d, e);
+  if (!ql_implicit(n, d, e, z_out ? q.data() : nullptr)) return 1;
+  // sort ascending, permuting eigenvector columns
+  std::vector<int> order(n);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return d[x] < d[y]; });
+  for (int t = 0; t < n; ++t) w[t] = d[order[t]];
+  if (z_out) {
+#pragma omp parallel for schedule(static) if (n >= kParallelMin)
+    for (int i = 0; i < n; ++i) {
+      const double* src = &q[(size_t)i * n];
+      double* dst = z_out + (size_t)i * n;
+      for (int t = 0; t < n; ++t) dst[t] = src[order[t]];
+    }
+  }
+  return 0;
+}
+
+}  // namespace sceig

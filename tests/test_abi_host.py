@@ -1,0 +1,111 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol the header declares,
+the host projected-eigenproblem solver is right, and argument errors that are decided before any
+GPU work come back as error codes."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1802_04450_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "sceig.h")).read()
+    declared = set(re.findall(r"\b(sc_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS), declared ^ set(binding.EXPORTS)
+    lib = binding.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.sc_version() >= 100
+    assert binding.strerror(binding.SC_EZERODEG)
+
+
+def test_struct_layouts_match_header_sizes():
+    # sc_options: 3 x int32 + uint32 + uint64 = 24 bytes; sc_stats: 6 x int32 + 2 x int64 + 4 x double = 72
+    assert ctypes.sizeof(binding.ScOptions) == 24
+    assert ctypes.sizeof(binding.ScStats) == 72
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 10, 57, 200])
+def test_sym_eig_against_numpy(n):
+    rng = np.random.default_rng(n)
+    a = rng.standard_normal((n, n))
+    a = a + a.T
+    w, z = binding.sc_sym_eig(a)
+    assert np.allclose(w, np.linalg.eigvalsh(a), atol=1e-11 * max(1, n))
+    assert np.max(np.abs(z.T @ z - np.eye(n))) < 1e-11
+    assert np.max(np.abs(a @ z - z * w[None, :])) < 1e-10 * max(1, n)
+
+
+def test_sym_eig_structured_cases():
+    # diagonal, repeated eigenvalues, block-tridiagonal with an arrow head and a decoupled -2 "ghost"
+    w, z = binding.sc_sym_eig(np.diag([3.0, -1.0, 2.0, 2.0]))
+    assert np.allclose(w, [-1.0, 2.0, 2.0, 3.0])
+    n = 24
+    t = np.zeros((n, n))
+    t[np.arange(8), np.arange(8)] = np.linspace(1.0, 0.9, 8)
+    rng = np.random.default_rng(0)
+    c = 1e-3 * rng.standard_normal((4, 8))
+    t[8:12, :8] = c
+    t[:8, 8:12] = c.T
+    for blk in range(8, n, 4):
+        a = rng.standard_normal((4, 4))
+        t[blk:blk + 4, blk:blk + 4] = 0.1 * (a + a.T)
+        if blk + 4 < n:
+            r = np.triu(rng.standard_normal((4, 4)))
+            t[blk + 4:blk + 8, blk:blk + 4] = r
+            t[blk:blk + 4, blk + 4:blk + 8] = r.T
+    t[5, :] = 0.0
+    t[:, 5] = 0.0
+    t[5, 5] = -2.0
+    w, z = binding.sc_sym_eig(t)
+    assert np.allclose(w, np.linalg.eigvalsh(t), atol=1e-12)
+    assert np.max(np.abs(t @ z - z * w[None, :])) < 1e-12
+    ghost = np.argmin(np.abs(w + 2.0))
+    assert abs(abs(z[5, ghost]) - 1.0) < 1e-14      # the decoupled row keeps its own unit eigenvector
+    w_only, none = binding.sc_sym_eig(t, vectors=False)
+    assert none is None and np.allclose(w_only, w, atol=1e-12)
+
+
+def test_sym_eig_larger_parallel_path():
+    n = 400
+    rng = np.random.default_rng(1)
+    q, _ = np.linalg.qr(rng.standard_normal((n, n)))
+    lam = np.concatenate([np.ones(40), rng.uniform(-1, 0.5, n - 40)])   # a 40-fold eigenvalue
+    a = (q * lam) @ q.T
+    w, z = binding.sc_sym_eig(a)
+    assert np.allclose(w, np.sort(lam), atol=1e-11)
+    assert np.max(np.abs(z.T @ z - np.eye(n))) < 1e-11
+    assert np.max(np.abs(a @ z - z * w[None, :])) < 1e-11
+
+
+def test_argument_errors_without_gpu():
+    lib = binding.lib()
+    one = ctypes.c_void_p(8)        # non-null dummy; never dereferenced because validation fails first
+    null = ctypes.c_void_p(0)
+    f = lib.sc_laplacian_eigsh
+    assert f(null, one, one, 10, 2, 1e-8, 10, one, one, null, None, None) == binding.SC_EINVAL
+    assert f(one, one, one, -1, 2, 1e-8, 10, one, one, null, None, None) == binding.SC_EINVAL
+    assert f(one, one, one, 10, 0, 1e-8, 10, one, one, null, None, None) == binding.SC_EDOMAIN
+    assert f(one, one, one, 10, 10, 1e-8, 10, one, one, null, None, None) == binding.SC_EDOMAIN   # k >= n
+    assert f(one, one, one, 10, 2, -1.0, 10, one, one, null, None, None) == binding.SC_EDOMAIN
+    assert f(one, one, one, 10, 2, float("nan"), 10, one, one, null, None, None) == binding.SC_EDOMAIN
+    assert f(one, one, one, 10, 2, 1e-8, 0, one, one, null, None, None) == binding.SC_EDOMAIN      # maxiter < 1
+    opt = binding.ScOptions(m=11)                                                                  # m > n
+    assert f(one, one, one, 10, 2, 1e-8, 10, one, one, null, ctypes.byref(opt), None) == binding.SC_EDOMAIN
+    opt = binding.ScOptions(m=10, block=3)                                                         # block not a power of 2
+    assert f(one, one, one, 10, 2, 1e-8, 10, one, one, null, ctypes.byref(opt), None) == binding.SC_EDOMAIN
+    opt = binding.ScOptions(m=10, block=4)                                                         # k + 3b > m
+    assert f(one, one, one, 10, 2, 1e-8, 10, one, one, null, ctypes.byref(opt), None) == binding.SC_EDOMAIN
+    assert lib.sc_spmm_normalized(one, one, one, one, 10, one, 3, one, 3, 3, null, null) == binding.SC_EDOMAIN
+    assert lib.sc_spmm_normalized(one, one, one, one, 10, one, 2, one, 4, 4, null, null) == binding.SC_EDOMAIN  # ldx < ncols
+    assert lib.sc_cgs2(null, 10, 8, 2, 2, null, null) == binding.SC_EINVAL
+    assert lib.sc_cgs2(one, 10, 3, 2, 2, null, null) == binding.SC_EDOMAIN                         # ld < j + b
+    assert lib.sc_block_qr(one, 10, 8, 2, 5, null, null, null) == binding.SC_EDOMAIN
+    assert lib.sc_rotate(one, 10, 8, 0, 9, one, 2, one, 2, 0, null) == binding.SC_EDOMAIN          # ld < j0 + ja
+    assert lib.sc_sym_eig(null, 3, one, null) == binding.SC_EINVAL
+    assert lib.sc_degree_scaling(one, one, one, 0, null, one, null) == binding.SC_OK               # n = 0: nothing to do

@@ -1,0 +1,172 @@
+"""GPU parity of the whole hot path (sc_laplacian_eigsh through the C ABI) against the CPU oracle.
+
+Bars (eigenvalue / residual / angle) are in tests/parity.py.  Inside a multiple eigenvalue any
+orthonormal basis is correct, so subspaces are compared per separated cluster; when k cuts a cluster the
+GPU vectors must lie in the oracle's cluster space."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import dense, lanczos, components, compare
+from paper_1802_04450_amd import workloads as wl
+from parity import check_against_oracle
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_1802_04450_amd import binding
+    binding.lib()
+    return binding
+
+
+def solve(B, graph, k, tol, **kw):
+    rp, c, v, n = graph
+    drp, dc, dv = B.csr_to_device(rp, c, v)
+    evals, evecs, code, stats = B.sc_laplacian_eigsh(drp, dc, dv, k, tol, **kw)
+    return evals.cpu().numpy(), evecs.cpu().numpy().T.copy(), code, stats
+
+
+CLOSED_FORM = [
+    ("ring50", lambda: wl.ring(50), 5),
+    ("path60", lambda: wl.path(60), 5),
+    ("hypercube6", lambda: wl.hypercube(6), 7),
+    ("complete12", lambda: wl.complete(12), 4),
+    ("bipartite4x7", lambda: wl.complete_bipartite(4, 7), 3),
+    ("union", lambda: wl.disjoint_union(wl.ring(9), wl.ring(14), wl.path(11), wl.random_weighted_connected(40, 80, 7),
+                                        wl.complete(6)), 7),
+    ("ring301", lambda: wl.ring(301), 9),
+]
+
+
+@pytest.mark.parametrize("name,make,k", CLOSED_FORM, ids=[c[0] for c in CLOSED_FORM])
+def test_closed_form_graphs_match_dense_oracle(B, name, make, k):
+    g = make()
+    rp, c, v, n = g
+    lam_full, vec_full = dense.full_spectrum(rp, c, v)
+    lam, vec, code, stats = solve(B, g, k, 1e-10)
+    assert code == B.SC_OK, stats
+    check_against_oracle(g, k, lam, vec, lam_full[:k + 1], vec_full[:, :k])
+
+
+@pytest.mark.parametrize("block", [1, 2, 4, 8])
+def test_block_sizes_on_multiplicity_graph(B, block):
+    # 6 components -> 6 zeros; then the rings' double eigenvalues
+    g = wl.disjoint_union(*[wl.ring(20 + 3 * t) for t in range(6)])
+    rp, c, v, n = g
+    lam_full, vec_full = dense.full_spectrum(rp, c, v)
+    k = 9
+    lam, vec, code, stats = solve(B, g, k, 1e-10, block=block, m=60)
+    assert code == B.SC_OK and stats["block"] == block
+    check_against_oracle(g, k, lam, vec, lam_full[:k + 1], vec_full[:, :k])
+    assert np.sum(np.abs(lam) < 1e-9) == 6
+
+
+def test_config1_full_size(B):
+    cfg = wl.CONFIGS[1]
+    g, label, _ = wl.build_config_graph(cfg, device="cpu")
+    rp, c, v, n = g
+    lam_full, vec_full = dense.full_spectrum(rp, c, v)
+    lam, vec, code, stats = solve(B, g, cfg.k, cfg.tol)
+    assert code == B.SC_OK, stats
+    out = check_against_oracle(g, cfg.k, lam, vec, lam_full[:cfg.k + 1], vec_full[:, :cfg.k],
+                               cluster_basis=components.null_space(rp, c, v))
+    assert np.max(np.abs(lam)) < 1e-9
+    # also against the Lanczos oracle, and for more pairs than components (k = 12 > 8)
+    lam_o, vec_o = lanczos.lanczos_smallest(rp, c, v, k=13, tol=1e-11, seed=3)
+    lam2, vec2, code2, _ = solve(B, g, 12, cfg.tol)
+    assert code2 == B.SC_OK
+    check_against_oracle(g, 12, lam2, vec2, lam_o, vec_o)
+
+
+def test_seed_independence_and_determinism(B):
+    cfg = wl.reduced(wl.CONFIGS[1], n=1500, components=6, k=8)
+    g, _, _ = wl.build_config_graph(cfg, device="cpu")
+    rp, c, v, n = g
+    lam_full, vec_full = dense.full_spectrum(rp, c, v)
+    a = solve(B, g, 8, 1e-10, seed=1)
+    b = solve(B, g, 8, 1e-10, seed=1)
+    c2 = solve(B, g, 8, 1e-10, seed=2)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])      # bitwise reproducible
+    for out in (a, c2):
+        check_against_oracle(g, 8, out[0], out[1], lam_full[:9], vec_full[:, :8])
+
+
+REDUCED = [
+    # (config id, n, components, k, m)   -- reduced instances of the large workloads, same recipe
+    (2, 6000, 12, 12, 48),
+    (3, 8000, 20, 10, 40),      # k < number of components: k cuts the null cluster
+    (5, 6000, 30, 30, 96),
+]
+
+
+@pytest.mark.parametrize("cid,n,comps,k,m", REDUCED, ids=[f"cfg{r[0]}_n{r[1]}" for r in REDUCED])
+def test_reduced_workloads_against_lanczos_and_component_oracles(B, cid, n, comps, k, m):
+    cfg = wl.reduced(wl.CONFIGS[cid], n=n, components=comps, k=k, m=m)
+    g, label, _ = wl.build_config_graph(cfg, device="cuda")
+    rp, c, v, nn = g
+    ncomp, _ = components.component_labels(rp, c, v)
+    lam_o, vec_o = lanczos.lanczos_smallest(rp, c, v, k=k + 1, tol=1e-10, m=max(m, 2 * (k + 1)), seed=11)
+    lam, vec, code, stats = solve(B, g, k, cfg.tol, m=m)
+    assert code == B.SC_OK, stats
+    basis = components.null_space(rp, c, v) if k <= ncomp else None
+    check_against_oracle(g, k, lam, vec, lam_o, vec_o, cluster_basis=basis)
+    assert np.sum(np.abs(lam) < 1e-8) == min(k, ncomp)
+
+
+def test_reduced_blob_workload_3d(B):
+    """Config-4 recipe at reduced size: anisotropic 3-D blobs, near-null ladder above the zeros."""
+    cfg = wl.reduced(wl.CONFIGS[4], n=20000, components=6, k=6, m=60)
+    g, label, _ = wl.build_config_graph(cfg, device="cuda")
+    rp, c, v, nn = g
+    ncomp, _ = components.component_labels(rp, c, v)
+    k = 6
+    lam, vec, code, stats = solve(B, g, k, cfg.tol, m=cfg.m)
+    assert code == B.SC_OK, stats
+    lam_c, vec_c = components.smallest_eigenpairs(rp, c, v, k + 1, dense_limit=1500, tol=1e-10)
+    check_against_oracle(g, k, lam, vec, lam_c, vec_c)
+
+
+def test_maxiter_gives_not_converged_with_finite_output(B):
+    g = wl.random_weighted_connected(3000, 9000, seed=9)
+    lam, vec, code, stats = solve(B, g, 6, 1e-13, m=24, block=2, maxiter=1)
+    assert code == B.SC_NOT_CONVERGED
+    assert np.all(np.isfinite(lam)) and np.all(np.diff(lam) >= 0)
+    assert compare.orthonormality_defect(vec) < 1e-9
+
+
+def test_solver_rejects_bad_inputs_on_device(B):
+    rp = np.array([0, 1, 1, 2, 3], dtype=np.int64)
+    c = np.array([2, 0, 2], dtype=np.int32)
+    v = np.array([1.0, 1.0, 1.0])
+    drp, dc, dv = B.csr_to_device(rp, c, v)
+    with pytest.raises(B.ScError) as e:
+        B.sc_laplacian_eigsh(drp, dc, dv, 1, 1e-8, m=4, block=1)
+    assert e.value.code == B.SC_EZERODEG
+    bad = torch.tensor([2, 0, 9], dtype=torch.int32, device="cuda")
+    with pytest.raises(B.ScError) as e:
+        B.sc_laplacian_eigsh(drp, bad, dv, 1, 1e-8, m=4, block=1)
+    assert e.value.code == B.SC_ECSR
+
+
+def test_config2_full_size_bench_configuration(B):
+    """The benchmark workload at full size (n = 100,000, k = 100, m = 200, tol 1e-8) in the launch
+    configuration bench.py times.  Reference: the closed-form null space of the 100 components (exact),
+    eigenvalue 0 with multiplicity 100; residuals recomputed on the host."""
+    cfg = wl.CONFIGS[2]
+    g, label, _ = wl.build_config_graph(cfg, device="cuda")
+    rp, c, v, n = g
+    ncomp, _ = components.component_labels(rp, c, v)
+    assert ncomp == cfg.components
+    lam, vec, code, stats = solve(B, g, cfg.k, cfg.tol, m=cfg.m)
+    assert code == B.SC_OK, stats
+    basis = components.null_space(rp, c, v)
+    out = check_against_oracle(g, cfg.k, lam, vec, np.zeros(cfg.k), basis, cluster_basis=basis)
+    assert np.max(compare.principal_angles(vec, basis)) <= 1e-5
+    print("config2", stats, out)

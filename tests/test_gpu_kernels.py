@@ -1,0 +1,165 @@
+"""GPU parity of every kernel-level step against the oracle's definitions, through the C ABI.
+
+Sizes span several tiles (64-column MFMA tiles, 16/32-row tiles, 256-column workgroups, LDS chunks of
+128/256 contraction indices) and ragged tails."""
+import numpy as np
+import pytest
+
+from oracle import laplacian, blockops
+from paper_1802_04450_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_1802_04450_amd import binding
+    binding.lib()
+    return binding
+
+
+def _graphs():
+    cfg = wl.reduced(wl.CONFIGS[2], n=5003, components=7, k=7)
+    g_knn, _, _ = wl.build_config_graph(cfg, device="cpu")
+    return {"knn5003": g_knn, "ring1000": wl.ring(1000), "hub": _hub_graph(), "path2": wl.path(2)}
+
+
+def _hub_graph():
+    # one node connected to everybody (degree n-1 = 2999) on top of a ring: extreme row-length skew
+    n = 3000
+    i = np.arange(1, n)
+    u = np.concatenate([np.zeros(n - 1, dtype=np.int64), i[:-1]])
+    v = np.concatenate([i, i[1:]])
+    w = np.random.default_rng(0).uniform(0.5, 2.0, size=u.size)
+    return wl.symmetric_from_edges(u, v, w, n)
+
+
+@pytest.fixture(scope="module")
+def graphs():
+    return _graphs()
+
+
+def test_degree_scaling(B, graphs):
+    for name, (rp, c, v, n) in graphs.items():
+        drp, dc, dv = B.csr_to_device(rp, c, v)
+        d, s = B.sc_degree_scaling(drp, dc, dv)
+        d0 = laplacian.degrees(rp, c, v)
+        assert np.allclose(d.cpu().numpy(), d0, rtol=1e-14, atol=0), name
+        assert np.allclose(s.cpu().numpy(), 1.0 / np.sqrt(d0), rtol=1e-14, atol=0), name
+
+
+def test_zero_degree_and_bad_csr_are_errors(B):
+    rp = np.array([0, 1, 1, 2], dtype=np.int64)      # node 1 isolated
+    c = np.array([2, 0], dtype=np.int32)
+    v = np.array([1.0, 1.0])
+    drp, dc, dv = B.csr_to_device(rp, c, v)
+    with pytest.raises(B.ScError) as e:
+        B.sc_degree_scaling(drp, dc, dv)
+    assert e.value.code == B.SC_EZERODEG
+    assert B.sc_validate_csr(drp, dc) == B.SC_OK
+    bad_col = torch.tensor([2, 7], dtype=torch.int32, device="cuda")
+    assert B.sc_validate_csr(drp, bad_col) == B.SC_ECSR
+    bad_rp = torch.tensor([0, 2, 1, 2], dtype=torch.int64, device="cuda")
+    assert B.sc_validate_csr(bad_rp, dc) == B.SC_ECSR
+    neg = torch.tensor([1.0, -1.0], dtype=torch.float64, device="cuda")   # degree of node 2 = -1
+    rp2 = torch.tensor([0, 1, 2], dtype=torch.int64, device="cuda")
+    c2 = torch.tensor([1, 0], dtype=torch.int32, device="cuda")
+    with pytest.raises(B.ScError) as e:
+        B.sc_degree_scaling(rp2, c2, neg)
+    assert e.value.code == B.SC_EZERODEG
+
+
+@pytest.mark.parametrize("ncols", [1, 2, 4, 8, 16, 32])
+def test_spmm_normalized(B, graphs, ncols):
+    rng = np.random.default_rng(ncols)
+    for name, (rp, c, v, n) in graphs.items():
+        drp, dc, dv = B.csr_to_device(rp, c, v)
+        _, s = B.sc_degree_scaling(drp, dc, dv)
+        x = rng.standard_normal((n, ncols))
+        # leading dimensions larger than ncols: the blocks live inside wider row-major buffers
+        xb = torch.zeros((n, ncols + 3), dtype=torch.float64, device="cuda")
+        xb[:, :ncols] = torch.from_numpy(x).cuda()
+        yb = torch.full((n, ncols + 5), 7.0, dtype=torch.float64, device="cuda")
+        B.sc_spmm_normalized(drp, dc, dv, s, xb[:, :ncols], yb[:, :ncols])
+        y0 = laplacian.apply_s(rp, c, v, x)
+        y = yb[:, :ncols].cpu().numpy()
+        scale = np.abs(y0).max() + 1e-300
+        assert np.max(np.abs(y - y0)) <= 1e-13 * scale, (name, ncols)
+        assert torch.all(yb[:, ncols:] == 7.0)        # nothing written outside the block
+
+
+@pytest.mark.parametrize("n,j,b", [(5000, 70, 16), (4099, 130, 8), (3001, 300, 32), (2500, 17, 1), (2000, 64, 4),
+                                   (777, 5, 2), (70000, 200, 16)])
+def test_cgs2(B, n, j, b):
+    rng = np.random.default_rng(n + j + b)
+    q, _ = np.linalg.qr(rng.standard_normal((n, j)))
+    w = rng.standard_normal((n, b)) + q @ rng.standard_normal((j, b)) * 3.0
+    ld = j + b + 5
+    basis = np.zeros((n, ld))
+    basis[:, :j] = q
+    basis[:, j:j + b] = w
+    basis[:, j + b:] = 3.25
+    dbasis = torch.from_numpy(basis).cuda()
+    h = B.sc_cgs2(dbasis, j, b)
+    w0, h0 = blockops.cgs2_block(q, w)
+    out = dbasis.cpu().numpy()
+    assert np.array_equal(out[:, :j], q) and np.all(out[:, j + b:] == 3.25)
+    assert np.max(np.abs(h.cpu().numpy() - h0)) <= 1e-12 * max(1.0, np.abs(h0).max())
+    assert np.max(np.abs(out[:, j:j + b] - w0)) <= 1e-12 * max(1.0, np.abs(w0).max())
+    assert np.max(np.abs(q.T @ out[:, j:j + b])) <= 1e-13 * np.sqrt(n)
+
+
+@pytest.mark.parametrize("n,j,b", [(5000, 0, 16), (4099, 7, 8), (3001, 40, 32), (2500, 3, 1), (999, 12, 4), (640, 2, 2)])
+def test_block_qr(B, n, j, b):
+    rng = np.random.default_rng(n + b)
+    w = rng.standard_normal((n, b)) * np.logspace(0, -3, b)[None, :]   # columns of different scale
+    ld = j + b + 2
+    basis = rng.standard_normal((n, ld))
+    basis[:, j:j + b] = w
+    before = basis.copy()
+    dbasis = torch.from_numpy(basis).cuda()
+    r, g = B.sc_block_qr(dbasis, j, b)
+    out = dbasis.cpu().numpy()
+    q = out[:, j:j + b]
+    r, g = r.cpu().numpy(), g.cpu().numpy()
+    assert np.array_equal(out[:, :j], before[:, :j]) and np.array_equal(out[:, j + b:], before[:, j + b:])
+    assert np.max(np.abs(q.T @ q - np.eye(b))) <= 1e-13
+    assert np.allclose(np.tril(r, -1), 0.0)
+    assert np.max(np.abs(q @ r - w)) <= 1e-12 * np.abs(w).max()
+    assert np.max(np.abs(g - w.T @ w)) <= 1e-12 * np.abs(w.T @ w).max()
+
+
+def test_block_qr_drops_dependent_and_zero_columns(B):
+    n, b = 3000, 8
+    rng = np.random.default_rng(5)
+    w = rng.standard_normal((n, b))
+    w[:, 3] = 2.0 * w[:, 0] - w[:, 2]        # dependent on earlier columns
+    w[:, 6] = 0.0                             # zero column
+    dbasis = torch.from_numpy(w.copy()).cuda()
+    r, g = B.sc_block_qr(dbasis, 0, b)
+    q = dbasis.cpu().numpy()
+    r = r.cpu().numpy()
+    keep = [0, 1, 2, 4, 5, 7]
+    assert np.all(q[:, 3] == 0.0) and np.all(q[:, 6] == 0.0)
+    assert np.all(r[3, :] == 0.0) and np.all(r[6, :] == 0.0)
+    assert np.max(np.abs(q[:, keep].T @ q[:, keep] - np.eye(6))) <= 1e-13
+    assert np.max(np.abs(q @ r - w)) <= 1e-11
+
+
+@pytest.mark.parametrize("n,j0,ja,l,colmajor", [(5000, 0, 100, 40, False), (4099, 3, 77, 5, False),
+                                                (3001, 8, 300, 130, True), (1000, 1, 16, 1, True),
+                                                (2048, 4, 520, 64, False)])
+def test_rotate(B, n, j0, ja, l, colmajor):
+    rng = np.random.default_rng(n + ja)
+    basis = rng.standard_normal((n, j0 + ja + 3))
+    y = rng.standard_normal((ja, l))
+    dbasis = torch.from_numpy(basis).cuda()
+    out = B.sc_rotate(dbasis, j0, ja, torch.from_numpy(y).cuda(), out_colmajor=colmajor).cpu().numpy()
+    ref = blockops.rotate(basis[:, j0:j0 + ja], y)
+    if colmajor:
+        out = out.T
+    assert np.max(np.abs(out - ref)) <= 1e-12 * np.abs(ref).max()
