@@ -55,7 +55,19 @@ typedef struct sc_options {
   int32_t check_every; /* block steps between convergence checks of the projected problem; default 2 */
   uint32_t flags; /* SC_FLAG_* */
   uint64_t seed;  /* seed of the start / re-injection blocks */
+  uint32_t timing_mask; /* bit f set: time every launch of kernel family f with HIP events on the stream
+                           (SC_FAM_*); results in sc_stats.fam_*; costs two event records per launch */
+  uint32_t reserved;
 } sc_options;
+
+/* kernel families for timing_mask / sc_stats.fam_* */
+#define SC_FAM_SPMM 0    /* sparse product with fused scaling */
+#define SC_FAM_PROJECT 1 /* block projection H = Q^T W of the reorthogonalization (fp64 MFMA) */
+#define SC_FAM_UPDATE 2  /* block update W -= Q H of the reorthogonalization (fp64 MFMA) */
+#define SC_FAM_ROTATE 3  /* restart rotation / Ritz vectors V Y (fp64 MFMA) */
+#define SC_FAM_QR 4      /* Cholesky QR of the new block (Gram, factorisation, scaling), per block step */
+#define SC_FAM_OTHER 5   /* reductions of partial results */
+#define SC_NUM_FAMILIES 6
 
 typedef struct sc_stats {
   int32_t nconv;      /* wanted pairs whose residual estimate met tol */
@@ -70,6 +82,11 @@ typedef struct sc_stats {
   double t_host_eig;  /* seconds in the host projected eigenproblems */
   double t_setup;     /* seconds: validation, degrees, allocation */
   double max_residual_est; /* largest residual estimate among the returned pairs */
+  /* per kernel family, only for the families selected in sc_options.timing_mask: */
+  double fam_time_s[6];   /* summed launch durations (HIP events) */
+  double fam_bytes[6];    /* summed algorithmic bytes of those launches */
+  double fam_flops[6];    /* summed algorithmic flops of those launches */
+  int64_t fam_launches[6];
 } sc_stats;
 
 /*

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libsceig.so")
 SC_OK, SC_NOT_CONVERGED = 0, 1
 SC_EINVAL, SC_EDOMAIN, SC_ECSR, SC_EZERODEG, SC_ENOMEM, SC_EHIP = -1, -2, -3, -4, -5, -6
 SC_FLAG_NO_VERIFY = 1
+FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 
 EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_cgs2",
            "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_strerror", "sc_version"]
@@ -24,17 +25,24 @@ EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_
 
 class ScOptions(ctypes.Structure):
     _fields_ = [("m", ctypes.c_int32), ("block", ctypes.c_int32), ("check_every", ctypes.c_int32),
-                ("flags", ctypes.c_uint32), ("seed", ctypes.c_uint64)]
+                ("flags", ctypes.c_uint32), ("seed", ctypes.c_uint64), ("timing_mask", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32)]
 
 
 class ScStats(ctypes.Structure):
     _fields_ = [("nconv", ctypes.c_int32), ("phases", ctypes.c_int32), ("restarts", ctypes.c_int32),
                 ("block", ctypes.c_int32), ("m", ctypes.c_int32), ("host_eigs", ctypes.c_int32),
                 ("block_steps", ctypes.c_int64), ("spmv_cols", ctypes.c_int64), ("t_total", ctypes.c_double),
-                ("t_host_eig", ctypes.c_double), ("t_setup", ctypes.c_double), ("max_residual_est", ctypes.c_double)]
+                ("t_host_eig", ctypes.c_double), ("t_setup", ctypes.c_double), ("max_residual_est", ctypes.c_double),
+                ("fam_time_s", ctypes.c_double * 6), ("fam_bytes", ctypes.c_double * 6),
+                ("fam_flops", ctypes.c_double * 6), ("fam_launches", ctypes.c_int64 * 6)]
 
     def as_dict(self) -> dict:
-        return {name: getattr(self, name) for name, _ in self._fields_}
+        out = {}
+        for name, _ in self._fields_:
+            v = getattr(self, name)
+            out[name] = list(v) if name.startswith("fam_") else v
+        return out
 
 
 class ScError(RuntimeError):
@@ -52,6 +60,10 @@ def lib() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_1802_04450_amd.build`")
+        # torch ships its own HIP runtime (same soname as the one this library links against).  Loading torch
+        # first makes the dynamic loader bind the library to that copy, so that torch's device pointers and
+        # streams are valid inside the library; two runtimes in one process do not see each other's memory.
+        import torch  # noqa: F401
         _lib = ctypes.CDLL(LIB_PATH)
         vp, i32, i64, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
         _lib.sc_laplacian_eigsh.argtypes = [vp, vp, vp, i64, i32, dbl, i32, vp, vp, vp, ctypes.POINTER(ScOptions),
@@ -106,7 +118,7 @@ def csr_to_device(rowptr: np.ndarray, col: np.ndarray, val: np.ndarray, device="
 
 # ----------------------------------------------------------------------------------------------
 def sc_laplacian_eigsh(rowptr, col, val, k: int, tol: float, maxiter: int = 100000, m: int = 0, block: int = 0,
-                       check_every: int = 0, flags: int = 0, seed: int = 0):
+                       check_every: int = 0, flags: int = 0, seed: int = 0, timing_mask: int = 0):
     """Returns (evals[k] device, evecs (k, n) device - row t is eigenvector t, i.e. the library's
     column-major n x k output -, status code, stats dict)."""
     import torch
@@ -114,7 +126,7 @@ def sc_laplacian_eigsh(rowptr, col, val, k: int, tol: float, maxiter: int = 1000
     _dev(rowptr, torch.int64), _dev(col, torch.int32), _dev(val, torch.float64)
     evals = torch.empty(max(k, 0), dtype=torch.float64, device=rowptr.device)
     evecs = torch.empty((max(k, 0), n), dtype=torch.float64, device=rowptr.device)
-    opt = ScOptions(m=m, block=block, check_every=check_every, flags=flags, seed=seed)
+    opt = ScOptions(m=m, block=block, check_every=check_every, flags=flags, seed=seed, timing_mask=timing_mask)
     stats = ScStats()
     with torch.cuda.device(rowptr.device):
         code = lib().sc_laplacian_eigsh(_ptr(rowptr), _ptr(col), _ptr(val), n, k, tol, maxiter, _ptr(evals),

@@ -19,6 +19,8 @@
 #include <chrono>
 #include <cmath>
 #include <cstdint>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <limits>
 #include <new>
@@ -35,13 +37,26 @@ struct ScError {
   int code;
 };
 
-#define HIP_TRY(expr)                                   \
-  do {                                                  \
-    hipError_t e__ = (expr);                            \
-    if (e__ != hipSuccess) {                            \
-      (void)hipGetLastError();                          \
-      throw ScError{e__ == hipErrorOutOfMemory ? SC_ENOMEM : SC_EHIP}; \
-    }                                                   \
+bool debug_on() {
+  static const bool on = std::getenv("SCEIG_DEBUG") != nullptr;
+  return on;
+}
+
+#define SC_THROW(code_)                                                                  \
+  do {                                                                                   \
+    if (debug_on()) std::fprintf(stderr, "[sceig] error %d at %s:%d\n", (code_), __FILE__, __LINE__); \
+    throw ScError{(code_)};                                                              \
+  } while (0)
+
+#define HIP_TRY(expr)                                                                              \
+  do {                                                                                             \
+    hipError_t e__ = (expr);                                                                       \
+    if (e__ != hipSuccess) {                                                                       \
+      (void)hipGetLastError();                                                                     \
+      if (debug_on())                                                                              \
+        std::fprintf(stderr, "[sceig] %s failed: %s (%s:%d)\n", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
+      throw ScError{e__ == hipErrorOutOfMemory ? SC_ENOMEM : SC_EHIP};                             \
+    }                                                                                              \
   } while (0)
 
 double now_s() {
@@ -84,6 +99,56 @@ struct PinnedBuf {
   ~PinnedBuf() { release(); }
 };
 
+// Optional per-launch timing of selected kernel families with HIP events on the solver's stream.
+enum Family { kFamSpmm = 0, kFamProject = 1, kFamUpdate = 2, kFamRotate = 3, kFamQr = 4, kFamOther = 5 };
+struct KTimer {
+  uint32_t mask = 0;
+  hipStream_t st = nullptr;
+  struct Rec {
+    int fam;
+    hipEvent_t a, b;
+    double bytes, flops;
+  };
+  std::vector<Rec> recs;
+  hipEvent_t cur = nullptr;
+  bool on(int fam) const { return (mask >> fam) & 1u; }
+  void begin(int fam) {
+    if (!on(fam)) return;
+    HIP_TRY(hipEventCreate(&cur));
+    HIP_TRY(hipEventRecord(cur, st));
+  }
+  void end(int fam, double bytes, double flops) {
+    if (!on(fam)) return;
+    hipEvent_t e;
+    HIP_TRY(hipEventCreate(&e));
+    HIP_TRY(hipEventRecord(e, st));
+    recs.push_back(Rec{fam, cur, e, bytes, flops});
+    cur = nullptr;
+  }
+  // after the stream has been synchronised
+  void collect(sc_stats* out) {
+    for (Rec& r : recs) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+        out->fam_time_s[r.fam] += (double)ms * 1e-3;
+        out->fam_launches[r.fam] += 1;
+        out->fam_bytes[r.fam] += r.bytes;
+        out->fam_flops[r.fam] += r.flops;
+      }
+      (void)hipEventDestroy(r.a);
+      (void)hipEventDestroy(r.b);
+    }
+    recs.clear();
+  }
+  ~KTimer() {
+    for (Rec& r : recs) {
+      (void)hipEventDestroy(r.a);
+      (void)hipEventDestroy(r.b);
+    }
+    if (cur) (void)hipEventDestroy(cur);
+  }
+};
+
 constexpr int kPP = kPartialPad;
 constexpr int kSlotDoubles = 3 * kPP * kPP;  // A, R, G
 constexpr int kMaxPartials = 1024;
@@ -99,28 +164,47 @@ int pow2_floor(int x) {
 // CGS2 of basis[:, wcol : wcol+b] against basis[:, 0 : j]; hsum (j x b, stride kPP) = H1 + H2.
 // slot_a (may be null) receives rows [slot_row0, j) of hsum.
 void enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, double* part, double* h1, double* hsum,
-                  double* slot_a, int slot_row0, hipStream_t st) {
+                  double* slot_a, int slot_row0, hipStream_t st, KTimer* tm) {
   if (j <= 0) return;
   const ProjectPlan plan = plan_project(n, j, kMaxPartials);
+  KTimer none;
+  if (!tm) tm = &none;
+  // algorithmic traffic of one pass over the basis: every row reads its j basis entries and its b block
+  // entries once (the update also writes the b block entries back)
+  const double rows = (double)n;
   for (int pass = 0; pass < 2; ++pass) {
+    tm->begin(kFamProject);
     HIP_TRY(launch_project(basis, n, ld, 0, j, wcol, b, plan, part, st));
+    tm->end(kFamProject, 8.0 * rows * (j + b), 2.0 * rows * j * b);
+    tm->begin(kFamOther);
     HIP_TRY(launch_reduce_partials(part, plan.npart, j, b, h1, hsum, pass, pass == 1 ? slot_a : nullptr, slot_row0, st));
+    tm->end(kFamOther, 8.0 * plan.npart * (double)j * b, 0.0);
+    tm->begin(kFamUpdate);
     HIP_TRY(launch_row_gemm(basis, n, ld, 0, j, h1, kPP, b, 0, wcol, nullptr, 0, st));
+    tm->end(kFamUpdate, 8.0 * rows * (j + 2 * b), 2.0 * rows * j * b);
   }
 }
 
-// Cholesky QR twice on basis[:, col : col+b].  r_out / g_out: device b x b (stride kPP) or null.
+// Cholesky QR twice on basis[:, col : col+b].  r_out / g_out: device b x b (stride kPP) or null;
+// gram, rinv, r1: device scratch of kPP*kPP doubles each.
 // z (may be null): packed s-scaled copy of the orthonormalised block.
-void enqueue_block_qr(double* basis, int64_t n, int64_t ld, int col, int b, double* part, double* rinv, double* r1,
-                      double* r_out, double* g_out, double* z, const double* s, hipStream_t st) {
+void enqueue_block_qr(double* basis, int64_t n, int64_t ld, int col, int b, double* part, double* gram, double* rinv,
+                      double* r1, double* r_out, double* g_out, double* z, const double* s, hipStream_t st, KTimer* tm) {
   const ProjectPlan plan = plan_project(n, b, kMaxPartials);
+  KTimer none;
+  if (!tm) tm = &none;
+  const double blk = 8.0 * (double)n * b;
+  tm->begin(kFamQr);
   HIP_TRY(launch_project(basis, n, ld, col, b, col, b, plan, part, st));
-  HIP_TRY(launch_gram_cholesky(part, plan.npart, b, g_out, rinv, r1, nullptr, kAbsDrop2, kRelDrop, st));
+  HIP_TRY(launch_reduce_partials(part, plan.npart, b, b, gram, nullptr, 0, nullptr, 0, st));
+  HIP_TRY(launch_gram_cholesky(gram, b, g_out, rinv, r1, nullptr, kAbsDrop2, kRelDrop, st));
   HIP_TRY(launch_apply_rinv(basis, n, ld, col, b, rinv, nullptr, nullptr, st));
   HIP_TRY(launch_project(basis, n, ld, col, b, col, b, plan, part, st));
+  HIP_TRY(launch_reduce_partials(part, plan.npart, b, b, gram, nullptr, 0, nullptr, 0, st));
   // second pass: a column that survived the first pass has unit norm, so only exact zeros are dropped
-  HIP_TRY(launch_gram_cholesky(part, plan.npart, b, nullptr, rinv, r_out, r1, 0.25, 1e-8, st));
+  HIP_TRY(launch_gram_cholesky(gram, b, nullptr, rinv, r_out, r1, 0.25, 1e-8, st));
   HIP_TRY(launch_apply_rinv(basis, n, ld, col, b, rinv, z, s, st));
+  tm->end(kFamQr, 6.0 * blk + (z ? blk : 0.0), 4.0 * (double)n * b * b + 2.0 * (double)n * b * b);
 }
 
 struct Solver {
@@ -149,9 +233,11 @@ struct Solver {
   int nl = 0;
   std::vector<double> theta_locked, rho_locked;
   sc_stats stats{};
+  KTimer timer;
 
   double* rinv() { return small.p; }
   double* r1() { return small.p + kPP * kPP; }
+  double* gram() { return small.p + 2 * kPP * kPP; }
   double* slot(int i) { return slots.p + (size_t)i * kSlotDoubles; }
   const double* hslot(int i) const { return slots_host.p + (size_t)i * kSlotDoubles; }
 
@@ -161,17 +247,17 @@ struct Solver {
     HIP_TRY(hipMemsetAsync(flag.p, 0, sizeof(int), st));
     HIP_TRY(hipMemcpyAsync(&nnz, rowptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
-    if (nnz < 0) throw ScError{SC_ECSR};
+    if (nnz < 0) SC_THROW(SC_ECSR);
     HIP_TRY(launch_validate_csr(rowptr, col, n, nnz, flag.p, st));
     int hflag = 0;
     HIP_TRY(hipMemcpyAsync(&hflag, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
-    if (hflag & 3) throw ScError{SC_ECSR};
+    if (hflag & 3) SC_THROW(SC_ECSR);
     s.alloc((size_t)n);
     HIP_TRY(launch_degree_scaling(rowptr, val, n, nullptr, s.p, flag.p, st));
     HIP_TRY(hipMemcpyAsync(&hflag, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
-    if (hflag & 4) throw ScError{SC_EZERODEG};
+    if (hflag & 4) SC_THROW(SC_EZERODEG);
     avg_deg = (double)nnz / (double)n;
 
     ld = ((int64_t)m + b + 15) / 16 * 16;
@@ -181,7 +267,7 @@ struct Solver {
     part.alloc((size_t)kMaxPartials * jmax * kPP);
     h1.alloc((size_t)jmax * kPP);
     hsum.alloc((size_t)jmax * kPP);
-    small.alloc(2 * kPP * kPP);
+    small.alloc(3 * kPP * kPP);
     max_slots = m / b + 4;
     slots.alloc((size_t)max_slots * kSlotDoubles);
     slots_host.alloc((size_t)max_slots * kSlotDoubles);
@@ -195,10 +281,14 @@ struct Solver {
   // ---- one block step on the last active block (columns [nl+ja-b, nl+ja)), results into slot si
   void enqueue_step(int ja, int si) {
     const int jt = nl + ja;
+    timer.begin(kFamSpmm);
     HIP_TRY(launch_spmm(rowptr, col, val, s.p, n, z.p, b, basis.p + jt, ld, avg_deg, st));
+    timer.end(kFamSpmm, 12.0 * (double)nnz + 8.0 * (double)(n + 1) + 8.0 * (double)n + 16.0 * (double)n * b,
+              2.0 * (double)nnz * b);
     double* sl = slot(si);
-    enqueue_cgs2(basis.p, n, ld, jt, jt, b, part.p, h1.p, hsum.p, sl, jt - b, st);
-    enqueue_block_qr(basis.p, n, ld, jt, b, part.p, rinv(), r1(), sl + kPP * kPP, sl + 2 * kPP * kPP, z.p, s.p, st);
+    enqueue_cgs2(basis.p, n, ld, jt, jt, b, part.p, h1.p, hsum.p, sl, jt - b, st, &timer);
+    enqueue_block_qr(basis.p, n, ld, jt, b, part.p, gram(), rinv(), r1(), sl + kPP * kPP, sl + 2 * kPP * kPP, z.p, s.p, st,
+                     &timer);
     stats.block_steps += 1;
     stats.spmv_cols += b;
   }
@@ -217,9 +307,11 @@ struct Solver {
     std::vector<double> yl((size_t)ja * l);
     for (int r = 0; r < ja; ++r)
       for (int t = 0; t < l; ++t) yl[(size_t)r * l + t] = ymat[(size_t)r * ycols + sel[t]];
-    if ((size_t)ja * l > yd_cap || (size_t)l > rot_cols) throw ScError{SC_EDOMAIN};
+    if ((size_t)ja * l > yd_cap || (size_t)l > rot_cols) SC_THROW(SC_EDOMAIN);
     HIP_TRY(hipMemcpyAsync(yd.p, yl.data(), yl.size() * sizeof(double), hipMemcpyHostToDevice, st));
+    timer.begin(kFamRotate);
     HIP_TRY(launch_row_gemm(basis.p, n, ld, nl, ja, yd.p, l, l, 1, 0, rot.p, l, st));
+    timer.end(kFamRotate, 8.0 * (double)n * (ja + l), 2.0 * (double)n * ja * l);
     HIP_TRY(launch_copy_cols(rot.p, l, 0, basis.p, ld, dst, l, n, st));
     HIP_TRY(hipStreamSynchronize(st));  // yl (pageable host memory) must stay alive until the copy is done
   }
@@ -246,6 +338,7 @@ struct Solver {
 
   int run(double* evals_out, double* evecs_out) {
     const double t_begin = now_s();
+    timer.st = st;
     setup();
     int cycles = 0;
     bool not_converged = false;
@@ -271,9 +364,9 @@ struct Solver {
 
       // ---- start block
       HIP_TRY(launch_random_block(basis.p, n, ld, nl, b, seed, stream_id++, st));
-      enqueue_cgs2(basis.p, n, ld, nl, nl, b, part.p, h1.p, hsum.p, nullptr, 0, st);
-      enqueue_block_qr(basis.p, n, ld, nl, b, part.p, rinv(), r1(), slot(0) + kPP * kPP, slot(0) + 2 * kPP * kPP, z.p,
-                       s.p, st);
+      enqueue_cgs2(basis.p, n, ld, nl, nl, b, part.p, h1.p, hsum.p, nullptr, 0, st, &timer);
+      enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gram(), rinv(), r1(), slot(0) + kPP * kPP, slot(0) + 2 * kPP * kPP, z.p,
+                       s.p, st, &timer);
       int ja = b;            // active columns whose coupling is (or will be) assembled
       int assembled = 0;     // active columns of T that are final (their block has been multiplied by S)
       int next_slot = 1;     // slot 0 = start block QR
@@ -289,7 +382,7 @@ struct Solver {
       bool phase_over = false;
 
       while (!phase_over) {
-        if (next_slot >= max_slots) throw ScError{SC_EDOMAIN};  // cannot happen: a cycle has at most m/b steps
+        if (next_slot >= max_slots) SC_THROW(SC_EDOMAIN);  // cannot happen: a cycle has at most m/b steps
         enqueue_step(ja, next_slot);
         ++next_slot;
         ++pending;
@@ -343,7 +436,7 @@ struct Solver {
         for (int x = 0; x < ja; ++x) std::memcpy(&Tsub[(size_t)x * ja], &T[(size_t)x * cap], sizeof(double) * ja);
         theta.resize(ja);
         Y.resize((size_t)ja * ja);
-        if (sym_eig(Tsub.data(), ja, theta.data(), Y.data()) != 0) throw ScError{SC_EHIP};
+        if (sym_eig(Tsub.data(), ja, theta.data(), Y.data()) != 0) SC_THROW(SC_EHIP);
         stats.t_host_eig += now_s() - te0;
         stats.host_eigs += 1;
         const double* Rl = hslot(next_slot - 1) + kPP * kPP;
@@ -425,7 +518,7 @@ struct Solver {
           stats.restarts += 1;
           int l = std::max(want + b, ja / 2);
           l = std::min({l, ja - b, nreal, (int)rot_cols});
-          if (l < 1) throw ScError{SC_EDOMAIN};
+          if (l < 1) SC_THROW(SC_EDOMAIN);
           std::vector<int> sel(l);
           for (int t = 0; t < l; ++t) sel[t] = ja - 1 - t;
           rotate_into(ja, Y, ja, sel, nl);
@@ -504,14 +597,14 @@ struct Solver {
       }
       const double te0 = now_s();
       std::vector<double> th(nx), Yx((size_t)nx * nx);
-      if (sym_eig(G.data(), nx, th.data(), Yx.data()) != 0) throw ScError{SC_EHIP};
+      if (sym_eig(G.data(), nx, th.data(), Yx.data()) != 0) SC_THROW(SC_EHIP);
       stats.t_host_eig += now_s() - te0;
       stats.host_eigs += 1;
       std::vector<double> yk((size_t)nx * nfound);
       for (int r = 0; r < nx; ++r)
         for (int t = 0; t < nfound; ++t) yk[(size_t)r * nfound + t] = Yx[(size_t)r * nx + (nx - 1 - t)];
       for (int t = 0; t < nfound; ++t) evals_host[t] = 1.0 - th[nx - 1 - t];
-      if ((size_t)nx * nfound > yd_cap) throw ScError{SC_EDOMAIN};
+      if ((size_t)nx * nfound > yd_cap) SC_THROW(SC_EDOMAIN);
       HIP_TRY(hipMemcpyAsync(yd.p, yk.data(), yk.size() * sizeof(double), hipMemcpyHostToDevice, st));
       HIP_TRY(launch_row_gemm(basis.p, n, ld, 0, nx, yd.p, nfound, nfound, 2, 0, evecs_out, n, st));
       HIP_TRY(hipStreamSynchronize(st));
@@ -529,6 +622,7 @@ struct Solver {
     stats.max_residual_est = maxr;
     stats.block = b;
     stats.m = m;
+    timer.collect(&stats);
     stats.t_total = now_s() - t_begin;
     if (nfound < k) not_converged = true;
     return not_converged ? SC_NOT_CONVERGED : SC_OK;
@@ -590,6 +684,7 @@ int sc_laplacian_eigsh(const int64_t* csr_rowptr, const int32_t* csr_col, const 
   sv.tol = tol;
   sv.maxiter = maxiter;
   sv.flags = o.flags;
+  sv.timer.mask = o.timing_mask;
   sv.seed = o.seed;
   sv.check_every = o.check_every > 0 ? o.check_every : 2;
   sv.st = reinterpret_cast<hipStream_t>(stream);
@@ -736,7 +831,7 @@ int sc_cgs2(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, double* 
         part.alloc((size_t)kMaxPartials * c->j * kPP);
         h1.alloc((size_t)c->j * kPP);
         hsum.alloc((size_t)c->j * kPP);
-        enqueue_cgs2(c->basis, c->n, c->ld, c->j, c->j, c->b, part.p, h1.p, hsum.p, nullptr, 0, c->st);
+        enqueue_cgs2(c->basis, c->n, c->ld, c->j, c->j, c->b, part.p, h1.p, hsum.p, nullptr, 0, c->st, nullptr);
         if (c->h)
           HIP_TRY(hipMemcpy2DAsync(c->h, (size_t)c->b * sizeof(double), hsum.p, (size_t)kPP * sizeof(double),
                                    (size_t)c->b * sizeof(double), (size_t)c->j, hipMemcpyDeviceToDevice, c->st));
@@ -763,12 +858,14 @@ int sc_block_qr(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, doub
         Ctx* c = static_cast<Ctx*>(p);
         DevBuf<double> part, small;
         part.alloc((size_t)kMaxPartials * c->b * kPP);
-        small.alloc(4 * kPP * kPP);
+        small.alloc(5 * kPP * kPP);
         double* rinv = small.p;
         double* r1 = small.p + kPP * kPP;
         double* rr = small.p + 2 * kPP * kPP;
         double* gg = small.p + 3 * kPP * kPP;
-        enqueue_block_qr(c->basis, c->n, c->ld, c->j, c->b, part.p, rinv, r1, rr, gg, nullptr, nullptr, c->st);
+        double* gram = small.p + 4 * kPP * kPP;
+        enqueue_block_qr(c->basis, c->n, c->ld, c->j, c->b, part.p, gram, rinv, r1, rr, gg, nullptr, nullptr, c->st,
+                         nullptr);
         const size_t w = (size_t)c->b * sizeof(double);
         if (c->r)
           HIP_TRY(hipMemcpy2DAsync(c->r, w, rr, (size_t)kPP * sizeof(double), w, (size_t)c->b, hipMemcpyDeviceToDevice,

@@ -54,11 +54,11 @@ hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int 
                            int ncols, int mode, int ccol0, double* out, int64_t ldo, hipStream_t st);
 
 // ---- block orthonormalization --------------------------------------------------------------
-// One Cholesky-QR pass bookkeeping on the summed Gram partials (single workgroup):
-//   g = sum_p part[p] (b x b);  Cholesky g = r^T r with dependent columns dropped (zero row in r,
-//   zero row+column in rinv);  rinv = r^-1 on the kept columns.
+// One Cholesky-QR pass bookkeeping on the Gram matrix g_in (b x b, stride kPartialPad; single workgroup):
+//   Cholesky g = r^T r with dependent columns dropped (zero row in r, zero row+column in rinv);
+//   rinv = r^-1 on the kept columns; g_out = symmetrised copy of g_in.
 //   If rprev != null: rout = r * rprev (composition of two passes) else rout = r.  Any output may be null.
-hipError_t launch_gram_cholesky(const double* part, int npart, int b, double* g_out, double* rinv, double* rout,
+hipError_t launch_gram_cholesky(const double* g_in, int b, double* g_out, double* rinv, double* rout,
                                 const double* rprev, double abs_tol2, double rel_tol, hipStream_t st);
 // basis[:, col0 : col0+b] = basis[:, col0 : col0+b] * rinv  (rinv b x b row-major stride kPartialPad);
 // if z != null also z[i*b + t] = s[i] * new value.

@@ -239,28 +239,43 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const double* __restr
       }
 }
 
+// One output element per 8 threads: thread (e, r) sums the partials p = r*chunk .. (r+1)*chunk-1 in
+// order, then the 8 sub-sums are added in the fixed order r = 0..7, so the result does not depend on
+// scheduling.  Only the b meaningful columns of every kPartialPad-wide row are touched.
+constexpr int kRedSplit = 8;
+constexpr int kRedElems = kThreads / kRedSplit;  // 32 output elements per workgroup
 __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double* __restrict__ part, int npart, int ja,
                                                                    int ncol, double* __restrict__ h,
                                                                    double* __restrict__ hsum, int accumulate,
                                                                    double* __restrict__ slot, int slot_row0) {
-  const int idx = blockIdx.x * kThreads + threadIdx.x;
-  if (idx >= ja * kPartialPad) return;
-  const int t = idx % kPartialPad;
+  __shared__ double sub[kRedSplit][kRedElems + 1];
+  const int el = threadIdx.x % kRedElems, r = threadIdx.x / kRedElems;
+  const int e = blockIdx.x * kRedElems + el;  // element index over ja * ncol
+  const int total = ja * ncol;
+  const int c = e / ncol, t = e - c * ncol;
   double acc = 0.0;
-  if (t < ncol) {
+  if (e < total) {
+    const int chunk = (npart + kRedSplit - 1) / kRedSplit;
+    const int p0 = r * chunk;
+    int p1 = p0 + chunk;
+    if (p1 > npart) p1 = npart;
     const int64_t stride = (int64_t)ja * kPartialPad;
-    const double* p = part + idx;
-    for (int q = 0; q < npart; ++q) acc += p[q * stride];
+    const double* p = part + (int64_t)c * kPartialPad + t;
+    for (int q = p0; q < p1; ++q) acc += p[q * stride];
   }
-  if (h) h[idx] = acc;
-  double tot = acc;
-  if (hsum) {
-    if (accumulate) tot += hsum[idx];
-    hsum[idx] = tot;
-  }
-  if (slot) {
-    const int c = idx / kPartialPad;
-    if (c >= slot_row0) slot[(c - slot_row0) * kPartialPad + t] = tot;
+  sub[r][el] = acc;
+  __syncthreads();
+  if (r == 0 && e < total) {
+    double tot = sub[0][el];
+#pragma unroll
+    for (int q = 1; q < kRedSplit; ++q) tot += sub[q][el];
+    const int idx = c * kPartialPad + t;
+    if (h) h[idx] = tot;
+    if (hsum) {
+      if (accumulate) tot += hsum[idx];
+      hsum[idx] = tot;
+    }
+    if (slot && c >= slot_row0) slot[(c - slot_row0) * kPartialPad + t] = tot;
   }
 }
 
@@ -357,7 +372,7 @@ __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__
 // --------------------------------------------------------------------------------------------
 // block orthonormalization helpers
 // --------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void gram_cholesky_kernel(const double* __restrict__ part, int npart, int b,
+__global__ __launch_bounds__(kThreads) void gram_cholesky_kernel(const double* __restrict__ g_in, int b,
                                                                  double* __restrict__ g_out,
                                                                  double* __restrict__ rinv_out,
                                                                  double* __restrict__ r_out,
@@ -370,11 +385,7 @@ __global__ __launch_bounds__(kThreads) void gram_cholesky_kernel(const double* _
   const int tid = threadIdx.x;
   for (int e = tid; e < b * b; e += kThreads) {
     const int c = e / b, t = e % b;
-    double acc = 0.0;
-    const double* p = part + (int64_t)c * kPartialPad + t;
-    const int64_t stride = (int64_t)b * kPartialPad;
-    for (int q = 0; q < npart; ++q) acc += p[q * stride];
-    G[c][t] = acc;
+    G[c][t] = g_in[c * kPartialPad + t];
     R[c][t] = 0.0;
     Ri[c][t] = 0.0;
   }
@@ -539,12 +550,14 @@ ProjectPlan plan_project(int64_t n, int ja, int max_partials) {
   ProjectPlan p;
   p.nwc = ja <= 64 ? 1 : (ja <= 128 ? 2 : 4);
   const int nwr = 4 / p.nwc;
-  // aim at ~1024 workgroups' worth of row panels, at least 64 rows per wave slice
-  int64_t rows = ceil_div64(n, 1024);
-  const int64_t min_rows = 64 * nwr;
-  if (rows < min_rows) rows = min_rows;
+  const int coltiles = (ja + 64 * p.nwc - 1) / (64 * p.nwc);
+  // about 768 workgroups in total (three per compute unit), at least 16 rows per wave slice, and no
+  // more partial blocks than the reduction is meant to sum
+  int64_t panels = 768 / coltiles;
+  if (panels < 16) panels = 16;
+  if (panels * nwr > max_partials) panels = max_partials / nwr;
+  int64_t rows = ceil_div64(n, panels);
   rows = ceil_div64(rows, 16 * nwr) * 16 * nwr;
-  while (ceil_div64(n, rows) * nwr > max_partials) rows *= 2;
   p.rows_per_panel = (int)rows;
   p.npart = (int)(ceil_div64(n, rows) * nwr);
   return p;
@@ -569,9 +582,9 @@ hipError_t launch_project(const double* basis, int64_t n, int64_t ld, int acol0,
 hipError_t launch_reduce_partials(const double* part, int npart, int ja, int b, double* h, double* hsum,
                                   int accumulate, double* slot, int slot_row0, hipStream_t st) {
   if (ja <= 0) return hipSuccess;
-  const int total = ja * kPartialPad;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
-                     part, npart, ja, b, h, hsum, accumulate, slot, slot_row0);
+  const int total = ja * b;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((total + kRedElems - 1) / kRedElems)), dim3(kThreads), 0,
+                     st, part, npart, ja, b, h, hsum, accumulate, slot, slot_row0);
   return hipGetLastError();
 }
 
@@ -595,9 +608,9 @@ hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int 
   return hipGetLastError();
 }
 
-hipError_t launch_gram_cholesky(const double* part, int npart, int b, double* g_out, double* rinv, double* rout,
+hipError_t launch_gram_cholesky(const double* g_in, int b, double* g_out, double* rinv, double* rout,
                                 const double* rprev, double abs_tol2, double rel_tol, hipStream_t st) {
-  hipLaunchKernelGGL(gram_cholesky_kernel, dim3(1), dim3(kThreads), 0, st, part, npart, b, g_out, rinv, rout, rprev,
+  hipLaunchKernelGGL(gram_cholesky_kernel, dim3(1), dim3(kThreads), 0, st, g_in, b, g_out, rinv, rout, rprev,
                      abs_tol2, rel_tol);
   return hipGetLastError();
 }
