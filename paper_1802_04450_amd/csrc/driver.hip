@@ -151,7 +151,7 @@ struct KTimer {
 
 constexpr int kPP = kPartialPad;
 constexpr int kSlotDoubles = 3 * kPP * kPP;  // A, R, G
-constexpr int kMaxPartials = 1024;
+constexpr int kMaxPartials = 512;
 constexpr double kAbsDrop2 = 1e-24;  // squared norm below which a residual column counts as zero
 constexpr double kRelDrop = 1e-12;   // squared sine below which a column counts as dependent
 

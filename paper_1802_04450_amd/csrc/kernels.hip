@@ -92,6 +92,7 @@ __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __re
   const int64_t e1 = rowptr[row + 1];
   double acc0 = 0.0, acc1 = 0.0;
   for (int64_t e = rowptr[row]; e < e1; e += B) {
+    // lanes past the end of the row carry (column 0, value 0): their products vanish
     int32_t c = 0;
     double a = 0.0;
     if (e + t < e1) {
@@ -99,17 +100,18 @@ __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __re
       a = val[e + t];
     }
     const int cnt = (int)((e1 - e) < (int64_t)B ? (e1 - e) : (int64_t)B);
-    int u = 0;
-    for (; u + 1 < cnt; u += 2) {
-      const int32_t cu0 = __shfl(c, u, B), cu1 = __shfl(c, u + 1, B);
-      const double au0 = __shfl(a, u, B), au1 = __shfl(a, u + 1, B);
-      acc0 += au0 * z[(int64_t)cu0 * B + t];
-      acc1 += au1 * z[(int64_t)cu1 * B + t];
-    }
-    if (u < cnt) {
-      const int32_t cu = __shfl(c, u, B);
-      const double au = __shfl(a, u, B);
-      acc0 += au * z[(int64_t)cu * B + t];
+    for (int u0 = 0; u0 < cnt; u0 += 8) {  // eight gathers in flight per lane
+      double zv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int32_t cu = __shfl(c, u0 + u, B);
+        zv[u] = z[(int64_t)cu * B + t];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u += 2) {
+        acc0 += __shfl(a, u0 + u, B) * zv[u];
+        acc1 += __shfl(a, u0 + u + 1, B) * zv[u + 1];
+      }
     }
   }
   y[row * ldy + t] = s[row] * (acc0 + acc1);
@@ -239,10 +241,10 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const double* __restr
       }
 }
 
-// One output element per 8 threads: thread (e, r) sums the partials p = r*chunk .. (r+1)*chunk-1 in
-// order, then the 8 sub-sums are added in the fixed order r = 0..7, so the result does not depend on
+// One output element per 32 threads: thread (e, r) sums the partials p = r*chunk .. (r+1)*chunk-1 in
+// order, then the 32 sub-sums are added in the fixed order r = 0..31, so the result does not depend on
 // scheduling.  Only the b meaningful columns of every kPartialPad-wide row are touched.
-constexpr int kRedSplit = 8;
+constexpr int kRedSplit = 32;
 constexpr int kRedElems = kThreads / kRedSplit;  // 32 output elements per workgroup
 __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double* __restrict__ part, int npart, int ja,
                                                                    int ncol, double* __restrict__ h,
@@ -261,7 +263,15 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double*
     if (p1 > npart) p1 = npart;
     const int64_t stride = (int64_t)ja * kPartialPad;
     const double* p = part + (int64_t)c * kPartialPad + t;
-    for (int q = p0; q < p1; ++q) acc += p[q * stride];
+    int q = p0;
+    for (; q + 8 <= p1; q += 8) {  // eight independent loads in flight, added in index order
+      double v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = p[(q + u) * stride];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    for (; q < p1; ++q) acc += p[q * stride];
   }
   sub[r][el] = acc;
   __syncthreads();
@@ -372,7 +382,8 @@ __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__
 // --------------------------------------------------------------------------------------------
 // block orthonormalization helpers
 // --------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void gram_cholesky_kernel(const double* __restrict__ g_in, int b,
+constexpr int kCholThreads = 64;  // one wave: its barriers cost next to nothing
+__global__ __launch_bounds__(kCholThreads) void gram_cholesky_kernel(const double* __restrict__ g_in, int b,
                                                                  double* __restrict__ g_out,
                                                                  double* __restrict__ rinv_out,
                                                                  double* __restrict__ r_out,
@@ -383,7 +394,7 @@ __global__ __launch_bounds__(kThreads) void gram_cholesky_kernel(const double* _
   __shared__ double Ri[kMaxBlock][kMaxBlock + 1];
   __shared__ int dropped;
   const int tid = threadIdx.x;
-  for (int e = tid; e < b * b; e += kThreads) {
+  for (int e = tid; e < b * b; e += kCholThreads) {
     const int c = e / b, t = e % b;
     G[c][t] = g_in[c * kPartialPad + t];
     R[c][t] = 0.0;
@@ -391,7 +402,7 @@ __global__ __launch_bounds__(kThreads) void gram_cholesky_kernel(const double* _
   }
   __syncthreads();
   if (g_out)
-    for (int e = tid; e < b * b; e += kThreads) {
+    for (int e = tid; e < b * b; e += kCholThreads) {
       const int c = e / b, t = e % b;
       g_out[c * kPartialPad + t] = c <= t ? G[c][t] : G[t][c];  // mirror the upper triangle
     }
@@ -426,7 +437,7 @@ __global__ __launch_bounds__(kThreads) void gram_cholesky_kernel(const double* _
     }
   }
   __syncthreads();
-  for (int e = tid; e < b * b; e += kThreads) {
+  for (int e = tid; e < b * b; e += kCholThreads) {
     const int c = e / b, t = e % b;
     if (rinv_out) rinv_out[c * kPartialPad + t] = Ri[c][t];
     if (r_out) {
@@ -444,17 +455,15 @@ __global__ __launch_bounds__(kThreads) void apply_rinv_kernel(double* __restrict
                                                               int col0, int b, const double* __restrict__ rinv,
                                                               double* __restrict__ z, const double* __restrict__ s) {
   __shared__ double Ri[kMaxBlock][kMaxBlock + 1];
+  __shared__ double Wt[2 * kThreads];  // rows_per_block rows of b + 1 doubles (b >= 1)
   for (int e = threadIdx.x; e < b * b; e += kThreads) Ri[e / b][e % b] = rinv[(e / b) * kPartialPad + (e % b)];
-  __syncthreads();
   const int rows_per_block = kThreads / b;
-  const int t = threadIdx.x % b;
-  const int64_t row = (int64_t)blockIdx.x * rows_per_block + threadIdx.x / b;
+  const int t = threadIdx.x % b, rl = threadIdx.x / b;
+  const int64_t row = (int64_t)blockIdx.x * rows_per_block + rl;
+  Wt[rl * (b + 1) + t] = row < n ? basis[row * ld + col0 + t] : 0.0;
+  __syncthreads();
   double acc = 0.0;
-  if (row < n) {
-    const double* w = basis + row * ld + col0;
-    for (int q = 0; q <= t; ++q) acc += w[q] * Ri[q][t];
-  }
-  __syncthreads();  // every thread of the block has read its row before anyone overwrites it
+  for (int q = 0; q <= t; ++q) acc += Wt[rl * (b + 1) + q] * Ri[q][t];
   if (row < n) {
     basis[row * ld + col0 + t] = acc;
     if (z) z[row * b + t] = s[row] * acc;
@@ -610,7 +619,7 @@ hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int 
 
 hipError_t launch_gram_cholesky(const double* g_in, int b, double* g_out, double* rinv, double* rout,
                                 const double* rprev, double abs_tol2, double rel_tol, hipStream_t st) {
-  hipLaunchKernelGGL(gram_cholesky_kernel, dim3(1), dim3(kThreads), 0, st, g_in, b, g_out, rinv, rout, rprev,
+  hipLaunchKernelGGL(gram_cholesky_kernel, dim3(1), dim3(kCholThreads), 0, st, g_in, b, g_out, rinv, rout, rprev,
                      abs_tol2, rel_tol);
   return hipGetLastError();
 }
