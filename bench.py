@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--m", type=int, default=-1)
     ap.add_argument("--check-every", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run a plain 1 GiB device copy 10 times (calibration of the HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1")
@@ -82,6 +84,14 @@ def main():
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         sys.exit(2)
+    if args.copy_probe:
+        src = torch.ones(1 << 27, dtype=torch.float64, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": src.numel() * 8, "copy_probe_bytes_written": src.numel() * 8}))
+        return
     from paper_1802_04450_amd import binding as B
     B.lib()
 
