@@ -180,6 +180,15 @@ int sc_rotate(const double* basis, int64_t n, int64_t ld, int32_t j0, int32_t ja
  */
 int sc_sym_eig(const double* a, int32_t n, double* w, double* z);
 
+/*
+ * The same projected eigenproblem when only the leading Ritz vectors are needed (convergence checks, locking,
+ * thick restart): all eigenvalues, eigenvectors of the `count` largest only.  HOST ONLY.
+ *   w     host fp64[n], eigenvalues ascending
+ *   z     host fp64[n*count], row-major n x count; column t is the eigenvector of w[n-1-t]
+ *   0 <= count <= n
+ */
+int sc_sym_eig_top(const double* a, int32_t n, int32_t count, double* w, double* z);
+
 const char* sc_strerror(int code);
 int sc_version(void);
 

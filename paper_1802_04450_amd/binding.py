@@ -20,7 +20,7 @@ SC_FLAG_NO_VERIFY = 1
 FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 
 EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_cgs2",
-           "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_strerror", "sc_version"]
+           "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version"]
 
 
 class ScOptions(ctypes.Structure):
@@ -75,6 +75,7 @@ def lib() -> ctypes.CDLL:
         _lib.sc_block_qr.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         _lib.sc_rotate.argtypes = [vp, i64, i64, i32, i32, vp, i32, vp, i64, i32, vp]
         _lib.sc_sym_eig.argtypes = [vp, i32, vp, vp]
+        _lib.sc_sym_eig_top.argtypes = [vp, i32, i32, vp, vp]
         for name in EXPORTS:
             getattr(_lib, name).restype = ctypes.c_int
         _lib.sc_strerror.restype = ctypes.c_char_p
@@ -220,3 +221,14 @@ def sc_sym_eig(a: np.ndarray, vectors: bool = True) -> Tuple[np.ndarray, Optiona
     code = lib().sc_sym_eig(a.ctypes.data, n, w.ctypes.data, z.ctypes.data if vectors else 0)
     _check(code, soft_ok=False)
     return w, z
+
+
+def sc_sym_eig_top(a: np.ndarray, count: int) -> Tuple[np.ndarray, np.ndarray]:
+    """All eigenvalues (ascending) and the eigenvectors of the `count` largest (column t <-> w[n-1-t])."""
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    n = a.shape[0]
+    w = np.empty(n)
+    z = np.empty((n, max(count, 1)))
+    code = lib().sc_sym_eig_top(a.ctypes.data, n, count, w.ctypes.data, z.ctypes.data)
+    _check(code, soft_ok=False)
+    return w, z[:, :count]

@@ -346,7 +346,9 @@ struct Solver {
     int prev_phase_steps = 0;
     uint64_t stream_id = 0;
 
-    std::vector<double> T, Tsub, theta, Y;
+    std::vector<double> T, Tsub, Y;
+    SelectedEig seig;
+    int ycols = 0;
     std::vector<char> ghost;
 
     while (!finished) {
@@ -430,35 +432,45 @@ struct Solver {
           }
         }
         pending = 0;
-        // ---- Ritz pairs of T[0:ja, 0:ja]
+        // ---- Ritz pairs of T[0:ja, 0:ja]: all values, vectors only for the leading ones that may be used
         const double te0 = now_s();
         Tsub.resize((size_t)ja * ja);
         for (int x = 0; x < ja; ++x) std::memcpy(&Tsub[(size_t)x * ja], &T[(size_t)x * cap], sizeof(double) * ja);
-        theta.resize(ja);
-        Y.resize((size_t)ja * ja);
-        if (sym_eig(Tsub.data(), ja, theta.data(), Y.data()) != 0) SC_THROW(SC_EHIP);
-        stats.t_host_eig += now_s() - te0;
-        stats.host_eigs += 1;
+        if (seig.factor(Tsub.data(), ja) != 0) SC_THROW(SC_EHIP);
+        const std::vector<double>& theta = seig.values();
         const double* Rl = hslot(next_slot - 1) + kPP * kPP;
         const double* Gl = hslot(next_slot - 1) + 2 * kPP * kPP;
         int nreal = 0;
         for (int x = 0; x < ja; ++x) nreal += ghost[x] ? 0 : 1;
         bool exhausted = true;
         for (int x = 0; x < b; ++x) exhausted = exhausted && (Rl[x * kPP + x] == 0.0);
-        // descending non-ghost Ritz pairs: indices ja-1, ja-2, ... (ghosts sit at -2, i.e. at the bottom)
-        std::vector<double> rho(nreal);
-        for (int t = 0; t < nreal; ++t) {
-          const int ci = ja - 1 - t;
+        // thick-restart size, should this inspection end in a restart
+        int l_restart = std::max(want + b, ja / 2);
+        l_restart = std::min({l_restart, ja - b, nreal, (int)rot_cols});
+        int nsel = std::min(nreal, std::max(b, full ? l_restart : 0));
+        auto ritz_vectors = [&](int count) {  // Y: ja x count, column t = Ritz vector of the t-th largest theta
+          std::vector<int> idx(count);
+          for (int t = 0; t < count; ++t) idx[t] = ja - 1 - t;
+          Y.resize((size_t)ja * std::max(count, 1));
+          seig.vectors(idx.data(), count, Y.data());
+          ycols = count;
+        };
+        ritz_vectors(nsel);
+        stats.t_host_eig += now_s() - te0;
+        stats.host_eigs += 1;
+        // residual estimates of the leading pairs (ghosts sit at -2, i.e. at the bottom of the spectrum)
+        std::vector<double> rho(nsel);
+        for (int t = 0; t < nsel; ++t) {
           double acc = 0.0;
           for (int x = 0; x < b; ++x) {
             double gx = 0.0;
-            for (int y = 0; y < b; ++y) gx += Gl[x * kPP + y] * Y[(size_t)(ja - b + y) * ja + ci];
-            acc += gx * Y[(size_t)(ja - b + x) * ja + ci];
+            for (int y = 0; y < b; ++y) gx += Gl[x * kPP + y] * Y[(size_t)(ja - b + y) * ycols + t];
+            acc += gx * Y[(size_t)(ja - b + x) * ycols + t];
           }
           rho[t] = std::sqrt(std::max(acc, 0.0));
         }
         int lead = 0;
-        while (lead < nreal && rho[lead] <= tol) ++lead;
+        while (lead < nsel && rho[lead] <= tol) ++lead;
 
         if (nreal == 0) {  // the deflated space is empty: nothing more exists
           finished = true;
@@ -480,8 +492,8 @@ struct Solver {
             }
           }
           std::vector<int> sel(nlock);
-          for (int t = 0; t < nlock; ++t) sel[t] = ja - 1 - t;
-          rotate_into(ja, Y, ja, sel, nl);
+          for (int t = 0; t < nlock; ++t) sel[t] = t;
+          rotate_into(ja, Y, ycols, sel, nl);
           for (int t = 0; t < nlock; ++t) {
             theta_locked.push_back(theta[ja - 1 - t]);
             rho_locked.push_back(rho[t]);
@@ -500,12 +512,13 @@ struct Solver {
         if (stop_now || (full && cycles >= maxiter)) {
           // out of cycles: take the best unconverged Ritz vectors to fill up the answer
           const int take = std::min({nreal, std::max(0, k - nl), (int)rot_cols});
+          if (take > nsel) ritz_vectors(take);
           std::vector<int> sel(take);
-          for (int t = 0; t < take; ++t) sel[t] = ja - 1 - t;
-          rotate_into(ja, Y, ja, sel, nl);
+          for (int t = 0; t < take; ++t) sel[t] = t;
+          rotate_into(ja, Y, ycols, sel, nl);
           for (int t = 0; t < take; ++t) {
             theta_locked.push_back(theta[ja - 1 - t]);
-            rho_locked.push_back(rho[t]);
+            rho_locked.push_back(t < nsel ? rho[t] : 1.0);
           }
           nl += take;
           not_converged = true;
@@ -516,22 +529,22 @@ struct Solver {
           // ---- thick restart: keep the leading Ritz vectors and the residual block
           cycles += 1;
           stats.restarts += 1;
-          int l = std::max(want + b, ja / 2);
-          l = std::min({l, ja - b, nreal, (int)rot_cols});
+          const int l = l_restart;
           if (l < 1) SC_THROW(SC_EDOMAIN);
+          if (l > ycols) ritz_vectors(l);
           std::vector<int> sel(l);
-          for (int t = 0; t < l; ++t) sel[t] = ja - 1 - t;
-          rotate_into(ja, Y, ja, sel, nl);
+          for (int t = 0; t < l; ++t) sel[t] = t;
+          rotate_into(ja, Y, ycols, sel, nl);
           HIP_TRY(launch_copy_cols(basis.p, ld, nl + ja, rot.p, b, 0, b, n, st));
           HIP_TRY(launch_copy_cols(rot.p, b, 0, basis.p, ld, nl + l, b, n, st));
           std::fill(T.begin(), T.end(), 0.0);
           std::fill(ghost.begin(), ghost.end(), 0);
-          for (int t = 0; t < l; ++t) T[(size_t)t * cap + t] = theta[sel[t]];
+          for (int t = 0; t < l; ++t) T[(size_t)t * cap + t] = theta[ja - 1 - t];
           for (int x = 0; x < b; ++x) {
             ghost[l + x] = (Rl[x * kPP + x] == 0.0);
             for (int t = 0; t < l; ++t) {
               double c = 0.0;
-              for (int y = 0; y < b; ++y) c += Rl[x * kPP + y] * Y[(size_t)(ja - b + y) * ja + sel[t]];
+              for (int y = 0; y < b; ++y) c += Rl[x * kPP + y] * Y[(size_t)(ja - b + y) * ycols + t];
               T[(size_t)(l + x) * cap + t] = c;
               T[(size_t)t * cap + l + x] = c;
             }
@@ -912,6 +925,25 @@ int sc_sym_eig(const double* a, int32_t n, double* w, double* z) {
   if (n == 0) return SC_OK;
   try {
     return sym_eig(a, n, w, z) == 0 ? SC_OK : SC_NOT_CONVERGED;
+  } catch (const std::bad_alloc&) {
+    return SC_ENOMEM;
+  } catch (...) {
+    return SC_EHIP;
+  }
+}
+
+int sc_sym_eig_top(const double* a, int32_t n, int32_t count, double* w, double* z) {
+  if (!a || !w || n < 0 || count < 0 || (count > 0 && !z)) return SC_EINVAL;
+  if (count > n) return SC_EDOMAIN;
+  if (n == 0) return SC_OK;
+  try {
+    SelectedEig se;
+    if (se.factor(a, n) != 0) return SC_NOT_CONVERGED;
+    std::memcpy(w, se.values().data(), sizeof(double) * n);
+    std::vector<int> idx(count);
+    for (int t = 0; t < count; ++t) idx[t] = n - 1 - t;
+    se.vectors(idx.data(), count, z);
+    return SC_OK;
   } catch (const std::bad_alloc&) {
     return SC_ENOMEM;
   } catch (...) {

@@ -22,9 +22,10 @@ constexpr int kParallelMin = 160;  // below this size the OpenMP fork/join costs
 // Reduce the symmetric matrix held in q (row-major n x n, full storage) to tridiagonal form
 // (diagonal d, sub-diagonal e with e[i] coupling i and i+1) and overwrite q with the orthogonal
 // matrix Q such that A = Q T Q^T.
-void tridiagonalize(int n, std::vector<double>& q, std::vector<double>& d, std::vector<double>& e) {
-  std::vector<double> vs((size_t)n * n, 0.0);  // Householder vectors, vector k in row k (entries k+1..n-1)
-  std::vector<double> betas(n, 0.0);
+void tridiagonalize(int n, std::vector<double>& q, std::vector<double>& d, std::vector<double>& e,
+                    std::vector<double>& vs, std::vector<double>& betas, bool form_q) {
+  vs.assign((size_t)n * n, 0.0);  // Householder vectors, vector k in row k (entries k+1..n-1)
+  betas.assign(n, 0.0);
   std::vector<double> p(n), w(n);
   double* a = q.data();
   for (int k = 0; k + 2 < n; ++k) {
@@ -48,25 +49,47 @@ void tridiagonalize(int n, std::vector<double>& q, std::vector<double>& d, std::
     betas[k] = beta;
     e[k] = alpha;
     d[k] = a[(size_t)k * n + k];
-    // p = beta * A22 v
+    // p = beta * A22 v and A22 -= v w^T + w v^T, both on the lower triangle only (row i, columns lo..i)
     const int lo = k + 1;
-#pragma omp parallel for schedule(static) if (n - lo >= kParallelMin)
-    for (int i = lo; i < n; ++i) {
-      const double* row = a + (size_t)i * n;
-      double s = 0.0;
-      for (int j = lo; j < n; ++j) s += row[j] * v[j];
-      p[i] = beta * s;
+    const int len = n - lo;
+    if (len >= kParallelMin) {
+#pragma omp parallel for schedule(static)
+      for (int i = lo; i < n; ++i) {
+        // row i of the symmetric block: left of the diagonal from row i, below the diagonal from column i
+        const double* row = a + (size_t)i * n;
+        double s = 0.0;
+#pragma omp simd reduction(+ : s)
+        for (int j = lo; j <= i; ++j) s += row[j] * v[j];
+        for (int j = i + 1; j < n; ++j) s += a[(size_t)j * n + i] * v[j];
+        p[i] = beta * s;
+      }
+    } else {
+      for (int i = lo; i < n; ++i) p[i] = 0.0;
+      for (int i = lo; i < n; ++i) {
+        const double* row = a + (size_t)i * n;
+        const double vi = v[i];
+        double s = 0.0;
+        double* pp = p.data();
+#pragma omp simd reduction(+ : s)
+        for (int j = lo; j < i; ++j) {
+          s += row[j] * v[j];
+          pp[j] += row[j] * vi;
+        }
+        p[i] += s + row[i] * vi;
+      }
+      for (int i = lo; i < n; ++i) p[i] *= beta;
     }
     double pv = 0.0;
     for (int i = lo; i < n; ++i) pv += p[i] * v[i];
     const double half = 0.5 * beta * pv;
     for (int i = lo; i < n; ++i) w[i] = p[i] - half * v[i];
-    // A22 -= v w^T + w v^T
-#pragma omp parallel for schedule(static) if (n - lo >= kParallelMin)
+#pragma omp parallel for schedule(static) if (len >= kParallelMin)
     for (int i = lo; i < n; ++i) {
       double* row = a + (size_t)i * n;
       const double vi = v[i], wi = w[i];
-      for (int j = lo; j < n; ++j) row[j] -= vi * w[j] + wi * v[j];
+      const double* wp = w.data();
+#pragma omp simd
+      for (int j = lo; j <= i; ++j) row[j] -= vi * wp[j] + wi * v[j];
     }
   }
   if (n >= 2) {
@@ -75,6 +98,7 @@ void tridiagonalize(int n, std::vector<double>& q, std::vector<double>& d, std::
   }
   d[n - 1] = a[(size_t)(n - 1) * n + (n - 1)];
   if (n >= 1) e[n - 1] = 0.0;
+  if (!form_q) return;
   // Q = H_0 H_1 ... H_{n-3}, accumulated backwards into q (row-major)
   std::fill(q.begin(), q.end(), 0.0);
   for (int i = 0; i < n; ++i) a[(size_t)i * n + i] = 1.0;
@@ -106,7 +130,8 @@ struct Rot {
 
 // Implicit QL on (d, e); z (row-major n x n, may be null) is multiplied from the right by the
 // accumulated rotations.  Returns false if some eigenvalue needs more than 60 iterations.
-bool ql_implicit(int n, std::vector<double>& d, std::vector<double>& e, double* z) {
+template <typename Record>
+bool ql_implicit(int n, std::vector<double>& d, std::vector<double>& e, double* z, Record record) {
   std::vector<Rot> rots(n);
   for (int l = 0; l < n; ++l) {
     int iter = 0;
@@ -128,7 +153,7 @@ bool ql_implicit(int n, std::vector<double>& d, std::vector<double>& e, double* 
       for (; i >= l; --i) {
         double f = s * e[i];
         const double b = c * e[i];
-        r = std::hypot(f, g);
+        r = std::sqrt(f * f + g * g);  // entries are O(1): no overflow; an underflow to 0 is handled below
         e[i + 1] = r;
         if (r == 0.0) {
           d[i + 1] -= p;
@@ -146,6 +171,7 @@ bool ql_implicit(int n, std::vector<double>& d, std::vector<double>& e, double* 
         rots[i] = {c, s};
       }
       const int first = underflow ? i + 1 : l;  // rotations recorded for indices first..m-1
+      for (int t = m - 1; t >= first; --t) record(t, rots[t].c, rots[t].s);
       if (z) {
         const int cnt = m - first;
         if (cnt > 0) {
@@ -184,8 +210,9 @@ int sym_eig(const double* a_in, int n, double* w, double* z_out) {
     if (z_out) z_out[0] = 1.0;
     return 0;
   }
-  tridiagonalize(n, q, d, e);
-  if (!ql_implicit(n, d, e, z_out ? q.data() : nullptr)) return 1;
+  std::vector<double> vs, betas;
+  tridiagonalize(n, q, d, e, vs, betas, z_out != nullptr);
+  if (!ql_implicit(n, d, e, z_out ? q.data() : nullptr, [](int, double, double) {})) return 1;
   // sort ascending, permuting eigenvector columns
   std::vector<int> order(n);
   std::iota(order.begin(), order.end(), 0);
@@ -200,6 +227,70 @@ int sym_eig(const double* a_in, int n, double* w, double* z_out) {
     }
   }
   return 0;
+}
+
+int SelectedEig::factor(const double* a_in, int n) {
+  n_ = n;
+  w_.assign(n, 0.0);
+  order_.resize(n);
+  rots_.clear();
+  if (n <= 0) return 0;
+  std::vector<double> q((size_t)n * n);
+  for (int i = 0; i < n; ++i)
+    for (int j = 0; j < n; ++j) q[(size_t)i * n + j] = 0.5 * (a_in[(size_t)i * n + j] + a_in[(size_t)j * n + i]);
+  std::vector<double> d(n), e(n);
+  if (n == 1) {
+    w_[0] = q[0];
+    order_[0] = 0;
+    vs_.assign(1, 0.0);
+    betas_.assign(1, 0.0);
+    return 0;
+  }
+  tridiagonalize(n, q, d, e, vs_, betas_, false);
+  rots_.reserve((size_t)n * n);
+  if (!ql_implicit(n, d, e, nullptr, [this](int i, double c, double s) { rots_.push_back(Rot{i, c, s}); })) return 1;
+  std::iota(order_.begin(), order_.end(), 0);
+  std::stable_sort(order_.begin(), order_.end(), [&](int x, int y) { return d[x] < d[y]; });
+  for (int t = 0; t < n; ++t) w_[t] = d[order_[t]];
+  return 0;
+}
+
+void SelectedEig::vectors(const int* idx, int count, double* out) const {
+  const int n = n_;
+  if (n <= 0 || count <= 0) return;
+  std::fill(out, out + (size_t)n * count, 0.0);
+  for (int t = 0; t < count; ++t) out[(size_t)order_[idx[t]] * count + t] = 1.0;
+  // eigenvectors of the tridiagonal matrix: Z e_j = G_1 (G_2 (... (G_N e_j))), so replay backwards
+  for (size_t r = rots_.size(); r-- > 0;) {
+    const Rot& g = rots_[r];
+    double* a = out + (size_t)g.i * count;
+    double* b = a + count;
+    const double c = g.c, s = g.s;
+#pragma omp simd
+    for (int t = 0; t < count; ++t) {
+      const double x = a[t], y = b[t];
+      a[t] = c * x + s * y;
+      b[t] = c * y - s * x;
+    }
+  }
+  // back through the reflectors: Y = H_0 H_1 ... H_{n-3} Z
+  std::vector<double> tmp(count);
+  for (int k = n - 3; k >= 0; --k) {
+    const double beta = betas_[k];
+    if (beta == 0.0) continue;
+    const double* v = &vs_[(size_t)k * n];
+    std::fill(tmp.begin(), tmp.end(), 0.0);
+    for (int i = k + 1; i < n; ++i) {
+      const double vi = v[i];
+      const double* row = out + (size_t)i * count;
+      for (int t = 0; t < count; ++t) tmp[t] += vi * row[t];
+    }
+    for (int i = k + 1; i < n; ++i) {
+      const double bv = beta * v[i];
+      double* row = out + (size_t)i * count;
+      for (int t = 0; t < count; ++t) row[t] -= bv * tmp[t];
+    }
+  }
 }
 
 }  // namespace sceig

@@ -84,6 +84,24 @@ def test_sym_eig_larger_parallel_path():
     assert np.max(np.abs(a @ z - z * w[None, :])) < 1e-11
 
 
+@pytest.mark.parametrize("n,count", [(1, 1), (2, 2), (9, 3), (64, 16), (150, 75), (333, 40)])
+def test_sym_eig_top_selected_vectors(n, count):
+    rng = np.random.default_rng(n * 7 + count)
+    q, _ = np.linalg.qr(rng.standard_normal((n, n)))
+    lam = rng.uniform(-1, 0.6, n)
+    lam[: min(n, 12)] = 1.0 - 1e-15 * np.arange(min(n, 12))          # a tight cluster at the top, as in the solver
+    a = (q * lam) @ q.T
+    a = 0.5 * (a + a.T)
+    w, z = binding.sc_sym_eig_top(a, count)
+    assert np.allclose(w, np.linalg.eigvalsh(a), atol=1e-12)
+    assert z.shape == (n, count)
+    assert np.max(np.abs(z.T @ z - np.eye(count))) < 1e-12
+    top = w[::-1][:count]
+    assert np.max(np.abs(a @ z - z * top[None, :])) < 1e-12
+    w_full, z_full = binding.sc_sym_eig(a)
+    assert np.allclose(w, w_full, atol=1e-13)
+
+
 def test_argument_errors_without_gpu():
     lib = binding.lib()
     one = ctypes.c_void_p(8)        # non-null dummy; never dereferenced because validation fails first
@@ -109,4 +127,6 @@ def test_argument_errors_without_gpu():
     assert lib.sc_block_qr(one, 10, 8, 2, 5, null, null, null) == binding.SC_EDOMAIN
     assert lib.sc_rotate(one, 10, 8, 0, 9, one, 2, one, 2, 0, null) == binding.SC_EDOMAIN          # ld < j0 + ja
     assert lib.sc_sym_eig(null, 3, one, null) == binding.SC_EINVAL
+    assert lib.sc_sym_eig_top(one, 3, 4, one, one) == binding.SC_EDOMAIN
+    assert lib.sc_sym_eig_top(one, 3, 2, one, null) == binding.SC_EINVAL
     assert lib.sc_degree_scaling(one, one, one, 0, null, one, null) == binding.SC_OK               # n = 0: nothing to do
