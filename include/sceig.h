@@ -146,10 +146,13 @@ int sc_validate_csr(const int64_t* csr_rowptr, const int32_t* csr_col, int64_t n
  * Gram-Schmidt applied twice to the block W = basis[:, j : j+b] against Q = basis[:, 0 : j]:
  *   H1 = Q^T W, W -= Q H1, H2 = Q^T W, W -= Q H2, h_out = H1 + H2.
  *   basis  device, row-major n x ld, ld >= j + b; columns j..j+b-1 are updated in place
- *   h_out  device fp64[j*b], row-major j x b (may be NULL)
- *   1 <= b <= 32, j >= 0.
+ *   h_out     device fp64[j*b], row-major j x b (may be NULL)
+ *   gram_out  device fp64[b*b], row-major: W^T W of the updated block, accumulated in the same pass as the
+ *             second update (this is the Gram matrix the block orthonormalization starts from); may be NULL
+ *   1 <= b <= 32, j >= 0 (j = 0: nothing is done, outputs untouched).
  */
-int sc_cgs2(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, double* h_out, void* stream);
+int sc_cgs2(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, double* h_out, double* gram_out,
+            void* stream);
 
 /*
  * Orthonormalization of the block W = basis[:, j : j+b] by Cholesky QR applied twice: W = Q R.

@@ -71,7 +71,7 @@ def lib() -> ctypes.CDLL:
         _lib.sc_degree_scaling.argtypes = [vp, vp, vp, i64, vp, vp, vp]
         _lib.sc_spmm_normalized.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, i64, i32, vp, vp]
         _lib.sc_validate_csr.argtypes = [vp, vp, i64, vp]
-        _lib.sc_cgs2.argtypes = [vp, i64, i64, i32, i32, vp, vp]
+        _lib.sc_cgs2.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         _lib.sc_block_qr.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         _lib.sc_rotate.argtypes = [vp, i64, i64, i32, i32, vp, i32, vp, i64, i32, vp]
         _lib.sc_sym_eig.argtypes = [vp, i32, vp, vp]
@@ -170,15 +170,17 @@ def sc_spmm_normalized(rowptr, col, val, s, x, y=None, work=None):
     return y.reshape(x.shape)
 
 
-def sc_cgs2(basis, j: int, b: int, want_h: bool = True):
-    """basis: (n, ld) row-major device tensor, columns j..j+b-1 updated in place.  Returns H (j, b) or None."""
+def sc_cgs2(basis, j: int, b: int, want_h: bool = True, want_gram: bool = False):
+    """basis: (n, ld) row-major device tensor, columns j..j+b-1 updated in place.  Returns H (j, b) or None;
+    with want_gram also the Gram matrix (b, b) of the updated block."""
     import torch
     n, ld = basis.shape
     h = torch.zeros((j, b), dtype=torch.float64, device=basis.device) if want_h else None
+    g = torch.zeros((b, b), dtype=torch.float64, device=basis.device) if want_gram else None
     with torch.cuda.device(basis.device):
-        code = lib().sc_cgs2(_ptr(basis), n, basis.stride(0), j, b, _ptr(h), _stream())
+        code = lib().sc_cgs2(_ptr(basis), n, basis.stride(0), j, b, _ptr(h), _ptr(g), _stream())
     _check(code)
-    return h
+    return (h, g) if want_gram else h
 
 
 def sc_block_qr(basis, j: int, b: int):

@@ -162,16 +162,18 @@ int pow2_floor(int x) {
 }
 
 // CGS2 of basis[:, wcol : wcol+b] against basis[:, 0 : j]; hsum (j x b, stride kPP) = H1 + H2.
-// slot_a (may be null) receives rows [slot_row0, j) of hsum.
-void enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, double* part, double* h1, double* hsum,
-                  double* slot_a, int slot_row0, hipStream_t st, KTimer* tm) {
-  if (j <= 0) return;
+// slot_a (may be null) receives rows [slot_row0, j) of hsum.  If gpart != null the second update also leaves
+// the Gram partials of the updated block there; returns their count (0 if none were produced).
+int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, double* part, double* h1, double* hsum,
+                 double* slot_a, int slot_row0, double* gpart, hipStream_t st, KTimer* tm) {
+  if (j <= 0) return 0;
   const ProjectPlan plan = plan_project(n, j, kMaxPartials);
   KTimer none;
   if (!tm) tm = &none;
   // algorithmic traffic of one pass over the basis: every row reads its j basis entries and its b block
   // entries once (the update also writes the b block entries back)
   const double rows = (double)n;
+  int ngram = 0;
   for (int pass = 0; pass < 2; ++pass) {
     tm->begin(kFamProject);
     HIP_TRY(launch_project(basis, n, ld, 0, j, wcol, b, plan, part, st));
@@ -180,32 +182,45 @@ void enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, 
     HIP_TRY(launch_reduce_partials(part, plan.npart, j, b, h1, hsum, pass, pass == 1 ? slot_a : nullptr, slot_row0, st));
     tm->end(kFamOther, 8.0 * plan.npart * (double)j * b, 0.0);
     tm->begin(kFamUpdate);
-    HIP_TRY(launch_row_gemm(basis, n, ld, 0, j, h1, kPP, b, 0, wcol, nullptr, 0, st));
+    if (pass == 1 && gpart) {
+      HIP_TRY(launch_update_gram(basis, n, ld, j, h1, b, wcol, gpart, st));
+      ngram = plan_update_gram(n);
+    } else {
+      HIP_TRY(launch_row_gemm(basis, n, ld, 0, j, h1, kPP, b, 0, wcol, nullptr, 0, st));
+    }
     tm->end(kFamUpdate, 8.0 * rows * (j + 2 * b), 2.0 * rows * j * b);
   }
+  return ngram;
 }
 
 // Cholesky QR twice on basis[:, col : col+b].  r_out / g_out: device b x b (stride kPP) or null;
-// gram, rinv, r1: device scratch of kPP*kPP doubles each.
+// gram, rinv, r1: device scratch of kPP*kPP doubles each; gpart: scratch for Gram partials (kGramPartials blocks).
+// ngram > 0: gpart already holds that many Gram partials of the block (left by enqueue_cgs2).
 // z (may be null): packed s-scaled copy of the orthonormalised block.
-void enqueue_block_qr(double* basis, int64_t n, int64_t ld, int col, int b, double* part, double* gram, double* rinv,
-                      double* r1, double* r_out, double* g_out, double* z, const double* s, hipStream_t st, KTimer* tm) {
-  const ProjectPlan plan = plan_project(n, b, kMaxPartials);
+void enqueue_block_qr(double* basis, int64_t n, int64_t ld, int col, int b, double* part, double* gpart, int ngram,
+                      double* gram, double* rinv, double* r1, double* r_out, double* g_out, double* z, const double* s,
+                      hipStream_t st, KTimer* tm) {
   KTimer none;
   if (!tm) tm = &none;
   const double blk = 8.0 * (double)n * b;
   tm->begin(kFamQr);
-  HIP_TRY(launch_project(basis, n, ld, col, b, col, b, plan, part, st));
-  HIP_TRY(launch_reduce_partials(part, plan.npart, b, b, gram, nullptr, 0, nullptr, 0, st));
+  if (ngram > 0) {
+    HIP_TRY(launch_reduce_partials(gpart, ngram, b, b, gram, nullptr, 0, nullptr, 0, st));
+  } else {
+    const ProjectPlan plan = plan_project(n, b, kMaxPartials);
+    HIP_TRY(launch_project(basis, n, ld, col, b, col, b, plan, part, st));
+    HIP_TRY(launch_reduce_partials(part, plan.npart, b, b, gram, nullptr, 0, nullptr, 0, st));
+  }
   HIP_TRY(launch_gram_cholesky(gram, b, g_out, rinv, r1, nullptr, kAbsDrop2, kRelDrop, st));
-  HIP_TRY(launch_apply_rinv(basis, n, ld, col, b, rinv, nullptr, nullptr, st));
-  HIP_TRY(launch_project(basis, n, ld, col, b, col, b, plan, part, st));
-  HIP_TRY(launch_reduce_partials(part, plan.npart, b, b, gram, nullptr, 0, nullptr, 0, st));
+  HIP_TRY(launch_apply_gram(basis, n, ld, col, b, rinv, gpart, st));
+  HIP_TRY(launch_reduce_partials(gpart, plan_apply_gram(n, b), b, b, gram, nullptr, 0, nullptr, 0, st));
   // second pass: a column that survived the first pass has unit norm, so only exact zeros are dropped
   HIP_TRY(launch_gram_cholesky(gram, b, nullptr, rinv, r_out, r1, 0.25, 1e-8, st));
   HIP_TRY(launch_apply_rinv(basis, n, ld, col, b, rinv, z, s, st));
-  tm->end(kFamQr, 6.0 * blk + (z ? blk : 0.0), 4.0 * (double)n * b * b + 2.0 * (double)n * b * b);
+  tm->end(kFamQr, (ngram > 0 ? 4.0 : 5.0) * blk + (z ? blk : 0.0), 4.0 * (double)n * b * b);
 }
+
+constexpr int kGramPartials = 1024;
 
 struct Solver {
   // problem
@@ -222,7 +237,7 @@ struct Solver {
   uint64_t seed;
   hipStream_t st;
   // device
-  DevBuf<double> basis, s, z, part, h1, hsum, small, slots, yd, rot;
+  DevBuf<double> basis, s, z, part, gpart, h1, hsum, small, slots, yd, rot;
   DevBuf<int> flag;
   PinnedBuf<double> slots_host;
   int64_t ld = 0;
@@ -265,6 +280,7 @@ struct Solver {
     z.alloc((size_t)n * b);
     const int jmax = m + b;
     part.alloc((size_t)kMaxPartials * jmax * kPP);
+    gpart.alloc((size_t)kGramPartials * kPP * kPP);
     h1.alloc((size_t)jmax * kPP);
     hsum.alloc((size_t)jmax * kPP);
     small.alloc(3 * kPP * kPP);
@@ -286,9 +302,9 @@ struct Solver {
     timer.end(kFamSpmm, 12.0 * (double)nnz + 8.0 * (double)(n + 1) + 8.0 * (double)n + 16.0 * (double)n * b,
               2.0 * (double)nnz * b);
     double* sl = slot(si);
-    enqueue_cgs2(basis.p, n, ld, jt, jt, b, part.p, h1.p, hsum.p, sl, jt - b, st, &timer);
-    enqueue_block_qr(basis.p, n, ld, jt, b, part.p, gram(), rinv(), r1(), sl + kPP * kPP, sl + 2 * kPP * kPP, z.p, s.p, st,
-                     &timer);
+    const int ngram = enqueue_cgs2(basis.p, n, ld, jt, jt, b, part.p, h1.p, hsum.p, sl, jt - b, gpart.p, st, &timer);
+    enqueue_block_qr(basis.p, n, ld, jt, b, part.p, gpart.p, ngram, gram(), rinv(), r1(), sl + kPP * kPP,
+                     sl + 2 * kPP * kPP, z.p, s.p, st, &timer);
     stats.block_steps += 1;
     stats.spmv_cols += b;
   }
@@ -366,9 +382,9 @@ struct Solver {
 
       // ---- start block
       HIP_TRY(launch_random_block(basis.p, n, ld, nl, b, seed, stream_id++, st));
-      enqueue_cgs2(basis.p, n, ld, nl, nl, b, part.p, h1.p, hsum.p, nullptr, 0, st, &timer);
-      enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gram(), rinv(), r1(), slot(0) + kPP * kPP, slot(0) + 2 * kPP * kPP, z.p,
-                       s.p, st, &timer);
+      const int ngram0 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
+      enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram0, gram(), rinv(), r1(), slot(0) + kPP * kPP,
+                       slot(0) + 2 * kPP * kPP, z.p, s.p, st, &timer);
       int ja = b;            // active columns whose coupling is (or will be) assembled
       int assembled = 0;     // active columns of T that are final (their block has been multiplied by S)
       int next_slot = 1;     // slot 0 = start block QR
@@ -826,7 +842,7 @@ int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const 
       &ctx);
 }
 
-int sc_cgs2(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, double* h_out, void* stream) {
+int sc_cgs2(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, double* h_out, double* gram_out, void* stream) {
   if (!basis || n < 0) return SC_EINVAL;
   if (b < 1 || b > kMaxBlock || j < 0 || ld < (int64_t)j + b) return SC_EDOMAIN;
   if (n == 0 || j == 0) return SC_OK;
@@ -834,20 +850,29 @@ int sc_cgs2(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, double* 
     double* basis;
     int64_t n, ld;
     int j, b;
-    double* h;
+    double *h, *g;
     hipStream_t st;
-  } ctx{basis, n, ld, j, b, h_out, reinterpret_cast<hipStream_t>(stream)};
+  } ctx{basis, n, ld, j, b, h_out, gram_out, reinterpret_cast<hipStream_t>(stream)};
   return guarded(
       [](void* p) {
         Ctx* c = static_cast<Ctx*>(p);
-        DevBuf<double> part, h1, hsum;
+        DevBuf<double> part, h1, hsum, gpart, gram;
         part.alloc((size_t)kMaxPartials * c->j * kPP);
         h1.alloc((size_t)c->j * kPP);
         hsum.alloc((size_t)c->j * kPP);
-        enqueue_cgs2(c->basis, c->n, c->ld, c->j, c->j, c->b, part.p, h1.p, hsum.p, nullptr, 0, c->st, nullptr);
+        gpart.alloc((size_t)kGramPartials * kPP * kPP);
+        gram.alloc((size_t)kPP * kPP);
+        const int ngram =
+            enqueue_cgs2(c->basis, c->n, c->ld, c->j, c->j, c->b, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, c->st, nullptr);
+        const size_t w = (size_t)c->b * sizeof(double);
         if (c->h)
-          HIP_TRY(hipMemcpy2DAsync(c->h, (size_t)c->b * sizeof(double), hsum.p, (size_t)kPP * sizeof(double),
-                                   (size_t)c->b * sizeof(double), (size_t)c->j, hipMemcpyDeviceToDevice, c->st));
+          HIP_TRY(hipMemcpy2DAsync(c->h, w, hsum.p, (size_t)kPP * sizeof(double), w, (size_t)c->j,
+                                   hipMemcpyDeviceToDevice, c->st));
+        if (c->g) {
+          HIP_TRY(launch_reduce_partials(gpart.p, ngram, c->b, c->b, gram.p, nullptr, 0, nullptr, 0, c->st));
+          HIP_TRY(hipMemcpy2DAsync(c->g, w, gram.p, (size_t)kPP * sizeof(double), w, (size_t)c->b,
+                                   hipMemcpyDeviceToDevice, c->st));
+        }
         HIP_TRY(hipStreamSynchronize(c->st));
         return SC_OK;
       },
@@ -869,16 +894,17 @@ int sc_block_qr(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, doub
   return guarded(
       [](void* p) {
         Ctx* c = static_cast<Ctx*>(p);
-        DevBuf<double> part, small;
+        DevBuf<double> part, small, gpart;
         part.alloc((size_t)kMaxPartials * c->b * kPP);
+        gpart.alloc((size_t)kGramPartials * kPP * kPP);
         small.alloc(5 * kPP * kPP);
         double* rinv = small.p;
         double* r1 = small.p + kPP * kPP;
         double* rr = small.p + 2 * kPP * kPP;
         double* gg = small.p + 3 * kPP * kPP;
         double* gram = small.p + 4 * kPP * kPP;
-        enqueue_block_qr(c->basis, c->n, c->ld, c->j, c->b, part.p, gram, rinv, r1, rr, gg, nullptr, nullptr, c->st,
-                         nullptr);
+        enqueue_block_qr(c->basis, c->n, c->ld, c->j, c->b, part.p, gpart.p, 0, gram, rinv, r1, rr, gg, nullptr, nullptr,
+                         c->st, nullptr);
         const size_t w = (size_t)c->b * sizeof(double);
         if (c->r)
           HIP_TRY(hipMemcpy2DAsync(c->r, w, rr, (size_t)kPP * sizeof(double), w, (size_t)c->b, hipMemcpyDeviceToDevice,

@@ -501,6 +501,264 @@ __global__ __launch_bounds__(kThreads) void copy_cols_kernel(const double* __res
   dst[i * ldd + dcol0 + t] = src[i * lds + scol0 + t];
 }
 
+
+// --------------------------------------------------------------------------------------------
+// fused pieces of the block step
+// --------------------------------------------------------------------------------------------
+// Second CGS2 update fused with the Gram matrix of the updated block:
+//   basis[:, ccol0 : ccol0+b] -= basis[:, 0 : kdim] * bmat,   gpart[blockIdx.x] = sum over this workgroup's
+//   rows of W_new^T W_new.
+// Workgroups walk the 128-row tiles with a grid stride, so the number of Gram partials is the grid size.
+template <int NT>
+__global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
+                                                               int kdim, const double* __restrict__ bmat, int b,
+                                                               int ccol0, int vec_ok, double* __restrict__ gpart) {
+  constexpr int MT = 2;
+  constexpr int BW = NT * 16;
+  constexpr int KC = 4096 / BW;
+  constexpr int WP = NT == 1 ? BW + 1 : BW;  // row pitch of the tile of new block rows
+  __shared__ double lds[KC * BW];
+  __shared__ double wt[128 * WP];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i = lane & 15, g = lane >> 4;
+  const int64_t ntiles = (n + 127) / 128;
+  const bool single = kdim <= KC;
+
+  auto load_chunk = [&](int k0, int kc, int kc16) {
+    for (int e = threadIdx.x; e < kc16 * BW; e += kThreads) {
+      const int kk = e / BW, t = e % BW;
+      double v = 0.0;
+      if (kk < kc && t < b) v = bmat[(int64_t)(k0 + kk) * kPartialPad + t];
+      const int kt = kk >> 4, rem = kk & 15, gg = rem >> 2, q = rem & 3;
+      const int nt = t >> 4, ii = t & 15;
+      lds[((((kt * 4 + q) * NT + nt) * 4 + gg) << 4) + ii] = v;
+    }
+  };
+  if (single) {
+    load_chunk(0, kdim, (kdim + 15) & ~15);
+    __syncthreads();
+  }
+
+  d4 gacc[NT][NT];
+#pragma unroll
+  for (int x = 0; x < NT; ++x)
+#pragma unroll
+    for (int y = 0; y < NT; ++y) gacc[x][y] = (d4){0.0, 0.0, 0.0, 0.0};
+
+  for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const int64_t row0 = (tile * 4 + wave) * (16 * MT);
+    d4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (d4){0.0, 0.0, 0.0, 0.0};
+    for (int k0 = 0; k0 < kdim; k0 += KC) {
+      const int kc = (kdim - k0) < KC ? (kdim - k0) : KC;
+      const int kc16 = (kc + 15) & ~15;
+      if (!single) {
+        __syncthreads();
+        load_chunk(k0, kc, kc16);
+        __syncthreads();
+      }
+      for (int kk = 0; kk < kc16; kk += 16) {
+        double a[MT][4];
+        const int kcol = k0 + kk + 4 * g;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const int64_t row = row0 + mt * 16 + i;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) a[mt][q] = 0.0;
+          if (row < n) {
+            const double* ap = basis + row * ld + kcol;
+            if (vec_ok && kcol + 3 < kdim) {
+              const d4 v = *reinterpret_cast<const d4*>(ap);
+              a[mt][0] = v[0]; a[mt][1] = v[1]; a[mt][2] = v[2]; a[mt][3] = v[3];
+            } else {
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+                if (kcol + q < kdim) a[mt][q] = ap[q];
+            }
+          }
+        }
+        const int kt = kk >> 4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            const double bq = lds[((((kt * 4 + q) * NT + nt) * 4 + g) << 4) + i];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = MFMA_F64(a[mt][q], bq, acc[mt][nt]);
+          }
+      }
+    }
+    // new block rows: to memory and into the tile
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          const int lr = wave * 32 + mt * 16 + 4 * rr + g;
+          const int64_t row = row0 + mt * 16 + 4 * rr + g;
+          const int t = nt * 16 + i;
+          double nv = 0.0;
+          if (row < n && t < b) {
+            double* p = basis + row * ld + ccol0 + t;
+            nv = *p - acc[mt][nt][rr];
+            *p = nv;
+          }
+          wt[lr * WP + t] = nv;
+        }
+    __syncthreads();
+    // Gram of this wave's 32 rows: contraction over rows, 4 rows per MFMA
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const int lr = wave * 32 + ks * 4 + g;
+      double av[NT];
+#pragma unroll
+      for (int x = 0; x < NT; ++x) av[x] = wt[lr * WP + i + 16 * x];
+#pragma unroll
+      for (int x = 0; x < NT; ++x)
+#pragma unroll
+        for (int y = 0; y < NT; ++y) gacc[x][y] = MFMA_F64(av[x], av[y], gacc[x][y]);
+    }
+    __syncthreads();
+  }
+  // the four waves' Gram blocks are added in wave order
+  __syncthreads();
+#pragma unroll
+  for (int x = 0; x < NT; ++x)
+#pragma unroll
+    for (int y = 0; y < NT; ++y)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int c1 = 16 * x + 4 * rr + g, c2 = 16 * y + i;
+        lds[(wave * BW + c1) * BW + c2] = gacc[x][y][rr];
+      }
+  __syncthreads();
+  for (int e = threadIdx.x; e < BW * BW; e += kThreads) {
+    const int c1 = e / BW, c2 = e % BW;
+    if (c1 < b && c2 < b) {
+      double tot = lds[c1 * BW + c2];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) tot += lds[(w * BW + c1) * BW + c2];
+      gpart[((int64_t)blockIdx.x * b + c1) * kPartialPad + c2] = tot;
+    }
+  }
+}
+
+// basis[:, col0 : col0+b] *= rinv (as apply_rinv_kernel) fused with the Gram matrix of the result;
+// grid-stride over groups of 256/b rows, one Gram partial per workgroup.
+__global__ __launch_bounds__(kThreads) void apply_gram_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
+                                                              int col0, int b, const double* __restrict__ rinv,
+                                                              double* __restrict__ gpart) {
+  __shared__ double Ri[kMaxBlock][kMaxBlock + 1];
+  __shared__ double Wt[2 * kThreads];
+  __shared__ double Qt[2 * kThreads];
+  for (int e = threadIdx.x; e < b * b; e += kThreads) Ri[e / b][e % b] = rinv[(e / b) * kPartialPad + (e % b)];
+  const int rows_per = kThreads / b;
+  const int t = threadIdx.x % b, rl = threadIdx.x / b;
+  const int64_t ngroups = (n + rows_per - 1) / rows_per;
+  double gacc[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int64_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
+    const int64_t row = grp * rows_per + rl;
+    __syncthreads();
+    Wt[rl * (b + 1) + t] = row < n ? basis[row * ld + col0 + t] : 0.0;
+    __syncthreads();
+    double acc = 0.0;
+    for (int q = 0; q <= t; ++q) acc += Wt[rl * (b + 1) + q] * Ri[q][t];
+    if (row < n) basis[row * ld + col0 + t] = acc;
+    Qt[rl * (b + 1) + t] = row < n ? acc : 0.0;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = threadIdx.x + u * kThreads;
+      if (e < b * b) {
+        const int c1 = e / b, c2 = e % b;
+        double v = gacc[u];
+        for (int r = 0; r < rows_per; ++r) v += Qt[r * (b + 1) + c1] * Qt[r * (b + 1) + c2];
+        gacc[u] = v;
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int e = threadIdx.x + u * kThreads;
+    if (e < b * b) gpart[((int64_t)blockIdx.x * b + e / b) * kPartialPad + (e % b)] = gacc[u];
+  }
+}
+
+// Cholesky of the b x b Gram matrix in the registers of one wave: lane t owns column t of G, R and R^-1;
+// values of other columns travel by lane reads.  Same dropping rule as documented in kernels.h.
+template <int B>
+__global__ __launch_bounds__(64) void chol_reg_kernel(const double* __restrict__ g_in, double* __restrict__ g_out,
+                                                      double* __restrict__ rinv_out, double* __restrict__ r_out,
+                                                      const double* __restrict__ rprev, double abs_tol2,
+                                                      double rel_tol) {
+  const int t = threadIdx.x;
+  const bool act = t < B;
+  const int tc = act ? t : 0;
+  double gcol[B], rcol[B], ricol[B];
+#pragma unroll
+  for (int q = 0; q < B; ++q) {
+    const int lo = q < tc ? q : tc, hi = q < tc ? tc : q;
+    gcol[q] = g_in[lo * kPartialPad + hi];  // upper triangle, mirrored
+    rcol[q] = 0.0;
+    ricol[q] = 0.0;
+  }
+  if (g_out && act) {
+#pragma unroll
+    for (int q = 0; q < B; ++q) g_out[q * kPartialPad + t] = gcol[q];
+  }
+#pragma unroll
+  for (int k = 0; k < B; ++k) {
+    double v = gcol[k];
+#pragma unroll
+    for (int q = 0; q < k; ++q) v -= __shfl(rcol[q], k) * rcol[q];
+    const double gkk = __shfl(gcol[k], k), pk = __shfl(v, k);
+    const bool drop = !(gkk > abs_tol2) || !(pk > rel_tol * gkk);
+    const double rkk = drop ? 0.0 : sqrt(pk);
+    rcol[k] = (t == k) ? rkk : ((t > k && !drop) ? v / rkk : 0.0);
+  }
+  double rcc = 0.0;  // own diagonal entry
+#pragma unroll
+  for (int q = 0; q < B; ++q) rcc = (q == t) ? rcol[q] : rcc;
+#pragma unroll
+  for (int r = B - 1; r >= 0; --r) {
+    const double rrr = __shfl(rcol[r], r);
+    double sum = 0.0;
+#pragma unroll
+    for (int x = r + 1; x < B; ++x) {
+      const double rrx = __shfl(rcol[r], x);
+      sum += (x <= t) ? rrx * ricol[x] : 0.0;
+    }
+    double v = 0.0;
+    if (rrr != 0.0 && rcc != 0.0) v = (t == r) ? 1.0 / rrr : (t > r ? -sum / rrr : 0.0);
+    ricol[r] = v;
+  }
+  if (rinv_out && act) {
+#pragma unroll
+    for (int q = 0; q < B; ++q) rinv_out[q * kPartialPad + t] = ricol[q];
+  }
+  if (r_out) {
+    double pcol[B];
+    if (rprev) {
+#pragma unroll
+      for (int x = 0; x < B; ++x) pcol[x] = rprev[x * kPartialPad + tc];
+    }
+#pragma unroll
+    for (int q = 0; q < B; ++q) {
+      double v = rcol[q];
+      if (rprev) {
+        v = 0.0;
+#pragma unroll
+        for (int x = q; x < B; ++x) v += __shfl(rcol[q], x) * pcol[x];
+      }
+      if (act) r_out[q * kPartialPad + t] = v;
+    }
+  }
+}
+
 }  // namespace
 
 // ============================================================================================
@@ -619,8 +877,52 @@ hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int 
 
 hipError_t launch_gram_cholesky(const double* g_in, int b, double* g_out, double* rinv, double* rout,
                                 const double* rprev, double abs_tol2, double rel_tol, hipStream_t st) {
-  hipLaunchKernelGGL(gram_cholesky_kernel, dim3(1), dim3(kCholThreads), 0, st, g_in, b, g_out, rinv, rout, rprev,
-                     abs_tol2, rel_tol);
+#define SC_CHOL(BB)                                                                                              \
+  hipLaunchKernelGGL((chol_reg_kernel<BB>), dim3(1), dim3(64), 0, st, g_in, g_out, rinv, rout, rprev, abs_tol2, \
+                     rel_tol)
+  switch (b) {
+    case 1: SC_CHOL(1); break;
+    case 2: SC_CHOL(2); break;
+    case 4: SC_CHOL(4); break;
+    case 8: SC_CHOL(8); break;
+    case 16: SC_CHOL(16); break;
+    case 32: SC_CHOL(32); break;
+    default:
+      hipLaunchKernelGGL(gram_cholesky_kernel, dim3(1), dim3(kCholThreads), 0, st, g_in, b, g_out, rinv, rout, rprev,
+                         abs_tol2, rel_tol);
+  }
+#undef SC_CHOL
+  return hipGetLastError();
+}
+
+int plan_update_gram(int64_t n) {
+  const int64_t ntiles = (n + 127) / 128;
+  return (int)(ntiles < 1024 ? ntiles : 1024);
+}
+
+hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int kdim, const double* bmat, int b, int ccol0,
+                              double* gpart, hipStream_t st) {
+  const int vec_ok = (ld % 4 == 0 && (reinterpret_cast<uintptr_t>(basis) % 32 == 0)) ? 1 : 0;
+  const unsigned grid = (unsigned)plan_update_gram(n);
+  if (b <= 16) {
+    hipLaunchKernelGGL((update_gram_kernel<1>), dim3(grid), dim3(kThreads), 0, st, basis, n, ld, kdim, bmat, b, ccol0,
+                       vec_ok, gpart);
+  } else {
+    hipLaunchKernelGGL((update_gram_kernel<2>), dim3(grid), dim3(kThreads), 0, st, basis, n, ld, kdim, bmat, b, ccol0,
+                       vec_ok, gpart);
+  }
+  return hipGetLastError();
+}
+
+int plan_apply_gram(int64_t n, int b) {
+  const int64_t groups = (n + (kThreads / b) - 1) / (kThreads / b);
+  return (int)(groups < 512 ? groups : 512);
+}
+
+hipError_t launch_apply_gram(double* basis, int64_t n, int64_t ld, int col0, int b, const double* rinv, double* gpart,
+                             hipStream_t st) {
+  hipLaunchKernelGGL(apply_gram_kernel, dim3((unsigned)plan_apply_gram(n, b)), dim3(kThreads), 0, st, basis, n, ld,
+                     col0, b, rinv, gpart);
   return hipGetLastError();
 }
 

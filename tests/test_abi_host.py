@@ -122,8 +122,8 @@ def test_argument_errors_without_gpu():
     assert f(one, one, one, 10, 2, 1e-8, 10, one, one, null, ctypes.byref(opt), None) == binding.SC_EDOMAIN
     assert lib.sc_spmm_normalized(one, one, one, one, 10, one, 3, one, 3, 3, null, null) == binding.SC_EDOMAIN
     assert lib.sc_spmm_normalized(one, one, one, one, 10, one, 2, one, 4, 4, null, null) == binding.SC_EDOMAIN  # ldx < ncols
-    assert lib.sc_cgs2(null, 10, 8, 2, 2, null, null) == binding.SC_EINVAL
-    assert lib.sc_cgs2(one, 10, 3, 2, 2, null, null) == binding.SC_EDOMAIN                         # ld < j + b
+    assert lib.sc_cgs2(null, 10, 8, 2, 2, null, null, null) == binding.SC_EINVAL
+    assert lib.sc_cgs2(one, 10, 3, 2, 2, null, null, null) == binding.SC_EDOMAIN                         # ld < j + b
     assert lib.sc_block_qr(one, 10, 8, 2, 5, null, null, null) == binding.SC_EDOMAIN
     assert lib.sc_rotate(one, 10, 8, 0, 9, one, 2, one, 2, 0, null) == binding.SC_EDOMAIN          # ld < j0 + ja
     assert lib.sc_sym_eig(null, 3, one, null) == binding.SC_EINVAL

@@ -93,7 +93,7 @@ def test_spmm_normalized(B, graphs, ncols):
 
 
 @pytest.mark.parametrize("n,j,b", [(5000, 70, 16), (4099, 130, 8), (3001, 300, 32), (2500, 17, 1), (2000, 64, 4),
-                                   (777, 5, 2), (70000, 200, 16)])
+                                   (777, 5, 2), (70000, 200, 16), (140000, 40, 32), (300, 280, 8)])
 def test_cgs2(B, n, j, b):
     rng = np.random.default_rng(n + j + b)
     q, _ = np.linalg.qr(rng.standard_normal((n, j)))
@@ -104,8 +104,10 @@ def test_cgs2(B, n, j, b):
     basis[:, j:j + b] = w
     basis[:, j + b:] = 3.25
     dbasis = torch.from_numpy(basis).cuda()
-    h = B.sc_cgs2(dbasis, j, b)
+    h, gram = B.sc_cgs2(dbasis, j, b, want_gram=True)
     w0, h0 = blockops.cgs2_block(q, w)
+    g0 = w0.T @ w0
+    assert np.max(np.abs(gram.cpu().numpy() - g0)) <= 1e-12 * np.abs(g0).max()
     out = dbasis.cpu().numpy()
     assert np.array_equal(out[:, :j], q) and np.all(out[:, j + b:] == 3.25)
     assert np.max(np.abs(h.cpu().numpy() - h0)) <= 1e-12 * max(1.0, np.abs(h0).max())
