@@ -487,6 +487,14 @@ struct Solver {
         }
         int lead = 0;
         while (lead < nsel && rho[lead] <= tol) ++lead;
+        if (debug_on()) {
+          const int wi = std::min(want, nsel) - 1;
+          std::fprintf(stderr,
+                       "[sceig] t=%.2fs phase %d step %d nl=%d ja=%d cap=%d full=%d lead=%d/%d theta[0]=%.12f rho[0]=%.2e "
+                       "theta[w]=%.12f rho[w]=%.2e\n",
+                       now_s() - t_begin, stats.phases, steps_in_phase, nl, ja, cap, (int)full, lead, want,
+                       theta[ja - 1], rho[0], wi >= 0 ? theta[ja - 1 - wi] : 0.0, wi >= 0 ? rho[wi] : 0.0);
+        }
 
         if (nreal == 0) {  // the deflated space is empty: nothing more exists
           finished = true;

@@ -231,7 +231,13 @@ def _knn_brute_torch(x: np.ndarray, k_nn: int, device: str, block: int = 4096):
     idx_out = np.empty((n, k_nn), dtype=np.int64)
     dist_out = np.empty((n, k_nn), dtype=np.float64)
     cand = min(n - 1, k_nn + 4)  # a few spare candidates; re-ranked exactly below
+    import sys
+    import time
+    last = time.time()
     for r0 in range(0, n, block):
+        if time.time() - last > 30.0:   # long builds say that they are alive
+            print(f"[workloads] kNN rows {r0}/{n}", file=sys.stderr, flush=True)
+            last = time.time()
         r1 = min(n, r0 + block)
         g = xt[r0:r1] @ xt.T
         d2 = sq[r0:r1, None] + sq[None, :] - 2.0 * g
@@ -258,8 +264,18 @@ def knn(x: np.ndarray, k_nn: int, device: Optional[str] = None):
 
 def knn_gaussian_graph(x: np.ndarray, k_nn: int, device: Optional[str] = None) -> Tuple[CSR, float]:
     """Union-symmetrized kNN graph with Gaussian weights.  Returns (CSR, sigma)."""
+    import sys
+    import time
     n = x.shape[0]
+    big = n * k_nn >= 20_000_000
+
+    def note(msg):   # long builds say that they are alive
+        if big:
+            print(f"[workloads] {msg} ({time.time() - t_start:.0f}s)", file=sys.stderr, flush=True)
+
+    t_start = time.time()
     idx, dist = knn(x, k_nn, device)
+    note("kNN done")
     sigma = float(np.median(dist))
     u = np.repeat(np.arange(n, dtype=np.int64), k_nn)
     v = idx.reshape(-1).astype(np.int64)
@@ -267,6 +283,7 @@ def knn_gaussian_graph(x: np.ndarray, k_nn: int, device: Optional[str] = None) -
     lo, hi = np.minimum(u, v), np.maximum(u, v)
     key = lo * n + hi
     key, first = np.unique(key, return_index=True)       # union: one undirected edge per pair
+    note("union done")
     dd = dd[first]
     w = np.exp(-(dd * dd) / (2.0 * sigma * sigma))
     keep = (w > 0.0) & ((key // n) != (key % n))           # drop underflowed weights / self loops
@@ -280,7 +297,9 @@ def knn_gaussian_graph(x: np.ndarray, k_nn: int, device: Optional[str] = None) -
         # positive degrees, "otherwise the isolated nodes can be removed from the graph")
         newid = np.cumsum(touched) - 1
         lo, hi, n = newid[lo], newid[hi], int(touched.sum())
-    return symmetric_from_edges(lo, hi, w, n), sigma
+    graph = symmetric_from_edges(lo, hi, w, n)
+    note("CSR done")
+    return graph, sigma
 
 
 def build_config_graph(cfg: MixtureConfig, device: Optional[str] = None):
