@@ -45,13 +45,19 @@ extern "C" {
 #define SC_EHIP (-6)       /* a HIP runtime call failed */
 
 #define SC_FLAG_NO_VERIFY 1u /* skip the final deflated check phase (see sc_laplacian_eigsh) */
+#define SC_FLAG_NO_REORDER 2u /* work on the CSR exactly as given: no connected-component pass, no internal
+                                 renumbering of the nodes for gather locality */
+#define SC_FLAG_COMPONENT_NULLSPACE 4u /* lock the closed-form eigenvalue-0 vectors D^1/2 1_C / sqrt(vol C) of the
+                                 connected components (vol as in the Ncut definition of Section II) before the first
+                                 Lanczos phase; off by default; ignored under SC_FLAG_NO_REORDER */
 
 /* Options; every field 0 = default. */
 typedef struct sc_options {
   int32_t m;      /* budget of basis columns (locked + active Krylov vectors), the "number m of Lanczos
-                     vectors" of Section IV-B; default min(n, max(2k, k + 24)); needs k + 3*block <= m <= n
+                     vectors" of Section IV-B; default min(n, max(2k, k + 56)); needs k + 3*block <= m <= n
                      (the library lowers `block` to fit when block is defaulted) */
-  int32_t block;  /* Lanczos block size b in {1,2,4,8,16,32}; default chosen from k and m */
+  int32_t block;  /* Lanczos block size b in {1,2,4,8,16,32}; default 8 (n < 300,000), 16, or 32 (k >= 1000),
+                     lowered to fit k + 3b <= m and b <= next power of two >= k */
   int32_t check_every; /* block steps between convergence checks of the projected problem; default 2 */
   uint32_t flags; /* SC_FLAG_* */
   uint64_t seed;  /* seed of the start / re-injection blocks */
@@ -76,6 +82,8 @@ typedef struct sc_stats {
   int32_t block;      /* block size used */
   int32_t m;          /* basis budget used */
   int32_t host_eigs;  /* projected eigenproblems solved on the host */
+  int32_t components; /* connected components found by the setup pass (0 under SC_FLAG_NO_REORDER) */
+  int32_t reserved;
   int64_t block_steps;
   int64_t spmv_cols;  /* columns multiplied by S in total */
   double t_total;     /* seconds, whole call */

@@ -20,8 +20,9 @@ def component_labels(rowptr, col, val):
     from scipy.sparse import csr_matrix
     from scipy.sparse.csgraph import connected_components
     n = rowptr.size - 1
-    pattern = csr_matrix(((np.asarray(val) != 0.0).astype(np.int8), np.asarray(col), np.asarray(rowptr)),
-                         shape=(n, n))
+    # copies: eliminate_zeros() rewrites the index arrays in place and must not touch the caller's CSR
+    pattern = csr_matrix(((np.asarray(val) != 0.0).astype(np.int8), np.array(col, copy=True),
+                          np.array(rowptr, copy=True)), shape=(n, n))
     pattern.eliminate_zeros()
     c, label = connected_components(pattern, directed=False)
     return int(c), label

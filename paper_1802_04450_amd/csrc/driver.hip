@@ -186,7 +186,7 @@ int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, d
       HIP_TRY(launch_update_gram(basis, n, ld, j, h1, b, wcol, gpart, st));
       ngram = plan_update_gram(n);
     } else {
-      HIP_TRY(launch_row_gemm(basis, n, ld, 0, j, h1, kPP, b, 0, wcol, nullptr, 0, st));
+      HIP_TRY(launch_row_gemm(basis, n, ld, 0, j, h1, kPP, b, 0, wcol, nullptr, 0, nullptr, st));
     }
     tm->end(kFamUpdate, 8.0 * rows * (j + 2 * b), 2.0 * rows * j * b);
   }
@@ -239,6 +239,12 @@ struct Solver {
   // device
   DevBuf<double> basis, s, z, part, gpart, h1, hsum, small, slots, yd, rot;
   DevBuf<int> flag;
+  DevBuf<int64_t> rowptr_p;
+  DevBuf<int32_t> col_p, label, old_of_new_d, new_of_old_d, comp_d;
+  DevBuf<double> val_p, coef_d;
+  const int32_t* rowmap = nullptr;  // device: original row of each internal row, null if not reordered
+  std::vector<int32_t> comp_host;   // component index of each internal row (only after reorder())
+  int ncomp = 0;
   PinnedBuf<double> slots_host;
   int64_t ld = 0;
   int max_slots = 0;
@@ -256,6 +262,89 @@ struct Solver {
   double* slot(int i) { return slots.p + (size_t)i * kSlotDoubles; }
   const double* hslot(int i) const { return slots_host.p + (size_t)i * kSlotDoubles; }
 
+  // Connected components by label propagation on the device, then rows and columns are renumbered so that
+  // every component is contiguous (stable inside a component).  The sparse products gather from a few hundred KB
+  // at a time instead of from all over the vector; mathematically the problem is a permutation similarity of
+  // the input, undone when the eigenvectors are written.
+  void reorder() {
+    label.alloc((size_t)n);
+    HIP_TRY(launch_iota(label.p, n, st));
+    for (int round = 0; round < 100000; ++round) {
+      int h = 0;
+      HIP_TRY(hipMemsetAsync(flag.p, 0, sizeof(int), st));
+      HIP_TRY(launch_cc_round(rowptr, col, val, label.p, n, flag.p, st));
+      HIP_TRY(launch_cc_round(rowptr, col, val, label.p, n, flag.p, st));
+      HIP_TRY(hipMemcpyAsync(&h, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipStreamSynchronize(st));
+      if (!h) break;
+    }
+    std::vector<int32_t> lab((size_t)n), new_of_old((size_t)n), old_of_new((size_t)n);
+    std::vector<int64_t> rp((size_t)n + 1), rp_new((size_t)n + 1);
+    HIP_TRY(hipMemcpyAsync(lab.data(), label.p, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(rp.data(), rowptr, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    // counting sort by component (component = its smallest node id), stable in the node id
+    std::vector<int64_t> start((size_t)n + 1, 0);
+    for (int64_t i = 0; i < n; ++i) start[(size_t)lab[i] + 1] += 1;
+    std::vector<int32_t> comp_of_root((size_t)n, -1);
+    ncomp = 0;
+    for (int64_t r = 0; r < n; ++r) {
+      if (start[r + 1] > 0) comp_of_root[r] = ncomp++;
+      start[r + 1] += start[r];
+    }
+    comp_host.assign((size_t)n, 0);
+    for (int64_t i = 0; i < n; ++i) {
+      const int64_t p = start[lab[i]]++;
+      new_of_old[i] = (int32_t)p;
+      old_of_new[p] = (int32_t)i;
+      comp_host[p] = comp_of_root[lab[i]];
+    }
+    rp_new[0] = 0;
+    for (int64_t p = 0; p < n; ++p) rp_new[p + 1] = rp_new[p] + (rp[old_of_new[p] + 1] - rp[old_of_new[p]]);
+    rowptr_p.alloc((size_t)n + 1);
+    col_p.alloc((size_t)nnz);
+    val_p.alloc((size_t)nnz);
+    old_of_new_d.alloc((size_t)n);
+    new_of_old_d.alloc((size_t)n);
+    HIP_TRY(hipMemcpyAsync(rowptr_p.p, rp_new.data(), ((size_t)n + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(old_of_new_d.p, old_of_new.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(new_of_old_d.p, new_of_old.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(launch_permute_csr(rowptr, col, val, old_of_new_d.p, new_of_old_d.p, rowptr_p.p, col_p.p, val_p.p, n, st));
+    HIP_TRY(hipStreamSynchronize(st));  // the host vectors above are pageable and go out of scope
+    rowptr = rowptr_p.p;
+    col = col_p.p;
+    val = val_p.p;
+    rowmap = old_of_new_d.p;
+    label.release();
+    new_of_old_d.release();
+  }
+
+  // Optional: the closed-form null vectors D^1/2 1_C / sqrt(vol C) of the first min(k, ncomp) components are
+  // written into the basis and locked before any Lanczos phase (needs reorder()).
+  void lock_component_nullspace() {
+    const int take = std::min(k, ncomp);
+    if (take <= 0) return;
+    DevBuf<double> deg;
+    deg.alloc((size_t)n);
+    HIP_TRY(launch_degree_scaling(rowptr, val, n, deg.p, s.p, flag.p, st));
+    std::vector<double> d((size_t)n), vol((size_t)ncomp, 0.0);
+    HIP_TRY(hipMemcpyAsync(d.data(), deg.p, (size_t)n * sizeof(double), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    for (int64_t i = 0; i < n; ++i) vol[comp_host[i]] += d[i];
+    for (int64_t i = 0; i < n; ++i) d[i] = std::sqrt(d[i] / vol[comp_host[i]]);
+    comp_d.alloc((size_t)n);
+    coef_d.alloc((size_t)n);
+    HIP_TRY(hipMemcpyAsync(comp_d.p, comp_host.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(coef_d.p, d.data(), (size_t)n * sizeof(double), hipMemcpyHostToDevice, st));
+    HIP_TRY(launch_nullspace_fill(basis.p, n, ld, 0, take, comp_d.p, coef_d.p, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    nl = take;
+    theta_locked.assign(take, 1.0);
+    rho_locked.assign(take, 0.0);
+    comp_d.release();
+    coef_d.release();
+  }
+
   void setup() {
     const double t0 = now_s();
     flag.alloc(1);
@@ -268,6 +357,7 @@ struct Solver {
     HIP_TRY(hipMemcpyAsync(&hflag, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     if (hflag & 3) SC_THROW(SC_ECSR);
+    if (!(flags & SC_FLAG_NO_REORDER)) reorder();
     s.alloc((size_t)n);
     HIP_TRY(launch_degree_scaling(rowptr, val, n, nullptr, s.p, flag.p, st));
     HIP_TRY(hipMemcpyAsync(&hflag, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
@@ -291,6 +381,8 @@ struct Solver {
     rot.alloc((size_t)n * rot_cols);
     yd_cap = (size_t)(m + b) * std::max<size_t>(rot_cols, (size_t)k);
     yd.alloc(yd_cap);
+    if ((flags & SC_FLAG_COMPONENT_NULLSPACE) && !(flags & SC_FLAG_NO_REORDER)) lock_component_nullspace();
+    stats.components = ncomp;
     stats.t_setup = now_s() - t0;
   }
 
@@ -326,7 +418,7 @@ struct Solver {
     if ((size_t)ja * l > yd_cap || (size_t)l > rot_cols) SC_THROW(SC_EDOMAIN);
     HIP_TRY(hipMemcpyAsync(yd.p, yl.data(), yl.size() * sizeof(double), hipMemcpyHostToDevice, st));
     timer.begin(kFamRotate);
-    HIP_TRY(launch_row_gemm(basis.p, n, ld, nl, ja, yd.p, l, l, 1, 0, rot.p, l, st));
+    HIP_TRY(launch_row_gemm(basis.p, n, ld, nl, ja, yd.p, l, l, 1, 0, rot.p, l, nullptr, st));
     timer.end(kFamRotate, 8.0 * (double)n * (ja + l), 2.0 * (double)n * ja * l);
     HIP_TRY(launch_copy_cols(rot.p, l, 0, basis.p, ld, dst, l, n, st));
     HIP_TRY(hipStreamSynchronize(st));  // yl (pageable host memory) must stay alive until the copy is done
@@ -643,7 +735,7 @@ struct Solver {
       for (int t = 0; t < nfound; ++t) evals_host[t] = 1.0 - th[nx - 1 - t];
       if ((size_t)nx * nfound > yd_cap) SC_THROW(SC_EDOMAIN);
       HIP_TRY(hipMemcpyAsync(yd.p, yk.data(), yk.size() * sizeof(double), hipMemcpyHostToDevice, st));
-      HIP_TRY(launch_row_gemm(basis.p, n, ld, 0, nx, yd.p, nfound, nfound, 2, 0, evecs_out, n, st));
+      HIP_TRY(launch_row_gemm(basis.p, n, ld, 0, nx, yd.p, nfound, nfound, 2, 0, evecs_out, n, rowmap, st));
       HIP_TRY(hipStreamSynchronize(st));
     }
     HIP_TRY(hipMemcpyAsync(evals_out, evals_host.data(), (size_t)k * sizeof(double), hipMemcpyHostToDevice, st));
@@ -730,8 +822,11 @@ int sc_laplacian_eigsh(const int64_t* csr_rowptr, const int32_t* csr_col, const 
   if (m > n || m < (int64_t)k + 3) return SC_EDOMAIN;
   int b = o.block;
   if (b == 0) {
-    b = pow2_floor((int)std::max<int64_t>(1, (m - k) / 3));
-    b = std::min(b, 16);
+    // Larger blocks amortise the passes over the basis (their cost grows with n), smaller blocks keep the
+    // projected problems and the number of block steps per converged vector small.
+    int target = n >= 300000 ? 16 : 8;
+    if (n >= 300000 && k >= 1000) target = 32;
+    b = std::min(target, pow2_floor((int)std::max<int64_t>(1, (m - k) / 3)));
     int kb = 1;
     while (kb < k) kb *= 2;
     b = std::min(b, kb);
@@ -947,7 +1042,7 @@ int sc_rotate(const double* basis, int64_t n, int64_t ld, int32_t j0, int32_t ja
       [](void* p) {
         Ctx* c = static_cast<Ctx*>(p);
         HIP_TRY(launch_row_gemm(const_cast<double*>(c->basis), c->n, c->ld, c->j0, c->ja, c->y, c->l, c->l,
-                                c->cm ? 2 : 1, 0, c->out, c->ldo, c->st));
+                                c->cm ? 2 : 1, 0, c->out, c->ldo, nullptr, c->st));
         HIP_TRY(hipStreamSynchronize(c->st));
         return SC_OK;
       },

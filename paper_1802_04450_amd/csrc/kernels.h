@@ -49,9 +49,10 @@ hipError_t launch_reduce_partials(const double* part, int npart, int ja, int b, 
 // C = A * B row GEMM:  A = basis[:, acol0 : acol0+kdim] (n x kdim), B = bmat (kdim x ncols, row-major, ldb).
 // mode 0: basis[:, ccol0 + t] -= C[:, t]          (in place update, ncols <= 32, out unused)
 // mode 1: out[i*ldo + t]  = C[i, t]                (row-major)
-// mode 2: out[t*ldo + i]  = C[i, t]                (column-major)
+// mode 2: out[t*ldo + r(i)] = C[i, t]             (column-major; r(i) = rowmap[i] if rowmap != null, else i)
 hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int ldb,
-                           int ncols, int mode, int ccol0, double* out, int64_t ldo, hipStream_t st);
+                           int ncols, int mode, int ccol0, double* out, int64_t ldo, const int32_t* rowmap,
+                           hipStream_t st);
 
 // ---- block orthonormalization --------------------------------------------------------------
 // One Cholesky-QR pass bookkeeping on the Gram matrix g_in (b x b, stride kPartialPad; single workgroup):
@@ -77,6 +78,20 @@ hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int kdim, co
 int plan_apply_gram(int64_t n, int b);
 hipError_t launch_apply_gram(double* basis, int64_t n, int64_t ld, int col0, int b, const double* rinv, double* gpart,
                              hipStream_t st);
+
+// ---- connected components and locality reordering (setup) --------------------------------------
+// label[i] = i
+hipError_t launch_iota(int32_t* label, int64_t n, hipStream_t st);
+// one round of minimum-label propagation with pointer jumping; *changed = 1 if a label moved
+hipError_t launch_cc_round(const int64_t* rowptr, const int32_t* col, const double* val, int32_t* label, int64_t n,
+                           int* changed, hipStream_t st);
+// permuted CSR: row p = input row old_of_new[p], column c renamed new_of_old[c]; rowptr_new precomputed
+hipError_t launch_permute_csr(const int64_t* rowptr, const int32_t* col, const double* val, const int32_t* old_of_new,
+                              const int32_t* new_of_old, const int64_t* rowptr_new, int32_t* col_new, double* val_new,
+                              int64_t n, hipStream_t st);
+// basis[i, col0 + t] = comp[i] == t ? coef[i] : 0  for t < ncols (closed-form null vectors of the components)
+hipError_t launch_nullspace_fill(double* basis, int64_t n, int64_t ld, int col0, int ncols, const int32_t* comp,
+                                 const double* coef, hipStream_t st);
 
 // ---- misc ----------------------------------------------------------------------------------
 // basis[i, col0 + t] = uniform(-1, 1) from a counter-based hash of (seed, stream_id, i, t)

@@ -299,7 +299,8 @@ template <int NT, int MT>
 __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
                                                             int acol0, int kdim, const double* __restrict__ bmat,
                                                             int ldb, int ncols, int mode, int ccol0,
-                                                            double* __restrict__ out, int64_t ldo, int vec_ok) {
+                                                            double* __restrict__ out, int64_t ldo, int vec_ok,
+                                                            const int32_t* __restrict__ rowmap) {
   constexpr int KC = 4096 / (NT * 16);  // contraction indices per LDS chunk (32 KB)
   __shared__ double lds[KC * NT * 16];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -373,7 +374,7 @@ __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__
           } else if (mode == 1) {
             out[row * ldo + t] = v;
           } else {
-            out[(int64_t)t * ldo + row] = v;
+            out[(int64_t)t * ldo + (rowmap ? (int64_t)rowmap[row] : row)] = v;
           }
         }
       }
@@ -759,6 +760,84 @@ __global__ __launch_bounds__(64) void chol_reg_kernel(const double* __restrict__
   }
 }
 
+
+// --------------------------------------------------------------------------------------------
+// connected components by minimum-label propagation, and the row/column permutation of the CSR
+// --------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void iota_kernel(int32_t* __restrict__ label, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < n) label[i] = (int32_t)i;
+}
+
+// One round: label[i] <- min over i and its neighbours (entries with weight exactly 0 do not connect), followed
+// by pointer jumping label <- label[label].  Labels only decrease and always name a node of the same component,
+// so concurrent in-place updates are harmless; *changed is set if anything moved.
+__global__ __launch_bounds__(kThreads) void cc_round_kernel(const int64_t* __restrict__ rowptr,
+                                                            const int32_t* __restrict__ col,
+                                                            const double* __restrict__ val, int32_t* label, int64_t n,
+                                                            int* __restrict__ changed) {
+  const int64_t row = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 4;
+  const int lane = threadIdx.x & 15;
+  if (row >= n) return;  // uniform over the 16-lane group
+  const int32_t mine = label[row];
+  int32_t m = mine;
+  const int64_t e1 = rowptr[row + 1];
+  for (int64_t e = rowptr[row] + lane; e < e1; e += 16) {
+    if (val[e] != 0.0) {
+      const int32_t l = label[col[e]];
+      m = l < m ? l : m;
+    }
+  }
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) {
+    const int32_t other = __shfl_xor(m, o, 16);
+    m = other < m ? other : m;
+  }
+  if (lane == 0) {
+    for (int hop = 0; hop < 64; ++hop) {  // labels strictly decrease along the chain
+      const int32_t up = label[m];
+      if (up >= m) break;
+      m = up;
+    }
+    if (m < mine) {
+      label[row] = m;
+      *changed = 1;
+    }
+  }
+}
+
+// Row p of the permuted matrix is row old_of_new[p] of the input with columns renamed by new_of_old.
+__global__ __launch_bounds__(kThreads) void permute_csr_kernel(const int64_t* __restrict__ rowptr,
+                                                               const int32_t* __restrict__ col,
+                                                               const double* __restrict__ val,
+                                                               const int32_t* __restrict__ old_of_new,
+                                                               const int32_t* __restrict__ new_of_old,
+                                                               const int64_t* __restrict__ rowptr_new,
+                                                               int32_t* __restrict__ col_new,
+                                                               double* __restrict__ val_new, int64_t n) {
+  const int64_t p = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 4;
+  const int lane = threadIdx.x & 15;
+  if (p >= n) return;
+  const int64_t old = old_of_new[p];
+  const int64_t src = rowptr[old], len = rowptr[old + 1] - src, dst = rowptr_new[p];
+  for (int64_t t = lane; t < len; t += 16) {
+    col_new[dst + t] = new_of_old[col[src + t]];
+    val_new[dst + t] = val[src + t];
+  }
+}
+
+// basis[i, col0 + t] = (label of row i == t-th wanted label) ? sqrt(d_i / vol) : 0, written from per-row data:
+// comp[i] in [0, ncomp) is the component of (permuted) row i, coef[i] = sqrt(d_i / vol(comp[i])).
+__global__ __launch_bounds__(kThreads) void nullspace_fill_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
+                                                                  int col0, int ncols, const int32_t* __restrict__ comp,
+                                                                  const double* __restrict__ coef) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= n * ncols) return;
+  const int64_t i = idx / ncols;
+  const int t = (int)(idx - i * ncols);
+  basis[i * ld + col0 + t] = comp[i] == t ? coef[i] : 0.0;
+}
+
 }  // namespace
 
 // ============================================================================================
@@ -856,21 +935,22 @@ hipError_t launch_reduce_partials(const double* part, int npart, int ja, int b, 
 }
 
 hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int ldb,
-                           int ncols, int mode, int ccol0, double* out, int64_t ldo, hipStream_t st) {
+                           int ncols, int mode, int ccol0, double* out, int64_t ldo, const int32_t* rowmap,
+                           hipStream_t st) {
   if (kdim <= 0 || ncols <= 0) return hipSuccess;
   const int vec_ok = (ld % 4 == 0 && acol0 % 4 == 0 && (reinterpret_cast<uintptr_t>(basis) % 32 == 0)) ? 1 : 0;
   constexpr int MT = 2;
   const unsigned gx = (unsigned)ceil_div64(n, 4 * 16 * MT);
   if (ncols <= 16) {
     hipLaunchKernelGGL((row_gemm_kernel<1, MT>), dim3(gx, 1), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, bmat,
-                       ldb, ncols, mode, ccol0, out, ldo, vec_ok);
+                       ldb, ncols, mode, ccol0, out, ldo, vec_ok, rowmap);
   } else if (ncols <= 32) {
     hipLaunchKernelGGL((row_gemm_kernel<2, MT>), dim3(gx, 1), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, bmat,
-                       ldb, ncols, mode, ccol0, out, ldo, vec_ok);
+                       ldb, ncols, mode, ccol0, out, ldo, vec_ok, rowmap);
   } else {
     if (mode == 0) return hipErrorInvalidValue;
     hipLaunchKernelGGL((row_gemm_kernel<4, MT>), dim3(gx, (unsigned)((ncols + 63) / 64)), dim3(kThreads), 0, st, basis,
-                       n, ld, acol0, kdim, bmat, ldb, ncols, mode, ccol0, out, ldo, vec_ok);
+                       n, ld, acol0, kdim, bmat, ldb, ncols, mode, ccol0, out, ldo, vec_ok, rowmap);
   }
   return hipGetLastError();
 }
@@ -945,6 +1025,38 @@ hipError_t launch_copy_cols(const double* src, int64_t lds, int scol0, double* d
   if (w <= 0) return hipSuccess;
   hipLaunchKernelGGL(copy_cols_kernel, dim3((unsigned)ceil_div64(n * w, kThreads)), dim3(kThreads), 0, st, src, lds,
                      scol0, dst, ldd, dcol0, w, n);
+  return hipGetLastError();
+}
+
+}  // namespace sceig
+
+namespace sceig {
+
+hipError_t launch_iota(int32_t* label, int64_t n, hipStream_t st) {
+  hipLaunchKernelGGL(iota_kernel, dim3((unsigned)ceil_div64(n, kThreads)), dim3(kThreads), 0, st, label, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_cc_round(const int64_t* rowptr, const int32_t* col, const double* val, int32_t* label, int64_t n,
+                           int* changed, hipStream_t st) {
+  hipLaunchKernelGGL(cc_round_kernel, dim3((unsigned)ceil_div64(n * 16, kThreads)), dim3(kThreads), 0, st, rowptr,
+                     col, val, label, n, changed);
+  return hipGetLastError();
+}
+
+hipError_t launch_permute_csr(const int64_t* rowptr, const int32_t* col, const double* val, const int32_t* old_of_new,
+                              const int32_t* new_of_old, const int64_t* rowptr_new, int32_t* col_new, double* val_new,
+                              int64_t n, hipStream_t st) {
+  hipLaunchKernelGGL(permute_csr_kernel, dim3((unsigned)ceil_div64(n * 16, kThreads)), dim3(kThreads), 0, st, rowptr,
+                     col, val, old_of_new, new_of_old, rowptr_new, col_new, val_new, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_nullspace_fill(double* basis, int64_t n, int64_t ld, int col0, int ncols, const int32_t* comp,
+                                 const double* coef, hipStream_t st) {
+  if (ncols <= 0) return hipSuccess;
+  hipLaunchKernelGGL(nullspace_fill_kernel, dim3((unsigned)ceil_div64(n * ncols, kThreads)), dim3(kThreads), 0, st,
+                     basis, n, ld, col0, ncols, comp, coef);
   return hipGetLastError();
 }
 

@@ -170,3 +170,59 @@ def test_config2_full_size_bench_configuration(B):
     out = check_against_oracle(g, cfg.k, lam, vec, np.zeros(cfg.k), basis, cluster_basis=basis)
     assert np.max(compare.principal_angles(vec, basis)) <= 1e-5
     print("config2", stats, out)
+
+
+def _interleaved_components_graph():
+    parts = [wl.ring(30), wl.path(41), wl.random_weighted_connected(200, 500, 3), wl.hypercube(5), wl.complete(9),
+             wl.random_weighted_connected(333, 900, 4)]
+    g = wl.disjoint_union(*parts)
+    perm = np.random.default_rng(12).permutation(g[3])
+    return wl.relabel(g, perm), len(parts)
+
+
+def test_internal_reordering_is_invisible(B):
+    """The component pass renumbers nodes internally; outputs must be in the caller's numbering and agree with
+    the run that uses the CSR as given."""
+    g, ncomp = _interleaved_components_graph()
+    rp, c, v, n = g
+    lam_full, vec_full = dense.full_spectrum(rp, c, v)
+    k = 9
+    a = solve(B, g, k, 1e-10)
+    b = solve(B, g, k, 1e-10, flags=B.SC_FLAG_NO_REORDER)
+    assert a[3]["components"] == ncomp == components.component_labels(rp, c, v)[0]
+    assert b[3]["components"] == 0
+    for out in (a, b):
+        assert out[2] == B.SC_OK
+        check_against_oracle(g, k, out[0], out[1], lam_full[:k + 1], vec_full[:, :k])
+
+
+def test_zero_weight_entries_do_not_connect(B):
+    # two rings joined by one explicit zero-weight edge: still two components, two zero eigenvalues
+    g = wl.disjoint_union(wl.ring(40), wl.ring(50))
+    rp, c, v, n = g
+    extra_u, extra_v = np.array([3]), np.array([60])
+    rows = np.repeat(np.arange(n), np.diff(rp))
+    g2 = wl.coo_to_csr(np.concatenate([rows, extra_u, extra_v]), np.concatenate([c.astype(np.int64), extra_v, extra_u]),
+                       np.concatenate([v, [0.0, 0.0]]), n, sum_duplicates=False)
+    lam, vec, code, stats = solve(B, g2, 3, 1e-10)
+    assert code == B.SC_OK and stats["components"] == 2 == components.component_labels(*g2[:3])[0]
+    lam_full, vec_full = dense.full_spectrum(*g2[:3])
+    check_against_oracle(g2, 3, lam, vec, lam_full[:4], vec_full[:, :3])
+
+
+@pytest.mark.parametrize("k", [4, 6, 9])
+def test_component_nullspace_option(B, k):
+    """Optional pre-pass: the closed-form null vectors of the components are locked first (k below, equal to
+    and above the number of components)."""
+    g, ncomp = _interleaved_components_graph()
+    rp, c, v, n = g
+    lam_full, vec_full = dense.full_spectrum(rp, c, v)
+    lam, vec, code, stats = solve(B, g, k, 1e-10, flags=B.SC_FLAG_COMPONENT_NULLSPACE)
+    assert code == B.SC_OK
+    basis = components.null_space(rp, c, v) if k <= ncomp else None
+    if k == ncomp:
+        check_against_oracle(g, k, lam, vec, lam_full[:k + 1], vec_full[:, :k], cluster_basis=basis)
+    else:
+        check_against_oracle(g, k, lam, vec, lam_full[:k] if k < ncomp else lam_full[:k + 1],
+                             vec_full[:, :k], cluster_basis=basis)
+    assert np.sum(np.abs(lam) < 1e-12) == min(k, ncomp)

@@ -276,3 +276,16 @@ def test_config1_full_size_three_oracles_agree():
     assert np.allclose(lam10, full[:10], atol=1e-10)
     lamc, vecc = components.smallest_eigenpairs(rp, c, v, 10)
     assert np.allclose(lamc, full[:10], atol=1e-11)
+
+
+def test_component_labels_leave_the_input_untouched_and_ignore_zero_weights():
+    g = wl.disjoint_union(wl.ring(6), wl.ring(5))
+    rp, c, v, n = g
+    rows = np.repeat(np.arange(n), np.diff(rp))
+    g2 = wl.coo_to_csr(np.concatenate([rows, [1], [8]]), np.concatenate([c.astype(np.int64), [8], [1]]),
+                       np.concatenate([v, [0.0, 0.0]]), n, sum_duplicates=False)
+    before = [a.copy() for a in g2[:3]]
+    ncomp, label = components.component_labels(*g2[:3])
+    assert ncomp == 2 and len(set(label[:6])) == 1 and len(set(label[6:])) == 1 and label[0] != label[6]
+    for a, b in zip(before, g2[:3]):
+        assert np.array_equal(a, b)
