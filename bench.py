@@ -123,22 +123,29 @@ def main():
     evals, evecs, code, stats = last
     sec = elapsed / args.steps
 
-    # SpMV (single vector) on the same graph: algorithmic bytes / kernel time
-    _, s = B.sc_degree_scaling(drp, dc, dv, want_degrees=False)
-    x = torch.randn(n, dtype=torch.float64, device="cuda")
-    y = torch.empty_like(x)
-    work = torch.empty_like(x)
-    for _ in range(5):
-        B.sc_spmm_normalized(drp, dc, dv, s, x, y, work)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    reps = 50
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(reps):
-        B.sc_spmm_normalized(drp, dc, dv, s, x, y, work)
-    e1.record()
-    torch.cuda.synchronize()
-    spmv_s = e0.elapsed_time(e1) * 1e-3 / reps
+    # SpMV (single vector y = S x): algorithmic bytes / time, on the node numbering the solver itself works in
+    # (its setup pass makes every connected component contiguous; that pass is part of every timed eigensolve)
+    # and, for context, on the numbering the caller handed over.  Products are enqueued back to back.
+    def time_spmv(rp_d, c_d, v_d):
+        _, s = B.sc_degree_scaling(rp_d, c_d, v_d, want_degrees=False)
+        x = torch.randn(n, dtype=torch.float64, device="cuda")
+        y = torch.empty_like(x)
+        work = torch.empty_like(x)
+        for _ in range(5):
+            B.sc_spmm_normalized(rp_d, c_d, v_d, s, x, y, work)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 50
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            B.sc_spmm_normalized(rp_d, c_d, v_d, s, x, y, work)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    rp2, c2, v2, _, ncomp = B.sc_reorder_csr(drp, dc, dv)
+    spmv_s = time_spmv(rp2, c2, v2)
+    spmv_s_given = time_spmv(drp, dc, dv)
     spmv_bytes = 12 * nnz + 8 * (n + 1) + 8 * n + 8 * n + 8 * n
     spmv_gbs = spmv_bytes / spmv_s / 1e9
 
@@ -150,7 +157,10 @@ def main():
         "config": {"workload": f"{cfg.name}: n={n}, nnz={nnz}, k={cfg.k}, m={stats['m']}, tol={cfg.tol}, "
                                f"block={stats['block']}", "status": int(code)},
         "spmv": {"gbps_algorithmic": spmv_gbs, "seconds": spmv_s, "bytes": spmv_bytes,
-                 "note": "single-vector y = S x incl. the s*x prescale pass; whole call timed with events"},
+                 "frac_of_hbm_peak": spmv_gbs / HBM_PEAK_GBS,
+                 "gbps_algorithmic_caller_numbering": spmv_bytes / spmv_s_given / 1e9,
+                 "note": "single-vector y = S x (prescale pass + product kernel), 50 back-to-back calls timed with "
+                         "events, on the component-contiguous numbering the solver uses internally"},
         "solver_stats": stats,
     }
     kt = stats["fam_time_s"][dom]

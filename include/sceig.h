@@ -140,11 +140,26 @@ int sc_degree_scaling(const int64_t* csr_rowptr, const int32_t* csr_col, const d
  *   y     device, row-major n x ncols, leading dimension ldy >= ncols; must not alias x
  *   work  device fp64[n*ncols] scratch (holds diag(s) X packed); may be NULL, then it is allocated
  *         and freed inside the call
+ * Exception to the general rule: when `work` is given this call only ENQUEUES on `stream` and returns without
+ * synchronising (products can be issued back to back); with work == NULL it returns after completion.
  * CSR columns are NOT range-checked here (sc_validate_csr does that).
  */
 int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, const double* s,
                        int64_t n, const double* x, int64_t ldx, double* y, int64_t ldy, int32_t ncols, double* work,
                        void* stream);
+
+/*
+ * The setup pass sc_laplacian_eigsh runs unless SC_FLAG_NO_REORDER is set, as a step of its own: connected
+ * components of W (entries with weight exactly 0 do not connect) by label propagation on the device, and the
+ * component-contiguous renumbering of the nodes (order inside a component unchanged).
+ *   rowptr_out int64[n+1], col_out int32[nnz], val_out fp64[nnz]   device, the renumbered CSR
+ *   old_of_new_out int32[n]   device: original index of new node p (y_orig[old_of_new[p]] = y_new[p])
+ *   ncomp_out                 host, number of connected components (may be NULL)
+ * The CSR is validated first (SC_ECSR).
+ */
+int sc_reorder_csr(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n,
+                   int64_t* rowptr_out, int32_t* col_out, double* val_out, int32_t* old_of_new_out, int32_t* ncomp_out,
+                   void* stream);
 
 /* Structural check of a device CSR: SC_OK or SC_ECSR. */
 int sc_validate_csr(const int64_t* csr_rowptr, const int32_t* csr_col, int64_t n, void* stream);

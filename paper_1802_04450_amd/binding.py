@@ -21,7 +21,7 @@ SC_FLAG_NO_REORDER = 2
 SC_FLAG_COMPONENT_NULLSPACE = 4
 FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 
-EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_cgs2",
+EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_reorder_csr", "sc_cgs2",
            "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version"]
 
 
@@ -74,6 +74,7 @@ def lib() -> ctypes.CDLL:
         _lib.sc_degree_scaling.argtypes = [vp, vp, vp, i64, vp, vp, vp]
         _lib.sc_spmm_normalized.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, i64, i32, vp, vp]
         _lib.sc_validate_csr.argtypes = [vp, vp, i64, vp]
+        _lib.sc_reorder_csr.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp]
         _lib.sc_cgs2.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         _lib.sc_block_qr.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         _lib.sc_rotate.argtypes = [vp, i64, i64, i32, i32, vp, i32, vp, i64, i32, vp]
@@ -157,8 +158,23 @@ def sc_validate_csr(rowptr, col) -> int:
         return lib().sc_validate_csr(_ptr(rowptr), _ptr(col), n, _stream())
 
 
+def sc_reorder_csr(rowptr, col, val):
+    """Component-contiguous renumbering.  Returns (rowptr', col', val', old_of_new int32[n], ncomp)."""
+    import torch
+    n = rowptr.numel() - 1
+    rp2, c2, v2 = torch.empty_like(rowptr), torch.empty_like(col), torch.empty_like(val)
+    oon = torch.empty(n, dtype=torch.int32, device=rowptr.device)
+    ncomp = ctypes.c_int32(0)
+    with torch.cuda.device(rowptr.device):
+        code = lib().sc_reorder_csr(_ptr(rowptr), _ptr(col), _ptr(val), n, _ptr(rp2), _ptr(c2), _ptr(v2), _ptr(oon),
+                                    ctypes.byref(ncomp), _stream())
+    _check(code)
+    return rp2, c2, v2, oon, int(ncomp.value)
+
+
 def sc_spmm_normalized(rowptr, col, val, s, x, y=None, work=None):
-    """x: (n, ncols) row-major device tensor (a 1-D tensor is one column).  Returns y of the same shape."""
+    """x: (n, ncols) row-major device tensor (a 1-D tensor is one column).  Returns y of the same shape.
+    With `work` given the call only enqueues on the current stream (synchronise before reading y on the host)."""
     import torch
     n = rowptr.numel() - 1
     x2 = x.reshape(n, -1)

@@ -222,6 +222,61 @@ void enqueue_block_qr(double* basis, int64_t n, int64_t ld, int col, int b, doub
 
 constexpr int kGramPartials = 1024;
 
+// Connected components by label propagation on the device, then rows and columns are renumbered so that every
+// component is contiguous (stable inside a component).  The sparse products then gather from a few hundred KB at
+// a time instead of from all over the vector; mathematically the result is a permutation similarity of the input.
+// Outputs: permuted CSR (device, caller-allocated, same sizes as the input), old_of_new (device int32[n]: original
+// index of each new row), optionally the component index of each new row (host).  Returns the component count.
+int reorder_csr(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n, int64_t nnz,
+                int64_t* rowptr_out, int32_t* col_out, double* val_out, int32_t* old_of_new_out,
+                std::vector<int32_t>* comp_of_new, hipStream_t st) {
+  DevBuf<int32_t> label, new_of_old_d;
+  DevBuf<int> flag;
+  label.alloc((size_t)n);
+  flag.alloc(1);
+  HIP_TRY(launch_iota(label.p, n, st));
+  for (int round = 0; round < 100000; ++round) {
+    int h = 0;
+    HIP_TRY(hipMemsetAsync(flag.p, 0, sizeof(int), st));
+    HIP_TRY(launch_cc_round(rowptr, col, val, label.p, n, flag.p, st));
+    HIP_TRY(launch_cc_round(rowptr, col, val, label.p, n, flag.p, st));
+    HIP_TRY(hipMemcpyAsync(&h, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (!h) break;
+  }
+  std::vector<int32_t> lab((size_t)n), new_of_old((size_t)n), old_of_new((size_t)n);
+  std::vector<int64_t> rp((size_t)n + 1), rp_new((size_t)n + 1);
+  HIP_TRY(hipMemcpyAsync(lab.data(), label.p, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync(rp.data(), rowptr, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  // counting sort by component (component = its smallest node id), stable in the node id
+  std::vector<int64_t> start((size_t)n + 1, 0);
+  for (int64_t i = 0; i < n; ++i) start[(size_t)lab[i] + 1] += 1;
+  std::vector<int32_t> comp_of_root((size_t)n, -1);
+  int ncomp = 0;
+  for (int64_t r = 0; r < n; ++r) {
+    if (start[r + 1] > 0) comp_of_root[r] = ncomp++;
+    start[r + 1] += start[r];
+  }
+  if (comp_of_new) comp_of_new->assign((size_t)n, 0);
+  for (int64_t i = 0; i < n; ++i) {
+    const int64_t p = start[lab[i]]++;
+    new_of_old[i] = (int32_t)p;
+    old_of_new[p] = (int32_t)i;
+    if (comp_of_new) (*comp_of_new)[p] = comp_of_root[lab[i]];
+  }
+  rp_new[0] = 0;
+  for (int64_t p = 0; p < n; ++p) rp_new[p + 1] = rp_new[p] + (rp[old_of_new[p] + 1] - rp[old_of_new[p]]);
+  new_of_old_d.alloc((size_t)n);
+  HIP_TRY(hipMemcpyAsync(rowptr_out, rp_new.data(), ((size_t)n + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipMemcpyAsync(old_of_new_out, old_of_new.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipMemcpyAsync(new_of_old_d.p, new_of_old.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  HIP_TRY(launch_permute_csr(rowptr, col, val, old_of_new_out, new_of_old_d.p, rowptr_out, col_out, val_out, n, st));
+  HIP_TRY(hipStreamSynchronize(st));  // the host vectors above are pageable and go out of scope
+  (void)nnz;
+  return ncomp;
+}
+
 struct Solver {
   // problem
   const int64_t* rowptr;
@@ -240,7 +295,7 @@ struct Solver {
   DevBuf<double> basis, s, z, part, gpart, h1, hsum, small, slots, yd, rot;
   DevBuf<int> flag;
   DevBuf<int64_t> rowptr_p;
-  DevBuf<int32_t> col_p, label, old_of_new_d, new_of_old_d, comp_d;
+  DevBuf<int32_t> col_p, old_of_new_d, comp_d;
   DevBuf<double> val_p, coef_d;
   const int32_t* rowmap = nullptr;  // device: original row of each internal row, null if not reordered
   std::vector<int32_t> comp_host;   // component index of each internal row (only after reorder())
@@ -262,61 +317,16 @@ struct Solver {
   double* slot(int i) { return slots.p + (size_t)i * kSlotDoubles; }
   const double* hslot(int i) const { return slots_host.p + (size_t)i * kSlotDoubles; }
 
-  // Connected components by label propagation on the device, then rows and columns are renumbered so that
-  // every component is contiguous (stable inside a component).  The sparse products gather from a few hundred KB
-  // at a time instead of from all over the vector; mathematically the problem is a permutation similarity of
-  // the input, undone when the eigenvectors are written.
   void reorder() {
-    label.alloc((size_t)n);
-    HIP_TRY(launch_iota(label.p, n, st));
-    for (int round = 0; round < 100000; ++round) {
-      int h = 0;
-      HIP_TRY(hipMemsetAsync(flag.p, 0, sizeof(int), st));
-      HIP_TRY(launch_cc_round(rowptr, col, val, label.p, n, flag.p, st));
-      HIP_TRY(launch_cc_round(rowptr, col, val, label.p, n, flag.p, st));
-      HIP_TRY(hipMemcpyAsync(&h, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
-      HIP_TRY(hipStreamSynchronize(st));
-      if (!h) break;
-    }
-    std::vector<int32_t> lab((size_t)n), new_of_old((size_t)n), old_of_new((size_t)n);
-    std::vector<int64_t> rp((size_t)n + 1), rp_new((size_t)n + 1);
-    HIP_TRY(hipMemcpyAsync(lab.data(), label.p, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-    HIP_TRY(hipMemcpyAsync(rp.data(), rowptr, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
-    HIP_TRY(hipStreamSynchronize(st));
-    // counting sort by component (component = its smallest node id), stable in the node id
-    std::vector<int64_t> start((size_t)n + 1, 0);
-    for (int64_t i = 0; i < n; ++i) start[(size_t)lab[i] + 1] += 1;
-    std::vector<int32_t> comp_of_root((size_t)n, -1);
-    ncomp = 0;
-    for (int64_t r = 0; r < n; ++r) {
-      if (start[r + 1] > 0) comp_of_root[r] = ncomp++;
-      start[r + 1] += start[r];
-    }
-    comp_host.assign((size_t)n, 0);
-    for (int64_t i = 0; i < n; ++i) {
-      const int64_t p = start[lab[i]]++;
-      new_of_old[i] = (int32_t)p;
-      old_of_new[p] = (int32_t)i;
-      comp_host[p] = comp_of_root[lab[i]];
-    }
-    rp_new[0] = 0;
-    for (int64_t p = 0; p < n; ++p) rp_new[p + 1] = rp_new[p] + (rp[old_of_new[p] + 1] - rp[old_of_new[p]]);
     rowptr_p.alloc((size_t)n + 1);
     col_p.alloc((size_t)nnz);
     val_p.alloc((size_t)nnz);
     old_of_new_d.alloc((size_t)n);
-    new_of_old_d.alloc((size_t)n);
-    HIP_TRY(hipMemcpyAsync(rowptr_p.p, rp_new.data(), ((size_t)n + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(old_of_new_d.p, old_of_new.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(new_of_old_d.p, new_of_old.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
-    HIP_TRY(launch_permute_csr(rowptr, col, val, old_of_new_d.p, new_of_old_d.p, rowptr_p.p, col_p.p, val_p.p, n, st));
-    HIP_TRY(hipStreamSynchronize(st));  // the host vectors above are pageable and go out of scope
+    ncomp = reorder_csr(rowptr, col, val, n, nnz, rowptr_p.p, col_p.p, val_p.p, old_of_new_d.p, &comp_host, st);
     rowptr = rowptr_p.p;
     col = col_p.p;
     val = val_p.p;
     rowmap = old_of_new_d.p;
-    label.release();
-    new_of_old_d.release();
   }
 
   // Optional: the closed-form null vectors D^1/2 1_C / sqrt(vol C) of the first min(k, ncomp) components are
@@ -905,6 +915,42 @@ int sc_validate_csr(const int64_t* csr_rowptr, const int32_t* csr_col, int64_t n
       &ctx);
 }
 
+int sc_reorder_csr(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n,
+                   int64_t* rowptr_out, int32_t* col_out, double* val_out, int32_t* old_of_new_out, int32_t* ncomp_out,
+                   void* stream) {
+  if (!csr_rowptr || !csr_col || !csr_val || !rowptr_out || !col_out || !val_out || !old_of_new_out || n < 0)
+    return SC_EINVAL;
+  if (n > (int64_t)0x7fffffff) return SC_EDOMAIN;
+  if (ncomp_out) *ncomp_out = 0;
+  if (n == 0) return SC_OK;
+  const int rc = sc_validate_csr(csr_rowptr, csr_col, n, stream);
+  if (rc != SC_OK) return rc;
+  struct Ctx {
+    const int64_t* rp;
+    const int32_t* c;
+    const double* v;
+    int64_t n;
+    int64_t* rpo;
+    int32_t* co;
+    double* vo;
+    int32_t* oon;
+    int32_t* nc;
+    hipStream_t st;
+  } ctx{csr_rowptr, csr_col, csr_val, n, rowptr_out, col_out, val_out, old_of_new_out, ncomp_out,
+        reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        int64_t nnz = 0;
+        HIP_TRY(hipMemcpyAsync(&nnz, c->rp + c->n, sizeof(int64_t), hipMemcpyDeviceToHost, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        const int ncomp = reorder_csr(c->rp, c->c, c->v, c->n, nnz, c->rpo, c->co, c->vo, c->oon, nullptr, c->st);
+        if (c->nc) *c->nc = ncomp;
+        return SC_OK;
+      },
+      &ctx);
+}
+
 int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, const double* s,
                        int64_t n, const double* x, int64_t ldx, double* y, int64_t ldy, int32_t ncols, double* work,
                        void* stream) {
@@ -934,12 +980,22 @@ int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const 
           own.alloc((size_t)c->n * c->b);
           z = own.p;
         }
-        int64_t nnz = 0;
-        HIP_TRY(hipMemcpyAsync(&nnz, c->rp + c->n, sizeof(int64_t), hipMemcpyDeviceToHost, c->st));
-        HIP_TRY(hipStreamSynchronize(c->st));
+        // the entry count only steers the kernel choice; it is remembered for the last graph seen so that
+        // repeated products with one matrix do not pay a device-to-host round trip each
+        static thread_local const int64_t* last_rp = nullptr;
+        static thread_local int64_t last_n = -1, last_nnz = 0;
+        if (last_rp != c->rp || last_n != c->n) {
+          int64_t nnz = 0;
+          HIP_TRY(hipMemcpyAsync(&nnz, c->rp + c->n, sizeof(int64_t), hipMemcpyDeviceToHost, c->st));
+          HIP_TRY(hipStreamSynchronize(c->st));
+          last_rp = c->rp;
+          last_n = c->n;
+          last_nnz = nnz;
+        }
         HIP_TRY(launch_pack_scaled(c->x, c->ldx, c->s, c->n, c->b, z, c->st));
-        HIP_TRY(launch_spmm(c->rp, c->c, c->v, c->s, c->n, z, c->b, c->y, c->ldy, (double)nnz / (double)c->n, c->st));
-        HIP_TRY(hipStreamSynchronize(c->st));
+        HIP_TRY(launch_spmm(c->rp, c->c, c->v, c->s, c->n, z, c->b, c->y, c->ldy, (double)last_nnz / (double)c->n,
+                            c->st));
+        if (own.p) HIP_TRY(hipStreamSynchronize(c->st));  // the internal scratch is freed on return
         return SC_OK;
       },
       &ctx);

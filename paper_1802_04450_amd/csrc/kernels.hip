@@ -134,11 +134,12 @@ __global__ __launch_bounds__(kThreads) void spmm_nz_kernel(const int64_t* __rest
   double acc[B];
 #pragma unroll
   for (int q = 0; q < B; ++q) acc[q] = 0.0;
-  for (int64_t e = rowptr[row] + t; e < e1; e += L) {
-    const int64_t c = col[e];
-    const double a = val[e];
+  for (int64_t e = rowptr[row] + t; e < e1; e += 2 * L) {
+    const bool ok1 = e + L < e1;
+    const int64_t c0 = col[e], c1 = ok1 ? col[e + L] : 0;
+    const double a0 = val[e], a1 = ok1 ? val[e + L] : 0.0;
 #pragma unroll
-    for (int q = 0; q < B; ++q) acc[q] += a * z[c * B + q];
+    for (int q = 0; q < B; ++q) acc[q] += a0 * z[c0 * B + q] + a1 * z[c1 * B + q];
   }
 #pragma unroll
   for (int o = L / 2; o > 0; o >>= 1) {
@@ -152,9 +153,87 @@ __global__ __launch_bounds__(kThreads) void spmm_nz_kernel(const int64_t* __rest
   }
 }
 
+// Row-block streaming product for narrow blocks (B = 1, 2, 4): a workgroup owns RB consecutive rows, streams their
+// entries fully coalesced (eight independent entry loads and gathers per thread in flight), parks the products
+// val * z[col] in LDS and then sums every row from LDS with 256/RB lanes.  No row is split between workgroups
+// and the order of every sum is fixed by the row's position, so results are reproducible.
+template <int B, int RB>
+__global__ __launch_bounds__(kThreads) void spmm_stream_kernel(const int64_t* __restrict__ rowptr,
+                                                               const int32_t* __restrict__ col,
+                                                               const double* __restrict__ val,
+                                                               const double* __restrict__ s,
+                                                               const double* __restrict__ z, double* __restrict__ y,
+                                                               int64_t ldy, int64_t n) {
+  constexpr int CH = 2048 / B;       // entries per LDS chunk
+  constexpr int LR = kThreads / RB;  // lanes per row in the summation
+  __shared__ double prod[CH * B];
+  __shared__ int64_t rp[RB + 1];
+  const int64_t r0 = (int64_t)blockIdx.x * RB;
+  const int nrows = (int)((n - r0) < RB ? (n - r0) : RB);
+  if (threadIdx.x <= nrows) rp[threadIdx.x] = rowptr[r0 + threadIdx.x];
+  __syncthreads();
+  const int64_t e_begin = rp[0], e_end = rp[nrows];
+  const int rl = threadIdx.x / LR, lane = threadIdx.x % LR;
+  double acc[B];
+#pragma unroll
+  for (int q = 0; q < B; ++q) acc[q] = 0.0;
+  for (int64_t c0 = e_begin; c0 < e_end; c0 += CH) {
+    const int64_t c1 = (c0 + CH) < e_end ? (c0 + CH) : e_end;
+    for (int64_t base = c0 + threadIdx.x; base < c1; base += 4 * kThreads) {
+      int32_t c[4];
+      double a[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bool ok = base + u * kThreads < c1;
+        c[u] = ok ? col[base + u * kThreads] : 0;
+        a[u] = ok ? val[base + u * kThreads] : 0.0;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (base + u * kThreads < c1) {
+#pragma unroll
+          for (int q = 0; q < B; ++q)
+            prod[(base + u * kThreads - c0) * B + q] = a[u] * z[(int64_t)c[u] * B + q];
+        }
+      }
+    }
+    __syncthreads();
+    if (rl < nrows) {
+      int64_t lo = rp[rl] > c0 ? rp[rl] : c0;
+      const int64_t hi = rp[rl + 1] < c1 ? rp[rl + 1] : c1;
+      for (int64_t e = lo + lane; e < hi; e += LR) {
+#pragma unroll
+        for (int q = 0; q < B; ++q) acc[q] += prod[(e - c0) * B + q];
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int o = LR / 2; o > 0; o >>= 1) {
+#pragma unroll
+    for (int q = 0; q < B; ++q) acc[q] += __shfl_xor(acc[q], o, LR);
+  }
+  if (lane == 0 && rl < nrows) {
+    const double sr = s[r0 + rl];
+#pragma unroll
+    for (int q = 0; q < B; ++q) y[(r0 + rl) * ldy + q] = sr * acc[q];
+  }
+}
+
 template <int B>
 hipError_t launch_spmm_nz(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
                           const double* z, double* y, int64_t ldy, double avg_deg, hipStream_t st) {
+  if (avg_deg >= 6.0) {
+    // row-block streaming: 64 rows per workgroup for short rows, 32 otherwise (4 or 8 lanes per row sum)
+    if (avg_deg < 24.0) {
+      hipLaunchKernelGGL((spmm_stream_kernel<B, 64>), dim3((unsigned)ceil_div64(n, 64)), dim3(kThreads), 0, st, rowptr,
+                         col, val, s, z, y, ldy, n);
+    } else {
+      hipLaunchKernelGGL((spmm_stream_kernel<B, 32>), dim3((unsigned)ceil_div64(n, 32)), dim3(kThreads), 0, st, rowptr,
+                         col, val, s, z, y, ldy, n);
+    }
+    return hipGetLastError();
+  }
   int lanes = 4;
   while (lanes < 64 && lanes * 2 <= avg_deg) lanes *= 2;  // largest power of two <= avg_deg, in [4, 64]
 #define SC_LAUNCH_NZ(LL)                                                                                       \

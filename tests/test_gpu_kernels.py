@@ -90,6 +90,12 @@ def test_spmm_normalized(B, graphs, ncols):
         scale = np.abs(y0).max() + 1e-300
         assert np.max(np.abs(y - y0)) <= 1e-13 * scale, (name, ncols)
         assert torch.all(yb[:, ncols:] == 7.0)        # nothing written outside the block
+        # caller-provided scratch: enqueue-only variant, result read after the stream is synchronised
+        work = torch.empty((n, ncols), dtype=torch.float64, device="cuda")
+        y2 = torch.zeros((n, ncols), dtype=torch.float64, device="cuda")
+        B.sc_spmm_normalized(drp, dc, dv, s, xb[:, :ncols], y2, work)
+        torch.cuda.synchronize()
+        assert torch.equal(y2, yb[:, :ncols])
 
 
 @pytest.mark.parametrize("n,j,b", [(5000, 70, 16), (4099, 130, 8), (3001, 300, 32), (2500, 17, 1), (2000, 64, 4),
@@ -165,3 +171,25 @@ def test_rotate(B, n, j0, ja, l, colmajor):
     if colmajor:
         out = out.T
     assert np.max(np.abs(out - ref)) <= 1e-12 * np.abs(ref).max()
+
+
+def test_reorder_csr_is_a_permutation_similarity(B):
+    from oracle import components
+    parts = [wl.ring(30), wl.path(41), wl.random_weighted_connected(200, 500, 3), wl.hypercube(5)]
+    g = wl.disjoint_union(*parts)
+    g = wl.relabel(g, np.random.default_rng(3).permutation(g[3]))
+    rp, c, v, n = g
+    drp, dc, dv = B.csr_to_device(rp, c, v)
+    rp2, c2, v2, oon, ncomp = B.sc_reorder_csr(drp, dc, dv)
+    assert ncomp == len(parts) == components.component_labels(rp, c, v)[0]
+    oon = oon.cpu().numpy().astype(np.int64)
+    assert np.array_equal(np.sort(oon), np.arange(n))
+    from scipy.sparse import csr_matrix
+    a = csr_matrix((v, c, rp), shape=(n, n)).toarray()
+    a2 = csr_matrix((v2.cpu().numpy(), c2.cpu().numpy(), rp2.cpu().numpy()), shape=(n, n)).toarray()
+    assert np.array_equal(a2, a[np.ix_(oon, oon)])                 # A'[p, q] = A[old(p), old(q)], bit for bit
+    _, label = components.component_labels(rp, c, v)
+    lab_new = label[oon]
+    assert np.all(np.diff(np.flatnonzero(np.diff(lab_new) != 0)) > 0) and len(set(lab_new)) == ncomp
+    # every component is one contiguous run
+    assert np.count_nonzero(np.diff(lab_new) != 0) == ncomp - 1
