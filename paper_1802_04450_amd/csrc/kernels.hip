@@ -280,32 +280,40 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const double* __restr
 
   const int cbase = c0 + 4 * i;
   const bool full = vec_ok && (cbase + 3 < ja);
-#pragma unroll 2
-  for (int64_t r = r0; r < r1; r += 4) {
-    const int64_t row = r + g;
-    double a[4] = {0.0, 0.0, 0.0, 0.0};
-    double bv[NT];
+  // four row-quads (16 rows) per trip: all their loads are issued before the first MFMA needs them
+  constexpr int U = 4;
+  for (int64_t r = r0; r < r1; r += 4 * U) {
+    double a[U][4];
+    double bv[U][NT];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) bv[nt] = 0.0;
-    if (row < r1) {
-      const double* rp = basis + row * ld;
-      const double* ap = rp + acol0 + cbase;
-      if (full) {
-        const d4 v = *reinterpret_cast<const d4*>(ap);
-        a[0] = v[0]; a[1] = v[1]; a[2] = v[2]; a[3] = v[3];
-      } else {
+    for (int u = 0; u < U; ++u) {
+      const int64_t row = r + 4 * u + g;
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          if (cbase + q < ja) a[q] = ap[q];
+      for (int q = 0; q < 4; ++q) a[u][q] = 0.0;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) bv[u][nt] = 0.0;
+      if (row < r1) {
+        const double* rp = basis + row * ld;
+        const double* ap = rp + acol0 + cbase;
+        if (full) {
+          const d4 v = *reinterpret_cast<const d4*>(ap);
+          a[u][0] = v[0]; a[u][1] = v[1]; a[u][2] = v[2]; a[u][3] = v[3];
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            if (cbase + q < ja) a[u][q] = ap[q];
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          if (i + 16 * nt < b) bv[u][nt] = rp[bcol0 + i + 16 * nt];
       }
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-        if (i + 16 * nt < b) bv[nt] = rp[bcol0 + i + 16 * nt];
     }
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+    for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) acc[nt][q] = MFMA_F64(a[q], bv[nt], acc[nt][q]);
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[nt][q] = MFMA_F64(a[u][q], bv[u][nt], acc[nt][q]);
   }
 
   double* out = part + (int64_t)pidx * ja * kPartialPad;
@@ -406,35 +414,44 @@ __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__
       lds[((((kt * 4 + q) * NT + nt) * 4 + gg) << 4) + ii] = v;
     }
     __syncthreads();
-    for (int kk = 0; kk < kc16; kk += 16) {
-      double a[MT][4];
-      const int kcol = k0 + kk + 4 * g;
+    // two 16-index groups per trip: their loads are issued together, ahead of the MFMAs that use them
+    for (int kk = 0; kk < kc16; kk += 32) {
+      double a[2][MT][4];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int64_t row = row0 + mt * 16 + i;
+      for (int h = 0; h < 2; ++h) {
+        const int kcol = k0 + kk + 16 * h + 4 * g;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) a[mt][q] = 0.0;
-        if (row < n) {
-          const double* ap = basis + row * ld + acol0 + kcol;
-          if (vec_ok && kcol + 3 < kdim) {
-            const d4 v = *reinterpret_cast<const d4*>(ap);
-            a[mt][0] = v[0]; a[mt][1] = v[1]; a[mt][2] = v[2]; a[mt][3] = v[3];
-          } else {
+        for (int mt = 0; mt < MT; ++mt) {
+          const int64_t row = row0 + mt * 16 + i;
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-              if (kcol + q < kdim) a[mt][q] = ap[q];
+          for (int q = 0; q < 4; ++q) a[h][mt][q] = 0.0;
+          if (row < n && kk + 16 * h < kc16) {
+            const double* ap = basis + row * ld + acol0 + kcol;
+            if (vec_ok && kcol + 3 < kdim) {
+              const d4 v = *reinterpret_cast<const d4*>(ap);
+              a[h][mt][0] = v[0]; a[h][mt][1] = v[1]; a[h][mt][2] = v[2]; a[h][mt][3] = v[3];
+            } else {
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+                if (kcol + q < kdim) a[h][mt][q] = ap[q];
+            }
           }
         }
       }
-      const int kt = kk >> 4;
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
+      for (int h = 0; h < 2; ++h) {
+        if (kk + 16 * h < kc16) {  // uniform; the LDS slots beyond kc16 were not filled
+          const int kt = (kk >> 4) + h;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          const double bq = lds[((((kt * 4 + q) * NT + nt) * 4 + g) << 4) + i];
+          for (int q = 0; q < 4; ++q)
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = MFMA_F64(a[mt][q], bq, acc[mt][nt]);
+            for (int nt = 0; nt < NT; ++nt) {
+              const double bq = lds[((((kt * 4 + q) * NT + nt) * 4 + g) << 4) + i];
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = MFMA_F64(a[h][mt][q], bq, acc[mt][nt]);
+            }
         }
+      }
     }
   }
 
@@ -640,35 +657,44 @@ __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restric
         load_chunk(k0, kc, kc16);
         __syncthreads();
       }
-      for (int kk = 0; kk < kc16; kk += 16) {
-        double a[MT][4];
-        const int kcol = k0 + kk + 4 * g;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const int64_t row = row0 + mt * 16 + i;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) a[mt][q] = 0.0;
-          if (row < n) {
-            const double* ap = basis + row * ld + kcol;
-            if (vec_ok && kcol + 3 < kdim) {
-              const d4 v = *reinterpret_cast<const d4*>(ap);
-              a[mt][0] = v[0]; a[mt][1] = v[1]; a[mt][2] = v[2]; a[mt][3] = v[3];
-            } else {
-#pragma unroll
-              for (int q = 0; q < 4; ++q)
-                if (kcol + q < kdim) a[mt][q] = ap[q];
+      // two 16-index groups per trip: their loads are issued together, ahead of the MFMAs that use them
+      for (int kk = 0; kk < kc16; kk += 32) {
+        double a[2][MT][4];
+  #pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int kcol = k0 + kk + 16 * h + 4 * g;
+  #pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const int64_t row = row0 + mt * 16 + i;
+  #pragma unroll
+            for (int q = 0; q < 4; ++q) a[h][mt][q] = 0.0;
+            if (row < n && kk + 16 * h < kc16) {
+              const double* ap = basis + row * ld + kcol;
+              if (vec_ok && kcol + 3 < kdim) {
+                const d4 v = *reinterpret_cast<const d4*>(ap);
+                a[h][mt][0] = v[0]; a[h][mt][1] = v[1]; a[h][mt][2] = v[2]; a[h][mt][3] = v[3];
+              } else {
+  #pragma unroll
+                for (int q = 0; q < 4; ++q)
+                  if (kcol + q < kdim) a[h][mt][q] = ap[q];
+              }
             }
           }
         }
-        const int kt = kk >> 4;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-          for (int nt = 0; nt < NT; ++nt) {
-            const double bq = lds[((((kt * 4 + q) * NT + nt) * 4 + g) << 4) + i];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = MFMA_F64(a[mt][q], bq, acc[mt][nt]);
+  #pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          if (kk + 16 * h < kc16) {  // uniform; the LDS slots beyond kc16 were not filled
+            const int kt = (kk >> 4) + h;
+  #pragma unroll
+            for (int q = 0; q < 4; ++q)
+  #pragma unroll
+              for (int nt = 0; nt < NT; ++nt) {
+                const double bq = lds[((((kt * 4 + q) * NT + nt) * 4 + g) << 4) + i];
+  #pragma unroll
+                for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = MFMA_F64(a[h][mt][q], bq, acc[mt][nt]);
+              }
           }
+        }
       }
     }
     // new block rows: to memory and into the tile
