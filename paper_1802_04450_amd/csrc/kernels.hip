@@ -754,7 +754,8 @@ __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restric
 }
 
 // basis[:, col0 : col0+b] *= rinv (as apply_rinv_kernel) fused with the Gram matrix of the result;
-// grid-stride over groups of 256/b rows, one Gram partial per workgroup.
+// grid-stride over groups of 256/b rows, one Gram partial per workgroup.  For the Gram sums the 256 threads are
+// split into NS = max(1, 256/b^2) row subsets per matrix entry, combined in subset order at the end.
 __global__ __launch_bounds__(kThreads) void apply_gram_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
                                                               int col0, int b, const double* __restrict__ rinv,
                                                               double* __restrict__ gpart) {
@@ -765,6 +766,9 @@ __global__ __launch_bounds__(kThreads) void apply_gram_kernel(double* __restrict
   const int rows_per = kThreads / b;
   const int t = threadIdx.x % b, rl = threadIdx.x / b;
   const int64_t ngroups = (n + rows_per - 1) / rows_per;
+  const int bb = b * b;
+  const int ns = bb >= kThreads ? 1 : kThreads / bb;  // row subsets per entry (b <= 8)
+  const int ent = threadIdx.x % bb, sub = threadIdx.x / bb;  // used when bb <= 256
   double gacc[4] = {0.0, 0.0, 0.0, 0.0};
   for (int64_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
     const int64_t row = grp * rows_per + rl;
@@ -776,10 +780,17 @@ __global__ __launch_bounds__(kThreads) void apply_gram_kernel(double* __restrict
     if (row < n) basis[row * ld + col0 + t] = acc;
     Qt[rl * (b + 1) + t] = row < n ? acc : 0.0;
     __syncthreads();
+    if (bb <= kThreads) {
+      if (sub < ns) {
+        const int c1 = ent / b, c2 = ent % b;
+        double v = gacc[0];
+        for (int r = sub; r < rows_per; r += ns) v += Qt[r * (b + 1) + c1] * Qt[r * (b + 1) + c2];
+        gacc[0] = v;
+      }
+    } else {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int e = threadIdx.x + u * kThreads;
-      if (e < b * b) {
+      for (int u = 0; u < 4; ++u) {
+        const int e = threadIdx.x + u * kThreads;
         const int c1 = e / b, c2 = e % b;
         double v = gacc[u];
         for (int r = 0; r < rows_per; ++r) v += Qt[r * (b + 1) + c1] * Qt[r * (b + 1) + c2];
@@ -787,10 +798,21 @@ __global__ __launch_bounds__(kThreads) void apply_gram_kernel(double* __restrict
       }
     }
   }
+  if (bb <= kThreads) {
+    __syncthreads();
+    Wt[threadIdx.x] = gacc[0];  // [sub][ent]
+    __syncthreads();
+    if (threadIdx.x < bb) {
+      double tot = Wt[threadIdx.x];
+      for (int q = 1; q < ns; ++q) tot += Wt[q * bb + threadIdx.x];
+      gpart[((int64_t)blockIdx.x * b + threadIdx.x / b) * kPartialPad + (threadIdx.x % b)] = tot;
+    }
+  } else {
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int e = threadIdx.x + u * kThreads;
-    if (e < b * b) gpart[((int64_t)blockIdx.x * b + e / b) * kPartialPad + (e % b)] = gacc[u];
+    for (int u = 0; u < 4; ++u) {
+      const int e = threadIdx.x + u * kThreads;
+      gpart[((int64_t)blockIdx.x * b + e / b) * kPartialPad + (e % b)] = gacc[u];
+    }
   }
 }
 
