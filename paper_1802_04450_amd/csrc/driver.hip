@@ -162,33 +162,43 @@ int pow2_floor(int x) {
 }
 
 // CGS2 of basis[:, wcol : wcol+b] against basis[:, 0 : j]; hsum (j x b, stride kPP) = H1 + H2.
+// The second pass runs against columns [second_from, j) only (0 = all of them, the plain CGS2).  The solver
+// passes the number of locked vectors here: the block's components along locked eigenvectors are of the order of
+// their residuals, so removing them once involves no cancellation, whereas the active Krylov vectors, which take
+// most of the block's norm away, get the second pass.
 // slot_a (may be null) receives rows [slot_row0, j) of hsum.  If gpart != null the second update also leaves
 // the Gram partials of the updated block there; returns their count (0 if none were produced).
-int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, double* part, double* h1, double* hsum,
-                 double* slot_a, int slot_row0, double* gpart, hipStream_t st, KTimer* tm) {
+int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, int second_from, double* part,
+                 double* h1, double* hsum, double* slot_a, int slot_row0, double* gpart, hipStream_t st, KTimer* tm) {
   if (j <= 0) return 0;
-  const ProjectPlan plan = plan_project(n, j, kMaxPartials);
   KTimer none;
   if (!tm) tm = &none;
-  // algorithmic traffic of one pass over the basis: every row reads its j basis entries and its b block
+  // algorithmic traffic of one pass over the basis: every row reads its basis entries and its b block
   // entries once (the update also writes the b block entries back)
   const double rows = (double)n;
   int ngram = 0;
   for (int pass = 0; pass < 2; ++pass) {
+    const int c0 = pass == 0 ? 0 : second_from;  // first basis column of this pass
+    const int jc = j - c0;
+    if (jc <= 0) {  // nothing to do in this pass: the Gram partials then come from the block QR itself
+      continue;
+    }
+    const ProjectPlan plan = plan_project(n, jc, kMaxPartials);
     tm->begin(kFamProject);
-    HIP_TRY(launch_project(basis, n, ld, 0, j, wcol, b, plan, part, st));
-    tm->end(kFamProject, 8.0 * rows * (j + b), 2.0 * rows * j * b);
+    HIP_TRY(launch_project(basis, n, ld, c0, jc, wcol, b, plan, part, st));
+    tm->end(kFamProject, 8.0 * rows * (jc + b), 2.0 * rows * jc * b);
     tm->begin(kFamOther);
-    HIP_TRY(launch_reduce_partials(part, plan.npart, j, b, h1, hsum, pass, pass == 1 ? slot_a : nullptr, slot_row0, st));
-    tm->end(kFamOther, 8.0 * plan.npart * (double)j * b, 0.0);
+    HIP_TRY(launch_reduce_partials(part, plan.npart, jc, b, h1, hsum + (size_t)c0 * kPP, pass,
+                                   pass == 1 ? slot_a : nullptr, slot_row0 - c0, st));
+    tm->end(kFamOther, 8.0 * plan.npart * (double)jc * b, 0.0);
     tm->begin(kFamUpdate);
     if (pass == 1 && gpart) {
-      HIP_TRY(launch_update_gram(basis, n, ld, j, h1, b, wcol, gpart, st));
+      HIP_TRY(launch_update_gram(basis, n, ld, c0, jc, h1, b, wcol, gpart, st));
       ngram = plan_update_gram(n);
     } else {
-      HIP_TRY(launch_row_gemm(basis, n, ld, 0, j, h1, kPP, b, 0, wcol, nullptr, 0, nullptr, st));
+      HIP_TRY(launch_row_gemm(basis, n, ld, c0, jc, h1, kPP, b, 0, wcol, nullptr, 0, nullptr, st));
     }
-    tm->end(kFamUpdate, 8.0 * rows * (j + 2 * b), 2.0 * rows * j * b);
+    tm->end(kFamUpdate, 8.0 * rows * (jc + 2 * b), 2.0 * rows * jc * b);
   }
   return ngram;
 }
@@ -404,7 +414,7 @@ struct Solver {
     timer.end(kFamSpmm, 12.0 * (double)nnz + 8.0 * (double)(n + 1) + 8.0 * (double)n + 16.0 * (double)n * b,
               2.0 * (double)nnz * b);
     double* sl = slot(si);
-    const int ngram = enqueue_cgs2(basis.p, n, ld, jt, jt, b, part.p, h1.p, hsum.p, sl, jt - b, gpart.p, st, &timer);
+    const int ngram = enqueue_cgs2(basis.p, n, ld, jt, jt, b, nl, part.p, h1.p, hsum.p, sl, jt - b, gpart.p, st, &timer);
     enqueue_block_qr(basis.p, n, ld, jt, b, part.p, gpart.p, ngram, gram(), rinv(), r1(), sl + kPP * kPP,
                      sl + 2 * kPP * kPP, z.p, s.p, st, &timer);
     stats.block_steps += 1;
@@ -484,7 +494,7 @@ struct Solver {
 
       // ---- start block
       HIP_TRY(launch_random_block(basis.p, n, ld, nl, b, seed, stream_id++, st));
-      const int ngram0 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
+      const int ngram0 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
       enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram0, gram(), rinv(), r1(), slot(0) + kPP * kPP,
                        slot(0) + 2 * kPP * kPP, z.p, s.p, st, &timer);
       int ja = b;            // active columns whose coupling is (or will be) assembled
@@ -1022,7 +1032,7 @@ int sc_cgs2(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, double* 
         gpart.alloc((size_t)kGramPartials * kPP * kPP);
         gram.alloc((size_t)kPP * kPP);
         const int ngram =
-            enqueue_cgs2(c->basis, c->n, c->ld, c->j, c->j, c->b, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, c->st, nullptr);
+            enqueue_cgs2(c->basis, c->n, c->ld, c->j, c->j, c->b, 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, c->st, nullptr);
         const size_t w = (size_t)c->b * sizeof(double);
         if (c->h)
           HIP_TRY(hipMemcpy2DAsync(c->h, w, hsum.p, (size_t)kPP * sizeof(double), w, (size_t)c->j,

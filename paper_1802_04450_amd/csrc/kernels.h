@@ -67,14 +67,15 @@ hipError_t launch_apply_rinv(double* basis, int64_t n, int64_t ld, int col0, int
                              const double* s, hipStream_t st);
 
 // Fused variants used inside the block step (same arithmetic as the separate kernels):
-//   update_gram: basis[:, ccol0 : ccol0+b] -= basis[:, 0 : kdim] * bmat (bmat kdim x b, row stride kPartialPad) and
+//   update_gram: basis[:, ccol0 : ccol0+b] -= basis[:, acol0 : acol0+kdim] * bmat (bmat kdim x b, row stride
+//                kPartialPad) and
 //                gpart[p] (b x b, row stride kPartialPad, p < plan_update_gram(n)) = partial Gram matrices of the
 //                updated block, to be summed with launch_reduce_partials(gpart, npart, b, b, ...).
 //   apply_gram:  basis[:, col0 : col0+b] *= rinv and gpart[p], p < plan_apply_gram(n, b), partial Gram matrices of
 //                the result.
 int plan_update_gram(int64_t n);
-hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int kdim, const double* bmat, int b, int ccol0,
-                              double* gpart, hipStream_t st);
+hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int b,
+                              int ccol0, double* gpart, hipStream_t st);
 int plan_apply_gram(int64_t n, int b);
 hipError_t launch_apply_gram(double* basis, int64_t n, int64_t ld, int col0, int b, const double* rinv, double* gpart,
                              hipStream_t st);

@@ -608,7 +608,7 @@ __global__ __launch_bounds__(kThreads) void copy_cols_kernel(const double* __res
 // Workgroups walk the 128-row tiles with a grid stride, so the number of Gram partials is the grid size.
 template <int NT>
 __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
-                                                               int kdim, const double* __restrict__ bmat, int b,
+                                                               int acol0, int kdim, const double* __restrict__ bmat, int b,
                                                                int ccol0, int vec_ok, double* __restrict__ gpart) {
   constexpr int MT = 2;
   constexpr int BW = NT * 16;
@@ -669,7 +669,7 @@ __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restric
   #pragma unroll
             for (int q = 0; q < 4; ++q) a[h][mt][q] = 0.0;
             if (row < n && kk + 16 * h < kc16) {
-              const double* ap = basis + row * ld + kcol;
+              const double* ap = basis + row * ld + acol0 + kcol;
               if (vec_ok && kcol + 3 < kdim) {
                 const d4 v = *reinterpret_cast<const d4*>(ap);
                 a[h][mt][0] = v[0]; a[h][mt][1] = v[1]; a[h][mt][2] = v[2]; a[h][mt][3] = v[3];
@@ -1107,16 +1107,16 @@ int plan_update_gram(int64_t n) {
   return (int)(ntiles < 1024 ? ntiles : 1024);
 }
 
-hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int kdim, const double* bmat, int b, int ccol0,
-                              double* gpart, hipStream_t st) {
-  const int vec_ok = (ld % 4 == 0 && (reinterpret_cast<uintptr_t>(basis) % 32 == 0)) ? 1 : 0;
+hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int b,
+                              int ccol0, double* gpart, hipStream_t st) {
+  const int vec_ok = (ld % 4 == 0 && acol0 % 4 == 0 && (reinterpret_cast<uintptr_t>(basis) % 32 == 0)) ? 1 : 0;
   const unsigned grid = (unsigned)plan_update_gram(n);
   if (b <= 16) {
-    hipLaunchKernelGGL((update_gram_kernel<1>), dim3(grid), dim3(kThreads), 0, st, basis, n, ld, kdim, bmat, b, ccol0,
-                       vec_ok, gpart);
+    hipLaunchKernelGGL((update_gram_kernel<1>), dim3(grid), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, bmat, b,
+                       ccol0, vec_ok, gpart);
   } else {
-    hipLaunchKernelGGL((update_gram_kernel<2>), dim3(grid), dim3(kThreads), 0, st, basis, n, ld, kdim, bmat, b, ccol0,
-                       vec_ok, gpart);
+    hipLaunchKernelGGL((update_gram_kernel<2>), dim3(grid), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, bmat, b,
+                       ccol0, vec_ok, gpart);
   }
   return hipGetLastError();
 }
