@@ -745,13 +745,15 @@ struct Solver {
         stats.spmv_cols += w;
       }
       const double te0 = now_s();
-      std::vector<double> th(nx), Yx((size_t)nx * nx);
-      if (sym_eig(G.data(), nx, th.data(), Yx.data()) != 0) SC_THROW(SC_EHIP);
+      SelectedEig rr;
+      if (rr.factor(G.data(), nx) != 0) SC_THROW(SC_EHIP);
+      const std::vector<double>& th = rr.values();
+      std::vector<int> idx(nfound);
+      for (int t = 0; t < nfound; ++t) idx[t] = nx - 1 - t;
+      std::vector<double> yk((size_t)nx * nfound);  // column t = Ritz vector of the t-th largest theta
+      rr.vectors(idx.data(), nfound, yk.data());
       stats.t_host_eig += now_s() - te0;
       stats.host_eigs += 1;
-      std::vector<double> yk((size_t)nx * nfound);
-      for (int r = 0; r < nx; ++r)
-        for (int t = 0; t < nfound; ++t) yk[(size_t)r * nfound + t] = Yx[(size_t)r * nx + (nx - 1 - t)];
       for (int t = 0; t < nfound; ++t) evals_host[t] = 1.0 - th[nx - 1 - t];
       if ((size_t)nx * nfound > yd_cap) SC_THROW(SC_EDOMAIN);
       HIP_TRY(hipMemcpyAsync(yd.p, yk.data(), yk.size() * sizeof(double), hipMemcpyHostToDevice, st));

@@ -13,11 +13,13 @@
 #include <numeric>
 #include <vector>
 
+#include <omp.h>
+
 namespace sceig {
 
 namespace {
 
-constexpr int kParallelMin = 160;  // below this size the OpenMP fork/join costs more than it saves
+constexpr int kParallelMin = 256;  // below this size the OpenMP fork/join costs more than it saves
 
 // Reduce the symmetric matrix held in q (row-major n x n, full storage) to tridiagonal form
 // (diagonal d, sub-diagonal e with e[i] coupling i and i+1) and overwrite q with the orthogonal
@@ -26,7 +28,7 @@ void tridiagonalize(int n, std::vector<double>& q, std::vector<double>& d, std::
                     std::vector<double>& vs, std::vector<double>& betas, bool form_q) {
   vs.assign((size_t)n * n, 0.0);  // Householder vectors, vector k in row k (entries k+1..n-1)
   betas.assign(n, 0.0);
-  std::vector<double> p(n), w(n);
+  std::vector<double> p(n), w(n), scatter;
   double* a = q.data();
   for (int k = 0; k + 2 < n; ++k) {
     // x = A[k+1:n, k]
@@ -53,15 +55,31 @@ void tridiagonalize(int n, std::vector<double>& q, std::vector<double>& d, std::
     const int lo = k + 1;
     const int len = n - lo;
     if (len >= kParallelMin) {
-#pragma omp parallel for schedule(static)
-      for (int i = lo; i < n; ++i) {
-        // row i of the symmetric block: left of the diagonal from row i, below the diagonal from column i
-        const double* row = a + (size_t)i * n;
-        double s = 0.0;
+      // rows are dealt out cyclically in chunks (a fixed assignment, so the result does not depend on timing);
+      // every thread scatters into a buffer of its own and the buffers are added in thread order
+      const int nth = omp_get_max_threads();
+      if ((int)scatter.size() < nth * n) scatter.resize((size_t)nth * n);
+#pragma omp parallel num_threads(nth)
+      {
+        double* pp = scatter.data() + (size_t)omp_get_thread_num() * n;
+        for (int j = lo; j < n; ++j) pp[j] = 0.0;
+#pragma omp for schedule(static, 8)
+        for (int i = lo; i < n; ++i) {
+          const double* row = a + (size_t)i * n;
+          const double vi = v[i];
+          double s = 0.0;
 #pragma omp simd reduction(+ : s)
-        for (int j = lo; j <= i; ++j) s += row[j] * v[j];
-        for (int j = i + 1; j < n; ++j) s += a[(size_t)j * n + i] * v[j];
-        p[i] = beta * s;
+          for (int j = lo; j < i; ++j) {
+            s += row[j] * v[j];
+            pp[j] += row[j] * vi;
+          }
+          pp[i] += s + row[i] * vi;
+        }
+      }
+      for (int j = lo; j < n; ++j) {
+        double tot = 0.0;
+        for (int t = 0; t < nth; ++t) tot += scatter[(size_t)t * n + j];
+        p[j] = beta * tot;
       }
     } else {
       for (int i = lo; i < n; ++i) p[i] = 0.0;
@@ -83,7 +101,7 @@ void tridiagonalize(int n, std::vector<double>& q, std::vector<double>& d, std::
     for (int i = lo; i < n; ++i) pv += p[i] * v[i];
     const double half = 0.5 * beta * pv;
     for (int i = lo; i < n; ++i) w[i] = p[i] - half * v[i];
-#pragma omp parallel for schedule(static) if (len >= kParallelMin)
+#pragma omp parallel for schedule(static, 8) if (len >= kParallelMin)
     for (int i = lo; i < n; ++i) {
       double* row = a + (size_t)i * n;
       const double vi = v[i], wi = w[i];
@@ -260,35 +278,42 @@ void SelectedEig::vectors(const int* idx, int count, double* out) const {
   if (n <= 0 || count <= 0) return;
   std::fill(out, out + (size_t)n * count, 0.0);
   for (int t = 0; t < count; ++t) out[(size_t)order_[idx[t]] * count + t] = 1.0;
-  // eigenvectors of the tridiagonal matrix: Z e_j = G_1 (G_2 (... (G_N e_j))), so replay backwards
-  for (size_t r = rots_.size(); r-- > 0;) {
-    const Rot& g = rots_[r];
-    double* a = out + (size_t)g.i * count;
-    double* b = a + count;
-    const double c = g.c, s = g.s;
+  // eigenvectors of the tridiagonal matrix: Z e_j = G_1 (G_2 (... (G_N e_j))), so replay backwards; then back
+  // through the reflectors: Y = H_0 H_1 ... H_{n-3} Z.  Columns are independent: slices of them go to threads.
+  const int slices = (count >= 64 && (long)n * count >= 200000) ? std::min(omp_get_max_threads(), count / 16) : 1;
+#pragma omp parallel for schedule(static) num_threads(slices) if (slices > 1)
+  for (int sl = 0; sl < slices; ++sl) {
+    const int t0 = (int)((long)count * sl / slices), t1 = (int)((long)count * (sl + 1) / slices);
+    for (size_t r = rots_.size(); r-- > 0;) {
+      const Rot& g = rots_[r];
+      double* a = out + (size_t)g.i * count;
+      double* b = a + count;
+      const double c = g.c, s = g.s;
 #pragma omp simd
-    for (int t = 0; t < count; ++t) {
-      const double x = a[t], y = b[t];
-      a[t] = c * x + s * y;
-      b[t] = c * y - s * x;
+      for (int t = t0; t < t1; ++t) {
+        const double x = a[t], y = b[t];
+        a[t] = c * x + s * y;
+        b[t] = c * y - s * x;
+      }
     }
-  }
-  // back through the reflectors: Y = H_0 H_1 ... H_{n-3} Z
-  std::vector<double> tmp(count);
-  for (int k = n - 3; k >= 0; --k) {
-    const double beta = betas_[k];
-    if (beta == 0.0) continue;
-    const double* v = &vs_[(size_t)k * n];
-    std::fill(tmp.begin(), tmp.end(), 0.0);
-    for (int i = k + 1; i < n; ++i) {
-      const double vi = v[i];
-      const double* row = out + (size_t)i * count;
-      for (int t = 0; t < count; ++t) tmp[t] += vi * row[t];
-    }
-    for (int i = k + 1; i < n; ++i) {
-      const double bv = beta * v[i];
-      double* row = out + (size_t)i * count;
-      for (int t = 0; t < count; ++t) row[t] -= bv * tmp[t];
+    std::vector<double> tmp(count);
+    for (int k = n - 3; k >= 0; --k) {
+      const double beta = betas_[k];
+      if (beta == 0.0) continue;
+      const double* v = &vs_[(size_t)k * n];
+      for (int t = t0; t < t1; ++t) tmp[t] = 0.0;
+      for (int i = k + 1; i < n; ++i) {
+        const double vi = v[i];
+        const double* row = out + (size_t)i * count;
+#pragma omp simd
+        for (int t = t0; t < t1; ++t) tmp[t] += vi * row[t];
+      }
+      for (int i = k + 1; i < n; ++i) {
+        const double bv = beta * v[i];
+        double* row = out + (size_t)i * count;
+#pragma omp simd
+        for (int t = t0; t < t1; ++t) row[t] -= bv * tmp[t];
+      }
     }
   }
 }
