@@ -114,7 +114,8 @@ typedef struct sc_stats {
  * Method: block Lanczos with full reorthogonalization (classical Gram-Schmidt applied twice against
  * all locked and active basis vectors), thick restart, locking, and re-injection of a fresh random
  * block after every lock so that multiple eigenvalues are found with their multiplicity; once k pairs
- * are locked one further deflated phase must find nothing better (skipped under SC_FLAG_NO_VERIFY);
+ * are locked one further deflated phase must find nothing better (skipped under SC_FLAG_NO_VERIFY, and when
+ * the k-th locked theta is already within tol of 1, the largest value the spectrum of S can reach for W >= 0);
  * a final Rayleigh-Ritz step over the locked vectors produces the outputs.  Only the projected
  * eigenproblems (size <= m) run on the host.
  *

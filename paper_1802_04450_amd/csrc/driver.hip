@@ -252,6 +252,7 @@ int reorder_csr(const int64_t* rowptr, const int32_t* col, const double* val, in
     HIP_TRY(launch_cc_round(rowptr, col, val, label.p, n, flag.p, st));
     HIP_TRY(hipMemcpyAsync(&h, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
+    if (debug_on() && (round % 50 == 49)) std::fprintf(stderr, "[sceig] component pass: %d rounds\n", 2 * (round + 1));
     if (!h) break;
   }
   std::vector<int32_t> lab((size_t)n), new_of_old((size_t)n), old_of_new((size_t)n);
@@ -404,6 +405,8 @@ struct Solver {
     if ((flags & SC_FLAG_COMPONENT_NULLSPACE) && !(flags & SC_FLAG_NO_REORDER)) lock_component_nullspace();
     stats.components = ncomp;
     stats.t_setup = now_s() - t0;
+    if (debug_on()) std::fprintf(stderr, "[sceig] setup %.3fs: n=%lld nnz=%lld components=%d m=%d b=%d locked=%d\n",
+                                 stats.t_setup, (long long)n, (long long)nnz, ncomp, m, b, nl);
   }
 
   // ---- one block step on the last active block (columns [nl+ja-b, nl+ja)), results into slot si
@@ -482,6 +485,9 @@ struct Solver {
     while (!finished) {
       const bool verifying = nl >= k;
       if (verifying && (flags & SC_FLAG_NO_VERIFY)) break;
+      // W >= 0 makes D^-1 W row-stochastic, so no eigenvalue of S exceeds 1: once the k-th locked theta is within
+      // tol of 1 a check phase could not find anything better by more than tol
+      if (verifying && kth_locked_theta() + tol >= 1.0) break;
       if ((int64_t)nl >= n) break;
       const bool last_cycle_phase = cycles >= maxiter;  // out of budget: only build enough Ritz vectors to answer
       if (last_cycle_phase && verifying) {
@@ -722,6 +728,7 @@ struct Solver {
 
     // ---- Rayleigh-Ritz over the locked vectors (the Ritz-vector step of Algorithm 3)
     const int nx = nl;
+    if (debug_on()) std::fprintf(stderr, "[sceig] t=%.2fs Rayleigh-Ritz over %d locked vectors\n", now_s() - t_begin, nx);
     std::vector<double> evals_host(k, std::numeric_limits<double>::quiet_NaN());
     HIP_TRY(hipMemsetAsync(evecs_out, 0, (size_t)n * k * sizeof(double), st));
     int nfound = std::min(nx, k);
@@ -762,6 +769,7 @@ struct Solver {
     }
     HIP_TRY(hipMemcpyAsync(evals_out, evals_host.data(), (size_t)k * sizeof(double), hipMemcpyHostToDevice, st));
     HIP_TRY(hipStreamSynchronize(st));
+    if (debug_on()) std::fprintf(stderr, "[sceig] t=%.2fs outputs written\n", now_s() - t_begin);
 
     int nconv = 0;
     double maxr = 0.0;
