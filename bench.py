@@ -32,6 +32,27 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+# kernel-name prefix of each timed family in the committed rocprofv3 traffic summary (sorted by total time, so the
+# first match is the family's dominant kernel)
+TRAFFIC_PREFIX = ["spmm_", "project_kernel", ("row_gemm_kernel", "update_gram_kernel"), "row_gemm_kernel",
+                  ("apply_gram_kernel", "apply_rinv_kernel", "chol_reg_kernel"), "reduce_partials_kernel"]
+
+
+def profiled_traffic(workload: str, family: int):
+    """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by the plain-copy calibration) of the family's dominant
+    kernel, from the rocprofv3 counter summary committed for this workload; None when there is none."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_bench_traffic.txt")
+    if not os.path.exists(path):
+        return None, None
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, fetch, write, _avg = line.rsplit(None, 3)
+        if name.startswith(TRAFFIC_PREFIX[family]):
+            return float(fetch) + float(write), name
+    return None, None
+
+
 def build_workload(name: str):
     from paper_1802_04450_amd import workloads as wl
     cid = int(name.replace("cfg", ""))
@@ -167,9 +188,10 @@ def main():
     if kt > 0:
         launches = stats["fam_launches"][dom]
         ach = stats["fam_bytes"][dom] / kt / 1e9
+        traffic, traffic_kernel = profiled_traffic(args.workload, dom) if args.block == 0 else (None, None)
         out["roofline"] = {"bound": "hbm", "kernel": KERNEL_OF_FAMILY[dom],
                            "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                           "traffic": None, "launches_per_step": launches,
+                           "traffic": traffic, "traffic_kernel": traffic_kernel, "launches_per_step": launches,
                            "avg_launch_us": kt / max(1, launches) * 1e6,
                            "algorithmic_bytes_per_launch": stats["fam_bytes"][dom] / max(1, launches),
                            "fp64_tflops": stats["fam_flops"][dom] / kt / 1e12,
