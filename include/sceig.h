@@ -51,6 +51,9 @@ extern "C" {
                                  connected components (vol as in the Ncut definition of Section II) before the first
                                  Lanczos phase; off by default; ignored under SC_FLAG_NO_REORDER */
 
+#define SC_FLAG_NO_START_FILTER 8u /* start every phase from the plain random block: no polynomial filtering of the
+                                 re-injection blocks (see sc_laplacian_eigsh) */
+
 /* Options; every field 0 = default. */
 typedef struct sc_options {
   int32_t m;      /* budget of basis columns (locked + active Krylov vectors), the "number m of Lanczos
@@ -83,7 +86,7 @@ typedef struct sc_stats {
   int32_t m;          /* basis budget used */
   int32_t host_eigs;  /* projected eigenproblems solved on the host */
   int32_t components; /* connected components found by the setup pass (0 under SC_FLAG_NO_REORDER) */
-  int32_t reserved;
+  int32_t filter_steps; /* block products spent on Chebyshev filtering of start blocks (counted in spmv_cols too) */
   int64_t block_steps;
   int64_t spmv_cols;  /* columns multiplied by S in total */
   double t_total;     /* seconds, whole call */
@@ -111,8 +114,9 @@ typedef struct sc_stats {
  *                                 (v = D^1/2 u for the eigenvectors u of the paper's D^-1 L)
  *   opt, stats                    host, may be NULL
  *
- * Method: block Lanczos with full reorthogonalization (classical Gram-Schmidt applied twice against
- * all locked and active basis vectors), thick restart, locking, and re-injection of a fresh random
+ * Method: block Lanczos with full reorthogonalization (classical Gram-Schmidt, first pass against all
+ * locked and active basis vectors, second pass against the active Krylov vectors; a phase's random start
+ * block gets both passes against everything), thick restart, locking, and re-injection of a fresh random
  * block after every lock so that multiple eigenvalues are found with their multiplicity; once k pairs
  * are locked one further deflated phase must find nothing better (skipped under SC_FLAG_NO_VERIFY, and when
  * the k-th locked theta is already within tol of 1, the largest value the spectrum of S can reach for W >= 0);
@@ -139,8 +143,8 @@ int sc_degree_scaling(const int64_t* csr_rowptr, const int32_t* csr_col, const d
  *   s     device fp64[n] (from sc_degree_scaling)
  *   x     device, row-major n x ncols, leading dimension ldx >= ncols
  *   y     device, row-major n x ncols, leading dimension ldy >= ncols; must not alias x
- *   work  device fp64[n*ncols] scratch (holds diag(s) X packed); may be NULL, then it is allocated
- *         and freed inside the call
+ *   work  device fp64[n*ncols] scratch (holds diag(s) X packed), 16-byte aligned (else SC_EINVAL); may be NULL,
+ *         then it is allocated and freed inside the call
  * Exception to the general rule: when `work` is given this call only ENQUEUES on `stream` and returns without
  * synchronising (products can be issued back to back); with work == NULL it returns after completion.
  * CSR columns are NOT range-checked here (sc_validate_csr does that).

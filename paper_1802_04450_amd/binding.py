@@ -19,6 +19,7 @@ SC_EINVAL, SC_EDOMAIN, SC_ECSR, SC_EZERODEG, SC_ENOMEM, SC_EHIP = -1, -2, -3, -4
 SC_FLAG_NO_VERIFY = 1
 SC_FLAG_NO_REORDER = 2
 SC_FLAG_COMPONENT_NULLSPACE = 4
+SC_FLAG_NO_START_FILTER = 8
 FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 
 EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_reorder_csr", "sc_cgs2",
@@ -34,7 +35,7 @@ class ScOptions(ctypes.Structure):
 class ScStats(ctypes.Structure):
     _fields_ = [("nconv", ctypes.c_int32), ("phases", ctypes.c_int32), ("restarts", ctypes.c_int32),
                 ("block", ctypes.c_int32), ("m", ctypes.c_int32), ("host_eigs", ctypes.c_int32),
-                ("components", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("components", ctypes.c_int32), ("filter_steps", ctypes.c_int32),
                 ("block_steps", ctypes.c_int64), ("spmv_cols", ctypes.c_int64), ("t_total", ctypes.c_double),
                 ("t_host_eig", ctypes.c_double), ("t_setup", ctypes.c_double), ("max_residual_est", ctypes.c_double),
                 ("fam_time_s", ctypes.c_double * 6), ("fam_bytes", ctypes.c_double * 6),

@@ -319,6 +319,10 @@ struct Solver {
   // state
   int nl = 0;
   std::vector<double> theta_locked, rho_locked;
+  // Chebyshev filter of the next phase's start block: degree (0 = none) and upper end of the damped interval
+  int filt_d = 0;
+  double filt_a = 0.0;
+  double filt_best = -2.0;  // best lower estimate so far of the largest eigenvalue below the locked cluster
   sc_stats stats{};
   KTimer timer;
 
@@ -431,6 +435,74 @@ struct Solver {
     HIP_TRY(hipStreamSynchronize(st));
   }
 
+  // Start-block filter.  The block at columns [nl, nl+b) (orthonormal, its s-scaled packed copy in z) is replaced
+  // by p(S) applied to it, p = Chebyshev polynomial of degree d of the interval [-1, a] mapped to [-1, 1]: what lies
+  // in [-1, a] stays bounded by 1, what lies above a grows like cosh(d acosh(x)).  Only products and a three-term
+  // recurrence: no reorthogonalization.  The caller orthogonalizes and orthonormalizes the result again.
+  void apply_start_filter(int d, double a) {
+    const double lo = -1.0;  // ||S||_2 = 1
+    const double c = 0.5 * (a + lo), e = 0.5 * (a - lo);
+    double* ycur = rot.p;
+    double* yprev = rot.p + (size_t)n * b;
+    double* w = rot.p + 2 * (size_t)n * b;
+    HIP_TRY(launch_copy_cols(basis.p, ld, nl, ycur, b, 0, b, n, st));
+    for (int i = 0; i < d; ++i) {
+      timer.begin(kFamSpmm);
+      HIP_TRY(launch_spmm(rowptr, col, val, s.p, n, z.p, b, w, b, avg_deg, st));
+      timer.end(kFamSpmm, 12.0 * (double)nnz + 8.0 * (double)(n + 1) + 8.0 * (double)n + 16.0 * (double)n * b,
+                2.0 * (double)nnz * b);
+      if (i == 0) {
+        HIP_TRY(launch_cheb_combine(w, ycur, ycur, s.p, 1.0 / e, c, 0.0, yprev, z.p, n, b, st));
+      } else {
+        HIP_TRY(launch_cheb_combine(w, ycur, yprev, s.p, 2.0 / e, c, 1.0, yprev, z.p, n, b, st));
+      }
+      std::swap(ycur, yprev);
+      stats.spmv_cols += b;
+      stats.filter_steps += 1;
+    }
+    HIP_TRY(launch_copy_cols(ycur, b, 0, basis.p, ld, nl, b, n, st));
+  }
+
+  // Decide the filter of the next phase from the Ritz values (ascending, ghosts at the bottom) of the phase that
+  // just locked its `nlock` leading pairs.  Further copies of the locked eigenvalues may remain (a block Krylov
+  // space holds at most b of them), so the polynomial is made large at the smallest value just locked and small
+  // below an estimate `a` of what follows: the largest unlocked Ritz value when a gap separates it from the locked
+  // ones (it approaches the next distinct eigenvalue from below; the best estimate over the phases is kept),
+  // otherwise the (b+1)-th unlocked one, below the b values the next phase is after.  A filter that is not worth
+  // its products (amplification below 100 at the degree cap) is left out; a wrong guess costs convergence speed,
+  // never correctness: the Lanczos phase that follows converges by its own residual test.
+  void plan_start_filter(const std::vector<double>& theta, int ja, int nlock, int nghost) {
+    filt_d = 0;
+    if (flags & SC_FLAG_NO_START_FILTER) return;
+    if (rot_cols < (size_t)3 * b) return;
+    const int nu = ja - nlock - nghost;
+    if (nlock < 1 || nu < 1) return;
+    const double th_min = theta[ja - nlock];
+    const double u1 = theta[ja - 1 - nlock];
+    const double ub = theta[std::max(ja - 1 - nlock - b, nghost)];
+    double a;
+    if (th_min - u1 > u1 - ub) {
+      if (filt_best >= th_min - 1e-6) filt_best = -2.0;  // the wanted values have moved below the old estimate
+      filt_best = std::max(filt_best, u1);
+      a = filt_best;
+    } else {
+      a = ub;
+    }
+    const double lo = -1.0;
+    if (!(a > lo + 0.05) || !(a < th_min)) return;
+    const double xt = (2.0 * th_min - a - lo) / (a - lo);
+    const double rate = std::acosh(xt);
+    static const double amp = [] {
+      const char* e = std::getenv("SCEIG_FILTER_AMP");
+      return e ? std::atof(e) : 1e7;
+    }();
+    const int dmax = 30;
+    if (!(rate > 0.0) || std::cosh(dmax * rate) < 100.0) return;
+    const int d = (int)std::ceil(std::log(2.0 * amp) / rate);
+    filt_d = std::min(std::max(d, 2), dmax);
+    filt_a = a;
+  }
+
   // out (n x l row-major in rot) = basis[:, nl : nl+ja] * Y[:, sel]; then copied to basis[:, dst : dst+l]
   void rotate_into(int ja, const std::vector<double>& ymat, int ycols, const std::vector<int>& sel, int dst) {
     const int l = (int)sel.size();
@@ -474,7 +546,7 @@ struct Solver {
     int cycles = 0;
     bool not_converged = false;
     bool finished = false;
-    int prev_phase_steps = 0;
+    int prev_phase_steps = 0, prev_filtered_steps = 0;
     uint64_t stream_id = 0;
 
     std::vector<double> T, Tsub, Y;
@@ -503,6 +575,17 @@ struct Solver {
       const int ngram0 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
       enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram0, gram(), rinv(), r1(), slot(0) + kPP * kPP,
                        slot(0) + 2 * kPP * kPP, z.p, s.p, st, &timer);
+      bool filtered = filt_d > 0;
+      if (filtered) {
+        if (debug_on())
+          std::fprintf(stderr, "[sceig] t=%.4fs phase %d start block filtered: degree %d, damped interval [-1, %.6f]\n",
+                       now_s() - t_begin, stats.phases, filt_d, filt_a);
+        apply_start_filter(filt_d, filt_a);
+        const int ngram1 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
+        enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram1, gram(), rinv(), r1(), slot(0) + kPP * kPP,
+                         slot(0) + 2 * kPP * kPP, z.p, s.p, st, &timer);
+        filt_d = 0;
+      }
       int ja = b;            // active columns whose coupling is (or will be) assembled
       int assembled = 0;     // active columns of T that are final (their block has been multiplied by S)
       int next_slot = 1;     // slot 0 = start block QR
@@ -512,7 +595,8 @@ struct Solver {
       ghost.assign((size_t)cap + b, 0);
       bool start_block_seen = false;
       int pending = 0;
-      int next_check = prev_phase_steps > 1 ? prev_phase_steps - 1 : 4;
+      const int prev_steps = filtered ? prev_filtered_steps : prev_phase_steps;
+      int next_check = prev_steps > 1 ? prev_steps - 1 : (filtered ? 2 : 4);
       double last_rho = -1.0;
       int last_rho_step = 0;
       bool phase_over = false;
@@ -608,7 +692,7 @@ struct Solver {
         if (debug_on()) {
           const int wi = std::min(want, nsel) - 1;
           std::fprintf(stderr,
-                       "[sceig] t=%.2fs phase %d step %d nl=%d ja=%d cap=%d full=%d lead=%d/%d theta[0]=%.12f rho[0]=%.2e "
+                       "[sceig] t=%.4fs phase %d step %d nl=%d ja=%d cap=%d full=%d lead=%d/%d theta[0]=%.12f rho[0]=%.2e "
                        "theta[w]=%.12f rho[w]=%.2e\n",
                        now_s() - t_begin, stats.phases, steps_in_phase, nl, ja, cap, (int)full, lead, want,
                        theta[ja - 1], rho[0], wi >= 0 ? theta[ja - 1 - wi] : 0.0, wi >= 0 ? rho[wi] : 0.0);
@@ -618,6 +702,39 @@ struct Solver {
           finished = true;
           if (nl < k) not_converged = true;
           break;
+        }
+        if (!filtered && !full && !last_cycle_phase && !exhausted && lead < want && steps_in_phase >= 4 && nsel >= b) {
+          // A phase that began from a plain random block (no spectrum estimate was available then): once its Ritz
+          // values give one, filter the leading Ritz vectors - a far better start than a random block - and begin
+          // the phase anew from the filtered block.
+          plan_start_filter(theta, ja, std::min(want, nreal), ja - nreal);
+          if (filt_d > 0) {
+            if (debug_on())
+              std::fprintf(stderr, "[sceig] t=%.4fs phase %d restarts from its %d leading Ritz vectors filtered: degree %d, "
+                           "damped interval [-1, %.6f]\n", now_s() - t_begin, stats.phases, b, filt_d, filt_a);
+            std::vector<int> sel(b);
+            for (int t = 0; t < b; ++t) sel[t] = t;
+            rotate_into(ja, Y, ycols, sel, nl);
+            HIP_TRY(launch_pack_scaled(basis.p + nl, ld, s.p, n, b, z.p, st));
+            apply_start_filter(filt_d, filt_a);
+            const int ngram1 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
+            enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram1, gram(), rinv(), r1(), slot(0) + kPP * kPP,
+                             slot(0) + 2 * kPP * kPP, z.p, s.p, st, &timer);
+            filt_d = 0;
+            filtered = true;
+            ja = b;
+            assembled = 0;
+            next_slot = 1;
+            fetched = 0;
+            steps_in_phase = 0;
+            std::fill(T.begin(), T.end(), 0.0);
+            std::fill(ghost.begin(), ghost.end(), 0);
+            start_block_seen = false;
+            next_check = prev_filtered_steps > 1 ? prev_filtered_steps - 1 : 2;
+            last_rho = -1.0;
+            last_rho_step = 0;
+            continue;
+          }
         }
         const bool stop_now = last_cycle_phase && !verifying;
         if ((lead >= want || exhausted) && !stop_now) {
@@ -648,7 +765,8 @@ struct Solver {
             drop_locked(worst);
           }
           phase_over = true;
-          prev_phase_steps = steps_in_phase;
+          (filtered ? prev_filtered_steps : prev_phase_steps) = steps_in_phase;
+          plan_start_filter(theta, ja, nlock, ja - nreal);
           break;
         }
         if (stop_now || (full && cycles >= maxiter)) {
@@ -728,7 +846,7 @@ struct Solver {
 
     // ---- Rayleigh-Ritz over the locked vectors (the Ritz-vector step of Algorithm 3)
     const int nx = nl;
-    if (debug_on()) std::fprintf(stderr, "[sceig] t=%.2fs Rayleigh-Ritz over %d locked vectors\n", now_s() - t_begin, nx);
+    if (debug_on()) std::fprintf(stderr, "[sceig] t=%.4fs Rayleigh-Ritz over %d locked vectors\n", now_s() - t_begin, nx);
     std::vector<double> evals_host(k, std::numeric_limits<double>::quiet_NaN());
     HIP_TRY(hipMemsetAsync(evecs_out, 0, (size_t)n * k * sizeof(double), st));
     int nfound = std::min(nx, k);
@@ -769,7 +887,7 @@ struct Solver {
     }
     HIP_TRY(hipMemcpyAsync(evals_out, evals_host.data(), (size_t)k * sizeof(double), hipMemcpyHostToDevice, st));
     HIP_TRY(hipStreamSynchronize(st));
-    if (debug_on()) std::fprintf(stderr, "[sceig] t=%.2fs outputs written\n", now_s() - t_begin);
+    if (debug_on()) std::fprintf(stderr, "[sceig] t=%.4fs outputs written\n", now_s() - t_begin);
 
     int nconv = 0;
     double maxr = 0.0;
@@ -976,6 +1094,7 @@ int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const 
                        void* stream) {
   if (!csr_rowptr || !csr_col || !csr_val || !s || !x || !y || n < 0) return SC_EINVAL;
   if (!supported_block(ncols) || ldx < ncols || ldy < ncols) return SC_EDOMAIN;
+  if (reinterpret_cast<uintptr_t>(work) % 16 != 0) return SC_EINVAL;  // the product gathers 16-byte pieces of it
   if (n == 0) return SC_OK;
   struct Ctx {
     const int64_t* rp;

@@ -99,6 +99,10 @@ hipError_t launch_nullspace_fill(double* basis, int64_t n, int64_t ld, int col0,
 hipError_t launch_random_block(double* basis, int64_t n, int64_t ld, int col0, int b, uint64_t seed,
                                uint64_t stream_id, hipStream_t st);
 // dst[i*ldd + dcol0 + t] = src[i*lds + scol0 + t], t < w (regions must not overlap)
+// ynext = alpha (w - shift ycur) - beta yprev and znext = s o ynext on packed n x b blocks (Chebyshev recurrence step)
+hipError_t launch_cheb_combine(const double* w, const double* ycur, const double* yprev, const double* s, double alpha,
+                               double shift, double beta, double* ynext, double* znext, int64_t n, int b,
+                               hipStream_t st);
 hipError_t launch_copy_cols(const double* src, int64_t lds, int scol0, double* dst, int64_t ldd, int dcol0, int w,
                             int64_t n, hipStream_t st);
 

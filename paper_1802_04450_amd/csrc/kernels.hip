@@ -76,45 +76,78 @@ __global__ __launch_bounds__(kThreads) void pack_scaled_kernel(const double* __r
   z[idx] = s[i] * x[i * ldx + t];
 }
 
-// B lanes per row, one lane per column of the block (B = 8, 16, 32).  The B lanes of a row load B
-// consecutive (col, val) pairs at once and broadcast them to each other.
-template <int B>
+// Workgroups are handed to the 8 XCDs (each with an L2 of its own) round-robin by their linear index.  The sparse
+// products gather rows of z that lie near the rows they compute (the solver numbers every connected component
+// contiguously), so each XCD should own one contiguous eighth of the row tiles instead of every eighth tile: then an
+// L2 holds an eighth of z rather than all of it.  The grid must be a multiple of kXcds; tiles past the end are idle.
+constexpr int kXcds = 8;
+__device__ __forceinline__ int64_t xcd_tile() {
+  return (int64_t)(blockIdx.x % kXcds) * (gridDim.x / kXcds) + blockIdx.x / kXcds;
+}
+static inline unsigned xcd_grid(int64_t tiles) { return (unsigned)(ceil_div64(tiles, kXcds) * kXcds); }
+
+// L lanes per row, B = 8, 16, 32 columns.  The L lanes load L consecutive (col, val) pairs of the row at once.  A
+// lane carries TWO adjacent columns of the block, so CL = B/2 lanes cover one entry with 16-byte gathers (the
+// texture addresser spends the same cycles on a 64-lane load whatever its width, and it is the unit this kernel
+// keeps busiest), and the L/CL sub-groups split the batch: sub-group g takes entries g*E ... g*E+E-1, E = CL.  A row
+// of up to L entries is one load -> gather -> sum chain; long rows (hubs of the kNN graph) take deg/L trips.  The
+// sub-group sums are combined in a fixed order by a shuffle tree.
+template <int B, int L>
 __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __restrict__ rowptr,
                                                              const int32_t* __restrict__ col,
                                                              const double* __restrict__ val,
                                                              const double* __restrict__ s,
                                                              const double* __restrict__ z, double* __restrict__ y,
                                                              int64_t ldy, int64_t n) {
-  constexpr int G = kThreads / B;
-  const int t = threadIdx.x % B;
-  const int64_t row = (int64_t)blockIdx.x * G + threadIdx.x / B;
-  if (row >= n) return;  // uniform over the B-lane group
+  constexpr int G = kThreads / L;  // rows per workgroup
+  constexpr int CL = B / 2;        // lanes per entry
+  constexpr int E = CL;            // entries per sub-group and batch: (L / CL) sub-groups * E = L
+  static_assert(L % CL == 0 && (L / CL) * E == L, "batch must split evenly");
+  const int lane = threadIdx.x % L;
+  const int tl = lane % CL;
+  const int sub = (lane / CL) * E;  // first entry of this sub-group inside a batch of L
+  const int64_t row = xcd_tile() * G + threadIdx.x / L;
+  if (row >= n) return;  // uniform over the L-lane group
   const int64_t e1 = rowptr[row + 1];
   double acc0 = 0.0, acc1 = 0.0;
-  for (int64_t e = rowptr[row]; e < e1; e += B) {
+  const double2* __restrict__ z2 = reinterpret_cast<const double2*>(z);
+  for (int64_t e = rowptr[row]; e < e1; e += L) {
     // lanes past the end of the row carry (column 0, value 0): their products vanish
     int32_t c = 0;
     double a = 0.0;
-    if (e + t < e1) {
-      c = col[e + t];
-      a = val[e + t];
+    if (e + lane < e1) {
+      c = col[e + lane];
+      a = val[e + lane];
     }
-    const int cnt = (int)((e1 - e) < (int64_t)B ? (e1 - e) : (int64_t)B);
-    for (int u0 = 0; u0 < cnt; u0 += 8) {  // eight gathers in flight per lane
-      double zv[8];
+    if (e + sub < e1) {  // uniform over the sub-group; the shuffles below only read lanes of this sub-group's entries
+      constexpr int U = E < 8 ? E : 8;  // gathers in flight per lane
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int32_t cu = __shfl(c, u0 + u, B);
-        zv[u] = z[(int64_t)cu * B + t];
-      }
+      for (int u0 = 0; u0 < E; u0 += U) {
+        double2 zv[U];
 #pragma unroll
-      for (int u = 0; u < 8; u += 2) {
-        acc0 += __shfl(a, u0 + u, B) * zv[u];
-        acc1 += __shfl(a, u0 + u + 1, B) * zv[u + 1];
+        for (int u = 0; u < U; ++u) {
+          const int32_t cu = __shfl(c, sub + u0 + u, L);
+          zv[u] = z2[(int64_t)cu * CL + tl];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const double au = __shfl(a, sub + u0 + u, L);
+          acc0 += au * zv[u].x;
+          acc1 += au * zv[u].y;
+        }
       }
     }
   }
-  y[row * ldy + t] = s[row] * (acc0 + acc1);
+#pragma unroll
+  for (int o = L / 2; o >= CL; o >>= 1) {
+    acc0 += __shfl_xor(acc0, o, L);
+    acc1 += __shfl_xor(acc1, o, L);
+  }
+  if (lane < CL) {
+    const double sr = s[row];
+    y[row * ldy + 2 * tl] = sr * acc0;
+    y[row * ldy + 2 * tl + 1] = sr * acc1;
+  }
 }
 
 // L lanes per row, each lane walks the entries of the row with stride L and keeps B accumulators
@@ -168,7 +201,8 @@ __global__ __launch_bounds__(kThreads) void spmm_stream_kernel(const int64_t* __
   constexpr int LR = kThreads / RB;  // lanes per row in the summation
   __shared__ double prod[CH * B];
   __shared__ int64_t rp[RB + 1];
-  const int64_t r0 = (int64_t)blockIdx.x * RB;
+  const int64_t r0 = xcd_tile() * RB;
+  if (r0 >= n) return;  // idle tile of the rounded-up grid (uniform over the workgroup)
   const int nrows = (int)((n - r0) < RB ? (n - r0) : RB);
   if (threadIdx.x <= nrows) rp[threadIdx.x] = rowptr[r0 + threadIdx.x];
   __syncthreads();
@@ -226,10 +260,10 @@ hipError_t launch_spmm_nz(const int64_t* rowptr, const int32_t* col, const doubl
   if (avg_deg >= 6.0) {
     // row-block streaming: 64 rows per workgroup for short rows, 32 otherwise (4 or 8 lanes per row sum)
     if (avg_deg < 24.0) {
-      hipLaunchKernelGGL((spmm_stream_kernel<B, 64>), dim3((unsigned)ceil_div64(n, 64)), dim3(kThreads), 0, st, rowptr,
+      hipLaunchKernelGGL((spmm_stream_kernel<B, 64>), dim3(xcd_grid(ceil_div64(n, 64))), dim3(kThreads), 0, st, rowptr,
                          col, val, s, z, y, ldy, n);
     } else {
-      hipLaunchKernelGGL((spmm_stream_kernel<B, 32>), dim3((unsigned)ceil_div64(n, 32)), dim3(kThreads), 0, st, rowptr,
+      hipLaunchKernelGGL((spmm_stream_kernel<B, 32>), dim3(xcd_grid(ceil_div64(n, 32))), dim3(kThreads), 0, st, rowptr,
                          col, val, s, z, y, ldy, n);
     }
     return hipGetLastError();
@@ -598,6 +632,21 @@ __global__ __launch_bounds__(kThreads) void copy_cols_kernel(const double* __res
   dst[i * ldd + dcol0 + t] = src[i * lds + scol0 + t];
 }
 
+// One step of the three-term Chebyshev recurrence on packed n x b blocks (leading dimension b):
+//   ynext = alpha * (w - shift * ycur) - beta * yprev,   znext = s o ynext   (the packed operand of the next product)
+// ynext may be the buffer of yprev (each element is read before it is written by the same thread).
+__global__ __launch_bounds__(kThreads) void cheb_combine_kernel(const double* __restrict__ w,
+                                                                const double* __restrict__ ycur, const double* yprev,
+                                                                const double* __restrict__ s, double alpha,
+                                                                double shift, double beta, double* ynext,
+                                                                double* __restrict__ znext, int64_t n, int b) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= n * b) return;
+  double v = alpha * (w[idx] - shift * ycur[idx]);
+  if (beta != 0.0) v -= beta * yprev[idx];
+  ynext[idx] = v;
+  znext[idx] = s[idx / b] * v;
+}
 
 // --------------------------------------------------------------------------------------------
 // fused pieces of the block step
@@ -996,24 +1045,50 @@ hipError_t launch_pack_scaled(const double* x, int64_t ldx, const double* s, int
   return hipGetLastError();
 }
 
+// lanes per row of the wide-block product: the smallest power of two that covers an average row in one batch, at
+// most 32 (measured on the kNN workloads: 32 lanes beat 8, 16 and 64 for every block width)
+static int spmm_lanes(int b, double avg_deg) {
+  static const int forced = [] {
+    const char* e = getenv("SCEIG_SPMM_LANES");
+    return e ? atoi(e) : 0;
+  }();
+  int lanes = b;
+  while (lanes < 32 && lanes < avg_deg) lanes *= 2;
+  if (forced >= b && forced <= 64 && (forced & (forced - 1)) == 0) lanes = forced;
+  return lanes;
+}
+
 hipError_t launch_spmm(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
                        const double* z, int b, double* y, int64_t ldy, double avg_deg, hipStream_t st) {
   switch (b) {
     case 1: return launch_spmm_nz<1>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
     case 2: return launch_spmm_nz<2>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
     case 4: return launch_spmm_nz<4>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
+#define SC_LAUNCH_COLS(BB, LL)                                                                                 \
+  hipLaunchKernelGGL((spmm_cols_kernel<BB, LL>), dim3(xcd_grid(ceil_div64(n, kThreads / LL))), dim3(kThreads), \
+                     0, st, rowptr, col, val, s, z, y, ldy, n)
     case 8:
-      hipLaunchKernelGGL((spmm_cols_kernel<8>), dim3((unsigned)ceil_div64(n, kThreads / 8)), dim3(kThreads), 0, st,
-                         rowptr, col, val, s, z, y, ldy, n);
+      switch (spmm_lanes(8, avg_deg)) {
+        case 8: SC_LAUNCH_COLS(8, 8); break;
+        case 16: SC_LAUNCH_COLS(8, 16); break;
+        case 32: SC_LAUNCH_COLS(8, 32); break;
+        default: SC_LAUNCH_COLS(8, 64); break;
+      }
       break;
     case 16:
-      hipLaunchKernelGGL((spmm_cols_kernel<16>), dim3((unsigned)ceil_div64(n, kThreads / 16)), dim3(kThreads), 0, st,
-                         rowptr, col, val, s, z, y, ldy, n);
+      switch (spmm_lanes(16, avg_deg)) {
+        case 16: SC_LAUNCH_COLS(16, 16); break;
+        case 32: SC_LAUNCH_COLS(16, 32); break;
+        default: SC_LAUNCH_COLS(16, 64); break;
+      }
       break;
     case 32:
-      hipLaunchKernelGGL((spmm_cols_kernel<32>), dim3((unsigned)ceil_div64(n, kThreads / 32)), dim3(kThreads), 0, st,
-                         rowptr, col, val, s, z, y, ldy, n);
+      switch (spmm_lanes(32, avg_deg)) {
+        case 32: SC_LAUNCH_COLS(32, 32); break;
+        default: SC_LAUNCH_COLS(32, 64); break;
+      }
       break;
+#undef SC_LAUNCH_COLS
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -1152,6 +1227,14 @@ hipError_t launch_copy_cols(const double* src, int64_t lds, int scol0, double* d
   if (w <= 0) return hipSuccess;
   hipLaunchKernelGGL(copy_cols_kernel, dim3((unsigned)ceil_div64(n * w, kThreads)), dim3(kThreads), 0, st, src, lds,
                      scol0, dst, ldd, dcol0, w, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_cheb_combine(const double* w, const double* ycur, const double* yprev, const double* s, double alpha,
+                               double shift, double beta, double* ynext, double* znext, int64_t n, int b,
+                               hipStream_t st) {
+  hipLaunchKernelGGL(cheb_combine_kernel, dim3((unsigned)ceil_div64(n * b, kThreads)), dim3(kThreads), 0, st, w, ycur,
+                     yprev, s, alpha, shift, beta, ynext, znext, n, b);
   return hipGetLastError();
 }
 
