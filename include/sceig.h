@@ -54,12 +54,15 @@ extern "C" {
 #define SC_FLAG_NO_START_FILTER 8u /* start every phase from the plain random block: no polynomial filtering of the
                                  re-injection blocks (see sc_laplacian_eigsh) */
 
+#define SC_FLAG_FINAL_RR 16u /* always finish with a Rayleigh-Ritz step over the k locked vectors; by default that step
+                                 only runs when some returned pair did not meet tol */
+
 /* Options; every field 0 = default. */
 typedef struct sc_options {
   int32_t m;      /* budget of basis columns (locked + active Krylov vectors), the "number m of Lanczos
                      vectors" of Section IV-B; default min(n, max(2k, k + 56)); needs k + 3*block <= m <= n
                      (the library lowers `block` to fit when block is defaulted) */
-  int32_t block;  /* Lanczos block size b in {1,2,4,8,16,32}; default 8 (n < 300,000), 16, or 32 (k >= 1000),
+  int32_t block;  /* Lanczos block size b in {1,2,4,8,16,32}; default 8 (n < 20,000), 16, or 32 (n >= 300,000 and k >= 1000),
                      lowered to fit k + 3b <= m and b <= next power of two >= k */
   int32_t check_every; /* block steps between convergence checks of the projected problem; default 2 */
   uint32_t flags; /* SC_FLAG_* */
@@ -120,7 +123,8 @@ typedef struct sc_stats {
  * block after every lock so that multiple eigenvalues are found with their multiplicity; once k pairs
  * are locked one further deflated phase must find nothing better (skipped under SC_FLAG_NO_VERIFY, and when
  * the k-th locked theta is already within tol of 1, the largest value the spectrum of S can reach for W >= 0);
- * a final Rayleigh-Ritz step over the locked vectors produces the outputs.  Only the projected
+ * the outputs are the locked Ritz pairs in ascending order of lambda (after a Rayleigh-Ritz step over them when
+ * some pair did not meet tol, or under SC_FLAG_FINAL_RR).  Only the projected
  * eigenproblems (size <= m) run on the host.
  *
  * Returns SC_OK, SC_NOT_CONVERGED, or an error (< 0).

@@ -24,6 +24,7 @@
 #include <cstring>
 #include <limits>
 #include <new>
+#include <numeric>
 #include <vector>
 
 #include "../../include/sceig.h"
@@ -306,7 +307,7 @@ struct Solver {
   DevBuf<double> basis, s, z, part, gpart, h1, hsum, small, slots, yd, rot;
   DevBuf<int> flag;
   DevBuf<int64_t> rowptr_p;
-  DevBuf<int32_t> col_p, old_of_new_d, comp_d;
+  DevBuf<int32_t> col_p, old_of_new_d, comp_d, perm_d;
   DevBuf<double> val_p, coef_d;
   const int32_t* rowmap = nullptr;  // device: original row of each internal row, null if not reordered
   std::vector<int32_t> comp_host;   // component index of each internal row (only after reorder())
@@ -406,6 +407,7 @@ struct Solver {
     rot.alloc((size_t)n * rot_cols);
     yd_cap = (size_t)(m + b) * std::max<size_t>(rot_cols, (size_t)k);
     yd.alloc(yd_cap);
+    perm_d.alloc((size_t)k);
     if ((flags & SC_FLAG_COMPONENT_NULLSPACE) && !(flags & SC_FLAG_NO_REORDER)) lock_component_nullspace();
     stats.components = ncomp;
     stats.t_setup = now_s() - t0;
@@ -442,6 +444,27 @@ struct Solver {
   void apply_start_filter(int d, double a) {
     const double lo = -1.0;  // ||S||_2 = 1
     const double c = 0.5 * (a + lo), e = 0.5 * (a - lo);
+    const double spmm_bytes = 12.0 * (double)nnz + 8.0 * (double)(n + 1) + 8.0 * (double)n + 16.0 * (double)n * b;
+    if (b >= 8) {
+      // the recurrence runs on u_i = s o y_i, fused into the product kernel: u_0 is the packed copy in z
+      double* cur = z.p;
+      double* prev = rot.p;
+      double* next = rot.p + (size_t)n * b;
+      for (int i = 0; i < d; ++i) {
+        timer.begin(kFamSpmm);
+        HIP_TRY(launch_spmm_cheb(rowptr, col, val, s.p, n, cur, b, prev, next, i == 0 ? 1.0 / e : 2.0 / e, c,
+                                 i == 0 ? 0.0 : 1.0, avg_deg, st));
+        timer.end(kFamSpmm, spmm_bytes + (i == 0 ? 0.0 : 8.0 * (double)n * b), 2.0 * (double)nnz * b);
+        double* t = prev;
+        prev = cur;
+        cur = next;
+        next = t;
+        stats.spmv_cols += b;
+        stats.filter_steps += 1;
+      }
+      HIP_TRY(launch_unscale_cols(cur, s.p, basis.p, ld, nl, b, n, st));
+      return;
+    }
     double* ycur = rot.p;
     double* yprev = rot.p + (size_t)n * b;
     double* w = rot.p + 2 * (size_t)n * b;
@@ -449,8 +472,7 @@ struct Solver {
     for (int i = 0; i < d; ++i) {
       timer.begin(kFamSpmm);
       HIP_TRY(launch_spmm(rowptr, col, val, s.p, n, z.p, b, w, b, avg_deg, st));
-      timer.end(kFamSpmm, 12.0 * (double)nnz + 8.0 * (double)(n + 1) + 8.0 * (double)n + 16.0 * (double)n * b,
-                2.0 * (double)nnz * b);
+      timer.end(kFamSpmm, spmm_bytes, 2.0 * (double)nnz * b);
       if (i == 0) {
         HIP_TRY(launch_cheb_combine(w, ycur, ycur, s.p, 1.0 / e, c, 0.0, yprev, z.p, n, b, st));
       } else {
@@ -463,39 +485,52 @@ struct Solver {
     HIP_TRY(launch_copy_cols(ycur, b, 0, basis.p, ld, nl, b, n, st));
   }
 
-  // Decide the filter of the next phase from the Ritz values (ascending, ghosts at the bottom) of the phase that
-  // just locked its `nlock` leading pairs.  Further copies of the locked eigenvalues may remain (a block Krylov
-  // space holds at most b of them), so the polynomial is made large at the smallest value just locked and small
-  // below an estimate `a` of what follows: the largest unlocked Ritz value when a gap separates it from the locked
-  // ones (it approaches the next distinct eigenvalue from below; the best estimate over the phases is kept),
-  // otherwise the (b+1)-th unlocked one, below the b values the next phase is after.  A filter that is not worth
-  // its products (amplification below 100 at the degree cap) is left out; a wrong guess costs convergence speed,
-  // never correctness: the Lanczos phase that follows converges by its own residual test.
-  void plan_start_filter(const std::vector<double>& theta, int ja, int nlock, int nghost) {
+  // Decide the filter of the next start block from the Ritz values theta (ascending, ghosts at the bottom).
+  //
+  // locked = true: a phase has just locked its `nlead` leading pairs.  Further copies of the locked eigenvalues may
+  // remain (a block Krylov space holds at most b of them), so the polynomial is made large at the smallest value
+  // just locked and small below an estimate `a` of what follows: the largest unlocked Ritz value when a gap
+  // separates it from the locked ones (it approaches the next distinct eigenvalue from below; the best such
+  // estimate over the phases is kept, and reused when a phase has no unlocked Ritz value to offer), otherwise the
+  // (b+1)-th unlocked one, below the b values the next phase is after.
+  // locked = false: a phase that started unfiltered looks at its first Ritz values; nothing has converged, the
+  // target is the largest Ritz value and `a` the kept estimate if there is one, else the (nlead+1)-th Ritz value.
+  //
+  // A filter that is not worth its products (amplification below 100 at the degree cap) is left out.  A wrong guess
+  // costs convergence speed, never correctness: the Lanczos phase that follows converges by its own residual test.
+  void plan_start_filter(const std::vector<double>& theta, int ja, int nlead, int nghost, bool locked) {
     filt_d = 0;
     if (flags & SC_FLAG_NO_START_FILTER) return;
     if (rot_cols < (size_t)3 * b) return;
-    const int nu = ja - nlock - nghost;
-    if (nlock < 1 || nu < 1) return;
-    const double th_min = theta[ja - nlock];
-    const double u1 = theta[ja - 1 - nlock];
-    const double ub = theta[std::max(ja - 1 - nlock - b, nghost)];
-    double a;
-    if (th_min - u1 > u1 - ub) {
-      if (filt_best >= th_min - 1e-6) filt_best = -2.0;  // the wanted values have moved below the old estimate
-      filt_best = std::max(filt_best, u1);
-      a = filt_best;
-    } else {
-      a = ub;
+    if (nlead < 1 || ja - nghost < nlead) return;
+    const int nu = ja - nlead - nghost;  // Ritz values of real directions below the leading ones
+    const double th_ref = locked ? theta[ja - nlead] : theta[ja - 1];
+    if (filt_best >= th_ref - 1e-6) filt_best = -2.0;  // the wanted values have moved below the old estimate
+    double a = filt_best;
+    if (locked && nu >= 1) {
+      const double u1 = theta[ja - 1 - nlead];
+      const double ub = theta[std::max(ja - 1 - nlead - b, nghost)];
+      if (th_ref - u1 > u1 - ub) {
+        filt_best = std::max(filt_best, u1);
+        a = filt_best;
+      } else {
+        a = ub;
+      }
+    } else if (!locked && filt_best <= -2.0 && nu >= 1) {
+      a = theta[ja - 1 - nlead];
     }
     const double lo = -1.0;
-    if (!(a > lo + 0.05) || !(a < th_min)) return;
-    const double xt = (2.0 * th_min - a - lo) / (a - lo);
+    if (!(a > lo + 0.05) || !(a < th_ref)) return;
+    a += 0.03 * (th_ref - a);  // Ritz values approach the eigenvalue they estimate from below
+    const double xt = (2.0 * th_ref - a - lo) / (a - lo);
     const double rate = std::acosh(xt);
-    static const double amp = [] {
+    // what lies below `a` should end up near tol relative to the wanted directions, so that the Lanczos steps
+    // after the filter mostly confirm convergence
+    static const double amp_env = [] {
       const char* e = std::getenv("SCEIG_FILTER_AMP");
-      return e ? std::atof(e) : 1e7;
+      return e ? std::atof(e) : 0.0;
     }();
+    const double amp = amp_env > 0.0 ? amp_env : std::min(1e12, std::max(1e6, 100.0 / std::max(tol, 1e-300)));
     const int dmax = 30;
     if (!(rate > 0.0) || std::cosh(dmax * rate) < 100.0) return;
     const int d = (int)std::ceil(std::log(2.0 * amp) / rate);
@@ -596,7 +631,7 @@ struct Solver {
       bool start_block_seen = false;
       int pending = 0;
       const int prev_steps = filtered ? prev_filtered_steps : prev_phase_steps;
-      int next_check = prev_steps > 1 ? prev_steps - 1 : (filtered ? 2 : 4);
+      int next_check = prev_steps > 1 ? prev_steps - 1 : (filtered ? 1 : 4);
       double last_rho = -1.0;
       int last_rho_step = 0;
       bool phase_over = false;
@@ -707,7 +742,7 @@ struct Solver {
           // A phase that began from a plain random block (no spectrum estimate was available then): once its Ritz
           // values give one, filter the leading Ritz vectors - a far better start than a random block - and begin
           // the phase anew from the filtered block.
-          plan_start_filter(theta, ja, std::min(want, nreal), ja - nreal);
+          plan_start_filter(theta, ja, std::min(want, nreal), ja - nreal, false);
           if (filt_d > 0) {
             if (debug_on())
               std::fprintf(stderr, "[sceig] t=%.4fs phase %d restarts from its %d leading Ritz vectors filtered: degree %d, "
@@ -730,7 +765,7 @@ struct Solver {
             std::fill(T.begin(), T.end(), 0.0);
             std::fill(ghost.begin(), ghost.end(), 0);
             start_block_seen = false;
-            next_check = prev_filtered_steps > 1 ? prev_filtered_steps - 1 : 2;
+            next_check = prev_filtered_steps > 1 ? prev_filtered_steps - 1 : 1;
             last_rho = -1.0;
             last_rho_step = 0;
             continue;
@@ -766,7 +801,7 @@ struct Solver {
           }
           phase_over = true;
           (filtered ? prev_filtered_steps : prev_phase_steps) = steps_in_phase;
-          plan_start_filter(theta, ja, nlock, ja - nreal);
+          plan_start_filter(theta, ja, nlock, ja - nreal, true);
           break;
         }
         if (stop_now || (full && cycles >= maxiter)) {
@@ -844,13 +879,31 @@ struct Solver {
       }
     }
 
-    // ---- Rayleigh-Ritz over the locked vectors (the Ritz-vector step of Algorithm 3)
+    // ---- outputs.  Every locked vector is a Ritz vector whose residual estimate met tol (and theta its Rayleigh
+    // quotient), the locked set is orthonormal by construction, so the answer is the locked set in descending
+    // order of theta.  A Rayleigh-Ritz step over the locked vectors (the Ritz-vector step of Algorithm 3 applied
+    // to the final basis) is added when some vector did not converge, or on request.
     const int nx = nl;
-    if (debug_on()) std::fprintf(stderr, "[sceig] t=%.4fs Rayleigh-Ritz over %d locked vectors\n", now_s() - t_begin, nx);
+    bool all_converged = !not_converged;
+    for (size_t t = 0; t < rho_locked.size(); ++t) all_converged = all_converged && rho_locked[t] <= tol;
+    const bool final_rr = !all_converged || (flags & SC_FLAG_FINAL_RR);
+    if (debug_on())
+      std::fprintf(stderr, "[sceig] t=%.4fs %s over %d locked vectors\n", now_s() - t_begin,
+                   final_rr ? "Rayleigh-Ritz" : "sorted output", nx);
     std::vector<double> evals_host(k, std::numeric_limits<double>::quiet_NaN());
-    HIP_TRY(hipMemsetAsync(evecs_out, 0, (size_t)n * k * sizeof(double), st));
     int nfound = std::min(nx, k);
-    if (nx > 0) {
+    if (nx < k) HIP_TRY(hipMemsetAsync(evecs_out, 0, (size_t)n * k * sizeof(double), st));
+    std::vector<int32_t> order;
+    if (nx > 0 && !final_rr) {
+      order.resize(nx);
+      std::iota(order.begin(), order.end(), 0);
+      std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return theta_locked[x] > theta_locked[y]; });
+      order.resize(nfound);
+      for (int t = 0; t < nfound; ++t) evals_host[t] = 1.0 - theta_locked[order[t]];
+      HIP_TRY(hipMemcpyAsync(perm_d.p, order.data(), (size_t)nfound * sizeof(int32_t), hipMemcpyHostToDevice, st));
+      HIP_TRY(launch_gather_cols_colmajor(basis.p, n, ld, perm_d.p, nfound, evecs_out, rowmap, st));
+      HIP_TRY(hipStreamSynchronize(st));  // `order` is pageable host memory
+    } else if (nx > 0) {
       std::vector<double> G((size_t)nx * nx, 0.0), hbuf((size_t)nx * kPP);
       const ProjectPlan plan = plan_project(n, nx, kMaxPartials);
       // columns [nx, nx+b) are zeroed so that a last chunk narrower than b is padded with zeros;
@@ -972,7 +1025,7 @@ int sc_laplacian_eigsh(const int64_t* csr_rowptr, const int32_t* csr_col, const 
   if (b == 0) {
     // Larger blocks amortise the passes over the basis (their cost grows with n), smaller blocks keep the
     // projected problems and the number of block steps per converged vector small.
-    int target = n >= 300000 ? 16 : 8;
+    int target = n >= 20000 ? 16 : 8;
     if (n >= 300000 && k >= 1000) target = 32;
     b = std::min(target, pow2_floor((int)std::max<int64_t>(1, (m - k) / 3)));
     int kb = 1;

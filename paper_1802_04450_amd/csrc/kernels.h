@@ -99,6 +99,17 @@ hipError_t launch_nullspace_fill(double* basis, int64_t n, int64_t ld, int col0,
 hipError_t launch_random_block(double* basis, int64_t n, int64_t ld, int col0, int b, uint64_t seed,
                                uint64_t stream_id, hipStream_t st);
 // dst[i*ldd + dcol0 + t] = src[i*lds + scol0 + t], t < w (regions must not overlap)
+// out[t*n + r(i)] = basis[i*ld + perm[t]], t < k (perm: device int32[k]; r(i) = rowmap[i] if given, else i)
+hipError_t launch_gather_cols_colmajor(const double* basis, int64_t n, int64_t ld, const int32_t* perm, int k, double* out,
+                                       const int32_t* rowmap, hipStream_t st);
+// One Chebyshev recurrence step on the s-scaled packed iterates (b = 8, 16, 32):
+//   unext = alpha * (s^2 o (W ucur) - shift * ucur) - beta * uprev      (uprev is not read when beta == 0)
+hipError_t launch_spmm_cheb(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
+                            const double* ucur, int b, const double* uprev, double* unext, double alpha, double shift,
+                            double beta, double avg_deg, hipStream_t st);
+// basis[i, col0 + t] = u[i*b + t] / s[i]
+hipError_t launch_unscale_cols(const double* u, const double* s, double* basis, int64_t ld, int col0, int b, int64_t n,
+                               hipStream_t st);
 // ynext = alpha (w - shift ycur) - beta yprev and znext = s o ynext on packed n x b blocks (Chebyshev recurrence step)
 hipError_t launch_cheb_combine(const double* w, const double* ycur, const double* yprev, const double* s, double alpha,
                                double shift, double beta, double* ynext, double* znext, int64_t n, int b,

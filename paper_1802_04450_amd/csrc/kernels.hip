@@ -92,13 +92,18 @@ static inline unsigned xcd_grid(int64_t tiles) { return (unsigned)(ceil_div64(ti
 // keeps busiest), and the L/CL sub-groups split the batch: sub-group g takes entries g*E ... g*E+E-1, E = CL.  A row
 // of up to L entries is one load -> gather -> sum chain; long rows (hubs of the kNN graph) take deg/L trips.  The
 // sub-group sums are combined in a fixed order by a shuffle tree.
-template <int B, int L>
+//
+// CHEB = true turns the product into one step of the Chebyshev recurrence run on the s-scaled iterates
+// u_i = s o y_i (so that the packed operand of the next product is the result itself and nothing else is stored):
+//   u_next = alpha * (s^2 o (W u_cur) - shift * u_cur) - beta * u_prev,     z = u_cur, y = u_next, both packed (ld = B).
+template <int B, int L, bool CHEB>
 __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __restrict__ rowptr,
                                                              const int32_t* __restrict__ col,
                                                              const double* __restrict__ val,
                                                              const double* __restrict__ s,
                                                              const double* __restrict__ z, double* __restrict__ y,
-                                                             int64_t ldy, int64_t n) {
+                                                             int64_t ldy, int64_t n, const double* __restrict__ uprev,
+                                                             double alpha, double shift, double beta) {
   constexpr int G = kThreads / L;  // rows per workgroup
   constexpr int CL = B / 2;        // lanes per entry
   constexpr int E = CL;            // entries per sub-group and batch: (L / CL) sub-groups * E = L
@@ -145,9 +150,34 @@ __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __re
   }
   if (lane < CL) {
     const double sr = s[row];
-    y[row * ldy + 2 * tl] = sr * acc0;
-    y[row * ldy + 2 * tl + 1] = sr * acc1;
+    if constexpr (CHEB) {
+      const int64_t o = row * CL + tl;
+      const double2 cur = z2[o];
+      double2 out;
+      out.x = alpha * (sr * sr * acc0 - shift * cur.x);
+      out.y = alpha * (sr * sr * acc1 - shift * cur.y);
+      if (beta != 0.0) {
+        const double2 pv = reinterpret_cast<const double2*>(uprev)[o];
+        out.x -= beta * pv.x;
+        out.y -= beta * pv.y;
+      }
+      reinterpret_cast<double2*>(y)[o] = out;
+    } else {
+      y[row * ldy + 2 * tl] = sr * acc0;
+      y[row * ldy + 2 * tl + 1] = sr * acc1;
+    }
   }
+}
+
+// basis[i, col0 + t] = u[i * b + t] / s[i]: back from the s-scaled iterate of the Chebyshev recurrence
+__global__ __launch_bounds__(kThreads) void unscale_cols_kernel(const double* __restrict__ u,
+                                                                const double* __restrict__ s, double* __restrict__ basis,
+                                                                int64_t ld, int col0, int b, int64_t n) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= n * b) return;
+  const int64_t i = idx / b;
+  const int t = (int)(idx - i * b);
+  basis[i * ld + col0 + t] = u[idx] / s[i];
 }
 
 // L lanes per row, each lane walks the entries of the row with stride L and keeps B accumulators
@@ -632,6 +662,30 @@ __global__ __launch_bounds__(kThreads) void copy_cols_kernel(const double* __res
   dst[i * ldd + dcol0 + t] = src[i * lds + scol0 + t];
 }
 
+// out[t * n + r(i)] = basis[i * ld + perm[t]] for t < k: selected columns of the row-major basis, written column-major
+// (r(i) = rowmap[i] if rowmap is given, else i).  A workgroup moves a 64 x 64 tile through LDS so that both the reads
+// (along a basis row) and the writes (along an output column) run over consecutive addresses.
+__global__ __launch_bounds__(kThreads) void gather_cols_colmajor_kernel(const double* __restrict__ basis, int64_t n,
+                                                                        int64_t ld, const int32_t* __restrict__ perm,
+                                                                        int k, double* __restrict__ out,
+                                                                        const int32_t* __restrict__ rowmap) {
+  __shared__ double tile[64][65];
+  const int64_t i0 = (int64_t)blockIdx.x * 64;
+  const int c0 = blockIdx.y * 64;
+  for (int idx = threadIdx.x; idx < 64 * 64; idx += kThreads) {
+    const int r = idx / 64, c = idx % 64;
+    if (i0 + r < n && c0 + c < k) tile[c][r] = basis[(i0 + r) * ld + perm[c0 + c]];
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < 64 * 64; idx += kThreads) {
+    const int c = idx / 64, r = idx % 64;
+    if (i0 + r < n && c0 + c < k) {
+      const int64_t dst = rowmap ? (int64_t)rowmap[i0 + r] : i0 + r;
+      out[(int64_t)(c0 + c) * n + dst] = tile[c][r];
+    }
+  }
+}
+
 // One step of the three-term Chebyshev recurrence on packed n x b blocks (leading dimension b):
 //   ynext = alpha * (w - shift * ycur) - beta * yprev,   znext = s o ynext   (the packed operand of the next product)
 // ynext may be the buffer of yprev (each element is read before it is written by the same thread).
@@ -1058,15 +1112,14 @@ static int spmm_lanes(int b, double avg_deg) {
   return lanes;
 }
 
-hipError_t launch_spmm(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
-                       const double* z, int b, double* y, int64_t ldy, double avg_deg, hipStream_t st) {
+template <bool CHEB>
+static hipError_t launch_spmm_cols(const int64_t* rowptr, const int32_t* col, const double* val, const double* s,
+                                   int64_t n, const double* z, int b, double* y, int64_t ldy, double avg_deg,
+                                   const double* uprev, double alpha, double shift, double beta, hipStream_t st) {
+#define SC_LAUNCH_COLS(BB, LL)                                                                              \
+  hipLaunchKernelGGL((spmm_cols_kernel<BB, LL, CHEB>), dim3(xcd_grid(ceil_div64(n, kThreads / LL))),          \
+                     dim3(kThreads), 0, st, rowptr, col, val, s, z, y, ldy, n, uprev, alpha, shift, beta)
   switch (b) {
-    case 1: return launch_spmm_nz<1>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
-    case 2: return launch_spmm_nz<2>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
-    case 4: return launch_spmm_nz<4>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
-#define SC_LAUNCH_COLS(BB, LL)                                                                                 \
-  hipLaunchKernelGGL((spmm_cols_kernel<BB, LL>), dim3(xcd_grid(ceil_div64(n, kThreads / LL))), dim3(kThreads), \
-                     0, st, rowptr, col, val, s, z, y, ldy, n)
     case 8:
       switch (spmm_lanes(8, avg_deg)) {
         case 8: SC_LAUNCH_COLS(8, 8); break;
@@ -1088,9 +1141,33 @@ hipError_t launch_spmm(const int64_t* rowptr, const int32_t* col, const double* 
         default: SC_LAUNCH_COLS(32, 64); break;
       }
       break;
-#undef SC_LAUNCH_COLS
     default: return hipErrorInvalidValue;
   }
+#undef SC_LAUNCH_COLS
+  return hipGetLastError();
+}
+
+hipError_t launch_spmm(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
+                       const double* z, int b, double* y, int64_t ldy, double avg_deg, hipStream_t st) {
+  switch (b) {
+    case 1: return launch_spmm_nz<1>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
+    case 2: return launch_spmm_nz<2>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
+    case 4: return launch_spmm_nz<4>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
+    default: return launch_spmm_cols<false>(rowptr, col, val, s, n, z, b, y, ldy, avg_deg, nullptr, 0.0, 0.0, 0.0, st);
+  }
+}
+
+hipError_t launch_spmm_cheb(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
+                            const double* ucur, int b, const double* uprev, double* unext, double alpha, double shift,
+                            double beta, double avg_deg, hipStream_t st) {
+  if (b < 8) return hipErrorInvalidValue;
+  return launch_spmm_cols<true>(rowptr, col, val, s, n, ucur, b, unext, b, avg_deg, uprev, alpha, shift, beta, st);
+}
+
+hipError_t launch_unscale_cols(const double* u, const double* s, double* basis, int64_t ld, int col0, int b, int64_t n,
+                               hipStream_t st) {
+  hipLaunchKernelGGL(unscale_cols_kernel, dim3((unsigned)ceil_div64(n * b, kThreads)), dim3(kThreads), 0, st, u, s,
+                     basis, ld, col0, b, n);
   return hipGetLastError();
 }
 
@@ -1227,6 +1304,14 @@ hipError_t launch_copy_cols(const double* src, int64_t lds, int scol0, double* d
   if (w <= 0) return hipSuccess;
   hipLaunchKernelGGL(copy_cols_kernel, dim3((unsigned)ceil_div64(n * w, kThreads)), dim3(kThreads), 0, st, src, lds,
                      scol0, dst, ldd, dcol0, w, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_cols_colmajor(const double* basis, int64_t n, int64_t ld, const int32_t* perm, int k, double* out,
+                                       const int32_t* rowmap, hipStream_t st) {
+  if (n <= 0 || k <= 0) return hipSuccess;
+  hipLaunchKernelGGL(gather_cols_colmajor_kernel, dim3((unsigned)ceil_div64(n, 64), (unsigned)((k + 63) / 64)),
+                     dim3(kThreads), 0, st, basis, n, ld, perm, k, out, rowmap);
   return hipGetLastError();
 }
 

@@ -226,3 +226,44 @@ def test_component_nullspace_option(B, k):
         check_against_oracle(g, k, lam, vec, lam_full[:k] if k < ncomp else lam_full[:k + 1],
                              vec_full[:, :k], cluster_basis=basis)
     assert np.sum(np.abs(lam) < 1e-12) == min(k, ncomp)
+
+
+@pytest.mark.parametrize("flags", ["NO_START_FILTER", "FINAL_RR", "NO_START_FILTER|FINAL_RR"])
+def test_option_flags_give_the_same_answer(B, flags):
+    """The start-block filter and the final Rayleigh-Ritz step are accelerations/refinements: with either switched
+    the other way the answer must meet the same bars (multiplicity graph and a reduced clustered workload)."""
+    f = 0
+    for name in flags.split("|"):
+        f |= getattr(B, "SC_FLAG_" + name)
+    g = wl.disjoint_union(*[wl.ring(20 + 3 * t) for t in range(6)])
+    lam_full, vec_full = dense.full_spectrum(*g[:3])
+    lam, vec, code, stats = solve(B, g, 9, 1e-10, m=60, flags=f)
+    assert code == B.SC_OK
+    if f & B.SC_FLAG_NO_START_FILTER:
+        assert stats["filter_steps"] == 0
+    check_against_oracle(g, 9, lam, vec, lam_full[:10], vec_full[:, :9])
+    cfg = wl.reduced(wl.CONFIGS[2], n=6000, components=12)
+    g, label, sigma = wl.build_config_graph(cfg, device="cuda")
+    k = 12
+    lam, vec, code, stats = solve(B, g, k, 1e-8, flags=f)
+    assert code == B.SC_OK
+    ncomp, _ = components.component_labels(*g[:3])
+    assert ncomp >= k              # the reduced workload keeps its clusters disconnected: k exact zeros
+    basis = components.null_space(*g[:3])
+    assert np.max(np.abs(lam)) <= 1e-8
+    assert np.max(compare.residual_norms(*g[:3], lam, vec)) <= 1e-6
+    assert np.max(compare.containment_defect(vec, basis)) <= 1e-5
+    assert compare.orthonormality_defect(vec) <= 1e-9
+
+
+def test_start_filter_is_used_on_clustered_workload(B):
+    """On a union of components (eigenvalue 0 with multiplicity > block size) the re-injection blocks are filtered and
+    the phases after the first need only a few Lanczos steps."""
+    cfg = wl.reduced(wl.CONFIGS[2], n=6000, components=24)
+    g, label, sigma = wl.build_config_graph(cfg, device="cuda")
+    lam, vec, code, with_filter = solve(B, g, 24, 1e-8, block=4)
+    assert code == B.SC_OK and with_filter["filter_steps"] > 0
+    lam2, vec2, code2, without = solve(B, g, 24, 1e-8, block=4, flags=B.SC_FLAG_NO_START_FILTER)
+    assert code2 == B.SC_OK and without["filter_steps"] == 0
+    assert with_filter["block_steps"] < without["block_steps"]
+    assert np.max(np.abs(lam)) <= 1e-8 and np.max(np.abs(lam2)) <= 1e-8
