@@ -194,7 +194,7 @@ int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, i
     tm->end(kFamOther, 8.0 * plan.npart * (double)jc * b, 0.0);
     tm->begin(kFamUpdate);
     if (pass == 1 && gpart) {
-      HIP_TRY(launch_update_gram(basis, n, ld, c0, jc, h1, b, wcol, gpart, st));
+      HIP_TRY(launch_update_gram(basis, n, ld, c0, jc, h1, b, wcol, 0, gpart, st));
       ngram = plan_update_gram(n);
     } else {
       HIP_TRY(launch_row_gemm(basis, n, ld, c0, jc, h1, kPP, b, 0, wcol, nullptr, 0, nullptr, st));
@@ -223,8 +223,8 @@ void enqueue_block_qr(double* basis, int64_t n, int64_t ld, int col, int b, doub
     HIP_TRY(launch_reduce_partials(part, plan.npart, b, b, gram, nullptr, 0, nullptr, 0, st));
   }
   HIP_TRY(launch_gram_cholesky(gram, b, g_out, rinv, r1, nullptr, kAbsDrop2, kRelDrop, st));
-  HIP_TRY(launch_apply_gram(basis, n, ld, col, b, rinv, gpart, st));
-  HIP_TRY(launch_reduce_partials(gpart, plan_apply_gram(n, b), b, b, gram, nullptr, 0, nullptr, 0, st));
+  HIP_TRY(launch_update_gram(basis, n, ld, col, b, rinv, b, col, 1, gpart, st));
+  HIP_TRY(launch_reduce_partials(gpart, plan_update_gram(n), b, b, gram, nullptr, 0, nullptr, 0, st));
   // second pass: a column that survived the first pass has unit norm, so only exact zeros are dropped
   HIP_TRY(launch_gram_cholesky(gram, b, nullptr, rinv, r_out, r1, 0.25, 1e-8, st));
   HIP_TRY(launch_apply_rinv(basis, n, ld, col, b, rinv, z, s, st));
@@ -309,6 +309,7 @@ struct Solver {
   DevBuf<int64_t> rowptr_p;
   DevBuf<int32_t> col_p, old_of_new_d, comp_d, perm_d;
   DevBuf<double> val_p, coef_d;
+  DevBuf<double> val_s;  // S_ij = s_i W_ij s_j multiplied out: the operator copy used when b >= 8
   const int32_t* rowmap = nullptr;  // device: original row of each internal row, null if not reordered
   std::vector<int32_t> comp_host;   // component index of each internal row (only after reorder())
   int ncomp = 0;
@@ -331,6 +332,20 @@ struct Solver {
   double* r1() { return small.p + kPP * kPP; }
   double* gram() { return small.p + 2 * kPP * kPP; }
   double* slot(int i) { return slots.p + (size_t)i * kSlotDoubles; }
+  // scaling applied when the packed operand z of the next product is written: the CSR product scales by s on both
+  // sides (z = s o x), the entry product has S multiplied out (z = x)
+  const double* zs() const { return val_s.p ? nullptr : s.p; }
+  double spmm_bytes() const {
+    return 12.0 * (double)nnz + 8.0 * (double)(n + 1) + (val_s.p ? 0.0 : 8.0 * (double)n) + 16.0 * (double)n * b;
+  }
+  // y (row-major, leading dimension ldy) = S x for the block whose packed operand is in z
+  void spmm_from_z(double* y, int64_t ldy) {
+    if (val_s.p) {
+      HIP_TRY(launch_spmm_vals(rowptr, col, val_s.p, n, z.p, b, y, ldy, avg_deg, st));
+    } else {
+      HIP_TRY(launch_spmm(rowptr, col, val, s.p, n, z.p, b, y, ldy, avg_deg, st));
+    }
+  }
   const double* hslot(int i) const { return slots_host.p + (size_t)i * kSlotDoubles; }
 
   void reorder() {
@@ -390,6 +405,10 @@ struct Solver {
     HIP_TRY(hipStreamSynchronize(st));
     if (hflag & 4) SC_THROW(SC_EZERODEG);
     avg_deg = (double)nnz / (double)n;
+    if (b >= 8) {
+      val_s.alloc((size_t)nnz);
+      HIP_TRY(launch_scale_values(rowptr, col, val, s.p, val_s.p, n, st));
+    }
 
     ld = ((int64_t)m + b + 15) / 16 * 16;
     basis.alloc((size_t)n * ld);
@@ -419,13 +438,12 @@ struct Solver {
   void enqueue_step(int ja, int si) {
     const int jt = nl + ja;
     timer.begin(kFamSpmm);
-    HIP_TRY(launch_spmm(rowptr, col, val, s.p, n, z.p, b, basis.p + jt, ld, avg_deg, st));
-    timer.end(kFamSpmm, 12.0 * (double)nnz + 8.0 * (double)(n + 1) + 8.0 * (double)n + 16.0 * (double)n * b,
-              2.0 * (double)nnz * b);
+    spmm_from_z(basis.p + jt, ld);
+    timer.end(kFamSpmm, spmm_bytes(), 2.0 * (double)nnz * b);
     double* sl = slot(si);
     const int ngram = enqueue_cgs2(basis.p, n, ld, jt, jt, b, nl, part.p, h1.p, hsum.p, sl, jt - b, gpart.p, st, &timer);
     enqueue_block_qr(basis.p, n, ld, jt, b, part.p, gpart.p, ngram, gram(), rinv(), r1(), sl + kPP * kPP,
-                     sl + 2 * kPP * kPP, z.p, s.p, st, &timer);
+                     sl + 2 * kPP * kPP, z.p, zs(), st, &timer);
     stats.block_steps += 1;
     stats.spmv_cols += b;
   }
@@ -444,17 +462,16 @@ struct Solver {
   void apply_start_filter(int d, double a) {
     const double lo = -1.0;  // ||S||_2 = 1
     const double c = 0.5 * (a + lo), e = 0.5 * (a - lo);
-    const double spmm_bytes = 12.0 * (double)nnz + 8.0 * (double)(n + 1) + 8.0 * (double)n + 16.0 * (double)n * b;
-    if (b >= 8) {
-      // the recurrence runs on u_i = s o y_i, fused into the product kernel: u_0 is the packed copy in z
+    if (val_s.p) {
+      // the recurrence is fused into the product kernel: y_0 is the packed copy of the block in z
       double* cur = z.p;
       double* prev = rot.p;
       double* next = rot.p + (size_t)n * b;
       for (int i = 0; i < d; ++i) {
         timer.begin(kFamSpmm);
-        HIP_TRY(launch_spmm_cheb(rowptr, col, val, s.p, n, cur, b, prev, next, i == 0 ? 1.0 / e : 2.0 / e, c,
-                                 i == 0 ? 0.0 : 1.0, avg_deg, st));
-        timer.end(kFamSpmm, spmm_bytes + (i == 0 ? 0.0 : 8.0 * (double)n * b), 2.0 * (double)nnz * b);
+        HIP_TRY(launch_spmm_vals_cheb(rowptr, col, val_s.p, n, cur, b, prev, next, i == 0 ? 1.0 / e : 2.0 / e, c,
+                                      i == 0 ? 0.0 : 1.0, avg_deg, st));
+        timer.end(kFamSpmm, spmm_bytes() + (i == 0 ? 0.0 : 8.0 * (double)n * b), 2.0 * (double)nnz * b);
         double* t = prev;
         prev = cur;
         cur = next;
@@ -462,7 +479,7 @@ struct Solver {
         stats.spmv_cols += b;
         stats.filter_steps += 1;
       }
-      HIP_TRY(launch_unscale_cols(cur, s.p, basis.p, ld, nl, b, n, st));
+      HIP_TRY(launch_copy_cols(cur, b, 0, basis.p, ld, nl, b, n, st));
       return;
     }
     double* ycur = rot.p;
@@ -471,8 +488,8 @@ struct Solver {
     HIP_TRY(launch_copy_cols(basis.p, ld, nl, ycur, b, 0, b, n, st));
     for (int i = 0; i < d; ++i) {
       timer.begin(kFamSpmm);
-      HIP_TRY(launch_spmm(rowptr, col, val, s.p, n, z.p, b, w, b, avg_deg, st));
-      timer.end(kFamSpmm, spmm_bytes, 2.0 * (double)nnz * b);
+      spmm_from_z(w, b);
+      timer.end(kFamSpmm, spmm_bytes(), 2.0 * (double)nnz * b);
       if (i == 0) {
         HIP_TRY(launch_cheb_combine(w, ycur, ycur, s.p, 1.0 / e, c, 0.0, yprev, z.p, n, b, st));
       } else {
@@ -609,7 +626,7 @@ struct Solver {
       HIP_TRY(launch_random_block(basis.p, n, ld, nl, b, seed, stream_id++, st));
       const int ngram0 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
       enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram0, gram(), rinv(), r1(), slot(0) + kPP * kPP,
-                       slot(0) + 2 * kPP * kPP, z.p, s.p, st, &timer);
+                       slot(0) + 2 * kPP * kPP, z.p, zs(), st, &timer);
       bool filtered = filt_d > 0;
       if (filtered) {
         if (debug_on())
@@ -618,7 +635,7 @@ struct Solver {
         apply_start_filter(filt_d, filt_a);
         const int ngram1 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
         enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram1, gram(), rinv(), r1(), slot(0) + kPP * kPP,
-                         slot(0) + 2 * kPP * kPP, z.p, s.p, st, &timer);
+                         slot(0) + 2 * kPP * kPP, z.p, zs(), st, &timer);
         filt_d = 0;
       }
       int ja = b;            // active columns whose coupling is (or will be) assembled
@@ -750,11 +767,11 @@ struct Solver {
             std::vector<int> sel(b);
             for (int t = 0; t < b; ++t) sel[t] = t;
             rotate_into(ja, Y, ycols, sel, nl);
-            HIP_TRY(launch_pack_scaled(basis.p + nl, ld, s.p, n, b, z.p, st));
+            HIP_TRY(launch_pack_scaled(basis.p + nl, ld, zs(), n, b, z.p, st));
             apply_start_filter(filt_d, filt_a);
             const int ngram1 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
             enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram1, gram(), rinv(), r1(), slot(0) + kPP * kPP,
-                             slot(0) + 2 * kPP * kPP, z.p, s.p, st, &timer);
+                             slot(0) + 2 * kPP * kPP, z.p, zs(), st, &timer);
             filt_d = 0;
             filtered = true;
             ja = b;
@@ -912,8 +929,8 @@ struct Solver {
       HIP_TRY(launch_copy_cols(z.p, b, 0, basis.p, ld, nx, b, n, st));
       for (int c0 = 0; c0 < nx; c0 += b) {
         const int w = std::min(b, nx - c0);
-        HIP_TRY(launch_pack_scaled(basis.p + c0, ld, s.p, n, b, z.p, st));
-        HIP_TRY(launch_spmm(rowptr, col, val, s.p, n, z.p, b, basis.p + nx + b, ld, avg_deg, st));
+        HIP_TRY(launch_pack_scaled(basis.p + c0, ld, zs(), n, b, z.p, st));
+        spmm_from_z(basis.p + nx + b, ld);
         HIP_TRY(launch_project(basis.p, n, ld, 0, nx, nx + b, b, plan, part.p, st));
         HIP_TRY(launch_reduce_partials(part.p, plan.npart, nx, b, h1.p, nullptr, 0, nullptr, 0, st));
         HIP_TRY(hipMemcpyAsync(hbuf.data(), h1.p, (size_t)nx * kPP * sizeof(double), hipMemcpyDeviceToHost, st));

@@ -66,20 +66,16 @@ hipError_t launch_gram_cholesky(const double* g_in, int b, double* g_out, double
 hipError_t launch_apply_rinv(double* basis, int64_t n, int64_t ld, int col0, int b, const double* rinv, double* z,
                              const double* s, hipStream_t st);
 
-// Fused variants used inside the block step (same arithmetic as the separate kernels):
+// Fused variant used inside the block step (same arithmetic as the separate kernels):
 //   update_gram: basis[:, ccol0 : ccol0+b] -= basis[:, acol0 : acol0+kdim] * bmat (bmat kdim x b, row stride
 //                kPartialPad) and
 //                gpart[p] (b x b, row stride kPartialPad, p < plan_update_gram(n)) = partial Gram matrices of the
 //                updated block, to be summed with launch_reduce_partials(gpart, npart, b, b, ...).
-//   apply_gram:  basis[:, col0 : col0+b] *= rinv and gpart[p], p < plan_apply_gram(n, b), partial Gram matrices of
-//                the result.
 int plan_update_gram(int64_t n);
+// overwrite != 0: the block is replaced by the product instead of having it subtracted (W <- W R^-1 with
+// acol0 = ccol0, kdim = b, bmat = R^-1)
 hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int b,
-                              int ccol0, double* gpart, hipStream_t st);
-int plan_apply_gram(int64_t n, int b);
-hipError_t launch_apply_gram(double* basis, int64_t n, int64_t ld, int col0, int b, const double* rinv, double* gpart,
-                             hipStream_t st);
-
+                              int ccol0, int overwrite, double* gpart, hipStream_t st);
 // ---- connected components and locality reordering (setup) --------------------------------------
 // label[i] = i
 hipError_t launch_iota(int32_t* label, int64_t n, hipStream_t st);
@@ -102,14 +98,19 @@ hipError_t launch_random_block(double* basis, int64_t n, int64_t ld, int col0, i
 // out[t*n + r(i)] = basis[i*ld + perm[t]], t < k (perm: device int32[k]; r(i) = rowmap[i] if given, else i)
 hipError_t launch_gather_cols_colmajor(const double* basis, int64_t n, int64_t ld, const int32_t* perm, int k, double* out,
                                        const int32_t* rowmap, hipStream_t st);
-// One Chebyshev recurrence step on the s-scaled packed iterates (b = 8, 16, 32):
-//   unext = alpha * (s^2 o (W ucur) - shift * ucur) - beta * uprev      (uprev is not read when beta == 0)
-hipError_t launch_spmm_cheb(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
-                            const double* ucur, int b, const double* uprev, double* unext, double alpha, double shift,
-                            double beta, double avg_deg, hipStream_t st);
-// basis[i, col0 + t] = u[i*b + t] / s[i]
-hipError_t launch_unscale_cols(const double* u, const double* s, double* basis, int64_t ld, int col0, int b, int64_t n,
-                               hipStream_t st);
+// The solver's own operator copy for wide blocks (b = 8, 16, 32) holds S_ij = s_i W_ij s_j multiplied out:
+// val_out[e] = s_i * val[e] * s_j (val_out may be val).
+hipError_t launch_scale_values(const int64_t* rowptr, const int32_t* col, const double* val, const double* s,
+                               double* val_out, int64_t n, hipStream_t st);
+// y = A x with the values as stored (the scaled copy); x packed n x b (b = 8, 16, 32; 16-byte aligned), y row-major
+// with leading dimension ldy.
+hipError_t launch_spmm_vals(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n, const double* x,
+                            int b, double* y, int64_t ldy, double avg_deg, hipStream_t st);
+// One Chebyshev recurrence step on packed blocks:  unext = alpha * (A ucur - shift * ucur) - beta * uprev
+// (uprev is not read when beta == 0; unext must not be ucur)
+hipError_t launch_spmm_vals_cheb(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n,
+                                 const double* ucur, int b, const double* uprev, double* unext, double alpha,
+                                 double shift, double beta, double avg_deg, hipStream_t st);
 // ynext = alpha (w - shift ycur) - beta yprev and znext = s o ynext on packed n x b blocks (Chebyshev recurrence step)
 hipError_t launch_cheb_combine(const double* w, const double* ycur, const double* yprev, const double* s, double alpha,
                                double shift, double beta, double* ynext, double* znext, int64_t n, int b,

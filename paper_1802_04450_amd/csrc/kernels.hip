@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kThreads) void pack_scaled_kernel(const double* __r
   if (idx >= n * b) return;
   const int64_t i = idx / b;
   const int t = (int)(idx - i * b);
-  z[idx] = s[i] * x[i * ldx + t];
+  z[idx] = s ? s[i] * x[i * ldx + t] : x[i * ldx + t];
 }
 
 // Workgroups are handed to the 8 XCDs (each with an L2 of its own) round-robin by their linear index.  The sparse
@@ -87,23 +87,25 @@ __device__ __forceinline__ int64_t xcd_tile() {
 static inline unsigned xcd_grid(int64_t tiles) { return (unsigned)(ceil_div64(tiles, kXcds) * kXcds); }
 
 // L lanes per row, B = 8, 16, 32 columns.  The L lanes load L consecutive (col, val) pairs of the row at once.  A
-// lane carries TWO adjacent columns of the block, so CL = B/2 lanes cover one entry with 16-byte gathers (the
-// texture addresser spends the same cycles on a 64-lane load whatever its width, and it is the unit this kernel
-// keeps busiest), and the L/CL sub-groups split the batch: sub-group g takes entries g*E ... g*E+E-1, E = CL.  A row
-// of up to L entries is one load -> gather -> sum chain; long rows (hubs of the kNN graph) take deg/L trips.  The
-// sub-group sums are combined in a fixed order by a shuffle tree.
+// lane carries TWO adjacent columns of the block, so CL = B/2 lanes cover one entry with 16-byte gathers, and the
+// L/CL sub-groups split the batch: sub-group g takes entries g*E ... g*E+E-1, E = CL.  A row of up to L entries is
+// one load -> gather -> sum chain; long rows (hubs of the kNN graph) take deg/L trips.  The sub-group sums are
+// combined in a fixed order by a shuffle tree.
 //
-// CHEB = true turns the product into one step of the Chebyshev recurrence run on the s-scaled iterates
-// u_i = s o y_i (so that the packed operand of the next product is the result itself and nothing else is stored):
-//   u_next = alpha * (s^2 o (W u_cur) - shift * u_cur) - beta * u_prev,     z = u_cur, y = u_next, both packed (ld = B).
-template <int B, int L, bool CHEB>
+// MODE 0: y = s o (W z), z = s o x packed by the caller (the operator applied from W and the scaling vector).
+// MODE 1: y = A z with the values as they are (the solver's copy holds S_ij = s_i W_ij s_j already multiplied out,
+//         as Algorithm 2's scaling step does), z = x packed.
+// MODE 2: one step of the Chebyshev recurrence on packed blocks with such values:
+//         y = alpha * (A z - shift * z) - beta * uprev   (uprev is not read when beta == 0; y packed, ldy = B).
+template <int B, int L, int MODE>
 __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __restrict__ rowptr,
                                                              const int32_t* __restrict__ col,
                                                              const double* __restrict__ val,
                                                              const double* __restrict__ s,
                                                              const double* __restrict__ z, double* __restrict__ y,
-                                                             int64_t ldy, int64_t n, const double* __restrict__ uprev,
-                                                             double alpha, double shift, double beta) {
+                                                             int64_t ldy, int64_t n, int vec_store,
+                                                             const double* __restrict__ uprev, double alpha,
+                                                             double shift, double beta) {
   constexpr int G = kThreads / L;  // rows per workgroup
   constexpr int CL = B / 2;        // lanes per entry
   constexpr int E = CL;            // entries per sub-group and batch: (L / CL) sub-groups * E = L
@@ -113,10 +115,17 @@ __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __re
   const int sub = (lane / CL) * E;  // first entry of this sub-group inside a batch of L
   const int64_t row = xcd_tile() * G + threadIdx.x / L;
   if (row >= n) return;  // uniform over the L-lane group
-  const int64_t e1 = rowptr[row + 1];
+  const int64_t e0 = rowptr[row], e1 = rowptr[row + 1];
   double acc0 = 0.0, acc1 = 0.0;
   const double2* __restrict__ z2 = reinterpret_cast<const double2*>(z);
-  for (int64_t e = rowptr[row]; e < e1; e += L) {
+  double2 cur = {0.0, 0.0}, pv = {0.0, 0.0};
+  if constexpr (MODE == 2) {
+    if (lane < CL) {  // the recurrence's own-row operands, requested ahead of the gathers
+      cur = z2[row * CL + tl];
+      if (beta != 0.0) pv = reinterpret_cast<const double2*>(uprev)[row * CL + tl];
+    }
+  }
+  for (int64_t e = e0; e < e1; e += L) {
     // lanes past the end of the row carry (column 0, value 0): their products vanish
     int32_t c = 0;
     double a = 0.0;
@@ -149,35 +158,44 @@ __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __re
     acc1 += __shfl_xor(acc1, o, L);
   }
   if (lane < CL) {
-    const double sr = s[row];
-    if constexpr (CHEB) {
-      const int64_t o = row * CL + tl;
-      const double2 cur = z2[o];
+    if constexpr (MODE == 2) {
       double2 out;
-      out.x = alpha * (sr * sr * acc0 - shift * cur.x);
-      out.y = alpha * (sr * sr * acc1 - shift * cur.y);
-      if (beta != 0.0) {
-        const double2 pv = reinterpret_cast<const double2*>(uprev)[o];
-        out.x -= beta * pv.x;
-        out.y -= beta * pv.y;
-      }
-      reinterpret_cast<double2*>(y)[o] = out;
+      out.x = alpha * (acc0 - shift * cur.x) - beta * pv.x;
+      out.y = alpha * (acc1 - shift * cur.y) - beta * pv.y;
+      reinterpret_cast<double2*>(y)[row * CL + tl] = out;
     } else {
-      y[row * ldy + 2 * tl] = sr * acc0;
-      y[row * ldy + 2 * tl + 1] = sr * acc1;
+      const double sr = MODE == 0 ? s[row] : 1.0;
+      if (vec_store) {  // one 16-byte store (y + row * ldy is 16-byte aligned)
+        double2 out;
+        out.x = sr * acc0;
+        out.y = sr * acc1;
+        *reinterpret_cast<double2*>(y + row * ldy + 2 * tl) = out;
+      } else {
+        y[row * ldy + 2 * tl] = sr * acc0;
+        y[row * ldy + 2 * tl + 1] = sr * acc1;
+      }
     }
   }
 }
 
-// basis[i, col0 + t] = u[i * b + t] / s[i]: back from the s-scaled iterate of the Chebyshev recurrence
-__global__ __launch_bounds__(kThreads) void unscale_cols_kernel(const double* __restrict__ u,
-                                                                const double* __restrict__ s, double* __restrict__ basis,
-                                                                int64_t ld, int col0, int b, int64_t n) {
-  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (idx >= n * b) return;
-  const int64_t i = idx / b;
-  const int t = (int)(idx - i * b);
-  basis[i * ld + col0 + t] = u[idx] / s[i];
+// val_out[e] = s_i * val[e] * s_j for entry e = (i, j): the scaled copy of the operator.  The same rounding for
+// (i, j) and (j, i), so the copy is exactly symmetric when W is.  val_out may be val.
+__global__ __launch_bounds__(kThreads) void scale_values_kernel(const int64_t* __restrict__ rowptr,
+                                                                const int32_t* __restrict__ col, const double* val,
+                                                                const double* __restrict__ s, double* val_out,
+                                                                int64_t n) {
+  constexpr int L = 16;  // lanes per row
+  const int lane = threadIdx.x % L;
+  const int64_t row = (int64_t)blockIdx.x * (kThreads / L) + threadIdx.x / L;
+  if (row >= n) return;
+  const double si = s[row];
+  const int64_t e1 = rowptr[row + 1];
+  for (int64_t e = rowptr[row] + lane; e < e1; e += L) {
+    const int32_t c = col[e];
+    const double sj = s[c];
+    const double ss = (int64_t)c < row ? sj * si : si * sj;
+    val_out[e] = val[e] * ss;
+  }
 }
 
 // L lanes per row, each lane walks the entries of the row with stride L and keeps B accumulators
@@ -627,7 +645,7 @@ __global__ __launch_bounds__(kThreads) void apply_rinv_kernel(double* __restrict
   for (int q = 0; q <= t; ++q) acc += Wt[rl * (b + 1) + q] * Ri[q][t];
   if (row < n) {
     basis[row * ld + col0 + t] = acc;
-    if (z) z[row * b + t] = s[row] * acc;
+    if (z) z[row * b + t] = s ? s[row] * acc : acc;
   }
 }
 
@@ -706,13 +724,17 @@ __global__ __launch_bounds__(kThreads) void cheb_combine_kernel(const double* __
 // fused pieces of the block step
 // --------------------------------------------------------------------------------------------
 // Second CGS2 update fused with the Gram matrix of the updated block:
-//   basis[:, ccol0 : ccol0+b] -= basis[:, 0 : kdim] * bmat,   gpart[blockIdx.x] = sum over this workgroup's
-//   rows of W_new^T W_new.
+//   basis[:, ccol0 : ccol0+b] -= basis[:, acol0 : acol0+kdim] * bmat,   gpart[blockIdx.x] = sum over this
+//   workgroup's rows of W_new^T W_new.
+// overwrite != 0: the product replaces the block instead of being subtracted from it.  With acol0 = ccol0, kdim = b
+// and bmat = R^-1 this is the scaling pass W <- W R^-1 of the Cholesky QR (a wave reads its own 32 rows of the
+// block completely before it writes them).
 // Workgroups walk the 128-row tiles with a grid stride, so the number of Gram partials is the grid size.
 template <int NT>
 __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
                                                                int acol0, int kdim, const double* __restrict__ bmat, int b,
-                                                               int ccol0, int vec_ok, double* __restrict__ gpart) {
+                                                               int ccol0, int vec_ok, int overwrite,
+                                                               double* __restrict__ gpart) {
   constexpr int MT = 2;
   constexpr int BW = NT * 16;
   constexpr int KC = 4096 / BW;
@@ -813,7 +835,7 @@ __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restric
           double nv = 0.0;
           if (row < n && t < b) {
             double* p = basis + row * ld + ccol0 + t;
-            nv = *p - acc[mt][nt][rr];
+            nv = overwrite ? acc[mt][nt][rr] : *p - acc[mt][nt][rr];
             *p = nv;
           }
           wt[lr * WP + t] = nv;
@@ -852,69 +874,6 @@ __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restric
 #pragma unroll
       for (int w = 1; w < 4; ++w) tot += lds[(w * BW + c1) * BW + c2];
       gpart[((int64_t)blockIdx.x * b + c1) * kPartialPad + c2] = tot;
-    }
-  }
-}
-
-// basis[:, col0 : col0+b] *= rinv (as apply_rinv_kernel) fused with the Gram matrix of the result;
-// grid-stride over groups of 256/b rows, one Gram partial per workgroup.  For the Gram sums the 256 threads are
-// split into NS = max(1, 256/b^2) row subsets per matrix entry, combined in subset order at the end.
-__global__ __launch_bounds__(kThreads) void apply_gram_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
-                                                              int col0, int b, const double* __restrict__ rinv,
-                                                              double* __restrict__ gpart) {
-  __shared__ double Ri[kMaxBlock][kMaxBlock + 1];
-  __shared__ double Wt[2 * kThreads];
-  __shared__ double Qt[2 * kThreads];
-  for (int e = threadIdx.x; e < b * b; e += kThreads) Ri[e / b][e % b] = rinv[(e / b) * kPartialPad + (e % b)];
-  const int rows_per = kThreads / b;
-  const int t = threadIdx.x % b, rl = threadIdx.x / b;
-  const int64_t ngroups = (n + rows_per - 1) / rows_per;
-  const int bb = b * b;
-  const int ns = bb >= kThreads ? 1 : kThreads / bb;  // row subsets per entry (b <= 8)
-  const int ent = threadIdx.x % bb, sub = threadIdx.x / bb;  // used when bb <= 256
-  double gacc[4] = {0.0, 0.0, 0.0, 0.0};
-  for (int64_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
-    const int64_t row = grp * rows_per + rl;
-    __syncthreads();
-    Wt[rl * (b + 1) + t] = row < n ? basis[row * ld + col0 + t] : 0.0;
-    __syncthreads();
-    double acc = 0.0;
-    for (int q = 0; q <= t; ++q) acc += Wt[rl * (b + 1) + q] * Ri[q][t];
-    if (row < n) basis[row * ld + col0 + t] = acc;
-    Qt[rl * (b + 1) + t] = row < n ? acc : 0.0;
-    __syncthreads();
-    if (bb <= kThreads) {
-      if (sub < ns) {
-        const int c1 = ent / b, c2 = ent % b;
-        double v = gacc[0];
-        for (int r = sub; r < rows_per; r += ns) v += Qt[r * (b + 1) + c1] * Qt[r * (b + 1) + c2];
-        gacc[0] = v;
-      }
-    } else {
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int e = threadIdx.x + u * kThreads;
-        const int c1 = e / b, c2 = e % b;
-        double v = gacc[u];
-        for (int r = 0; r < rows_per; ++r) v += Qt[r * (b + 1) + c1] * Qt[r * (b + 1) + c2];
-        gacc[u] = v;
-      }
-    }
-  }
-  if (bb <= kThreads) {
-    __syncthreads();
-    Wt[threadIdx.x] = gacc[0];  // [sub][ent]
-    __syncthreads();
-    if (threadIdx.x < bb) {
-      double tot = Wt[threadIdx.x];
-      for (int q = 1; q < ns; ++q) tot += Wt[q * bb + threadIdx.x];
-      gpart[((int64_t)blockIdx.x * b + threadIdx.x / b) * kPartialPad + (threadIdx.x % b)] = tot;
-    }
-  } else {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int e = threadIdx.x + u * kThreads;
-      gpart[((int64_t)blockIdx.x * b + e / b) * kPartialPad + (e % b)] = gacc[u];
     }
   }
 }
@@ -1108,39 +1067,33 @@ static int spmm_lanes(int b, double avg_deg) {
   }();
   int lanes = b;
   while (lanes < 32 && lanes < avg_deg) lanes *= 2;
-  if (forced >= b && forced <= 64 && (forced & (forced - 1)) == 0) lanes = forced;
+  if (forced >= b && forced <= 32 && (forced & (forced - 1)) == 0) lanes = forced;
   return lanes;
 }
 
-template <bool CHEB>
-static hipError_t launch_spmm_cols(const int64_t* rowptr, const int32_t* col, const double* val, const double* s,
-                                   int64_t n, const double* z, int b, double* y, int64_t ldy, double avg_deg,
-                                   const double* uprev, double alpha, double shift, double beta, hipStream_t st) {
-#define SC_LAUNCH_COLS(BB, LL)                                                                              \
-  hipLaunchKernelGGL((spmm_cols_kernel<BB, LL, CHEB>), dim3(xcd_grid(ceil_div64(n, kThreads / LL))),          \
-                     dim3(kThreads), 0, st, rowptr, col, val, s, z, y, ldy, n, uprev, alpha, shift, beta)
+template <int MODE>
+static hipError_t launch_spmm_cols_t(const int64_t* rowptr, const int32_t* col, const double* val, const double* s,
+                                     int64_t n, const double* z, int b, double* y, int64_t ldy, double avg_deg,
+                                     const double* uprev, double alpha, double shift, double beta, hipStream_t st) {
+  const int vec_store = (ldy % 2 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0) ? 1 : 0;
+#define SC_LAUNCH_COLS(BB, LL)                                                                                \
+  hipLaunchKernelGGL((spmm_cols_kernel<BB, LL, MODE>), dim3(xcd_grid(ceil_div64(n, kThreads / LL))),            \
+                     dim3(kThreads), 0, st, rowptr, col, val, s, z, y, ldy, n, vec_store, uprev, alpha, shift, beta)
   switch (b) {
     case 8:
       switch (spmm_lanes(8, avg_deg)) {
         case 8: SC_LAUNCH_COLS(8, 8); break;
         case 16: SC_LAUNCH_COLS(8, 16); break;
-        case 32: SC_LAUNCH_COLS(8, 32); break;
-        default: SC_LAUNCH_COLS(8, 64); break;
+        default: SC_LAUNCH_COLS(8, 32); break;
       }
       break;
     case 16:
       switch (spmm_lanes(16, avg_deg)) {
         case 16: SC_LAUNCH_COLS(16, 16); break;
-        case 32: SC_LAUNCH_COLS(16, 32); break;
-        default: SC_LAUNCH_COLS(16, 64); break;
+        default: SC_LAUNCH_COLS(16, 32); break;
       }
       break;
-    case 32:
-      switch (spmm_lanes(32, avg_deg)) {
-        case 32: SC_LAUNCH_COLS(32, 32); break;
-        default: SC_LAUNCH_COLS(32, 64); break;
-      }
-      break;
+    case 32: SC_LAUNCH_COLS(32, 32); break;
     default: return hipErrorInvalidValue;
   }
 #undef SC_LAUNCH_COLS
@@ -1153,22 +1106,28 @@ hipError_t launch_spmm(const int64_t* rowptr, const int32_t* col, const double* 
     case 1: return launch_spmm_nz<1>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
     case 2: return launch_spmm_nz<2>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
     case 4: return launch_spmm_nz<4>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
-    default: return launch_spmm_cols<false>(rowptr, col, val, s, n, z, b, y, ldy, avg_deg, nullptr, 0.0, 0.0, 0.0, st);
+    default:
+      return launch_spmm_cols_t<0>(rowptr, col, val, s, n, z, b, y, ldy, avg_deg, nullptr, 0.0, 0.0, 0.0, st);
   }
 }
 
-hipError_t launch_spmm_cheb(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
-                            const double* ucur, int b, const double* uprev, double* unext, double alpha, double shift,
-                            double beta, double avg_deg, hipStream_t st) {
-  if (b < 8) return hipErrorInvalidValue;
-  return launch_spmm_cols<true>(rowptr, col, val, s, n, ucur, b, unext, b, avg_deg, uprev, alpha, shift, beta, st);
+hipError_t launch_scale_values(const int64_t* rowptr, const int32_t* col, const double* val, const double* s,
+                               double* val_out, int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(scale_values_kernel, dim3((unsigned)ceil_div64(n, kThreads / 16)), dim3(kThreads), 0, st, rowptr,
+                     col, val, s, val_out, n);
+  return hipGetLastError();
 }
 
-hipError_t launch_unscale_cols(const double* u, const double* s, double* basis, int64_t ld, int col0, int b, int64_t n,
-                               hipStream_t st) {
-  hipLaunchKernelGGL(unscale_cols_kernel, dim3((unsigned)ceil_div64(n * b, kThreads)), dim3(kThreads), 0, st, u, s,
-                     basis, ld, col0, b, n);
-  return hipGetLastError();
+hipError_t launch_spmm_vals(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n, const double* x,
+                            int b, double* y, int64_t ldy, double avg_deg, hipStream_t st) {
+  return launch_spmm_cols_t<1>(rowptr, col, val, nullptr, n, x, b, y, ldy, avg_deg, nullptr, 0.0, 0.0, 0.0, st);
+}
+
+hipError_t launch_spmm_vals_cheb(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n,
+                                 const double* ucur, int b, const double* uprev, double* unext, double alpha,
+                                 double shift, double beta, double avg_deg, hipStream_t st) {
+  return launch_spmm_cols_t<2>(rowptr, col, val, nullptr, n, ucur, b, unext, b, avg_deg, uprev, alpha, shift, beta, st);
 }
 
 ProjectPlan plan_project(int64_t n, int ja, int max_partials) {
@@ -1260,28 +1219,16 @@ int plan_update_gram(int64_t n) {
 }
 
 hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int b,
-                              int ccol0, double* gpart, hipStream_t st) {
+                              int ccol0, int overwrite, double* gpart, hipStream_t st) {
   const int vec_ok = (ld % 4 == 0 && acol0 % 4 == 0 && (reinterpret_cast<uintptr_t>(basis) % 32 == 0)) ? 1 : 0;
   const unsigned grid = (unsigned)plan_update_gram(n);
   if (b <= 16) {
     hipLaunchKernelGGL((update_gram_kernel<1>), dim3(grid), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, bmat, b,
-                       ccol0, vec_ok, gpart);
+                       ccol0, vec_ok, overwrite, gpart);
   } else {
     hipLaunchKernelGGL((update_gram_kernel<2>), dim3(grid), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, bmat, b,
-                       ccol0, vec_ok, gpart);
+                       ccol0, vec_ok, overwrite, gpart);
   }
-  return hipGetLastError();
-}
-
-int plan_apply_gram(int64_t n, int b) {
-  const int64_t groups = (n + (kThreads / b) - 1) / (kThreads / b);
-  return (int)(groups < 512 ? groups : 512);
-}
-
-hipError_t launch_apply_gram(double* basis, int64_t n, int64_t ld, int col0, int b, const double* rinv, double* gpart,
-                             hipStream_t st) {
-  hipLaunchKernelGGL(apply_gram_kernel, dim3((unsigned)plan_apply_gram(n, b)), dim3(kThreads), 0, st, basis, n, ld,
-                     col0, b, rinv, gpart);
   return hipGetLastError();
 }
 
