@@ -624,20 +624,22 @@ struct Solver {
 
       // ---- start block
       HIP_TRY(launch_random_block(basis.p, n, ld, nl, b, seed, stream_id++, st));
-      const int ngram0 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
-      enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram0, gram(), rinv(), r1(), slot(0) + kPP * kPP,
-                       slot(0) + 2 * kPP * kPP, z.p, zs(), st, &timer);
       bool filtered = filt_d > 0;
       if (filtered) {
+        // the filter is linear and takes the random block as it is, after one projection pass against the locked
+        // vectors: their eigenvalues lie above the damped interval too, so what the block holds along them is
+        // amplified like the wanted directions, and removing it afterwards is only as exact as the locked vectors
         if (debug_on())
           std::fprintf(stderr, "[sceig] t=%.4fs phase %d start block filtered: degree %d, damped interval [-1, %.6f]\n",
                        now_s() - t_begin, stats.phases, filt_d, filt_a);
+        (void)enqueue_cgs2(basis.p, n, ld, nl, nl, b, nl, part.p, h1.p, hsum.p, nullptr, 0, nullptr, st, &timer);
+        HIP_TRY(launch_pack_scaled(basis.p + nl, ld, zs(), n, b, z.p, st));
         apply_start_filter(filt_d, filt_a);
-        const int ngram1 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
-        enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram1, gram(), rinv(), r1(), slot(0) + kPP * kPP,
-                         slot(0) + 2 * kPP * kPP, z.p, zs(), st, &timer);
         filt_d = 0;
       }
+      const int ngram0 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
+      enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram0, gram(), rinv(), r1(), slot(0) + kPP * kPP,
+                       slot(0) + 2 * kPP * kPP, z.p, zs(), st, &timer);
       int ja = b;            // active columns whose coupling is (or will be) assembled
       int assembled = 0;     // active columns of T that are final (their block has been multiplied by S)
       int next_slot = 1;     // slot 0 = start block QR
