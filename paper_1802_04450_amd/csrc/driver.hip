@@ -237,11 +237,12 @@ constexpr int kGramPartials = 1024;
 // component is contiguous (stable inside a component).  The sparse products then gather from a few hundred KB at
 // a time instead of from all over the vector; mathematically the result is a permutation similarity of the input.
 // Outputs: permuted CSR (device, caller-allocated, same sizes as the input), old_of_new (device int32[n]: original
-// index of each new row), optionally the component index of each new row (host).  Returns the component count.
+// index of each new row), optionally new_of_old (device int32[n], the inverse map) and the component index of each
+// new row (host).  Returns the component count.
 int reorder_csr(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n, int64_t nnz,
                 int64_t* rowptr_out, int32_t* col_out, double* val_out, int32_t* old_of_new_out,
-                std::vector<int32_t>* comp_of_new, hipStream_t st) {
-  DevBuf<int32_t> label, new_of_old_d;
+                int32_t* new_of_old_out, std::vector<int32_t>* comp_of_new, hipStream_t st) {
+  DevBuf<int32_t> label, new_of_old_own;
   DevBuf<int> flag;
   label.alloc((size_t)n);
   flag.alloc(1);
@@ -279,11 +280,15 @@ int reorder_csr(const int64_t* rowptr, const int32_t* col, const double* val, in
   }
   rp_new[0] = 0;
   for (int64_t p = 0; p < n; ++p) rp_new[p + 1] = rp_new[p] + (rp[old_of_new[p] + 1] - rp[old_of_new[p]]);
-  new_of_old_d.alloc((size_t)n);
+  int32_t* new_of_old_dev = new_of_old_out;
+  if (!new_of_old_dev) {
+    new_of_old_own.alloc((size_t)n);
+    new_of_old_dev = new_of_old_own.p;
+  }
   HIP_TRY(hipMemcpyAsync(rowptr_out, rp_new.data(), ((size_t)n + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
   HIP_TRY(hipMemcpyAsync(old_of_new_out, old_of_new.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
-  HIP_TRY(hipMemcpyAsync(new_of_old_d.p, new_of_old.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
-  HIP_TRY(launch_permute_csr(rowptr, col, val, old_of_new_out, new_of_old_d.p, rowptr_out, col_out, val_out, n, st));
+  HIP_TRY(hipMemcpyAsync(new_of_old_dev, new_of_old.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  HIP_TRY(launch_permute_csr(rowptr, col, val, old_of_new_out, new_of_old_dev, rowptr_out, col_out, val_out, n, st));
   HIP_TRY(hipStreamSynchronize(st));  // the host vectors above are pageable and go out of scope
   (void)nnz;
   return ncomp;
@@ -307,10 +312,11 @@ struct Solver {
   DevBuf<double> basis, s, z, part, gpart, h1, hsum, small, slots, yd, rot;
   DevBuf<int> flag;
   DevBuf<int64_t> rowptr_p;
-  DevBuf<int32_t> col_p, old_of_new_d, comp_d, perm_d;
+  DevBuf<int32_t> col_p, old_of_new_d, new_of_old_d, comp_d, perm_d;
   DevBuf<double> val_p, coef_d;
   DevBuf<double> val_s;  // S_ij = s_i W_ij s_j multiplied out: the operator copy used when b >= 8
   const int32_t* rowmap = nullptr;  // device: original row of each internal row, null if not reordered
+  const int32_t* rowinv = nullptr;  // device: internal row of each original row, null if not reordered
   std::vector<int32_t> comp_host;   // component index of each internal row (only after reorder())
   int ncomp = 0;
   PinnedBuf<double> slots_host;
@@ -353,11 +359,14 @@ struct Solver {
     col_p.alloc((size_t)nnz);
     val_p.alloc((size_t)nnz);
     old_of_new_d.alloc((size_t)n);
-    ncomp = reorder_csr(rowptr, col, val, n, nnz, rowptr_p.p, col_p.p, val_p.p, old_of_new_d.p, &comp_host, st);
+    new_of_old_d.alloc((size_t)n);
+    ncomp = reorder_csr(rowptr, col, val, n, nnz, rowptr_p.p, col_p.p, val_p.p, old_of_new_d.p, new_of_old_d.p, &comp_host,
+                        st);
     rowptr = rowptr_p.p;
     col = col_p.p;
     val = val_p.p;
     rowmap = old_of_new_d.p;
+    rowinv = new_of_old_d.p;
   }
 
   // Optional: the closed-form null vectors D^1/2 1_C / sqrt(vol C) of the first min(k, ncomp) components are
@@ -398,7 +407,9 @@ struct Solver {
     HIP_TRY(hipMemcpyAsync(&hflag, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     if (hflag & 3) SC_THROW(SC_ECSR);
+    const double t1 = now_s();
     if (!(flags & SC_FLAG_NO_REORDER)) reorder();
+    const double t2 = now_s();
     s.alloc((size_t)n);
     HIP_TRY(launch_degree_scaling(rowptr, val, n, nullptr, s.p, flag.p, st));
     HIP_TRY(hipMemcpyAsync(&hflag, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
@@ -409,6 +420,7 @@ struct Solver {
       val_s.alloc((size_t)nnz);
       HIP_TRY(launch_scale_values(rowptr, col, val, s.p, val_s.p, n, st));
     }
+    const double t3 = now_s();
 
     ld = ((int64_t)m + b + 15) / 16 * 16;
     basis.alloc((size_t)n * ld);
@@ -430,6 +442,9 @@ struct Solver {
     if ((flags & SC_FLAG_COMPONENT_NULLSPACE) && !(flags & SC_FLAG_NO_REORDER)) lock_component_nullspace();
     stats.components = ncomp;
     stats.t_setup = now_s() - t0;
+    if (debug_on())
+      std::fprintf(stderr, "[sceig] setup parts: validate %.0f us, reorder %.0f us, degrees+scaling %.0f us, buffers %.0f us\n",
+                   (t1 - t0) * 1e6, (t2 - t1) * 1e6, (t3 - t2) * 1e6, (now_s() - t3) * 1e6);
     if (debug_on()) std::fprintf(stderr, "[sceig] setup %.3fs: n=%lld nnz=%lld components=%d m=%d b=%d locked=%d\n",
                                  stats.t_setup, (long long)n, (long long)nnz, ncomp, m, b, nl);
   }
@@ -920,7 +935,7 @@ struct Solver {
       order.resize(nfound);
       for (int t = 0; t < nfound; ++t) evals_host[t] = 1.0 - theta_locked[order[t]];
       HIP_TRY(hipMemcpyAsync(perm_d.p, order.data(), (size_t)nfound * sizeof(int32_t), hipMemcpyHostToDevice, st));
-      HIP_TRY(launch_gather_cols_colmajor(basis.p, n, ld, perm_d.p, nfound, evecs_out, rowmap, st));
+      HIP_TRY(launch_gather_cols_colmajor(basis.p, n, ld, perm_d.p, nfound, evecs_out, rowinv, st));
       HIP_TRY(hipStreamSynchronize(st));  // `order` is pageable host memory
     } else if (nx > 0) {
       std::vector<double> G((size_t)nx * nx, 0.0), hbuf((size_t)nx * kPP);
@@ -1154,7 +1169,7 @@ int sc_reorder_csr(const int64_t* csr_rowptr, const int32_t* csr_col, const doub
         int64_t nnz = 0;
         HIP_TRY(hipMemcpyAsync(&nnz, c->rp + c->n, sizeof(int64_t), hipMemcpyDeviceToHost, c->st));
         HIP_TRY(hipStreamSynchronize(c->st));
-        const int ncomp = reorder_csr(c->rp, c->c, c->v, c->n, nnz, c->rpo, c->co, c->vo, c->oon, nullptr, c->st);
+        const int ncomp = reorder_csr(c->rp, c->c, c->v, c->n, nnz, c->rpo, c->co, c->vo, c->oon, nullptr, nullptr, c->st);
         if (c->nc) *c->nc = ncomp;
         return SC_OK;
       },

@@ -680,27 +680,28 @@ __global__ __launch_bounds__(kThreads) void copy_cols_kernel(const double* __res
   dst[i * ldd + dcol0 + t] = src[i * lds + scol0 + t];
 }
 
-// out[t * n + r(i)] = basis[i * ld + perm[t]] for t < k: selected columns of the row-major basis, written column-major
-// (r(i) = rowmap[i] if rowmap is given, else i).  A workgroup moves a 64 x 64 tile through LDS so that both the reads
-// (along a basis row) and the writes (along an output column) run over consecutive addresses.
+// out[t * n + o] = basis[r(o) * ld + perm[t]] for t < k: selected columns of the row-major basis, written column-major
+// in the caller's row numbering (r(o) = inv[o], the internal row of original row o, if inv is given, else o).  A
+// workgroup moves a 64 x 64 tile through LDS: the reads run along basis rows (whole 512-byte pieces of the rows the
+// permutation points to), the writes along output columns over consecutive addresses.
 __global__ __launch_bounds__(kThreads) void gather_cols_colmajor_kernel(const double* __restrict__ basis, int64_t n,
                                                                         int64_t ld, const int32_t* __restrict__ perm,
                                                                         int k, double* __restrict__ out,
-                                                                        const int32_t* __restrict__ rowmap) {
+                                                                        const int32_t* __restrict__ inv) {
   __shared__ double tile[64][65];
   const int64_t i0 = (int64_t)blockIdx.x * 64;
   const int c0 = blockIdx.y * 64;
   for (int idx = threadIdx.x; idx < 64 * 64; idx += kThreads) {
     const int r = idx / 64, c = idx % 64;
-    if (i0 + r < n && c0 + c < k) tile[c][r] = basis[(i0 + r) * ld + perm[c0 + c]];
+    if (i0 + r < n && c0 + c < k) {
+      const int64_t src = inv ? (int64_t)inv[i0 + r] : i0 + r;
+      tile[c][r] = basis[src * ld + perm[c0 + c]];
+    }
   }
   __syncthreads();
   for (int idx = threadIdx.x; idx < 64 * 64; idx += kThreads) {
     const int c = idx / 64, r = idx % 64;
-    if (i0 + r < n && c0 + c < k) {
-      const int64_t dst = rowmap ? (int64_t)rowmap[i0 + r] : i0 + r;
-      out[(int64_t)(c0 + c) * n + dst] = tile[c][r];
-    }
+    if (i0 + r < n && c0 + c < k) out[(int64_t)(c0 + c) * n + i0 + r] = tile[c][r];
   }
 }
 
@@ -1255,10 +1256,10 @@ hipError_t launch_copy_cols(const double* src, int64_t lds, int scol0, double* d
 }
 
 hipError_t launch_gather_cols_colmajor(const double* basis, int64_t n, int64_t ld, const int32_t* perm, int k, double* out,
-                                       const int32_t* rowmap, hipStream_t st) {
+                                       const int32_t* inv, hipStream_t st) {
   if (n <= 0 || k <= 0) return hipSuccess;
   hipLaunchKernelGGL(gather_cols_colmajor_kernel, dim3((unsigned)ceil_div64(n, 64), (unsigned)((k + 63) / 64)),
-                     dim3(kThreads), 0, st, basis, n, ld, perm, k, out, rowmap);
+                     dim3(kThreads), 0, st, basis, n, ld, perm, k, out, inv);
   return hipGetLastError();
 }
 
