@@ -24,6 +24,7 @@
  *     n x ncols block with leading dimension ld lives at base[i * ld + c].  The final eigenvector
  *     output of sc_laplacian_eigsh is COLUMN-MAJOR (vector t contiguous at evecs_out + t * n).
  *   - Calls that use the same stream or the same buffers must not overlap.
+ *   - Workspace of a call is allocated inside it and cached between calls: see sc_release_cache().
  */
 #ifndef SCEIG_H
 #define SCEIG_H
@@ -226,6 +227,16 @@ int sc_sym_eig_top(const double* a, int32_t n, int32_t count, double* w, double*
 
 const char* sc_strerror(int code);
 int sc_version(void);
+
+/*
+ * Memory.  Device and pinned-host blocks that a call allocates for itself are kept by the library when the call
+ * returns and handed to later calls that ask for a block of exactly the same size on the same device (a repeated
+ * solve of one problem shape then allocates nothing).  At most 4 GiB of device memory (and as much pinned memory)
+ * are held this way; the environment variable SCEIG_CACHE_LIMIT_MB, read once, sets another limit, 0 switches the
+ * caching off.  sc_release_cache() gives everything held back to the HIP runtime; call it only while no other call
+ * into the library is running.  Returns SC_OK.
+ */
+int sc_release_cache(void);
 
 #ifdef __cplusplus
 }

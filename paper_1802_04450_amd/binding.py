@@ -24,7 +24,7 @@ SC_FLAG_FINAL_RR = 16
 FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 
 EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_reorder_csr", "sc_cgs2",
-           "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version"]
+           "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version", "sc_release_cache"]
 
 
 class ScOptions(ctypes.Structure):
@@ -87,7 +87,13 @@ def lib() -> ctypes.CDLL:
         _lib.sc_strerror.restype = ctypes.c_char_p
         _lib.sc_strerror.argtypes = [ctypes.c_int]
         _lib.sc_version.argtypes = []
+        _lib.sc_release_cache.argtypes = []
     return _lib
+
+
+def sc_release_cache() -> int:
+    """Give the device and pinned blocks the library keeps between calls back to the HIP runtime."""
+    return int(lib().sc_release_cache())
 
 
 def strerror(code: int) -> str:

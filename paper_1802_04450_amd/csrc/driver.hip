@@ -23,6 +23,8 @@
 #include <cstdlib>
 #include <cstring>
 #include <limits>
+#include <map>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <vector>
@@ -64,20 +66,109 @@ double now_s() {
   return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
 
+// Device and pinned-host blocks released by a call are kept for the next call instead of going back to the driver
+// (hipMalloc / hipFree / hipHostMalloc cost tens of microseconds each and hipFree synchronises the device; a solve
+// makes about thirty of them).  A block is reused only for a request of exactly its size on the same device, which is
+// what repeated solves of one problem shape ask for.  Every entry point synchronises its stream before it returns, so
+// no kernel of the releasing call can still be using a block when it is handed out again.  The cache holds at most
+// `limit` bytes per kind (default 4 GiB, SCEIG_CACHE_LIMIT_MB overrides, 0 switches caching off); sc_release_cache()
+// empties it.
+class BlockCache {
+ public:
+  explicit BlockCache(bool pinned) : pinned_(pinned) {
+    const char* e = std::getenv("SCEIG_CACHE_LIMIT_MB");
+    limit_ = e ? (size_t)std::strtoull(e, nullptr, 10) << 20 : (size_t)4 << 30;
+  }
+  hipError_t get(size_t bytes, void** p) {
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    {
+      std::lock_guard<std::mutex> lock(mu_);
+      auto range = blocks_.equal_range(bytes);
+      for (auto it = range.first; it != range.second; ++it) {
+        if (it->second.dev == dev) {
+          *p = it->second.p;
+          blocks_.erase(it);
+          held_ -= bytes;
+          return hipSuccess;
+        }
+      }
+    }
+    return pinned_ ? hipHostMalloc(p, bytes, hipHostMallocDefault) : hipMalloc(p, bytes);
+  }
+  void put(void* p, size_t bytes) {
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    {
+      std::lock_guard<std::mutex> lock(mu_);
+      if (held_ + bytes <= limit_) {
+        blocks_.emplace(bytes, Block{p, dev});
+        held_ += bytes;
+        return;
+      }
+    }
+    if (pinned_) {
+      (void)hipHostFree(p);
+    } else {
+      (void)hipFree(p);
+    }
+  }
+  void clear() {
+    std::lock_guard<std::mutex> lock(mu_);
+    int cur = 0;
+    (void)hipGetDevice(&cur);
+    for (auto& kv : blocks_) {
+      if (pinned_) {
+        (void)hipHostFree(kv.second.p);
+      } else {
+        (void)hipSetDevice(kv.second.dev);
+        (void)hipFree(kv.second.p);
+      }
+    }
+    (void)hipSetDevice(cur);
+    blocks_.clear();
+    held_ = 0;
+  }
+
+ private:
+  struct Block {
+    void* p;
+    int dev;
+  };
+  bool pinned_;
+  size_t limit_ = 0, held_ = 0;
+  std::mutex mu_;
+  std::multimap<size_t, Block> blocks_;
+};
+
+BlockCache& device_cache() {
+  static BlockCache* c = new BlockCache(false);  // never destroyed: the HIP runtime may be gone at exit
+  return *c;
+}
+BlockCache& pinned_cache() {
+  static BlockCache* c = new BlockCache(true);
+  return *c;
+}
+
 template <typename T>
 struct DevBuf {
   T* p = nullptr;
+  size_t bytes = 0;
   DevBuf() = default;
   DevBuf(const DevBuf&) = delete;
   DevBuf& operator=(const DevBuf&) = delete;
   void alloc(size_t count) {
     release();
     if (count == 0) count = 1;
-    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p), count * sizeof(T)));
+    void* q = nullptr;
+    HIP_TRY(device_cache().get(count * sizeof(T), &q));
+    p = static_cast<T*>(q);
+    bytes = count * sizeof(T);
   }
   void release() {
-    if (p) (void)hipFree(p);
+    if (p) device_cache().put(p, bytes);
     p = nullptr;
+    bytes = 0;
   }
   ~DevBuf() { release(); }
 };
@@ -85,17 +176,22 @@ struct DevBuf {
 template <typename T>
 struct PinnedBuf {
   T* p = nullptr;
+  size_t bytes = 0;
   PinnedBuf() = default;
   PinnedBuf(const PinnedBuf&) = delete;
   PinnedBuf& operator=(const PinnedBuf&) = delete;
   void alloc(size_t count) {
     release();
     if (count == 0) count = 1;
-    HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&p), count * sizeof(T), hipHostMallocDefault));
+    void* q = nullptr;
+    HIP_TRY(pinned_cache().get(count * sizeof(T), &q));
+    p = static_cast<T*>(q);
+    bytes = count * sizeof(T);
   }
   void release() {
-    if (p) (void)hipHostFree(p);
+    if (p) pinned_cache().put(p, bytes);
     p = nullptr;
+    bytes = 0;
   }
   ~PinnedBuf() { release(); }
 };
@@ -109,6 +205,7 @@ struct KTimer {
     int fam;
     hipEvent_t a, b;
     double bytes, flops;
+    int launches;
   };
   std::vector<Rec> recs;
   hipEvent_t cur = nullptr;
@@ -118,12 +215,13 @@ struct KTimer {
     HIP_TRY(hipEventCreate(&cur));
     HIP_TRY(hipEventRecord(cur, st));
   }
-  void end(int fam, double bytes, double flops) {
+  // bytes, flops: totals of the `launches` back-to-back launches between begin() and this call
+  void end(int fam, double bytes, double flops, int launches = 1) {
     if (!on(fam)) return;
     hipEvent_t e;
     HIP_TRY(hipEventCreate(&e));
     HIP_TRY(hipEventRecord(e, st));
-    recs.push_back(Rec{fam, cur, e, bytes, flops});
+    recs.push_back(Rec{fam, cur, e, bytes, flops, launches});
     cur = nullptr;
   }
   // after the stream has been synchronised
@@ -132,7 +230,7 @@ struct KTimer {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
         out->fam_time_s[r.fam] += (double)ms * 1e-3;
-        out->fam_launches[r.fam] += 1;
+        out->fam_launches[r.fam] += r.launches;
         out->fam_bytes[r.fam] += r.bytes;
         out->fam_flops[r.fam] += r.flops;
       }
@@ -482,11 +580,10 @@ struct Solver {
       double* cur = z.p;
       double* prev = rot.p;
       double* next = rot.p + (size_t)n * b;
+      timer.begin(kFamSpmm);  // one event pair round the d back-to-back launches
       for (int i = 0; i < d; ++i) {
-        timer.begin(kFamSpmm);
         HIP_TRY(launch_spmm_vals_cheb(rowptr, col, val_s.p, n, cur, b, prev, next, i == 0 ? 1.0 / e : 2.0 / e, c,
                                       i == 0 ? 0.0 : 1.0, avg_deg, st));
-        timer.end(kFamSpmm, spmm_bytes() + (i == 0 ? 0.0 : 8.0 * (double)n * b), 2.0 * (double)nnz * b);
         double* t = prev;
         prev = cur;
         cur = next;
@@ -494,6 +591,7 @@ struct Solver {
         stats.spmv_cols += b;
         stats.filter_steps += 1;
       }
+      timer.end(kFamSpmm, d * spmm_bytes() + (d - 1) * 8.0 * (double)n * b, d * 2.0 * (double)nnz * b, d);
       HIP_TRY(launch_copy_cols(cur, b, 0, basis.p, ld, nl, b, n, st));
       return;
     }
@@ -1015,6 +1113,12 @@ using namespace sceig;
 extern "C" {
 
 int sc_version(void) { return 100; }
+
+int sc_release_cache(void) {
+  device_cache().clear();
+  pinned_cache().clear();
+  return SC_OK;
+}
 
 const char* sc_strerror(int code) {
   switch (code) {

@@ -267,3 +267,15 @@ def test_start_filter_is_used_on_clustered_workload(B):
     assert code2 == B.SC_OK and without["filter_steps"] == 0
     assert with_filter["block_steps"] < without["block_steps"]
     assert np.max(np.abs(lam)) <= 1e-8 and np.max(np.abs(lam2)) <= 1e-8
+
+
+def test_release_cache_between_calls(B):
+    """Workspace blocks are kept between calls; giving them back must not change any later result."""
+    g = wl.disjoint_union(*[wl.ring(20 + 3 * t) for t in range(6)])
+    lam1, vec1, code1, _ = solve(B, g, 9, 1e-10, m=60, seed=5)
+    lam2, vec2, code2, _ = solve(B, g, 9, 1e-10, m=60, seed=5)        # served from the kept blocks
+    assert B.sc_release_cache() == B.SC_OK
+    lam3, vec3, code3, _ = solve(B, g, 9, 1e-10, m=60, seed=5)        # fresh allocations again
+    assert code1 == code2 == code3 == B.SC_OK
+    assert np.array_equal(lam1, lam2) and np.array_equal(lam1, lam3)
+    assert np.array_equal(vec1, vec2) and np.array_equal(vec1, vec3)
