@@ -355,39 +355,28 @@ int reorder_csr(const int64_t* rowptr, const int32_t* col, const double* val, in
     if (debug_on() && (round % 50 == 49)) std::fprintf(stderr, "[sceig] component pass: %d rounds\n", 2 * (round + 1));
     if (!h) break;
   }
-  std::vector<int32_t> lab((size_t)n), new_of_old((size_t)n), old_of_new((size_t)n);
-  std::vector<int64_t> rp((size_t)n + 1), rp_new((size_t)n + 1);
-  HIP_TRY(hipMemcpyAsync(lab.data(), label.p, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipMemcpyAsync(rp.data(), rowptr, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipStreamSynchronize(st));
-  // counting sort by component (component = its smallest node id), stable in the node id
-  std::vector<int64_t> start((size_t)n + 1, 0);
-  for (int64_t i = 0; i < n; ++i) start[(size_t)lab[i] + 1] += 1;
-  std::vector<int32_t> comp_of_root((size_t)n, -1);
-  int ncomp = 0;
-  for (int64_t r = 0; r < n; ++r) {
-    if (start[r + 1] > 0) comp_of_root[r] = ncomp++;
-    start[r + 1] += start[r];
-  }
-  if (comp_of_new) comp_of_new->assign((size_t)n, 0);
-  for (int64_t i = 0; i < n; ++i) {
-    const int64_t p = start[lab[i]]++;
-    new_of_old[i] = (int32_t)p;
-    old_of_new[p] = (int32_t)i;
-    if (comp_of_new) (*comp_of_new)[p] = comp_of_root[lab[i]];
-  }
-  rp_new[0] = 0;
-  for (int64_t p = 0; p < n; ++p) rp_new[p + 1] = rp_new[p] + (rp[old_of_new[p] + 1] - rp[old_of_new[p]]);
+  // numbering, permuted row pointers and component index of every new row, all on the device
   int32_t* new_of_old_dev = new_of_old_out;
   if (!new_of_old_dev) {
     new_of_old_own.alloc((size_t)n);
     new_of_old_dev = new_of_old_own.p;
   }
-  HIP_TRY(hipMemcpyAsync(rowptr_out, rp_new.data(), ((size_t)n + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
-  HIP_TRY(hipMemcpyAsync(old_of_new_out, old_of_new.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
-  HIP_TRY(hipMemcpyAsync(new_of_old_dev, new_of_old.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  DevBuf<char> work;
+  DevBuf<int32_t> comp_dev;
+  const size_t work_bytes = order_by_component_workspace(n);
+  work.alloc(work_bytes);
+  comp_dev.alloc((size_t)n);
+  HIP_TRY(order_by_component(rowptr, col, label.p, n, work.p, work_bytes, old_of_new_out, new_of_old_dev, rowptr_out,
+                             comp_dev.p, st));
   HIP_TRY(launch_permute_csr(rowptr, col, val, old_of_new_out, new_of_old_dev, rowptr_out, col_out, val_out, n, st));
-  HIP_TRY(hipStreamSynchronize(st));  // the host vectors above are pageable and go out of scope
+  int32_t last_comp = 0;
+  HIP_TRY(hipMemcpyAsync(&last_comp, comp_dev.p + (n - 1), sizeof(int32_t), hipMemcpyDeviceToHost, st));
+  if (comp_of_new) {
+    comp_of_new->assign((size_t)n, 0);
+    HIP_TRY(hipMemcpyAsync(comp_of_new->data(), comp_dev.p, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+  }
+  HIP_TRY(hipStreamSynchronize(st));
+  const int ncomp = (int)last_comp + 1;
   (void)nnz;
   return ncomp;
 }
@@ -458,8 +447,8 @@ struct Solver {
     val_p.alloc((size_t)nnz);
     old_of_new_d.alloc((size_t)n);
     new_of_old_d.alloc((size_t)n);
-    ncomp = reorder_csr(rowptr, col, val, n, nnz, rowptr_p.p, col_p.p, val_p.p, old_of_new_d.p, new_of_old_d.p, &comp_host,
-                        st);
+    ncomp = reorder_csr(rowptr, col, val, n, nnz, rowptr_p.p, col_p.p, val_p.p, old_of_new_d.p, new_of_old_d.p,
+                        (flags & SC_FLAG_COMPONENT_NULLSPACE) ? &comp_host : nullptr, st);
     rowptr = rowptr_p.p;
     col = col_p.p;
     val = val_p.p;

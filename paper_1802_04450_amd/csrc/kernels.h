@@ -77,6 +77,15 @@ int plan_update_gram(int64_t n);
 hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int b,
                               int ccol0, int overwrite, double* gpart, hipStream_t st);
 // ---- connected components and locality reordering (setup) --------------------------------------
+// Renumbering from the component labels (label[i] = smallest node index of i's component), on the device:
+//   old_of_new[p] = original index of new row p (components contiguous, ordered by their smallest node; inside a
+//   component by the min-hash of the closed neighbourhood, ties in original order), new_of_old = its inverse,
+//   rowptr_new (n+1) = row pointers of the permuted matrix, comp_of_new[p] = component index of new row p.
+// work: device scratch of order_by_component_workspace(n) bytes.  All outputs are device arrays; n <= INT32_MAX.
+size_t order_by_component_workspace(int64_t n);
+hipError_t order_by_component(const int64_t* rowptr, const int32_t* col, const int32_t* label, int64_t n, void* work,
+                              size_t work_bytes, int32_t* old_of_new, int32_t* new_of_old, int64_t* rowptr_new,
+                              int32_t* comp_of_new, hipStream_t st);
 // label[i] = i
 hipError_t launch_iota(int32_t* label, int64_t n, hipStream_t st);
 // one round of minimum-label propagation with pointer jumping; *changed = 1 if a label moved
