@@ -84,6 +84,40 @@ def cpu_baseline(cfg, graph, budget_s: float = 20.0):
                       f"grows with the number of locked vectors)"}
 
 
+def measure_spmv(B, torch, drp, dc, dv, n, nnz):
+    """Single-vector y = S x: algorithmic bytes / time, on the node numbering the solver itself works in (its setup
+    pass makes every connected component contiguous and orders each by neighbourhood min-hash; that pass is part of
+    every timed eigensolve) and, for context, on the numbering the caller handed over.  Products are enqueued back to
+    back."""
+    def time_spmv(rp_d, c_d, v_d):
+        _, s = B.sc_degree_scaling(rp_d, c_d, v_d, want_degrees=False)
+        x = torch.randn(n, dtype=torch.float64, device="cuda")
+        y = torch.empty_like(x)
+        work = torch.empty_like(x)
+        for _ in range(5):
+            B.sc_spmm_normalized(rp_d, c_d, v_d, s, x, y, work)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 50
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            B.sc_spmm_normalized(rp_d, c_d, v_d, s, x, y, work)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    rp2, c2, v2, _, ncomp = B.sc_reorder_csr(drp, dc, dv)
+    spmv_s = time_spmv(rp2, c2, v2)
+    spmv_s_given = time_spmv(drp, dc, dv)
+    spmv_bytes = 12 * nnz + 8 * (n + 1) + 8 * n + 8 * n + 8 * n
+    spmv_gbs = spmv_bytes / spmv_s / 1e9
+    return {"gbps_algorithmic": spmv_gbs, "seconds": spmv_s, "bytes": spmv_bytes,
+            "frac_of_hbm_peak": spmv_gbs / HBM_PEAK_GBS,
+            "gbps_algorithmic_caller_numbering": spmv_bytes / spmv_s_given / 1e9, "components": int(ncomp),
+            "note": "single-vector y = S x (prescale pass + product kernel), 50 back-to-back calls timed with "
+                    "events, on the numbering the solver uses internally"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -94,6 +128,9 @@ def main():
     ap.add_argument("--m", type=int, default=-1)
     ap.add_argument("--check-every", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--spmv-only", action="store_true",
+                    help="build the workload, measure only the single-vector product y = S x, print its JSON and stop "
+                         "(for the workloads whose eigensolve is not the benchmark: cfg3, cfg4, cfg5)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device copy 10 times (calibration of the HBM traffic counters)")
     args = ap.parse_args()
@@ -120,6 +157,10 @@ def main():
     rp, c, v, n = graph
     nnz = int(rp[-1])
     drp, dc, dv = B.csr_to_device(rp, c, v)
+    if args.spmv_only:
+        print(json.dumps({"workload": f"{cfg.name}: n={n}, nnz={nnz}", "spmv": measure_spmv(B, torch, drp, dc, dv, n, nnz)}),
+              flush=True)
+        return
     m = cfg.m if args.m < 0 else args.m
     kw = dict(m=m, block=args.block, check_every=args.check_every)
 
@@ -144,31 +185,7 @@ def main():
     evals, evecs, code, stats = last
     sec = elapsed / args.steps
 
-    # SpMV (single vector y = S x): algorithmic bytes / time, on the node numbering the solver itself works in
-    # (its setup pass makes every connected component contiguous; that pass is part of every timed eigensolve)
-    # and, for context, on the numbering the caller handed over.  Products are enqueued back to back.
-    def time_spmv(rp_d, c_d, v_d):
-        _, s = B.sc_degree_scaling(rp_d, c_d, v_d, want_degrees=False)
-        x = torch.randn(n, dtype=torch.float64, device="cuda")
-        y = torch.empty_like(x)
-        work = torch.empty_like(x)
-        for _ in range(5):
-            B.sc_spmm_normalized(rp_d, c_d, v_d, s, x, y, work)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 50
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            B.sc_spmm_normalized(rp_d, c_d, v_d, s, x, y, work)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e-3 / reps
-
-    rp2, c2, v2, _, ncomp = B.sc_reorder_csr(drp, dc, dv)
-    spmv_s = time_spmv(rp2, c2, v2)
-    spmv_s_given = time_spmv(drp, dc, dv)
-    spmv_bytes = 12 * nnz + 8 * (n + 1) + 8 * n + 8 * n + 8 * n
-    spmv_gbs = spmv_bytes / spmv_s / 1e9
+    spmv = measure_spmv(B, torch, drp, dc, dv, n, nnz)
 
     out = {
         "metric": "eigensolve s + SpMV HBM GB/s, k smallest eigvecs of n-node kNN Laplacian",
@@ -177,11 +194,7 @@ def main():
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={n}, nnz={nnz}, k={cfg.k}, m={stats['m']}, tol={cfg.tol}, "
                                f"block={stats['block']}", "status": int(code)},
-        "spmv": {"gbps_algorithmic": spmv_gbs, "seconds": spmv_s, "bytes": spmv_bytes,
-                 "frac_of_hbm_peak": spmv_gbs / HBM_PEAK_GBS,
-                 "gbps_algorithmic_caller_numbering": spmv_bytes / spmv_s_given / 1e9,
-                 "note": "single-vector y = S x (prescale pass + product kernel), 50 back-to-back calls timed with "
-                         "events, on the component-contiguous numbering the solver uses internally"},
+        "spmv": spmv,
         "solver_stats": stats,
     }
     kt = stats["fam_time_s"][dom]
