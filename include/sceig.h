@@ -58,6 +58,11 @@ extern "C" {
 #define SC_FLAG_FINAL_RR 16u /* always finish with a Rayleigh-Ritz step over the k locked vectors; by default that step
                                  only runs when some returned pair did not meet tol */
 
+#define SC_FLAG_RANDOM_WALK_VECTORS 32u /* return u = D^-1/2 v, the eigenvectors of the paper's L_n = D^-1 L (Section II
+                                 Steps 2-3), instead of the orthonormal v of the symmetric form: same eigenvalues,
+                                 columns D-orthonormal (u_i^T D u_j = delta_ij), constant on every connected
+                                 component for eigenvalue 0 */
+
 /* Options; every field 0 = default. */
 typedef struct sc_options {
   int32_t m;      /* budget of basis columns (locked + active Krylov vectors), the "number m of Lanczos
@@ -115,7 +120,8 @@ typedef struct sc_stats {
  *   maxiter                       upper bound on restart cycles (phase starts + thick restarts); >= 1
  *   evals_out                     device, fp64[k], ascending eigenvalues of L
  *   evecs_out                     device, fp64[n*k], column-major, orthonormal eigenvectors of L
- *                                 (v = D^1/2 u for the eigenvectors u of the paper's D^-1 L)
+ *                                 (v = D^1/2 u for the eigenvectors u of the paper's D^-1 L; u itself under
+ *                                 SC_FLAG_RANDOM_WALK_VECTORS)
  *   opt, stats                    host, may be NULL
  *
  * Method: block Lanczos with full reorthogonalization (classical Gram-Schmidt, first pass against all

@@ -82,3 +82,19 @@ def dense_laplacian(rowptr, col, val) -> np.ndarray:
     """Dense L_sym = I - D^-1/2 W D^-1/2."""
     n = rowptr.size - 1
     return np.eye(n) - dense_s(rowptr, col, val)
+
+
+def random_walk_vectors(rowptr, col, val, vec_sym: np.ndarray) -> np.ndarray:
+    """Eigenvectors of the paper's L_n = D^-1 L (Section II Steps 2-3) from those of the symmetric form.
+
+    If L_sym v = lambda v with L_sym = I - D^-1/2 W D^-1/2 then u = D^-1/2 v satisfies
+    (I - D^-1 W) u = lambda u.  No renormalization: orthonormal v give D-orthonormal u (u_i^T D u_j = delta_ij)."""
+    s = inv_sqrt_degrees(rowptr, col, val)
+    return s[:, None] * vec_sym if vec_sym.ndim == 2 else s * vec_sym
+
+
+def apply_random_walk_laplacian(rowptr, col, val, x: np.ndarray) -> np.ndarray:
+    """y = L_n x = x - D^-1 (W x), entry by entry (Section II Step 2)."""
+    d = degrees(rowptr, col, val)
+    wx = apply_w(rowptr, col, val, x)
+    return x - (wx / d[:, None] if x.ndim == 2 else wx / d)

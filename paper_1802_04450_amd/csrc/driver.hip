@@ -1059,6 +1059,9 @@ struct Solver {
       HIP_TRY(launch_row_gemm(basis.p, n, ld, 0, nx, yd.p, nfound, nfound, 2, 0, evecs_out, n, rowmap, st));
       HIP_TRY(hipStreamSynchronize(st));
     }
+    // the paper's Step 3 asks for the eigenvectors of L_n = D^-1 L: u = D^-1/2 v
+    if ((flags & SC_FLAG_RANDOM_WALK_VECTORS) && nfound > 0)
+      HIP_TRY(launch_scale_rows_colmajor(evecs_out, n, nfound, s.p, rowinv, st));
     HIP_TRY(hipMemcpyAsync(evals_out, evals_host.data(), (size_t)k * sizeof(double), hipMemcpyHostToDevice, st));
     HIP_TRY(hipStreamSynchronize(st));
     if (debug_on()) std::fprintf(stderr, "[sceig] t=%.4fs outputs written\n", now_s() - t_begin);

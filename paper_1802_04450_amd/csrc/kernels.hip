@@ -705,6 +705,17 @@ __global__ __launch_bounds__(kThreads) void gather_cols_colmajor_kernel(const do
   }
 }
 
+// out[t * n + o] *= s[r(o)] for t < k: column-major vectors in the caller's numbering times the scaling vector held in
+// the internal numbering (r(o) = inv[o] if inv is given, else o).
+__global__ __launch_bounds__(kThreads) void scale_rows_colmajor_kernel(double* __restrict__ out, int64_t n, int k,
+                                                                       const double* __restrict__ s,
+                                                                       const int32_t* __restrict__ inv) {
+  const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (o >= n) return;
+  const double f = s[inv ? (int64_t)inv[o] : o];
+  for (int t = 0; t < k; ++t) out[(int64_t)t * n + o] *= f;
+}
+
 // One step of the three-term Chebyshev recurrence on packed n x b blocks (leading dimension b):
 //   ynext = alpha * (w - shift * ycur) - beta * yprev,   znext = s o ynext   (the packed operand of the next product)
 // ynext may be the buffer of yprev (each element is read before it is written by the same thread).
@@ -1260,6 +1271,13 @@ hipError_t launch_gather_cols_colmajor(const double* basis, int64_t n, int64_t l
   if (n <= 0 || k <= 0) return hipSuccess;
   hipLaunchKernelGGL(gather_cols_colmajor_kernel, dim3((unsigned)ceil_div64(n, 64), (unsigned)((k + 63) / 64)),
                      dim3(kThreads), 0, st, basis, n, ld, perm, k, out, inv);
+  return hipGetLastError();
+}
+
+hipError_t launch_scale_rows_colmajor(double* out, int64_t n, int k, const double* s, const int32_t* inv, hipStream_t st) {
+  if (n <= 0 || k <= 0) return hipSuccess;
+  hipLaunchKernelGGL(scale_rows_colmajor_kernel, dim3((unsigned)ceil_div64(n, kThreads)), dim3(kThreads), 0, st, out, n,
+                     k, s, inv);
   return hipGetLastError();
 }
 

@@ -279,3 +279,31 @@ def test_release_cache_between_calls(B):
     assert code1 == code2 == code3 == B.SC_OK
     assert np.array_equal(lam1, lam2) and np.array_equal(lam1, lam3)
     assert np.array_equal(vec1, vec2) and np.array_equal(vec1, vec3)
+
+
+@pytest.mark.parametrize("extra", [0, "FINAL_RR"])
+def test_random_walk_vectors_of_the_papers_laplacian(B, extra):
+    """SC_FLAG_RANDOM_WALK_VECTORS: eigenvectors of L_n = D^-1 L (Section II Steps 2-3).  Checked against the
+    definition (L_n u = lambda u entry by entry), D-orthonormality, constancy on components for lambda = 0, and
+    against the symmetric-form output of the same solve scaled by the oracle."""
+    from oracle import laplacian
+    parts = [wl.ring(9), wl.path(14), wl.random_weighted_connected(30, 60, 5), wl.complete(5), wl.ring(21)]
+    g = wl.disjoint_union(*parts)
+    g = wl.relabel(g, np.random.default_rng(8).permutation(g[3]))
+    rp, c, v, n = g
+    k = 8
+    f = B.SC_FLAG_RANDOM_WALK_VECTORS | (getattr(B, "SC_FLAG_" + extra) if extra else 0)
+    lam, u, code, _ = solve(B, g, k, 1e-10, flags=f, seed=3)
+    lam_v, vec, code_v, _ = solve(B, g, k, 1e-10, flags=f & ~B.SC_FLAG_RANDOM_WALK_VECTORS, seed=3)
+    assert code == code_v == B.SC_OK
+    assert np.array_equal(lam, lam_v)
+    assert np.max(np.abs(u - laplacian.random_walk_vectors(rp, c, v, vec))) <= 1e-14      # one scaling by s = d^-1/2
+    lam_full, _ = dense.full_spectrum(rp, c, v)
+    assert np.max(np.abs(lam - lam_full[:k])) <= 1e-8
+    assert np.max(np.abs(laplacian.apply_random_walk_laplacian(rp, c, v, u) - u * lam[None, :])) <= 1e-6
+    d = laplacian.degrees(rp, c, v)
+    assert np.max(np.abs(u.T @ (d[:, None] * u) - np.eye(k))) <= 1e-9
+    ncomp, label = components.component_labels(rp, c, v)
+    for t in range(ncomp):
+        for comp in range(ncomp):
+            assert np.ptp(u[label == comp, t]) <= 1e-8

@@ -289,3 +289,33 @@ def test_component_labels_leave_the_input_untouched_and_ignore_zero_weights():
     assert ncomp == 2 and len(set(label[:6])) == 1 and len(set(label[6:])) == 1 and label[0] != label[6]
     for a, b in zip(before, g2[:3]):
         assert np.array_equal(a, b)
+
+
+def test_random_walk_vectors_are_eigenvectors_of_the_papers_laplacian():
+    """Section II Steps 2-3 work with L_n = D^-1 L.  u = D^-1/2 v must satisfy L_n u = lambda u with the same lambda,
+    be D-orthonormal, and - the textbook reason for using L_n - be constant on every connected component for
+    lambda = 0, so that the null vectors span the component indicators exactly."""
+    parts = [wl.ring(9), wl.path(14), wl.random_weighted_connected(30, 60, 5), wl.complete(5)]
+    g = wl.disjoint_union(*parts)
+    g = wl.relabel(g, np.random.default_rng(8).permutation(g[3]))
+    rp, c, v, n = g
+    lam, vec = dense.full_spectrum(rp, c, v)
+    u = laplacian.random_walk_vectors(rp, c, v, vec)
+    lnu = laplacian.apply_random_walk_laplacian(rp, c, v, u)
+    assert np.max(np.abs(lnu - u * lam[None, :])) < 1e-12
+    d = laplacian.degrees(rp, c, v)
+    assert np.max(np.abs(u.T @ (d[:, None] * u) - np.eye(n))) < 1e-12
+    ncomp, label = components.component_labels(rp, c, v)
+    assert ncomp == 4 and np.all(np.abs(lam[:4]) < 1e-13)
+    for t in range(4):                      # every null vector is constant on every component
+        for comp in range(ncomp):
+            vals = u[label == comp, t]
+            assert np.ptp(vals) < 1e-12
+    # the span of the null vectors is the span of the component indicators
+    ind = np.stack([(label == comp).astype(float) for comp in range(ncomp)], axis=1)
+    assert np.max(compare.containment_defect(ind / np.linalg.norm(ind, axis=0), np.linalg.qr(u[:, :4])[0])) < 1e-12
+    # hand value: on a connected graph the null vector is the constant 1/sqrt(vol)
+    rp1, c1, v1, n1 = wl.random_weighted_connected(12, 20, 2)
+    lam1, vec1 = dense.full_spectrum(rp1, c1, v1)
+    u1 = laplacian.random_walk_vectors(rp1, c1, v1, vec1[:, 0])
+    assert np.allclose(np.abs(u1), 1.0 / np.sqrt(laplacian.degrees(rp1, c1, v1).sum()), atol=1e-13)
