@@ -291,7 +291,8 @@ int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, i
                                    pass == 1 ? slot_a : nullptr, slot_row0 - c0, st));
     tm->end(kFamOther, 8.0 * plan.npart * (double)jc * b, 0.0);
     tm->begin(kFamUpdate);
-    if (pass == 1 && gpart) {
+    const bool last_pass = pass == 1 || j - second_from <= 0;  // the last update leaves the Gram partials
+    if (last_pass && gpart) {
       HIP_TRY(launch_update_gram(basis, n, ld, c0, jc, h1, b, wcol, 0, gpart, st));
       ngram = plan_update_gram(n);
     } else {
@@ -739,7 +740,10 @@ struct Solver {
         apply_start_filter(filt_d, filt_a);
         filt_d = 0;
       }
-      const int ngram0 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
+      // a filtered block went into the filter orthogonal to the locked vectors; what it picked up along them since is
+      // of the order of their residuals relative to the block, so one projection removes it without cancellation
+      const int ngram0 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, filtered ? nl : 0, part.p, h1.p, hsum.p, nullptr, 0,
+                                      gpart.p, st, &timer);
       enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram0, gram(), rinv(), r1(), slot(0) + kPP * kPP,
                        slot(0) + 2 * kPP * kPP, z.p, zs(), st, &timer);
       int ja = b;            // active columns whose coupling is (or will be) assembled
@@ -873,7 +877,7 @@ struct Solver {
             rotate_into(ja, Y, ycols, sel, nl);
             HIP_TRY(launch_pack_scaled(basis.p + nl, ld, zs(), n, b, z.p, st));
             apply_start_filter(filt_d, filt_a);
-            const int ngram1 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
+            const int ngram1 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, nl, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st, &timer);
             enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram1, gram(), rinv(), r1(), slot(0) + kPP * kPP,
                              slot(0) + 2 * kPP * kPP, z.p, zs(), st, &timer);
             filt_d = 0;
