@@ -181,6 +181,23 @@ int sc_reorder_csr(const int64_t* csr_rowptr, const int32_t* csr_col, const doub
 int sc_validate_csr(const int64_t* csr_rowptr, const int32_t* csr_col, int64_t n, void* stream);
 
 /*
+ * The start-block filter of sc_laplacian_eigsh as a step of its own (the start vector of Algorithm 3 is free; the
+ * solver passes its re-injection blocks through this polynomial):
+ *   Y = T_d(g(S)) X,   T_d = Chebyshev polynomial of the first kind of degree d,
+ *   g(S) = (2 S - (a - 1) I) / (a + 1), the affine map that takes the interval [-1, a] of the spectrum to [-1, 1],
+ * by the three-term recurrence Y_0 = X, Y_1 = g(S) X, Y_{i+1} = 2 g(S) Y_i - Y_{i-1}: d sparse products, nothing else.
+ * An eigenvector of S with eigenvalue theta is multiplied by T_d((2 theta - a + 1) / (a + 1)): at most 1 in modulus
+ * for theta in [-1, a], cosh(d acosh(.)) above a.
+ *   x, y    device, row-major n x ncols with leading dimensions ldx, ldy >= ncols; ncols in {1,2,4,8,16,32}; y may be x
+ *   a       -1 < a < 1;  degree >= 1
+ * For ncols >= 8 the products run on a scaled copy of the operator made inside the call (as the solver does), for
+ * narrower blocks on W and the scaling vector.  Returns SC_EZERODEG if some degree is not positive.
+ */
+int sc_chebyshev_filter(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n,
+                        const double* x, int64_t ldx, int32_t ncols, double a, int32_t degree, double* y, int64_t ldy,
+                        void* stream);
+
+/*
  * One reorthogonalization of the Lanczos recurrence (inside TakeStep of Algorithm 3): classical
  * Gram-Schmidt applied twice to the block W = basis[:, j : j+b] against Q = basis[:, 0 : j]:
  *   H1 = Q^T W, W -= Q H1, H2 = Q^T W, W -= Q H2, h_out = H1 + H2.

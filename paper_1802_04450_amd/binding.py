@@ -25,7 +25,8 @@ SC_FLAG_RANDOM_WALK_VECTORS = 32
 FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 
 EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_reorder_csr", "sc_cgs2",
-           "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version", "sc_release_cache"]
+           "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version", "sc_release_cache",
+           "sc_chebyshev_filter"]
 
 
 class ScOptions(ctypes.Structure):
@@ -81,6 +82,7 @@ def lib() -> ctypes.CDLL:
         _lib.sc_cgs2.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         _lib.sc_block_qr.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         _lib.sc_rotate.argtypes = [vp, i64, i64, i32, i32, vp, i32, vp, i64, i32, vp]
+        _lib.sc_chebyshev_filter.argtypes = [vp, vp, vp, i64, vp, i64, i32, dbl, i32, vp, i64, vp]
         _lib.sc_sym_eig.argtypes = [vp, i32, vp, vp]
         _lib.sc_sym_eig_top.argtypes = [vp, i32, i32, vp, vp]
         for name in EXPORTS:
@@ -240,6 +242,19 @@ def sc_rotate(basis, j0: int, ja: int, y, out_colmajor: bool = False):
                                1 if out_colmajor else 0, _stream())
     _check(code)
     return out
+
+
+def sc_chebyshev_filter(rowptr, col, val, x, a: float, degree: int):
+    """T_degree(g(S)) x for a row-major (n, ncols) block x, g mapping [-1, a] to [-1, 1].  Returns a new (n, ncols) tensor."""
+    import torch
+    n = rowptr.numel() - 1
+    ncols = x.shape[1]
+    y = torch.empty((n, ncols), dtype=torch.float64, device=x.device)
+    with torch.cuda.device(x.device):
+        code = lib().sc_chebyshev_filter(_ptr(rowptr), _ptr(col), _ptr(val), n, _ptr(x), x.stride(0), ncols,
+                                         float(a), int(degree), _ptr(y), ncols, _stream())
+    _check(code)
+    return y
 
 
 def sc_sym_eig(a: np.ndarray, vectors: bool = True) -> Tuple[np.ndarray, Optional[np.ndarray]]:

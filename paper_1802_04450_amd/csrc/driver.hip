@@ -330,6 +330,50 @@ void enqueue_block_qr(double* basis, int64_t n, int64_t ld, int col, int b, doub
   tm->end(kFamQr, (ngram > 0 ? 4.0 : 5.0) * blk + (z ? blk : 0.0), 4.0 * (double)n * b * b);
 }
 
+// Chebyshev filter of a packed block: result = T_d(g(S)) X, g the affine map taking [-1, a] to [-1, 1], by the
+// three-term recurrence Y_0 = X, Y_1 = g(S) X, Y_{i+1} = 2 g(S) Y_i - Y_{i-1}; one sparse product per step.
+//   wide blocks (val_scaled != null, b >= 8): z holds X packed; the recurrence is fused into the product kernel and
+//     rotates through z, buf1 and buf2.
+//   narrow blocks: z holds s o X packed and buf1 holds X packed; buf2 and buf3 are scratch (product + combine kernel).
+// All buffers are packed n x b.  Returns the buffer that holds the result.
+double* enqueue_cheb_filter(const int64_t* rowptr, const int32_t* col, const double* val, const double* val_scaled,
+                            const double* s, int64_t n, int64_t nnz, int b, int d, double a, double* z, double* buf1,
+                            double* buf2, double* buf3, double avg_deg, hipStream_t st, KTimer* tm) {
+  KTimer none;
+  if (!tm) tm = &none;
+  const double lo = -1.0;  // ||S||_2 = 1
+  const double c = 0.5 * (a + lo), e = 0.5 * (a - lo);
+  const double bytes = 12.0 * (double)nnz + 8.0 * (double)(n + 1) + (val_scaled ? 0.0 : 8.0 * (double)n) +
+                       16.0 * (double)n * b;
+  if (val_scaled) {
+    double* cur = z;
+    double* prev = buf1;
+    double* next = buf2;
+    tm->begin(kFamSpmm);  // one event pair round the d back-to-back launches
+    for (int i = 0; i < d; ++i) {
+      HIP_TRY(launch_spmm_vals_cheb(rowptr, col, val_scaled, n, cur, b, prev, next, i == 0 ? 1.0 / e : 2.0 / e, c,
+                                    i == 0 ? 0.0 : 1.0, avg_deg, st));
+      double* t = prev;
+      prev = cur;
+      cur = next;
+      next = t;
+    }
+    tm->end(kFamSpmm, d * bytes + (d - 1) * 8.0 * (double)n * b, d * 2.0 * (double)nnz * b, d);
+    return cur;
+  }
+  double* ycur = buf1;
+  double* yprev = buf2;
+  for (int i = 0; i < d; ++i) {
+    tm->begin(kFamSpmm);
+    HIP_TRY(launch_spmm(rowptr, col, val, s, n, z, b, buf3, b, avg_deg, st));
+    tm->end(kFamSpmm, bytes, 2.0 * (double)nnz * b);
+    HIP_TRY(launch_cheb_combine(buf3, ycur, i == 0 ? ycur : yprev, s, i == 0 ? 1.0 / e : 2.0 / e, c, i == 0 ? 0.0 : 1.0,
+                                yprev, z, n, b, st));
+    std::swap(ycur, yprev);
+  }
+  return ycur;
+}
+
 constexpr int kGramPartials = 1024;
 
 // Connected components by label propagation on the device, then rows and columns are renumbered so that every
@@ -563,46 +607,15 @@ struct Solver {
   // in [-1, a] stays bounded by 1, what lies above a grows like cosh(d acosh(x)).  Only products and a three-term
   // recurrence: no reorthogonalization.  The caller orthogonalizes and orthonormalizes the result again.
   void apply_start_filter(int d, double a) {
-    const double lo = -1.0;  // ||S||_2 = 1
-    const double c = 0.5 * (a + lo), e = 0.5 * (a - lo);
-    if (val_s.p) {
-      // the recurrence is fused into the product kernel: y_0 is the packed copy of the block in z
-      double* cur = z.p;
-      double* prev = rot.p;
-      double* next = rot.p + (size_t)n * b;
-      timer.begin(kFamSpmm);  // one event pair round the d back-to-back launches
-      for (int i = 0; i < d; ++i) {
-        HIP_TRY(launch_spmm_vals_cheb(rowptr, col, val_s.p, n, cur, b, prev, next, i == 0 ? 1.0 / e : 2.0 / e, c,
-                                      i == 0 ? 0.0 : 1.0, avg_deg, st));
-        double* t = prev;
-        prev = cur;
-        cur = next;
-        next = t;
-        stats.spmv_cols += b;
-        stats.filter_steps += 1;
-      }
-      timer.end(kFamSpmm, d * spmm_bytes() + (d - 1) * 8.0 * (double)n * b, d * 2.0 * (double)nnz * b, d);
-      HIP_TRY(launch_copy_cols(cur, b, 0, basis.p, ld, nl, b, n, st));
-      return;
-    }
-    double* ycur = rot.p;
-    double* yprev = rot.p + (size_t)n * b;
-    double* w = rot.p + 2 * (size_t)n * b;
-    HIP_TRY(launch_copy_cols(basis.p, ld, nl, ycur, b, 0, b, n, st));
-    for (int i = 0; i < d; ++i) {
-      timer.begin(kFamSpmm);
-      spmm_from_z(w, b);
-      timer.end(kFamSpmm, spmm_bytes(), 2.0 * (double)nnz * b);
-      if (i == 0) {
-        HIP_TRY(launch_cheb_combine(w, ycur, ycur, s.p, 1.0 / e, c, 0.0, yprev, z.p, n, b, st));
-      } else {
-        HIP_TRY(launch_cheb_combine(w, ycur, yprev, s.p, 2.0 / e, c, 1.0, yprev, z.p, n, b, st));
-      }
-      std::swap(ycur, yprev);
-      stats.spmv_cols += b;
-      stats.filter_steps += 1;
-    }
-    HIP_TRY(launch_copy_cols(ycur, b, 0, basis.p, ld, nl, b, n, st));
+    double* buf1 = rot.p;
+    double* buf2 = rot.p + (size_t)n * b;
+    double* buf3 = rot.p + 2 * (size_t)n * b;
+    if (!val_s.p) HIP_TRY(launch_copy_cols(basis.p, ld, nl, buf1, b, 0, b, n, st));
+    const double* res = enqueue_cheb_filter(rowptr, col, val, val_s.p, s.p, n, nnz, b, d, a, z.p, buf1, buf2, buf3,
+                                            avg_deg, st, &timer);
+    stats.spmv_cols += (int64_t)d * b;
+    stats.filter_steps += d;
+    HIP_TRY(launch_copy_cols(res, b, 0, basis.p, ld, nl, b, n, st));
   }
 
   // Decide the filter of the next start block from the Ritz values theta (ascending, ghosts at the bottom).
@@ -1425,6 +1438,67 @@ int sc_rotate(const double* basis, int64_t n, int64_t ld, int32_t j0, int32_t ja
         Ctx* c = static_cast<Ctx*>(p);
         HIP_TRY(launch_row_gemm(const_cast<double*>(c->basis), c->n, c->ld, c->j0, c->ja, c->y, c->l, c->l,
                                 c->cm ? 2 : 1, 0, c->out, c->ldo, nullptr, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        return SC_OK;
+      },
+      &ctx);
+}
+
+int sc_chebyshev_filter(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n,
+                        const double* x, int64_t ldx, int32_t ncols, double a, int32_t degree, double* y, int64_t ldy,
+                        void* stream) {
+  if (!csr_rowptr || !csr_col || !csr_val || !x || !y || n < 0) return SC_EINVAL;
+  if (!supported_block(ncols) || ldx < ncols || ldy < ncols || degree < 1 || !(a > -1.0) || !(a < 1.0))
+    return SC_EDOMAIN;
+  if (n == 0) return SC_OK;
+  struct Ctx {
+    const int64_t* rp;
+    const int32_t* c;
+    const double* v;
+    int64_t n;
+    const double* x;
+    int64_t ldx;
+    int b;
+    double a;
+    int d;
+    double* y;
+    int64_t ldy;
+    hipStream_t st;
+  } ctx{csr_rowptr, csr_col, csr_val, n, x, ldx, ncols, a, degree, y, ldy, reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        int64_t nnz = 0;
+        HIP_TRY(hipMemcpyAsync(&nnz, c->rp + c->n, sizeof(int64_t), hipMemcpyDeviceToHost, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        if (nnz < 0) SC_THROW(SC_ECSR);
+        DevBuf<double> s, vals, z, b1, b2, b3;
+        DevBuf<int> flag;
+        flag.alloc(1);
+        HIP_TRY(hipMemsetAsync(flag.p, 0, sizeof(int), c->st));
+        s.alloc((size_t)c->n);
+        HIP_TRY(launch_degree_scaling(c->rp, c->v, c->n, nullptr, s.p, flag.p, c->st));
+        int hflag = 0;
+        HIP_TRY(hipMemcpyAsync(&hflag, flag.p, sizeof(int), hipMemcpyDeviceToHost, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        if (hflag & 4) SC_THROW(SC_EZERODEG);
+        const size_t blk = (size_t)c->n * c->b;
+        z.alloc(blk);
+        b1.alloc(blk);
+        b2.alloc(blk);
+        const bool wide = c->b >= 8;
+        if (wide) {
+          vals.alloc((size_t)nnz);
+          HIP_TRY(launch_scale_values(c->rp, c->c, c->v, s.p, vals.p, c->n, c->st));
+          HIP_TRY(launch_pack_scaled(c->x, c->ldx, nullptr, c->n, c->b, z.p, c->st));
+        } else {
+          b3.alloc(blk);
+          HIP_TRY(launch_pack_scaled(c->x, c->ldx, s.p, c->n, c->b, z.p, c->st));
+          HIP_TRY(launch_pack_scaled(c->x, c->ldx, nullptr, c->n, c->b, b1.p, c->st));
+        }
+        const double* res = enqueue_cheb_filter(c->rp, c->c, c->v, wide ? vals.p : nullptr, s.p, c->n, nnz, c->b, c->d,
+                                                c->a, z.p, b1.p, b2.p, b3.p, (double)nnz / (double)c->n, c->st, nullptr);
+        HIP_TRY(launch_copy_cols(res, c->b, 0, c->y, c->ldy, 0, c->b, c->n, c->st));
         HIP_TRY(hipStreamSynchronize(c->st));
         return SC_OK;
       },

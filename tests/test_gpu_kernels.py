@@ -193,3 +193,36 @@ def test_reorder_csr_is_a_permutation_similarity(B):
     assert np.all(np.diff(np.flatnonzero(np.diff(lab_new) != 0)) > 0) and len(set(lab_new)) == ncomp
     # every component is one contiguous run
     assert np.count_nonzero(np.diff(lab_new) != 0) == ncomp - 1
+
+
+@pytest.mark.parametrize("ncols", [1, 4, 8, 16, 32])
+def test_chebyshev_filter(B, ncols):
+    """The start-block filter as a step of its own against the oracle's three-term recurrence: a graph that spans
+    several row tiles with a ragged tail, hub rows longer than one batch, both code paths (narrow blocks on W and s,
+    wide blocks on the scaled copy with the recurrence fused into the product)."""
+    from oracle import blockops
+    rng = np.random.default_rng(40 + ncols)
+    g = wl.disjoint_union(wl.random_weighted_connected(700, 9000, 5), wl.ring(257), wl.complete(70),
+                          wl.random_weighted_connected(333, 700, 6))
+    g = wl.relabel(g, rng.permutation(g[3]))
+    rp, c, v, n = g
+    x = rng.standard_normal((n, ncols))
+    a, d = 0.4, 12
+    want = blockops.chebyshev_filter(rp, c, v, x, a, d)
+    drp, dc, dv = B.csr_to_device(rp, c, v)
+    got = B.sc_chebyshev_filter(drp, dc, dv, torch.from_numpy(x).cuda(), a, d).cpu().numpy()
+    scale = np.max(np.abs(want))
+    assert scale > 1e3                                   # the polynomial did amplify the top of the spectrum
+    assert np.max(np.abs(got - want)) <= 1e-11 * scale   # d products and a three-term recurrence in fp64
+    # degree 1 is the plain affine image of S
+    got1 = B.sc_chebyshev_filter(drp, dc, dv, torch.from_numpy(x).cuda(), a, 1).cpu().numpy()
+    assert np.max(np.abs(got1 - blockops.chebyshev_filter(rp, c, v, x, a, 1))) <= 1e-13 * max(1.0, np.max(np.abs(x)))
+
+
+def test_chebyshev_filter_rejects_bad_arguments(B):
+    rp, c, v, n = wl.ring(20)
+    drp, dc, dv = B.csr_to_device(rp, c, v)
+    x = torch.zeros((n, 8), dtype=torch.float64, device="cuda")
+    for a, d in ((1.0, 3), (-1.0, 3), (0.3, 0)):
+        with pytest.raises(B.ScError):
+            B.sc_chebyshev_filter(drp, dc, dv, x, a, d)

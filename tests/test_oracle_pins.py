@@ -319,3 +319,26 @@ def test_random_walk_vectors_are_eigenvectors_of_the_papers_laplacian():
     lam1, vec1 = dense.full_spectrum(rp1, c1, v1)
     u1 = laplacian.random_walk_vectors(rp1, c1, v1, vec1[:, 0])
     assert np.allclose(np.abs(u1), 1.0 / np.sqrt(laplacian.degrees(rp1, c1, v1).sum()), atol=1e-13)
+
+
+def test_chebyshev_filter_closed_form_on_eigenvectors():
+    """An eigenvector of S with eigenvalue theta goes to T_d(t) v with t = (2 theta - a + 1)/(a + 1); T_d(t) =
+    cos(d arccos t) inside [-1, 1] and cosh(d arccosh t) above 1 - the closed forms, not the recurrence."""
+    from oracle import blockops
+    g = wl.disjoint_union(wl.ring(11), wl.random_weighted_connected(25, 50, 4), wl.path(9))
+    rp, c, v, n = g
+    lam, vec = dense.full_spectrum(rp, c, v)
+    theta = 1.0 - lam
+    a, d = 0.35, 9
+    y = blockops.chebyshev_filter(rp, c, v, vec, a, d)
+    t = (2.0 * theta - a + 1.0) / (a + 1.0)
+    inside = np.abs(t) <= 1.0
+    factor = np.where(inside, np.cos(d * np.arccos(np.clip(t, -1, 1))), np.cosh(d * np.arccosh(np.maximum(t, 1.0))))
+    assert inside.any() and (~inside).any()
+    assert np.max(np.abs(y - vec * factor[None, :]) / np.maximum(1.0, np.abs(factor))[None, :]) < 1e-11
+    assert np.all(np.abs(factor[inside]) <= 1.0 + 1e-12) and np.all(factor[~inside] > 1.0)
+    # degree 1 and 2 by hand: g(S) x and 2 g(S)^2 x - x
+    x = np.random.default_rng(1).standard_normal((n, 3))
+    gs = (2.0 * laplacian.dense_s(rp, c, v) - (a - 1.0) * np.eye(n)) / (a + 1.0)
+    assert np.max(np.abs(blockops.chebyshev_filter(rp, c, v, x, a, 1) - gs @ x)) < 1e-13
+    assert np.max(np.abs(blockops.chebyshev_filter(rp, c, v, x, a, 2) - (2.0 * gs @ (gs @ x) - x))) < 1e-12
