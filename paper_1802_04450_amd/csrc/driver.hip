@@ -659,11 +659,7 @@ struct Solver {
     const double rate = std::acosh(xt);
     // what lies below `a` should end up near tol relative to the wanted directions, so that the Lanczos steps
     // after the filter mostly confirm convergence
-    static const double amp_env = [] {
-      const char* e = std::getenv("SCEIG_FILTER_AMP");
-      return e ? std::atof(e) : 0.0;
-    }();
-    const double amp = amp_env > 0.0 ? amp_env : std::min(1e12, std::max(1e6, 100.0 / std::max(tol, 1e-300)));
+    const double amp = std::min(1e12, std::max(1e6, 100.0 / std::max(tol, 1e-300)));
     const int dmax = 30;
     if (!(rate > 0.0) || std::cosh(dmax * rate) < 100.0) return;
     const int d = (int)std::ceil(std::log(2.0 * amp) / rate);

@@ -1073,13 +1073,8 @@ hipError_t launch_pack_scaled(const double* x, int64_t ldx, const double* s, int
 // lanes per row of the wide-block product: the smallest power of two that covers an average row in one batch, at
 // most 32 (measured on the kNN workloads: 32 lanes beat 8, 16 and 64 for every block width)
 static int spmm_lanes(int b, double avg_deg) {
-  static const int forced = [] {
-    const char* e = getenv("SCEIG_SPMM_LANES");
-    return e ? atoi(e) : 0;
-  }();
   int lanes = b;
   while (lanes < 32 && lanes < avg_deg) lanes *= 2;
-  if (forced >= b && forced <= 32 && (forced & (forced - 1)) == 0) lanes = forced;
   return lanes;
 }
 

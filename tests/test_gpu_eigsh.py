@@ -4,6 +4,7 @@ Bars (eigenvalue / residual / angle) are in tests/parity.py.  Inside a multiple 
 orthonormal basis is correct, so subspaces are compared per separated cluster; when k cuts a cluster the
 GPU vectors must lie in the oracle's cluster space."""
 import math
+import os
 
 import numpy as np
 import pytest
@@ -307,3 +308,48 @@ def test_random_walk_vectors_of_the_papers_laplacian(B, extra):
     for t in range(ncomp):
         for comp in range(ncomp):
             assert np.ptp(u[label == comp, t]) <= 1e-8
+
+
+def _random_family(seed):
+    """Seeded small graphs that exercise the solver's decisions: connected graphs without a gap, unions of
+    components of uneven size (multiplicity above, at and below the block size), k below / at / above the
+    multiplicity, tight and generous basis budgets."""
+    rng = np.random.default_rng(1000 + seed)
+    kind = seed % 4
+    if kind == 0:                                   # one connected graph, dense spectrum
+        n = int(rng.integers(80, 400))
+        g = wl.random_weighted_connected(n, int(rng.integers(2, 6)) * n, seed)
+        k = int(rng.integers(2, 12))
+    elif kind == 1:                                 # many small components, k cuts the null cluster
+        parts = [wl.random_weighted_connected(int(rng.integers(6, 40)), 60, seed * 31 + t) for t in range(int(rng.integers(5, 30)))]
+        g = wl.disjoint_union(*parts)
+        k = int(rng.integers(2, len(parts)))
+    elif kind == 2:                                 # k beyond the number of components
+        parts = [wl.ring(int(rng.integers(8, 30))) if t % 2 else wl.random_weighted_connected(int(rng.integers(10, 50)), 90, seed * 17 + t)
+                 for t in range(int(rng.integers(3, 12)))]
+        g = wl.disjoint_union(*parts)
+        k = len(parts) + int(rng.integers(1, 6))
+    else:                                           # k equal to the multiplicity, strongly uneven sizes
+        sizes = [int(s) for s in rng.integers(5, 120, size=int(rng.integers(4, 20)))]
+        parts = [wl.random_weighted_connected(s, 3 * s, seed * 13 + t) for t, s in enumerate(sizes)]
+        g = wl.disjoint_union(*parts)
+        k = len(parts)
+    g = wl.relabel(g, rng.permutation(g[3]))
+    n = g[3]
+    k = max(1, min(k, n - 2))
+    m = int(min(n, k + rng.choice([8, 24, 60]) + 3))
+    return g, k, m
+
+
+@pytest.mark.parametrize("seed", range(int(os.environ.get("SCEIG_RANDOM_CASES", "24"))))
+def test_random_graph_families_against_dense_oracle(B, seed):
+    g, k, m = _random_family(seed)
+    rp, c, v, n = g
+    lam_full, vec_full = dense.full_spectrum(rp, c, v)
+    try:
+        lam, vec, code, stats = solve(B, g, k, 1e-10, m=m, seed=seed)
+    except B.ScError as e:                          # the budget can be too tight for any block size: a domain error
+        assert e.args[0] == B.SC_EDOMAIN and k + 3 > m
+        return
+    assert code == B.SC_OK, stats
+    check_against_oracle(g, k, lam, vec, lam_full[:k + 1], vec_full[:, :k])
