@@ -63,6 +63,10 @@ extern "C" {
                                  columns D-orthonormal (u_i^T D u_j = delta_ij), constant on every connected
                                  component for eigenvalue 0 */
 
+#define SC_FLAG_ROW_NORMALIZE 64u /* scale every row of the n x k output (the k-dimensional embedding of a node that
+                                 Section II Step 4 hands to k-means) to unit 2-norm; the columns are then no longer
+                                 eigenvectors.  Applied after SC_FLAG_RANDOM_WALK_VECTORS, which it makes immaterial */
+
 /* Options; every field 0 = default. */
 typedef struct sc_options {
   int32_t m;      /* budget of basis columns (locked + active Krylov vectors), the "number m of Lanczos

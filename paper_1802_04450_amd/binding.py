@@ -22,6 +22,7 @@ SC_FLAG_COMPONENT_NULLSPACE = 4
 SC_FLAG_NO_START_FILTER = 8
 SC_FLAG_FINAL_RR = 16
 SC_FLAG_RANDOM_WALK_VECTORS = 32
+SC_FLAG_ROW_NORMALIZE = 64
 FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 
 EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_reorder_csr", "sc_cgs2",

@@ -1075,6 +1075,8 @@ struct Solver {
     // the paper's Step 3 asks for the eigenvectors of L_n = D^-1 L: u = D^-1/2 v
     if ((flags & SC_FLAG_RANDOM_WALK_VECTORS) && nfound > 0)
       HIP_TRY(launch_scale_rows_colmajor(evecs_out, n, nfound, s.p, rowinv, st));
+    // the embedding handed to k-means (Section II Step 4) with every point on the unit sphere
+    if ((flags & SC_FLAG_ROW_NORMALIZE) && nfound > 0) HIP_TRY(launch_normalize_rows_colmajor(evecs_out, n, nfound, st));
     HIP_TRY(hipMemcpyAsync(evals_out, evals_host.data(), (size_t)k * sizeof(double), hipMemcpyHostToDevice, st));
     HIP_TRY(hipStreamSynchronize(st));
     if (debug_on()) std::fprintf(stderr, "[sceig] t=%.4fs outputs written\n", now_s() - t_begin);

@@ -123,6 +123,8 @@ hipError_t launch_spmm_vals_cheb(const int64_t* rowptr, const int32_t* col, cons
                                  double shift, double beta, double avg_deg, hipStream_t st);
 // out[t*n + o] *= s[r(o)], t < k (column-major vectors in the caller's numbering; s in the internal numbering)
 hipError_t launch_scale_rows_colmajor(double* out, int64_t n, int k, const double* s, const int32_t* inv, hipStream_t st);
+// every row of the n x k column-major matrix scaled to unit 2-norm (zero rows stay zero)
+hipError_t launch_normalize_rows_colmajor(double* out, int64_t n, int k, hipStream_t st);
 // ynext = alpha (w - shift ycur) - beta yprev and znext = s o ynext on packed n x b blocks (Chebyshev recurrence step)
 hipError_t launch_cheb_combine(const double* w, const double* ycur, const double* yprev, const double* s, double alpha,
                                double shift, double beta, double* ynext, double* znext, int64_t n, int b,

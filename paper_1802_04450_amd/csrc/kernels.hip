@@ -716,6 +716,21 @@ __global__ __launch_bounds__(kThreads) void scale_rows_colmajor_kernel(double* _
   for (int t = 0; t < k; ++t) out[(int64_t)t * n + o] *= f;
 }
 
+// Row o of the n x k column-major matrix out (the embedding of node o) is scaled to unit 2-norm; a zero row stays zero.
+__global__ __launch_bounds__(kThreads) void normalize_rows_colmajor_kernel(double* __restrict__ out, int64_t n, int k) {
+  const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (o >= n) return;
+  double ss = 0.0;
+  for (int t = 0; t < k; ++t) {
+    const double v = out[(int64_t)t * n + o];
+    ss += v * v;
+  }
+  if (ss > 0.0) {
+    const double f = 1.0 / sqrt(ss);
+    for (int t = 0; t < k; ++t) out[(int64_t)t * n + o] *= f;
+  }
+}
+
 // One step of the three-term Chebyshev recurrence on packed n x b blocks (leading dimension b):
 //   ynext = alpha * (w - shift * ycur) - beta * yprev,   znext = s o ynext   (the packed operand of the next product)
 // ynext may be the buffer of yprev (each element is read before it is written by the same thread).
@@ -1273,6 +1288,13 @@ hipError_t launch_scale_rows_colmajor(double* out, int64_t n, int k, const doubl
   if (n <= 0 || k <= 0) return hipSuccess;
   hipLaunchKernelGGL(scale_rows_colmajor_kernel, dim3((unsigned)ceil_div64(n, kThreads)), dim3(kThreads), 0, st, out, n,
                      k, s, inv);
+  return hipGetLastError();
+}
+
+hipError_t launch_normalize_rows_colmajor(double* out, int64_t n, int k, hipStream_t st) {
+  if (n <= 0 || k <= 0) return hipSuccess;
+  hipLaunchKernelGGL(normalize_rows_colmajor_kernel, dim3((unsigned)ceil_div64(n, kThreads)), dim3(kThreads), 0, st, out,
+                     n, k);
   return hipGetLastError();
 }
 

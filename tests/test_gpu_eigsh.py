@@ -353,3 +353,24 @@ def test_random_graph_families_against_dense_oracle(B, seed):
         return
     assert code == B.SC_OK, stats
     check_against_oracle(g, k, lam, vec, lam_full[:k + 1], vec_full[:, :k])
+
+
+def test_row_normalized_embedding(B):
+    """SC_FLAG_ROW_NORMALIZE: the rows of the output (the points k-means clusters, Section II Step 4) have unit norm and
+    equal the rows of the plain output divided by their norm; on a union of components with k = their number the rows
+    of one component coincide and rows of different components are orthogonal."""
+    parts = [wl.ring(9), wl.path(14), wl.random_weighted_connected(30, 60, 5), wl.complete(5), wl.ring(21)]
+    g = wl.disjoint_union(*parts)
+    g = wl.relabel(g, np.random.default_rng(9).permutation(g[3]))
+    rp, c, v, n = g
+    k = len(parts)
+    _, vec, code, _ = solve(B, g, k, 1e-10, seed=3)
+    for f in (B.SC_FLAG_ROW_NORMALIZE, B.SC_FLAG_ROW_NORMALIZE | B.SC_FLAG_RANDOM_WALK_VECTORS):
+        _, emb, code2, _ = solve(B, g, k, 1e-10, seed=3, flags=f)
+        assert code == code2 == B.SC_OK
+        assert np.max(np.abs(np.linalg.norm(emb, axis=1) - 1.0)) <= 1e-14
+        assert np.max(np.abs(emb - vec / np.linalg.norm(vec, axis=1, keepdims=True))) <= 1e-13
+        _, label = components.component_labels(rp, c, v)
+        gram = emb @ emb.T
+        same = label[:, None] == label[None, :]
+        assert np.max(np.abs(gram[same] - 1.0)) <= 1e-7 and np.max(np.abs(gram[~same])) <= 1e-7

@@ -342,3 +342,58 @@ def test_chebyshev_filter_closed_form_on_eigenvectors():
     gs = (2.0 * laplacian.dense_s(rp, c, v) - (a - 1.0) * np.eye(n)) / (a + 1.0)
     assert np.max(np.abs(blockops.chebyshev_filter(rp, c, v, x, a, 1) - gs @ x)) < 1e-13
     assert np.max(np.abs(blockops.chebyshev_filter(rp, c, v, x, a, 2) - (2.0 * gs @ (gs @ x) - x))) < 1e-12
+
+
+def test_kmeans_oracle_pins():
+    """Algorithms 4-5 against what the mathematics fixes: hand-computed tiny cases, exact recovery of far-apart
+    groups with centres equal to the group means, monotone objective, the fixed-point conditions, and the sampling
+    rule of the seeding on a case whose draws can be followed by hand."""
+    from oracle import kmeans as km
+    # the generator: values in [0, 1), reproducible, different per index and seed
+    u = [km.uniform01(7, i) for i in range(1000)]
+    assert all(0.0 <= t < 1.0 for t in u) and len(set(u)) == 1000 and u[3] == km.uniform01(7, 3) != km.uniform01(8, 3)
+    assert abs(np.mean(u) - 0.5) < 0.03 and abs(np.var(u) - 1.0 / 12.0) < 0.01
+    # four points on a line, centres started at the two left points: by hand
+    x = np.array([[0.0], [1.0], [9.0], [10.0]])
+    labels, cen, iters, hist, conv = km.lloyd(x, x[:2], 10)
+    # it 1: centres 0,1 -> labels 0,1,1,1 (objective 0+0+64+81); centres 0, 20/3
+    # it 2: point 1 is nearer to 0 (1 < 5.67) -> labels 0,0,1,1; centres 0.5, 9.5;  it 3: unchanged
+    assert labels.tolist() == [0, 0, 1, 1] and np.allclose(cen[:, 0], [0.5, 9.5]) and conv and iters == 3
+    assert np.allclose(hist, [145.0, 1.0 + (9 - 20 / 3) ** 2 + (10 - 20 / 3) ** 2, 1.0])
+    # ties go to the first centre; an empty cluster keeps its centre
+    lab, _ = km.assign(np.array([[1.0]]), np.array([[0.0], [2.0]]))
+    assert lab.tolist() == [0]
+    assert np.array_equal(km.update_centroids(x, np.array([0, 0, 0, 0]), np.array([[5.0], [7.0]])), [[5.0], [7.0]])
+    # far-apart groups: exact recovery whatever the seed, centres are the group means, objective = within-group scatter
+    rng = np.random.default_rng(3)
+    means = 100.0 * np.eye(5)[:, :4] + 50.0
+    truth = rng.integers(0, 5, size=400)
+    pts = means[truth] + rng.standard_normal((400, 4))
+    for seed in range(5):
+        labels, cen, iters, hist, conv = km.kmeans(pts, 5, seed)
+        assert conv and np.all(np.diff(hist) <= 1e-9)
+        perm = {int(labels[np.flatnonzero(truth == g)[0]]): g for g in range(5)}
+        assert len(perm) == 5 and all(perm[int(l)] == t for l, t in zip(labels, truth))
+        for j, g in perm.items():
+            assert np.allclose(cen[j], pts[truth == g].mean(axis=0), atol=1e-12)
+        scatter = sum(((pts[truth == g] - pts[truth == g].mean(axis=0)) ** 2).sum() for g in range(5))
+        assert abs(km.objective(pts, labels, cen) - scatter) < 1e-9 * scatter
+        # fixed point: every point is at least as near to its own centre as to any other
+        lab2, dist = km.assign(pts, cen)
+        assert np.array_equal(lab2, labels)
+    # seeding: k = n distinct points picks every point once (a chosen point has distance 0 and cannot be drawn again)
+    idx = km.kmeanspp_indices(pts[:40], 40, 11)
+    assert sorted(idx.tolist()) == list(range(40))
+    # seeding by hand: points 0, 1, 3 on a line, seed chosen so that the first draw is point 0: the second point is
+    # 1 with probability 1/10 and 3 with probability 9/10 (squared distances 1 and 9)
+    line = np.array([[0.0], [1.0], [3.0]])
+    counts = {1: 0, 2: 0}
+    tried = 0
+    for seed in range(4000):
+        if int(km.uniform01(seed, 0) * 3) != 0:
+            continue
+        tried += 1
+        second = int(km.kmeanspp_indices(line, 2, seed)[1])
+        assert second == (1 if km.uniform01(seed, 1) * 10.0 < 1.0 else 2)
+        counts[second] += 1
+    assert tried > 1000 and abs(counts[2] / tried - 0.9) < 0.03
