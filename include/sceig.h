@@ -252,6 +252,55 @@ int sc_sym_eig(const double* a, int32_t n, double* w, double* z);
  */
 int sc_sym_eig_top(const double* a, int32_t n, int32_t count, double* w, double* z);
 
+/*
+ * k-means on the rows of the eigenvector matrix (Section II Step 4; Section IV-C, Algorithms 4 and 5).
+ *
+ * Points: n points with d coordinates, device fp64, read only.  colmajor != 0: coordinate t of point i at
+ * points[t*ld + i], ld >= n (the evecs_out layout of sc_laplacian_eigsh, so its output can be passed on as it is);
+ * colmajor == 0: points[i*ld + t], ld >= d.  Centres: device fp64[k*d], row-major k x d.  Labels: device int32[n].
+ * 1 <= k <= n <= 2^27, d >= 1 (else SC_EDOMAIN).  All work is enqueued on `stream`; the calls return after it is done.
+ * The library stages its own row-major copy of the points and never keeps a caller's pointer.
+ */
+typedef struct sc_kmeans_stats {
+  int32_t iterations;   /* labelling steps done */
+  int32_t converged;    /* 1 if the last labelling step changed no label */
+  int32_t last_changes; /* labels changed by the last labelling step */
+  int32_t reserved;
+  double objective;     /* sum of squared distances of the points to the centres of their labels; -1 if the run stopped
+                           at max_iter (the centres moved after the last labelling) */
+  double t_total;       /* seconds, host clock, whole call */
+  double t_seed;        /* seconds spent in the seeding */
+} sc_kmeans_stats;
+
+/*
+ * Seeding (Algorithm 5): the first centre is the point floor(u_0 * n); centre i > 0 is drawn with probability
+ * proportional to the squared distance to the nearest centre chosen so far: the first index whose inclusive prefix
+ * sum of those squared distances exceeds u_i * (their total); the last point if no index does.  u_i is the i-th
+ * number of a counter-based generator: the top 53 bits of mix(mix(seed) + i) scaled to [0, 1), mix being the
+ * splitmix64 output function (add 0x9E3779B97F4A7C15, xor-shift 30, multiply 0xBF58476D1CE4E5B9, xor-shift 27,
+ * multiply 0x94D049BB133111EB, xor-shift 31).
+ *   chosen_out     device int32[k], indices of the chosen points in drawing order (may be NULL)
+ *   centroids_out  device fp64[k*d], the chosen points
+ */
+int sc_kmeanspp(const double* points, int64_t ld, int32_t colmajor, int64_t n, int32_t d, int32_t k, uint64_t seed,
+                int32_t* chosen_out, double* centroids_out, void* stream);
+
+/*
+ * Lloyd iterations (Algorithm 4 step 3) from the centres given in `centroids`, which are updated in place.
+ * One iteration: label of every point = the nearest centre, decided on |c_j|^2 - 2 <v_i, c_j> (the expanded form of
+ * Section IV-C with the product V C^T on the fp64 matrix cores; the lowest index wins a tie); stop if no label
+ * changed; else every centre becomes the mean of its points (points grouped by a sort on the labels; a centre without
+ * points stays where it is).  At most max_iter (>= 1) labelling steps.
+ * Returns SC_OK, or SC_NOT_CONVERGED if labels still changed in the last step (outputs hold the last labels and the
+ * centres computed from them).
+ */
+int sc_kmeans_lloyd(const double* points, int64_t ld, int32_t colmajor, int64_t n, int32_t d, int32_t k,
+                    double* centroids, int32_t max_iter, int32_t* labels_out, sc_kmeans_stats* stats, void* stream);
+
+/* Algorithm 4: sc_kmeanspp followed by sc_kmeans_lloyd. */
+int sc_kmeans(const double* points, int64_t ld, int32_t colmajor, int64_t n, int32_t d, int32_t k, uint64_t seed,
+              int32_t max_iter, int32_t* labels_out, double* centroids_out, sc_kmeans_stats* stats, void* stream);
+
 const char* sc_strerror(int code);
 int sc_version(void);
 

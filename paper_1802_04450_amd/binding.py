@@ -27,7 +27,7 @@ FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 
 EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_reorder_csr", "sc_cgs2",
            "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version", "sc_release_cache",
-           "sc_chebyshev_filter"]
+           "sc_chebyshev_filter", "sc_kmeanspp", "sc_kmeans_lloyd", "sc_kmeans"]
 
 
 class ScOptions(ctypes.Structure):
@@ -51,6 +51,15 @@ class ScStats(ctypes.Structure):
             v = getattr(self, name)
             out[name] = list(v) if name.startswith("fam_") else v
         return out
+
+
+class ScKMeansStats(ctypes.Structure):
+    _fields_ = [("iterations", ctypes.c_int32), ("converged", ctypes.c_int32), ("last_changes", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("objective", ctypes.c_double), ("t_total", ctypes.c_double),
+                ("t_seed", ctypes.c_double)]
+
+    def as_dict(self) -> dict:
+        return {name: getattr(self, name) for name, _ in self._fields_ if name != "reserved"}
 
 
 class ScError(RuntimeError):
@@ -84,6 +93,10 @@ def lib() -> ctypes.CDLL:
         _lib.sc_block_qr.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         _lib.sc_rotate.argtypes = [vp, i64, i64, i32, i32, vp, i32, vp, i64, i32, vp]
         _lib.sc_chebyshev_filter.argtypes = [vp, vp, vp, i64, vp, i64, i32, dbl, i32, vp, i64, vp]
+        u64 = ctypes.c_uint64
+        _lib.sc_kmeanspp.argtypes = [vp, i64, i32, i64, i32, i32, u64, vp, vp, vp]
+        _lib.sc_kmeans_lloyd.argtypes = [vp, i64, i32, i64, i32, i32, vp, i32, vp, ctypes.POINTER(ScKMeansStats), vp]
+        _lib.sc_kmeans.argtypes = [vp, i64, i32, i64, i32, i32, u64, i32, vp, vp, ctypes.POINTER(ScKMeansStats), vp]
         _lib.sc_sym_eig.argtypes = [vp, i32, vp, vp]
         _lib.sc_sym_eig_top.argtypes = [vp, i32, i32, vp, vp]
         for name in EXPORTS:
@@ -256,6 +269,61 @@ def sc_chebyshev_filter(rowptr, col, val, x, a: float, degree: int):
                                          float(a), int(degree), _ptr(y), ncols, _stream())
     _check(code)
     return y
+
+
+def _points_layout(points, colmajor: bool):
+    """(n, d, ld) of a 2-d device tensor holding the points: shape (n, d) row-major, or shape (d, n) with
+    colmajor=True (row t = coordinate t of every point, the layout sc_laplacian_eigsh returns)."""
+    import torch
+    _dev(points, torch.float64)
+    if colmajor:
+        d, n = points.shape
+    else:
+        n, d = points.shape
+    return n, d, points.stride(0)
+
+
+def sc_kmeanspp(points, k: int, seed: int, colmajor: bool = False):
+    """Algorithm 5.  Returns (chosen int32[k] device, centres (k, d) device)."""
+    import torch
+    n, d, ld = _points_layout(points, colmajor)
+    chosen = torch.empty(max(k, 0), dtype=torch.int32, device=points.device)
+    cen = torch.empty((max(k, 0), d), dtype=torch.float64, device=points.device)
+    with torch.cuda.device(points.device):
+        code = lib().sc_kmeanspp(_ptr(points), ld, 1 if colmajor else 0, n, d, k, seed, _ptr(chosen), _ptr(cen),
+                                 _stream())
+    _check(code)
+    return chosen, cen
+
+
+def sc_kmeans_lloyd(points, centroids, max_iter: int = 100, colmajor: bool = False):
+    """Algorithm 4 step 3 from `centroids` ((k, d) device, not modified).  Returns (labels int32[n], centres (k, d),
+    status code, stats dict)."""
+    import torch
+    n, d, ld = _points_layout(points, colmajor)
+    cen = _dev(centroids, torch.float64).clone()
+    k = cen.shape[0]
+    labels = torch.empty(n, dtype=torch.int32, device=points.device)
+    stats = ScKMeansStats()
+    with torch.cuda.device(points.device):
+        code = lib().sc_kmeans_lloyd(_ptr(points), ld, 1 if colmajor else 0, n, d, k, _ptr(cen), max_iter,
+                                     _ptr(labels), ctypes.byref(stats), _stream())
+    _check(code)
+    return labels, cen, code, stats.as_dict()
+
+
+def sc_kmeans(points, k: int, seed: int, max_iter: int = 100, colmajor: bool = False):
+    """Algorithm 4.  Returns (labels int32[n], centres (k, d), status code, stats dict)."""
+    import torch
+    n, d, ld = _points_layout(points, colmajor)
+    labels = torch.empty(n, dtype=torch.int32, device=points.device)
+    cen = torch.empty((max(k, 0), d), dtype=torch.float64, device=points.device)
+    stats = ScKMeansStats()
+    with torch.cuda.device(points.device):
+        code = lib().sc_kmeans(_ptr(points), ld, 1 if colmajor else 0, n, d, k, seed, max_iter, _ptr(labels),
+                               _ptr(cen), ctypes.byref(stats), _stream())
+    _check(code)
+    return labels, cen, code, stats.as_dict()
 
 
 def sc_sym_eig(a: np.ndarray, vectors: bool = True) -> Tuple[np.ndarray, Optional[np.ndarray]]:

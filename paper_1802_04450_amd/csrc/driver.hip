@@ -1117,6 +1117,162 @@ bool supported_block(int b) { return b == 1 || b == 2 || b == 4 || b == 8 || b =
 
 using namespace sceig;
 
+// ---- k-means on the embedding (Section II Step 4, Section IV-C, Algorithms 4 and 5) ------------------------------
+namespace {
+
+// Counter-based uniform numbers in [0, 1) for the seeding draws: top 53 bits of mix(mix(seed) + index).
+uint64_t km_mix64(uint64_t x) {
+  x += 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+double km_uniform01(uint64_t seed, uint64_t index) {
+  return (double)(km_mix64(km_mix64(seed) + index) >> 11) * (1.0 / 9007199254740992.0);
+}
+
+struct KMeans {
+  const double* points;
+  int64_t ld;
+  int colmajor;
+  int64_t n;
+  int d, k;
+  hipStream_t st;
+  int64_t ldx = 0;
+  DevBuf<double> x;
+
+  void stage() {  // row-major, zero padded, 32-byte aligned rows: the left operand of the distance product
+    ldx = ((int64_t)d + 3) / 4 * 4;
+    x.alloc((size_t)n * ldx);
+    HIP_TRY(launch_points_to_rowmajor(points, ld, colmajor, n, d, x.p, ldx, st));
+  }
+
+  // Algorithm 5: chosen (device int32[k]) and the chosen points as centres (device k x ldx)
+  void seed(uint64_t seed_value, int32_t* chosen, double* c) {
+    std::vector<double> u((size_t)k);
+    for (int i = 0; i < k; ++i) u[i] = km_uniform01(seed_value, (uint64_t)i);
+    const size_t wb = kmeans_seed_workspace(n);
+    DevBuf<char> work;
+    work.alloc(wb);
+    HIP_TRY(launch_kmeanspp(x.p, ldx, d, n, k, u.data(), work.p, wb, chosen, st));
+    HIP_TRY(launch_gather_rows(x.p, ldx, chosen, k, c, st));
+    HIP_TRY(hipStreamSynchronize(st));  // u and work are released on return
+  }
+
+  // Algorithm 4 step 3 from the centres in c (device k x ldx, updated in place)
+  int lloyd(double* c, int max_iter, int32_t* labels, sc_kmeans_stats* stats) {
+    const int64_t ldc = ((int64_t)k + 15) / 16 * 16;
+    int64_t chunk = ((int64_t)1 << 27) / ldc / 128 * 128;  // distance block of at most 1 GiB
+    if (chunk < 128) chunk = 128;
+    if (chunk > n) chunk = n;
+    DevBuf<double> ct, cnorm, sblock, part;
+    DevBuf<int32_t> start;
+    DevBuf<int> changes;
+    DevBuf<char> work;
+    PinnedBuf<int> hchanges;
+    ct.alloc((size_t)ldx * ldc);
+    cnorm.alloc((size_t)k);
+    sblock.alloc((size_t)chunk * ldc);
+    start.alloc((size_t)k + 1);
+    changes.alloc(1);
+    hchanges.alloc(1);
+    const size_t wb = kmeans_update_workspace(n);
+    work.alloc(wb);
+    HIP_TRY(launch_fill_int32(labels, n, -1, 0, st));
+    int iters = 0, converged = 0, last_changes = 0;
+    for (int it = 0; it < max_iter; ++it) {
+      HIP_TRY(launch_fill_int32(changes.p, 1, 0, 0, st));
+      HIP_TRY(launch_centroid_operand(c, ldx, k, d, (int)ldx, ct.p, ldc, cnorm.p, st));
+      for (int64_t r0 = 0; r0 < n; r0 += chunk) {
+        const int64_t rows = std::min<int64_t>(chunk, n - r0);
+        HIP_TRY(launch_row_gemm(x.p + r0 * ldx, rows, ldx, 0, d, ct.p, (int)ldc, k, 1, 0, sblock.p, ldc, nullptr, st));
+        HIP_TRY(launch_argmin(sblock.p, ldc, rows, k, cnorm.p, labels + r0, changes.p, st));
+      }
+      HIP_TRY(hipMemcpyAsync(hchanges.p, changes.p, sizeof(int), hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipStreamSynchronize(st));
+      ++iters;
+      last_changes = *hchanges.p;
+      if (last_changes == 0) {
+        converged = 1;
+        break;
+      }
+      HIP_TRY(launch_centroid_update(x.p, ldx, d, n, labels, k, work.p, wb, start.p, c, st));
+    }
+    if (stats) {
+      // objective of the final labelling against the centres it was computed from (after a converged run these are
+      // also the means of their clusters)
+      const int np = kmeans_objective_parts();
+      part.alloc((size_t)np);
+      std::vector<double> hp((size_t)np);
+      if (converged || max_iter == 0 || iters == 0) {
+        HIP_TRY(launch_objective(x.p, ldx, d, n, labels, c, part.p, st));
+        HIP_TRY(hipMemcpyAsync(hp.data(), part.p, sizeof(double) * np, hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        double tot = 0.0;
+        for (int p = 0; p < np; ++p) tot += hp[p];
+        stats->objective = tot;
+      } else {
+        stats->objective = -1.0;  // the centres moved after the last labelling
+      }
+      stats->iterations = iters;
+      stats->converged = converged;
+      stats->last_changes = last_changes;
+    }
+    return converged ? SC_OK : SC_NOT_CONVERGED;
+  }
+};
+
+struct KMeansCall {
+  KMeans km;
+  uint64_t seed;
+  int max_iter;
+  int mode;  // 0 = seeding only, 1 = Lloyd from given centres, 2 = both
+  int32_t* chosen_out;
+  int32_t* labels_out;
+  double* centroids;  // k x d row-major, caller's
+  sc_kmeans_stats* stats;
+};
+
+int run_kmeans(void* p) {
+  KMeansCall* c = static_cast<KMeansCall*>(p);
+  KMeans& km = c->km;
+  const auto t0 = std::chrono::steady_clock::now();
+  km.stage();
+  DevBuf<double> cen;
+  DevBuf<int32_t> chosen;
+  cen.alloc((size_t)km.k * km.ldx);
+  double t_seed = 0.0;
+  if (c->mode != 1) {
+    int32_t* ch = c->chosen_out;
+    if (!ch) {
+      chosen.alloc((size_t)km.k);
+      ch = chosen.p;
+    }
+    km.seed(c->seed, ch, cen.p);
+    t_seed = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+  } else {
+    HIP_TRY(launch_points_to_rowmajor(c->centroids, km.d, 0, km.k, km.d, cen.p, km.ldx, km.st));
+  }
+  int rc = SC_OK;
+  if (c->mode != 0) rc = km.lloyd(cen.p, c->max_iter, c->labels_out, c->stats);
+  HIP_TRY(launch_copy_rows(cen.p, km.ldx, c->centroids, km.d, km.k, km.d, km.st));
+  HIP_TRY(hipStreamSynchronize(km.st));
+  if (c->stats) {
+    c->stats->t_seed = t_seed;
+    c->stats->t_total = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+  }
+  return rc;
+}
+
+int kmeans_args_ok(const double* points, int64_t ld, int32_t colmajor, int64_t n, int32_t d, int32_t k) {
+  if (!points || n < 0 || ld < 0) return SC_EINVAL;
+  if (n < 1 || n > (int64_t)0x7fffffff / 16 || d < 1 || k < 1 || (int64_t)k > n) return SC_EDOMAIN;
+  if (ld < (colmajor ? n : (int64_t)d)) return SC_EDOMAIN;
+  return SC_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 int sc_version(void) { return 100; }
@@ -1501,6 +1657,40 @@ int sc_chebyshev_filter(const int64_t* csr_rowptr, const int32_t* csr_col, const
         return SC_OK;
       },
       &ctx);
+}
+
+int sc_kmeanspp(const double* points, int64_t ld, int32_t colmajor, int64_t n, int32_t d, int32_t k, uint64_t seed,
+                int32_t* chosen_out, double* centroids_out, void* stream) {
+  if (!centroids_out) return SC_EINVAL;
+  const int a = kmeans_args_ok(points, ld, colmajor, n, d, k);
+  if (a != SC_OK) return a;
+  KMeansCall call{{points, ld, colmajor, n, d, k, reinterpret_cast<hipStream_t>(stream)}, seed, 0, 0, chosen_out, nullptr,
+                  centroids_out, nullptr};
+  return guarded(run_kmeans, &call);
+}
+
+int sc_kmeans_lloyd(const double* points, int64_t ld, int32_t colmajor, int64_t n, int32_t d, int32_t k,
+                    double* centroids, int32_t max_iter, int32_t* labels_out, sc_kmeans_stats* stats, void* stream) {
+  if (!centroids || !labels_out) return SC_EINVAL;
+  const int a = kmeans_args_ok(points, ld, colmajor, n, d, k);
+  if (a != SC_OK) return a;
+  if (max_iter < 1) return SC_EDOMAIN;
+  if (stats) *stats = sc_kmeans_stats{};
+  KMeansCall call{{points, ld, colmajor, n, d, k, reinterpret_cast<hipStream_t>(stream)}, 0, max_iter, 1, nullptr,
+                  labels_out, centroids, stats};
+  return guarded(run_kmeans, &call);
+}
+
+int sc_kmeans(const double* points, int64_t ld, int32_t colmajor, int64_t n, int32_t d, int32_t k, uint64_t seed,
+              int32_t max_iter, int32_t* labels_out, double* centroids_out, sc_kmeans_stats* stats, void* stream) {
+  if (!centroids_out || !labels_out) return SC_EINVAL;
+  const int a = kmeans_args_ok(points, ld, colmajor, n, d, k);
+  if (a != SC_OK) return a;
+  if (max_iter < 1) return SC_EDOMAIN;
+  if (stats) *stats = sc_kmeans_stats{};
+  KMeansCall call{{points, ld, colmajor, n, d, k, reinterpret_cast<hipStream_t>(stream)}, seed, max_iter, 2, nullptr,
+                  labels_out, centroids_out, stats};
+  return guarded(run_kmeans, &call);
 }
 
 int sc_sym_eig(const double* a, int32_t n, double* w, double* z) {

@@ -132,4 +132,31 @@ hipError_t launch_cheb_combine(const double* w, const double* ycur, const double
 hipError_t launch_copy_cols(const double* src, int64_t lds, int scol0, double* dst, int64_t ldd, int dcol0, int w,
                             int64_t n, hipStream_t st);
 
+// ---- k-means on the embedding (Section IV-C, Algorithms 4-5; kmeans.hip) ------------------------
+// x (n x ldx row-major, zero padded beyond d) from the caller's points (column-major v[t*ldv + i] or row-major)
+hipError_t launch_points_to_rowmajor(const double* v, int64_t ldv, int colmajor, int64_t n, int d, double* x, int64_t ldx,
+                                     hipStream_t st);
+// ct (dpad x ldc row-major) = transpose of the k x ldx centre array, cnorm[j] = |c_j|^2
+hipError_t launch_centroid_operand(const double* c, int64_t ldx, int k, int d, int dpad, double* ct, int64_t ldc,
+                                   double* cnorm, hipStream_t st);
+// label[i] = arg-min_j cnorm[j] - 2 s[i, j] (first on ties); *changes += number of labels that changed
+hipError_t launch_argmin(const double* s, int64_t lds, int64_t n, int k, const double* cnorm, int32_t* label,
+                         int* changes, hipStream_t st);
+hipError_t launch_fill_int32(int32_t* a, int64_t n, int32_t value, int use_iota, hipStream_t st);
+// centres = means of their points (sort by label, fixed summation order); empty clusters keep their centre.
+// work: kmeans_update_workspace(n) bytes; start: device int32[k+1] (first sorted position of every cluster)
+size_t kmeans_update_workspace(int64_t n);
+hipError_t launch_centroid_update(const double* x, int64_t ldx, int d, int64_t n, const int32_t* label, int k, void* work,
+                                  size_t work_bytes, int32_t* start, double* c, hipStream_t st);
+// Algorithm 5 with the uniform numbers u[0..k-1] supplied by the host; chosen: device int32[k]
+size_t kmeans_seed_workspace(int64_t n);
+hipError_t launch_kmeanspp(const double* x, int64_t ldx, int d, int64_t n, int k, const double* u, void* work,
+                           size_t work_bytes, int32_t* chosen, hipStream_t st);
+hipError_t launch_gather_rows(const double* x, int64_t ldx, const int32_t* index, int k, double* c, hipStream_t st);
+// part[p], p < kmeans_objective_parts(): partial sums of |x_i - c_label(i)|^2 (add them in order on the host)
+int kmeans_objective_parts();
+hipError_t launch_objective(const double* x, int64_t ldx, int d, int64_t n, const int32_t* label, const double* c,
+                            double* part, hipStream_t st);
+hipError_t launch_copy_rows(const double* src, int64_t lds, double* dst, int64_t ldd, int rows, int cols, hipStream_t st);
+
 }  // namespace sceig

@@ -1,0 +1,354 @@
+// k-means on the rows of the eigenvector matrix (paper Section II Step 4, Section IV-C, Algorithms 4 and 5): device
+// kernels.  The distance step is the paper's expanded form S = |v|^2 + |c|^2 - 2 V C^T with the product on the fp64
+// matrix cores (row_gemm_kernel, kernels.hip); |v|^2 does not change the arg-min and is left out.  The centre update
+// is sort based as in the paper (points ordered by label, every cluster a contiguous run), with a fixed summation
+// order so that results are reproducible.  The seeding follows Algorithm 5 with the uniform numbers supplied by the
+// host (a counter-based generator), prefix sums from hipCUB.
+#include <hip/hip_runtime.h>
+#include <hipcub/hipcub.hpp>
+
+#include <cstdint>
+
+#include "kernels.h"
+
+namespace sceig {
+namespace {
+
+constexpr int kT = 256;
+inline unsigned blocks(int64_t n) { return (unsigned)((n + kT - 1) / kT); }
+
+// X[i, t] (row-major, leading dimension ldx >= d, zero padded) from the caller's points: coordinate t of point i at
+// v[t * ldv + i] (column-major, the eigenvector output) or v[i * ldv + t] (row-major).  64 x 64 tiles through LDS so
+// that reads and writes both run over consecutive addresses in the column-major case.
+__global__ __launch_bounds__(kT) void points_to_rowmajor_kernel(const double* __restrict__ v, int64_t ldv, int colmajor,
+                                                                int64_t n, int d, double* __restrict__ x,
+                                                                int64_t ldx) {
+  __shared__ double tile[64][65];
+  const int64_t i0 = (int64_t)blockIdx.x * 64;
+  const int t0 = blockIdx.y * 64;
+  for (int idx = threadIdx.x; idx < 64 * 64; idx += kT) {
+    // column-major source: consecutive threads walk the points; row-major source: they walk the coordinates
+    const int a = idx / 64, b = idx % 64;
+    const int64_t i = i0 + (colmajor ? b : a);
+    const int t = t0 + (colmajor ? a : b);
+    double val = 0.0;
+    if (i < n && t < d) val = colmajor ? v[(int64_t)t * ldv + i] : v[i * ldv + t];
+    tile[colmajor ? b : a][colmajor ? a : b] = val;  // tile[point][coordinate]
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < 64 * 64; idx += kT) {
+    const int r = idx / 64, c = idx % 64;
+    if (i0 + r < n && t0 + c < ldx) x[(i0 + r) * ldx + t0 + c] = tile[r][c];
+  }
+}
+
+// ct[t * ldc + j] = c[j * ldx + t] (the right-hand operand of V C^T, zero padded to ldc columns and dpad rows) and
+// cnorm[j] = |c_j|^2.  One workgroup per centre.
+__global__ __launch_bounds__(kT) void centroid_operand_kernel(const double* __restrict__ c, int64_t ldx, int k, int d,
+                                                              int dpad, double* __restrict__ ct, int64_t ldc,
+                                                              double* __restrict__ cnorm) {
+  __shared__ double part[kT / 64];
+  const int j = blockIdx.x;
+  double ss = 0.0;
+  for (int t = threadIdx.x; t < dpad; t += kT) {
+    const double val = t < d ? c[(int64_t)j * ldx + t] : 0.0;
+    ct[(int64_t)t * ldc + j] = val;
+    ss += val * val;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+  if (threadIdx.x % 64 == 0) part[threadIdx.x / 64] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double tot = 0.0;
+    for (int w = 0; w < kT / 64; ++w) tot += part[w];
+    cnorm[j] = tot;
+  }
+  (void)k;
+}
+
+// label[i] = arg-min over j of cnorm[j] - 2 s[i, j] (the first one on ties); counts the labels that changed.
+// 16 lanes per point.
+__global__ __launch_bounds__(kT) void argmin_kernel(const double* __restrict__ s, int64_t lds, int64_t n, int k,
+                                                    const double* __restrict__ cnorm, int32_t* __restrict__ label,
+                                                    int* __restrict__ changes) {
+  constexpr int L = 16;
+  __shared__ int block_changes;
+  if (threadIdx.x == 0) block_changes = 0;
+  __syncthreads();
+  const int lane = threadIdx.x % L;
+  const int64_t i = (int64_t)blockIdx.x * (kT / L) + threadIdx.x / L;
+  if (i < n) {
+    double best = 1.79769313486231570815e308;
+    int bj = 0x7fffffff;
+    for (int j = lane; j < k; j += L) {
+      const double val = cnorm[j] - 2.0 * s[i * lds + j];
+      if (val < best) {  // j grows: an equal value later does not replace an earlier one
+        best = val;
+        bj = j;
+      }
+    }
+#pragma unroll
+    for (int o = L / 2; o > 0; o >>= 1) {
+      const double ob = __shfl_xor(best, o, L);
+      const int oj = __shfl_xor(bj, o, L);
+      if (ob < best || (ob == best && oj < bj)) {
+        best = ob;
+        bj = oj;
+      }
+    }
+    if (lane == 0) {
+      if (label[i] != bj) atomicAdd(&block_changes, 1);
+      label[i] = bj;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0 && block_changes) atomicAdd(changes, block_changes);
+}
+
+__global__ __launch_bounds__(kT) void iota_fill_kernel(int32_t* __restrict__ a, int64_t n, int32_t value, int use_iota) {
+  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i < n) a[i] = use_iota ? (int32_t)i : value;
+}
+
+// start[c] = first position in the sorted label array with label >= c, c = 0 .. k
+__global__ __launch_bounds__(kT) void cluster_starts_kernel(const int32_t* __restrict__ sorted_label, int64_t n, int k,
+                                                            int32_t* __restrict__ start) {
+  const int c = blockIdx.x * kT + threadIdx.x;
+  if (c > k) return;
+  int64_t lo = 0, hi = n;
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) / 2;
+    if (sorted_label[mid] < c) {
+      lo = mid + 1;
+    } else {
+      hi = mid;
+    }
+  }
+  start[c] = (int32_t)lo;
+}
+
+// c[j, :] = mean of the points of cluster j (rows x[member[m]], start[j] <= m < start[j+1]); an empty cluster keeps
+// its centre.  Workgroup (j, column tile of 64): wave w sums the members w, w+4, ... in order, the four partial sums
+// are added in wave order.
+__global__ __launch_bounds__(kT) void centroid_mean_kernel(const double* __restrict__ x, int64_t ldx, int d,
+                                                           const int32_t* __restrict__ member,
+                                                           const int32_t* __restrict__ start, double* __restrict__ c) {
+  __shared__ double part[kT / 64][64];
+  const int j = blockIdx.x;
+  const int t = blockIdx.y * 64 + threadIdx.x % 64;
+  const int w = threadIdx.x / 64;
+  const int m0 = start[j], m1 = start[j + 1];
+  double acc = 0.0;
+  if (t < d)
+    for (int m = m0 + w; m < m1; m += kT / 64) acc += x[(int64_t)member[m] * ldx + t];
+  part[w][threadIdx.x % 64] = acc;
+  __syncthreads();
+  if (w == 0 && t < d && m1 > m0) {
+    double tot = part[0][threadIdx.x];
+    for (int q = 1; q < kT / 64; ++q) tot += part[q][threadIdx.x];
+    c[(int64_t)j * ldx + t] = tot / (double)(m1 - m0);
+  }
+}
+
+// dist2[i] = |x_i - x_c|^2 (first != 0) or min(dist2[i], |x_i - x_c|^2), c = *centre.  16 lanes per point.
+__global__ __launch_bounds__(kT) void seed_distance_kernel(const double* __restrict__ x, int64_t ldx, int d, int64_t n,
+                                                           const int32_t* __restrict__ centre, int first,
+                                                           double* __restrict__ dist2) {
+  constexpr int L = 16;
+  const int lane = threadIdx.x % L;
+  const int64_t i = (int64_t)blockIdx.x * (kT / L) + threadIdx.x / L;
+  if (i >= n) return;
+  const int64_t c = *centre;
+  double acc = 0.0;
+  for (int t = lane; t < d; t += L) {
+    const double diff = x[i * ldx + t] - x[c * ldx + t];
+    acc += diff * diff;
+  }
+#pragma unroll
+  for (int o = L / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, L);
+  if (lane == 0) dist2[i] = first ? acc : (acc < dist2[i] ? acc : dist2[i]);
+}
+
+// Algorithm 5's draw: the first index whose inclusive prefix sum exceeds u * total; *chosen was preset to n - 1 for
+// the case that no index qualifies.  A parallel prefix sum may be non-monotone by a rounding, so more than one index
+// can pass the test: the smallest one wins (atomic minimum), whatever the order the threads run in.
+__global__ __launch_bounds__(kT) void seed_pick_kernel(const double* __restrict__ cs, int64_t n, double u,
+                                                       int32_t* __restrict__ chosen) {
+  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= n) return;
+  const double r = u * cs[n - 1];
+  const double prev = i ? cs[i - 1] : 0.0;
+  if (prev <= r && r < cs[i]) atomicMin(chosen, (int32_t)i);
+}
+
+// c[j, :] = x[index[j], :]
+__global__ __launch_bounds__(kT) void gather_rows_kernel(const double* __restrict__ x, int64_t ldx,
+                                                         const int32_t* __restrict__ index, int k,
+                                                         double* __restrict__ c) {
+  const int64_t idx = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (idx >= (int64_t)k * ldx) return;
+  const int64_t j = idx / ldx;
+  c[idx] = x[(int64_t)index[j] * ldx + (idx - j * ldx)];
+}
+
+// part[block] = sum over the block's points of |x_i - c_label(i)|^2; fixed assignment of points to threads and a
+// fixed tree, so the partial sums are reproducible.  Grid-stride over points, one thread per point and trip.
+__global__ __launch_bounds__(kT) void objective_kernel(const double* __restrict__ x, int64_t ldx, int d, int64_t n,
+                                                       const int32_t* __restrict__ label, const double* __restrict__ c,
+                                                       double* __restrict__ part) {
+  __shared__ double red[kT];
+  double acc = 0.0;
+  for (int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x; i < n; i += (int64_t)gridDim.x * kT) {
+    const double* xi = x + i * ldx;
+    const double* cj = c + (int64_t)label[i] * ldx;
+    double s2 = 0.0;
+    for (int t = 0; t < d; ++t) {
+      const double diff = xi[t] - cj[t];
+      s2 += diff * diff;
+    }
+    acc += s2;
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int o = kT / 2; o > 0; o >>= 1) {
+    if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) part[blockIdx.x] = red[0];
+}
+
+// out[i * ldo + t] = c[j * ldx + t] for the caller's row-major k x d centre array
+__global__ __launch_bounds__(kT) void copy_rows_kernel(const double* __restrict__ src, int64_t lds_, double* __restrict__ dst,
+                                                       int64_t ldd, int rows, int cols) {
+  const int64_t idx = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (idx >= (int64_t)rows * cols) return;
+  const int64_t r = idx / cols;
+  const int t = (int)(idx - r * cols);
+  dst[r * ldd + t] = src[r * lds_ + t];
+}
+
+int bits_for(int64_t n) {
+  int b = 1;
+  while (b < 31 && ((int64_t)1 << b) < n) ++b;
+  return b;
+}
+
+}  // namespace
+
+hipError_t launch_points_to_rowmajor(const double* v, int64_t ldv, int colmajor, int64_t n, int d, double* x, int64_t ldx,
+                                     hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(points_to_rowmajor_kernel, dim3((unsigned)((n + 63) / 64), (unsigned)((ldx + 63) / 64)), dim3(kT), 0,
+                     st, v, ldv, colmajor, n, d, x, ldx);
+  return hipGetLastError();
+}
+
+hipError_t launch_centroid_operand(const double* c, int64_t ldx, int k, int d, int dpad, double* ct, int64_t ldc,
+                                   double* cnorm, hipStream_t st) {
+  hipLaunchKernelGGL(centroid_operand_kernel, dim3((unsigned)k), dim3(kT), 0, st, c, ldx, k, d, dpad, ct, ldc, cnorm);
+  return hipGetLastError();
+}
+
+hipError_t launch_argmin(const double* s, int64_t lds, int64_t n, int k, const double* cnorm, int32_t* label,
+                         int* changes, hipStream_t st) {
+  hipLaunchKernelGGL(argmin_kernel, dim3(blocks(n * 16)), dim3(kT), 0, st, s, lds, n, k, cnorm, label, changes);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_int32(int32_t* a, int64_t n, int32_t value, int use_iota, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(iota_fill_kernel, dim3(blocks(n)), dim3(kT), 0, st, a, n, value, use_iota);
+  return hipGetLastError();
+}
+
+size_t kmeans_update_workspace(int64_t n) {
+  size_t sort_bytes = 0;
+  (void)hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const int32_t*)nullptr, (int32_t*)nullptr,
+                                           (const int32_t*)nullptr, (int32_t*)nullptr, (int)n, 0, 32, nullptr);
+  sort_bytes = (sort_bytes + 255) / 256 * 256;
+  // temp | ident[n] | sorted_label[n] | member[n]
+  return sort_bytes + (size_t)n * 12 + 1024;
+}
+
+hipError_t launch_centroid_update(const double* x, int64_t ldx, int d, int64_t n, const int32_t* label, int k, void* work,
+                                  size_t work_bytes, int32_t* start, double* c, hipStream_t st) {
+  if (n <= 0 || n > INT32_MAX) return hipErrorInvalidValue;
+  size_t sort_bytes = 0;
+  hipError_t e = hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const int32_t*)nullptr, (int32_t*)nullptr,
+                                                    (const int32_t*)nullptr, (int32_t*)nullptr, (int)n, 0, 32, st);
+  if (e != hipSuccess) return e;
+  const size_t tmp = (sort_bytes + 255) / 256 * 256;
+  if (work_bytes < tmp + (size_t)n * 12) return hipErrorInvalidValue;
+  char* base = static_cast<char*>(work);
+  int32_t* ident = reinterpret_cast<int32_t*>(base + tmp);
+  int32_t* sorted_label = ident + n;
+  int32_t* member = sorted_label + n;
+  hipLaunchKernelGGL(iota_fill_kernel, dim3(blocks(n)), dim3(kT), 0, st, ident, n, 0, 1);
+  size_t sb = sort_bytes;
+  e = hipcub::DeviceRadixSort::SortPairs(base, sb, label, sorted_label, ident, member, (int)n, 0, bits_for(k), st);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(cluster_starts_kernel, dim3(blocks(k + 1)), dim3(kT), 0, st, sorted_label, n, k, start);
+  hipLaunchKernelGGL(centroid_mean_kernel, dim3((unsigned)k, (unsigned)((d + 63) / 64)), dim3(kT), 0, st, x, ldx, d, member,
+                     start, c);
+  return hipGetLastError();
+}
+
+size_t kmeans_seed_workspace(int64_t n) {
+  size_t scan_bytes = 0;
+  (void)hipcub::DeviceScan::InclusiveSum(nullptr, scan_bytes, (const double*)nullptr, (double*)nullptr, (int)n, nullptr);
+  scan_bytes = (scan_bytes + 255) / 256 * 256;
+  // temp | dist2[n] | cs[n]
+  return scan_bytes + (size_t)n * 16 + 1024;
+}
+
+// Algorithm 5.  u[0 .. k-1]: host array of uniform numbers in [0, 1).  chosen: device int32[k], the indices of the
+// chosen points in the order they were drawn.
+hipError_t launch_kmeanspp(const double* x, int64_t ldx, int d, int64_t n, int k, const double* u, void* work,
+                           size_t work_bytes, int32_t* chosen, hipStream_t st) {
+  if (n <= 0 || n > INT32_MAX || k < 1) return hipErrorInvalidValue;
+  size_t scan_bytes = 0;
+  hipError_t e = hipcub::DeviceScan::InclusiveSum(nullptr, scan_bytes, (const double*)nullptr, (double*)nullptr, (int)n, st);
+  if (e != hipSuccess) return e;
+  const size_t tmp = (scan_bytes + 255) / 256 * 256;
+  if (work_bytes < tmp + (size_t)n * 16) return hipErrorInvalidValue;
+  char* base = static_cast<char*>(work);
+  double* dist2 = reinterpret_cast<double*>(base + tmp);
+  double* cs = dist2 + n;
+  int64_t first = (int64_t)(u[0] * (double)n);
+  first = first < n - 1 ? first : n - 1;
+  hipLaunchKernelGGL(iota_fill_kernel, dim3(1), dim3(kT), 0, st, chosen, 1, (int32_t)first, 0);
+  for (int i = 1; i < k; ++i) {
+    hipLaunchKernelGGL(seed_distance_kernel, dim3(blocks(n * 16)), dim3(kT), 0, st, x, ldx, d, n, chosen + (i - 1),
+                       i == 1 ? 1 : 0, dist2);
+    size_t sb = scan_bytes;
+    e = hipcub::DeviceScan::InclusiveSum(base, sb, dist2, cs, (int)n, st);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(iota_fill_kernel, dim3(1), dim3(kT), 0, st, chosen + i, 1, (int32_t)(n - 1), 0);
+    hipLaunchKernelGGL(seed_pick_kernel, dim3(blocks(n)), dim3(kT), 0, st, cs, n, u[i], chosen + i);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const double* x, int64_t ldx, const int32_t* index, int k, double* c, hipStream_t st) {
+  hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks((int64_t)k * ldx)), dim3(kT), 0, st, x, ldx, index, k, c);
+  return hipGetLastError();
+}
+
+int kmeans_objective_parts() { return 1024; }
+
+hipError_t launch_objective(const double* x, int64_t ldx, int d, int64_t n, const int32_t* label, const double* c,
+                            double* part, hipStream_t st) {
+  hipLaunchKernelGGL(objective_kernel, dim3((unsigned)kmeans_objective_parts()), dim3(kT), 0, st, x, ldx, d, n, label, c,
+                     part);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_rows(const double* src, int64_t lds, double* dst, int64_t ldd, int rows, int cols, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  hipLaunchKernelGGL(copy_rows_kernel, dim3(blocks((int64_t)rows * cols)), dim3(kT), 0, st, src, lds, dst, ldd, rows,
+                     cols);
+  return hipGetLastError();
+}
+
+}  // namespace sceig
