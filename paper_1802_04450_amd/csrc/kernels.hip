@@ -302,9 +302,128 @@ __global__ __launch_bounds__(kThreads) void spmm_stream_kernel(const int64_t* __
   }
 }
 
+// Single-vector product, one wave per tile of RW consecutive rows.  The wave requests the tile's whole (col, val)
+// stream at once - entry u*64 + lane in lane's registers, so every load instruction covers 64 consecutive entries -,
+// then the gathers z[col], parks the products in its own LDS strip and sums every row from there with 64/RW lanes.
+// No workgroup barrier: the four waves of a workgroup never wait for each other, and because every wave is short
+// lived the tiles in flight form one window that moves through the matrix in memory order.  All index arithmetic
+// inside the tile is 32-bit on a wave-uniform base.  Loads past the tile's end are clamped to its last entry (their
+// products are never summed) instead of being predicated.  Tiles with more than U*64 entries take further chunks on
+// demand.  The order of every row sum is fixed by the row's position in its tile.
+__device__ __forceinline__ int64_t readlane64(int64_t v, int l) {
+  const int lo = __builtin_amdgcn_readlane((int)v, l);
+  const int hi = __builtin_amdgcn_readlane((int)(v >> 32), l);
+  return ((int64_t)hi << 32) | (uint32_t)lo;
+}
+
+template <int RW, int U>
+__global__ __launch_bounds__(kThreads) void spmv_tile_kernel(const int64_t* __restrict__ rowptr,
+                                                             const int32_t* __restrict__ col,
+                                                             const double* __restrict__ val,
+                                                             const double* __restrict__ s,
+                                                             const double* __restrict__ z, double* __restrict__ y,
+                                                             int64_t ldy, int64_t n, int64_t ntiles) {
+  constexpr int LR = 64 / RW;  // lanes per row in the summation
+  constexpr int CH = U * 64;   // entries per chunk
+  __shared__ double prod_all[kThreads / 64][CH];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  double* prod = prod_all[wave];
+  const int64_t tile = (int64_t)blockIdx.x * (kThreads / 64) + wave;
+  if (tile >= ntiles) return;  // wave-uniform; there is no workgroup barrier below
+  const int g = lane / LR, sl = lane % LR;
+  const int64_t row0 = tile * RW;
+  int64_t r = row0 + lane;
+  r = r < n ? r : n;  // rows past the end are empty: their pointers equal rowptr[n]
+  const int64_t rpv = lane <= RW ? rowptr[r] : 0;
+  const double sv = (lane < RW && row0 + lane < n) ? s[row0 + lane] : 0.0;
+  const int64_t e0 = readlane64(rpv, 0);
+  const int len = (int)(readlane64(rpv, RW) - e0);
+  const bool mine = sl == 0 && row0 + g < n;
+  if (len <= 0) {
+    if (mine) y[(row0 + g) * ldy] = 0.0;
+    return;
+  }
+  const int32_t* cp = col + e0;
+  const double* vp = val + e0;
+  int32_t c[U];
+  double a[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    int idx = u * 64 + lane;
+    idx = idx < len ? idx : len - 1;
+    c[u] = cp[idx];
+    a[u] = vp[idx];
+  }
+  const int rel = (int)(rpv - e0);
+  const int rlo = __shfl(rel, g), rhi = __shfl(rel, g + 1);
+  const double sg = __shfl(sv, g);
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const double zz = *reinterpret_cast<const double*>(reinterpret_cast<const char*>(z) + ((uint64_t)(uint32_t)c[u] << 3));
+    prod[u * 64 + lane] = a[u] * zz;
+  }
+  // LDS operations of one wave complete in program order; the fence keeps the compiler from moving them
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  double acc = 0.0, acc2 = 0.0;
+  {
+    const int c1 = CH < len ? CH : len;
+    const int hi = rhi < c1 ? rhi : c1;
+    int e = rlo + sl;
+    for (; e + LR < hi; e += 2 * LR) {
+      acc += prod[e];
+      acc2 += prod[e + LR];
+    }
+    if (e < hi) acc += prod[e];
+  }
+  for (int c0 = CH; c0 < len; c0 += CH) {
+    __builtin_amdgcn_wave_barrier();
+    const int c1 = (c0 + CH) < len ? (c0 + CH) : len;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int idx = c0 + u * 64 + lane;
+      idx = idx < len ? idx : len - 1;
+      prod[u * 64 + lane] = vp[idx] * z[cp[idx]];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const int lo = rlo > c0 ? rlo : c0;
+    const int hi = rhi < c1 ? rhi : c1;
+    for (int e = lo + sl; e < hi; e += LR) acc += prod[e - c0];
+  }
+  acc += acc2;
+#pragma unroll
+  for (int o = LR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, LR);
+  if (mine) y[(row0 + g) * ldy] = sg * acc;
+}
+
+// Tile shape by the average row length: the register buffer (U*64 entries) should hold an average tile with some room.
+static hipError_t launch_spmv_tile(const int64_t* rowptr, const int32_t* col, const double* val, const double* s,
+                                   int64_t n, const double* z, double* y, int64_t ldy, double avg_deg,
+                                   hipStream_t st) {
+#define SC_LAUNCH_TILE(RW_, U_)                                                                                    \
+  do {                                                                                                             \
+    const int64_t ntiles = ceil_div64(n, RW_);                                                                     \
+    hipLaunchKernelGGL((spmv_tile_kernel<RW_, U_>), dim3((unsigned)ceil_div64(ntiles, kThreads / 64)),              \
+                       dim3(kThreads), 0, st, rowptr, col, val, s, z, y, ldy, n, ntiles);                          \
+  } while (0)
+  const double need = avg_deg * 1.08 / 64.0;  // register slots per lane and row of the tile
+  if (need * 32 <= 8) SC_LAUNCH_TILE(32, 8);
+  else if (need * 32 <= 12) SC_LAUNCH_TILE(32, 12);
+  else if (need * 32 <= 16) SC_LAUNCH_TILE(32, 16);
+  else if (need * 32 <= 22) SC_LAUNCH_TILE(32, 22);
+  else if (need * 16 <= 22) SC_LAUNCH_TILE(16, 22);
+  else SC_LAUNCH_TILE(8, 22);
+#undef SC_LAUNCH_TILE
+  return hipGetLastError();
+}
+
 template <int B>
 hipError_t launch_spmm_nz(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
                           const double* z, double* y, int64_t ldy, double avg_deg, hipStream_t st) {
+  if constexpr (B == 1) {
+    if (avg_deg >= 6.0) return launch_spmv_tile(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
+  }
   if (avg_deg >= 6.0) {
     // row-block streaming: 64 rows per workgroup for short rows, 32 otherwise (4 or 8 lanes per row sum)
     if (avg_deg < 24.0) {
