@@ -88,16 +88,16 @@ static inline unsigned xcd_grid(int64_t tiles) { return (unsigned)(ceil_div64(ti
 
 // L lanes per row, B = 8, 16, 32 columns.  The L lanes load L consecutive (col, val) pairs of the row at once.  A
 // lane carries TWO adjacent columns of the block, so CL = B/2 lanes cover one entry with 16-byte gathers, and the
-// L/CL sub-groups split the batch: sub-group g takes entries g*E ... g*E+E-1, E = CL.  A row of up to L entries is
-// one load -> gather -> sum chain; long rows (hubs of the kNN graph) take deg/L trips.  The sub-group sums are
-// combined in a fixed order by a shuffle tree.
+// NS = L/CL sub-groups split the batch round-robin (entry r*NS + g goes to sub-group g in round r).  A row of up to
+// L entries is one load -> gather -> sum chain; long rows (hubs of the kNN graph) take deg/L trips.  The sub-group
+// sums are combined in a fixed order by a shuffle tree.
 //
 // MODE 0: y = s o (W z), z = s o x packed by the caller (the operator applied from W and the scaling vector).
 // MODE 1: y = A z with the values as they are (the solver's copy holds S_ij = s_i W_ij s_j already multiplied out,
 //         as Algorithm 2's scaling step does), z = x packed.
 // MODE 2: one step of the Chebyshev recurrence on packed blocks with such values:
 //         y = alpha * (A z - shift * z) - beta * uprev   (uprev is not read when beta == 0; y packed, ldy = B).
-template <int B, int L, int MODE>
+template <int B, int L, int MODE, int R>
 __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __restrict__ rowptr,
                                                              const int32_t* __restrict__ col,
                                                              const double* __restrict__ val,
@@ -106,73 +106,114 @@ __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __re
                                                              int64_t ldy, int64_t n, int vec_store,
                                                              const double* __restrict__ uprev, double alpha,
                                                              double shift, double beta) {
-  constexpr int G = kThreads / L;  // rows per workgroup
+  constexpr int G = kThreads / L;  // lane groups per workgroup; a group owns R consecutive rows
   constexpr int CL = B / 2;        // lanes per entry
-  constexpr int E = CL;            // entries per sub-group and batch: (L / CL) sub-groups * E = L
-  static_assert(L % CL == 0 && (L / CL) * E == L, "batch must split evenly");
+  static_assert(L % CL == 0 && R + 1 <= L, "batch must split evenly");
+  constexpr int NS = L / CL;        // sub-groups of a row
   const int lane = threadIdx.x % L;
   const int tl = lane % CL;
-  const int sub = (lane / CL) * E;  // first entry of this sub-group inside a batch of L
-  const int64_t row = xcd_tile() * G + threadIdx.x / L;
-  if (row >= n) return;  // uniform over the L-lane group
-  const int64_t e0 = rowptr[row], e1 = rowptr[row + 1];
-  double acc0 = 0.0, acc1 = 0.0;
-  const double2* __restrict__ z2 = reinterpret_cast<const double2*>(z);
-  double2 cur = {0.0, 0.0}, pv = {0.0, 0.0};
-  if constexpr (MODE == 2) {
-    if (lane < CL) {  // the recurrence's own-row operands, requested ahead of the gathers
-      cur = z2[row * CL + tl];
-      if (beta != 0.0) pv = reinterpret_cast<const double2*>(uprev)[row * CL + tl];
+  const int sg = lane / CL;         // this lane's sub-group
+  const int64_t row0 = (xcd_tile() * G + threadIdx.x / L) * R;
+  if (row0 >= n) return;  // uniform over the L-lane group
+  // The group's R + 1 row pointers in one load, then the first batch of every row and (MODE 2) the recurrence's
+  // own-row operands: everything the R rows need from memory before their gathers is requested at once.
+  int64_t rpl;
+  {
+    int64_t r = row0 + lane;
+    r = r < n ? r : n;  // rows past the end are empty
+    rpl = lane <= R ? rowptr[r] : 0;
+  }
+  int64_t e0[R], e1[R];
+  int32_t c0[R];
+  double a0[R];
+#pragma unroll
+  for (int q = 0; q < R; ++q) {
+    e0[q] = __shfl(rpl, q, L);
+    e1[q] = __shfl(rpl, q + 1, L);
+    c0[q] = 0;
+    a0[q] = 0.0;
+    if (e0[q] + lane < e1[q]) {
+      c0[q] = col[e0[q] + lane];
+      a0[q] = val[e0[q] + lane];
     }
   }
-  for (int64_t e = e0; e < e1; e += L) {
-    // lanes past the end of the row carry (column 0, value 0): their products vanish
-    int32_t c = 0;
-    double a = 0.0;
-    if (e + lane < e1) {
-      c = col[e + lane];
-      a = val[e + lane];
-    }
-    if (e + sub < e1) {  // uniform over the sub-group; the shuffles below only read lanes of this sub-group's entries
-      constexpr int U = E < 8 ? E : 8;  // gathers in flight per lane
+  const double2* __restrict__ z2 = reinterpret_cast<const double2*>(z);
+  double2 cur[R], pv[R];
+  if constexpr (MODE == 2) {
 #pragma unroll
-      for (int u0 = 0; u0 < E; u0 += U) {
-        double2 zv[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int32_t cu = __shfl(c, sub + u0 + u, L);
-          zv[u] = z2[(int64_t)cu * CL + tl];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const double au = __shfl(a, sub + u0 + u, L);
-          acc0 += au * zv[u].x;
-          acc1 += au * zv[u].y;
-        }
+    for (int q = 0; q < R; ++q) {
+      cur[q] = {0.0, 0.0};
+      pv[q] = {0.0, 0.0};
+      if (lane < CL && row0 + q < n) {
+        cur[q] = z2[(row0 + q) * CL + tl];
+        if (beta != 0.0) pv[q] = reinterpret_cast<const double2*>(uprev)[(row0 + q) * CL + tl];
       }
     }
   }
 #pragma unroll
-  for (int o = L / 2; o >= CL; o >>= 1) {
-    acc0 += __shfl_xor(acc0, o, L);
-    acc1 += __shfl_xor(acc1, o, L);
+  for (int q = 0; q < R; ++q) {
+    const int64_t row = row0 + q;
+    if (row >= n) break;  // uniform over the group
+    double acc0 = 0.0, acc1 = 0.0;
+    for (int64_t e = e0[q]; e < e1[q]; e += L) {
+      // lanes past the end of the row carry (column 0, value 0): their products vanish
+      int32_t c = c0[q];
+      double a = a0[q];
+      if (e != e0[q]) {  // further batches of a long row, on demand
+        c = 0;
+        a = 0.0;
+        if (e + lane < e1[q]) {
+          c = col[e + lane];
+          a = val[e + lane];
+        }
+      }
+      // The batch's entries go round-robin to the NS sub-groups (entry r*NS + g to sub-group g in round r), so a
+      // batch of cnt entries costs ceil(cnt / NS) gather instructions: a row of 24 entries takes 6 rounds at B = 16,
+      // the one-entry tail of a row of 33 takes 1.
+      const int cnt = (e1[q] - e) < L ? (int)(e1[q] - e) : L;  // uniform over the row's lanes
+      const int rounds = (cnt + NS - 1) / NS;
+      int r = 0;
+#define SC_GATHER_ROUNDS(K)                                  \
+  {                                                          \
+    double2 zv[K];                                           \
+    _Pragma("unroll") for (int u = 0; u < K; ++u) {          \
+      const int32_t cu = __shfl(c, (r + u) * NS + sg, L);    \
+      zv[u] = z2[(int64_t)cu * CL + tl];                     \
+    }                                                        \
+    _Pragma("unroll") for (int u = 0; u < K; ++u) {          \
+      const double au = __shfl(a, (r + u) * NS + sg, L);     \
+      acc0 += au * zv[u].x;                                  \
+      acc1 += au * zv[u].y;                                  \
+    }                                                        \
+    r += K;                                                  \
   }
-  if (lane < CL) {
-    if constexpr (MODE == 2) {
-      double2 out;
-      out.x = alpha * (acc0 - shift * cur.x) - beta * pv.x;
-      out.y = alpha * (acc1 - shift * cur.y) - beta * pv.y;
-      reinterpret_cast<double2*>(y)[row * CL + tl] = out;
-    } else {
-      const double sr = MODE == 0 ? s[row] : 1.0;
-      if (vec_store) {  // one 16-byte store (y + row * ldy is 16-byte aligned)
+      while (rounds - r >= 4) SC_GATHER_ROUNDS(4)
+      if (rounds - r >= 2) SC_GATHER_ROUNDS(2)
+      if (rounds - r >= 1) SC_GATHER_ROUNDS(1)
+#undef SC_GATHER_ROUNDS
+    }
+#pragma unroll
+    for (int o = L / 2; o >= CL; o >>= 1) {
+      acc0 += __shfl_xor(acc0, o, L);
+      acc1 += __shfl_xor(acc1, o, L);
+    }
+    if (lane < CL) {
+      if constexpr (MODE == 2) {
         double2 out;
-        out.x = sr * acc0;
-        out.y = sr * acc1;
-        *reinterpret_cast<double2*>(y + row * ldy + 2 * tl) = out;
+        out.x = alpha * (acc0 - shift * cur[q].x) - beta * pv[q].x;
+        out.y = alpha * (acc1 - shift * cur[q].y) - beta * pv[q].y;
+        reinterpret_cast<double2*>(y)[row * CL + tl] = out;
       } else {
-        y[row * ldy + 2 * tl] = sr * acc0;
-        y[row * ldy + 2 * tl + 1] = sr * acc1;
+        const double sr = MODE == 0 ? s[row] : 1.0;
+        if (vec_store) {  // one 16-byte store (y + row * ldy is 16-byte aligned)
+          double2 out;
+          out.x = sr * acc0;
+          out.y = sr * acc1;
+          *reinterpret_cast<double2*>(y + row * ldy + 2 * tl) = out;
+        } else {
+          y[row * ldy + 2 * tl] = sr * acc0;
+          y[row * ldy + 2 * tl + 1] = sr * acc1;
+        }
       }
     }
   }
@@ -1217,9 +1258,13 @@ static hipError_t launch_spmm_cols_t(const int64_t* rowptr, const int32_t* col, 
                                      int64_t n, const double* z, int b, double* y, int64_t ldy, double avg_deg,
                                      const double* uprev, double alpha, double shift, double beta, hipStream_t st) {
   const int vec_store = (ldy % 2 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0) ? 1 : 0;
+  // One row per lane group: two and four consecutive rows per group with all their loads requested up front were
+  // measured slower on the 100,000-node workload (36 -> 43 and 49 us per product at B = 16): fewer, longer-lived waves.
+  constexpr int kRowsPerGroup = 1;
 #define SC_LAUNCH_COLS(BB, LL)                                                                                \
-  hipLaunchKernelGGL((spmm_cols_kernel<BB, LL, MODE>), dim3(xcd_grid(ceil_div64(n, kThreads / LL))),            \
-                     dim3(kThreads), 0, st, rowptr, col, val, s, z, y, ldy, n, vec_store, uprev, alpha, shift, beta)
+  hipLaunchKernelGGL((spmm_cols_kernel<BB, LL, MODE, kRowsPerGroup>),                                           \
+                     dim3(xcd_grid(ceil_div64(n, (kThreads / LL) * kRowsPerGroup))), dim3(kThreads), 0, st,      \
+                     rowptr, col, val, s, z, y, ldy, n, vec_store, uprev, alpha, shift, beta)
   switch (b) {
     case 8:
       switch (spmm_lanes(8, avg_deg)) {
