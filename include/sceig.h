@@ -265,11 +265,16 @@ typedef struct sc_kmeans_stats {
   int32_t iterations;   /* labelling steps done */
   int32_t converged;    /* 1 if the last labelling step changed no label */
   int32_t last_changes; /* labels changed by the last labelling step */
-  int32_t reserved;
+  int32_t timing;       /* INPUT: nonzero = bracket every distance-product launch with events on the stream and
+                           report their summed duration below (the only field read on entry; all others are outputs) */
   double objective;     /* sum of squared distances of the points to the centres of their labels; -1 if the run stopped
                            at max_iter (the centres moved after the last labelling) */
   double t_total;       /* seconds, host clock, whole call */
   double t_seed;        /* seconds spent in the seeding */
+  double t_distance;    /* seconds, device clock, all distance-product launches (V C^T); 0 unless timing was set */
+  int64_t distance_launches;
+  double distance_bytes; /* algorithmic bytes of those launches: points read + product block written + centres */
+  double distance_flops; /* 2 n k d per labelling step */
 } sc_kmeans_stats;
 
 /*

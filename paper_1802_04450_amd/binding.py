@@ -55,11 +55,12 @@ class ScStats(ctypes.Structure):
 
 class ScKMeansStats(ctypes.Structure):
     _fields_ = [("iterations", ctypes.c_int32), ("converged", ctypes.c_int32), ("last_changes", ctypes.c_int32),
-                ("reserved", ctypes.c_int32), ("objective", ctypes.c_double), ("t_total", ctypes.c_double),
-                ("t_seed", ctypes.c_double)]
+                ("timing", ctypes.c_int32), ("objective", ctypes.c_double), ("t_total", ctypes.c_double),
+                ("t_seed", ctypes.c_double), ("t_distance", ctypes.c_double), ("distance_launches", ctypes.c_int64),
+                ("distance_bytes", ctypes.c_double), ("distance_flops", ctypes.c_double)]
 
     def as_dict(self) -> dict:
-        return {name: getattr(self, name) for name, _ in self._fields_ if name != "reserved"}
+        return {name: getattr(self, name) for name, _ in self._fields_}
 
 
 class ScError(RuntimeError):
@@ -296,7 +297,7 @@ def sc_kmeanspp(points, k: int, seed: int, colmajor: bool = False):
     return chosen, cen
 
 
-def sc_kmeans_lloyd(points, centroids, max_iter: int = 100, colmajor: bool = False):
+def sc_kmeans_lloyd(points, centroids, max_iter: int = 100, colmajor: bool = False, timing: bool = False):
     """Algorithm 4 step 3 from `centroids` ((k, d) device, not modified).  Returns (labels int32[n], centres (k, d),
     status code, stats dict)."""
     import torch
@@ -304,7 +305,7 @@ def sc_kmeans_lloyd(points, centroids, max_iter: int = 100, colmajor: bool = Fal
     cen = _dev(centroids, torch.float64).clone()
     k = cen.shape[0]
     labels = torch.empty(n, dtype=torch.int32, device=points.device)
-    stats = ScKMeansStats()
+    stats = ScKMeansStats(timing=1 if timing else 0)
     with torch.cuda.device(points.device):
         code = lib().sc_kmeans_lloyd(_ptr(points), ld, 1 if colmajor else 0, n, d, k, _ptr(cen), max_iter,
                                      _ptr(labels), ctypes.byref(stats), _stream())
@@ -312,13 +313,13 @@ def sc_kmeans_lloyd(points, centroids, max_iter: int = 100, colmajor: bool = Fal
     return labels, cen, code, stats.as_dict()
 
 
-def sc_kmeans(points, k: int, seed: int, max_iter: int = 100, colmajor: bool = False):
+def sc_kmeans(points, k: int, seed: int, max_iter: int = 100, colmajor: bool = False, timing: bool = False):
     """Algorithm 4.  Returns (labels int32[n], centres (k, d), status code, stats dict)."""
     import torch
     n, d, ld = _points_layout(points, colmajor)
     labels = torch.empty(n, dtype=torch.int32, device=points.device)
     cen = torch.empty((max(k, 0), d), dtype=torch.float64, device=points.device)
-    stats = ScKMeansStats()
+    stats = ScKMeansStats(timing=1 if timing else 0)
     with torch.cuda.device(points.device):
         code = lib().sc_kmeans(_ptr(points), ld, 1 if colmajor else 0, n, d, k, seed, max_iter, _ptr(labels),
                                _ptr(cen), ctypes.byref(stats), _stream())

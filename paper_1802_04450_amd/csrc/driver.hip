@@ -1180,12 +1180,30 @@ struct KMeans {
     work.alloc(wb);
     HIP_TRY(launch_fill_int32(labels, n, -1, 0, st));
     int iters = 0, converged = 0, last_changes = 0;
+    const bool timing = stats && stats->timing;
+    struct EventPair {
+      hipEvent_t a, b;
+    };
+    std::vector<EventPair> events;
+    double dist_bytes = 0.0, dist_flops = 0.0;
     for (int it = 0; it < max_iter; ++it) {
       HIP_TRY(launch_fill_int32(changes.p, 1, 0, 0, st));
       HIP_TRY(launch_centroid_operand(c, ldx, k, d, (int)ldx, ct.p, ldc, cnorm.p, st));
       for (int64_t r0 = 0; r0 < n; r0 += chunk) {
         const int64_t rows = std::min<int64_t>(chunk, n - r0);
+        EventPair ev{};
+        if (timing) {
+          HIP_TRY(hipEventCreate(&ev.a));
+          HIP_TRY(hipEventCreate(&ev.b));
+          HIP_TRY(hipEventRecord(ev.a, st));
+        }
         HIP_TRY(launch_row_gemm(x.p + r0 * ldx, rows, ldx, 0, d, ct.p, (int)ldc, k, 1, 0, sblock.p, ldc, nullptr, st));
+        if (timing) {
+          HIP_TRY(hipEventRecord(ev.b, st));
+          events.push_back(ev);
+        }
+        dist_bytes += 8.0 * ((double)rows * d + (double)rows * k + (double)k * d);
+        dist_flops += 2.0 * (double)rows * k * d;
         HIP_TRY(launch_argmin(sblock.p, ldc, rows, k, cnorm.p, labels + r0, changes.p, st));
       }
       HIP_TRY(hipMemcpyAsync(hchanges.p, changes.p, sizeof(int), hipMemcpyDeviceToHost, st));
@@ -1217,6 +1235,17 @@ struct KMeans {
       stats->iterations = iters;
       stats->converged = converged;
       stats->last_changes = last_changes;
+      stats->distance_launches = (int64_t)(timing ? events.size() : 0);
+      stats->distance_bytes = dist_bytes;
+      stats->distance_flops = dist_flops;
+      double td = 0.0;
+      for (EventPair& ev : events) {  // every launch has completed: the stream was synchronized above
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, ev.a, ev.b) == hipSuccess) td += ms * 1e-3;
+        (void)hipEventDestroy(ev.a);
+        (void)hipEventDestroy(ev.b);
+      }
+      stats->t_distance = td;
     }
     return converged ? SC_OK : SC_NOT_CONVERGED;
   }
@@ -1675,7 +1704,11 @@ int sc_kmeans_lloyd(const double* points, int64_t ld, int32_t colmajor, int64_t 
   const int a = kmeans_args_ok(points, ld, colmajor, n, d, k);
   if (a != SC_OK) return a;
   if (max_iter < 1) return SC_EDOMAIN;
-  if (stats) *stats = sc_kmeans_stats{};
+  if (stats) {
+    const int32_t timing = stats->timing;
+    *stats = sc_kmeans_stats{};
+    stats->timing = timing;
+  }
   KMeansCall call{{points, ld, colmajor, n, d, k, reinterpret_cast<hipStream_t>(stream)}, 0, max_iter, 1, nullptr,
                   labels_out, centroids, stats};
   return guarded(run_kmeans, &call);
@@ -1687,7 +1720,11 @@ int sc_kmeans(const double* points, int64_t ld, int32_t colmajor, int64_t n, int
   const int a = kmeans_args_ok(points, ld, colmajor, n, d, k);
   if (a != SC_OK) return a;
   if (max_iter < 1) return SC_EDOMAIN;
-  if (stats) *stats = sc_kmeans_stats{};
+  if (stats) {
+    const int32_t timing = stats->timing;
+    *stats = sc_kmeans_stats{};
+    stats->timing = timing;
+  }
   KMeansCall call{{points, ld, colmajor, n, d, k, reinterpret_cast<hipStream_t>(stream)}, seed, max_iter, 2, nullptr,
                   labels_out, centroids_out, stats};
   return guarded(run_kmeans, &call);

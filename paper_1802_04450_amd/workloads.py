@@ -410,6 +410,25 @@ def build_second_workload(name: str, n: Optional[int] = None, blocks: Optional[i
     return g, spec
 
 
+# ---- point sets for the k-means step -------------------------------------------------------------------------------
+def gaussian_blobs(n: int, d: int, k: int, seed: int, spread: float = 0.15) -> np.ndarray:
+    """n points in d dimensions around k standard-normal centres (labels uniform), isotropic noise of std `spread`."""
+    rng = np.random.default_rng(seed)
+    cen = rng.normal(size=(max(k, 1), d))
+    lab = rng.integers(0, max(k, 1), size=n)
+    return cen[lab] + spread * rng.normal(size=(n, d))
+
+
+def embedding_like(n: int, k: int, seed: int, noise: float = 1e-3) -> np.ndarray:
+    """Rows of an orthonormal n x k matrix that is constant on k groups up to `noise`, scaled to unit length: the shape
+    of the row-normalised spectral embedding of a graph with k clusters (Section II Steps 3-4)."""
+    rng = np.random.default_rng(seed)
+    lab = rng.integers(0, k, size=n)
+    rot = np.linalg.qr(rng.normal(size=(k, k)))[0]
+    q, _ = np.linalg.qr(rot[lab] + noise * rng.normal(size=(n, k)))
+    return q / np.linalg.norm(q, axis=1, keepdims=True)
+
+
 def describe(graph: CSR) -> dict:
     rowptr, col, val, n = graph
     deg = np.diff(rowptr)

@@ -8,6 +8,7 @@ import numpy as np
 import pytest
 
 from oracle import kmeans as okm
+from paper_1802_04450_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
@@ -24,21 +25,11 @@ def B():
 
 
 def _blobs(n, d, k, seed, spread=0.15):
-    rng = np.random.default_rng(seed)
-    cen = rng.normal(size=(k, d))
-    lab = rng.integers(0, k, size=n)
-    return cen[lab] + spread * rng.normal(size=(n, d))
+    return wl.gaussian_blobs(n, d, k, seed, spread)
 
 
 def _embedding_like(n, k, seed):
-    """Rows of an orthonormal n x k matrix that is constant on k groups plus small noise, made unit length: the shape of
-    a row-normalised spectral embedding of a graph with k components."""
-    rng = np.random.default_rng(seed)
-    lab = rng.integers(0, k, size=n)
-    ind = np.zeros((n, k))
-    ind[np.arange(n), lab] = 1.0
-    q, _ = np.linalg.qr(ind @ np.linalg.qr(rng.normal(size=(k, k)))[0] + 1e-3 * rng.normal(size=(n, k)))
-    return q / np.linalg.norm(q, axis=1, keepdims=True)
+    return wl.embedding_like(n, k, seed)
 
 
 def _dev(a, dtype=torch.float64):
