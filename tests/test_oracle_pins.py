@@ -397,3 +397,52 @@ def test_kmeans_oracle_pins():
         assert second == (1 if km.uniform01(seed, 1) * 10.0 < 1.0 else 2)
         counts[second] += 1
     assert tried > 1000 and abs(counts[2] / tried - 0.9) < 0.03
+
+
+def test_similarity_oracle_pins():
+    """Section IV-A measures and Algorithm 1: hand-computed values, the library's Pearson correlation, invariances that
+    a dropped mean, a missing norm or a wrong sign would break, and the harness's own Gaussian kNN weights."""
+    from oracle import similarity as sim
+    # hand computed: x0 = (1,2,3), x1 = (2,4,6.5), x2 = (3,1,2)
+    x = np.array([[1.0, 2.0, 3.0], [2.0, 4.0, 6.5], [3.0, 1.0, 2.0]])
+    u, v = np.array([0, 0, 1]), np.array([1, 2, 2])
+    # centred rows: (-1,0,1), (-13/6,-1/6,14/6), (1,-1,0); norms sqrt2, sqrt(366)/6, sqrt2
+    cc = sim.edge_similarity(x, u, v, sim.CROSS_CORRELATION)
+    np.testing.assert_allclose(cc, [(27 / 6) / (np.sqrt(2) * np.sqrt(366) / 6), -1 / 2,
+                                    (-12 / 6) / (np.sqrt(366) / 6 * np.sqrt(2))], rtol=1e-14)
+    cs = sim.edge_similarity(x, u, v, sim.COSINE)
+    np.testing.assert_allclose(cs, [29.5 / np.sqrt(14 * 62.25), 11 / 14, 23 / np.sqrt(62.25 * 14)], rtol=1e-14)
+    ed = sim.edge_similarity(x, u, v, sim.EXP_DECAY, sigma=2.0)
+    np.testing.assert_allclose(ed, np.exp(-np.array([17.25, 6.0, 30.25]) / 8.0), rtol=1e-14)
+    np.testing.assert_allclose(sim.row_means(x), [2.0, 25 / 6, 2.0], rtol=1e-15)
+    np.testing.assert_allclose(sim.centered_norms(x), [np.sqrt(2), np.sqrt(366) / 6, np.sqrt(2)], rtol=1e-15)
+    # library Pearson correlation; invariances
+    rng = np.random.default_rng(0)
+    x = rng.normal(size=(40, 90)) + rng.normal(size=(40, 1)) * 3
+    u, v = np.triu_indices(40, 1)
+    cc = sim.edge_similarity(x, u, v, sim.CROSS_CORRELATION)
+    np.testing.assert_allclose(cc, np.corrcoef(x)[u, v], rtol=1e-12, atol=1e-14)
+    shift, scale = rng.normal(size=(40, 1)) * 10, rng.uniform(0.5, 2.0, size=(40, 1))
+    np.testing.assert_allclose(sim.edge_similarity(x * scale + shift, u, v, sim.CROSS_CORRELATION), cc, atol=1e-12)
+    cs = sim.edge_similarity(x, u, v, sim.COSINE)
+    np.testing.assert_allclose(sim.edge_similarity(x * scale, u, v, sim.COSINE), cs, atol=1e-13)
+    assert np.max(np.abs(sim.edge_similarity(x + shift, u, v, sim.COSINE) - cs)) > 1e-3      # not shift invariant
+    assert np.all(np.abs(cc) <= 1 + 1e-14) and np.all(np.abs(cs) <= 1 + 1e-14)
+    np.testing.assert_allclose(sim.edge_similarity(x, u[:5], u[:5], sim.CROSS_CORRELATION), 1.0, rtol=1e-14)
+    ed = sim.edge_similarity(x, u, v, sim.EXP_DECAY, sigma=7.0)
+    assert np.all((ed > 0) & (ed < 1))
+    np.testing.assert_allclose(sim.edge_similarity(x, v, u, sim.EXP_DECAY, sigma=7.0), ed, rtol=0)
+    # larger sigma, larger similarity; orthogonal transformations leave it alone
+    assert np.all(sim.edge_similarity(x, u, v, sim.EXP_DECAY, sigma=9.0) > ed)
+    q = np.linalg.qr(rng.normal(size=(90, 90)))[0]
+    np.testing.assert_allclose(sim.edge_similarity(x @ q, u, v, sim.EXP_DECAY, sigma=7.0), ed, rtol=1e-10)
+    # the harness's Gaussian kNN graph (its own distance code) carries exactly these weights
+    pts = rng.normal(size=(300, 5))
+    (rp, c, val, n), sigma = wl.knn_gaussian_graph(pts, 6, device="cpu")
+    rows = np.repeat(np.arange(n), np.diff(rp))
+    np.testing.assert_allclose(sim.edge_similarity(pts, rows, c, sim.EXP_DECAY, sigma=sigma), val, rtol=1e-12)
+    # COO semantics: duplicates add, symmetrization mirrors off-diagonal pairs only
+    a = sim.coo_to_dense([0, 0, 2, 1], [1, 1, 2, 0], [1.0, 2.0, 5.0, 4.0], 3, symmetrize=True)
+    np.testing.assert_array_equal(a, [[0, 7, 0], [7, 0, 0], [0, 0, 5]])
+    a = sim.coo_to_dense([0, 0, 2, 1], [1, 1, 2, 0], [1.0, 2.0, 5.0, 4.0], 3, symmetrize=False)
+    np.testing.assert_array_equal(a, [[0, 3, 0], [4, 0, 0], [0, 0, 5]])
