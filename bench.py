@@ -181,6 +181,64 @@ def bench_kmeans(B, torch, args):
     print(json.dumps(out), flush=True)
 
 
+def bench_similarity(B, torch, args):
+    """One step = cross-correlation similarity of every listed pair + symmetric CSR of the result, inputs resident in
+    HBM.  Shape of the paper's DTI input (142,541 points of 90 coordinates, ~4.0 M neighbouring pairs)."""
+    from paper_1802_04450_amd import workloads as wl
+    n, d = 142_541, 90
+    t0 = time.time()
+    u, v = wl.voxel_neighbour_pairs(n)
+    x = wl.connectivity_profiles(n, d, 1802044500 + 21)
+    ne = int(u.size)
+    log(f"[bench] similarity input: n={n}, d={d}, pairs={ne} in {time.time() - t0:.1f}s")
+    dx = torch.as_tensor(x, device="cuda")
+    du, dv = torch.as_tensor(u, device="cuda"), torch.as_tensor(v, device="cuda")
+
+    def step():
+        w = B.sc_edge_similarity(dx, du, dv, B.SC_SIM_CROSS_CORRELATION)
+        return B.sc_coo_to_csr(du, dv, w, n, True)
+
+    for _ in range(max(1, args.warmup)):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        rp, co, vo = step()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    # the similarity call alone, with events on the stream it runs on
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    e0.record()
+    for _ in range(reps):
+        B.sc_edge_similarity(dx, du, dv, B.SC_SIM_CROSS_CORRELATION)
+    e1.record()
+    torch.cuda.synchronize()
+    t_sim = e0.elapsed_time(e1) * 1e-3 / reps
+    # algorithmic bytes: the data once, the pair list, the values, the row statistics; what the kernel gathers is
+    # 2 d 8 bytes per pair (5.7 GB here), served by the caches when neighbouring pairs share rows
+    alg = 8.0 * n * d + 8.0 * ne + 8.0 * ne + 16.0 * n
+    gathered = 16.0 * d * ne
+    out = {"metric": "similarity graph s (Algorithm 1 cross correlation + COO to symmetric CSR)", "value": sec,
+           "unit": "s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3,
+           "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+           "config": {"workload": f"dti_like: n={n}, d={d}, pairs={ne}, nnz={int(rp[-1])}"},
+           "roofline": {"bound": "hbm", "kernel": "row_stats_kernel + edge_similarity_kernel (one sc_edge_similarity call)",
+                        "achieved": alg / t_sim / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": alg / t_sim / 1e9 / HBM_PEAK_GBS, "traffic": None, "call_us": t_sim * 1e6,
+                        "gathered_gbps": gathered / t_sim / 1e9}}
+    if not args.no_cpu_baseline:
+        from oracle import similarity as osim
+        ns = min(ne, 400_000)
+        t0 = time.time()
+        osim.edge_similarity(x, u[:ns], v[:ns], osim.CROSS_CORRELATION)
+        dt = time.time() - t0
+        out["cpu_baseline"] = {"value": dt * ne / ns, "unit": "s", "cores": 1, "kind": "oracle",
+                               "sample": f"oracle cross correlation of the first {ns} of {ne} pairs took {dt:.2f}s; "
+                                         f"scaled by pairs/{ns} (similarity only, no conversion)"}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -197,6 +255,9 @@ def main():
     ap.add_argument("--kmeans", action="store_true",
                     help="the clustering step that follows the eigensolve (Algorithms 4-5) on a synthetic row-normalised "
                          "embedding of the benchmark workload's shape (n points, d = k); prints its own JSON line")
+    ap.add_argument("--similarity", action="store_true",
+                    help="the graph-construction step (Algorithm 1 + the COO to CSR conversion of Algorithm 2) on "
+                         "synthetic data of the shape of the paper's DTI input; prints its own JSON line")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device copy 10 times (calibration of the HBM traffic counters)")
     args = ap.parse_args()
@@ -221,6 +282,9 @@ def main():
 
     if args.kmeans:
         bench_kmeans(B, torch, args)
+        return
+    if args.similarity:
+        bench_similarity(B, torch, args)
         return
     cfg, graph = build_workload(args.workload)
     rp, c, v, n = graph

@@ -306,6 +306,41 @@ int sc_kmeans_lloyd(const double* points, int64_t ld, int32_t colmajor, int64_t 
 int sc_kmeans(const double* points, int64_t ld, int32_t colmajor, int64_t n, int32_t d, int32_t k, uint64_t seed,
               int32_t max_iter, int32_t* labels_out, double* centroids_out, sc_kmeans_stats* stats, void* stream);
 
+/*
+ * Similarity of the listed pairs of data points (Section IV-A; Algorithm 1 steps 4-6).
+ *   x        device fp64, n x d row-major with leading dimension ldx >= d (read only: the centring of Algorithm 1 step 5
+ *            is applied on the fly, the caller's data are not modified)
+ *   edge_u, edge_v  device int32[nedges]: the pairs (the paper's list E of neighbouring points)
+ *   measure  SC_SIM_CROSS_CORRELATION: <x_u - mean(x_u), x_v - mean(x_v)> / (|x_u - mean(x_u)| |x_v - mean(x_v)|)
+ *            SC_SIM_COSINE:            <x_u, x_v> / (|x_u| |x_v|)
+ *            SC_SIM_EXP_DECAY:         exp(-|x_u - x_v|^2 / (2 sigma^2)), sigma > 0 (the paper prints this measure
+ *                                      without the minus sign and the square; a similarity has both)
+ *   val_out  device fp64[nedges]; a constant row gives NaN under the first two measures (0/0), as the definition does
+ * Returns SC_ECSR if an index is outside [0, n) (that edge's value is NaN, no row was read for it), SC_EDOMAIN for
+ * d < 1, ldx < d, an unknown measure or sigma <= 0.
+ */
+#define SC_SIM_CROSS_CORRELATION 0
+#define SC_SIM_COSINE 1
+#define SC_SIM_EXP_DECAY 2
+int sc_edge_similarity(const double* x, int64_t ldx, int64_t n, int32_t d, const int32_t* edge_u, const int32_t* edge_v,
+                       int64_t nedges, int32_t measure, double sigma, double* val_out, void* stream);
+
+/*
+ * Coordinate format to CSR (Algorithm 2 step 4), on the device.
+ *   row, col, val   device, nnz_in entries (r, c, w) in any order
+ *   symmetrize      nonzero: every listed entry with r != c also stands for (c, r, w) - the list names each undirected
+ *                   edge once, as Algorithm 1's pair list does
+ *   rowptr_out      device int64[n+1]
+ *   col_out, val_out  device, room for nnz_in * (symmetrize ? 2 : 1) entries; the first rowptr_out[n] are the matrix,
+ *                   sorted by (row, col); entries listed more than once stay separate (the products add them up) in
+ *                   listing order; what lies beyond rowptr_out[n] is unspecified
+ *   nnz_out         host, = rowptr_out[n]; may be NULL
+ * n <= 2^31 - 1 and at most 2^31 - 1 output entries (else SC_EDOMAIN); SC_ECSR if an index is outside [0, n).
+ */
+int sc_coo_to_csr(const int32_t* row, const int32_t* col, const double* val, int64_t nnz_in, int64_t n,
+                  int32_t symmetrize, int64_t* rowptr_out, int32_t* col_out, double* val_out, int64_t* nnz_out,
+                  void* stream);
+
 const char* sc_strerror(int code);
 int sc_version(void);
 

@@ -27,7 +27,8 @@ FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 
 EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_reorder_csr", "sc_cgs2",
            "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version", "sc_release_cache",
-           "sc_chebyshev_filter", "sc_kmeanspp", "sc_kmeans_lloyd", "sc_kmeans"]
+           "sc_chebyshev_filter", "sc_kmeanspp", "sc_kmeans_lloyd", "sc_kmeans", "sc_edge_similarity",
+           "sc_coo_to_csr"]
 
 
 class ScOptions(ctypes.Structure):
@@ -98,6 +99,8 @@ def lib() -> ctypes.CDLL:
         _lib.sc_kmeanspp.argtypes = [vp, i64, i32, i64, i32, i32, u64, vp, vp, vp]
         _lib.sc_kmeans_lloyd.argtypes = [vp, i64, i32, i64, i32, i32, vp, i32, vp, ctypes.POINTER(ScKMeansStats), vp]
         _lib.sc_kmeans.argtypes = [vp, i64, i32, i64, i32, i32, u64, i32, vp, vp, ctypes.POINTER(ScKMeansStats), vp]
+        _lib.sc_edge_similarity.argtypes = [vp, i64, i64, i32, vp, vp, i64, i32, dbl, vp, vp]
+        _lib.sc_coo_to_csr.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_int64), vp]
         _lib.sc_sym_eig.argtypes = [vp, i32, vp, vp]
         _lib.sc_sym_eig_top.argtypes = [vp, i32, i32, vp, vp]
         for name in EXPORTS:
@@ -325,6 +328,40 @@ def sc_kmeans(points, k: int, seed: int, max_iter: int = 100, colmajor: bool = F
                                _ptr(cen), ctypes.byref(stats), _stream())
     _check(code)
     return labels, cen, code, stats.as_dict()
+
+
+SC_SIM_CROSS_CORRELATION, SC_SIM_COSINE, SC_SIM_EXP_DECAY = 0, 1, 2
+
+
+def sc_edge_similarity(x, edge_u, edge_v, measure: int, sigma: float = 1.0):
+    """Algorithm 1: similarity of the listed pairs of rows of x ((n, d) device).  Returns val fp64[nedges] device."""
+    import torch
+    _dev(x, torch.float64), _dev(edge_u, torch.int32), _dev(edge_v, torch.int32)
+    n, d = x.shape
+    ne = edge_u.numel()
+    val = torch.empty(ne, dtype=torch.float64, device=x.device)
+    with torch.cuda.device(x.device):
+        code = lib().sc_edge_similarity(_ptr(x), x.stride(0), n, d, _ptr(edge_u), _ptr(edge_v), ne, measure,
+                                        float(sigma), _ptr(val), _stream())
+    _check(code)
+    return val
+
+
+def sc_coo_to_csr(row, col, val, n: int, symmetrize: bool):
+    """Algorithm 2 step 4.  Returns (rowptr int64[n+1], col int32[nnz], val fp64[nnz]) device, sorted by (row, col)."""
+    import torch
+    _dev(row, torch.int32), _dev(col, torch.int32), _dev(val, torch.float64)
+    nnz_in = row.numel()
+    total = nnz_in * (2 if symmetrize else 1)
+    rp = torch.empty(n + 1, dtype=torch.int64, device=row.device)
+    co = torch.empty(max(total, 1), dtype=torch.int32, device=row.device)
+    vo = torch.empty(max(total, 1), dtype=torch.float64, device=row.device)
+    nnz = ctypes.c_int64(0)
+    with torch.cuda.device(row.device):
+        code = lib().sc_coo_to_csr(_ptr(row), _ptr(col), _ptr(val), nnz_in, n, 1 if symmetrize else 0, _ptr(rp), _ptr(co),
+                                   _ptr(vo), ctypes.byref(nnz), _stream())
+    _check(code)
+    return rp, co[:nnz.value], vo[:nnz.value]
 
 
 def sc_sym_eig(a: np.ndarray, vectors: bool = True) -> Tuple[np.ndarray, Optional[np.ndarray]]:

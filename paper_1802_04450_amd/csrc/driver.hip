@@ -1730,6 +1730,93 @@ int sc_kmeans(const double* points, int64_t ld, int32_t colmajor, int64_t n, int
   return guarded(run_kmeans, &call);
 }
 
+int sc_edge_similarity(const double* x, int64_t ldx, int64_t n, int32_t d, const int32_t* edge_u, const int32_t* edge_v,
+                       int64_t nedges, int32_t measure, double sigma, double* val_out, void* stream) {
+  if (!x || n < 0 || nedges < 0 || (nedges > 0 && (!edge_u || !edge_v || !val_out))) return SC_EINVAL;
+  if (d < 1 || ldx < d || measure < 0 || measure > 2 || (measure == 2 && !(sigma > 0.0))) return SC_EDOMAIN;
+  if (nedges == 0 || n == 0) return nedges == 0 ? SC_OK : SC_EDOMAIN;
+  struct Ctx {
+    const double* x;
+    int64_t ldx, n;
+    int d;
+    const int32_t *u, *v;
+    int64_t ne;
+    int measure;
+    double sigma;
+    double* val;
+    hipStream_t st;
+  } ctx{x, ldx, n, d, edge_u, edge_v, nedges, measure, sigma, val_out, reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        DevBuf<double> mean, norm;
+        DevBuf<int> bad;
+        PinnedBuf<int> hbad;
+        bad.alloc(1);
+        hbad.alloc(1);
+        HIP_TRY(launch_fill_int32(bad.p, 1, 0, 0, c->st));
+        if (c->measure != 2) {
+          mean.alloc((size_t)c->n);
+          norm.alloc((size_t)c->n);
+          HIP_TRY(launch_row_stats(c->x, c->ldx, c->n, c->d, c->measure == 0 ? 1 : 0, mean.p, norm.p, c->st));
+        }
+        HIP_TRY(launch_edge_similarity(c->x, c->ldx, c->d, c->u, c->v, c->ne, c->measure, c->sigma, mean.p, norm.p,
+                                       c->n, bad.p, c->val, c->st));
+        HIP_TRY(hipMemcpyAsync(hbad.p, bad.p, sizeof(int), hipMemcpyDeviceToHost, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        return *hbad.p ? SC_ECSR : SC_OK;
+      },
+      &ctx);
+}
+
+int sc_coo_to_csr(const int32_t* row, const int32_t* col, const double* val, int64_t nnz_in, int64_t n,
+                  int32_t symmetrize, int64_t* rowptr_out, int32_t* col_out, double* val_out, int64_t* nnz_out,
+                  void* stream) {
+  if (!rowptr_out || n < 0 || nnz_in < 0 || (nnz_in > 0 && (!row || !col || !val || !col_out || !val_out)))
+    return SC_EINVAL;
+  if (n > (int64_t)0x7fffffff || nnz_in * (symmetrize ? 2 : 1) > (int64_t)0x7fffffff) return SC_EDOMAIN;
+  if (nnz_out) *nnz_out = 0;
+  struct Ctx {
+    const int32_t *row, *col;
+    const double* val;
+    int64_t nnz, n;
+    int sym;
+    int64_t* rp;
+    int32_t* co;
+    double* vo;
+    int64_t* nnz_out;
+    hipStream_t st;
+  } ctx{row, col, val, nnz_in, n, symmetrize ? 1 : 0, rowptr_out, col_out, val_out, nnz_out,
+        reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        if (c->nnz == 0) {  // an empty list: all row pointers zero
+          HIP_TRY(hipMemsetAsync(c->rp, 0, sizeof(int64_t) * (size_t)(c->n + 1), c->st));
+          HIP_TRY(hipStreamSynchronize(c->st));
+          return SC_OK;
+        }
+        const int64_t total = c->nnz * (c->sym ? 2 : 1);
+        const size_t wb = coo_to_csr_workspace(total);
+        DevBuf<char> work;
+        DevBuf<int> bad;
+        PinnedBuf<int64_t> host;
+        work.alloc(wb);
+        bad.alloc(1);
+        host.alloc(2);
+        HIP_TRY(launch_fill_int32(bad.p, 1, 0, 0, c->st));
+        HIP_TRY(coo_to_csr(c->row, c->col, c->val, c->nnz, c->n, c->sym, work.p, wb, c->rp, c->co, c->vo, bad.p, c->st));
+        HIP_TRY(hipMemcpyAsync(host.p, c->rp + c->n, sizeof(int64_t), hipMemcpyDeviceToHost, c->st));
+        int hbad = 0;
+        HIP_TRY(hipMemcpyAsync(&hbad, bad.p, sizeof(int), hipMemcpyDeviceToHost, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        if (hbad) return SC_ECSR;
+        if (c->nnz_out) *c->nnz_out = host.p[0];
+        return SC_OK;
+      },
+      &ctx);
+}
+
 int sc_sym_eig(const double* a, int32_t n, double* w, double* z) {
   if (!a || !w || n < 0) return SC_EINVAL;
   if (n == 0) return SC_OK;

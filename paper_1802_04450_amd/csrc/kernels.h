@@ -159,4 +159,18 @@ hipError_t launch_objective(const double* x, int64_t ldx, int d, int64_t n, cons
                             double* part, hipStream_t st);
 hipError_t launch_copy_rows(const double* src, int64_t lds, double* dst, int64_t ldd, int rows, int cols, hipStream_t st);
 
+// ---- similarity graph (Section IV-A, Algorithm 1; Algorithm 2 step 4; similarity.hip) ----------------------------
+// mean[i] = row mean (0 if centre == 0), norm[i] = 2-norm of the row minus that mean; x row-major n x ldx
+hipError_t launch_row_stats(const double* x, int64_t ldx, int64_t n, int d, int centre, double* mean, double* norm,
+                            hipStream_t st);
+// measure 0 cross correlation, 1 cosine (both with mean/norm from launch_row_stats), 2 exp(-|xu-xv|^2 / (2 sigma^2));
+// *bad |= 1 and val[e] = NaN for an edge with an index outside [0, n)
+hipError_t launch_edge_similarity(const double* x, int64_t ldx, int d, const int32_t* eu, const int32_t* ev,
+                                  int64_t nedges, int measure, double sigma, const double* mean, const double* norm,
+                                  int64_t n, int* bad, double* val, hipStream_t st);
+size_t coo_to_csr_workspace(int64_t total);
+hipError_t coo_to_csr(const int32_t* row, const int32_t* col, const double* val, int64_t nnz_in, int64_t n,
+                      int symmetrize, void* work, size_t work_bytes, int64_t* rowptr_out, int32_t* col_out,
+                      double* val_out, int* bad, hipStream_t st);
+
 }  // namespace sceig

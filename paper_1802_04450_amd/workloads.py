@@ -429,6 +429,42 @@ def embedding_like(n: int, k: int, seed: int, noise: float = 1e-3) -> np.ndarray
     return q / np.linalg.norm(q, axis=1, keepdims=True)
 
 
+def voxel_neighbour_pairs(n: int, radius2: int = 5, side: Optional[int] = None):
+    """Pair list of the shape of the paper's DTI input (Section V-A: 142,541 voxels, 3,992,290 pairs within 4 mm on a
+    2 mm grid): the first n cells of a side^3 grid in x-fastest order, every pair of cells whose integer offset has
+    squared length <= radius2 listed once (u < v).  radius2 = 5 gives 28 pairs per interior cell."""
+    if side is None:
+        side = int(math.ceil(n ** (1.0 / 3.0)))
+    idx = np.arange(n, dtype=np.int64)
+    ix, iy, iz = idx % side, (idx // side) % side, idx // (side * side)
+    us, vs = [], []
+    r = int(math.isqrt(radius2))
+    for dz in range(0, r + 1):
+        for dy in range(-r, r + 1):
+            for dx in range(-r, r + 1):
+                if dx * dx + dy * dy + dz * dz > radius2 or (dz, dy, dx) <= (0, 0, 0):
+                    continue
+                ok = (ix + dx >= 0) & (ix + dx < side) & (iy + dy >= 0) & (iy + dy < side) & (iz + dz < side)
+                j = idx + dx + dy * side + dz * side * side
+                ok &= j < n
+                us.append(idx[ok])
+                vs.append(j[ok])
+    return np.concatenate(us).astype(np.int32), np.concatenate(vs).astype(np.int32)
+
+
+def connectivity_profiles(n: int, d: int, seed: int, side: Optional[int] = None) -> np.ndarray:
+    """n x d non-negative rows that vary smoothly over the voxel grid (a few smooth spatial modes per coordinate plus
+    noise): the shape of the DTI connectivity profiles (d = 90 regions)."""
+    rng = np.random.default_rng(seed)
+    if side is None:
+        side = int(math.ceil(n ** (1.0 / 3.0)))
+    idx = np.arange(n)
+    pos = np.stack([idx % side, (idx // side) % side, idx // (side * side)], axis=1) / side
+    freq = rng.uniform(0.5, 3.0, size=(3, d))
+    phase = rng.uniform(0, 2 * np.pi, size=d)
+    return np.abs(np.sin(2 * np.pi * pos @ freq + phase) + 0.3 * rng.normal(size=(n, d)))
+
+
 def describe(graph: CSR) -> dict:
     rowptr, col, val, n = graph
     deg = np.diff(rowptr)

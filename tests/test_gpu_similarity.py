@@ -1,0 +1,132 @@
+"""GPU parity of the similarity-graph step (Section IV-A, Algorithm 1; Algorithm 2 step 4) against the oracle,
+through the C ABI, and the chain points -> similarity -> CSR -> eigensolver input."""
+import numpy as np
+import pytest
+
+from oracle import similarity as osim
+from paper_1802_04450_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_1802_04450_amd import binding
+    binding.lib()
+    return binding
+
+
+def _dev(a, dtype):
+    return torch.as_tensor(np.ascontiguousarray(a), dtype=dtype, device="cuda:0")
+
+
+def _edges(n, ne, seed):
+    rng = np.random.default_rng(seed)
+    u = rng.integers(0, n, size=ne)
+    v = rng.integers(0, n, size=ne)
+    return u, v
+
+
+@pytest.mark.parametrize("n,d,ne", [(5003, 90, 40011), (1000, 3, 7777), (300, 1, 500), (2000, 33, 20000),
+                                    (700, 257, 3000), (10, 16, 0)])
+@pytest.mark.parametrize("measure", [0, 1, 2])
+def test_edge_similarity_matches_oracle(B, n, d, ne, measure):
+    rng = np.random.default_rng(n + d + measure)
+    x = rng.normal(size=(n, d)) + 2.0 * rng.normal(size=(n, 1))
+    u, v = _edges(n, ne, 3)
+    if d == 1 and measure == 0:
+        pytest.skip("one coordinate: every centred row is zero, the measure is 0/0 by definition")
+    sigma = 1.7 * np.sqrt(d)
+    ref = osim.edge_similarity(x, u, v, measure, sigma) if ne else np.zeros(0)
+    got = B.sc_edge_similarity(_dev(x, torch.float64), _dev(u, torch.int32), _dev(v, torch.int32), measure, sigma)
+    np.testing.assert_allclose(got.cpu().numpy(), ref, rtol=1e-12, atol=1e-14)
+
+
+def test_edge_similarity_strided_rows_and_errors(B):
+    rng = np.random.default_rng(1)
+    n, d = 400, 7
+    big = torch.as_tensor(rng.normal(size=(n, 11)), device="cuda:0")        # odd leading dimension: scalar loads
+    x = big[:, :d]
+    u, v = _edges(n, 3000, 5)
+    du, dv = _dev(u, torch.int32), _dev(v, torch.int32)
+    val = torch.empty(3000, dtype=torch.float64, device="cuda:0")
+    lib = B.lib()
+    st = torch.cuda.current_stream().cuda_stream
+    assert lib.sc_edge_similarity(x.data_ptr(), 11, n, d, du.data_ptr(), dv.data_ptr(), 3000, 0, 1.0, val.data_ptr(), st) == 0
+    ref = osim.edge_similarity(big.cpu().numpy()[:, :d], u, v, 0)
+    np.testing.assert_allclose(val.cpu().numpy(), ref, rtol=1e-12, atol=1e-14)
+    assert lib.sc_edge_similarity(x.data_ptr(), 5, n, d, du.data_ptr(), dv.data_ptr(), 3000, 0, 1.0, val.data_ptr(), st) == B.SC_EDOMAIN
+    assert lib.sc_edge_similarity(x.data_ptr(), 11, n, d, du.data_ptr(), dv.data_ptr(), 3000, 2, 0.0, val.data_ptr(), st) == B.SC_EDOMAIN
+    assert lib.sc_edge_similarity(x.data_ptr(), 11, n, d, du.data_ptr(), dv.data_ptr(), 3000, 3, 1.0, val.data_ptr(), st) == B.SC_EDOMAIN
+    assert lib.sc_edge_similarity(None, 11, n, d, du.data_ptr(), dv.data_ptr(), 3000, 0, 1.0, val.data_ptr(), st) == B.SC_EINVAL
+    u2 = u.copy()
+    u2[17] = n          # an index past the end is reported, not read
+    assert lib.sc_edge_similarity(x.data_ptr(), 11, n, d, _dev(u2, torch.int32).data_ptr(), dv.data_ptr(), 3000, 0, 1.0,
+                                  val.data_ptr(), st) == B.SC_ECSR
+    out = val.cpu().numpy()
+    assert np.isnan(out[17]) and np.all(np.isfinite(np.delete(out, 17)))
+
+
+@pytest.mark.parametrize("symmetrize", [False, True])
+@pytest.mark.parametrize("n,ne", [(50, 400), (3001, 40000), (7, 5), (100000, 300000)])
+def test_coo_to_csr_matches_oracle(B, n, ne, symmetrize):
+    rng = np.random.default_rng(n + ne)
+    r, c = _edges(n, ne, 11)                     # random pairs: duplicates and self loops occur
+    w = rng.uniform(0.1, 1.0, size=ne)
+    rp, co, vo = B.sc_coo_to_csr(_dev(r, torch.int32), _dev(c, torch.int32), _dev(w, torch.float64), n, symmetrize)
+    rp, co, vo = rp.cpu().numpy(), co.cpu().numpy(), vo.cpu().numpy()
+    nself = int(np.sum(r == c))
+    assert rp[0] == 0 and rp[-1] == (2 * ne - nself if symmetrize else ne) == co.size
+    assert np.all(np.diff(rp) >= 0) and osim.csr_rows_sorted(rp, co)
+    from scipy.sparse import csr_matrix, coo_matrix
+    got = csr_matrix((vo, co, rp), shape=(n, n))
+    if n <= 5000:
+        np.testing.assert_allclose(got.toarray(), osim.coo_to_dense(r, c, w, n, symmetrize), rtol=1e-15, atol=0)
+    else:   # same matrix through the library's own conversion (sums duplicates in an order of its own)
+        rr, cc, ww = (np.concatenate([r, c[r != c]]), np.concatenate([c, r[r != c]]),
+                      np.concatenate([w, w[r != c]])) if symmetrize else (r, c, w)
+        ref = coo_matrix((ww, (rr, cc)), shape=(n, n)).tocsr()
+        assert abs(got - ref).max() <= 1e-15
+    # listed duplicates stay separate entries, in listing order
+    if n == 7:
+        for i in range(n):
+            for j in np.unique(co[rp[i]:rp[i + 1]]):
+                mine = vo[rp[i]:rp[i + 1]][co[rp[i]:rp[i + 1]] == j]
+                listed = [w[e] for e in range(ne) if (r[e], c[e]) == (i, j)]
+                if symmetrize:
+                    listed += [w[e] for e in range(ne) if (c[e], r[e]) == (i, j) and r[e] != c[e]]
+                assert sorted(mine.tolist()) == sorted(listed)
+
+
+def test_coo_to_csr_edge_cases(B):
+    z32 = torch.empty(0, dtype=torch.int32, device="cuda:0")
+    z64 = torch.empty(0, dtype=torch.float64, device="cuda:0")
+    rp, co, vo = B.sc_coo_to_csr(z32, z32, z64, 5, True)
+    assert rp.cpu().tolist() == [0] * 6 and co.numel() == 0
+    with pytest.raises(B.ScError) as err:
+        B.sc_coo_to_csr(_dev([0, 9], torch.int32), _dev([1, 2], torch.int32), _dev([1.0, 1.0], torch.float64), 5, True)
+    assert err.value.code == B.SC_ECSR
+
+
+def test_points_to_eigenpairs_chain(B):
+    """Algorithm 1 -> Algorithm 2's conversion -> eigensolver, all on the device, from the pair list of the harness's
+    kNN search: the CSR equals the harness's own graph and the eigenvalues the dense oracle's."""
+    from oracle import dense
+    cfg = wl.reduced(wl.CONFIGS[1], n=1500, components=5, k=5)
+    pts, _ = wl.mixture_points(cfg)
+    (rp, c, v, n), sigma = wl.knn_gaussian_graph(pts, cfg.k_nn, device="cpu")
+    rows = np.repeat(np.arange(n), np.diff(rp))
+    upper = rows < c                                 # every undirected edge once
+    eu, ev = _dev(rows[upper], torch.int32), _dev(c[upper], torch.int32)
+    w = B.sc_edge_similarity(_dev(pts, torch.float64), eu, ev, B.SC_SIM_EXP_DECAY, sigma)
+    rp2, c2, v2 = B.sc_coo_to_csr(eu, ev, w, n, True)
+    np.testing.assert_array_equal(rp2.cpu().numpy(), rp)
+    np.testing.assert_array_equal(c2.cpu().numpy(), c)
+    np.testing.assert_allclose(v2.cpu().numpy(), v, rtol=1e-12)
+    evals, evecs, code, _ = B.sc_laplacian_eigsh(rp2, c2, v2, 5, 1e-10)
+    lam_full, _ = dense.full_spectrum(rp, c, v)
+    assert code == 0 and np.max(np.abs(evals.cpu().numpy() - lam_full[:5])) <= 1e-8
