@@ -769,6 +769,22 @@ struct Solver {
       double last_rho = -1.0;
       int last_rho_step = 0;
       bool phase_over = false;
+      // Block steps until the next inspection, from the decay of the residual estimate r_now of the last wanted pair
+      // since the previous inspection of this phase: 85 % of the steps that rate needs to reach tol, at most 12 -
+      // unless that is more than twice the `room` steps left before the basis is full (Lanczos converges faster
+      // than its early rate, hence the factor), when only the restart inspects.
+      auto schedule_check = [&](double r_now, int room) {
+        int next = std::max(1, check_every);
+        if (last_rho > 0.0 && r_now > 0.0 && r_now < last_rho && steps_in_phase > last_rho_step) {
+          const double rate = std::log(last_rho / r_now) / (steps_in_phase - last_rho_step);
+          const double need = std::log(r_now / std::max(tol, 1e-300)) / rate;
+          const int guess = (int)std::floor(0.85 * std::min(need, 1e6));
+          next = guess > 2 * room ? room + 1 : std::min(std::max(guess, 1), 12);
+        }
+        last_rho = r_now;
+        last_rho_step = steps_in_phase;
+        return next;
+      };
 
       while (!phase_over) {
         if (next_slot >= max_slots) SC_THROW(SC_EDOMAIN);  // cannot happen: a cycle has at most m/b steps
@@ -982,8 +998,10 @@ struct Solver {
           assembled = l;
           next_slot = 1;
           fetched = 1;
-          next_check = std::max(1, check_every);
-          last_rho = -1.0;
+          // The residual of the last wanted pair keeps decaying across restarts: when the rate observed so far says
+          // that convergence is further away than the basis has room for, the next inspection worth its projected
+          // eigenproblem is the one at the next restart.
+          next_check = schedule_check(rho[std::min({want, nreal, nsel}) - 1], (cap - ja) / b + 1);
           continue;
         }
         // ---- continue: the new block joins; schedule the next inspection from the observed decay
@@ -998,16 +1016,7 @@ struct Solver {
             }
           }
           ja += b;
-          const double r_now = rho[std::min(want, nreal) - 1];
-          next_check = std::max(1, check_every);
-          if (last_rho > 0.0 && r_now > 0.0 && r_now < last_rho && steps_in_phase > last_rho_step) {
-            const double rate = std::log(last_rho / r_now) / (steps_in_phase - last_rho_step);
-            const double need = std::log(r_now / std::max(tol, 1e-300)) / rate;
-            int guess = (int)std::floor(0.85 * need);
-            next_check = std::min(std::max(guess, 1), 12);
-          }
-          last_rho = r_now;
-          last_rho_step = steps_in_phase;
+          next_check = schedule_check(rho[std::min({want, nreal, nsel}) - 1], (cap - ja) / b + 1);
         }
         (void)assembled;
       }
