@@ -252,6 +252,10 @@ def main():
     ap.add_argument("--spmv-only", action="store_true",
                     help="build the workload, measure only the single-vector product y = S x, print its JSON and stop "
                          "(for the workloads whose eigensolve is not the benchmark: cfg3, cfg4, cfg5)")
+    ap.add_argument("--no-large-spmv", action="store_true",
+                    help="skip the single-vector product on the 4,000,000-node workload (config 4) that the default run "
+                         "adds as `spmv_large`: the product is bandwidth-bound only at that size (about 40 s, most of "
+                         "it building the graph)")
     ap.add_argument("--kmeans", action="store_true",
                     help="the clustering step that follows the eigensolve (Algorithms 4-5) on a synthetic row-normalised "
                          "embedding of the benchmark workload's shape (n points, d = k); prints its own JSON line")
@@ -343,6 +347,21 @@ def main():
                            "fp64_tflops": stats["fam_flops"][dom] / kt / 1e12,
                            "fp64_mfma_frac": stats["fam_flops"][dom] / kt / 1e12 / FP64_MFMA_PEAK_TFLOPS,
                            "family_seconds_per_step": {B.FAMILIES[f]: fam_t[f] for f in range(6)}}
+    if args.workload == "cfg2" and not args.no_large_spmv:
+        # The benchmark workload's product moves 42 MB and is launch-latency bound; the HBM-bound figure is the one of
+        # the 4,000,000-node workload, measured here in the same run (graph built on the box, resident in HBM).
+        del drp, dc, dv
+        B.sc_release_cache()
+        torch.cuda.empty_cache()
+        cfg4, graph4 = build_workload("cfg4")
+        rp4, c4, v4, n4 = graph4
+        nnz4 = int(rp4[-1])
+        d4 = B.csr_to_device(rp4, c4, v4)
+        large = measure_spmv(B, torch, d4[0], d4[1], d4[2], n4, nnz4)
+        large["workload"] = f"{cfg4.name}: n={n4}, nnz={nnz4}"
+        out["spmv_large"] = large
+        del d4
+        B.sc_release_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, graph)
     print(json.dumps(out), flush=True)
