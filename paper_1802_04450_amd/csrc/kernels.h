@@ -79,7 +79,7 @@ hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, i
 // ---- connected components and locality reordering (setup) --------------------------------------
 // Renumbering from the component labels (label[i] = smallest node index of i's component), on the device:
 //   old_of_new[p] = original index of new row p (components contiguous, ordered by their smallest node; inside a
-//   component by the min-hash of the closed neighbourhood, ties in original order), new_of_old = its inverse,
+//   component by three levels of neighbourhood min-hash, ties in original order), new_of_old = its inverse,
 //   rowptr_new (n+1) = row pointers of the permuted matrix, comp_of_new[p] = component index of new row p.
 // work: device scratch of order_by_component_workspace(n) bytes.  All outputs are device arrays; n <= INT32_MAX.
 size_t order_by_component_workspace(int64_t n);

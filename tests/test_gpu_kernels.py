@@ -98,6 +98,28 @@ def test_spmm_normalized(B, graphs, ncols):
         assert torch.equal(y2, yb[:, :ncols])
 
 
+@pytest.mark.parametrize("shift", [0, 1, 2, 3])
+def test_single_vector_product_on_offset_arrays(B, graphs, shift):
+    """The single-vector product clamps its stream loads to the tile instead of predicating them: the same answer from
+    (col, val) arrays that start 0..3 elements into a buffer (nothing before or after them is needed), on hub rows
+    longer than the register buffer and on a graph of two rows."""
+    rng = np.random.default_rng(shift)
+    for name, (rp, c, v, n) in graphs.items():
+        nnz = int(rp[-1])
+        cbuf = torch.zeros(nnz + 8, dtype=torch.int32, device="cuda")
+        vbuf = torch.zeros(nnz + 8, dtype=torch.float64, device="cuda")
+        dc, dv = cbuf[shift:shift + nnz], vbuf[shift:shift + nnz]
+        dc.copy_(torch.from_numpy(c))
+        dv.copy_(torch.from_numpy(v))
+        drp = torch.from_numpy(rp).cuda()
+        _, s = B.sc_degree_scaling(drp, dc, dv)
+        x = rng.standard_normal(n)
+        y = B.sc_spmm_normalized(drp, dc, dv, s, torch.from_numpy(x).cuda()).cpu().numpy()
+        y0 = laplacian.apply_s(rp, c, v, x)
+        assert np.max(np.abs(y - y0)) <= 1e-13 * (np.abs(y0).max() + 1e-300), (name, shift)
+        assert torch.all(cbuf[shift + nnz:] == 0) and torch.all(vbuf[:shift] == 0.0)
+
+
 @pytest.mark.parametrize("n,j,b", [(5000, 70, 16), (4099, 130, 8), (3001, 300, 32), (2500, 17, 1), (2000, 64, 4),
                                    (777, 5, 2), (70000, 200, 16), (140000, 40, 32), (300, 280, 8)])
 def test_cgs2(B, n, j, b):
