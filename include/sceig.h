@@ -145,6 +145,17 @@ int sc_laplacian_eigsh(const int64_t* csr_rowptr, const int32_t* csr_col, const 
                        const sc_options* opt, sc_stats* stats);
 
 /*
+ * Device memory, in bytes, that sc_laplacian_eigsh takes for itself for a problem of this size (an upper estimate of the
+ * sum of its blocks: its renumbered copy of the operator, the basis n x (m + b), the rotation workspace, the packed
+ * block, partial-sum and coefficient buffers), with the same defaults for opt->m and opt->block as the solve.  Nothing is
+ * allocated and no GPU is needed.  The blocks come from the library's cache (see sc_release_cache); there is no
+ * caller-provided workspace: every buffer a caller hands over is an input or an output.
+ *   bytes_out  host
+ * Returns SC_OK, SC_EINVAL, or SC_EDOMAIN exactly where the solve would.
+ */
+int sc_workspace_bytes(int64_t n, int64_t nnz, int32_t k, const sc_options* opt, size_t* bytes_out);
+
+/*
  * Setup step (Algorithm 2 steps 1-2, with the scaling kept as a vector instead of a scaled copy of W):
  * d_i = sum_j W_ij and s_i = d_i^-1/2.   d_out, s_out: device fp64[n] (d_out may be NULL).
  * Returns SC_EZERODEG if some d_i is <= 0 or not finite (outputs then hold what was computed).

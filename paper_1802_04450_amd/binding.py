@@ -28,7 +28,7 @@ FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_reorder_csr", "sc_cgs2",
            "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version", "sc_release_cache",
            "sc_chebyshev_filter", "sc_kmeanspp", "sc_kmeans_lloyd", "sc_kmeans", "sc_edge_similarity",
-           "sc_coo_to_csr"]
+           "sc_coo_to_csr", "sc_workspace_bytes"]
 
 
 class ScOptions(ctypes.Structure):
@@ -87,6 +87,7 @@ def lib() -> ctypes.CDLL:
         vp, i32, i64, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
         _lib.sc_laplacian_eigsh.argtypes = [vp, vp, vp, i64, i32, dbl, i32, vp, vp, vp, ctypes.POINTER(ScOptions),
                                             ctypes.POINTER(ScStats)]
+        _lib.sc_workspace_bytes.argtypes = [i64, i64, i32, ctypes.POINTER(ScOptions), ctypes.POINTER(ctypes.c_size_t)]
         _lib.sc_degree_scaling.argtypes = [vp, vp, vp, i64, vp, vp, vp]
         _lib.sc_spmm_normalized.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, i64, i32, vp, vp]
         _lib.sc_validate_csr.argtypes = [vp, vp, i64, vp]
@@ -167,6 +168,14 @@ def sc_laplacian_eigsh(rowptr, col, val, k: int, tol: float, maxiter: int = 1000
                                         _ptr(evecs), _stream(), ctypes.byref(opt), ctypes.byref(stats))
     _check(code)
     return evals, evecs, code, stats.as_dict()
+
+
+def sc_workspace_bytes(n: int, nnz: int, k: int, m: int = 0, block: int = 0, flags: int = 0) -> int:
+    """Device bytes a solve of this size allocates for itself (host-only query)."""
+    opt = ScOptions(m=m, block=block, flags=flags)
+    out = ctypes.c_size_t(0)
+    _check(lib().sc_workspace_bytes(n, nnz, k, ctypes.byref(opt), ctypes.byref(out)), soft_ok=False)
+    return int(out.value)
 
 
 def sc_degree_scaling(rowptr, col, val, want_degrees: bool = True):

@@ -1126,6 +1126,28 @@ bool supported_block(int b) { return b == 1 || b == 2 || b == 4 || b == 8 || b =
 
 using namespace sceig;
 
+// Basis budget m and block size b of a solve: the caller's values, or the defaults.
+int resolve_basis(int64_t n, int32_t k, const sc_options& o, int64_t* m_out, int* b_out) {
+  int64_t m = o.m;
+  if (m == 0) m = std::min<int64_t>(n, std::max<int64_t>(2 * (int64_t)k, (int64_t)k + 56));
+  if (m > n || m < (int64_t)k + 3) return SC_EDOMAIN;
+  int b = o.block;
+  if (b == 0) {
+    // Larger blocks amortise the passes over the basis (their cost grows with n), smaller blocks keep the
+    // projected problems and the number of block steps per converged vector small.
+    int target = n >= 20000 ? 16 : 8;
+    if (n >= 300000 && k >= 1000) target = 32;
+    b = std::min(target, pow2_floor((int)std::max<int64_t>(1, (m - k) / 3)));
+    int kb = 1;
+    while (kb < k) kb *= 2;
+    b = std::min(b, kb);
+  }
+  if (!supported_block(b) || (int64_t)k + 3 * (int64_t)b > m) return SC_EDOMAIN;
+  *m_out = m;
+  *b_out = b;
+  return SC_OK;
+}
+
 // ---- k-means on the embedding (Section II Step 4, Section IV-C, Algorithms 4 and 5) ------------------------------
 namespace {
 
@@ -1357,21 +1379,10 @@ int sc_laplacian_eigsh(const int64_t* csr_rowptr, const int32_t* csr_col, const 
   sv.seed = o.seed;
   sv.check_every = o.check_every > 0 ? o.check_every : 2;
   sv.st = reinterpret_cast<hipStream_t>(stream);
-  int64_t m = o.m;
-  if (m == 0) m = std::min<int64_t>(n, std::max<int64_t>(2 * (int64_t)k, (int64_t)k + 56));
-  if (m > n || m < (int64_t)k + 3) return SC_EDOMAIN;
-  int b = o.block;
-  if (b == 0) {
-    // Larger blocks amortise the passes over the basis (their cost grows with n), smaller blocks keep the
-    // projected problems and the number of block steps per converged vector small.
-    int target = n >= 20000 ? 16 : 8;
-    if (n >= 300000 && k >= 1000) target = 32;
-    b = std::min(target, pow2_floor((int)std::max<int64_t>(1, (m - k) / 3)));
-    int kb = 1;
-    while (kb < k) kb *= 2;
-    b = std::min(b, kb);
-  }
-  if (!supported_block(b) || (int64_t)k + 3 * (int64_t)b > m) return SC_EDOMAIN;
+  int64_t m = 0;
+  int b = 0;
+  const int rc0 = resolve_basis(n, k, o, &m, &b);
+  if (rc0 != SC_OK) return rc0;
   sv.m = (int)m;
   sv.b = b;
   struct Ctx {
@@ -1388,6 +1399,38 @@ int sc_laplacian_eigsh(const int64_t* csr_rowptr, const int32_t* csr_col, const 
   if (stats) *stats = sv.stats;
   if (rc < 0) (void)hipStreamSynchronize(sv.st);
   return rc;
+}
+
+int sc_workspace_bytes(int64_t n, int64_t nnz, int32_t k, const sc_options* opt, size_t* bytes_out) {
+  if (!bytes_out || n < 0 || nnz < 0) return SC_EINVAL;
+  if (k < 1 || (int64_t)k >= n || n > (int64_t)0x7fffffff) return SC_EDOMAIN;
+  sc_options o{};
+  if (opt) o = *opt;
+  int64_t m = 0;
+  int b = 0;
+  const int rc = resolve_basis(n, k, o, &m, &b);
+  if (rc != SC_OK) return rc;
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  const size_t N = (size_t)n, Z = (size_t)nnz;
+  const size_t ld = ((size_t)m + b + 15) / 16 * 16;
+  const size_t jmax = (size_t)m + b;
+  const size_t rot_cols = (size_t)std::min<int64_t>(m, std::max<int64_t>(m / 2 + b, 2 * (int64_t)b));
+  size_t total = 0;
+  if (!(o.flags & SC_FLAG_NO_REORDER)) {
+    // the renumbered operator copy, the two row maps, and the sort's scratch (released before the basis is allocated,
+    // but held while the copy is built)
+    total += up((N + 1) * 8) + up(Z * 4) + up(Z * 8) + 2 * up(N * 4);
+    total += up(order_by_component_workspace(n)) + 2 * up(N * 4);
+  }
+  total += up(N * 8);                       // scaling vector
+  if (b >= 8) total += up(Z * 8);           // scaled operator values
+  total += up(N * ld * 8) + up(N * (size_t)b * 8) + up(N * rot_cols * 8);  // basis, packed block, rotation workspace
+  total += up((size_t)kMaxPartials * jmax * kPP * 8) + up((size_t)kGramPartials * kPP * kPP * 8) + 2 * up(jmax * kPP * 8);
+  total += up((size_t)(m / b + 4) * kSlotDoubles * 8) + up(jmax * std::max<size_t>(rot_cols, (size_t)k) * 8);
+  if (o.flags & SC_FLAG_COMPONENT_NULLSPACE) total += up(N * 8) + up(N * 4) + up(N * 8);
+  total += 16 * 256;                        // flags, small matrices, the output permutation
+  *bytes_out = total;
+  return SC_OK;
 }
 
 int sc_degree_scaling(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n,

@@ -130,3 +130,25 @@ def test_argument_errors_without_gpu():
     assert lib.sc_sym_eig_top(one, 3, 4, one, one) == binding.SC_EDOMAIN
     assert lib.sc_sym_eig_top(one, 3, 2, one, null) == binding.SC_EINVAL
     assert lib.sc_degree_scaling(one, one, one, 0, null, one, null) == binding.SC_OK               # n = 0: nothing to do
+
+
+def test_workspace_bytes_query():
+    """Host-only query: the figure contains the big blocks (basis n x (m + b), rotation workspace, operator copy),
+    grows with m, and fails exactly where a solve would."""
+    from paper_1802_04450_amd import binding as B
+    n, nnz, k = 500_000, 8_100_000, 2000
+    w = B.sc_workspace_bytes(n, nnz, k, m=4000)
+    basis = n * 4032 * 8                       # block 32 by default at this size: ld = roundup16(4000 + 32)
+    rot = n * (4000 // 2 + 32) * 8
+    copy = nnz * 12 + nnz * 8
+    assert basis + rot + copy < w < 1.1 * (basis + rot + copy) + (64 << 20)
+    assert B.sc_workspace_bytes(n, nnz, k, m=5000) > w
+    assert B.sc_workspace_bytes(n, nnz, k, m=4000, flags=B.SC_FLAG_NO_REORDER) < w
+    small = B.sc_workspace_bytes(2000, 30000, 8)
+    assert 2000 * 64 * 8 < small < (64 << 20)    # dominated by the fixed partial-sum buffers at this size
+    for bad in (dict(n=10, nnz=20, k=10), dict(n=10, nnz=20, k=0), dict(n=100, nnz=500, k=5, m=6),
+                dict(n=100, nnz=500, k=5, m=101), dict(n=100, nnz=500, k=5, block=3)):
+        with pytest.raises(B.ScError) as e:
+            B.sc_workspace_bytes(**bad)
+        assert e.value.code == B.SC_EDOMAIN
+    assert B.lib().sc_workspace_bytes(100, 500, 5, None, None) == B.SC_EINVAL
