@@ -374,3 +374,23 @@ def test_row_normalized_embedding(B):
         gram = emb @ emb.T
         same = label[:, None] == label[None, :]
         assert np.max(np.abs(gram[same] - 1.0)) <= 1e-7 and np.max(np.abs(gram[~same])) <= 1e-7
+
+
+def test_workspace_estimate_covers_what_a_solve_allocates(B):
+    """sc_workspace_bytes against the device memory that actually leaves the free pool during a solve (the library
+    keeps its blocks cached afterwards, so the drop in free memory is what the solve took)."""
+    cfg = wl.reduced(wl.CONFIGS[2], n=60000, components=60, k=60)
+    g, _, _ = wl.build_config_graph(cfg, device="cuda")
+    rp, c, v, n = g
+    drp, dc, dv = B.csr_to_device(rp, c, v)
+    B.sc_release_cache()
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    evals, evecs, code, stats = B.sc_laplacian_eigsh(drp, dc, dv, cfg.k, 1e-8, m=cfg.m)
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    taken = free0 - free1 - evals.numel() * 8 - evecs.numel() * 8      # the outputs are torch's, allocated in between
+    est = B.sc_workspace_bytes(n, int(rp[-1]), cfg.k, m=cfg.m)
+    assert code == B.SC_OK
+    assert 0.8 * taken <= est <= 1.5 * taken + (32 << 20), (taken, est)
+    B.sc_release_cache()
