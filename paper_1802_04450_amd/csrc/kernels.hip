@@ -1067,6 +1067,15 @@ __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restric
 
 // Cholesky of the b x b Gram matrix in the registers of one wave: lane t owns column t of G, R and R^-1;
 // values of other columns travel by lane reads.  Same dropping rule as documented in kernels.h.
+// Value of lane `l` (a compile-time constant after unrolling) for the whole wave: a scalar lane read, not a trip
+// through the LDS crossbar.
+__device__ __forceinline__ double bcast_lane(double v, int l) {
+  const long long bits = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_readlane((int)bits, l);
+  const int hi = __builtin_amdgcn_readlane((int)(bits >> 32), l);
+  return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
 template <int B>
 __global__ __launch_bounds__(64) void chol_reg_kernel(const double* __restrict__ g_in, double* __restrict__ g_out,
                                                       double* __restrict__ rinv_out, double* __restrict__ r_out,
@@ -1091,8 +1100,8 @@ __global__ __launch_bounds__(64) void chol_reg_kernel(const double* __restrict__
   for (int k = 0; k < B; ++k) {
     double v = gcol[k];
 #pragma unroll
-    for (int q = 0; q < k; ++q) v -= __shfl(rcol[q], k) * rcol[q];
-    const double gkk = __shfl(gcol[k], k), pk = __shfl(v, k);
+    for (int q = 0; q < k; ++q) v -= bcast_lane(rcol[q], k) * rcol[q];
+    const double gkk = bcast_lane(gcol[k], k), pk = bcast_lane(v, k);
     const bool drop = !(gkk > abs_tol2) || !(pk > rel_tol * gkk);
     const double rkk = drop ? 0.0 : sqrt(pk);
     rcol[k] = (t == k) ? rkk : ((t > k && !drop) ? v / rkk : 0.0);
@@ -1102,11 +1111,11 @@ __global__ __launch_bounds__(64) void chol_reg_kernel(const double* __restrict__
   for (int q = 0; q < B; ++q) rcc = (q == t) ? rcol[q] : rcc;
 #pragma unroll
   for (int r = B - 1; r >= 0; --r) {
-    const double rrr = __shfl(rcol[r], r);
+    const double rrr = bcast_lane(rcol[r], r);
     double sum = 0.0;
 #pragma unroll
     for (int x = r + 1; x < B; ++x) {
-      const double rrx = __shfl(rcol[r], x);
+      const double rrx = bcast_lane(rcol[r], x);
       sum += (x <= t) ? rrx * ricol[x] : 0.0;
     }
     double v = 0.0;
@@ -1129,7 +1138,7 @@ __global__ __launch_bounds__(64) void chol_reg_kernel(const double* __restrict__
       if (rprev) {
         v = 0.0;
 #pragma unroll
-        for (int x = q; x < B; ++x) v += __shfl(rcol[q], x) * pcol[x];
+        for (int x = q; x < B; ++x) v += bcast_lane(rcol[q], x) * pcol[x];
       }
       if (act) r_out[q * kPartialPad + t] = v;
     }
