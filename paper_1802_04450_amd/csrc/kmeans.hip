@@ -3,7 +3,8 @@
 // matrix cores (row_gemm_kernel, kernels.hip); |v|^2 does not change the arg-min and is left out.  The centre update
 // is sort based as in the paper (points ordered by label, every cluster a contiguous run), with a fixed summation
 // order so that results are reproducible.  The seeding follows Algorithm 5 with the uniform numbers supplied by the
-// host (a counter-based generator), prefix sums from hipCUB.
+// host (a counter-based generator); a draw is one distance pass that also leaves block sums and one single-workgroup
+// kernel that walks the sums level by level to the drawn point.
 #include <hip/hip_runtime.h>
 #include <hipcub/hipcub.hpp>
 
@@ -151,35 +152,126 @@ __global__ __launch_bounds__(kT) void centroid_mean_kernel(const double* __restr
   }
 }
 
-// dist2[i] = |x_i - x_c|^2 (first != 0) or min(dist2[i], |x_i - x_c|^2), c = *centre.  16 lanes per point.
+// dist2[i] = |x_i - x_c|^2 (first != 0) or min(dist2[i], |x_i - x_c|^2), c = *centre; bsum[block] = the sum of the
+// block's 16 values of dist2 in point order.  16 lanes per point, 16 points per workgroup.
+constexpr int kSeedPoints = kT / 16;
 __global__ __launch_bounds__(kT) void seed_distance_kernel(const double* __restrict__ x, int64_t ldx, int d, int64_t n,
                                                            const int32_t* __restrict__ centre, int first,
-                                                           double* __restrict__ dist2) {
+                                                           double* __restrict__ dist2, double* __restrict__ bsum) {
   constexpr int L = 16;
+  __shared__ double pts[kSeedPoints];
   const int lane = threadIdx.x % L;
-  const int64_t i = (int64_t)blockIdx.x * (kT / L) + threadIdx.x / L;
-  if (i >= n) return;
-  const int64_t c = *centre;
-  double acc = 0.0;
-  for (int t = lane; t < d; t += L) {
-    const double diff = x[i * ldx + t] - x[c * ldx + t];
-    acc += diff * diff;
-  }
+  const int64_t i = (int64_t)blockIdx.x * kSeedPoints + threadIdx.x / L;
+  double mine = 0.0;
+  if (i < n) {  // uniform over the point's lanes
+    const int64_t c = *centre;
+    double acc = 0.0;
+    for (int t = lane; t < d; t += L) {
+      const double diff = x[i * ldx + t] - x[c * ldx + t];
+      acc += diff * diff;
+    }
 #pragma unroll
-  for (int o = L / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, L);
-  if (lane == 0) dist2[i] = first ? acc : (acc < dist2[i] ? acc : dist2[i]);
+    for (int o = L / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, L);
+    mine = first ? acc : (acc < dist2[i] ? acc : dist2[i]);
+    if (lane == 0) dist2[i] = mine;
+  }
+  if (lane == 0) pts[threadIdx.x / L] = mine;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double tot = 0.0;
+#pragma unroll
+    for (int q = 0; q < kSeedPoints; ++q) tot += pts[q];
+    bsum[blockIdx.x] = tot;
+  }
 }
 
-// Algorithm 5's draw: the first index whose inclusive prefix sum exceeds u * total; *chosen was preset to n - 1 for
-// the case that no index qualifies.  A parallel prefix sum may be non-monotone by a rounding, so more than one index
-// can pass the test: the smallest one wins (atomic minimum), whatever the order the threads run in.
-__global__ __launch_bounds__(kT) void seed_pick_kernel(const double* __restrict__ cs, int64_t n, double u,
-                                                       int32_t* __restrict__ chosen) {
-  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
-  if (i >= n) return;
-  const double r = u * cs[n - 1];
-  const double prev = i ? cs[i - 1] : 0.0;
-  if (prev <= r && r < cs[i]) atomicMin(chosen, (int32_t)i);
+// Inclusive prefix sums of one value per lane over the wave (fixed shuffle tree).
+__device__ __forceinline__ double wave_inclusive(double v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const double up = __shfl_up(v, o, 64);
+    if (lane >= o) v += up;
+  }
+  return v;
+}
+
+// The first position p in [0, count) with base + (v[0] + ... + v[p]) > r, searched by one wave in pieces of 64; *base
+// receives the sum before that position.  -1 if there is none (then *base = base + the whole sum).
+__device__ int wave_first_exceeding(const double* __restrict__ v, int64_t count, double r, double* base, int lane) {
+  double acc = *base;
+  for (int64_t p0 = 0; p0 < count; p0 += 64) {
+    const double mine = p0 + lane < count ? v[p0 + lane] : 0.0;
+    const double incl = wave_inclusive(mine, lane) + acc;
+    const bool hit = p0 + lane < count && incl > r;
+    const uint64_t mask = __ballot(hit);
+    if (mask) {
+      const int l = __ffsll((long long)mask) - 1;
+      *base = __shfl(incl - mine, l, 64);
+      return (int)p0 + l;
+    }
+    acc = __shfl(incl, 63, 64);
+  }
+  *base = acc;
+  return -1;
+}
+
+// Algorithm 5's draw in one workgroup: total = sum of all dist2 (through the block sums), r = u * total, and the first
+// point whose inclusive prefix sum exceeds r, found level by level: the 1024 threads each sum a contiguous run of
+// block sums, their prefix sums name the run, one wave then finds the block inside the run and the point inside the
+// block.  Every sum has a fixed order.  If rounding makes a level miss (the finer sums fall short of the coarser
+// one) the last block / point of that level is taken; if no run qualifies (total = 0) the last point, as the
+// definition says.
+constexpr int kSelectThreads = 1024;
+__global__ __launch_bounds__(kSelectThreads) void seed_select_kernel(const double* __restrict__ bsum, int64_t nb,
+                                                                     const double* __restrict__ dist2, int64_t n, double u,
+                                                                     int32_t* __restrict__ chosen) {
+  __shared__ double wave_tot[kSelectThreads / 64];
+  __shared__ double excl[kSelectThreads];
+  __shared__ int first_run;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int64_t chunk = (nb + kSelectThreads - 1) / kSelectThreads;
+  const int64_t j0 = (int64_t)t * chunk;
+  int64_t j1 = j0 + chunk;
+  j1 = j1 < nb ? j1 : nb;
+  double run = 0.0;
+  for (int64_t j = j0; j < j1; ++j) run += bsum[j];
+  const double incl_w = wave_inclusive(run, lane);
+  if (lane == 63) wave_tot[wave] = incl_w;
+  if (t == 0) first_run = kSelectThreads;
+  __syncthreads();
+  double offset = 0.0, total = 0.0;
+#pragma unroll
+  for (int w = 0; w < kSelectThreads / 64; ++w) {
+    if (w < wave) offset += wave_tot[w];
+    total += wave_tot[w];
+  }
+  const double incl = incl_w + offset;
+  excl[t] = incl - run;
+  const double r = u * total;
+  if (j0 < j1 && incl > r) atomicMin(&first_run, t);
+  __syncthreads();
+  if (wave != 0) return;
+  const int tr = first_run;
+  if (tr == kSelectThreads) {  // nothing exceeds r: all distances are zero (or u * total rounded up to the total)
+    if (lane == 0) *chosen = (int32_t)(n - 1);
+    return;
+  }
+  const int64_t b0 = (int64_t)tr * chunk;
+  int64_t b1 = b0 + chunk;
+  b1 = b1 < nb ? b1 : nb;
+  double base = excl[tr];
+  bool missed = false;
+  int jb = wave_first_exceeding(bsum + b0, b1 - b0, r, &base, lane);
+  if (jb < 0) {  // the run's own sum exceeded r but its block sums, added up one by one, do not: take its last block
+    jb = (int)(b1 - b0) - 1;
+    missed = true;
+  }
+  const int64_t p0 = (b0 + jb) * kSeedPoints;
+  int64_t p1 = p0 + kSeedPoints;
+  p1 = p1 < n ? p1 : n;
+  int jp = missed ? -1 : wave_first_exceeding(dist2 + p0, p1 - p0, r, &base, lane);
+  if (jp < 0) jp = (int)(p1 - p0) - 1;
+  if (lane == 0) *chosen = (int32_t)(p0 + jp);
 }
 
 // c[j, :] = x[index[j], :]
@@ -295,37 +387,27 @@ hipError_t launch_centroid_update(const double* x, int64_t ldx, int d, int64_t n
 }
 
 size_t kmeans_seed_workspace(int64_t n) {
-  size_t scan_bytes = 0;
-  (void)hipcub::DeviceScan::InclusiveSum(nullptr, scan_bytes, (const double*)nullptr, (double*)nullptr, (int)n, nullptr);
-  scan_bytes = (scan_bytes + 255) / 256 * 256;
-  // temp | dist2[n] | cs[n]
-  return scan_bytes + (size_t)n * 16 + 1024;
+  // dist2[n] | bsum[ceil(n / 16)]
+  const size_t nb = (size_t)((n + kSeedPoints - 1) / kSeedPoints);
+  return (size_t)n * 8 + nb * 8 + 1024;
 }
 
 // Algorithm 5.  u[0 .. k-1]: host array of uniform numbers in [0, 1).  chosen: device int32[k], the indices of the
-// chosen points in the order they were drawn.
+// chosen points in the order they were drawn.  Two launches per draw.
 hipError_t launch_kmeanspp(const double* x, int64_t ldx, int d, int64_t n, int k, const double* u, void* work,
                            size_t work_bytes, int32_t* chosen, hipStream_t st) {
   if (n <= 0 || n > INT32_MAX || k < 1) return hipErrorInvalidValue;
-  size_t scan_bytes = 0;
-  hipError_t e = hipcub::DeviceScan::InclusiveSum(nullptr, scan_bytes, (const double*)nullptr, (double*)nullptr, (int)n, st);
-  if (e != hipSuccess) return e;
-  const size_t tmp = (scan_bytes + 255) / 256 * 256;
-  if (work_bytes < tmp + (size_t)n * 16) return hipErrorInvalidValue;
-  char* base = static_cast<char*>(work);
-  double* dist2 = reinterpret_cast<double*>(base + tmp);
-  double* cs = dist2 + n;
+  const int64_t nb = (n + kSeedPoints - 1) / kSeedPoints;
+  if (work_bytes < (size_t)n * 8 + (size_t)nb * 8) return hipErrorInvalidValue;
+  double* dist2 = static_cast<double*>(work);
+  double* bsum = dist2 + n;
   int64_t first = (int64_t)(u[0] * (double)n);
   first = first < n - 1 ? first : n - 1;
   hipLaunchKernelGGL(iota_fill_kernel, dim3(1), dim3(kT), 0, st, chosen, 1, (int32_t)first, 0);
   for (int i = 1; i < k; ++i) {
-    hipLaunchKernelGGL(seed_distance_kernel, dim3(blocks(n * 16)), dim3(kT), 0, st, x, ldx, d, n, chosen + (i - 1),
-                       i == 1 ? 1 : 0, dist2);
-    size_t sb = scan_bytes;
-    e = hipcub::DeviceScan::InclusiveSum(base, sb, dist2, cs, (int)n, st);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(iota_fill_kernel, dim3(1), dim3(kT), 0, st, chosen + i, 1, (int32_t)(n - 1), 0);
-    hipLaunchKernelGGL(seed_pick_kernel, dim3(blocks(n)), dim3(kT), 0, st, cs, n, u[i], chosen + i);
+    hipLaunchKernelGGL(seed_distance_kernel, dim3((unsigned)nb), dim3(kT), 0, st, x, ldx, d, n, chosen + (i - 1),
+                       i == 1 ? 1 : 0, dist2, bsum);
+    hipLaunchKernelGGL(seed_select_kernel, dim3(1), dim3(kSelectThreads), 0, st, bsum, nb, dist2, n, u[i], chosen + i);
   }
   return hipGetLastError();
 }
