@@ -128,8 +128,11 @@ def bench_kmeans(B, torch, args):
     """One step = one whole sc_kmeans call (seeding + Lloyd iterations to convergence) on points resident in HBM in
     the eigensolver's output layout.  Not the headline metric: a secondary line for the clustering step."""
     from paper_1802_04450_amd import workloads as wl
-    cid = int(args.workload.replace("cfg", ""))
-    cfg = wl.CONFIGS[cid]
+    if args.workload == "dti_like":     # the paper's largest clustering problem (Table "Datasets": 142,541 points, 500 clusters)
+        import types
+        cfg = types.SimpleNamespace(name="dti_like", n=142_541, k=500, seed=1802044500 + 31)
+    else:
+        cfg = wl.CONFIGS[int(args.workload.replace("cfg", ""))]
     n, k = cfg.n, cfg.k
     t0 = time.time()
     x = wl.embedding_like(n, k, cfg.seed + 100)
