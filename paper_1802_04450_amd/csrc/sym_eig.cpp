@@ -276,45 +276,50 @@ int SelectedEig::factor(const double* a_in, int n) {
 void SelectedEig::vectors(const int* idx, int count, double* out) const {
   const int n = n_;
   if (n <= 0 || count <= 0) return;
-  std::fill(out, out + (size_t)n * count, 0.0);
-  for (int t = 0; t < count; ++t) out[(size_t)order_[idx[t]] * count + t] = 1.0;
-  // eigenvectors of the tridiagonal matrix: Z e_j = G_1 (G_2 (... (G_N e_j))), so replay backwards; then back
-  // through the reflectors: Y = H_0 H_1 ... H_{n-3} Z.  Columns are independent: slices of them go to threads.
-  const int slices = (count >= 64 && (long)n * count >= 200000) ? std::min(omp_get_max_threads(), count / 16) : 1;
+  // Eigenvectors of the tridiagonal matrix: Z e_j = G_1 (G_2 (... (G_N e_j))), so the recorded rotations are replayed
+  // backwards on the selected unit vectors; then back through the reflectors: Y = H_0 H_1 ... H_{n-3} Z.  Columns are
+  // independent.  Every thread takes a slice of them into a buffer of its own (n x width, contiguous) and copies the
+  // result back at the end: slices of one shared array would put several threads on the same cache lines for every
+  // one of the ~n^2 rotations.
+  const int slices = (count >= 32 && (long)n * count >= 20000) ? std::min(omp_get_max_threads(), count / 8) : 1;
 #pragma omp parallel for schedule(static) num_threads(slices) if (slices > 1)
   for (int sl = 0; sl < slices; ++sl) {
     const int t0 = (int)((long)count * sl / slices), t1 = (int)((long)count * (sl + 1) / slices);
+    const int w = t1 - t0;
+    if (w <= 0) continue;
+    std::vector<double> buf((size_t)n * w, 0.0), tmp(w);
+    for (int t = t0; t < t1; ++t) buf[(size_t)order_[idx[t]] * w + (t - t0)] = 1.0;
     for (size_t r = rots_.size(); r-- > 0;) {
       const Rot& g = rots_[r];
-      double* a = out + (size_t)g.i * count;
-      double* b = a + count;
+      double* a = buf.data() + (size_t)g.i * w;
+      double* b = a + w;
       const double c = g.c, s = g.s;
 #pragma omp simd
-      for (int t = t0; t < t1; ++t) {
+      for (int t = 0; t < w; ++t) {
         const double x = a[t], y = b[t];
         a[t] = c * x + s * y;
         b[t] = c * y - s * x;
       }
     }
-    std::vector<double> tmp(count);
     for (int k = n - 3; k >= 0; --k) {
       const double beta = betas_[k];
       if (beta == 0.0) continue;
       const double* v = &vs_[(size_t)k * n];
-      for (int t = t0; t < t1; ++t) tmp[t] = 0.0;
+      for (int t = 0; t < w; ++t) tmp[t] = 0.0;
       for (int i = k + 1; i < n; ++i) {
         const double vi = v[i];
-        const double* row = out + (size_t)i * count;
+        const double* row = buf.data() + (size_t)i * w;
 #pragma omp simd
-        for (int t = t0; t < t1; ++t) tmp[t] += vi * row[t];
+        for (int t = 0; t < w; ++t) tmp[t] += vi * row[t];
       }
       for (int i = k + 1; i < n; ++i) {
         const double bv = beta * v[i];
-        double* row = out + (size_t)i * count;
+        double* row = buf.data() + (size_t)i * w;
 #pragma omp simd
-        for (int t = t0; t < t1; ++t) row[t] -= bv * tmp[t];
+        for (int t = 0; t < w; ++t) row[t] -= bv * tmp[t];
       }
     }
+    for (int i = 0; i < n; ++i) std::memcpy(out + (size_t)i * count + t0, buf.data() + (size_t)i * w, sizeof(double) * w);
   }
 }
 
