@@ -350,6 +350,17 @@ def main():
                            "fp64_tflops": stats["fam_flops"][dom] / kt / 1e12,
                            "fp64_mfma_frac": stats["fam_flops"][dom] / kt / 1e12 / FP64_MFMA_PEAK_TFLOPS,
                            "family_seconds_per_step": {B.FAMILIES[f]: fam_t[f] for f in range(6)}}
+    # the reorthogonalization GEMMs (CGS2 projection H = Q^T W and update W -= Q H, fp64 MFMA), from the survey solve in
+    # which every family was event-timed: achieved HBM rate by the byte model and fp64 rate against the matrix peak
+    reorth = {}
+    for f in (1, 2):
+        if fam_t[f] > 0:
+            reorth[B.FAMILIES[f]] = {"seconds_per_step": fam_t[f], "launches": survey["fam_launches"][f],
+                                     "hbm_gbps_algorithmic": survey["fam_bytes"][f] / fam_t[f] / 1e9,
+                                     "hbm_frac": survey["fam_bytes"][f] / fam_t[f] / 1e9 / HBM_PEAK_GBS,
+                                     "fp64_tflops": survey["fam_flops"][f] / fam_t[f] / 1e12,
+                                     "fp64_mfma_frac": survey["fam_flops"][f] / fam_t[f] / 1e12 / FP64_MFMA_PEAK_TFLOPS}
+    out["reorth"] = reorth
     if args.workload == "cfg2" and not args.no_large_spmv:
         # The benchmark workload's product moves 42 MB and is launch-latency bound; the HBM-bound figure is the one of
         # the 4,000,000-node workload, measured here in the same run (graph built on the box, resident in HBM).
