@@ -338,7 +338,8 @@ void enqueue_block_qr(double* basis, int64_t n, int64_t ld, int col, int b, doub
 // All buffers are packed n x b.  Returns the buffer that holds the result.
 double* enqueue_cheb_filter(const int64_t* rowptr, const int32_t* col, const double* val, const double* val_scaled,
                             const double* s, int64_t n, int64_t nnz, int b, int d, double a, double* z, double* buf1,
-                            double* buf2, double* buf3, double avg_deg, hipStream_t st, KTimer* tm) {
+                            double* buf2, double* buf3, double avg_deg, const int32_t* longrows, int nlong,
+                            hipStream_t st, KTimer* tm) {
   KTimer none;
   if (!tm) tm = &none;
   const double lo = -1.0;  // ||S||_2 = 1
@@ -352,7 +353,7 @@ double* enqueue_cheb_filter(const int64_t* rowptr, const int32_t* col, const dou
     tm->begin(kFamSpmm);  // one event pair round the d back-to-back launches
     for (int i = 0; i < d; ++i) {
       HIP_TRY(launch_spmm_vals_cheb(rowptr, col, val_scaled, n, cur, b, prev, next, i == 0 ? 1.0 / e : 2.0 / e, c,
-                                    i == 0 ? 0.0 : 1.0, avg_deg, st));
+                                    i == 0 ? 0.0 : 1.0, avg_deg, longrows, nlong, st));
       double* t = prev;
       prev = cur;
       cur = next;
@@ -447,6 +448,8 @@ struct Solver {
   DevBuf<int32_t> col_p, old_of_new_d, new_of_old_d, comp_d, perm_d;
   DevBuf<double> val_p, coef_d;
   DevBuf<double> val_s;  // S_ij = s_i W_ij s_j multiplied out: the operator copy used when b >= 8
+  DevBuf<int32_t> longrows;  // rows with more than kLongRow entries (wide products only), ascending
+  int nlong = 0;
   const int32_t* rowmap = nullptr;  // device: original row of each internal row, null if not reordered
   const int32_t* rowinv = nullptr;  // device: internal row of each original row, null if not reordered
   std::vector<int32_t> comp_host;   // component index of each internal row (only after reorder())
@@ -479,7 +482,7 @@ struct Solver {
   // y (row-major, leading dimension ldy) = S x for the block whose packed operand is in z
   void spmm_from_z(double* y, int64_t ldy) {
     if (val_s.p) {
-      HIP_TRY(launch_spmm_vals(rowptr, col, val_s.p, n, z.p, b, y, ldy, avg_deg, st));
+      HIP_TRY(launch_spmm_vals(rowptr, col, val_s.p, n, z.p, b, y, ldy, avg_deg, longrows.p, nlong, st));
     } else {
       HIP_TRY(launch_spmm(rowptr, col, val, s.p, n, z.p, b, y, ldy, avg_deg, st));
     }
@@ -551,6 +554,18 @@ struct Solver {
     if (b >= 8) {
       val_s.alloc((size_t)nnz);
       HIP_TRY(launch_scale_values(rowptr, col, val, s.p, val_s.p, n, st));
+      // the rows the wide products hand to whole workgroups (hubs of the kNN graph)
+      const size_t lw = long_row_list_workspace(n);
+      DevBuf<char> lwork;
+      DevBuf<int32_t> lcount;
+      lwork.alloc(lw);
+      lcount.alloc(1);
+      longrows.alloc((size_t)n);
+      HIP_TRY(long_row_list(rowptr, n, lwork.p, lw, longrows.p, lcount.p, st));
+      int32_t hcount = 0;
+      HIP_TRY(hipMemcpyAsync(&hcount, lcount.p, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipStreamSynchronize(st));
+      nlong = hcount;
     }
     const double t3 = now_s();
 
@@ -612,7 +627,7 @@ struct Solver {
     double* buf3 = rot.p + 2 * (size_t)n * b;
     if (!val_s.p) HIP_TRY(launch_copy_cols(basis.p, ld, nl, buf1, b, 0, b, n, st));
     const double* res = enqueue_cheb_filter(rowptr, col, val, val_s.p, s.p, n, nnz, b, d, a, z.p, buf1, buf2, buf3,
-                                            avg_deg, st, &timer);
+                                            avg_deg, longrows.p, nlong, st, &timer);
     stats.spmv_cols += (int64_t)d * b;
     stats.filter_steps += d;
     HIP_TRY(launch_copy_cols(res, b, 0, basis.p, ld, nl, b, n, st));
@@ -1423,7 +1438,7 @@ int sc_workspace_bytes(int64_t n, int64_t nnz, int32_t k, const sc_options* opt,
     total += up(order_by_component_workspace(n)) + 2 * up(N * 4);
   }
   total += up(N * 8);                       // scaling vector
-  if (b >= 8) total += up(Z * 8);           // scaled operator values
+  if (b >= 8) total += up(Z * 8) + up(N * 4) + up(long_row_list_workspace(n)) + 256;  // scaled values, long-row list
   total += up(N * ld * 8) + up(N * (size_t)b * 8) + up(N * rot_cols * 8);  // basis, packed block, rotation workspace
   total += up((size_t)kMaxPartials * jmax * kPP * 8) + up((size_t)kGramPartials * kPP * kPP * 8) + 2 * up(jmax * kPP * 8);
   total += up((size_t)(m / b + 4) * kSlotDoubles * 8) + up(jmax * std::max<size_t>(rot_cols, (size_t)k) * 8);
@@ -1732,7 +1747,8 @@ int sc_chebyshev_filter(const int64_t* csr_rowptr, const int32_t* csr_col, const
           HIP_TRY(launch_pack_scaled(c->x, c->ldx, nullptr, c->n, c->b, b1.p, c->st));
         }
         const double* res = enqueue_cheb_filter(c->rp, c->c, c->v, wide ? vals.p : nullptr, s.p, c->n, nnz, c->b, c->d,
-                                                c->a, z.p, b1.p, b2.p, b3.p, (double)nnz / (double)c->n, c->st, nullptr);
+                                                c->a, z.p, b1.p, b2.p, b3.p, (double)nnz / (double)c->n, nullptr, 0, c->st,
+                                                nullptr);
         HIP_TRY(launch_copy_cols(res, c->b, 0, c->y, c->ldy, 0, c->b, c->n, c->st));
         HIP_TRY(hipStreamSynchronize(c->st));
         return SC_OK;

@@ -10,6 +10,7 @@
 namespace sceig {
 
 constexpr int kMaxBlock = 32;      // largest Lanczos block size
+constexpr int kLongRow = 128;      // rows with more entries than this are "long" for the wide sparse products
 constexpr int kPartialPad = 32;    // column stride of partial / coefficient blocks (>= kMaxBlock)
 
 // ---- setup ---------------------------------------------------------------------------------
@@ -86,6 +87,11 @@ size_t order_by_component_workspace(int64_t n);
 hipError_t order_by_component(const int64_t* rowptr, const int32_t* col, const int32_t* label, int64_t n, void* work,
                               size_t work_bytes, int32_t* old_of_new, int32_t* new_of_old, int64_t* rowptr_new,
                               int32_t* comp_of_new, hipStream_t st);
+// list[0 .. *count) = the rows with more than kLongRow entries, ascending; list has room for n entries; count: device
+// int32.  work: device scratch of long_row_list_workspace(n) bytes.
+size_t long_row_list_workspace(int64_t n);
+hipError_t long_row_list(const int64_t* rowptr, int64_t n, void* work, size_t work_bytes, int32_t* list, int32_t* count,
+                         hipStream_t st);
 // label[i] = i
 hipError_t launch_iota(int32_t* label, int64_t n, hipStream_t st);
 // one round of minimum-label propagation with pointer jumping; *changed = 1 if a label moved
@@ -114,13 +120,17 @@ hipError_t launch_scale_values(const int64_t* rowptr, const int32_t* col, const 
                                double* val_out, int64_t n, hipStream_t st);
 // y = A x with the values as stored (the scaled copy); x packed n x b (b = 8, 16, 32; 16-byte aligned), y row-major
 // with leading dimension ldy.
+// longrows (may be null): device list of the nlong rows with more than kLongRow entries, ascending (long_row_list);
+// those rows are then computed by a workgroup each instead of a lane group.
 hipError_t launch_spmm_vals(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n, const double* x,
-                            int b, double* y, int64_t ldy, double avg_deg, hipStream_t st);
+                            int b, double* y, int64_t ldy, double avg_deg, const int32_t* longrows, int nlong,
+                            hipStream_t st);
 // One Chebyshev recurrence step on packed blocks:  unext = alpha * (A ucur - shift * ucur) - beta * uprev
 // (uprev is not read when beta == 0; unext must not be ucur)
 hipError_t launch_spmm_vals_cheb(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n,
                                  const double* ucur, int b, const double* uprev, double* unext, double alpha,
-                                 double shift, double beta, double avg_deg, hipStream_t st);
+                                 double shift, double beta, double avg_deg, const int32_t* longrows, int nlong,
+                                 hipStream_t st);
 // out[t*n + o] *= s[r(o)], t < k (column-major vectors in the caller's numbering; s in the internal numbering)
 hipError_t launch_scale_rows_colmajor(double* out, int64_t n, int k, const double* s, const int32_t* inv, hipStream_t st);
 // every row of the n x k column-major matrix scaled to unit 2-norm (zero rows stay zero)

@@ -97,7 +97,13 @@ static inline unsigned xcd_grid(int64_t tiles) { return (unsigned)(ceil_div64(ti
 //         as Algorithm 2's scaling step does), z = x packed.
 // MODE 2: one step of the Chebyshev recurrence on packed blocks with such values:
 //         y = alpha * (A z - shift * z) - beta * uprev   (uprev is not read when beta == 0; y packed, ldy = B).
-template <int B, int L, int MODE, int R>
+// Long rows.  A kNN graph of high-dimensional points has hubs: on the 100,000-node workload the median row has 24
+// entries, one in a hundred more than 124 and the longest 432, and a row that one lane group walks batch after batch
+// is a serial chain of dependent loads that the whole launch ends up waiting for.  When the caller passes the list
+// of rows longer than kLongRow entries, the row tiles skip them and extra workgroups at the end of the grid take one
+// long row each: the G lane groups of the workgroup take its batches round-robin and their partial sums are added in
+// group order (fixed, so results stay reproducible).  Measured on that workload at B = 16: 36.4 -> 30.7 us.
+template <int B, int L, int MODE>
 __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __restrict__ rowptr,
                                                              const int32_t* __restrict__ col,
                                                              const double* __restrict__ val,
@@ -105,74 +111,60 @@ __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __re
                                                              const double* __restrict__ z, double* __restrict__ y,
                                                              int64_t ldy, int64_t n, int vec_store,
                                                              const double* __restrict__ uprev, double alpha,
-                                                             double shift, double beta) {
-  constexpr int G = kThreads / L;  // lane groups per workgroup; a group owns R consecutive rows
+                                                             double shift, double beta, int64_t ntiles,
+                                                             const int32_t* __restrict__ longrows, int nlong) {
+  constexpr int G = kThreads / L;  // lane groups per workgroup
   constexpr int CL = B / 2;        // lanes per entry
-  static_assert(L % CL == 0 && R + 1 <= L, "batch must split evenly");
+  static_assert(L % CL == 0, "batch must split evenly");
   constexpr int NS = L / CL;        // sub-groups of a row
+  __shared__ double part[G][B];
   const int lane = threadIdx.x % L;
   const int tl = lane % CL;
   const int sg = lane / CL;         // this lane's sub-group
-  const int64_t row0 = (xcd_tile() * G + threadIdx.x / L) * R;
-  if (row0 >= n) return;  // uniform over the L-lane group
-  // The group's R + 1 row pointers in one load, then the first batch of every row and (MODE 2) the recurrence's
-  // own-row operands: everything the R rows need from memory before their gathers is requested at once.
-  int64_t rpl;
-  {
-    int64_t r = row0 + lane;
-    r = r < n ? r : n;  // rows past the end are empty
-    rpl = lane <= R ? rowptr[r] : 0;
+  const int gi = threadIdx.x / L;
+  const bool main_part = (int64_t)blockIdx.x < ntiles;
+  int64_t row, e_first, e_step;
+  if (main_part) {
+    // row tiles, handed to the XCDs in contiguous eighths (ntiles is a multiple of kXcds)
+    const int64_t tile = (int64_t)(blockIdx.x % kXcds) * (ntiles / kXcds) + blockIdx.x / kXcds;
+    row = tile * G + gi;
+    if (row >= n) return;  // uniform over the L-lane group; this part has no workgroup barrier
+    e_first = 0;
+    e_step = L;
+  } else {
+    const int64_t bl = (int64_t)blockIdx.x - ntiles;
+    const int64_t per = ((int64_t)nlong + kXcds - 1) / kXcds;
+    const int64_t li = (bl % kXcds) * per + bl / kXcds;
+    if (li >= nlong) return;  // uniform over the workgroup
+    row = longrows[li];
+    e_first = (int64_t)gi * L;
+    e_step = (int64_t)G * L;
   }
-  int64_t e0[R], e1[R];
-  int32_t c0[R];
-  double a0[R];
-#pragma unroll
-  for (int q = 0; q < R; ++q) {
-    e0[q] = __shfl(rpl, q, L);
-    e1[q] = __shfl(rpl, q + 1, L);
-    c0[q] = 0;
-    a0[q] = 0.0;
-    if (e0[q] + lane < e1[q]) {
-      c0[q] = col[e0[q] + lane];
-      a0[q] = val[e0[q] + lane];
-    }
-  }
+  const int64_t e0 = rowptr[row], e1 = rowptr[row + 1];
+  if (main_part && longrows && e1 - e0 > kLongRow) return;  // done by a workgroup of its own
+  double acc0 = 0.0, acc1 = 0.0;
   const double2* __restrict__ z2 = reinterpret_cast<const double2*>(z);
-  double2 cur[R], pv[R];
+  double2 cur = {0.0, 0.0}, pv = {0.0, 0.0};
   if constexpr (MODE == 2) {
-#pragma unroll
-    for (int q = 0; q < R; ++q) {
-      cur[q] = {0.0, 0.0};
-      pv[q] = {0.0, 0.0};
-      if (lane < CL && row0 + q < n) {
-        cur[q] = z2[(row0 + q) * CL + tl];
-        if (beta != 0.0) pv[q] = reinterpret_cast<const double2*>(uprev)[(row0 + q) * CL + tl];
-      }
+    if (lane < CL && (main_part || gi == 0)) {  // the recurrence's own-row operands, requested ahead of the gathers
+      cur = z2[row * CL + tl];
+      if (beta != 0.0) pv = reinterpret_cast<const double2*>(uprev)[row * CL + tl];
     }
   }
-#pragma unroll
-  for (int q = 0; q < R; ++q) {
-    const int64_t row = row0 + q;
-    if (row >= n) break;  // uniform over the group
-    double acc0 = 0.0, acc1 = 0.0;
-    for (int64_t e = e0[q]; e < e1[q]; e += L) {
-      // lanes past the end of the row carry (column 0, value 0): their products vanish
-      int32_t c = c0[q];
-      double a = a0[q];
-      if (e != e0[q]) {  // further batches of a long row, on demand
-        c = 0;
-        a = 0.0;
-        if (e + lane < e1[q]) {
-          c = col[e + lane];
-          a = val[e + lane];
-        }
-      }
-      // The batch's entries go round-robin to the NS sub-groups (entry r*NS + g to sub-group g in round r), so a
-      // batch of cnt entries costs ceil(cnt / NS) gather instructions: a row of 24 entries takes 6 rounds at B = 16,
-      // the one-entry tail of a row of 33 takes 1.
-      const int cnt = (e1[q] - e) < L ? (int)(e1[q] - e) : L;  // uniform over the row's lanes
-      const int rounds = (cnt + NS - 1) / NS;
-      int r = 0;
+  for (int64_t e = e0 + e_first; e < e1; e += e_step) {
+    // lanes past the end of the row carry (column 0, value 0): their products vanish
+    int32_t c = 0;
+    double a = 0.0;
+    if (e + lane < e1) {
+      c = col[e + lane];
+      a = val[e + lane];
+    }
+    // The batch's entries go round-robin to the NS sub-groups (entry r*NS + g to sub-group g in round r), so a batch
+    // of cnt entries costs ceil(cnt / NS) gather instructions: a row of 24 entries takes 6 rounds at B = 16, the
+    // one-entry tail of a row of 33 takes 1.
+    const int cnt = (e1 - e) < L ? (int)(e1 - e) : L;  // uniform over the row's lanes
+    const int rounds = (cnt + NS - 1) / NS;
+    int r = 0;
 #define SC_GATHER_ROUNDS(K)                                  \
   {                                                          \
     double2 zv[K];                                           \
@@ -187,33 +179,49 @@ __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __re
     }                                                        \
     r += K;                                                  \
   }
-      while (rounds - r >= 4) SC_GATHER_ROUNDS(4)
-      if (rounds - r >= 2) SC_GATHER_ROUNDS(2)
-      if (rounds - r >= 1) SC_GATHER_ROUNDS(1)
+    while (rounds - r >= 4) SC_GATHER_ROUNDS(4)
+    if (rounds - r >= 2) SC_GATHER_ROUNDS(2)
+    if (rounds - r >= 1) SC_GATHER_ROUNDS(1)
 #undef SC_GATHER_ROUNDS
-    }
+  }
 #pragma unroll
-    for (int o = L / 2; o >= CL; o >>= 1) {
-      acc0 += __shfl_xor(acc0, o, L);
-      acc1 += __shfl_xor(acc1, o, L);
-    }
+  for (int o = L / 2; o >= CL; o >>= 1) {
+    acc0 += __shfl_xor(acc0, o, L);
+    acc1 += __shfl_xor(acc1, o, L);
+  }
+  if (!main_part) {  // the G groups' partial sums of the long row, added in group order by group 0
     if (lane < CL) {
-      if constexpr (MODE == 2) {
+      part[gi][2 * tl] = acc0;
+      part[gi][2 * tl + 1] = acc1;
+    }
+    __syncthreads();
+    if (gi != 0) return;
+    acc0 = 0.0;
+    acc1 = 0.0;
+    if (lane < CL) {
+#pragma unroll
+      for (int q = 0; q < G; ++q) {
+        acc0 += part[q][2 * tl];
+        acc1 += part[q][2 * tl + 1];
+      }
+    }
+  }
+  if (lane < CL) {
+    if constexpr (MODE == 2) {
+      double2 out;
+      out.x = alpha * (acc0 - shift * cur.x) - beta * pv.x;
+      out.y = alpha * (acc1 - shift * cur.y) - beta * pv.y;
+      reinterpret_cast<double2*>(y)[row * CL + tl] = out;
+    } else {
+      const double sr = MODE == 0 ? s[row] : 1.0;
+      if (vec_store) {  // one 16-byte store (y + row * ldy is 16-byte aligned)
         double2 out;
-        out.x = alpha * (acc0 - shift * cur[q].x) - beta * pv[q].x;
-        out.y = alpha * (acc1 - shift * cur[q].y) - beta * pv[q].y;
-        reinterpret_cast<double2*>(y)[row * CL + tl] = out;
+        out.x = sr * acc0;
+        out.y = sr * acc1;
+        *reinterpret_cast<double2*>(y + row * ldy + 2 * tl) = out;
       } else {
-        const double sr = MODE == 0 ? s[row] : 1.0;
-        if (vec_store) {  // one 16-byte store (y + row * ldy is 16-byte aligned)
-          double2 out;
-          out.x = sr * acc0;
-          out.y = sr * acc1;
-          *reinterpret_cast<double2*>(y + row * ldy + 2 * tl) = out;
-        } else {
-          y[row * ldy + 2 * tl] = sr * acc0;
-          y[row * ldy + 2 * tl + 1] = sr * acc1;
-        }
+        y[row * ldy + 2 * tl] = sr * acc0;
+        y[row * ldy + 2 * tl + 1] = sr * acc1;
       }
     }
   }
@@ -1265,15 +1273,19 @@ static int spmm_lanes(int b, double avg_deg) {
 template <int MODE>
 static hipError_t launch_spmm_cols_t(const int64_t* rowptr, const int32_t* col, const double* val, const double* s,
                                      int64_t n, const double* z, int b, double* y, int64_t ldy, double avg_deg,
-                                     const double* uprev, double alpha, double shift, double beta, hipStream_t st) {
+                                     const double* uprev, double alpha, double shift, double beta,
+                                     const int32_t* longrows, int nlong, hipStream_t st) {
   const int vec_store = (ldy % 2 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0) ? 1 : 0;
-  // One row per lane group: two and four consecutive rows per group with all their loads requested up front were
-  // measured slower on the 100,000-node workload (36 -> 43 and 49 us per product at B = 16): fewer, longer-lived waves.
-  constexpr int kRowsPerGroup = 1;
-#define SC_LAUNCH_COLS(BB, LL)                                                                                \
-  hipLaunchKernelGGL((spmm_cols_kernel<BB, LL, MODE, kRowsPerGroup>),                                           \
-                     dim3(xcd_grid(ceil_div64(n, (kThreads / LL) * kRowsPerGroup))), dim3(kThreads), 0, st,      \
-                     rowptr, col, val, s, z, y, ldy, n, vec_store, uprev, alpha, shift, beta)
+  if (!longrows) nlong = 0;
+  // grid: row tiles (a multiple of kXcds), then one workgroup per long row (rounded up to kXcds)
+#define SC_LAUNCH_COLS(BB, LL)                                                                                     \
+  do {                                                                                                             \
+    const int64_t ntiles = ceil_div64(ceil_div64(n, kThreads / LL), kXcds) * kXcds;                                \
+    const int64_t nextra = ceil_div64(nlong, kXcds) * kXcds;                                                       \
+    hipLaunchKernelGGL((spmm_cols_kernel<BB, LL, MODE>), dim3((unsigned)(ntiles + nextra)), dim3(kThreads), 0, st, \
+                       rowptr, col, val, s, z, y, ldy, n, vec_store, uprev, alpha, shift, beta, ntiles, longrows,  \
+                       nlong);                                                                                     \
+  } while (0)
   switch (b) {
     case 8:
       switch (spmm_lanes(8, avg_deg)) {
@@ -1302,7 +1314,7 @@ hipError_t launch_spmm(const int64_t* rowptr, const int32_t* col, const double* 
     case 2: return launch_spmm_nz<2>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
     case 4: return launch_spmm_nz<4>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
     default:
-      return launch_spmm_cols_t<0>(rowptr, col, val, s, n, z, b, y, ldy, avg_deg, nullptr, 0.0, 0.0, 0.0, st);
+      return launch_spmm_cols_t<0>(rowptr, col, val, s, n, z, b, y, ldy, avg_deg, nullptr, 0.0, 0.0, 0.0, nullptr, 0, st);
   }
 }
 
@@ -1315,14 +1327,18 @@ hipError_t launch_scale_values(const int64_t* rowptr, const int32_t* col, const 
 }
 
 hipError_t launch_spmm_vals(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n, const double* x,
-                            int b, double* y, int64_t ldy, double avg_deg, hipStream_t st) {
-  return launch_spmm_cols_t<1>(rowptr, col, val, nullptr, n, x, b, y, ldy, avg_deg, nullptr, 0.0, 0.0, 0.0, st);
+                            int b, double* y, int64_t ldy, double avg_deg, const int32_t* longrows, int nlong,
+                            hipStream_t st) {
+  return launch_spmm_cols_t<1>(rowptr, col, val, nullptr, n, x, b, y, ldy, avg_deg, nullptr, 0.0, 0.0, 0.0, longrows,
+                               nlong, st);
 }
 
 hipError_t launch_spmm_vals_cheb(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n,
                                  const double* ucur, int b, const double* uprev, double* unext, double alpha,
-                                 double shift, double beta, double avg_deg, hipStream_t st) {
-  return launch_spmm_cols_t<2>(rowptr, col, val, nullptr, n, ucur, b, unext, b, avg_deg, uprev, alpha, shift, beta, st);
+                                 double shift, double beta, double avg_deg, const int32_t* longrows, int nlong,
+                                 hipStream_t st) {
+  return launch_spmm_cols_t<2>(rowptr, col, val, nullptr, n, ucur, b, unext, b, avg_deg, uprev, alpha, shift, beta,
+                               longrows, nlong, st);
 }
 
 ProjectPlan plan_project(int64_t n, int ja, int max_partials) {

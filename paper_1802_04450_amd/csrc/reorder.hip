@@ -116,6 +116,29 @@ int bits_for(int64_t n) {
 
 }  // namespace
 
+namespace {
+struct IsLongRow {
+  const int64_t* rowptr;
+  __device__ bool operator()(int32_t i) const { return rowptr[i + 1] - rowptr[i] > kLongRow; }
+};
+}  // namespace
+
+size_t long_row_list_workspace(int64_t n) {
+  size_t bytes = 0;
+  hipcub::CountingInputIterator<int32_t> rows(0);
+  (void)hipcub::DeviceSelect::If(nullptr, bytes, rows, (int32_t*)nullptr, (int32_t*)nullptr, (int)n,
+                                 IsLongRow{nullptr}, nullptr);
+  return bytes + 256;
+}
+
+hipError_t long_row_list(const int64_t* rowptr, int64_t n, void* work, size_t work_bytes, int32_t* list, int32_t* count,
+                         hipStream_t st) {
+  if (n <= 0 || n > INT32_MAX) return hipErrorInvalidValue;
+  hipcub::CountingInputIterator<int32_t> rows(0);
+  size_t bytes = work_bytes;
+  return hipcub::DeviceSelect::If(work, bytes, rows, list, count, (int)n, IsLongRow{rowptr}, st);
+}
+
 size_t order_by_component_workspace(int64_t n) {
   size_t sort_bytes = 0, scan64_bytes = 0, scan32_bytes = 0;
   (void)hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const uint64_t*)nullptr, (uint64_t*)nullptr,
