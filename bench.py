@@ -121,7 +121,7 @@ def measure_spmv(B, torch, drp, dc, dv, n, nnz):
             "frac_of_hbm_peak": spmv_gbs / HBM_PEAK_GBS,
             "gbps_algorithmic_caller_numbering": spmv_bytes / spmv_s_given / 1e9, "components": int(ncomp),
             "note": "single-vector y = S x (prescale pass + product kernel), 50 back-to-back calls timed with "
-                    "events, on the numbering the solver uses internally"}
+                    "events, on the component-contiguous numbering of sc_reorder_csr (the solver's own)"}
 
 
 def bench_kmeans(B, torch, args):

@@ -182,7 +182,10 @@ int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const 
 /*
  * The setup pass sc_laplacian_eigsh runs unless SC_FLAG_NO_REORDER is set, as a step of its own: connected
  * components of W (entries with weight exactly 0 do not connect) by label propagation on the device, and the
- * component-contiguous renumbering of the nodes (order inside a component unchanged).
+ * component-contiguous renumbering of the nodes; inside a component nodes are ordered by three levels of
+ * neighbourhood min-hash (nodes that share neighbours become neighbours; a deterministic function of the graph).
+ * The solver itself, when it works with blocks of 8 or more vectors on a graph with hubs (longest row more than
+ * three average rows), puts the row length before the min-hash levels; this call never does.
  *   rowptr_out int64[n+1], col_out int32[nnz], val_out fp64[nnz]   device, the renumbered CSR
  *   old_of_new_out int32[n]   device: original index of new node p (y_orig[old_of_new[p]] = y_new[p])
  *   ncomp_out                 host, number of connected components (may be NULL)

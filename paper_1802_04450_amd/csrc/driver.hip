@@ -385,7 +385,7 @@ constexpr int kGramPartials = 1024;
 // new row (host).  Returns the component count.
 int reorder_csr(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n, int64_t nnz,
                 int64_t* rowptr_out, int32_t* col_out, double* val_out, int32_t* old_of_new_out,
-                int32_t* new_of_old_out, std::vector<int32_t>* comp_of_new, hipStream_t st) {
+                int32_t* new_of_old_out, std::vector<int32_t>* comp_of_new, int by_length, hipStream_t st) {
   DevBuf<int32_t> label, new_of_old_own;
   DevBuf<int> flag;
   label.alloc((size_t)n);
@@ -412,8 +412,8 @@ int reorder_csr(const int64_t* rowptr, const int32_t* col, const double* val, in
   const size_t work_bytes = order_by_component_workspace(n);
   work.alloc(work_bytes);
   comp_dev.alloc((size_t)n);
-  HIP_TRY(order_by_component(rowptr, col, label.p, n, work.p, work_bytes, old_of_new_out, new_of_old_dev, rowptr_out,
-                             comp_dev.p, st));
+  HIP_TRY(order_by_component(rowptr, col, label.p, n, by_length, work.p, work_bytes, old_of_new_out, new_of_old_dev,
+                             rowptr_out, comp_dev.p, st));
   HIP_TRY(launch_permute_csr(rowptr, col, val, old_of_new_out, new_of_old_dev, rowptr_out, col_out, val_out, n, st));
   int32_t last_comp = 0;
   HIP_TRY(hipMemcpyAsync(&last_comp, comp_dev.p + (n - 1), sizeof(int32_t), hipMemcpyDeviceToHost, st));
@@ -496,7 +496,7 @@ struct Solver {
     old_of_new_d.alloc((size_t)n);
     new_of_old_d.alloc((size_t)n);
     ncomp = reorder_csr(rowptr, col, val, n, nnz, rowptr_p.p, col_p.p, val_p.p, old_of_new_d.p, new_of_old_d.p,
-                        (flags & SC_FLAG_COMPONENT_NULLSPACE) ? &comp_host : nullptr, st);
+                        (flags & SC_FLAG_COMPONENT_NULLSPACE) ? &comp_host : nullptr, b >= 8 ? 1 : 0, st);
     rowptr = rowptr_p.p;
     col = col_p.p;
     val = val_p.p;
@@ -1532,7 +1532,7 @@ int sc_reorder_csr(const int64_t* csr_rowptr, const int32_t* csr_col, const doub
         int64_t nnz = 0;
         HIP_TRY(hipMemcpyAsync(&nnz, c->rp + c->n, sizeof(int64_t), hipMemcpyDeviceToHost, c->st));
         HIP_TRY(hipStreamSynchronize(c->st));
-        const int ncomp = reorder_csr(c->rp, c->c, c->v, c->n, nnz, c->rpo, c->co, c->vo, c->oon, nullptr, nullptr, c->st);
+        const int ncomp = reorder_csr(c->rp, c->c, c->v, c->n, nnz, c->rpo, c->co, c->vo, c->oon, nullptr, nullptr, 0, c->st);
         if (c->nc) *c->nc = ncomp;
         return SC_OK;
       },

@@ -84,7 +84,10 @@ hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, i
 //   rowptr_new (n+1) = row pointers of the permuted matrix, comp_of_new[p] = component index of new row p.
 // work: device scratch of order_by_component_workspace(n) bytes.  All outputs are device arrays; n <= INT32_MAX.
 size_t order_by_component_workspace(int64_t n);
-hipError_t order_by_component(const int64_t* rowptr, const int32_t* col, const int32_t* label, int64_t n, void* work,
+// by_length != 0: on a graph with hubs (longest row > 3 average rows) the rows of a component are ordered by decreasing
+// length first (for the wide sparse products), then by the min-hash levels.
+hipError_t order_by_component(const int64_t* rowptr, const int32_t* col, const int32_t* label, int64_t n, int by_length,
+                              void* work,
                               size_t work_bytes, int32_t* old_of_new, int32_t* new_of_old, int64_t* rowptr_new,
                               int32_t* comp_of_new, hipStream_t st);
 // list[0 .. *count) = the rows with more than kLongRow entries, ascending; list has room for n entries; count: device

@@ -20,6 +20,11 @@
 // on the 3-D workload: component order 771, one level 106, two 66, three 57; reverse Cuthill-McKee 64).
 // The three values are re-hashed, cut to w = (64 - bits(n)) / 3 bits each and packed under the label into one 64-bit
 // key: only their equality matters, and a collision merely interleaves two groups.
+// On request (by_length: the solver asks for it when it will use the wide products), graphs with hubs (the longest
+// row more than three average rows: kNN graphs of high-dimensional points, where the
+// neighbourhoods of neighbours hardly overlap and no order helps the gathers) get the row length in place of the
+// three-hop value: rows of similar length become neighbours, so the rows that share a wave of the wide products do
+// the same number of trips, and the long rows of a component sit together.
 // The sort is a stable LSD radix sort on that key: ties keep the original node order, so the numbering is a
 // deterministic function of the graph.
 #include <hip/hip_runtime.h>
@@ -69,16 +74,42 @@ __global__ __launch_bounds__(kT) void minhash_level_kernel(const int64_t* __rest
   if (lane == 0) hout[row] = m;
 }
 
-// key[i] = label << 3w | g(h3) << 2w | g(h2) << w | g(h1), g = the top w bits of a re-hash; ident[i] = i
+// *maxlen = the largest number of entries of a row (the slot must hold 0 on entry)
+__global__ __launch_bounds__(kT) void max_row_len_kernel(const int64_t* __restrict__ rowptr, int64_t n,
+                                                         int* __restrict__ maxlen) {
+  int m = 0;
+  for (int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x; i < n; i += (int64_t)gridDim.x * kT) {
+    const int len = (int)(rowptr[i + 1] - rowptr[i]);
+    m = len > m ? len : m;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const int other = __shfl_xor(m, o, 64);
+    m = other > m ? other : m;
+  }
+  if (threadIdx.x % 64 == 0 && m > 0) atomicMax(maxlen, m);
+}
+
+// key[i] = label << 3w | f << 2w | g(h2) << w | g(h1), g = the top w bits of a re-hash; ident[i] = i.
+// f = g(h3), or, if by_length is set and the graph has hubs (longest row > 3 average rows),
+// 2^w - 1 - min(row length, 2^w - 1): rows of a component then come in order of decreasing length.
 __global__ __launch_bounds__(kT) void pack_key_kernel(const int32_t* __restrict__ label, const uint32_t* __restrict__ h1,
                                                       const uint32_t* __restrict__ h2, const uint32_t* __restrict__ h3,
-                                                      int w, int64_t n, uint64_t* __restrict__ key,
+                                                      const int64_t* __restrict__ rowptr, const int* __restrict__ maxlen,
+                                                      int by_length, int w, int64_t n, uint64_t* __restrict__ key,
                                                       int32_t* __restrict__ ident) {
   const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (i >= n) return;
   const int sh = 32 - w;
-  const uint64_t g1 = hash32(h1[i]) >> sh, g2 = hash32(h2[i]) >> sh, g3 = hash32(h3[i]) >> sh;
-  key[i] = ((uint64_t)(uint32_t)label[i] << (3 * w)) | (g3 << (2 * w)) | (g2 << w) | g1;
+  const bool hubs = by_length && (int64_t)(*maxlen) * n > 3 * rowptr[n];
+  const uint64_t g1 = hash32(h1[i]) >> sh, g2 = hash32(h2[i]) >> sh;
+  uint64_t f = hash32(h3[i]) >> sh;
+  if (hubs) {
+    const int64_t cap = ((int64_t)1 << w) - 1;
+    const int64_t len = rowptr[i + 1] - rowptr[i];
+    f = (uint64_t)(cap - (len < cap ? len : cap));
+  }
+  key[i] = ((uint64_t)(uint32_t)label[i] << (3 * w)) | (f << (2 * w)) | (g2 << w) | g1;
   ident[i] = (int32_t)i;
 }
 
@@ -154,7 +185,8 @@ size_t order_by_component_workspace(int64_t n) {
   return tmp + (size_t)n * (8 + 8 + 8 + 8 + 4 + 12) + 1024;
 }
 
-hipError_t order_by_component(const int64_t* rowptr, const int32_t* col, const int32_t* label, int64_t n, void* work,
+hipError_t order_by_component(const int64_t* rowptr, const int32_t* col, const int32_t* label, int64_t n, int by_length,
+                              void* work,
                               size_t work_bytes, int32_t* old_of_new, int32_t* new_of_old, int64_t* rowptr_new,
                               int32_t* comp_of_new, hipStream_t st) {
   if (n <= 0) return hipSuccess;
@@ -170,7 +202,7 @@ hipError_t order_by_component(const int64_t* rowptr, const int32_t* col, const i
   size_t tmp = sort_bytes > scan64_bytes ? sort_bytes : scan64_bytes;
   tmp = tmp > scan32_bytes ? tmp : scan32_bytes;
   tmp = (tmp + 255) / 256 * 256;
-  if (work_bytes < tmp + (size_t)n * 48) return hipErrorInvalidValue;
+  if (work_bytes < tmp + (size_t)n * 48 + 64) return hipErrorInvalidValue;
   char* base = static_cast<char*>(work);
   void* temp = base;
   uint64_t* key = reinterpret_cast<uint64_t*>(base + tmp);
@@ -189,7 +221,13 @@ hipError_t order_by_component(const int64_t* rowptr, const int32_t* col, const i
   // labels are node indices: bits_for(n) bits above three hash fields of w bits each
   const int lb = bits_for(n);
   const int w = (64 - lb) / 3 < 16 ? (64 - lb) / 3 : 16;
-  hipLaunchKernelGGL(pack_key_kernel, dim3(blocks(n)), dim3(kT), 0, st, label, h1, h2, h3, w, n, key, ident);
+  int* maxlen = reinterpret_cast<int*>(h3 + n);  // in the spare bytes at the end of the workspace
+  hipError_t em = hipMemsetAsync(maxlen, 0, sizeof(int), st);
+  if (em != hipSuccess) return em;
+  hipLaunchKernelGGL(max_row_len_kernel, dim3((unsigned)(blocks(n) < 1024 ? blocks(n) : 1024)), dim3(kT), 0, st, rowptr, n,
+                     maxlen);
+  hipLaunchKernelGGL(pack_key_kernel, dim3(blocks(n)), dim3(kT), 0, st, label, h1, h2, h3, rowptr, maxlen, by_length,
+                     w, n, key, ident);
   size_t sb = sort_bytes;
   e = hipcub::DeviceRadixSort::SortPairs(temp, sb, key, key_sorted, ident, old_of_new, (int)n, 0, 3 * w + lb, st);
   if (e != hipSuccess) return e;
