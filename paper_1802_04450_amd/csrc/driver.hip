@@ -1746,9 +1746,23 @@ int sc_chebyshev_filter(const int64_t* csr_rowptr, const int32_t* csr_col, const
           HIP_TRY(launch_pack_scaled(c->x, c->ldx, s.p, c->n, c->b, z.p, c->st));
           HIP_TRY(launch_pack_scaled(c->x, c->ldx, nullptr, c->n, c->b, b1.p, c->st));
         }
+        DevBuf<int32_t> longrows, lcount;
+        int nlong = 0;
+        if (wide) {  // the rows the wide product hands to whole workgroups, as in the solver's setup
+          const size_t lw = long_row_list_workspace(c->n);
+          DevBuf<char> lwork;
+          lwork.alloc(lw);
+          lcount.alloc(1);
+          longrows.alloc((size_t)c->n);
+          HIP_TRY(long_row_list(c->rp, c->n, lwork.p, lw, longrows.p, lcount.p, c->st));
+          int32_t hcount = 0;
+          HIP_TRY(hipMemcpyAsync(&hcount, lcount.p, sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
+          HIP_TRY(hipStreamSynchronize(c->st));
+          nlong = hcount;
+        }
         const double* res = enqueue_cheb_filter(c->rp, c->c, c->v, wide ? vals.p : nullptr, s.p, c->n, nnz, c->b, c->d,
-                                                c->a, z.p, b1.p, b2.p, b3.p, (double)nnz / (double)c->n, nullptr, 0, c->st,
-                                                nullptr);
+                                                c->a, z.p, b1.p, b2.p, b3.p, (double)nnz / (double)c->n,
+                                                wide ? longrows.p : nullptr, nlong, c->st, nullptr);
         HIP_TRY(launch_copy_cols(res, c->b, 0, c->y, c->ldy, 0, c->b, c->n, c->st));
         HIP_TRY(hipStreamSynchronize(c->st));
         return SC_OK;

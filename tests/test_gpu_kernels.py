@@ -224,10 +224,14 @@ def test_chebyshev_filter(B, ncols):
     wide blocks on the scaled copy with the recurrence fused into the product)."""
     from oracle import blockops
     rng = np.random.default_rng(40 + ncols)
+    # complete(70) gives rows of 69 entries (three batches of a 32-lane group); complete(300) and the star's centre
+    # give rows of 299 and 500 entries, beyond the 128 above which the wide products hand a row to a whole workgroup
+    star = wl.symmetric_from_edges(np.zeros(500, dtype=np.int64), np.arange(1, 501), np.linspace(0.5, 1.5, 500), 501)
     g = wl.disjoint_union(wl.random_weighted_connected(700, 9000, 5), wl.ring(257), wl.complete(70),
-                          wl.random_weighted_connected(333, 700, 6))
+                          wl.random_weighted_connected(333, 700, 6), wl.complete(300), star)
     g = wl.relabel(g, rng.permutation(g[3]))
     rp, c, v, n = g
+    assert np.sum(np.diff(rp) > 128) == 301
     x = rng.standard_normal((n, ncols))
     a, d = 0.4, 12
     want = blockops.chebyshev_filter(rp, c, v, x, a, d)
