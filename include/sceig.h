@@ -166,18 +166,28 @@ int sc_degree_scaling(const int64_t* csr_rowptr, const int32_t* csr_col, const d
 /*
  * The sparse product of Algorithm 3's loop body with the degree scaling fused in:
  *   Y = diag(s) W diag(s) X   for an n x ncols block, ncols in {1,2,4,8,16,32}.
- *   s     device fp64[n] (from sc_degree_scaling)
+ *   s     device fp64[n] (from sc_degree_scaling); or NULL: csr_val then holds the scaled operator S_ij = s_i W_ij s_j
+ *         (from sc_scale_operator, the materialised form of Algorithm 2 step 3) and Y = S X is one launch with no
+ *         scaling pass; x is gathered in place when it is packed (ldx == ncols) and 16-byte aligned
  *   x     device, row-major n x ncols, leading dimension ldx >= ncols
  *   y     device, row-major n x ncols, leading dimension ldy >= ncols; must not alias x
  *   work  device fp64[n*ncols] scratch (holds diag(s) X packed), 16-byte aligned (else SC_EINVAL); may be NULL,
- *         then it is allocated and freed inside the call
- * Exception to the general rule: when `work` is given this call only ENQUEUES on `stream` and returns without
- * synchronising (products can be issued back to back); with work == NULL it returns after completion.
+ *         then it is allocated and freed inside the call (nothing is needed when x is gathered in place)
+ * Exception to the general rule: when `work` is given, or x is gathered in place, this call only ENQUEUES on `stream`
+ * and returns without synchronising (products can be issued back to back); else it returns after completion.
  * CSR columns are NOT range-checked here (sc_validate_csr does that).
  */
 int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, const double* s,
                        int64_t n, const double* x, int64_t ldx, double* y, int64_t ldy, int32_t ncols, double* work,
                        void* stream);
+
+/*
+ * Algorithm 2 step 3 (ScaleElements) in its symmetric form: val_out[e] = s_i * csr_val[e] * s_j for entry e = (i, j).
+ * The two factors are applied in index order, so (i, j) and (j, i) get the same rounding and the copy is exactly
+ * symmetric when W is.  val_out (device fp64[nnz]) may be csr_val itself.
+ */
+int sc_scale_operator(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, const double* s,
+                      int64_t n, double* val_out, void* stream);
 
 /*
  * The setup pass sc_laplacian_eigsh runs unless SC_FLAG_NO_REORDER is set, as a step of its own: connected

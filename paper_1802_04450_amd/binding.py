@@ -28,7 +28,7 @@ FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_reorder_csr", "sc_cgs2",
            "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version", "sc_release_cache",
            "sc_chebyshev_filter", "sc_kmeanspp", "sc_kmeans_lloyd", "sc_kmeans", "sc_edge_similarity",
-           "sc_coo_to_csr", "sc_workspace_bytes"]
+           "sc_coo_to_csr", "sc_workspace_bytes", "sc_scale_operator"]
 
 
 class ScOptions(ctypes.Structure):
@@ -89,6 +89,7 @@ def lib() -> ctypes.CDLL:
                                             ctypes.POINTER(ScStats)]
         _lib.sc_workspace_bytes.argtypes = [i64, i64, i32, ctypes.POINTER(ScOptions), ctypes.POINTER(ctypes.c_size_t)]
         _lib.sc_degree_scaling.argtypes = [vp, vp, vp, i64, vp, vp, vp]
+        _lib.sc_scale_operator.argtypes = [vp, vp, vp, vp, i64, vp, vp]
         _lib.sc_spmm_normalized.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, i64, i32, vp, vp]
         _lib.sc_validate_csr.argtypes = [vp, vp, i64, vp]
         _lib.sc_reorder_csr.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp]
@@ -189,6 +190,17 @@ def sc_degree_scaling(rowptr, col, val, want_degrees: bool = True):
     return d, s
 
 
+def sc_scale_operator(rowptr, col, val, s):
+    """Algorithm 2 step 3, symmetric form: a new value array S_ij = s_i W_ij s_j."""
+    import torch
+    n = rowptr.numel() - 1
+    out = torch.empty_like(val)
+    with torch.cuda.device(rowptr.device):
+        code = lib().sc_scale_operator(_ptr(rowptr), _ptr(col), _ptr(val), _ptr(s), n, _ptr(out), _stream())
+    _check(code)
+    return out
+
+
 def sc_validate_csr(rowptr, col) -> int:
     import torch
     n = rowptr.numel() - 1
@@ -212,7 +224,9 @@ def sc_reorder_csr(rowptr, col, val):
 
 def sc_spmm_normalized(rowptr, col, val, s, x, y=None, work=None):
     """x: (n, ncols) row-major device tensor (a 1-D tensor is one column).  Returns y of the same shape.
-    With `work` given the call only enqueues on the current stream (synchronise before reading y on the host)."""
+    s=None: `val` holds the scaled operator from sc_scale_operator and y = S x is one launch.
+    With `work` given (or s=None and a packed x) the call only enqueues on the current stream (synchronise before
+    reading y on the host)."""
     import torch
     n = rowptr.numel() - 1
     x2 = x.reshape(n, -1)

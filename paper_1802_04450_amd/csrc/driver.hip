@@ -1542,7 +1542,7 @@ int sc_reorder_csr(const int64_t* csr_rowptr, const int32_t* csr_col, const doub
 int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, const double* s,
                        int64_t n, const double* x, int64_t ldx, double* y, int64_t ldy, int32_t ncols, double* work,
                        void* stream) {
-  if (!csr_rowptr || !csr_col || !csr_val || !s || !x || !y || n < 0) return SC_EINVAL;
+  if (!csr_rowptr || !csr_col || !csr_val || !x || !y || n < 0) return SC_EINVAL;
   if (!supported_block(ncols) || ldx < ncols || ldy < ncols) return SC_EDOMAIN;
   if (reinterpret_cast<uintptr_t>(work) % 16 != 0) return SC_EINVAL;  // the product gathers 16-byte pieces of it
   if (n == 0) return SC_OK;
@@ -1564,8 +1564,11 @@ int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const 
       [](void* p) {
         Ctx* c = static_cast<Ctx*>(p);
         DevBuf<double> own;
+        // s == null: the values are the scaled operator and the operand needs no scaling; if it is already packed
+        // (and 16-byte aligned, which the wide products' gathers need) it is gathered from where it is
+        const bool in_place = !c->s && c->ldx == c->b && reinterpret_cast<uintptr_t>(c->x) % 16 == 0;
         double* z = c->work;
-        if (!z) {
+        if (!z && !in_place) {
           own.alloc((size_t)c->n * c->b);
           z = own.p;
         }
@@ -1581,10 +1584,32 @@ int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const 
           last_n = c->n;
           last_nnz = nnz;
         }
-        HIP_TRY(launch_pack_scaled(c->x, c->ldx, c->s, c->n, c->b, z, c->st));
-        HIP_TRY(launch_spmm(c->rp, c->c, c->v, c->s, c->n, z, c->b, c->y, c->ldy, (double)last_nnz / (double)c->n,
-                            c->st));
+        if (!in_place) HIP_TRY(launch_pack_scaled(c->x, c->ldx, c->s, c->n, c->b, z, c->st));
+        HIP_TRY(launch_spmm(c->rp, c->c, c->v, c->s, c->n, in_place ? c->x : z, c->b, c->y, c->ldy,
+                            (double)last_nnz / (double)c->n, c->st));
         if (own.p) HIP_TRY(hipStreamSynchronize(c->st));  // the internal scratch is freed on return
+        return SC_OK;
+      },
+      &ctx);
+}
+
+int sc_scale_operator(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, const double* s,
+                      int64_t n, double* val_out, void* stream) {
+  if (!csr_rowptr || !csr_col || !csr_val || !s || !val_out || n < 0) return SC_EINVAL;
+  if (n == 0) return SC_OK;
+  struct Ctx {
+    const int64_t* rp;
+    const int32_t* c;
+    const double *v, *s;
+    int64_t n;
+    double* out;
+    hipStream_t st;
+  } ctx{csr_rowptr, csr_col, csr_val, s, n, val_out, reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        HIP_TRY(launch_scale_values(c->rp, c->c, c->v, c->s, c->out, c->n, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
         return SC_OK;
       },
       &ctx);

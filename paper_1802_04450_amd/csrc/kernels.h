@@ -26,6 +26,7 @@ hipError_t launch_degree_scaling(const int64_t* rowptr, const double* val, int64
 hipError_t launch_pack_scaled(const double* x, int64_t ldx, const double* s, int64_t n, int b, double* z,
                               hipStream_t st);
 // y[i*ldy + t] = s[i] * sum_e val[e] * z[col[e]*b + t]  over the entries e of row i; b in {1,2,4,8,16,32}.
+// s == null: no row scaling (the values are the scaled operator S_ij and z = x).
 // avg_deg steers the lanes-per-row choice of the b <= 4 kernels.
 hipError_t launch_spmm(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
                        const double* z, int b, double* y, int64_t ldy, double avg_deg, hipStream_t st);

@@ -277,7 +277,7 @@ __global__ __launch_bounds__(kThreads) void spmm_nz_kernel(const int64_t* __rest
     for (int q = 0; q < B; ++q) acc[q] += __shfl_xor(acc[q], o, L);
   }
   if (t == 0) {
-    const double sr = s[row];
+    const double sr = s ? s[row] : 1.0;
 #pragma unroll
     for (int q = 0; q < B; ++q) y[row * ldy + q] = sr * acc[q];
   }
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(kThreads) void spmm_stream_kernel(const int64_t* __
     for (int q = 0; q < B; ++q) acc[q] += __shfl_xor(acc[q], o, LR);
   }
   if (lane == 0 && rl < nrows) {
-    const double sr = s[r0 + rl];
+    const double sr = s ? s[r0 + rl] : 1.0;
 #pragma unroll
     for (int q = 0; q < B; ++q) y[(r0 + rl) * ldy + q] = sr * acc[q];
   }
@@ -384,7 +384,7 @@ __global__ __launch_bounds__(kThreads) void spmv_tile_kernel(const int64_t* __re
   int64_t r = row0 + lane;
   r = r < n ? r : n;  // rows past the end are empty: their pointers equal rowptr[n]
   const int64_t rpv = lane <= RW ? rowptr[r] : 0;
-  const double sv = (lane < RW && row0 + lane < n) ? s[row0 + lane] : 0.0;
+  const double sv = (lane < RW && row0 + lane < n) ? (s ? s[row0 + lane] : 1.0) : 0.0;  // s == null: values are S
   const int64_t e0 = readlane64(rpv, 0);
   const int len = (int)(readlane64(rpv, RW) - e0);
   const bool mine = sl == 0 && row0 + g < n;
@@ -1314,6 +1314,8 @@ hipError_t launch_spmm(const int64_t* rowptr, const int32_t* col, const double* 
     case 2: return launch_spmm_nz<2>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
     case 4: return launch_spmm_nz<4>(rowptr, col, val, s, n, z, y, ldy, avg_deg, st);
     default:
+      if (!s) return launch_spmm_cols_t<1>(rowptr, col, val, nullptr, n, z, b, y, ldy, avg_deg, nullptr, 0.0, 0.0, 0.0,
+                                           nullptr, 0, st);
       return launch_spmm_cols_t<0>(rowptr, col, val, s, n, z, b, y, ldy, avg_deg, nullptr, 0.0, 0.0, 0.0, nullptr, 0, st);
   }
 }

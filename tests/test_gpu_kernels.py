@@ -98,6 +98,37 @@ def test_spmm_normalized(B, graphs, ncols):
         assert torch.equal(y2, yb[:, :ncols])
 
 
+@pytest.mark.parametrize("ncols", [1, 2, 8, 16])
+def test_scaled_operator_and_its_product(B, graphs, ncols):
+    """Algorithm 2 step 3 as a step of its own: the scaled values are s_i w_ij s_j entry by entry and exactly symmetric,
+    and the product with them (no scaling vector, operand gathered in place) is the oracle's S x."""
+    rng = np.random.default_rng(100 + ncols)
+    for name, (rp, c, v, n) in graphs.items():
+        drp, dc, dv = B.csr_to_device(rp, c, v)
+        _, s = B.sc_degree_scaling(drp, dc, dv)
+        vs = B.sc_scale_operator(drp, dc, dv, s)
+        s0 = laplacian.inv_sqrt_degrees(rp, c, v)
+        rows = np.repeat(np.arange(n), np.diff(rp))
+        want = s0[rows] * v * s0[c]
+        got = vs.cpu().numpy()
+        assert np.max(np.abs(got - want)) <= 4e-16 * np.max(np.abs(want)), name
+        from scipy.sparse import csr_matrix
+        a = csr_matrix((got, c, rp), shape=(n, n))
+        assert abs(a - a.T).max() == 0.0, name                     # the same rounding for (i, j) and (j, i)
+        x = rng.standard_normal((n, ncols))
+        dx = torch.from_numpy(x).cuda()
+        y = B.sc_spmm_normalized(drp, dc, vs, None, dx)
+        torch.cuda.synchronize()
+        y0 = laplacian.apply_s(rp, c, v, x)
+        assert np.max(np.abs(y.cpu().numpy() - y0)) <= 1e-13 * (np.abs(y0).max() + 1e-300), (name, ncols)
+        # an operand inside a wider buffer is packed first (no scaling), same answer
+        xb = torch.zeros((n, ncols + 3), dtype=torch.float64, device="cuda")
+        xb[:, :ncols] = dx
+        y2 = B.sc_spmm_normalized(drp, dc, vs, None, xb[:, :ncols])
+        torch.cuda.synchronize()
+        assert torch.equal(y2, y), (name, ncols)
+
+
 @pytest.mark.parametrize("shift", [0, 1, 2, 3])
 def test_single_vector_product_on_offset_arrays(B, graphs, shift):
     """The single-vector product clamps its stream loads to the tile instead of predicating them: the same answer from
