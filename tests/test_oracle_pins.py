@@ -446,3 +446,37 @@ def test_similarity_oracle_pins():
     np.testing.assert_array_equal(a, [[0, 7, 0], [7, 0, 0], [0, 0, 5]])
     a = sim.coo_to_dense([0, 0, 2, 1], [1, 1, 2, 0], [1.0, 2.0, 5.0, 4.0], 3, symmetrize=False)
     np.testing.assert_array_equal(a, [[0, 3, 0], [4, 0, 0], [0, 0, 5]])
+
+
+def test_knn_oracle_pins():
+    """Section III-A's k-nearest-neighbour graph: points on a line with known neighbours and the tie rule, the
+    library's KD-tree on random points, and the union rule against a dense adjacency matrix."""
+    from scipy.spatial import cKDTree
+    from oracle import knn
+    # points 0, 1, 2, 3, 10 on a line: neighbours by hand; equal distances go to the lower index
+    x = np.array([[0.0], [1.0], [2.0], [3.0], [10.0]])
+    idx, dist = knn.knn_bruteforce(x, 2)
+    np.testing.assert_array_equal(idx, [[1, 2], [0, 2], [1, 3], [2, 1], [3, 2]])
+    np.testing.assert_allclose(dist, [[1, 2], [1, 1], [1, 1], [1, 2], [7, 8]], rtol=0, atol=0)
+    # random points in 5 dimensions against the library's exact KD-tree search (no ties in random data)
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((400, 5))
+    idx, dist = knn.knn_bruteforce(x, 7)
+    td, ti = cKDTree(x).query(x, k=8)
+    np.testing.assert_array_equal(idx, ti[:, 1:])
+    np.testing.assert_allclose(dist, td[:, 1:], rtol=1e-13)
+    assert np.all(np.diff(dist, axis=1) >= 0) and np.all(idx != np.arange(400)[:, None])
+    # union rule: dense OR of the directed relation, upper triangle
+    adj = np.zeros((400, 400), dtype=bool)
+    adj[np.repeat(np.arange(400), 7), idx.reshape(-1)] = True
+    und = adj | adj.T
+    eu, ev = np.nonzero(np.triu(und, 1))
+    u, v, w = knn.knn_union_pairs(idx, dist)
+    np.testing.assert_array_equal(u, eu)
+    np.testing.assert_array_equal(v, ev)
+    np.testing.assert_allclose(w, np.sqrt(((x[u] - x[v]) ** 2).sum(axis=1)), rtol=1e-13)
+    assert len(u) > 400 * 7 / 2 and len(u) < 400 * 7          # some pairs are mutual, not all
+    # Gaussian weights: the similarity oracle's exponential-decay measure on the same pairs
+    from oracle import similarity as sim
+    _, _, g = knn.knn_union_pairs(idx, dist, sigma=0.8)
+    np.testing.assert_allclose(g, sim.edge_similarity(x, u, v, sim.EXP_DECAY, 0.8), rtol=1e-12)
