@@ -267,6 +267,67 @@ def bench_similarity(B, torch, args):
     print(json.dumps(out), flush=True)
 
 
+def bench_knn(B, torch, args):
+    """One step = points -> exact k nearest neighbours -> undirected edge list with Gaussian weights -> symmetric CSR
+    (Section III-A's k-nearest-neighbour graph), on the points of the benchmark workload, resident in HBM."""
+    from paper_1802_04450_amd import workloads as wl
+    key = int(args.workload[3:]) if args.workload.startswith("cfg") else 2
+    cfg = wl.CONFIGS[key]
+    x, _ = wl.mixture_points(cfg)
+    n, d = x.shape
+    k = cfg.k_nn
+    dx = torch.as_tensor(x, device="cuda")
+
+    def step():
+        idx, dist = B.sc_knn_search(dx, k)
+        sigma = float(dist.median())          # the workloads' bandwidth: the median neighbour distance
+        eu, ev, w = B.sc_knn_union_pairs(idx, dist, sigma)
+        return B.sc_coo_to_csr(eu, ev, w, n, True)
+
+    for _ in range(max(1, args.warmup)):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        rp, co, vo = step()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(1, min(5, args.steps))
+    e0.record()
+    for _ in range(reps):
+        B.sc_knn_search(dx, k)
+    e1.record()
+    torch.cuda.synchronize()
+    t_knn = e0.elapsed_time(e1) * 1e-3 / reps
+    # the search is arithmetic: one subtraction and one multiply-add per coordinate of every ordered pair of points,
+    # 3 flops, against the fp64 vector peak (256 CUs x 64 lanes x 2 flops x 2.4 GHz = 78.6 TFLOP/s); a subtraction
+    # counts one flop of the two its issue slot could hold, so a loop of nothing else tops out at 3/4 of that
+    flops = 3.0 * n * n * d
+    out = {"metric": "kNN similarity graph s (exact k nearest neighbours + union edge list + symmetric CSR)",
+           "value": sec, "unit": "s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3,
+           "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+           "config": {"workload": f"{cfg.name} points: n={n}, d={d}, k_nn={k}, nnz={int(rp[-1])}"},
+           "roofline": {"bound": "alu", "kernel": "knn_search_kernel (one sc_knn_search call, with the row padding)",
+                        "achieved": flops / t_knn / 1e12, "peak": 78.6, "unit": "TFLOP/s",
+                        "frac": flops / t_knn / 1e12 / 78.6, "traffic": None, "call_ms": t_knn * 1e3}}
+    if not args.no_cpu_baseline:
+        from oracle import knn as oknn
+        ns = max(2 * k, min(n, int(2.0e9 / (n * d))))       # queries whose n x d difference arrays take ~10-20 s
+        t0 = time.time()
+        ids = np.arange(n)
+        for i in range(ns):                                   # the oracle's loop body on the first ns queries
+            diff = x - x[i]
+            d2 = (diff * diff).sum(axis=1)
+            d2[i] = np.inf
+            np.lexsort((ids, d2))[:k]
+        dt = time.time() - t0
+        out["cpu_baseline"] = {"value": dt * n / ns, "unit": "s", "cores": 1, "kind": "oracle",
+                               "sample": f"the oracle's per-query search (all n distances, then the k smallest) for the "
+                                         f"first {ns} of {n} queries took {dt:.2f}s; scaled by n/{ns} (search only)"}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -290,6 +351,9 @@ def main():
     ap.add_argument("--similarity", action="store_true",
                     help="the graph-construction step (Algorithm 1 + the COO to CSR conversion of Algorithm 2) on "
                          "synthetic data of the shape of the paper's DTI input; prints its own JSON line")
+    ap.add_argument("--knn", action="store_true",
+                    help="the k-nearest-neighbour graph construction (Section III-A) on the points of --workload "
+                         "(default config 2: n = 100,000, d = 32, k_nn = 20); prints its own JSON line")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device copy 10 times (calibration of the HBM traffic counters)")
     args = ap.parse_args()
@@ -317,6 +381,9 @@ def main():
         return
     if args.similarity:
         bench_similarity(B, torch, args)
+        return
+    if args.knn:
+        bench_knn(B, torch, args)
         return
     cfg, graph = build_workload(args.workload)
     rp, c, v, n = graph

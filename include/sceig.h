@@ -350,6 +350,37 @@ int sc_edge_similarity(const double* x, int64_t ldx, int64_t n, int32_t d, const
                        int64_t nedges, int32_t measure, double sigma, double* val_out, void* stream);
 
 /*
+ * k-nearest-neighbour search for the k-nearest-neighbour similarity graph (Section III-A: x_i and x_j are connected
+ * if either is among the k nearest of the other; k_nn is unrelated to the number of clusters).  Exact, by Euclidean
+ * distance, brute force: the squared distance is the plain sum of squared coordinate differences in fp64.
+ *   x         device fp64, n x d row-major with leading dimension ldx >= d (read only)
+ *   idx_out   device int32[n * k_nn]: row i = the k_nn points nearest to x_i other than i, nearest first; equal
+ *             distances are ordered by index, so the result is unique
+ *   dist_out  device fp64[n * k_nn]: their Euclidean distances
+ * 2 <= n <= 2^31 - 1, d >= 1, 1 <= k_nn <= n - 1, and 128 * (8 * ceil(d / 8) * 8 + 12 * k_nn) bytes must fit the
+ * LDS of a workgroup (160 KB: e.g. d <= 128 with k_nn <= 20), else SC_EDOMAIN.  The library allocates n * 8 *
+ * ceil(d / 8) * 8 bytes of scratch for the call.  Returns after the work on `stream` is done.
+ */
+int sc_knn_search(const double* x, int64_t ldx, int64_t n, int32_t d, int32_t k_nn, int32_t* idx_out, double* dist_out,
+                  void* stream);
+
+/*
+ * The undirected edges of the k-nearest-neighbour graph (Section III-A's "either ... or": the union of the directed
+ * neighbour relation), each once, in the form sc_coo_to_csr takes with symmetrize = 1.
+ *   idx, dist  device, n x k_nn neighbour lists as sc_knn_search writes them (entries < 0 or >= n and i's own index
+ *              are skipped, a neighbour listed twice in a row counts once)
+ *   sigma      0: val = the listed distance; > 0: val = exp(-dist^2 / (2 sigma^2)), the Gaussian weight of Section
+ *              IV-A (weights that underflow to 0 are kept: dropping them is the caller's choice)
+ *   edge_u, edge_v, val_out  device, room for n * k_nn entries; the first *npairs_out are the edges with
+ *              edge_u < edge_v, grouped by the row whose list emitted them (the lower index, or the higher one if
+ *              only its list holds the pair), in list order; what lies beyond is unspecified
+ *   npairs_out host
+ * n * k_nn <= 2^31 - 1, k_nn >= 1, sigma >= 0 (else SC_EDOMAIN).
+ */
+int sc_knn_union_pairs(const int32_t* idx, const double* dist, int64_t n, int32_t k_nn, double sigma, int32_t* edge_u,
+                       int32_t* edge_v, double* val_out, int64_t* npairs_out, void* stream);
+
+/*
  * Coordinate format to CSR (Algorithm 2 step 4), on the device.
  *   row, col, val   device, nnz_in entries (r, c, w) in any order
  *   symmetrize      nonzero: every listed entry with r != c also stands for (c, r, w) - the list names each undirected

@@ -27,7 +27,7 @@ FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 
 EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_reorder_csr", "sc_cgs2",
            "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version", "sc_release_cache",
-           "sc_chebyshev_filter", "sc_kmeanspp", "sc_kmeans_lloyd", "sc_kmeans", "sc_edge_similarity",
+           "sc_chebyshev_filter", "sc_kmeanspp", "sc_kmeans_lloyd", "sc_kmeans", "sc_edge_similarity", "sc_knn_search", "sc_knn_union_pairs",
            "sc_coo_to_csr", "sc_workspace_bytes", "sc_scale_operator"]
 
 
@@ -103,6 +103,8 @@ def lib() -> ctypes.CDLL:
         _lib.sc_kmeans.argtypes = [vp, i64, i32, i64, i32, i32, u64, i32, vp, vp, ctypes.POINTER(ScKMeansStats), vp]
         _lib.sc_edge_similarity.argtypes = [vp, i64, i64, i32, vp, vp, i64, i32, dbl, vp, vp]
         _lib.sc_coo_to_csr.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_int64), vp]
+        _lib.sc_knn_search.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
+        _lib.sc_knn_union_pairs.argtypes = [vp, vp, i64, i32, dbl, vp, vp, vp, ctypes.POINTER(ctypes.c_int64), vp]
         _lib.sc_sym_eig.argtypes = [vp, i32, vp, vp]
         _lib.sc_sym_eig_top.argtypes = [vp, i32, i32, vp, vp]
         for name in EXPORTS:
@@ -385,6 +387,38 @@ def sc_coo_to_csr(row, col, val, n: int, symmetrize: bool):
                                    _ptr(vo), ctypes.byref(nnz), _stream())
     _check(code)
     return rp, co[:nnz.value], vo[:nnz.value]
+
+
+def sc_knn_search(x, k_nn: int):
+    """Section III-A's k nearest neighbours of every row of x ((n, d) device).  Returns (idx int32 (n, k_nn),
+    dist fp64 (n, k_nn)) device, nearest first."""
+    import torch
+    _dev(x, torch.float64)
+    n, d = x.shape
+    idx = torch.empty((n, k_nn), dtype=torch.int32, device=x.device)
+    dist = torch.empty((n, k_nn), dtype=torch.float64, device=x.device)
+    with torch.cuda.device(x.device):
+        code = lib().sc_knn_search(_ptr(x), x.stride(0), n, d, k_nn, _ptr(idx), _ptr(dist), _stream())
+    _check(code)
+    return idx, dist
+
+
+def sc_knn_union_pairs(idx, dist, sigma: float = 0.0):
+    """The undirected edges of the kNN graph, each once.  Returns (edge_u, edge_v int32, val fp64) device."""
+    import torch
+    _dev(idx, torch.int32), _dev(dist, torch.float64)
+    n, k_nn = idx.shape
+    assert idx.is_contiguous() and dist.is_contiguous() and dist.shape == idx.shape
+    eu = torch.empty(max(n * k_nn, 1), dtype=torch.int32, device=idx.device)
+    ev = torch.empty(max(n * k_nn, 1), dtype=torch.int32, device=idx.device)
+    val = torch.empty(max(n * k_nn, 1), dtype=torch.float64, device=idx.device)
+    npairs = ctypes.c_int64(0)
+    with torch.cuda.device(idx.device):
+        code = lib().sc_knn_union_pairs(_ptr(idx), _ptr(dist), n, k_nn, float(sigma), _ptr(eu), _ptr(ev), _ptr(val),
+                                        ctypes.byref(npairs), _stream())
+    _check(code)
+    m = npairs.value
+    return eu[:m], ev[:m], val[:m]
 
 
 def sc_sym_eig(a: np.ndarray, vectors: bool = True) -> Tuple[np.ndarray, Optional[np.ndarray]]:

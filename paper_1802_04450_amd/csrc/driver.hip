@@ -1924,6 +1924,72 @@ int sc_coo_to_csr(const int32_t* row, const int32_t* col, const double* val, int
       &ctx);
 }
 
+int sc_knn_search(const double* x, int64_t ldx, int64_t n, int32_t d, int32_t k_nn, int32_t* idx_out, double* dist_out,
+                  void* stream) {
+  if (!x || !idx_out || !dist_out || n < 0) return SC_EINVAL;
+  if (d < 1 || ldx < d || n < 2 || n > (int64_t)0x7fffffff || k_nn < 1 || (int64_t)k_nn > n - 1) return SC_EDOMAIN;
+  struct Ctx {
+    const double* x;
+    int64_t ldx, n;
+    int d, k;
+    int32_t* idx;
+    double* dist;
+    hipStream_t st;
+  } ctx{x, ldx, n, d, k_nn, idx_out, dist_out, reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        int dev = 0, lds_max = 0;
+        HIP_TRY(hipGetDevice(&dev));
+        HIP_TRY(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+        if (knn_search_lds_bytes(c->d, c->k) > (size_t)lds_max) return SC_EDOMAIN;  // d and k_nn too large together
+        DevBuf<double> xp;
+        xp.alloc((size_t)c->n * knn_padded_dim(c->d));
+        HIP_TRY(launch_knn_search(c->x, c->ldx, c->n, c->d, c->k, xp.p, c->idx, c->dist, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        return SC_OK;
+      },
+      &ctx);
+}
+
+int sc_knn_union_pairs(const int32_t* idx, const double* dist, int64_t n, int32_t k_nn, double sigma, int32_t* edge_u,
+                       int32_t* edge_v, double* val_out, int64_t* npairs_out, void* stream) {
+  if (!idx || !dist || !edge_u || !edge_v || !val_out || !npairs_out || n < 0) return SC_EINVAL;
+  *npairs_out = 0;
+  if (k_nn < 1 || n > (int64_t)0x7fffffff || n * (int64_t)k_nn > (int64_t)0x7fffffff || sigma < 0.0 || sigma != sigma)
+    return SC_EDOMAIN;
+  if (n == 0) return SC_OK;
+  struct Ctx {
+    const int32_t* idx;
+    const double* dist;
+    int64_t n;
+    int k;
+    double sigma;
+    int32_t *eu, *ev;
+    double* val;
+    int64_t* np;
+    hipStream_t st;
+  } ctx{idx, dist, n, k_nn, sigma, edge_u, edge_v, val_out, npairs_out, reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        const size_t wb = knn_pairs_workspace(c->n);
+        DevBuf<char> work;
+        DevBuf<int32_t> two;
+        PinnedBuf<int32_t> host;
+        work.alloc(wb);
+        two.alloc(2);
+        host.alloc(2);
+        HIP_TRY(launch_knn_union_pairs(c->idx, c->dist, c->n, c->k, c->sigma, work.p, wb, c->eu, c->ev, c->val, two.p,
+                                       c->st));
+        HIP_TRY(hipMemcpyAsync(host.p, two.p, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
+        HIP_TRY(hipStreamSynchronize(c->st));
+        *c->np = (int64_t)host.p[0] + (int64_t)host.p[1];
+        return SC_OK;
+      },
+      &ctx);
+}
+
 int sc_sym_eig(const double* a, int32_t n, double* w, double* z) {
   if (!a || !w || n < 0) return SC_EINVAL;
   if (n == 0) return SC_OK;

@@ -182,6 +182,22 @@ hipError_t launch_row_stats(const double* x, int64_t ldx, int64_t n, int d, int 
 hipError_t launch_edge_similarity(const double* x, int64_t ldx, int d, const int32_t* eu, const int32_t* ev,
                                   int64_t nedges, int measure, double sigma, const double* mean, const double* norm,
                                   int64_t n, int* bad, double* val, hipStream_t st);
+// ---- k-nearest-neighbour graph (Section III-A; knn.hip) -------------------------------------------------------
+// Exact Euclidean k nearest neighbours of every row of x (n x d, leading dimension ldx) other than the row itself:
+// idx_out[i*k + a] / dist_out[i*k + a] = index / distance of the a-th nearest, nearest first, equal distances by
+// index.  xp: device scratch of n * knn_padded_dim(d) doubles.  2 <= n <= INT32_MAX, 1 <= k <= n - 1, and
+// knn_search_lds_bytes(d, k) must not exceed the LDS a workgroup may have (else hipErrorInvalidValue).
+int knn_padded_dim(int d);
+size_t knn_search_lds_bytes(int d, int k);
+hipError_t launch_knn_search(const double* x, int64_t ldx, int64_t n, int d, int k, double* xp, int32_t* idx_out,
+                             double* dist_out, hipStream_t st);
+// The undirected edges {i, j} (j in i's list or i in j's) once each as eu < ev, in row order of the emitting list;
+// val = the listed distance, or exp(-dist^2 / (2 sigma^2)) if sigma > 0.  eu, ev, val have room for n * k entries;
+// last_two (device int32[2]) receives two numbers whose sum is the pair count.  work: knn_pairs_workspace(n) bytes.
+size_t knn_pairs_workspace(int64_t n);
+hipError_t launch_knn_union_pairs(const int32_t* idx, const double* dist, int64_t n, int k, double sigma, void* work,
+                                  size_t work_bytes, int32_t* eu, int32_t* ev, double* val, int32_t* last_two,
+                                  hipStream_t st);
 size_t coo_to_csr_workspace(int64_t total);
 hipError_t coo_to_csr(const int32_t* row, const int32_t* col, const double* val, int64_t nnz_in, int64_t n,
                       int symmetrize, void* work, size_t work_bytes, int64_t* rowptr_out, int32_t* col_out,

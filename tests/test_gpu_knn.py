@@ -1,0 +1,156 @@
+"""GPU parity of the k-nearest-neighbour graph construction (Section III-A) against the oracle, through the C ABI:
+the exact search, the list of undirected edges, and the chain points -> neighbours -> edges -> CSR."""
+import numpy as np
+import pytest
+
+from oracle import knn as oknn
+from paper_1802_04450_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_1802_04450_amd import binding
+    binding.lib()
+    return binding
+
+
+def _dev(a, dtype):
+    return torch.as_tensor(np.ascontiguousarray(a), dtype=dtype, device="cuda:0")
+
+
+def _check_search(B, x, k):
+    ref_i, ref_d = oknn.knn_bruteforce(x, k)
+    idx, dist = B.sc_knn_search(_dev(x, torch.float64), k)
+    idx, dist = idx.cpu().numpy(), dist.cpu().numpy()
+    # the neighbour sets are integers decided by fp64 distances on both sides: equal unless two candidates of one
+    # query are closer than the rounding of the sum, which the distances themselves then show
+    same = idx == ref_i
+    if not same.all():
+        bad = np.argwhere(~same)
+        for i, a in bad:
+            assert abs(dist[i, a] - ref_d[i, a]) <= 4e-15 * max(ref_d[i, a], 1e-300), (i, a)
+        assert len(bad) <= 2 * max(1, x.shape[0] // 1000)
+    np.testing.assert_allclose(dist, ref_d, rtol=1e-13, atol=0)
+    return idx, dist
+
+
+# several workgroups of 128 queries and a ragged last one; candidate counts not a multiple of 4; padded and unpadded
+# dimensions; k from 1 to all the other points
+@pytest.mark.parametrize("n,d,k", [(1500, 5, 7), (1003, 3, 1), (130, 33, 20), (641, 16, 10), (20, 2, 19), (2, 1, 1),
+                                   (515, 128, 10), (300, 8, 32)])
+def test_search_matches_oracle(B, n, d, k):
+    rng = np.random.default_rng(100 * n + d)
+    x = rng.standard_normal((n, d)) * rng.uniform(0.5, 2.0, size=(1, d))
+    idx, dist = _check_search(B, x, k)
+    assert np.all(idx != np.arange(n)[:, None]) and np.all(np.diff(dist, axis=1) >= 0)
+
+
+def test_search_orders_equal_distances_by_index(B):
+    # integer points on a line and on a small grid: many exactly equal distances, all sums exact in fp64
+    x = np.arange(37, dtype=np.float64)[:, None]
+    ref_i, ref_d = oknn.knn_bruteforce(x, 6)
+    idx, dist = B.sc_knn_search(_dev(x, torch.float64), 6)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref_i)
+    np.testing.assert_array_equal(dist.cpu().numpy(), ref_d)
+    g = np.stack(np.meshgrid(np.arange(13.0), np.arange(11.0), indexing="ij"), axis=-1).reshape(-1, 2)
+    ref_i, ref_d = oknn.knn_bruteforce(g, 8)
+    idx, dist = B.sc_knn_search(_dev(g, torch.float64), 8)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref_i)
+    np.testing.assert_array_equal(dist.cpu().numpy(), ref_d)
+
+
+def test_search_strided_rows_and_errors(B):
+    rng = np.random.default_rng(2)
+    n, d, k = 700, 6, 5
+    big = torch.as_tensor(rng.standard_normal((n, 9)), device="cuda:0")
+    x = big[:, :d]                                   # leading dimension 9: through the C ABI directly
+    lib = B.lib()
+    st = torch.cuda.current_stream().cuda_stream
+    io = torch.empty((n, k), dtype=torch.int32, device="cuda:0")
+    do = torch.empty((n, k), dtype=torch.float64, device="cuda:0")
+    assert lib.sc_knn_search(x.data_ptr(), 9, n, d, k, io.data_ptr(), do.data_ptr(), st) == 0
+    ref_i, ref_d = oknn.knn_bruteforce(big.cpu().numpy()[:, :d], k)
+    np.testing.assert_array_equal(io.cpu().numpy(), ref_i)
+    np.testing.assert_allclose(do.cpu().numpy(), ref_d, rtol=1e-13)
+    assert lib.sc_knn_search(x.data_ptr(), 9, n, d, n, io.data_ptr(), do.data_ptr(), st) == -2      # k_nn > n - 1
+    assert lib.sc_knn_search(x.data_ptr(), 5, n, d, k, io.data_ptr(), do.data_ptr(), st) == -2      # ldx < d
+    assert lib.sc_knn_search(x.data_ptr(), 9, 1, d, 1, io.data_ptr(), do.data_ptr(), st) == -2      # one point
+    assert lib.sc_knn_search(0, 9, n, d, k, io.data_ptr(), do.data_ptr(), st) == -1                 # null pointer
+    assert lib.sc_knn_search(x.data_ptr(), 9, n, 160, 5, io.data_ptr(), do.data_ptr(), st) == -2    # LDS: d too large
+
+
+@pytest.mark.parametrize("n,d,k,sigma", [(1200, 4, 6, 0.0), (777, 10, 15, 1.3), (50, 2, 49, 0.5)])
+def test_union_pairs_match_oracle(B, n, d, k, sigma):
+    rng = np.random.default_rng(n)
+    x = rng.standard_normal((n, d))
+    ref_i, ref_d = oknn.knn_bruteforce(x, k)
+    u, v, w = oknn.knn_union_pairs(ref_i, ref_d, sigma)
+    eu, ev, val = B.sc_knn_union_pairs(_dev(ref_i, torch.int32), _dev(ref_d, torch.float64), sigma)
+    eu, ev, val = eu.cpu().numpy().astype(np.int64), ev.cpu().numpy().astype(np.int64), val.cpu().numpy()
+    assert np.all(eu < ev)
+    order = np.lexsort((ev, eu))                     # the library lists by emitting row; the set is what is unique
+    np.testing.assert_array_equal(eu[order], u)
+    np.testing.assert_array_equal(ev[order], v)
+    np.testing.assert_allclose(val[order], w, rtol=1e-14, atol=0)
+
+
+def test_union_pairs_skip_invalid_and_repeated_entries(B):
+    # hand-made lists: -1 padding, a self reference, a neighbour listed twice, an out-of-range index
+    idx = np.array([[1, 1, -1], [0, 2, 1], [7, 0, -1], [2, 3, 0]], dtype=np.int32)
+    dist = np.array([[1.0, 1.0, 9.0], [1.0, 2.0, 0.0], [9.0, 3.0, 9.0], [4.0, 0.0, 5.0]])
+    eu, ev, val = B.sc_knn_union_pairs(_dev(idx, torch.int32), _dev(dist, torch.float64), 0.0)
+    got = sorted(zip(eu.cpu().tolist(), ev.cpu().tolist(), val.cpu().tolist()))
+    # {0,1} from row 0; {1,2} from row 1; {0,2} from row 2 (row 0 does not list 2); {2,3} and {0,3} from row 3
+    assert got == [(0, 1, 1.0), (0, 2, 3.0), (0, 3, 5.0), (1, 2, 2.0), (2, 3, 4.0)]
+
+
+def test_points_to_graph_chain(B):
+    """points -> sc_knn_search -> sc_knn_union_pairs (Gaussian weights) -> sc_coo_to_csr: the matrix equals the
+    oracle's (dense, from its own neighbours and pairs), and the seeded input generator's graph of the same points."""
+    from oracle import similarity as osim
+    cfg = wl.CONFIGS[1]
+    x, _ = wl.mixture_points(cfg)
+    n = x.shape[0]
+    ref_i, ref_d = oknn.knn_bruteforce(x, cfg.k_nn)
+    sigma = float(np.median(ref_d))
+    u, v, w = oknn.knn_union_pairs(ref_i, ref_d, sigma)
+    dense = osim.coo_to_dense(u, v, w, n, True)
+    idx, dist = B.sc_knn_search(_dev(x, torch.float64), cfg.k_nn)
+    eu, ev, val = B.sc_knn_union_pairs(idx, dist, sigma)
+    rp, co, va = B.sc_coo_to_csr(eu, ev, val, n, True)
+    rp, co, va = rp.cpu().numpy(), co.cpu().numpy(), va.cpu().numpy()
+    assert osim.csr_rows_sorted(rp, co)
+    got = np.zeros((n, n))
+    got[np.repeat(np.arange(n), np.diff(rp)), co] = va
+    np.testing.assert_allclose(got, dense, rtol=1e-12, atol=0)
+    assert np.count_nonzero(got) == rp[-1] == 2 * len(u)
+    graph, gsigma = wl.knn_gaussian_graph(x, cfg.k_nn, "cpu")
+    if graph[3] == n:                                  # the generator dropped no isolated point on this workload
+        assert abs(gsigma - sigma) <= 1e-12 * sigma
+        np.testing.assert_array_equal(rp, graph[0])
+        np.testing.assert_array_equal(co, graph[1])
+        np.testing.assert_allclose(va, graph[2], rtol=1e-6, atol=0)
+
+
+def test_search_at_benchmark_size_on_sampled_queries(B):
+    """Config 2's points (n = 100,000, d = 32, k_nn = 20): 48 sampled queries against the oracle's definition."""
+    cfg = wl.CONFIGS[2]
+    x, _ = wl.mixture_points(cfg)
+    idx, dist = B.sc_knn_search(_dev(x, torch.float64), cfg.k_nn)
+    idx, dist = idx.cpu().numpy(), dist.cpu().numpy()
+    rng = np.random.default_rng(5)
+    ids = np.arange(x.shape[0])
+    for i in rng.choice(x.shape[0], size=48, replace=False):
+        diff = x - x[i]
+        d2 = (diff * diff).sum(axis=1)
+        d2[i] = np.inf
+        order = np.lexsort((ids, d2))[:cfg.k_nn]
+        np.testing.assert_array_equal(idx[i], order)
+        np.testing.assert_allclose(dist[i], np.sqrt(d2[order]), rtol=1e-13)
+    assert np.all(np.diff(dist, axis=1) >= 0) and idx.min() >= 0 and idx.max() < x.shape[0]
