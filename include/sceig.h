@@ -357,9 +357,10 @@ int sc_edge_similarity(const double* x, int64_t ldx, int64_t n, int32_t d, const
  *   idx_out   device int32[n * k_nn]: row i = the k_nn points nearest to x_i other than i, nearest first; equal
  *             distances are ordered by index, so the result is unique
  *   dist_out  device fp64[n * k_nn]: their Euclidean distances
- * 2 <= n <= 2^31 - 1, d >= 1, 1 <= k_nn <= n - 1, and 128 * (8 * ceil(d / 8) * 8 + 12 * k_nn) bytes must fit the
- * LDS of a workgroup (160 KB: e.g. d <= 128 with k_nn <= 20), else SC_EDOMAIN.  The library allocates n * 8 *
- * ceil(d / 8) * 8 bytes of scratch for the call.  Returns after the work on `stream` is done.
+ * 2 <= n <= 2^31 - 1, d >= 1, 1 <= k_nn <= n - 1, and the kernel's LDS need must fit a workgroup's 160 KB, else
+ * SC_EDOMAIN: 1536 * k_nn + 256 * dp bytes for d <= 32 (dp = d rounded up to 8, 16 or 32), 128 * (8 * dp + 12 * k_nn)
+ * bytes for d > 32 (dp = d rounded up to a multiple of 8; e.g. d = 128 with k_nn <= 20).  The library allocates
+ * n * dp * 8 bytes of scratch for the call.  Returns after the work on `stream` is done.
  */
 int sc_knn_search(const double* x, int64_t ldx, int64_t n, int32_t d, int32_t k_nn, int32_t* idx_out, double* dist_out,
                   void* stream);

@@ -24,7 +24,7 @@ namespace {
 
 constexpr int kT = 256;
 constexpr int kQ = 128;  // queries per workgroup of the search
-constexpr int kJU = 4;   // candidates in flight
+constexpr int kJU = 4;   // candidates in flight (the asm statements that pin the order name four sums)
 constexpr int kDC = 8;   // coordinates per piece (rows are padded to a multiple of it)
 inline unsigned blocks(int64_t n) { return (unsigned)((n + kT - 1) / kT); }
 
@@ -73,12 +73,15 @@ __global__ __launch_bounds__(kQ) void knn_search_kernel(const double* __restrict
           const double df = qv - y[u][c + t];
           acc[u] = fma(df, df, acc[u]);
         }
+        asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]));  // the four sums advance together
       }
     }
+    __builtin_amdgcn_sched_barrier(0);  // the sums stay in front of the tests
 #pragma unroll
     for (int u = 0; u < kJU; ++u) {
       const int64_t j = j0 + u;
-      if (j < n && j != i && (acc[u] < thr || (acc[u] == thr && (int32_t)j < thr_idx))) {
+      const bool pass = (j < n) & (j != i) & ((acc[u] < thr) | ((acc[u] == thr) & ((int32_t)j < thr_idx)));
+      if (pass) {  // bitwise, not short-circuit: the sums must not be moved behind a test of j
         bd[thr_slot * kQ + tid] = acc[u];
         bi[thr_slot * kQ + tid] = (int32_t)j;
         thr = -1.0;
@@ -115,6 +118,164 @@ __global__ __launch_bounds__(kQ) void knn_search_kernel(const double* __restrict
     bi[a * kQ + tid] = bid;
     idx_out[i * k + a] = bid == INT32_MAX ? -1 : bid;
     dist_out[i * k + a] = sqrt(bv);
+  }
+}
+
+// The same search for rows of at most 32 (padded) coordinates: the queries sit in registers, NQ per thread, and the
+// candidates come through LDS in tiles of kTC rows that the workgroup copies with coalesced loads (the next tile is
+// fetched into registers while the current one is used; one barrier per tile).  All lanes read the same candidate
+// coordinate at the same time (an LDS broadcast), so no load of the inner loop waits on memory.  Tiles are small (16
+// rows) so that four workgroups fit a compute unit beside their lists: the loop lives on several waves per SIMD
+// covering each other's LDS latency.
+constexpr int kTC = 16;  // candidates per tile
+template <int DP, int NQ>
+__global__ __launch_bounds__(kQ) void knn_tile_kernel(const double* __restrict__ xp, int64_t n, int k,
+                                                      int32_t* __restrict__ idx_out, double* __restrict__ dist_out) {
+  constexpr int TD2 = kTC * DP / 2;    // 16-byte elements of a tile
+  constexpr int NPRE = (TD2 + kQ - 1) / kQ;
+  constexpr int QW = kQ * NQ;          // queries per workgroup = columns of the lists
+  extern __shared__ double lds[];
+  double2* yt = reinterpret_cast<double2*>(lds);                 // [2][kTC][DP/2]
+  double* bd = lds + 2 * kTC * DP;                               // [k][QW]
+  int32_t* bi = reinterpret_cast<int32_t*>(bd + (size_t)k * QW); // [k][QW]
+  const int tid = threadIdx.x;
+  int64_t qi[NQ];       // this thread's queries: one in each block of kQ consecutive points
+  int col[NQ];          // and their columns of the lists
+  double q[NQ][DP];
+  double thr[NQ];       // the worst of the kept candidates: (thr, thr_idx) in slot thr_slot; a dead query accepts nothing
+  int32_t thr_idx[NQ];
+  int thr_slot[NQ];
+#pragma unroll
+  for (int v = 0; v < NQ; ++v) {
+    qi[v] = (int64_t)blockIdx.x * QW + v * kQ + tid;
+    col[v] = v * kQ + tid;
+    const bool live = qi[v] < n;
+#pragma unroll
+    for (int t = 0; t < DP; ++t) q[v][t] = live ? xp[qi[v] * DP + t] : 0.0;
+    for (int s = 0; s < k; ++s) {
+      bd[s * QW + col[v]] = INFINITY;
+      bi[s * QW + col[v]] = INT32_MAX;
+    }
+    thr[v] = live ? INFINITY : -1.0;
+    thr_idx[v] = INT32_MAX;
+    thr_slot[v] = 0;
+  }
+  const double2* __restrict__ xp2 = reinterpret_cast<const double2*>(xp);
+  const int64_t total2 = n * (DP / 2);
+  const int64_t ntile = (n + kTC - 1) / kTC;
+  double2 pre[NPRE];
+#pragma unroll
+  for (int u = 0; u < NPRE; ++u) {
+    const int e = tid + u * kQ;
+    if (e < TD2) yt[e] = e < total2 ? xp2[e] : double2{0.0, 0.0};
+  }
+  __syncthreads();
+  for (int64_t tile = 0; tile < ntile; ++tile) {
+    const int buf = (int)(tile & 1);
+    // the next tile's rows, requested now and parked in LDS after this tile's arithmetic
+#pragma unroll
+    for (int u = 0; u < NPRE; ++u) {
+      const int e = tid + u * kQ;
+      const int64_t g = (tile + 1) * TD2 + e;
+      pre[u] = (e < TD2 && g < total2) ? xp2[g] : double2{0.0, 0.0};
+    }
+    const double2* __restrict__ yb = yt + buf * TD2;
+    for (int c0 = 0; c0 < kTC; c0 += kJU) {
+      double acc[NQ][kJU];
+#pragma unroll
+      for (int v = 0; v < NQ; ++v)
+#pragma unroll
+        for (int u = 0; u < kJU; ++u) acc[v][u] = 0.0;
+      double2 ycur[kJU], ynxt[kJU];
+#pragma unroll
+      for (int u = 0; u < kJU; ++u) ycur[u] = yb[(c0 + u) * (DP / 2)];  // the same address in every lane
+#pragma unroll
+      for (int t = 0; t < DP; t += 2) {
+        if (t + 2 < DP) {  // the next two coordinates are requested before these two are used
+#pragma unroll
+          for (int u = 0; u < kJU; ++u) ynxt[u] = yb[(c0 + u) * (DP / 2) + t / 2 + 1];
+        }
+#pragma unroll
+        for (int u = 0; u < kJU; ++u) {
+#pragma unroll
+          for (int v = 0; v < NQ; ++v) {
+            const double d0 = q[v][t] - ycur[u].x;
+            acc[v][u] = fma(d0, d0, acc[v][u]);
+            const double d1 = q[v][t + 1] - ycur[u].y;
+            acc[v][u] = fma(d1, d1, acc[v][u]);
+          }
+        }
+        // all the sums advance together, two coordinates at a time: left alone, the compiler finishes one candidate's
+        // chain of dependent multiply-adds before it starts the next and the loop runs at the latency of one
+#pragma unroll
+        for (int v = 0; v < NQ; ++v) asm volatile("" : "+v"(acc[v][0]), "+v"(acc[v][1]), "+v"(acc[v][2]), "+v"(acc[v][3]));
+#pragma unroll
+        for (int u = 0; u < kJU; ++u) ycur[u] = ynxt[u];
+      }
+      // the sums stay in front of the tests: the compiler otherwise moves each behind the test of its candidate
+      // and computes them there one dependent chain at a time
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int v = 0; v < NQ; ++v)
+#pragma unroll
+        for (int u = 0; u < kJU; ++u) {
+          const int64_t j = tile * kTC + c0 + u;
+          const double a = acc[v][u];
+          // bitwise, not short-circuit: the sums above must not be moved behind a test of j, one chain at a time
+          const bool pass = (j < n) & (j != qi[v]) & ((a < thr[v]) | ((a == thr[v]) & ((int32_t)j < thr_idx[v])));
+          if (pass) {
+            bd[thr_slot[v] * QW + col[v]] = a;
+            bi[thr_slot[v] * QW + col[v]] = (int32_t)j;
+            double w = -1.0;
+            int32_t wid = INT32_MAX;
+            int ws = 0;
+            for (int s = 0; s < k; ++s) {
+              const double x = bd[s * QW + col[v]];
+              const int32_t id = bi[s * QW + col[v]];
+              if (x > w || (x == w && id > wid)) {
+                w = x;
+                wid = id;
+                ws = s;
+              }
+            }
+            thr[v] = w;
+            thr_idx[v] = wid;
+            thr_slot[v] = ws;
+          }
+        }
+    }
+    double2* yn = yt + (buf ^ 1) * TD2;
+#pragma unroll
+    for (int u = 0; u < NPRE; ++u) {
+      const int e = tid + u * kQ;
+      if (e < TD2) yn[e] = pre[u];
+    }
+    __syncthreads();  // every thread, dead queries included, passes here once per tile
+  }
+#pragma unroll
+  for (int v = 0; v < NQ; ++v) {
+    if (qi[v] >= n) continue;
+    const int cq = col[v];
+    for (int a = 0; a < k; ++a) {  // nearest first (ties: lower index first): selection sort of the k slots
+      int best = a;
+      double bv = bd[a * QW + cq];
+      int32_t bid = bi[a * QW + cq];
+      for (int s = a + 1; s < k; ++s) {
+        const double x = bd[s * QW + cq];
+        const int32_t id = bi[s * QW + cq];
+        if (x < bv || (x == bv && id < bid)) {
+          best = s;
+          bv = x;
+          bid = id;
+        }
+      }
+      bd[best * QW + cq] = bd[a * QW + cq];
+      bi[best * QW + cq] = bi[a * QW + cq];
+      bd[a * QW + cq] = bv;
+      bi[a * QW + cq] = bid;
+      idx_out[qi[v] * k + a] = bid == INT32_MAX ? -1 : bid;
+      dist_out[qi[v] * k + a] = sqrt(bv);
+    }
   }
 }
 
@@ -160,10 +321,13 @@ __global__ __launch_bounds__(kT) void pair_emit_kernel(const int32_t* __restrict
 
 }  // namespace
 
-int knn_padded_dim(int d) { return (d + kDC - 1) / kDC * kDC; }
+int knn_padded_dim(int d) { return d <= 8 ? 8 : d <= 16 ? 16 : d <= 32 ? 32 : (d + kDC - 1) / kDC * kDC; }
 
 size_t knn_search_lds_bytes(int d, int k) {
-  return (size_t)kQ * ((size_t)knn_padded_dim(d) * sizeof(double) + (size_t)k * (sizeof(double) + sizeof(int32_t)));
+  const size_t lists = (size_t)kQ * k * (sizeof(double) + sizeof(int32_t));
+  const int dp = knn_padded_dim(d);
+  if (dp <= 32) return lists + 2 * (size_t)kTC * dp * sizeof(double);  // two candidate tiles
+  return lists + (size_t)kQ * dp * sizeof(double);                     // the queries
 }
 
 hipError_t launch_knn_search(const double* x, int64_t ldx, int64_t n, int d, int k, double* xp, int32_t* idx_out,
@@ -177,14 +341,37 @@ hipError_t launch_knn_search(const double* x, int64_t ldx, int64_t n, int d, int
   e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
   if (e != hipSuccess) return e;
   if (lds > (size_t)lds_max) return hipErrorInvalidValue;
-  if (lds > 64 * 1024) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&knn_search_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-  }
   hipLaunchKernelGGL(pad_rows_kernel, dim3(blocks(n * dp)), dim3(kT), 0, st, x, ldx, n, d, dp, xp);
-  hipLaunchKernelGGL(knn_search_kernel, dim3((unsigned)((n + kQ - 1) / kQ)), dim3(kQ), lds, st, xp, n, dp, k, idx_out,
-                     dist_out);
+#define SC_KNN_TILE(DPV, NQV)                                                                                  \
+  do {                                                                                                         \
+    const size_t l = lds;                                                                                      \
+    if (l > 64 * 1024) {                                                                                       \
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&knn_tile_kernel<DPV, NQV>),                       \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)l);                             \
+      if (e != hipSuccess) return e;                                                                           \
+    }                                                                                                          \
+    hipLaunchKernelGGL((knn_tile_kernel<DPV, NQV>), dim3((unsigned)((n + kQ * NQV - 1) / (kQ * NQV))), dim3(kQ), l, \
+                       st, xp, n, k, idx_out, dist_out);                                                       \
+  } while (0)
+  // one query per thread: with two (NQ = 2) every LDS read feeds twice the arithmetic, but the lists of 256 queries
+  // leave room for two workgroups per compute unit only, and the search of 100,000 points in 32 dimensions took 86 ms
+  // instead of 59 ms
+  if (dp == 8) {
+    SC_KNN_TILE(8, 1);
+  } else if (dp == 16) {
+    SC_KNN_TILE(16, 1);
+  } else if (dp == 32) {
+    SC_KNN_TILE(32, 1);
+  } else {
+    if (lds > 64 * 1024) {
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&knn_search_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(knn_search_kernel, dim3((unsigned)((n + kQ - 1) / kQ)), dim3(kQ), lds, st, xp, n, dp, k,
+                       idx_out, dist_out);
+  }
+#undef SC_KNN_TILE
   return hipGetLastError();
 }
 

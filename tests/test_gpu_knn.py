@@ -43,7 +43,9 @@ def _check_search(B, x, k):
 # several workgroups of 128 queries and a ragged last one; candidate counts not a multiple of 4; padded and unpadded
 # dimensions; k from 1 to all the other points
 @pytest.mark.parametrize("n,d,k", [(1500, 5, 7), (1003, 3, 1), (130, 33, 20), (641, 16, 10), (20, 2, 19), (2, 1, 1),
-                                   (515, 128, 10), (300, 8, 32)])
+                                   (515, 128, 10), (300, 8, 32),
+                                   # many workgroups, many candidate tiles
+                                   (8300, 8, 5), (8450, 32, 12), (9001, 13, 10)])
 def test_search_matches_oracle(B, n, d, k):
     rng = np.random.default_rng(100 * n + d)
     x = rng.standard_normal((n, d)) * rng.uniform(0.5, 2.0, size=(1, d))
