@@ -125,8 +125,9 @@ __global__ __launch_bounds__(kQ) void knn_search_kernel(const double* __restrict
 // candidates come through LDS in tiles of kTC rows that the workgroup copies with coalesced loads (the next tile is
 // fetched into registers while the current one is used; one barrier per tile).  All lanes read the same candidate
 // coordinate at the same time (an LDS broadcast), so no load of the inner loop waits on memory.  Tiles are small (16
-// rows) so that four workgroups fit a compute unit beside their lists: the loop lives on several waves per SIMD
-// covering each other's LDS latency.
+// rows) so that four workgroups fit a compute unit beside their lists (two waves per SIMD).  What bounds the loop is
+// the LDS itself: a broadcast read hands 16 bytes to each of 64 lanes, 1 KB over a 128-byte-per-cycle path, and there
+// is one such read for every four subtract / multiply-add pairs.
 constexpr int kTC = 16;  // candidates per tile
 template <int DP, int NQ>
 __global__ __launch_bounds__(kQ) void knn_tile_kernel(const double* __restrict__ xp, int64_t n, int k,
@@ -180,28 +181,45 @@ __global__ __launch_bounds__(kQ) void knn_tile_kernel(const double* __restrict__
       pre[u] = (e < TD2 && g < total2) ? xp2[g] : double2{0.0, 0.0};
     }
     const double2* __restrict__ yb = yt + buf * TD2;
-    for (int c0 = 0; c0 < kTC; c0 += kJU) {
-      double acc[NQ][kJU];
+    // The tile is walked in pieces of kJU candidates x CH coordinates.  The LDS reads of a piece are issued at the top
+    // of the piece before it (the first statements behind an asm statement, which the scheduler does not move code
+    // across), so they are long back when the piece is used; the sums are pinned every two coordinates.
+    constexpr int CH = NQ == 2 ? 4 : 8;       // coordinates per piece (DP is a multiple of 8)
+    constexpr int NPC = DP / CH;              // pieces per candidate group
+    constexpr int NG = kTC / kJU;             // candidate groups per tile
+    double2 yp[2][kJU][CH / 2];
 #pragma unroll
-      for (int v = 0; v < NQ; ++v)
+    for (int u = 0; u < kJU; ++u)
 #pragma unroll
-        for (int u = 0; u < kJU; ++u) acc[v][u] = 0.0;
-      double2 ycur[kJU], ynxt[kJU];
+      for (int h = 0; h < CH / 2; ++h) yp[0][u][h] = yb[u * (DP / 2) + h];  // the same address in every lane
+    double acc[NQ][kJU];
 #pragma unroll
-      for (int u = 0; u < kJU; ++u) ycur[u] = yb[(c0 + u) * (DP / 2)];  // the same address in every lane
+    for (int p = 0; p < NG * NPC; ++p) {
+      const int g = p / NPC, pc = p % NPC, cur = p & 1;
+      if (pc == 0) {
 #pragma unroll
-      for (int t = 0; t < DP; t += 2) {
-        if (t + 2 < DP) {  // the next two coordinates are requested before these two are used
+        for (int v = 0; v < NQ; ++v)
 #pragma unroll
-          for (int u = 0; u < kJU; ++u) ynxt[u] = yb[(c0 + u) * (DP / 2) + t / 2 + 1];
-        }
+          for (int u = 0; u < kJU; ++u) acc[v][u] = 0.0;
+      }
+      if (p + 1 < NG * NPC) {  // the next piece's reads
+        const int g1 = (p + 1) / NPC, pc1 = (p + 1) % NPC;
+#pragma unroll
+        for (int u = 0; u < kJU; ++u)
+#pragma unroll
+          for (int h = 0; h < CH / 2; ++h)
+            yp[cur ^ 1][u][h] = yb[(g1 * kJU + u) * (DP / 2) + pc1 * (CH / 2) + h];
+      }
+#pragma unroll
+      for (int h = 0; h < CH / 2; ++h) {
+        const int t = pc * CH + 2 * h;
 #pragma unroll
         for (int u = 0; u < kJU; ++u) {
 #pragma unroll
           for (int v = 0; v < NQ; ++v) {
-            const double d0 = q[v][t] - ycur[u].x;
+            const double d0 = q[v][t] - yp[cur][u][h].x;
             acc[v][u] = fma(d0, d0, acc[v][u]);
-            const double d1 = q[v][t + 1] - ycur[u].y;
+            const double d1 = q[v][t + 1] - yp[cur][u][h].y;
             acc[v][u] = fma(d1, d1, acc[v][u]);
           }
         }
@@ -209,40 +227,38 @@ __global__ __launch_bounds__(kQ) void knn_tile_kernel(const double* __restrict__
         // chain of dependent multiply-adds before it starts the next and the loop runs at the latency of one
 #pragma unroll
         for (int v = 0; v < NQ; ++v) asm volatile("" : "+v"(acc[v][0]), "+v"(acc[v][1]), "+v"(acc[v][2]), "+v"(acc[v][3]));
-#pragma unroll
-        for (int u = 0; u < kJU; ++u) ycur[u] = ynxt[u];
       }
-      // the sums stay in front of the tests: the compiler otherwise moves each behind the test of its candidate
-      // and computes them there one dependent chain at a time
-      __builtin_amdgcn_sched_barrier(0);
+      if (pc == NPC - 1) {
+        const int c0 = g * kJU;
 #pragma unroll
-      for (int v = 0; v < NQ; ++v)
+        for (int v = 0; v < NQ; ++v)
 #pragma unroll
-        for (int u = 0; u < kJU; ++u) {
-          const int64_t j = tile * kTC + c0 + u;
-          const double a = acc[v][u];
-          // bitwise, not short-circuit: the sums above must not be moved behind a test of j, one chain at a time
-          const bool pass = (j < n) & (j != qi[v]) & ((a < thr[v]) | ((a == thr[v]) & ((int32_t)j < thr_idx[v])));
-          if (pass) {
-            bd[thr_slot[v] * QW + col[v]] = a;
-            bi[thr_slot[v] * QW + col[v]] = (int32_t)j;
-            double w = -1.0;
-            int32_t wid = INT32_MAX;
-            int ws = 0;
-            for (int s = 0; s < k; ++s) {
-              const double x = bd[s * QW + col[v]];
-              const int32_t id = bi[s * QW + col[v]];
-              if (x > w || (x == w && id > wid)) {
-                w = x;
-                wid = id;
-                ws = s;
+          for (int u = 0; u < kJU; ++u) {
+            const int64_t j = tile * kTC + c0 + u;
+            const double a = acc[v][u];
+            // bitwise, not short-circuit: the sums above must not be moved behind a test of j
+            const bool pass = (j < n) & (j != qi[v]) & ((a < thr[v]) | ((a == thr[v]) & ((int32_t)j < thr_idx[v])));
+            if (pass) {
+              bd[thr_slot[v] * QW + col[v]] = a;
+              bi[thr_slot[v] * QW + col[v]] = (int32_t)j;
+              double w = -1.0;
+              int32_t wid = INT32_MAX;
+              int ws = 0;
+              for (int s = 0; s < k; ++s) {
+                const double x = bd[s * QW + col[v]];
+                const int32_t id = bi[s * QW + col[v]];
+                if (x > w || (x == w && id > wid)) {
+                  w = x;
+                  wid = id;
+                  ws = s;
+                }
               }
+              thr[v] = w;
+              thr_idx[v] = wid;
+              thr_slot[v] = ws;
             }
-            thr[v] = w;
-            thr_idx[v] = wid;
-            thr_slot[v] = ws;
           }
-        }
+      }
     }
     double2* yn = yt + (buf ^ 1) * TD2;
 #pragma unroll
@@ -344,7 +360,7 @@ hipError_t launch_knn_search(const double* x, int64_t ldx, int64_t n, int d, int
   hipLaunchKernelGGL(pad_rows_kernel, dim3(blocks(n * dp)), dim3(kT), 0, st, x, ldx, n, d, dp, xp);
 #define SC_KNN_TILE(DPV, NQV)                                                                                  \
   do {                                                                                                         \
-    const size_t l = lds;                                                                                      \
+    const size_t l = lds + (NQV - 1) * (size_t)kQ * k * 12;                                                    \
     if (l > 64 * 1024) {                                                                                       \
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(&knn_tile_kernel<DPV, NQV>),                       \
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)l);                             \
@@ -354,8 +370,8 @@ hipError_t launch_knn_search(const double* x, int64_t ldx, int64_t n, int d, int
                        st, xp, n, k, idx_out, dist_out);                                                       \
   } while (0)
   // one query per thread: with two (NQ = 2) every LDS read feeds twice the arithmetic, but the lists of 256 queries
-  // leave room for two workgroups per compute unit only, and the search of 100,000 points in 32 dimensions took 86 ms
-  // instead of 59 ms
+  // leave room for two workgroups per compute unit only (one wave per SIMD), and the search of 100,000 points in 32
+  // dimensions took 69 ms instead of 50 ms
   if (dp == 8) {
     SC_KNN_TILE(8, 1);
   } else if (dp == 16) {
