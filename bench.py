@@ -300,15 +300,15 @@ def bench_knn(B, torch, args):
     e1.record()
     torch.cuda.synchronize()
     t_knn = e0.elapsed_time(e1) * 1e-3 / reps
-    # the search is arithmetic: one subtraction and one multiply-add per coordinate of every ordered pair of points,
-    # 3 flops, against the fp64 vector peak (256 CUs x 64 lanes x 2 flops x 2.4 GHz = 78.6 TFLOP/s); a subtraction
-    # counts one flop of the two its issue slot could hold, so a loop of nothing else tops out at 3/4 of that
-    flops = 3.0 * n * n * d
+    # the search is a dense contraction (the cross term q.y of |q|^2 + |y|^2 - 2 q.y over all ordered pairs) on the
+    # fp64 matrix cores, 2 n^2 d flops against their 78.6 TFLOP/s; the exact re-evaluation of the few candidates the
+    # screen lets through is not counted
+    flops = 2.0 * n * n * d
     out = {"metric": "kNN similarity graph s (exact k nearest neighbours + union edge list + symmetric CSR)",
            "value": sec, "unit": "s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3,
            "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
            "config": {"workload": f"{cfg.name} points: n={n}, d={d}, k_nn={k}, nnz={int(rp[-1])}"},
-           "roofline": {"bound": "alu", "kernel": "knn_search_kernel (one sc_knn_search call, with the row padding)",
+           "roofline": {"bound": "mfma", "kernel": "knn_mfma_kernel (one sc_knn_search call, with row padding and norms)",
                         "achieved": flops / t_knn / 1e12, "peak": 78.6, "unit": "TFLOP/s",
                         "frac": flops / t_knn / 1e12 / 78.6, "traffic": None, "call_ms": t_knn * 1e3}}
     if not args.no_cpu_baseline:

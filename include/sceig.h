@@ -358,9 +358,9 @@ int sc_edge_similarity(const double* x, int64_t ldx, int64_t n, int32_t d, const
  *             distances are ordered by index, so the result is unique
  *   dist_out  device fp64[n * k_nn]: their Euclidean distances
  * 2 <= n <= 2^31 - 1, d >= 1, 1 <= k_nn <= n - 1, and the kernel's LDS need must fit a workgroup's 160 KB, else
- * SC_EDOMAIN: 1536 * k_nn + 256 * dp bytes for d <= 32 (dp = d rounded up to 8, 16 or 32), 128 * (8 * dp + 12 * k_nn)
- * bytes for d > 32 (dp = d rounded up to a multiple of 8; e.g. d = 128 with k_nn <= 20).  The library allocates
- * n * dp * 8 bytes of scratch for the call.  Returns after the work on `stream` is done.
+ * SC_EDOMAIN: 768 * k_nn + 1536 bytes for d <= 128 (any k_nn up to 200), 128 * (8 * dp + 12 * k_nn) bytes for d > 128
+ * (dp = d rounded up to a multiple of 8).  The library allocates n * (dp + 1) * 8 bytes of scratch for the call, dp = d
+ * rounded up to 8, 16, 32, 64 or 128 (to a multiple of 8 beyond).  Returns after the work on `stream` is done.
  */
 int sc_knn_search(const double* x, int64_t ldx, int64_t n, int32_t d, int32_t k_nn, int32_t* idx_out, double* dist_out,
                   void* stream);

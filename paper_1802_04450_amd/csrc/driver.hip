@@ -1944,7 +1944,7 @@ int sc_knn_search(const double* x, int64_t ldx, int64_t n, int32_t d, int32_t k_
         HIP_TRY(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
         if (knn_search_lds_bytes(c->d, c->k) > (size_t)lds_max) return SC_EDOMAIN;  // d and k_nn too large together
         DevBuf<double> xp;
-        xp.alloc((size_t)c->n * knn_padded_dim(c->d));
+        xp.alloc((size_t)c->n * (knn_padded_dim(c->d) + 1));  // padded rows, then one squared norm per row
         HIP_TRY(launch_knn_search(c->x, c->ldx, c->n, c->d, c->k, xp.p, c->idx, c->dist, c->st));
         HIP_TRY(hipStreamSynchronize(c->st));
         return SC_OK;

@@ -185,7 +185,7 @@ hipError_t launch_edge_similarity(const double* x, int64_t ldx, int d, const int
 // ---- k-nearest-neighbour graph (Section III-A; knn.hip) -------------------------------------------------------
 // Exact Euclidean k nearest neighbours of every row of x (n x d, leading dimension ldx) other than the row itself:
 // idx_out[i*k + a] / dist_out[i*k + a] = index / distance of the a-th nearest, nearest first, equal distances by
-// index.  xp: device scratch of n * knn_padded_dim(d) doubles.  2 <= n <= INT32_MAX, 1 <= k <= n - 1, and
+// index.  xp: device scratch of n * (knn_padded_dim(d) + 1) doubles.  2 <= n <= INT32_MAX, 1 <= k <= n - 1, and
 // knn_search_lds_bytes(d, k) must not exceed the LDS a workgroup may have (else hipErrorInvalidValue).
 int knn_padded_dim(int d);
 size_t knn_search_lds_bytes(int d, int k);

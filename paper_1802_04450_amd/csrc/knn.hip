@@ -2,22 +2,23 @@
 // similar points of the other), device kernels: exact brute-force search by Euclidean distance and the list of the
 // graph's undirected edges.
 //
-// Search.  One thread per query point, 128 queries per workgroup; every workgroup walks over all n candidate points.
-// A candidate's coordinates are the same for all lanes, so they are read with wave-uniform addresses (the rows are
-// first copied into a zero-padded array so that whole 64-byte pieces can be read); the query's own coordinates sit in
-// LDS, one column per thread.  Four candidates are in flight per pass over the coordinates, so a coordinate of the
-// query is read once for four subtract / multiply-add pairs: the loop is bound by the fp64 vector units.  The squared
-// distance is the plain sum of squared differences in coordinate order (no |x|^2 + |y|^2 - 2xy expansion: the
-// ranking of near neighbours must not suffer cancellation).  Each thread keeps its k best so far in LDS together with
-// the worst of them; a candidate that beats the worst replaces it and the worst is found again by a scan of the k
-// slots, which after the first few hundred candidates happens rarely.  Equal distances are ranked by index, so the
-// result is unique.
+// Search.  The distance that ranks the neighbours is the plain sum of squared coordinate differences in coordinate
+// order (the |x|^2 + |y|^2 - 2xy expansion loses digits to cancellation), and equal distances are ranked by index,
+// so the result is unique.  Up to 128 coordinates the expansion is still used, on the matrix cores, but only to screen
+// the candidates (knn_mfma_kernel); beyond, a vector kernel computes every distance directly (knn_search_kernel: one
+// thread per query, the query's coordinates in LDS, the candidates' read with wave-uniform addresses from a
+// zero-padded copy, four candidates in flight).  Either way a query keeps its k best so far in LDS together with the
+// worst of them; a candidate that beats the worst replaces it and the worst is found again by a scan of the k slots,
+// which after the first few hundred candidates happens rarely.
 #include <hip/hip_runtime.h>
 #include <hipcub/hipcub.hpp>
 
 #include <cstdint>
 
 #include "kernels.h"
+
+typedef double d4 __attribute__((ext_vector_type(4)));
+#define MFMA_F64(a, b, c) __builtin_amdgcn_mfma_f64_16x16x4f64((a), (b), (c), 0, 0, 0)
 
 namespace sceig {
 namespace {
@@ -121,177 +122,235 @@ __global__ __launch_bounds__(kQ) void knn_search_kernel(const double* __restrict
   }
 }
 
-// The same search for rows of at most 32 (padded) coordinates: the queries sit in registers, NQ per thread, and the
-// candidates come through LDS in tiles of kTC rows that the workgroup copies with coalesced loads (the next tile is
-// fetched into registers while the current one is used; one barrier per tile).  All lanes read the same candidate
-// coordinate at the same time (an LDS broadcast), so no load of the inner loop waits on memory.  Tiles are small (16
-// rows) so that four workgroups fit a compute unit beside their lists (two waves per SIMD).  What bounds the loop is
-// the LDS itself: a broadcast read hands 16 bytes to each of 64 lanes, 1 KB over a 128-byte-per-cycle path, and there
-// is one such read for every four subtract / multiply-add pairs.
-constexpr int kTC = 16;  // candidates per tile
-template <int DP, int NQ>
-__global__ __launch_bounds__(kQ) void knn_tile_kernel(const double* __restrict__ xp, int64_t n, int k,
-                                                      int32_t* __restrict__ idx_out, double* __restrict__ dist_out) {
-  constexpr int TD2 = kTC * DP / 2;    // 16-byte elements of a tile
-  constexpr int NPRE = (TD2 + kQ - 1) / kQ;
-  constexpr int QW = kQ * NQ;          // queries per workgroup = columns of the lists
+// xn[i] = sum_t xp[i][t]^2 in coordinate order
+__global__ __launch_bounds__(kT) void row_norms_kernel(const double* __restrict__ xp, int64_t n, int dp,
+                                                       double* __restrict__ xn) {
+  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= n) return;
+  double acc = 0.0;
+  for (int t = 0; t < dp; ++t) acc = fma(xp[i * dp + t], xp[i * dp + t], acc);
+  xn[i] = acc;
+}
+
+// The search with the cross term on the matrix cores.  |q - y|^2 = |q|^2 + |y|^2 - 2 q.y, and q.y over 64 queries x
+// 64 candidates is a dense contraction: a workgroup of four waves owns 64 queries, wave w the 16 x 64 block of its 16
+// queries, as 16x16x4 fp64 MFMAs with the queries' coordinates resident in registers and the candidates' loaded with
+// 16-byte loads one step ahead.  The expanded form loses digits to cancellation, so it only screens: a candidate
+// whose approximate squared distance lies below the query's threshold (the k-th best exact distance so far) plus a
+// bound of the rounding error, kMarginUlps * 2^-53 * (|q|^2 + |y|^2), gets a bit in an LDS mask, and every kRound
+// steps one thread per query walks its bits, computes the exact distance as the plain sum of squared differences in
+// coordinate order and keeps the k best by (distance, index) exactly as the other kernels do.  The thresholds the
+// screen uses are those of the last walk: they only ever shrink, so a lagging threshold lets more candidates
+// through, never fewer; the result is the exact one.
+// Error bound: both norms carry a relative error of dp * u (u = 2^-53), the dot product an absolute error of
+// dp * u * |q||y| <= dp * u * (|q|^2 + |y|^2) / 2, the two final additions 2u more of the terms' size: together
+// below (2 dp + 3) u (|q|^2 + |y|^2); the margin is twice that and more.
+constexpr int kMq = 64;      // queries per workgroup
+constexpr int kMt = 256;     // threads
+constexpr int kRound = 2;    // steps of 64 candidates between two walks of the masks
+template <int DP>
+__global__ __launch_bounds__(kMt) __attribute__((amdgpu_waves_per_eu(2))) void knn_mfma_kernel(
+    const double* __restrict__ xp, const double* __restrict__ xn, int64_t n, int k, int32_t* __restrict__ idx_out,
+    double* __restrict__ dist_out) {
+  constexpr int NS = DP / 4;            // MFMAs per 16 x 16 block
+  constexpr int KC = DP < 32 ? DP : 32;  // coordinates per piece of a step (the B operands of one piece are in flight)
+  constexpr int NCH = DP / KC;           // pieces per step: 1, 2 or 4
+  constexpr int NSC = KC / 4;            // MFMAs per block and piece
+  constexpr double kMargin = (4.0 * DP + 16.0) * 1.1102230246251565e-16;
   extern __shared__ double lds[];
-  double2* yt = reinterpret_cast<double2*>(lds);                 // [2][kTC][DP/2]
-  double* bd = lds + 2 * kTC * DP;                               // [k][QW]
-  int32_t* bi = reinterpret_cast<int32_t*>(bd + (size_t)k * QW); // [k][QW]
+  double* bd = lds;                                   // [k][kMq]
+  double* thrq = bd + (size_t)k * kMq;                // [kMq]      thresholds of the last walk
+  unsigned long long* mask = reinterpret_cast<unsigned long long*>(thrq + kMq);  // [kRound][kMq]
+  int32_t* bi = reinterpret_cast<int32_t*>(mask + kRound * kMq);                 // [k][kMq]
   const int tid = threadIdx.x;
-  int64_t qi[NQ];       // this thread's queries: one in each block of kQ consecutive points
-  int col[NQ];          // and their columns of the lists
-  double q[NQ][DP];
-  double thr[NQ];       // the worst of the kept candidates: (thr, thr_idx) in slot thr_slot; a dead query accepts nothing
-  int32_t thr_idx[NQ];
-  int thr_slot[NQ];
-#pragma unroll
-  for (int v = 0; v < NQ; ++v) {
-    qi[v] = (int64_t)blockIdx.x * QW + v * kQ + tid;
-    col[v] = v * kQ + tid;
-    const bool live = qi[v] < n;
-#pragma unroll
-    for (int t = 0; t < DP; ++t) q[v][t] = live ? xp[qi[v] * DP + t] : 0.0;
-    for (int s = 0; s < k; ++s) {
-      bd[s * QW + col[v]] = INFINITY;
-      bi[s * QW + col[v]] = INT32_MAX;
-    }
-    thr[v] = live ? INFINITY : -1.0;
-    thr_idx[v] = INT32_MAX;
-    thr_slot[v] = 0;
-  }
+  const int wave = tid >> 6, lane = tid & 63, i = lane & 15, g = lane >> 4;
+  const int64_t q0 = (int64_t)blockIdx.x * kMq;
   const double2* __restrict__ xp2 = reinterpret_cast<const double2*>(xp);
-  const int64_t total2 = n * (DP / 2);
-  const int64_t ntile = (n + kTC - 1) / kTC;
-  double2 pre[NPRE];
-#pragma unroll
-  for (int u = 0; u < NPRE; ++u) {
-    const int e = tid + u * kQ;
-    if (e < TD2) yt[e] = e < total2 ? xp2[e] : double2{0.0, 0.0};
+
+  // setup: lists, thresholds, masks
+  for (int e = tid; e < k * kMq; e += kMt) {
+    bd[e] = INFINITY;
+    bi[e] = INT32_MAX;
   }
-  __syncthreads();
-  for (int64_t tile = 0; tile < ntile; ++tile) {
-    const int buf = (int)(tile & 1);
-    // the next tile's rows, requested now and parked in LDS after this tile's arithmetic
+  for (int e = tid; e < kRound * kMq; e += kMt) mask[e] = 0ull;
+  if (tid < kMq) thrq[tid] = q0 + tid < n ? INFINITY : -INFINITY;  // a query past the end lets nothing through
+  // this lane's part of the A operand: query 16 wave + i, coordinates 8m + 2g, 8m + 2g + 1
+  double a[NS];
+  {
+    const int64_t qrow = q0 + 16 * wave + i < n ? q0 + 16 * wave + i : n - 1;
 #pragma unroll
-    for (int u = 0; u < NPRE; ++u) {
-      const int e = tid + u * kQ;
-      const int64_t g = (tile + 1) * TD2 + e;
-      pre[u] = (e < TD2 && g < total2) ? xp2[g] : double2{0.0, 0.0};
+    for (int m = 0; m < NS / 2; ++m) {
+      const double2 v = xp2[(qrow * DP + 8 * m + 2 * g) / 2];
+      a[2 * m] = v.x;
+      a[2 * m + 1] = v.y;
     }
-    const double2* __restrict__ yb = yt + buf * TD2;
-    // The tile is walked in pieces of kJU candidates x CH coordinates.  The LDS reads of a piece are issued at the top
-    // of the piece before it (the first statements behind an asm statement, which the scheduler does not move code
-    // across), so they are long back when the piece is used; the sums are pinned every two coordinates.
-    constexpr int CH = NQ == 2 ? 4 : 8;       // coordinates per piece (DP is a multiple of 8)
-    constexpr int NPC = DP / CH;              // pieces per candidate group
-    constexpr int NG = kTC / kJU;             // candidate groups per tile
-    double2 yp[2][kJU][CH / 2];
+  }
+  // the queries whose results this lane holds after an MFMA: 16 wave + 4 rr + g
+  double qn[4];
+  int64_t qidx[4];
 #pragma unroll
-    for (int u = 0; u < kJU; ++u)
+  for (int rr = 0; rr < 4; ++rr) {
+    qidx[rr] = q0 + 16 * wave + 4 * rr + g;
+    qn[rr] = qidx[rr] < n ? xn[qidx[rr]] : 0.0;
+  }
+  // the walking lanes' state: lanes 0..15 of every wave, one of the wave's queries each.  A wave screens and walks
+  // on its own: after the setup no barrier joins the four waves, so one wave's walk does not hold up the others.
+  double thr = INFINITY;
+  int32_t thr_idx = INT32_MAX;
+  int thr_slot = 0;
+  const int myql = 16 * wave + lane;  // meaningful for lane < 16
+  const int64_t myq = q0 + myql;
+  __syncthreads();
+
+  const int64_t nstep = (n + 63) / 64;
+  double2 b0[4][NSC / 2], b1[4][NSC / 2];
 #pragma unroll
-      for (int h = 0; h < CH / 2; ++h) yp[0][u][h] = yb[u * (DP / 2) + h];  // the same address in every lane
-    double acc[NQ][kJU];
+  for (int cb = 0; cb < 4; ++cb) {
+    const int64_t c = 16 * cb + i < n ? 16 * cb + i : n - 1;
 #pragma unroll
-    for (int p = 0; p < NG * NPC; ++p) {
-      const int g = p / NPC, pc = p % NPC, cur = p & 1;
-      if (pc == 0) {
+    for (int m = 0; m < NSC / 2; ++m) b0[cb][m] = xp2[(c * DP + 8 * m + 2 * g) / 2];
+  }
+  d4 acc[4];
+  double yn[4];
+  // one piece (KC coordinates) of a step of 64 candidates: operands in bcur, the next piece's are fetched into bnxt
+  auto do_piece = [&](double2 (&bcur)[4][NSC / 2], double2 (&bnxt)[4][NSC / 2], int64_t step, int kc)
+                      __attribute__((always_inline)) {
+    const int64_t c0 = step * 64;
+    {  // the next piece: the next coordinates of this step, or the first of the next step.  Rows are clamped to the
+       // last one: straight-line loads, masked out by the index test of the screen.
+      const int kcn = kc + 1 < NCH ? kc + 1 : 0;
+      const int64_t cn = kc + 1 < NCH ? c0 : c0 + 64;
 #pragma unroll
-        for (int v = 0; v < NQ; ++v)
+      for (int cb = 0; cb < 4; ++cb) {
+        int64_t c = cn + 16 * cb + i;
+        c = c < n ? c : n - 1;
 #pragma unroll
-          for (int u = 0; u < kJU; ++u) acc[v][u] = 0.0;
+        for (int m = 0; m < NSC / 2; ++m) bnxt[cb][m] = xp2[(c * DP + kcn * KC + 8 * m + 2 * g) / 2];
       }
-      if (p + 1 < NG * NPC) {  // the next piece's reads
-        const int g1 = (p + 1) / NPC, pc1 = (p + 1) % NPC;
+    }
+    if (kc == 0) {
 #pragma unroll
-        for (int u = 0; u < kJU; ++u)
-#pragma unroll
-          for (int h = 0; h < CH / 2; ++h)
-            yp[cur ^ 1][u][h] = yb[(g1 * kJU + u) * (DP / 2) + pc1 * (CH / 2) + h];
+      for (int cb = 0; cb < 4; ++cb) {
+        acc[cb] = (d4){0.0, 0.0, 0.0, 0.0};
+        const int64_t c = c0 + 16 * cb + i;
+        yn[cb] = xn[c < n ? c : n - 1];  // used after the step's MFMAs
       }
+    }
+    // four independent accumulators between two MFMAs on the same one
 #pragma unroll
-      for (int h = 0; h < CH / 2; ++h) {
-        const int t = pc * CH + 2 * h;
+    for (int m = 0; m < NSC / 2; ++m) {
 #pragma unroll
-        for (int u = 0; u < kJU; ++u) {
+      for (int cb = 0; cb < 4; ++cb) acc[cb] = MFMA_F64(a[kc * NSC + 2 * m], bcur[cb][m].x, acc[cb]);
 #pragma unroll
-          for (int v = 0; v < NQ; ++v) {
-            const double d0 = q[v][t] - yp[cur][u][h].x;
-            acc[v][u] = fma(d0, d0, acc[v][u]);
-            const double d1 = q[v][t + 1] - yp[cur][u][h].y;
-            acc[v][u] = fma(d1, d1, acc[v][u]);
-          }
+      for (int cb = 0; cb < 4; ++cb) acc[cb] = MFMA_F64(a[kc * NSC + 2 * m + 1], bcur[cb][m].y, acc[cb]);
+    }
+    if (kc != NCH - 1) return;
+    const int sr = (int)(step % kRound);
+    // only the last step has candidates past the end, only the step with the workgroup's own rows a query's self
+    const bool edge = (c0 + 64 > n) | ((c0 < q0 + kMq) & (c0 + 64 > q0));  // uniform
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int ql = 16 * wave + 4 * rr + g;
+      const double tq = thrq[ql];
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb) {
+        const double sum = qn[rr] + yn[cb];
+        const double d2 = fma(-2.0, acc[cb][rr], sum);
+        bool pass = d2 < fma(kMargin, sum, tq);
+        if (edge) {
+          const int64_t c = c0 + 16 * cb + i;
+          pass = pass & (c < n) & (c != qidx[rr]);
         }
-        // all the sums advance together, two coordinates at a time: left alone, the compiler finishes one candidate's
-        // chain of dependent multiply-adds before it starts the next and the loop runs at the latency of one
-#pragma unroll
-        for (int v = 0; v < NQ; ++v) asm volatile("" : "+v"(acc[v][0]), "+v"(acc[v][1]), "+v"(acc[v][2]), "+v"(acc[v][3]));
+        if (pass) atomicOr(&mask[sr * kMq + ql], 1ull << (16 * cb + i));
       }
-      if (pc == NPC - 1) {
-        const int c0 = g * kJU;
-#pragma unroll
-        for (int v = 0; v < NQ; ++v)
-#pragma unroll
-          for (int u = 0; u < kJU; ++u) {
-            const int64_t j = tile * kTC + c0 + u;
-            const double a = acc[v][u];
-            // bitwise, not short-circuit: the sums above must not be moved behind a test of j
-            const bool pass = (j < n) & (j != qi[v]) & ((a < thr[v]) | ((a == thr[v]) & ((int32_t)j < thr_idx[v])));
-            if (pass) {
-              bd[thr_slot[v] * QW + col[v]] = a;
-              bi[thr_slot[v] * QW + col[v]] = (int32_t)j;
+    }
+    if (sr == kRound - 1 || step == nstep - 1) {  // uniform
+      // the wave's own LDS operations complete in order; the fence keeps the compiler from moving them
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      if (lane < 16 && myq < n) {
+        const int cq = myql;   // this lane's column of the per-query arrays
+        const int64_t cbase = (step - sr) * 64;
+        for (int st = 0; st <= sr; ++st) {
+          unsigned long long mbits = mask[st * kMq + cq];
+          mask[st * kMq + cq] = 0ull;
+          while (mbits) {
+            const int bit = __ffsll((long long)mbits) - 1;
+            mbits &= mbits - 1;
+            const int64_t j = cbase + st * 64 + bit;
+            double ex = 0.0;
+            const double2* __restrict__ qr = xp2 + myq * (DP / 2);
+            const double2* __restrict__ yr = xp2 + j * (DP / 2);
+#pragma unroll 4
+            for (int t = 0; t < DP / 2; ++t) {  // rarely run: kept small, the registers belong to the MFMA loop
+              const double2 qv = qr[t], yv = yr[t];
+              const double d0 = qv.x - yv.x;
+              ex = fma(d0, d0, ex);
+              const double d1 = qv.y - yv.y;
+              ex = fma(d1, d1, ex);
+            }
+            if (ex < thr || (ex == thr && (int32_t)j < thr_idx)) {
+              bd[thr_slot * kMq + cq] = ex;
+              bi[thr_slot * kMq + cq] = (int32_t)j;
               double w = -1.0;
               int32_t wid = INT32_MAX;
               int ws = 0;
               for (int s = 0; s < k; ++s) {
-                const double x = bd[s * QW + col[v]];
-                const int32_t id = bi[s * QW + col[v]];
+                const double x = bd[s * kMq + cq];
+                const int32_t id = bi[s * kMq + cq];
                 if (x > w || (x == w && id > wid)) {
                   w = x;
                   wid = id;
                   ws = s;
                 }
               }
-              thr[v] = w;
-              thr_idx[v] = wid;
-              thr_slot[v] = ws;
+              thr = w;
+              thr_idx = wid;
+              thr_slot = ws;
             }
           }
-      }
-    }
-    double2* yn = yt + (buf ^ 1) * TD2;
-#pragma unroll
-    for (int u = 0; u < NPRE; ++u) {
-      const int e = tid + u * kQ;
-      if (e < TD2) yn[e] = pre[u];
-    }
-    __syncthreads();  // every thread, dead queries included, passes here once per tile
-  }
-#pragma unroll
-  for (int v = 0; v < NQ; ++v) {
-    if (qi[v] >= n) continue;
-    const int cq = col[v];
-    for (int a = 0; a < k; ++a) {  // nearest first (ties: lower index first): selection sort of the k slots
-      int best = a;
-      double bv = bd[a * QW + cq];
-      int32_t bid = bi[a * QW + cq];
-      for (int s = a + 1; s < k; ++s) {
-        const double x = bd[s * QW + cq];
-        const int32_t id = bi[s * QW + cq];
-        if (x < bv || (x == bv && id < bid)) {
-          best = s;
-          bv = x;
-          bid = id;
         }
+        thrq[cq] = thr;
       }
-      bd[best * QW + cq] = bd[a * QW + cq];
-      bi[best * QW + cq] = bi[a * QW + cq];
-      bd[a * QW + cq] = bv;
-      bi[a * QW + cq] = bid;
-      idx_out[qi[v] * k + a] = bid == INT32_MAX ? -1 : bid;
-      dist_out[qi[v] * k + a] = sqrt(bv);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
+  };
+  if constexpr (NCH == 1) {
+    for (int64_t step = 0; step < nstep; step += 2) {
+      do_piece(b0, b1, step, 0);
+      if (step + 1 < nstep) do_piece(b1, b0, step + 1, 0);
+    }
+  } else {  // an even number of pieces per step: every step starts on b0
+    for (int64_t step = 0; step < nstep; ++step) {
+#pragma unroll
+      for (int kc = 0; kc < NCH; kc += 2) {
+        do_piece(b0, b1, step, kc);
+        do_piece(b1, b0, step, kc + 1);
+      }
+    }
+  }
+  if (lane >= 16 || myq >= n) return;
+  const int tidq = myql;
+  for (int aidx = 0; aidx < k; ++aidx) {  // nearest first (ties: lower index first): selection sort of the k slots
+    int best = aidx;
+    double bv = bd[aidx * kMq + tidq];
+    int32_t bid = bi[aidx * kMq + tidq];
+    for (int s = aidx + 1; s < k; ++s) {
+      const double x = bd[s * kMq + tidq];
+      const int32_t id = bi[s * kMq + tidq];
+      if (x < bv || (x == bv && id < bid)) {
+        best = s;
+        bv = x;
+        bid = id;
+      }
+    }
+    bd[best * kMq + tidq] = bd[aidx * kMq + tidq];
+    bi[best * kMq + tidq] = bi[aidx * kMq + tidq];
+    bd[aidx * kMq + tidq] = bv;
+    bi[aidx * kMq + tidq] = bid;
+    idx_out[myq * k + aidx] = bid == INT32_MAX ? -1 : bid;
+    dist_out[myq * k + aidx] = sqrt(bv);
   }
 }
 
@@ -337,13 +396,15 @@ __global__ __launch_bounds__(kT) void pair_emit_kernel(const int32_t* __restrict
 
 }  // namespace
 
-int knn_padded_dim(int d) { return d <= 8 ? 8 : d <= 16 ? 16 : d <= 32 ? 32 : (d + kDC - 1) / kDC * kDC; }
+int knn_padded_dim(int d) {
+  return d <= 8 ? 8 : d <= 16 ? 16 : d <= 32 ? 32 : d <= 64 ? 64 : d <= 128 ? 128 : (d + kDC - 1) / kDC * kDC;
+}
 
 size_t knn_search_lds_bytes(int d, int k) {
-  const size_t lists = (size_t)kQ * k * (sizeof(double) + sizeof(int32_t));
   const int dp = knn_padded_dim(d);
-  if (dp <= 32) return lists + 2 * (size_t)kTC * dp * sizeof(double);  // two candidate tiles
-  return lists + (size_t)kQ * dp * sizeof(double);                     // the queries
+  if (dp <= 128)  // distances, thresholds, masks, indices of the MFMA kernel
+    return 8 * ((size_t)k * kMq + kMq + kRound * kMq) + 4 * (size_t)k * kMq;
+  return (size_t)kQ * ((size_t)dp * sizeof(double) + (size_t)k * (sizeof(double) + sizeof(int32_t)));
 }
 
 hipError_t launch_knn_search(const double* x, int64_t ldx, int64_t n, int d, int k, double* xp, int32_t* idx_out,
@@ -358,36 +419,35 @@ hipError_t launch_knn_search(const double* x, int64_t ldx, int64_t n, int d, int
   if (e != hipSuccess) return e;
   if (lds > (size_t)lds_max) return hipErrorInvalidValue;
   hipLaunchKernelGGL(pad_rows_kernel, dim3(blocks(n * dp)), dim3(kT), 0, st, x, ldx, n, d, dp, xp);
-#define SC_KNN_TILE(DPV, NQV)                                                                                  \
+  if (dp <= 128) {
+    double* xn = xp + (size_t)n * dp;
+    hipLaunchKernelGGL(row_norms_kernel, dim3(blocks(n)), dim3(kT), 0, st, xp, n, dp, xn);
+    const size_t l = lds;
+    const dim3 grid((unsigned)((n + kMq - 1) / kMq));
+#define SC_KNN_MFMA(DPV)                                                                                       \
   do {                                                                                                         \
-    const size_t l = lds + (NQV - 1) * (size_t)kQ * k * 12;                                                    \
     if (l > 64 * 1024) {                                                                                       \
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&knn_tile_kernel<DPV, NQV>),                       \
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&knn_mfma_kernel<DPV>),                            \
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)l);                             \
       if (e != hipSuccess) return e;                                                                           \
     }                                                                                                          \
-    hipLaunchKernelGGL((knn_tile_kernel<DPV, NQV>), dim3((unsigned)((n + kQ * NQV - 1) / (kQ * NQV))), dim3(kQ), l, \
-                       st, xp, n, k, idx_out, dist_out);                                                       \
+    hipLaunchKernelGGL(knn_mfma_kernel<DPV>, grid, dim3(kMt), l, st, xp, xn, n, k, idx_out, dist_out);         \
   } while (0)
-  // one query per thread: with two (NQ = 2) every LDS read feeds twice the arithmetic, but the lists of 256 queries
-  // leave room for two workgroups per compute unit only (one wave per SIMD), and the search of 100,000 points in 32
-  // dimensions took 69 ms instead of 50 ms
-  if (dp == 8) {
-    SC_KNN_TILE(8, 1);
-  } else if (dp == 16) {
-    SC_KNN_TILE(16, 1);
-  } else if (dp == 32) {
-    SC_KNN_TILE(32, 1);
-  } else {
-    if (lds > 64 * 1024) {
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&knn_search_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL(knn_search_kernel, dim3((unsigned)((n + kQ - 1) / kQ)), dim3(kQ), lds, st, xp, n, dp, k,
-                       idx_out, dist_out);
+    if (dp == 8) SC_KNN_MFMA(8);
+    else if (dp == 16) SC_KNN_MFMA(16);
+    else if (dp == 32) SC_KNN_MFMA(32);
+    else if (dp == 64) SC_KNN_MFMA(64);
+    else SC_KNN_MFMA(128);
+#undef SC_KNN_MFMA
+    return hipGetLastError();
   }
-#undef SC_KNN_TILE
+  if (lds > 64 * 1024) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&knn_search_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(knn_search_kernel, dim3((unsigned)((n + kQ - 1) / kQ)), dim3(kQ), lds, st, xp, n, dp, k, idx_out,
+                     dist_out);
   return hipGetLastError();
 }
 

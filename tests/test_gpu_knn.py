@@ -43,7 +43,7 @@ def _check_search(B, x, k):
 # several workgroups of 128 queries and a ragged last one; candidate counts not a multiple of 4; padded and unpadded
 # dimensions; k from 1 to all the other points
 @pytest.mark.parametrize("n,d,k", [(1500, 5, 7), (1003, 3, 1), (130, 33, 20), (641, 16, 10), (20, 2, 19), (2, 1, 1),
-                                   (515, 128, 10), (300, 8, 32),
+                                   (515, 128, 10), (300, 8, 32), (300, 130, 5), (700, 64, 12), (333, 100, 3),
                                    # many workgroups, many candidate tiles
                                    (8300, 8, 5), (8450, 32, 12), (9001, 13, 10)])
 def test_search_matches_oracle(B, n, d, k):
@@ -84,7 +84,7 @@ def test_search_strided_rows_and_errors(B):
     assert lib.sc_knn_search(x.data_ptr(), 5, n, d, k, io.data_ptr(), do.data_ptr(), st) == -2      # ldx < d
     assert lib.sc_knn_search(x.data_ptr(), 9, 1, d, 1, io.data_ptr(), do.data_ptr(), st) == -2      # one point
     assert lib.sc_knn_search(0, 9, n, d, k, io.data_ptr(), do.data_ptr(), st) == -1                 # null pointer
-    assert lib.sc_knn_search(x.data_ptr(), 9, n, 160, 5, io.data_ptr(), do.data_ptr(), st) == -2    # LDS: d too large
+    assert lib.sc_knn_search(x.data_ptr(), 9, n, 6, 250, io.data_ptr(), do.data_ptr(), st) == -2    # LDS: k_nn too large
 
 
 @pytest.mark.parametrize("n,d,k,sigma", [(1200, 4, 6, 0.0), (777, 10, 15, 1.3), (50, 2, 49, 0.5)])
