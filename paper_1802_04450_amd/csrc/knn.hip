@@ -281,7 +281,7 @@ __global__ __launch_bounds__(kMt) __attribute__((amdgpu_waves_per_eu(2))) void k
             double ex = 0.0;
             const double2* __restrict__ qr = xp2 + myq * (DP / 2);
             const double2* __restrict__ yr = xp2 + j * (DP / 2);
-#pragma unroll 4
+#pragma unroll 8
             for (int t = 0; t < DP / 2; ++t) {  // rarely run: kept small, the registers belong to the MFMA loop
               const double2 qv = qr[t], yv = yr[t];
               const double d0 = qv.x - yv.x;
