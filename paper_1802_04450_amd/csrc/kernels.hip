@@ -532,7 +532,47 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const double* __restr
   const bool full = vec_ok && (cbase + 3 < ja);
   // four row-quads (16 rows) per trip: all their loads are issued before the first MFMA needs them
   constexpr int U = 4;
-  for (int64_t r = r0; r < r1; r += 4 * U) {
+  int64_t rstart = r0;
+  // Interior waves (all 64 columns and all 16 NT block columns present, vector loads allowed) run the whole trips of
+  // their row slice without a branch round any load: the operands of the next trip are requested before the MFMAs of
+  // this one (the last request reads the slice's last rows again and is dropped).  With conditional loads the compiler
+  // has to wait for every load in flight before the first MFMA, so a wave alternates between loading and multiplying.
+  if (vec_ok && c0 + 64 <= ja && b == 16 * NT && r1 - r0 >= 4 * U) {  // wave-uniform
+    const int64_t rfull = r0 + (r1 - r0) / (4 * U) * (4 * U);
+    const int64_t rlast = rfull - 4 * U;  // first row of the last whole trip
+    const double* __restrict__ abase = basis + acol0 + cbase;
+    const double* __restrict__ bbase = basis + bcol0 + i;
+    d4 a0[U], a1[U];
+    double v0[U][NT], v1[U][NT];
+    auto fetch = [&](d4 (&av)[U], double (&vv)[U][NT], int64_t r) __attribute__((always_inline)) {
+      const int64_t rr = r < rlast ? r : rlast;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t row = rr + 4 * u + g;
+        av[u] = *reinterpret_cast<const d4*>(abase + row * ld);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) vv[u][nt] = bbase[row * ld + 16 * nt];
+      }
+    };
+    auto mult = [&](const d4 (&av)[U], const double (&vv)[U][NT]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) acc[nt][q] = MFMA_F64(av[u][q], vv[u][nt], acc[nt][q]);
+    };
+    fetch(a0, v0, r0);
+    for (int64_t r = r0; r < rfull; r += 8 * U) {
+      fetch(a1, v1, r + 4 * U);
+      mult(a0, v0);
+      if (r + 4 * U >= rfull) break;
+      fetch(a0, v0, r + 8 * U);
+      mult(a1, v1);
+    }
+    rstart = rfull;
+  }
+  for (int64_t r = rstart; r < r1; r += 4 * U) {
     double a[U][4];
     double bv[U][NT];
 #pragma unroll
@@ -977,8 +1017,49 @@ __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restric
         load_chunk(k0, kc, kc16);
         __syncthreads();
       }
+      int kk0 = 0;
+      // A wave whose 32 rows all exist runs the whole 32-index trips of the chunk without a branch round any load:
+      // the operands of the next trip are requested before the MFMAs of this one (the last request repeats the last
+      // trip's and is dropped).  Behind conditional loads the compiler waits for every load in flight before the
+      // first MFMA.
+      if (vec_ok && row0 + 16 * MT <= n && kc >= 32) {  // wave-uniform
+        const int kfull = kc / 32 * 32;
+        const double* __restrict__ abase = basis + (row0 + i) * ld + acol0 + k0 + 4 * g;
+        d4 a0[2][MT], a1[2][MT];
+        auto fetch = [&](d4 (&av)[2][MT], int kb) __attribute__((always_inline)) {
+          const int kq = kb < kfull - 32 ? kb : kfull - 32;
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              av[h][mt] = *reinterpret_cast<const d4*>(abase + (int64_t)mt * 16 * ld + kq + 16 * h);
+        };
+        auto mult = [&](const d4 (&av)[2][MT], int kb) __attribute__((always_inline)) {
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const int kt = (kb >> 4) + h;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+              for (int nt = 0; nt < NT; ++nt) {
+                const double bq = lds[((((kt * 4 + q) * NT + nt) * 4 + g) << 4) + i];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = MFMA_F64(av[h][mt][q], bq, acc[mt][nt]);
+              }
+          }
+        };
+        fetch(a0, 0);
+        for (int kb = 0; kb < kfull; kb += 64) {
+          fetch(a1, kb + 32);
+          mult(a0, kb);
+          if (kb + 32 >= kfull) break;
+          fetch(a0, kb + 64);
+          mult(a1, kb + 32);
+        }
+        kk0 = kfull;
+      }
       // two 16-index groups per trip: their loads are issued together, ahead of the MFMAs that use them
-      for (int kk = 0; kk < kc16; kk += 32) {
+      for (int kk = kk0; kk < kc16; kk += 32) {
         double a[2][MT][4];
   #pragma unroll
         for (int h = 0; h < 2; ++h) {
