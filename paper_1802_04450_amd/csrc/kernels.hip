@@ -533,14 +533,15 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const double* __restr
   // four row-quads (16 rows) per trip: all their loads are issued before the first MFMA needs them
   constexpr int U = 4;
   int64_t rstart = r0;
-  // Interior waves (all 64 columns and all 16 NT block columns present, vector loads allowed) run the whole trips of
-  // their row slice without a branch round any load: the operands of the next trip are requested before the MFMAs of
+  // With all 16 NT block columns present and vector loads allowed, a wave runs the whole trips of its row slice
+  // without a branch round any load: the operands of the next trip are requested before the MFMAs of
   // this one (the last request reads the slice's last rows again and is dropped).  With conditional loads the compiler
   // has to wait for every load in flight before the first MFMA, so a wave alternates between loading and multiplying.
-  if (vec_ok && c0 + 64 <= ja && b == 16 * NT && r1 - r0 >= 4 * U) {  // wave-uniform
+  if (vec_ok && ja % 4 == 0 && b == 16 * NT && r1 - r0 >= 4 * U) {  // wave-uniform
     const int64_t rfull = r0 + (r1 - r0) / (4 * U) * (4 * U);
     const int64_t rlast = rfull - 4 * U;  // first row of the last whole trip
-    const double* __restrict__ abase = basis + acol0 + cbase;
+    // lanes whose four columns lie past ja read the last four instead: their results are never stored
+    const double* __restrict__ abase = basis + acol0 + (cbase + 3 < ja ? cbase : ja - 4);
     const double* __restrict__ bbase = basis + bcol0 + i;
     d4 a0[U], a1[U];
     double v0[U][NT], v1[U][NT];
@@ -1018,45 +1019,51 @@ __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restric
         __syncthreads();
       }
       int kk0 = 0;
-      // A wave whose 32 rows all exist runs the whole 32-index trips of the chunk without a branch round any load:
-      // the operands of the next trip are requested before the MFMAs of this one (the last request repeats the last
-      // trip's and is dropped).  Behind conditional loads the compiler waits for every load in flight before the
+      // A wave whose 32 rows all exist runs the trips of the chunk without a branch round any load: the operands of
+      // the next trip are requested before the MFMAs of this one (the last request repeats the last trip's and is
+      // dropped).  Behind conditional loads the compiler waits for every load in flight before the
       // first MFMA.
-      if (vec_ok && row0 + 16 * MT <= n && kc >= 32) {  // wave-uniform
-        const int kfull = kc / 32 * 32;
-        const double* __restrict__ abase = basis + (row0 + i) * ld + acol0 + k0 + 4 * g;
+      if (vec_ok && row0 + 16 * MT <= n && kdim % 4 == 0) {  // wave-uniform
+        const int klast = (kc16 - 1) / 32 * 32;  // start of the chunk's last trip
+        const double* __restrict__ abase = basis + (row0 + i) * ld + acol0;
         d4 a0[2][MT], a1[2][MT];
+        // columns past kdim are read from the last four instead: their B rows in LDS are zero (or skipped)
         auto fetch = [&](d4 (&av)[2][MT], int kb) __attribute__((always_inline)) {
-          const int kq = kb < kfull - 32 ? kb : kfull - 32;
+          const int kq = kb < klast ? kb : klast;
 #pragma unroll
-          for (int h = 0; h < 2; ++h)
+          for (int h = 0; h < 2; ++h) {
+            int kcol = k0 + kq + 16 * h + 4 * g;
+            kcol = kcol + 3 < kdim ? kcol : kdim - 4;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-              av[h][mt] = *reinterpret_cast<const d4*>(abase + (int64_t)mt * 16 * ld + kq + 16 * h);
+              av[h][mt] = *reinterpret_cast<const d4*>(abase + (int64_t)mt * 16 * ld + kcol);
+          }
         };
         auto mult = [&](const d4 (&av)[2][MT], int kb) __attribute__((always_inline)) {
 #pragma unroll
           for (int h = 0; h < 2; ++h) {
-            const int kt = (kb >> 4) + h;
+            if (kb + 16 * h < kc16) {  // uniform; the LDS slots beyond kc16 were not filled
+              const int kt = (kb >> 4) + h;
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+              for (int q = 0; q < 4; ++q)
 #pragma unroll
-              for (int nt = 0; nt < NT; ++nt) {
-                const double bq = lds[((((kt * 4 + q) * NT + nt) * 4 + g) << 4) + i];
+                for (int nt = 0; nt < NT; ++nt) {
+                  const double bq = lds[((((kt * 4 + q) * NT + nt) * 4 + g) << 4) + i];
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = MFMA_F64(av[h][mt][q], bq, acc[mt][nt]);
-              }
+                  for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = MFMA_F64(av[h][mt][q], bq, acc[mt][nt]);
+                }
+            }
           }
         };
         fetch(a0, 0);
-        for (int kb = 0; kb < kfull; kb += 64) {
+        for (int kb = 0; kb < kc16; kb += 64) {
           fetch(a1, kb + 32);
           mult(a0, kb);
-          if (kb + 32 >= kfull) break;
+          if (kb + 32 >= kc16) break;
           fetch(a0, kb + 64);
           mult(a1, kb + 32);
         }
-        kk0 = kfull;
+        kk0 = kc16;
       }
       // two 16-index groups per trip: their loads are issued together, ahead of the MFMAs that use them
       for (int kk = kk0; kk < kc16; kk += 32) {
