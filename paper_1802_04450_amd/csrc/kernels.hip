@@ -705,53 +705,8 @@ __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__
       lds[((((kt * 4 + q) * NT + nt) * 4 + gg) << 4) + ii] = v;
     }
     __syncthreads();
-    int kk0 = 0;
-    // A wave whose rows all exist runs the trips of the chunk without a branch round any load: the operands of the
-    // next trip are requested before the MFMAs of this one (the last request repeats the last trip's and is dropped);
-    // columns past kdim are read from the last four instead: their B rows in LDS are zero (or skipped).
-    if (vec_ok && row0 + 16 * MT <= n && kdim % 4 == 0) {  // wave-uniform
-      const int klast = (kc16 - 1) / 32 * 32;  // start of the chunk's last trip
-      const double* __restrict__ abase = basis + (row0 + i) * ld + acol0;
-      d4 a0[2][MT], a1[2][MT];
-      auto fetch = [&](d4 (&av)[2][MT], int kb) __attribute__((always_inline)) {
-        const int kq = kb < klast ? kb : klast;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          int kcol = k0 + kq + 16 * h + 4 * g;
-          kcol = kcol + 3 < kdim ? kcol : kdim - 4;
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-            av[h][mt] = *reinterpret_cast<const d4*>(abase + (int64_t)mt * 16 * ld + kcol);
-        }
-      };
-      auto mult = [&](const d4 (&av)[2][MT], int kb) __attribute__((always_inline)) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          if (kb + 16 * h < kc16) {  // uniform; the LDS slots beyond kc16 were not filled
-            const int kt = (kb >> 4) + h;
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-              for (int nt = 0; nt < NT; ++nt) {
-                const double bq = lds[((((kt * 4 + q) * NT + nt) * 4 + g) << 4) + i];
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = MFMA_F64(av[h][mt][q], bq, acc[mt][nt]);
-              }
-          }
-        }
-      };
-      fetch(a0, 0);
-      for (int kb = 0; kb < kc16; kb += 64) {
-        fetch(a1, kb + 32);
-        mult(a0, kb);
-        if (kb + 32 >= kc16) break;
-        fetch(a0, kb + 64);
-        mult(a1, kb + 32);
-      }
-      kk0 = kc16;
-    }
     // two 16-index groups per trip: their loads are issued together, ahead of the MFMAs that use them
-    for (int kk = kk0; kk < kc16; kk += 32) {
+    for (int kk = 0; kk < kc16; kk += 32) {
       double a[2][MT][4];
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
