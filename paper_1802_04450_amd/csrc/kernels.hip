@@ -966,7 +966,9 @@ __global__ __launch_bounds__(kThreads) void cheb_combine_kernel(const double* __
 // and bmat = R^-1 this is the scaling pass W <- W R^-1 of the Cholesky QR (a wave reads its own 32 rows of the
 // block completely before it writes them).
 // Workgroups walk the 128-row tiles with a grid stride, so the number of Gram partials is the grid size.
-template <int NT>
+// PIPE: the variant for long contractions, see the note at its loop.  It needs more registers (fewer resident waves),
+// which costs more than it gains when the contraction has only a trip or two, so it is a kernel of its own.
+template <int NT, bool PIPE>
 __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
                                                                int acol0, int kdim, const double* __restrict__ bmat, int b,
                                                                int ccol0, int vec_ok, int overwrite,
@@ -1023,7 +1025,7 @@ __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restric
       // the next trip are requested before the MFMAs of this one (the last request repeats the last trip's and is
       // dropped).  Behind conditional loads the compiler waits for every load in flight before the
       // first MFMA.
-      if (vec_ok && row0 + 16 * MT <= n && kdim % 4 == 0) {  // wave-uniform
+      if (PIPE && vec_ok && row0 + 16 * MT <= n && kdim % 4 == 0) {  // wave-uniform
         const int klast = (kc16 - 1) / 32 * 32;  // start of the chunk's last trip
         const double* __restrict__ abase = basis + (row0 + i) * ld + acol0;
         d4 a0[2][MT], a1[2][MT];
@@ -1523,13 +1525,16 @@ hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, i
                               int ccol0, int overwrite, double* gpart, hipStream_t st) {
   const int vec_ok = (ld % 4 == 0 && acol0 % 4 == 0 && (reinterpret_cast<uintptr_t>(basis) % 32 == 0)) ? 1 : 0;
   const unsigned grid = (unsigned)plan_update_gram(n);
+  const bool pipe = kdim >= 128;  // loads one trip ahead pay from a few trips on
+#define SC_LAUNCH_UG(NTV, PV)                                                                                     \
+  hipLaunchKernelGGL((update_gram_kernel<NTV, PV>), dim3(grid), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, \
+                     bmat, b, ccol0, vec_ok, overwrite, gpart)
   if (b <= 16) {
-    hipLaunchKernelGGL((update_gram_kernel<1>), dim3(grid), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, bmat, b,
-                       ccol0, vec_ok, overwrite, gpart);
+    if (pipe) SC_LAUNCH_UG(1, true); else SC_LAUNCH_UG(1, false);
   } else {
-    hipLaunchKernelGGL((update_gram_kernel<2>), dim3(grid), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, bmat, b,
-                       ccol0, vec_ok, overwrite, gpart);
+    if (pipe) SC_LAUNCH_UG(2, true); else SC_LAUNCH_UG(2, false);
   }
+#undef SC_LAUNCH_UG
   return hipGetLastError();
 }
 
