@@ -152,13 +152,14 @@ __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __re
     }
   }
   for (int64_t e = e0 + e_first; e < e1; e += e_step) {
-    // lanes past the end of the row carry (column 0, value 0): their products vanish
-    int32_t c = 0;
-    double a = 0.0;
-    if (e + lane < e1) {
-      c = col[e + lane];
-      a = val[e + lane];
-    }
+    // Lanes past the end of the row load the row's last entry again and take the value 0: their products vanish.
+    // The loads are unconditional on purpose: defaults written to the same registers before a conditional load make
+    // the compiler wait for every load still in flight (the recurrence's own-row operands, requested above) before
+    // this one is even issued.
+    const int64_t el = e + lane < e1 ? e + lane : e1 - 1;
+    const int32_t c = col[el];
+    const double av = val[el];
+    const double a = e + lane < e1 ? av : 0.0;
     // The batch's entries go round-robin to the NS sub-groups (entry r*NS + g to sub-group g in round r), so a batch
     // of cnt entries costs ceil(cnt / NS) gather instructions: a row of 24 entries takes 6 rounds at B = 16, the
     // one-entry tail of a row of 33 takes 1.
