@@ -674,7 +674,8 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double*
 // A wave owns MT*16 rows and NT*16 output columns.  Per step of 16 contraction indices lane (i, g)
 // loads A[row0+i][k + 4g .. 4g+3]; MFMA q contracts over the indices k + 4g + q, g = 0..3.  The Bm
 // chunk sits in LDS permuted so that the 64 lanes of one MFMA read 64 consecutive doubles.
-template <int NT, int MT>
+// PIPE: loads one trip ahead of the MFMAs, for long contractions only (see update_gram_kernel).
+template <int NT, int MT, bool PIPE>
 __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
                                                             int acol0, int kdim, const double* __restrict__ bmat,
                                                             int ldb, int ncols, int mode, int ccol0,
@@ -706,8 +707,53 @@ __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__
       lds[((((kt * 4 + q) * NT + nt) * 4 + gg) << 4) + ii] = v;
     }
     __syncthreads();
+    int kk0 = 0;
+    // A wave whose rows all exist runs the trips of the chunk without a branch round any load: the operands of the
+    // next trip are requested before the MFMAs of this one (the last request repeats the last trip's and is dropped);
+    // columns past kdim are read from the last four instead: their B rows in LDS are zero (or skipped).
+    if (PIPE && vec_ok && row0 + 16 * MT <= n && kdim % 4 == 0) {  // wave-uniform
+      const int klast = (kc16 - 1) / 32 * 32;  // start of the chunk's last trip
+      const double* __restrict__ abase = basis + (row0 + i) * ld + acol0;
+      d4 a0[2][MT], a1[2][MT];
+      auto fetch = [&](d4 (&av)[2][MT], int kb) __attribute__((always_inline)) {
+        const int kq = kb < klast ? kb : klast;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          int kcol = k0 + kq + 16 * h + 4 * g;
+          kcol = kcol + 3 < kdim ? kcol : kdim - 4;
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            av[h][mt] = *reinterpret_cast<const d4*>(abase + (int64_t)mt * 16 * ld + kcol);
+        }
+      };
+      auto mult = [&](const d4 (&av)[2][MT], int kb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          if (kb + 16 * h < kc16) {  // uniform; the LDS slots beyond kc16 were not filled
+            const int kt = (kb >> 4) + h;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+              for (int nt = 0; nt < NT; ++nt) {
+                const double bq = lds[((((kt * 4 + q) * NT + nt) * 4 + g) << 4) + i];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = MFMA_F64(av[h][mt][q], bq, acc[mt][nt]);
+              }
+          }
+        }
+      };
+      fetch(a0, 0);
+      for (int kb = 0; kb < kc16; kb += 64) {
+        fetch(a1, kb + 32);
+        mult(a0, kb);
+        if (kb + 32 >= kc16) break;
+        fetch(a0, kb + 64);
+        mult(a1, kb + 32);
+      }
+      kk0 = kc16;
+    }
     // two 16-index groups per trip: their loads are issued together, ahead of the MFMAs that use them
-    for (int kk = 0; kk < kc16; kk += 32) {
+    for (int kk = kk0; kk < kc16; kk += 32) {
       double a[2][MT][4];
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
@@ -1483,17 +1529,20 @@ hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int 
   const int vec_ok = (ld % 4 == 0 && acol0 % 4 == 0 && (reinterpret_cast<uintptr_t>(basis) % 32 == 0)) ? 1 : 0;
   constexpr int MT = 2;
   const unsigned gx = (unsigned)ceil_div64(n, 4 * 16 * MT);
+  const bool pipe = kdim >= 128;  // loads one trip ahead pay from a few trips on
+#define SC_LAUNCH_RG(NTV, PV, GY)                                                                                  \
+  hipLaunchKernelGGL((row_gemm_kernel<NTV, MT, PV>), dim3(gx, (GY)), dim3(kThreads), 0, st, basis, n, ld, acol0,   \
+                     kdim, bmat, ldb, ncols, mode, ccol0, out, ldo, vec_ok, rowmap)
   if (ncols <= 16) {
-    hipLaunchKernelGGL((row_gemm_kernel<1, MT>), dim3(gx, 1), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, bmat,
-                       ldb, ncols, mode, ccol0, out, ldo, vec_ok, rowmap);
+    if (pipe) SC_LAUNCH_RG(1, true, 1); else SC_LAUNCH_RG(1, false, 1);
   } else if (ncols <= 32) {
-    hipLaunchKernelGGL((row_gemm_kernel<2, MT>), dim3(gx, 1), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, bmat,
-                       ldb, ncols, mode, ccol0, out, ldo, vec_ok, rowmap);
+    if (pipe) SC_LAUNCH_RG(2, true, 1); else SC_LAUNCH_RG(2, false, 1);
   } else {
     if (mode == 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((row_gemm_kernel<4, MT>), dim3(gx, (unsigned)((ncols + 63) / 64)), dim3(kThreads), 0, st, basis,
-                       n, ld, acol0, kdim, bmat, ldb, ncols, mode, ccol0, out, ldo, vec_ok, rowmap);
+    const unsigned gy = (unsigned)((ncols + 63) / 64);
+    if (pipe) SC_LAUNCH_RG(4, true, gy); else SC_LAUNCH_RG(4, false, gy);
   }
+#undef SC_LAUNCH_RG
   return hipGetLastError();
 }
 
