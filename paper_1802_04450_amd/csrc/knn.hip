@@ -149,11 +149,15 @@ constexpr int kMq = 64;      // queries per workgroup
 constexpr int kMt = 256;     // threads
 constexpr int kRound = 2;    // steps of 64 candidates between two walks of the masks
 template <int DP>
-__global__ __launch_bounds__(kMt) __attribute__((amdgpu_waves_per_eu(2))) void knn_mfma_kernel(
+__global__ __launch_bounds__(kMt) __attribute__((amdgpu_waves_per_eu(DP <= 32 ? 3 : 2))) void knn_mfma_kernel(
     const double* __restrict__ xp, const double* __restrict__ xn, int64_t n, int k, int32_t* __restrict__ idx_out,
     double* __restrict__ dist_out) {
   constexpr int NS = DP / 4;            // MFMAs per 16 x 16 block
-  constexpr int KC = DP < 32 ? DP : 32;  // coordinates per piece of a step (the B operands of one piece are in flight)
+  // coordinates per piece of a step (the B operands of one piece are in flight).  Up to 32 coordinates the pieces are
+  // 16 wide, which fits three waves per SIMD without spills (28 instead of 30 ms on 100,000 points of 32 coordinates:
+  // three rounds of workgroups instead of four); at 128 coordinates three waves spill and lose (2.08 against 1.93 s
+  // on 500,000 points), so the wider kernels keep 32-wide pieces and two waves.
+  constexpr int KC = DP <= 32 ? (DP < 16 ? DP : 16) : 32;
   constexpr int NCH = DP / KC;           // pieces per step: 1, 2 or 4
   constexpr int NSC = KC / 4;            // MFMAs per block and piece
   constexpr double kMargin = (4.0 * DP + 16.0) * 1.1102230246251565e-16;
