@@ -480,3 +480,79 @@ def test_knn_oracle_pins():
     from oracle import similarity as sim
     _, _, g = knn.knn_union_pairs(idx, dist, sigma=0.8)
     np.testing.assert_allclose(g, sim.edge_similarity(x, u, v, sim.EXP_DECAY, 0.8), rtol=1e-12)
+
+
+def test_cgs2_block_and_rotate_pins():
+    """oracle/blockops.cgs2_block (the reorthogonalization inside TakeStep, Section IV-B: classical Gram-Schmidt applied
+    twice) and blockops.rotate (FindEigenvectors of Algorithm 3: Ritz vectors V Y) against values worked by hand, the
+    identities the definitions fix, and planted mistakes."""
+    from oracle import blockops
+    # by hand, exact in binary up to the thirds: q1 = (1,2,2)/3, q2 = (2,1,-2)/3, q3 = (2,-2,1)/3 is the third direction
+    q = np.array([[1.0, 2.0], [2.0, 1.0], [2.0, -2.0]]) / 3.0
+    w = np.array([[3.0, 0.0], [0.0, 3.0], [0.0, 3.0]])
+    w_out, h = blockops.cgs2_block(q, w)
+    # q1.w1 = 1, q2.w1 = 2, q1.w2 = 4, q2.w2 = -1;  w1 - q1 - 2 q2 = 2 q3,  w2 - 4 q1 + q2 = -q3
+    assert np.allclose(h, [[1.0, 4.0], [2.0, -1.0]], atol=1e-15)
+    q3 = np.array([2.0, -2.0, 1.0]) / 3.0
+    assert np.allclose(w_out, np.stack([2.0 * q3, -q3], axis=1), atol=1e-15)
+    assert np.array_equal(w, [[3.0, 0.0], [0.0, 3.0], [0.0, 3.0]])          # the input block is not modified
+
+    rng = np.random.default_rng(5)
+    n, j, b = 60, 7, 3
+    qo, _ = np.linalg.qr(rng.standard_normal((n, j)))
+    wi = rng.standard_normal((n, b))
+    wo, h = blockops.cgs2_block(qo, wi)
+    assert np.max(np.abs(qo.T @ wo)) < 1e-14                              # orthogonal to every column of Q
+    assert np.max(np.abs(h - qo.T @ wi)) < 1e-14                          # H = Q^T W for an orthonormal Q
+    assert np.max(np.abs(wo + qo @ h - wi)) < 1e-14                       # W_in = Q H + W_out
+    # a block already orthogonal to Q comes back unchanged with H = 0
+    perp = wi - qo @ (qo.T @ wi)
+    perp -= qo @ (qo.T @ perp)
+    wo2, h2 = blockops.cgs2_block(qo, perp)
+    assert np.max(np.abs(h2)) < 1e-15 and np.max(np.abs(wo2 - perp)) < 1e-15
+
+    # "applied twice" is what the second pass is for: a block that lies in span(Q) up to 1e-10 loses ten digits to
+    # cancellation in one pass (what is left along Q is rounding of the size 1e-16 |w| against |w_out| = 1e-10 |w|)
+    small = rng.standard_normal((n, b))
+    small -= qo @ (qo.T @ small)
+    near = qo @ rng.standard_normal((j, b)) + 1e-10 * small
+    wo3, h3 = blockops.cgs2_block(qo, near)
+    def defect(x):
+        return np.max(np.abs(qo.T @ x)) / np.min(np.linalg.norm(x, axis=0))
+    once = near - qo @ (qo.T @ near)
+    assert defect(wo3) < 1e-14 and defect(once) > 1e-9
+    # and for a basis that is orthonormal only to 1e-6, H1 + H2 is the least-squares coefficient block to second order
+    # (H1 alone is off in first order)
+    qe = qo + 1e-6 * rng.standard_normal((n, j))
+    wo4, h4 = blockops.cgs2_block(qe, wi)
+    h_ls = np.linalg.lstsq(qe, wi, rcond=None)[0]
+    assert np.max(np.abs(h4 - h_ls)) < 1e-9 and np.max(np.abs(qe.T @ wi - h_ls)) > 1e-7
+    assert np.max(np.abs(qe.T @ wo4)) < 1e-9 and np.max(np.abs(qe.T @ (wi - qe @ (qe.T @ wi)))) > 1e-7
+
+    # planted mistakes: second pass computed from the block as it came in; H1 returned alone
+    def stale_second_pass(qm, wm):
+        h1 = qm.T @ wm
+        out = wm - qm @ h1
+        h2_ = qm.T @ wm
+        return out - qm @ h2_, h1 + h2_
+    ws, hs = stale_second_pass(q, w)
+    assert np.max(np.abs(hs - [[1.0, 4.0], [2.0, -1.0]])) > 0.5 and np.max(np.abs(q.T @ ws)) > 0.5
+    assert np.max(np.abs((qe.T @ wi) - h_ls)) > 100 * np.max(np.abs(h4 - h_ls))
+
+    # rotation, by hand: column t of V Y is sum_r V[:, r] Y[r, t]
+    v = np.array([[1.0, 2.0], [3.0, 4.0], [5.0, 6.0]])
+    y = np.array([[1.0, -1.0, 0.5], [2.0, 0.0, -1.0]])
+    assert np.array_equal(blockops.rotate(v, y), [[5.0, -1.0, -1.5], [11.0, -3.0, -2.5], [17.0, -5.0, -3.5]])
+    assert np.array_equal(blockops.rotate(v, np.eye(2)), v)
+    # an orthonormal basis rotated by the eigenvectors of its projected matrix gives Ritz vectors: orthonormal, and
+    # X^T A X diagonal with the Ritz values
+    a = rng.standard_normal((n, n))
+    a = a + a.T
+    tproj = qo.T @ a @ qo
+    ritz, yv = np.linalg.eigh(tproj)
+    x = blockops.rotate(qo, yv[:, -3:])
+    assert np.max(np.abs(x.T @ x - np.eye(3))) < 1e-14
+    assert np.max(np.abs(x.T @ a @ x - np.diag(ritz[-3:]))) < 1e-12
+    # planted mistake: the transposed coefficient block (only possible when square) gives something else
+    ysq = np.array([[1.0, -1.0], [2.0, 0.0]])
+    assert np.max(np.abs(v @ ysq.T - blockops.rotate(v, ysq))) > 1.0
