@@ -56,14 +56,14 @@ def test_closed_form_graphs_match_dense_oracle(B, name, make, k):
     check_against_oracle(g, k, lam, vec, lam_full[:k + 1], vec_full[:, :k])
 
 
-@pytest.mark.parametrize("block", [1, 2, 4, 8])
+@pytest.mark.parametrize("block", [1, 2, 4, 8, 16, 32])
 def test_block_sizes_on_multiplicity_graph(B, block):
     # 6 components -> 6 zeros; then the rings' double eigenvalues
     g = wl.disjoint_union(*[wl.ring(20 + 3 * t) for t in range(6)])
     rp, c, v, n = g
     lam_full, vec_full = dense.full_spectrum(rp, c, v)
     k = 9
-    lam, vec, code, stats = solve(B, g, k, 1e-10, block=block, m=60)
+    lam, vec, code, stats = solve(B, g, k, 1e-10, block=block, m=max(60, k + 3 * block))
     assert code == B.SC_OK and stats["block"] == block
     check_against_oracle(g, k, lam, vec, lam_full[:k + 1], vec_full[:, :k])
     assert np.sum(np.abs(lam) < 1e-9) == 6
@@ -116,6 +116,23 @@ def test_reduced_workloads_against_lanczos_and_component_oracles(B, cid, n, comp
     lam_o, vec_o = lanczos.lanczos_smallest(rp, c, v, k=k + 1, tol=1e-10, m=max(m, 2 * (k + 1)), seed=11)
     lam, vec, code, stats = solve(B, g, k, cfg.tol, m=m)
     assert code == B.SC_OK, stats
+    basis = components.null_space(rp, c, v) if k <= ncomp else None
+    check_against_oracle(g, k, lam, vec, lam_o, vec_o, cluster_basis=basis)
+    assert np.sum(np.abs(lam) < 1e-8) == min(k, ncomp)
+
+
+def test_block32_on_reduced_large_k_workload(B):
+    """The block size the library picks for the reorthogonalization-dominated workload (n >= 300,000 and k >= 1000:
+    32 columns per step), end to end on a reduced instance of the same recipe, against the Lanczos oracle and the
+    closed-form null space."""
+    cfg = wl.reduced(wl.CONFIGS[5], n=12000, components=48, k=48, m=160)
+    g, label, _ = wl.build_config_graph(cfg, device="cuda")
+    rp, c, v, nn = g
+    ncomp, _ = components.component_labels(rp, c, v)
+    k = cfg.k
+    lam_o, vec_o = lanczos.lanczos_smallest(rp, c, v, k=k + 1, tol=1e-10, m=max(cfg.m, 2 * (k + 1)), seed=11)
+    lam, vec, code, stats = solve(B, g, k, cfg.tol, m=cfg.m, block=32)
+    assert code == B.SC_OK and stats["block"] == 32, stats
     basis = components.null_space(rp, c, v) if k <= ncomp else None
     check_against_oracle(g, k, lam, vec, lam_o, vec_o, cluster_basis=basis)
     assert np.sum(np.abs(lam) < 1e-8) == min(k, ncomp)

@@ -98,6 +98,41 @@ def test_spmm_normalized(B, graphs, ncols):
         assert torch.equal(y2, yb[:, :ncols])
 
 
+def _regular_with_hub(n, deg, seed):
+    """Every node linked to its deg/2 successors on a ring (degree = deg everywhere), random weights, plus one hub
+    joined to a quarter of the nodes: average degree close to deg, one row far longer than any register buffer."""
+    rng = np.random.default_rng(seed)
+    i = np.arange(n, dtype=np.int64)
+    u = np.concatenate([i for _ in range(deg // 2)])
+    v = np.concatenate([(i + t) % n for t in range(1, deg // 2 + 1)])
+    far = np.arange(deg // 2 + 1, n - deg // 2 - 1, 4, dtype=np.int64)     # not already neighbours of node 0
+    u = np.concatenate([u, np.zeros(far.size, dtype=np.int64)])
+    v = np.concatenate([v, far])
+    return wl.symmetric_from_edges(u, v, rng.uniform(0.5, 2.0, size=u.size), n)
+
+
+@pytest.mark.parametrize("deg", [8, 18, 26, 36, 60, 100])
+def test_single_vector_product_over_average_degrees(B, deg):
+    """The single-vector product picks its tile height and register buffer from the average row length (six
+    combinations, boundaries at about 14.8, 22.2, 29.6, 40.7 and 81.5 entries per row): one graph per combination,
+    each with a hub row, with and without the scaling vector (the materialised operator), ragged last tile."""
+    n = 4099
+    rp, c, v, _ = _regular_with_hub(n, deg, deg)
+    avg = rp[-1] / n
+    assert deg <= avg < deg + 0.6
+    drp, dc, dv = B.csr_to_device(rp, c, v)
+    _, s = B.sc_degree_scaling(drp, dc, dv)
+    x = np.random.default_rng(deg).standard_normal(n)
+    y0 = laplacian.apply_s(rp, c, v, x)
+    dx = torch.from_numpy(x).cuda()
+    y = B.sc_spmm_normalized(drp, dc, dv, s, dx).cpu().numpy()
+    assert np.max(np.abs(y - y0)) <= 1e-13 * np.abs(y0).max(), deg
+    vs = B.sc_scale_operator(drp, dc, dv, s)
+    y2 = B.sc_spmm_normalized(drp, dc, vs, None, dx)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(y2.cpu().numpy() - y0)) <= 1e-13 * np.abs(y0).max(), deg
+
+
 @pytest.mark.parametrize("ncols", [1, 2, 8, 16])
 def test_scaled_operator_and_its_product(B, graphs, ncols):
     """Algorithm 2 step 3 as a step of its own: the scaled values are s_i w_ij s_j entry by entry and exactly symmetric,
