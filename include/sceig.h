@@ -19,12 +19,14 @@
  *     outputs are unspecified.  No C++ exception crosses this boundary.
  *   - CSR: rowptr int64[n+1] with rowptr[0] = 0, non-decreasing, rowptr[n] = nnz; col int32[nnz] in
  *     [0, n); val fp64[nnz].  Columns need not be sorted; duplicate entries add up.  W must be
- *     symmetric (not checked).  Self loops are allowed and count towards the degree.
+ *     symmetric with w_ij >= 0 (checked only under SC_FLAG_VALIDATE_SYMMETRY).  Self loops are allowed
+ *     and count towards the degree.
  *   - Dense blocks handed to the kernel-level entry points are ROW-MAJOR: element (i, c) of an
  *     n x ncols block with leading dimension ld lives at base[i * ld + c].  The final eigenvector
  *     output of sc_laplacian_eigsh is COLUMN-MAJOR (vector t contiguous at evecs_out + t * n).
  *   - Calls that use the same stream or the same buffers must not overlap.
- *   - Workspace of a call is allocated inside it and cached between calls: see sc_release_cache().
+ *   - Workspace of a call is allocated inside it and cached between calls (see sc_release_cache()), except
+ *     for sc_laplacian_eigsh_ws, which works inside a buffer of the caller's.
  */
 #ifndef SCEIG_H
 #define SCEIG_H
@@ -40,17 +42,20 @@ extern "C" {
 #define SC_NOT_CONVERGED 1 /* maxiter reached; outputs hold the best k Ritz pairs, stats->nconv met tol */
 #define SC_EINVAL (-1)     /* null pointer, negative size */
 #define SC_EDOMAIN (-2)    /* k < 1, k >= n, m out of range, block not supported, tol < 0 */
-#define SC_ECSR (-3)       /* malformed CSR (rowptr not monotone, rowptr[0] != 0, column out of range) */
+#define SC_ECSR (-3)       /* malformed CSR (rowptr not monotone, rowptr[0] != 0, column out of range); under
+                              SC_FLAG_VALIDATE_SYMMETRY also an asymmetric W, a negative or a non-finite weight */
 #define SC_EZERODEG (-4)   /* a row whose degree is <= 0 or not finite (Section IV-B: remove isolated nodes first) */
 #define SC_ENOMEM (-5)     /* device or host allocation failed */
 #define SC_EHIP (-6)       /* a HIP runtime call failed */
+#define SC_EINTERNAL (-7)  /* an internal iteration limit was exceeded (the component pass did not settle) */
 
 #define SC_FLAG_NO_VERIFY 1u /* skip the final deflated check phase (see sc_laplacian_eigsh) */
 #define SC_FLAG_NO_REORDER 2u /* work on the CSR exactly as given: no connected-component pass, no internal
                                  renumbering of the nodes for gather locality */
 #define SC_FLAG_COMPONENT_NULLSPACE 4u /* lock the closed-form eigenvalue-0 vectors D^1/2 1_C / sqrt(vol C) of the
                                  connected components (vol as in the Ncut definition of Section II) before the first
-                                 Lanczos phase; off by default; ignored under SC_FLAG_NO_REORDER */
+                                 Lanczos phase, after their residuals ||S v - v||, formed with block products, have met
+                                 tol (if one does not, none is locked); off by default; ignored under SC_FLAG_NO_REORDER */
 
 #define SC_FLAG_NO_START_FILTER 8u /* start every phase from the plain random block: no polynomial filtering of the
                                  re-injection blocks (see sc_laplacian_eigsh) */
@@ -67,6 +72,12 @@ extern "C" {
                                  Section II Step 4 hands to k-means) to unit 2-norm; the columns are then no longer
                                  eigenvectors.  Applied after SC_FLAG_RANDOM_WALK_VECTORS, which it makes immaterial */
 
+#define SC_FLAG_VALIDATE_SYMMETRY 128u /* check the precondition of the problem statement (Section II: W symmetric,
+                                 w_ij >= 0) on the device before anything else: for every entry (i, j) the weights that row
+                                 i lists under column j and row j under column i must add up to the same value (to four
+                                 units in the last place), and every weight must be finite and >= 0; else SC_ECSR.  Costs
+                                 one pass that reads two rows per entry */
+
 /* Options; every field 0 = default. */
 typedef struct sc_options {
   int32_t m;      /* budget of basis columns (locked + active Krylov vectors), the "number m of Lanczos
@@ -79,7 +90,12 @@ typedef struct sc_options {
   uint64_t seed;  /* seed of the start / re-injection blocks */
   uint32_t timing_mask; /* bit f set: time every launch of kernel family f with HIP events on the stream
                            (SC_FAM_*); results in sc_stats.fam_*; costs two event records per launch */
-  uint32_t reserved;
+  int32_t guard;  /* extra pairs beyond k that the iteration converges and locks like the wanted ones (k + guard takes
+                     the place of k in the defaults and limits of m and block); the k leading pairs are returned.  Makes
+                     the k-th eigenvalue accurate to second order in tol when lambda_k and lambda_k+1 are close */
+  const double* v0; /* device fp64[n], caller's numbering, finite, or NULL: start vector (Section IV-B notes that the
+                     number of iterations varies with it); it becomes the first column of the first start block, the
+                     other block - 1 columns and all later re-injection blocks are the seeded random ones */
 } sc_options;
 
 /* kernel families for timing_mask / sc_stats.fam_* */
@@ -147,13 +163,28 @@ int sc_laplacian_eigsh(const int64_t* csr_rowptr, const int32_t* csr_col, const 
 /*
  * Device memory, in bytes, that sc_laplacian_eigsh takes for itself for a problem of this size (an upper estimate of the
  * sum of its blocks: its renumbered copy of the operator, the basis n x (m + b), the rotation workspace, the packed
- * block, partial-sum and coefficient buffers), with the same defaults for opt->m and opt->block as the solve.  Nothing is
- * allocated and no GPU is needed.  The blocks come from the library's cache (see sc_release_cache); there is no
- * caller-provided workspace: every buffer a caller hands over is an input or an output.
+ * block, partial-sum and coefficient buffers), with the same defaults for opt->m and opt->block as the solve (opt->flags
+ * and opt->guard count too).  Nothing is allocated and no GPU is needed.  This is also the size of the buffer that
+ * sc_laplacian_eigsh_ws needs.
  *   bytes_out  host
  * Returns SC_OK, SC_EINVAL, or SC_EDOMAIN exactly where the solve would.
  */
 int sc_workspace_bytes(int64_t n, int64_t nnz, int32_t k, const sc_options* opt, size_t* bytes_out);
+
+/*
+ * sc_laplacian_eigsh (same problem statement: Section II Steps 2-3, Section IV-B) with every device block of the solve
+ * carved out of a buffer that the caller owns, so that the caller's allocator (PyTorch's, say) accounts for all device
+ * memory: the call makes no device allocation and does not touch the library's block cache.
+ *   workspace        device, at least sc_workspace_bytes(n, nnz, k, opt) bytes (nnz = csr_rowptr[n]); any alignment
+ *                    (up to 255 bytes are skipped to reach a 256-byte boundary; the estimate allows for that);
+ *                    contents on entry are ignored, on return unspecified
+ *   workspace_bytes  its size; SC_ENOMEM if it is smaller than the estimate (nothing has been computed then)
+ * Everything else as sc_laplacian_eigsh, results bitwise equal to it for equal arguments.  A few KB of pinned host
+ * memory (coefficient blocks read back during convergence checks) still come from the library's own pinned cache.
+ */
+int sc_laplacian_eigsh_ws(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n, int32_t k,
+                          double tol, int32_t maxiter, double* evals_out, double* evecs_out, void* stream,
+                          const sc_options* opt, sc_stats* stats, void* workspace, size_t workspace_bytes);
 
 /*
  * Setup step (Algorithm 2 steps 1-2, with the scaling kept as a vector instead of a scaled copy of W):

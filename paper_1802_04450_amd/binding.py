@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsceig.so")
 
 SC_OK, SC_NOT_CONVERGED = 0, 1
-SC_EINVAL, SC_EDOMAIN, SC_ECSR, SC_EZERODEG, SC_ENOMEM, SC_EHIP = -1, -2, -3, -4, -5, -6
+SC_EINVAL, SC_EDOMAIN, SC_ECSR, SC_EZERODEG, SC_ENOMEM, SC_EHIP, SC_EINTERNAL = -1, -2, -3, -4, -5, -6, -7
 SC_FLAG_NO_VERIFY = 1
 SC_FLAG_NO_REORDER = 2
 SC_FLAG_COMPONENT_NULLSPACE = 4
@@ -23,18 +23,19 @@ SC_FLAG_NO_START_FILTER = 8
 SC_FLAG_FINAL_RR = 16
 SC_FLAG_RANDOM_WALK_VECTORS = 32
 SC_FLAG_ROW_NORMALIZE = 64
+SC_FLAG_VALIDATE_SYMMETRY = 128
 FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 
 EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_reorder_csr", "sc_cgs2",
            "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version", "sc_release_cache",
            "sc_chebyshev_filter", "sc_kmeanspp", "sc_kmeans_lloyd", "sc_kmeans", "sc_edge_similarity", "sc_knn_search", "sc_knn_union_pairs",
-           "sc_coo_to_csr", "sc_workspace_bytes", "sc_scale_operator"]
+           "sc_coo_to_csr", "sc_workspace_bytes", "sc_scale_operator", "sc_laplacian_eigsh_ws"]
 
 
 class ScOptions(ctypes.Structure):
     _fields_ = [("m", ctypes.c_int32), ("block", ctypes.c_int32), ("check_every", ctypes.c_int32),
                 ("flags", ctypes.c_uint32), ("seed", ctypes.c_uint64), ("timing_mask", ctypes.c_uint32),
-                ("reserved", ctypes.c_uint32)]
+                ("guard", ctypes.c_int32), ("v0", ctypes.c_void_p)]
 
 
 class ScStats(ctypes.Structure):
@@ -87,6 +88,8 @@ def lib() -> ctypes.CDLL:
         vp, i32, i64, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
         _lib.sc_laplacian_eigsh.argtypes = [vp, vp, vp, i64, i32, dbl, i32, vp, vp, vp, ctypes.POINTER(ScOptions),
                                             ctypes.POINTER(ScStats)]
+        _lib.sc_laplacian_eigsh_ws.argtypes = [vp, vp, vp, i64, i32, dbl, i32, vp, vp, vp, ctypes.POINTER(ScOptions),
+                                               ctypes.POINTER(ScStats), vp, ctypes.c_size_t]
         _lib.sc_workspace_bytes.argtypes = [i64, i64, i32, ctypes.POINTER(ScOptions), ctypes.POINTER(ctypes.c_size_t)]
         _lib.sc_degree_scaling.argtypes = [vp, vp, vp, i64, vp, vp, vp]
         _lib.sc_scale_operator.argtypes = [vp, vp, vp, vp, i64, vp, vp]
@@ -156,26 +159,43 @@ def csr_to_device(rowptr: np.ndarray, col: np.ndarray, val: np.ndarray, device="
 
 # ----------------------------------------------------------------------------------------------
 def sc_laplacian_eigsh(rowptr, col, val, k: int, tol: float, maxiter: int = 100000, m: int = 0, block: int = 0,
-                       check_every: int = 0, flags: int = 0, seed: int = 0, timing_mask: int = 0):
+                       check_every: int = 0, flags: int = 0, seed: int = 0, timing_mask: int = 0, guard: int = 0,
+                       v0=None, workspace=None, out=None):
     """Returns (evals[k] device, evecs (k, n) device - row t is eigenvector t, i.e. the library's
-    column-major n x k output -, status code, stats dict)."""
+    column-major n x k output -, status code, stats dict).  workspace: a device tensor that the solve works inside
+    (sc_laplacian_eigsh_ws); out: (evals, evecs) tensors to write into instead of new ones."""
     import torch
     n = rowptr.numel() - 1
     _dev(rowptr, torch.int64), _dev(col, torch.int32), _dev(val, torch.float64)
-    evals = torch.empty(max(k, 0), dtype=torch.float64, device=rowptr.device)
-    evecs = torch.empty((max(k, 0), n), dtype=torch.float64, device=rowptr.device)
-    opt = ScOptions(m=m, block=block, check_every=check_every, flags=flags, seed=seed, timing_mask=timing_mask)
+    if out is None:
+        evals = torch.empty(max(k, 0), dtype=torch.float64, device=rowptr.device)
+        evecs = torch.empty((max(k, 0), n), dtype=torch.float64, device=rowptr.device)
+    else:
+        evals, evecs = out
+        _dev(evals, torch.float64), _dev(evecs, torch.float64)
+        assert evals.numel() >= k and evecs.numel() >= k * n
+    if v0 is not None:
+        _dev(v0, torch.float64)
+        assert v0.numel() == n
+    opt = ScOptions(m=m, block=block, check_every=check_every, flags=flags, seed=seed, timing_mask=timing_mask,
+                    guard=guard, v0=_ptr(v0))
     stats = ScStats()
     with torch.cuda.device(rowptr.device):
-        code = lib().sc_laplacian_eigsh(_ptr(rowptr), _ptr(col), _ptr(val), n, k, tol, maxiter, _ptr(evals),
-                                        _ptr(evecs), _stream(), ctypes.byref(opt), ctypes.byref(stats))
+        if workspace is None:
+            code = lib().sc_laplacian_eigsh(_ptr(rowptr), _ptr(col), _ptr(val), n, k, tol, maxiter, _ptr(evals),
+                                            _ptr(evecs), _stream(), ctypes.byref(opt), ctypes.byref(stats))
+        else:
+            assert workspace.is_cuda and workspace.is_contiguous()
+            code = lib().sc_laplacian_eigsh_ws(_ptr(rowptr), _ptr(col), _ptr(val), n, k, tol, maxiter, _ptr(evals),
+                                               _ptr(evecs), _stream(), ctypes.byref(opt), ctypes.byref(stats),
+                                               _ptr(workspace), workspace.numel() * workspace.element_size())
     _check(code)
     return evals, evecs, code, stats.as_dict()
 
 
-def sc_workspace_bytes(n: int, nnz: int, k: int, m: int = 0, block: int = 0, flags: int = 0) -> int:
+def sc_workspace_bytes(n: int, nnz: int, k: int, m: int = 0, block: int = 0, flags: int = 0, guard: int = 0) -> int:
     """Device bytes a solve of this size allocates for itself (host-only query)."""
-    opt = ScOptions(m=m, block=block, flags=flags)
+    opt = ScOptions(m=m, block=block, flags=flags, guard=guard)
     out = ctypes.c_size_t(0)
     _check(lib().sc_workspace_bytes(n, nnz, k, ctypes.byref(opt), ctypes.byref(out)), soft_ok=False)
     return int(out.value)

@@ -69,8 +69,9 @@ double now_s() {
 // Device and pinned-host blocks released by a call are kept for the next call instead of going back to the driver
 // (hipMalloc / hipFree / hipHostMalloc cost tens of microseconds each and hipFree synchronises the device; a solve
 // makes about thirty of them).  A block is reused only for a request of exactly its size on the same device, which is
-// what repeated solves of one problem shape ask for.  Every entry point synchronises its stream before it returns, so
-// no kernel of the releasing call can still be using a block when it is handed out again.  The cache holds at most
+// what repeated solves of one problem shape ask for.  Every entry point synchronises its stream before it returns (and
+// a call that fails waits for the device before its blocks are released, see settle_before_release), so no kernel of
+// the releasing call can still be using a block when it is handed out again.  The cache holds at most
 // `limit` bytes per kind (default 4 GiB, SCEIG_CACHE_LIMIT_MB overrides, 0 switches caching off); sc_release_cache()
 // empties it.
 class BlockCache {
@@ -150,10 +151,63 @@ BlockCache& pinned_cache() {
   return *c;
 }
 
+// A caller-provided workspace: while one is installed on the calling thread every device block of the call is carved
+// out of it instead of coming from the cache, and nothing is allocated.  Blocks are 256-byte aligned and handed out
+// bottom-up; a released block is reclaimed as soon as everything above it has been released too (the solver's blocks
+// live in nested scopes, so the high-water mark stays at the sum of the blocks alive at one time).
+class Arena {
+ public:
+  Arena(void* base, size_t bytes) {
+    const uintptr_t b = reinterpret_cast<uintptr_t>(base), a = (b + 255) / 256 * 256;
+    base_ = reinterpret_cast<char*>(a);
+    cap_ = bytes > a - b ? bytes - (a - b) : 0;
+  }
+  void* get(size_t bytes) {
+    const size_t need = (bytes + 255) / 256 * 256;
+    if (need > cap_ - top_) return nullptr;
+    void* p = base_ + top_;
+    live_.push_back(Block{top_, need, false});
+    top_ += need;
+    peak_ = std::max(peak_, top_);
+    return p;
+  }
+  void put(void* p) {
+    const size_t off = (size_t)(static_cast<char*>(p) - base_);
+    for (auto it = live_.rbegin(); it != live_.rend(); ++it)
+      if (it->off == off) {
+        it->freed = true;
+        break;
+      }
+    while (!live_.empty() && live_.back().freed) {
+      top_ = live_.back().off;
+      live_.pop_back();
+    }
+  }
+  size_t peak() const { return peak_; }
+
+ private:
+  struct Block {
+    size_t off, bytes;
+    bool freed;
+  };
+  char* base_ = nullptr;
+  size_t cap_ = 0, top_ = 0, peak_ = 0;
+  std::vector<Block> live_;
+};
+thread_local Arena* tl_arena = nullptr;
+
+// Blocks that go back to the cache while an exception unwinds the call may still be in use by kernels the call had
+// enqueued before it failed (the normal path synchronises its stream before it returns; the error path has not got
+// there).  Waiting for the device first keeps a concurrent call on another stream from being handed such a block.
+inline void settle_before_release() {
+  if (std::uncaught_exceptions() > 0) (void)hipDeviceSynchronize();
+}
+
 template <typename T>
 struct DevBuf {
   T* p = nullptr;
   size_t bytes = 0;
+  Arena* arena = nullptr;
   DevBuf() = default;
   DevBuf(const DevBuf&) = delete;
   DevBuf& operator=(const DevBuf&) = delete;
@@ -161,14 +215,28 @@ struct DevBuf {
     release();
     if (count == 0) count = 1;
     void* q = nullptr;
-    HIP_TRY(device_cache().get(count * sizeof(T), &q));
+    if (tl_arena) {
+      q = tl_arena->get(count * sizeof(T));
+      if (!q) SC_THROW(SC_ENOMEM);  // the caller's workspace is too small
+      arena = tl_arena;
+    } else {
+      HIP_TRY(device_cache().get(count * sizeof(T), &q));
+    }
     p = static_cast<T*>(q);
     bytes = count * sizeof(T);
   }
   void release() {
-    if (p) device_cache().put(p, bytes);
+    if (p) {
+      if (arena) {
+        arena->put(p);
+      } else {
+        settle_before_release();
+        device_cache().put(p, bytes);
+      }
+    }
     p = nullptr;
     bytes = 0;
+    arena = nullptr;
   }
   ~DevBuf() { release(); }
 };
@@ -189,7 +257,10 @@ struct PinnedBuf {
     bytes = count * sizeof(T);
   }
   void release() {
-    if (p) pinned_cache().put(p, bytes);
+    if (p) {
+      settle_before_release();
+      pinned_cache().put(p, bytes);
+    }
     p = nullptr;
     bytes = 0;
   }
@@ -400,6 +471,7 @@ int reorder_csr(const int64_t* rowptr, const int32_t* col, const double* val, in
     HIP_TRY(hipStreamSynchronize(st));
     if (debug_on() && (round % 50 == 49)) std::fprintf(stderr, "[sceig] component pass: %d rounds\n", 2 * (round + 1));
     if (!h) break;
+    if (round + 1 == 100000) SC_THROW(SC_EINTERNAL);  // labels still changing: they do not name the components yet
   }
   // numbering, permuted row pointers and component index of every new row, all on the device
   int32_t* new_of_old_dev = new_of_old_out;
@@ -433,13 +505,16 @@ struct Solver {
   const int32_t* col;
   const double* val;
   int64_t n, nnz;
-  int k;
+  int k;      // pairs the iteration works for: the caller's k plus the guard vectors
+  int k_out;  // pairs returned
   double tol;
   int maxiter;
   // options
   int m, b, check_every;
   uint32_t flags;
   uint64_t seed;
+  const double* v0 = nullptr;  // caller's start vector (caller's numbering), or null
+  size_t ws_limit = 0;         // > 0: size of the caller's workspace, checked against the estimate once nnz is known
   hipStream_t st;
   // device
   DevBuf<double> basis, s, z, part, gpart, h1, hsum, small, slots, yd, rot;
@@ -522,12 +597,39 @@ struct Solver {
     HIP_TRY(hipMemcpyAsync(comp_d.p, comp_host.data(), (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(coef_d.p, d.data(), (size_t)n * sizeof(double), hipMemcpyHostToDevice, st));
     HIP_TRY(launch_nullspace_fill(basis.p, n, ld, 0, take, comp_d.p, coef_d.p, st));
-    HIP_TRY(hipStreamSynchronize(st));
-    nl = take;
-    theta_locked.assign(take, 1.0);
-    rho_locked.assign(take, 0.0);
     comp_d.release();
     coef_d.release();
+    // Nothing is locked unverified: the residual S v - v of every vector is formed, b columns per product, and its
+    // norm must meet tol like that of any Ritz pair (a component pass gone wrong, or a W that is not symmetric, shows
+    // here).  If one fails, none is locked and the solve takes the plain path.
+    std::vector<double> rho((size_t)take, 0.0), g((size_t)kPP * kPP);
+    const int ycol = take + b;  // product block; columns [take, take + b) pad the last chunk with zeros
+    HIP_TRY(hipMemsetAsync(z.p, 0, (size_t)n * b * sizeof(double), st));
+    HIP_TRY(launch_copy_cols(z.p, b, 0, basis.p, ld, take, b, n, st));
+    const ProjectPlan plan = plan_project(n, b, kMaxPartials);
+    bool ok = true;
+    for (int c0 = 0; c0 < take && ok; c0 += b) {
+      const int w = std::min(b, take - c0);
+      HIP_TRY(launch_pack_scaled(basis.p + c0, ld, zs(), n, b, z.p, st));
+      spmm_from_z(basis.p + ycol, ld);
+      HIP_TRY(launch_sub_cols(basis.p, ld, c0, basis.p, ld, ycol, w, n, st));
+      HIP_TRY(launch_project(basis.p, n, ld, ycol, b, ycol, b, plan, part.p, st));
+      HIP_TRY(launch_reduce_partials(part.p, plan.npart, b, b, gram(), nullptr, 0, nullptr, 0, st));
+      HIP_TRY(hipMemcpyAsync(g.data(), gram(), g.size() * sizeof(double), hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipStreamSynchronize(st));
+      stats.spmv_cols += w;
+      for (int t = 0; t < w; ++t) {
+        rho[c0 + t] = std::sqrt(std::max(g[(size_t)t * kPP + t], 0.0));
+        if (!(rho[c0 + t] <= tol)) ok = false;
+      }
+    }
+    if (!ok) {
+      if (debug_on()) std::fprintf(stderr, "[sceig] component null vectors failed the residual test: plain path\n");
+      return;
+    }
+    nl = take;
+    theta_locked.assign(take, 1.0);
+    rho_locked = rho;
   }
 
   void setup() {
@@ -542,6 +644,20 @@ struct Solver {
     HIP_TRY(hipMemcpyAsync(&hflag, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     if (hflag & 3) SC_THROW(SC_ECSR);
+    if (ws_limit > 0) {  // a workspace that cannot hold the solve is refused before anything is computed
+      sc_options o{};
+      o.m = m;
+      o.block = b;
+      o.flags = flags;
+      size_t need = 0;
+      if (sc_workspace_bytes(n, nnz, k, &o, &need) != SC_OK || need > ws_limit) SC_THROW(SC_ENOMEM);
+    }
+    if (flags & SC_FLAG_VALIDATE_SYMMETRY) {
+      HIP_TRY(launch_validate_symmetry(rowptr, col, val, n, flag.p, st));
+      HIP_TRY(hipMemcpyAsync(&hflag, flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipStreamSynchronize(st));
+      if (hflag & (8 | 16)) SC_THROW(SC_ECSR);
+    }
     const double t1 = now_s();
     if (!(flags & SC_FLAG_NO_REORDER)) reorder();
     const double t2 = now_s();
@@ -751,6 +867,8 @@ struct Solver {
 
       // ---- start block
       HIP_TRY(launch_random_block(basis.p, n, ld, nl, b, seed, stream_id++, st));
+      if (v0 && stats.phases == 1)  // the caller's start vector leads the first block, the other columns stay random
+        HIP_TRY(launch_set_column(basis.p, n, ld, nl, v0, rowmap, st));
       bool filtered = filt_d > 0;
       if (filtered) {
         // the filter is linear and takes the random block as it is, after one projection pass against the locked
@@ -1048,9 +1166,9 @@ struct Solver {
     if (debug_on())
       std::fprintf(stderr, "[sceig] t=%.4fs %s over %d locked vectors\n", now_s() - t_begin,
                    final_rr ? "Rayleigh-Ritz" : "sorted output", nx);
-    std::vector<double> evals_host(k, std::numeric_limits<double>::quiet_NaN());
-    int nfound = std::min(nx, k);
-    if (nx < k) HIP_TRY(hipMemsetAsync(evecs_out, 0, (size_t)n * k * sizeof(double), st));
+    std::vector<double> evals_host(k_out, std::numeric_limits<double>::quiet_NaN());
+    int nfound = std::min(nx, k_out);
+    if (nx < k_out) HIP_TRY(hipMemsetAsync(evecs_out, 0, (size_t)n * k_out * sizeof(double), st));
     std::vector<int32_t> order;
     if (nx > 0 && !final_rr) {
       order.resize(nx);
@@ -1101,23 +1219,29 @@ struct Solver {
       HIP_TRY(launch_scale_rows_colmajor(evecs_out, n, nfound, s.p, rowinv, st));
     // the embedding handed to k-means (Section II Step 4) with every point on the unit sphere
     if ((flags & SC_FLAG_ROW_NORMALIZE) && nfound > 0) HIP_TRY(launch_normalize_rows_colmajor(evecs_out, n, nfound, st));
-    HIP_TRY(hipMemcpyAsync(evals_out, evals_host.data(), (size_t)k * sizeof(double), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(evals_out, evals_host.data(), (size_t)k_out * sizeof(double), hipMemcpyHostToDevice, st));
     HIP_TRY(hipStreamSynchronize(st));
     if (debug_on()) std::fprintf(stderr, "[sceig] t=%.4fs outputs written\n", now_s() - t_begin);
 
+    // the k_out returned pairs are the leading ones of the locked set: count and bound those
     int nconv = 0;
     double maxr = 0.0;
-    for (size_t t = 0; t < rho_locked.size(); ++t) {
-      if (rho_locked[t] <= tol) ++nconv;
-      maxr = std::max(maxr, rho_locked[t]);
+    {
+      std::vector<int> byth(rho_locked.size());
+      std::iota(byth.begin(), byth.end(), 0);
+      std::stable_sort(byth.begin(), byth.end(), [&](int x, int y) { return theta_locked[x] > theta_locked[y]; });
+      for (size_t t = 0; t < byth.size() && (int)t < k_out; ++t) {
+        if (rho_locked[byth[t]] <= tol) ++nconv;
+        maxr = std::max(maxr, rho_locked[byth[t]]);
+      }
     }
-    stats.nconv = std::min(nconv, k);
+    stats.nconv = std::min(nconv, k_out);
     stats.max_residual_est = maxr;
     stats.block = b;
     stats.m = m;
     timer.collect(&stats);
     stats.t_total = now_s() - t_begin;
-    if (nfound < k) not_converged = true;
+    if (nfound < k_out) not_converged = true;
     return not_converged ? SC_NOT_CONVERGED : SC_OK;
   }
 };
@@ -1368,46 +1492,60 @@ const char* sc_strerror(int code) {
     case SC_EZERODEG: return "a node has a non-positive or non-finite degree";
     case SC_ENOMEM: return "out of memory";
     case SC_EHIP: return "HIP runtime failure";
+    case SC_EINTERNAL: return "an internal iteration limit was exceeded";
     default: return "unknown code";
   }
 }
 
-int sc_laplacian_eigsh(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n, int32_t k,
-                       double tol, int32_t maxiter, double* evals_out, double* evecs_out, void* stream,
-                       const sc_options* opt, sc_stats* stats) {
+namespace {
+
+int eigsh_entry(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n, int32_t k, double tol,
+                int32_t maxiter, double* evals_out, double* evecs_out, void* stream, const sc_options* opt, sc_stats* stats,
+                void* workspace, size_t workspace_bytes, bool use_workspace) {
   if (!csr_rowptr || !csr_col || !csr_val || !evals_out || !evecs_out || n < 0) return SC_EINVAL;
-  if (k < 1 || (int64_t)k >= n || !(tol >= 0.0) || maxiter < 1) return SC_EDOMAIN;
-  if (n > (int64_t)0x7fffffff) return SC_EDOMAIN;
+  if (use_workspace && !workspace) return SC_EINVAL;
   sc_options o{};
   if (opt) o = *opt;
+  if (k < 1 || o.guard < 0 || (int64_t)k + o.guard >= n || !(tol >= 0.0) || maxiter < 1) return SC_EDOMAIN;
+  if (n > (int64_t)0x7fffffff) return SC_EDOMAIN;
+  const int kk = k + o.guard;
+  int64_t m = 0;
+  int b = 0;
+  const int rc0 = resolve_basis(n, kk, o, &m, &b);
+  if (rc0 != SC_OK) return rc0;
+  Arena arena(workspace, workspace_bytes);  // outlives the solver, whose blocks point into it
   Solver sv;
   sv.rowptr = csr_rowptr;
   sv.col = csr_col;
   sv.val = csr_val;
   sv.n = n;
   sv.nnz = 0;
-  sv.k = k;
+  sv.k = kk;
+  sv.k_out = k;
   sv.tol = tol;
   sv.maxiter = maxiter;
   sv.flags = o.flags;
   sv.timer.mask = o.timing_mask;
   sv.seed = o.seed;
+  sv.v0 = o.v0;
   sv.check_every = o.check_every > 0 ? o.check_every : 2;
   sv.st = reinterpret_cast<hipStream_t>(stream);
-  int64_t m = 0;
-  int b = 0;
-  const int rc0 = resolve_basis(n, k, o, &m, &b);
-  if (rc0 != SC_OK) return rc0;
   sv.m = (int)m;
   sv.b = b;
+  sv.ws_limit = use_workspace ? std::max<size_t>(workspace_bytes, 1) : 0;
   struct Ctx {
     Solver* sv;
     double* ev;
     double* evec;
-  } ctx{&sv, evals_out, evecs_out};
+    Arena* arena;
+  } ctx{&sv, evals_out, evecs_out, use_workspace ? &arena : nullptr};
   const int rc = guarded(
       [](void* p) {
         Ctx* c = static_cast<Ctx*>(p);
+        struct Install {  // the workspace serves every device block of this call, on this thread only
+          explicit Install(Arena* a) { tl_arena = a; }
+          ~Install() { tl_arena = nullptr; }
+        } install(c->arena);
         return c->sv->run(c->ev, c->evec);
       },
       &ctx);
@@ -1416,11 +1554,28 @@ int sc_laplacian_eigsh(const int64_t* csr_rowptr, const int32_t* csr_col, const 
   return rc;
 }
 
+}  // namespace
+
+int sc_laplacian_eigsh(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n, int32_t k,
+                       double tol, int32_t maxiter, double* evals_out, double* evecs_out, void* stream,
+                       const sc_options* opt, sc_stats* stats) {
+  return eigsh_entry(csr_rowptr, csr_col, csr_val, n, k, tol, maxiter, evals_out, evecs_out, stream, opt, stats, nullptr, 0,
+                     false);
+}
+
+int sc_laplacian_eigsh_ws(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n, int32_t k,
+                          double tol, int32_t maxiter, double* evals_out, double* evecs_out, void* stream,
+                          const sc_options* opt, sc_stats* stats, void* workspace, size_t workspace_bytes) {
+  return eigsh_entry(csr_rowptr, csr_col, csr_val, n, k, tol, maxiter, evals_out, evecs_out, stream, opt, stats, workspace,
+                     workspace_bytes, true);
+}
+
 int sc_workspace_bytes(int64_t n, int64_t nnz, int32_t k, const sc_options* opt, size_t* bytes_out) {
   if (!bytes_out || n < 0 || nnz < 0) return SC_EINVAL;
-  if (k < 1 || (int64_t)k >= n || n > (int64_t)0x7fffffff) return SC_EDOMAIN;
   sc_options o{};
   if (opt) o = *opt;
+  if (k < 1 || o.guard < 0 || (int64_t)k + o.guard >= n || n > (int64_t)0x7fffffff) return SC_EDOMAIN;
+  k += o.guard;  // the iteration works for k + guard pairs
   int64_t m = 0;
   int b = 0;
   const int rc = resolve_basis(n, k, o, &m, &b);
@@ -1575,12 +1730,16 @@ int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const 
         // the entry count only steers the kernel choice; it is remembered for the last graph seen so that
         // repeated products with one matrix do not pay a device-to-host round trip each
         static thread_local const int64_t* last_rp = nullptr;
+        static thread_local const int32_t* last_col = nullptr;
+        static thread_local const double* last_val = nullptr;
         static thread_local int64_t last_n = -1, last_nnz = 0;
-        if (last_rp != c->rp || last_n != c->n) {
+        if (last_rp != c->rp || last_col != c->c || last_val != c->v || last_n != c->n) {
           int64_t nnz = 0;
           HIP_TRY(hipMemcpyAsync(&nnz, c->rp + c->n, sizeof(int64_t), hipMemcpyDeviceToHost, c->st));
           HIP_TRY(hipStreamSynchronize(c->st));
           last_rp = c->rp;
+          last_col = c->c;
+          last_val = c->v;
           last_n = c->n;
           last_nnz = nnz;
         }

@@ -17,6 +17,11 @@ constexpr int kPartialPad = 32;    // column stride of partial / coefficient blo
 // flag[0] |= 1 if rowptr is not monotone / rowptr[0] != 0, |= 2 if a column is out of range.
 hipError_t launch_validate_csr(const int64_t* rowptr, const int32_t* col, int64_t n, int64_t nnz, int* flag,
                                hipStream_t st);
+// flag[0] |= 8 if W is not symmetric (for some entry (i, j) the weights listed in row i under column j and in row j
+// under column i add up to different values), |= 16 if a weight is negative or not finite.  Only for a CSR that
+// launch_validate_csr has accepted (columns are used as row indices).
+hipError_t launch_validate_symmetry(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n, int* flag,
+                                    hipStream_t st);
 // d_i = sum of row i, s_i = d_i^-1/2; flag[0] |= 4 if some d_i is <= 0 or not finite.  d may be null.
 hipError_t launch_degree_scaling(const int64_t* rowptr, const double* val, int64_t n, double* d, double* s, int* flag,
                                  hipStream_t st);
@@ -110,6 +115,12 @@ hipError_t launch_nullspace_fill(double* basis, int64_t n, int64_t ld, int col0,
                                  const double* coef, hipStream_t st);
 
 // ---- misc ----------------------------------------------------------------------------------
+// dst[i*ldd + dcol0 + t] -= src[i*lds + scol0 + t], t < w (regions must not overlap)
+hipError_t launch_sub_cols(const double* src, int64_t lds, int scol0, double* dst, int64_t ldd, int dcol0, int w,
+                           int64_t n, hipStream_t st);
+// basis[i*ld + col] = v[rowmap ? rowmap[i] : i]
+hipError_t launch_set_column(double* basis, int64_t n, int64_t ld, int col, const double* v, const int32_t* rowmap,
+                             hipStream_t st);
 // basis[i, col0 + t] = uniform(-1, 1) from a counter-based hash of (seed, stream_id, i, t)
 hipError_t launch_random_block(double* basis, int64_t n, int64_t ld, int col0, int b, uint64_t seed,
                                uint64_t stream_id, hipStream_t st);

@@ -43,6 +43,34 @@ __global__ __launch_bounds__(kThreads) void validate_col_kernel(const int32_t* _
   if (bad) atomicOr(flag, 2);
 }
 
+// Symmetry and sign of the weights, one wave per row.  For every entry (i, j) the weights of row i listed under
+// column j must add up to the weights of row j listed under column i (rows may be unsorted and may list a column
+// more than once, so both sides are summed in storage order); equality is required up to four units in the last
+// place of the larger side, the most that two different summation orders of a handful of duplicates can differ by.
+// flag |= 8 if some pair differs, |= 16 if a weight is negative or not finite.
+__global__ __launch_bounds__(kThreads) void validate_symmetry_kernel(const int64_t* __restrict__ rowptr,
+                                                                     const int32_t* __restrict__ col,
+                                                                     const double* __restrict__ val, int64_t n,
+                                                                     int* __restrict__ flag) {
+  const int64_t i = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6;
+  const int lane = threadIdx.x & 63;
+  if (i >= n) return;
+  const int64_t a0 = rowptr[i], a1 = rowptr[i + 1];
+  int bad = 0;
+  for (int64_t e = a0 + lane; e < a1; e += 64) {
+    const int32_t j = col[e];
+    const double w = val[e];
+    if (!(w >= 0.0) || isinf(w)) bad |= 16;
+    double mine = 0.0, theirs = 0.0;
+    for (int64_t f = a0; f < a1; ++f) mine += col[f] == j ? val[f] : 0.0;
+    const int64_t b0 = rowptr[j], b1 = rowptr[j + 1];
+    for (int64_t f = b0; f < b1; ++f) theirs += (int64_t)col[f] == i ? val[f] : 0.0;
+    const double big = fmax(fabs(mine), fabs(theirs));
+    if (!(fabs(mine - theirs) <= 8.9e-16 * big)) bad |= 8;
+  }
+  if (bad) atomicOr(flag, bad);
+}
+
 // 16 lanes per row
 __global__ __launch_bounds__(kThreads) void degree_kernel(const int64_t* __restrict__ rowptr,
                                                           const double* __restrict__ val, int64_t n,
@@ -926,6 +954,27 @@ __global__ __launch_bounds__(kThreads) void random_block_kernel(double* __restri
   basis[i * ld + col0 + t] = 2.0 * u - 1.0;
 }
 
+// dst[i, dcol0 + t] -= src[i, scol0 + t], t < w
+__global__ __launch_bounds__(kThreads) void sub_cols_kernel(const double* __restrict__ src, int64_t lds, int scol0,
+                                                            double* __restrict__ dst, int64_t ldd, int dcol0, int w,
+                                                            int64_t n) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= n * w) return;
+  const int64_t i = idx / w;
+  const int t = (int)(idx - i * w);
+  dst[i * ldd + dcol0 + t] -= src[i * lds + scol0 + t];
+}
+
+// basis[i, col] = v[r(i)]: one column of the row-major basis from a plain vector in the caller's numbering
+// (r(i) = rowmap[i], the original index of internal row i, if rowmap is given, else i)
+__global__ __launch_bounds__(kThreads) void set_column_kernel(double* __restrict__ basis, int64_t n, int64_t ld, int col,
+                                                              const double* __restrict__ v,
+                                                              const int32_t* __restrict__ rowmap) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= n) return;
+  basis[i * ld + col] = v[rowmap ? (int64_t)rowmap[i] : i];
+}
+
 __global__ __launch_bounds__(kThreads) void copy_cols_kernel(const double* __restrict__ src, int64_t lds, int scol0,
                                                              double* __restrict__ dst, int64_t ldd, int dcol0, int w,
                                                              int64_t n) {
@@ -1385,6 +1434,14 @@ hipError_t launch_validate_csr(const int64_t* rowptr, const int32_t* col, int64_
   return hipGetLastError();
 }
 
+hipError_t launch_validate_symmetry(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n, int* flag,
+                                    hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(validate_symmetry_kernel, dim3((unsigned)ceil_div64(n * 64, kThreads)), dim3(kThreads), 0, st,
+                     rowptr, col, val, n, flag);
+  return hipGetLastError();
+}
+
 hipError_t launch_degree_scaling(const int64_t* rowptr, const double* val, int64_t n, double* d, double* s, int* flag,
                                  hipStream_t st) {
   hipLaunchKernelGGL(degree_kernel, dim3((unsigned)ceil_div64(n * 16, kThreads)), dim3(kThreads), 0, st, rowptr, val,
@@ -1599,6 +1656,22 @@ hipError_t launch_random_block(double* basis, int64_t n, int64_t ld, int col0, i
                                uint64_t stream_id, hipStream_t st) {
   hipLaunchKernelGGL(random_block_kernel, dim3((unsigned)ceil_div64(n * b, kThreads)), dim3(kThreads), 0, st, basis, n,
                      ld, col0, b, seed, stream_id);
+  return hipGetLastError();
+}
+
+hipError_t launch_sub_cols(const double* src, int64_t lds, int scol0, double* dst, int64_t ldd, int dcol0, int w,
+                           int64_t n, hipStream_t st) {
+  if (w <= 0 || n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(sub_cols_kernel, dim3((unsigned)ceil_div64(n * w, kThreads)), dim3(kThreads), 0, st, src, lds, scol0,
+                     dst, ldd, dcol0, w, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_set_column(double* basis, int64_t n, int64_t ld, int col, const double* v, const int32_t* rowmap,
+                             hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(set_column_kernel, dim3((unsigned)ceil_div64(n, kThreads)), dim3(kThreads), 0, st, basis, n, ld, col,
+                     v, rowmap);
   return hipGetLastError();
 }
 

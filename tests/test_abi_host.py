@@ -25,9 +25,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layouts_match_header_sizes():
-    # sc_options: 3 x int32 + uint32 + uint64 + 2 x uint32 = 32 bytes;
+    # sc_options: 3 x int32 + uint32 + uint64 + uint32 + int32 + pointer = 40 bytes;
     # sc_stats: 8 x int32 + 2 x int64 + 4 x double + 3 x double[6] + int64[6] = 80 + 192 = 272
-    assert ctypes.sizeof(binding.ScOptions) == 32
+    assert ctypes.sizeof(binding.ScOptions) == 40
     assert ctypes.sizeof(binding.ScStats) == 272
 
 

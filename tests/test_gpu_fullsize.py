@@ -14,8 +14,9 @@ Config 4 (4,000,000 nodes) gets three runs, each named for what it is:
     them at tol = 1e-7 within minutes); the run must execute sparse products and reorthogonalizations at k = 200,
     m = 400 and report what it reached;
   * plain path, unit weights on the same edges (a clean gap after the zeros): full parity against the component oracle;
-  * SC_FLAG_COMPONENT_NULLSPACE: the closed-form null vectors of the components, locked by the optional pre-pass.  This
-    run does no sparse product; it is a check of the pre-pass, not of the hot path."""
+  * SC_FLAG_COMPONENT_NULLSPACE: the closed-form null vectors of the components, locked by the optional pre-pass after
+    their residuals have been formed with block products.  This run takes no Lanczos step; it is a check of the
+    pre-pass, not of the hot path."""
 import os
 import sys
 import time
@@ -166,10 +167,14 @@ def test_config4_plain_path_bounded(cfg4):
 
 def test_config4_unit_weights_plain_path(cfg4):
     """Secondary run, labelled as such: config 4's edges with unit weights.  Same 200 components, but the ladder of
-    near-zero eigenvalues that the global Gaussian bandwidth creates is gone, so the plain path converges; full parity
-    against the component oracle (closed-form null space)."""
+    near-zero eigenvalues that the global Gaussian bandwidth creates is gone (the next eigenvalue is about 0.009), so
+    the plain path converges; full parity against the component oracle (closed-form null space).  tol = 1e-8 instead
+    of the workload's 1e-7: the containment bar of 1e-5 rad needs residual / gap <= 1e-5, and 1e-7 / 0.009 is just
+    above it (measured 1.06e-5 at tol = 1e-7)."""
+    import dataclasses
     from paper_1802_04450_amd import binding as B
     cfg, g, _ = cfg4
+    cfg = dataclasses.replace(cfg, tol=1e-8)
     rp, c, v, n = g
     gu = (rp, c, np.ones_like(v), n)
     host = HostChecks(gu, "cfg4 unit")
@@ -180,10 +185,11 @@ def test_config4_unit_weights_plain_path(cfg4):
 
 def test_config4_component_nullspace_prepass(cfg4):
     """SC_FLAG_COMPONENT_NULLSPACE on the Gaussian-weight graph: the pre-pass locks D^1/2 1_C / sqrt(vol C) for the 200
-    components and the solver returns them.  No sparse product of the Lanczos loop runs; the vectors are verified here
-    by recomputed residuals and containment."""
+    components (each after its residual ||S v - v|| met tol) and the solver returns them.  No Lanczos step runs
+    (block_steps = 0): this is the shortcut, not the hot path; the vectors are verified here by recomputed residuals and
+    containment."""
     from paper_1802_04450_amd import binding as B
     cfg, g, host = cfg4
     assert host.ncomp >= cfg.k
     lam, res, code, stats = solve_and_check(B, cfg, g, host, "cfg4 prepass", flags=B.SC_FLAG_COMPONENT_NULLSPACE)
-    assert stats["components"] == host.ncomp
+    assert stats["components"] == host.ncomp and stats["block_steps"] == 0 and stats["spmv_cols"] == cfg.k
