@@ -4,7 +4,13 @@
 A "step" is one complete eigensolve (sc_laplacian_eigsh: setup, block Lanczos, final Ritz vectors) of the
 benchmark workload with the CSR graph already resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|...] [--no-cpu-baseline]
+The headline workload is the largest one, config 5 (n = 500,000, k = 2,000, m = 4,000: a 16 GB basis, the
+reorthogonalization-dominated case), through the plain path.  The default run adds, as extra keys of the same line,
+the eigensolve seconds of configs 1, 2 and 3 (`per_config`), the single-vector product on the 4,000,000-node graph of
+config 4 (`spmv_large`: the only size at which the product is bandwidth-bound), a complete run of the CPU oracle on
+config 2 (`cpu_baseline_cfg2`) and an extrapolated oracle time for the headline workload (`cpu_baseline`).
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg2|...] [--no-extras] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -40,17 +46,25 @@ TRAFFIC_PREFIX = ["spmm_", "project_kernel", ("row_gemm_kernel", "update_gram_ke
 
 def profiled_traffic(workload: str, family: int):
     """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by the plain-copy calibration) of the family's dominant
-    kernel, from the rocprofv3 counter summary committed for this workload; None when there is none."""
-    path = os.path.join(ROOT, "profiles", f"{workload}_bench_traffic.txt")
+    kernel, from the rocprofv3 counter summary committed for this workload.  The summary records the hash of the kernel
+    sources it was measured on; when that is not the tree's hash (or there is no summary) the figure is None: a
+    counter reading of other code is not a measurement of this run."""
+    from paper_1802_04450_amd.build import source_hash
+    path = os.path.join(ROOT, "profiles", f"{workload}_eigensolve_traffic.txt")
     if not os.path.exists(path):
-        return None, None
+        return None, None, "no counter summary for this workload"
+    recorded, rows = None, []
     for line in open(path):
-        if line.startswith("#") or not line.strip():
-            continue
-        name, fetch, write, _avg = line.rsplit(None, 3)
+        if line.startswith("# csrc_sha256:"):
+            recorded = line.split(":", 1)[1].strip()
+        elif line.strip() and not line.startswith("#"):
+            rows.append(line.rsplit(None, 3))
+    if recorded != source_hash():
+        return None, None, "counter summary was measured on other kernel sources"
+    for name, fetch, write, _avg in rows:
         if name.startswith(TRAFFIC_PREFIX[family]):
-            return float(fetch) + float(write), name
-    return None, None
+            return float(fetch) + float(write), name, f"profiles/{workload}_eigensolve_traffic.txt"
+    return None, None, "kernel not in the counter summary"
 
 
 def build_workload(name: str):
@@ -69,25 +83,57 @@ def build_workload(name: str):
     return cfg, graph
 
 
-def cpu_baseline(cfg, graph, budget_s: float = 20.0):
-    """The oracle as it stands, on the host cores, on a bounded sample: the first `ks` of the k wanted pairs
-    (same graph, same tolerance, same basis budget), time scaled by k / ks."""
-    from oracle import lanczos
-    rp, c, v, n = graph
-    ks = max(2, min(cfg.k, 10))
+def host_threads() -> int:
     try:
         import threadpoolctl
-        threads = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
+        return int(max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1))
     except Exception:
-        threads = os.cpu_count() or 1
+        return os.cpu_count() or 1
+
+
+def cpu_baseline_full(cfg, graph):
+    """The oracle as it stands, run to the end on this workload (same graph, tolerance and basis budget)."""
+    from oracle import lanczos
+    rp, c, v, n = graph
+    t0 = time.time()
+    lam, vec, info = lanczos.lanczos_smallest(rp, c, v, k=cfg.k, tol=cfg.tol, m=cfg.m or None, seed=0, return_info=True)
+    dt = time.time() - t0
+    return {"value": dt, "unit": "s", "cores": host_threads(), "kind": "oracle",
+            "sample": f"one complete oracle solve of {cfg.name} (k={cfg.k}, m={cfg.m}, tol={cfg.tol}): {info['spmv']} SpMV, "
+                      f"{info['phases']} phases, converged={info['converged']}, largest |lambda| {float(np.max(np.abs(lam))):.1e}"}
+
+
+def cpu_baseline_extrapolated(cfg, graph):
+    """For the workloads whose complete oracle run takes hours: the oracle's own pieces timed at the real size -
+    its Lanczos for the first few pairs (steps per pair), its sparse product, and its twice-applied Gram-Schmidt
+    against k/2 stored vectors (the average number over a solve that locks one pair per phase) - and
+    steps x seconds-per-step from them.  Labelled as an extrapolation."""
+    from oracle import lanczos, laplacian
+    rp, c, v, n = graph
+    ks = 3
     t0 = time.time()
     lam, vec, info = lanczos.lanczos_smallest(rp, c, v, k=ks, tol=cfg.tol, m=cfg.m or None, seed=0, return_info=True)
-    dt = time.time() - t0
-    scaled = dt * cfg.k / ks
-    return {"value": scaled, "unit": "s", "cores": int(threads), "kind": "oracle",
-            "sample": f"oracle Lanczos for the first {ks} of k={cfg.k} pairs took {dt:.2f}s ({info['spmv']} SpMV, "
-                      f"{info['phases']} phases); scaled by k/{ks} (a lower bound: its reorthogonalization cost "
-                      f"grows with the number of locked vectors)"}
+    dt_few = time.time() - t0
+    steps_per_pair = info["spmv"] / max(1, info["locked"])
+    op = laplacian.NormalizedOperator(rp, c, v)
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal(n)
+    t0 = time.time()
+    for _ in range(3):
+        op(x)
+    t_spmv = (time.time() - t0) / 3
+    j = max(1, min(cfg.k // 2, int(3.0e9 / (8 * n))))       # stored vectors of the timed reorthogonalization (<= 3 GB)
+    basis = rng.standard_normal((n, j))
+    t0 = time.time()
+    lanczos._cgs2(x.copy(), [basis])
+    t_cgs2_j = time.time() - t0
+    t_cgs2 = t_cgs2_j * (cfg.k / 2) / j                     # linear in the number of stored vectors
+    steps = steps_per_pair * cfg.k
+    return {"value": steps * (t_spmv + t_cgs2), "unit": "s", "cores": host_threads(), "kind": "oracle-extrapolated",
+            "sample": f"oracle Lanczos for the first {info['locked']} pairs: {info['spmv']} steps in {dt_few:.1f}s "
+                      f"({steps_per_pair:.1f} steps per pair); oracle product {t_spmv * 1e3:.1f} ms; oracle CGS2 against "
+                      f"{j} vectors {t_cgs2_j * 1e3:.0f} ms, scaled to the average {cfg.k // 2}; value = {steps:.0f} steps x "
+                      f"{(t_spmv + t_cgs2) * 1e3:.0f} ms (no complete oracle run at this size: it would take hours)"}
 
 
 def measure_spmv(B, torch, drp, dc, dv, n, nnz):
@@ -328,26 +374,70 @@ def bench_knn(B, torch, args):
     print(json.dumps(out), flush=True)
 
 
+def timed_eigensolve(B, torch, cfg, dev, steps, warmup, block=0, m=None, check_every=0):
+    """Survey solve (every kernel family event-timed, untimed by the wall clock), warm-ups, then `steps` solves timed
+    with the wall clock between device synchronisations, HIP events round every launch of the dominant family only."""
+    drp, dc, dv = dev
+    kw = dict(m=cfg.m if m is None else m, block=block, check_every=check_every)
+
+    def solve(timing_mask=0):
+        return B.sc_laplacian_eigsh(drp, dc, dv, cfg.k, cfg.tol, timing_mask=timing_mask, **kw)
+
+    survey = solve(timing_mask=63)[3]
+    fam_t = survey["fam_time_s"]
+    dom = int(np.argmax(fam_t))
+    log(f"[bench] {cfg.name} kernel families (s per solve): "
+        + ", ".join(f"{B.FAMILIES[f]}={fam_t[f]:.4f}" for f in range(6))
+        + f"; host eig={survey['t_host_eig']:.4f}; total={survey['t_total']:.4f}")
+    for _ in range(max(0, warmup - 1)):
+        solve()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    last = None
+    for _ in range(steps):
+        last = solve(timing_mask=1 << dom)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
+    return sec, last, survey, dom
+
+
+def family_rates(B, survey):
+    out = {}
+    for f in range(6):
+        t = survey["fam_time_s"][f]
+        if t > 0:
+            out[B.FAMILIES[f]] = {"seconds_per_step": t, "launches": survey["fam_launches"][f],
+                                  "hbm_gbps_algorithmic": survey["fam_bytes"][f] / t / 1e9,
+                                  "hbm_frac": survey["fam_bytes"][f] / t / 1e9 / HBM_PEAK_GBS,
+                                  "fp64_tflops": survey["fam_flops"][f] / t / 1e12,
+                                  "fp64_mfma_frac": survey["fam_flops"][f] / t / 1e12 / FP64_MFMA_PEAK_TFLOPS}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--workload", default=None,
+                    help="cfg1..cfg5, syn200, dblp_like, fb_like; default cfg5 for the eigensolve, cfg2 for the secondary "
+                         "stages (--kmeans, --knn)")
     ap.add_argument("--block", type=int, default=0)
     ap.add_argument("--m", type=int, default=-1)
     ap.add_argument("--check-every", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the headline workload: no per_config solves of configs 1-3, no spmv_large, no complete "
+                         "oracle run on config 2")
     ap.add_argument("--spmv-only", action="store_true",
-                    help="build the workload, measure only the single-vector product y = S x, print its JSON and stop "
-                         "(for the workloads whose eigensolve is not the benchmark: cfg3, cfg4, cfg5)")
+                    help="build the workload, measure only the single-vector product y = S x, print its JSON and stop")
     ap.add_argument("--no-large-spmv", action="store_true",
                     help="skip the single-vector product on the 4,000,000-node workload (config 4) that the default run "
                          "adds as `spmv_large`: the product is bandwidth-bound only at that size (about 40 s, most of "
                          "it building the graph)")
     ap.add_argument("--kmeans", action="store_true",
                     help="the clustering step that follows the eigensolve (Algorithms 4-5) on a synthetic row-normalised "
-                         "embedding of the benchmark workload's shape (n points, d = k); prints its own JSON line")
+                         "embedding of the workload's shape (n points, d = k; default config 2); prints its own JSON line")
     ap.add_argument("--similarity", action="store_true",
                     help="the graph-construction step (Algorithm 1 + the COO to CSR conversion of Algorithm 2) on "
                          "synthetic data of the shape of the paper's DTI input; prints its own JSON line")
@@ -376,6 +466,8 @@ def main():
     from paper_1802_04450_amd import binding as B
     B.lib()
 
+    if args.workload is None:
+        args.workload = "cfg2" if (args.kmeans or args.knn) else "cfg5"
     if args.kmeans:
         bench_kmeans(B, torch, args)
         return
@@ -388,36 +480,16 @@ def main():
     cfg, graph = build_workload(args.workload)
     rp, c, v, n = graph
     nnz = int(rp[-1])
-    drp, dc, dv = B.csr_to_device(rp, c, v)
+    dev = B.csr_to_device(rp, c, v)
     if args.spmv_only:
-        print(json.dumps({"workload": f"{cfg.name}: n={n}, nnz={nnz}", "spmv": measure_spmv(B, torch, drp, dc, dv, n, nnz)}),
+        print(json.dumps({"workload": f"{cfg.name}: n={n}, nnz={nnz}", "spmv": measure_spmv(B, torch, *dev, n, nnz)}),
               flush=True)
         return
-    m = cfg.m if args.m < 0 else args.m
-    kw = dict(m=m, block=args.block, check_every=args.check_every)
-
-    def solve(timing_mask=0):
-        return B.sc_laplacian_eigsh(drp, dc, dv, cfg.k, cfg.tol, timing_mask=timing_mask, **kw)
-
-    # untimed: every kernel family is event-timed once to find the dominant one
-    survey = solve(timing_mask=63)[3]
-    fam_t = survey["fam_time_s"]
-    dom = int(np.argmax(fam_t))
-    log("[bench] kernel families (s per solve): " + ", ".join(f"{B.FAMILIES[f]}={fam_t[f]:.4f}" for f in range(6))
-        + f"; host eig={survey['t_host_eig']:.4f}; total={survey['t_total']:.4f}")
-    for _ in range(max(0, args.warmup - 1)):
-        solve()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    last = None
-    for _ in range(args.steps):
-        last = solve(timing_mask=1 << dom)     # HIP events around every launch of the dominant family only
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    sec, last, survey, dom = timed_eigensolve(B, torch, cfg, dev, args.steps, args.warmup, block=args.block,
+                                              m=None if args.m < 0 else args.m, check_every=args.check_every)
     evals, evecs, code, stats = last
-    sec = elapsed / args.steps
-
-    spmv = measure_spmv(B, torch, drp, dc, dv, n, nnz)
+    fam_t = survey["fam_time_s"]
+    spmv = measure_spmv(B, torch, *dev, n, nnz)
 
     out = {
         "metric": "eigensolve s + SpMV HBM GB/s, k smallest eigvecs of n-node kNN Laplacian",
@@ -425,7 +497,7 @@ def main():
         "ms_per_step": sec * 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={n}, nnz={nnz}, k={cfg.k}, m={stats['m']}, tol={cfg.tol}, "
-                               f"block={stats['block']}", "status": int(code)},
+                               f"block={stats['block']}", "status": int(code), "path": "plain (default options)"},
         "spmv": spmv,
         "solver_stats": stats,
     }
@@ -433,43 +505,67 @@ def main():
     if kt > 0:
         launches = stats["fam_launches"][dom]
         ach = stats["fam_bytes"][dom] / kt / 1e9
-        traffic, traffic_kernel = profiled_traffic(args.workload, dom) if args.block == 0 else (None, None)
+        if args.block == 0 and args.m < 0:
+            traffic, traffic_kernel, traffic_source = profiled_traffic(args.workload, dom)
+        else:
+            traffic, traffic_kernel, traffic_source = None, None, "non-default options"
         out["roofline"] = {"bound": "hbm", "kernel": KERNEL_OF_FAMILY[dom],
                            "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                           "traffic": traffic, "traffic_kernel": traffic_kernel, "launches_per_step": launches,
-                           "avg_launch_us": kt / max(1, launches) * 1e6,
+                           "traffic": traffic, "traffic_kernel": traffic_kernel, "traffic_source": traffic_source,
+                           "launches_per_step": launches, "avg_launch_us": kt / max(1, launches) * 1e6,
                            "algorithmic_bytes_per_launch": stats["fam_bytes"][dom] / max(1, launches),
                            "fp64_tflops": stats["fam_flops"][dom] / kt / 1e12,
                            "fp64_mfma_frac": stats["fam_flops"][dom] / kt / 1e12 / FP64_MFMA_PEAK_TFLOPS,
                            "family_seconds_per_step": {B.FAMILIES[f]: fam_t[f] for f in range(6)}}
-    # the reorthogonalization GEMMs (CGS2 projection H = Q^T W and update W -= Q H, fp64 MFMA), from the survey solve in
-    # which every family was event-timed: achieved HBM rate by the byte model and fp64 rate against the matrix peak
-    reorth = {}
-    for f in (1, 2):
-        if fam_t[f] > 0:
-            reorth[B.FAMILIES[f]] = {"seconds_per_step": fam_t[f], "launches": survey["fam_launches"][f],
-                                     "hbm_gbps_algorithmic": survey["fam_bytes"][f] / fam_t[f] / 1e9,
-                                     "hbm_frac": survey["fam_bytes"][f] / fam_t[f] / 1e9 / HBM_PEAK_GBS,
-                                     "fp64_tflops": survey["fam_flops"][f] / fam_t[f] / 1e12,
-                                     "fp64_mfma_frac": survey["fam_flops"][f] / fam_t[f] / 1e12 / FP64_MFMA_PEAK_TFLOPS}
-    out["reorth"] = reorth
-    if args.workload == "cfg2" and not args.no_large_spmv:
-        # The benchmark workload's product moves 42 MB and is launch-latency bound; the HBM-bound figure is the one of
-        # the 4,000,000-node workload, measured here in the same run (graph built on the box, resident in HBM).
-        del drp, dc, dv
-        B.sc_release_cache()
-        torch.cuda.empty_cache()
-        cfg4, graph4 = build_workload("cfg4")
-        rp4, c4, v4, n4 = graph4
-        nnz4 = int(rp4[-1])
-        d4 = B.csr_to_device(rp4, c4, v4)
-        large = measure_spmv(B, torch, d4[0], d4[1], d4[2], n4, nnz4)
-        large["workload"] = f"{cfg4.name}: n={n4}, nnz={nnz4}"
-        out["spmv_large"] = large
-        del d4
-        B.sc_release_cache()
+    # every kernel family of the survey solve (all of them event-timed): achieved HBM rate by the byte model and fp64
+    # rate against the matrix peak; "project" and "update" are the reorthogonalization GEMMs
+    rates = family_rates(B, survey)
+    out["families"] = rates
+    out["reorth"] = {f: rates[f] for f in ("project", "update") if f in rates}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, graph)
+        if cfg.n <= 150_000:
+            out["cpu_baseline"] = cpu_baseline_full(cfg, graph)
+        else:
+            out["cpu_baseline"] = cpu_baseline_extrapolated(cfg, graph)
+    del dev, evals, evecs, last
+    B.sc_release_cache()
+    torch.cuda.empty_cache()
+
+    if not args.no_extras:
+        per = {}
+        for name in ("cfg1", "cfg2", "cfg3"):
+            if name == args.workload:
+                continue
+            cfg_x, graph_x = build_workload(name)
+            dev_x = B.csr_to_device(*graph_x[:3])
+            sec_x, last_x, survey_x, dom_x = timed_eigensolve(B, torch, cfg_x, dev_x, max(2, args.steps), 1)
+            st = last_x[3]
+            per[name] = {"workload": f"{cfg_x.name}: n={graph_x[3]}, nnz={int(graph_x[0][-1])}, k={cfg_x.k}, m={st['m']}, "
+                                     f"tol={cfg_x.tol}, block={st['block']}",
+                         "seconds": sec_x, "status": int(last_x[2]), "block_steps": st["block_steps"],
+                         "filter_steps": st["filter_steps"], "spmv_cols": st["spmv_cols"], "phases": st["phases"],
+                         "dominant_family": B.FAMILIES[dom_x], "families": family_rates(B, survey_x)}
+            if name == "cfg2":
+                per[name]["spmv"] = measure_spmv(B, torch, *dev_x, graph_x[3], int(graph_x[0][-1]))
+                if not args.no_cpu_baseline:
+                    out["cpu_baseline_cfg2"] = cpu_baseline_full(cfg_x, graph_x)
+            del dev_x, last_x
+            B.sc_release_cache()
+            torch.cuda.empty_cache()
+        out["per_config"] = per
+        if not args.no_large_spmv and args.workload != "cfg4":
+            # The product of the other workloads moves at most a few hundred MB and is latency bound; the HBM-bound figure
+            # is the one of the 4,000,000-node workload, measured here in the same run (graph built on the box, resident
+            # in HBM), on the numbering the solver works in.
+            cfg4, graph4 = build_workload("cfg4")
+            rp4, c4, v4, n4 = graph4
+            nnz4 = int(rp4[-1])
+            d4 = B.csr_to_device(rp4, c4, v4)
+            large = measure_spmv(B, torch, d4[0], d4[1], d4[2], n4, nnz4)
+            large["workload"] = f"{cfg4.name}: n={n4}, nnz={nnz4}"
+            out["spmv_large"] = large
+            del d4
+            B.sc_release_cache()
     print(json.dumps(out), flush=True)
 
 

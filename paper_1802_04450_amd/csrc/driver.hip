@@ -1472,6 +1472,40 @@ int kmeans_args_ok(const double* points, int64_t ld, int32_t colmajor, int64_t n
 
 }  // namespace
 
+namespace {
+
+// Block QR on caller-visible scratch: part (kMaxPartials * b * kPP doubles), gpart (kGramPartials * kPP * kPP) and
+// small (5 * kPP * kPP).  Every entry of the scratch is written by a kernel before a kernel reads it, so its contents
+// on entry do not matter.
+void run_block_qr(double* basis, int64_t n, int64_t ld, int j, int b, double* r_out, double* g_out, double* part,
+                  double* gpart, double* small, hipStream_t st) {
+  double* rinv = small;
+  double* r1 = small + kPP * kPP;
+  double* rr = small + 2 * kPP * kPP;
+  double* gg = small + 3 * kPP * kPP;
+  double* gram = small + 4 * kPP * kPP;
+  enqueue_block_qr(basis, n, ld, j, b, part, gpart, 0, gram, rinv, r1, rr, gg, nullptr, nullptr, st, nullptr);
+  const size_t w = (size_t)b * sizeof(double);
+  if (r_out)
+    HIP_TRY(hipMemcpy2DAsync(r_out, w, rr, (size_t)kPP * sizeof(double), w, (size_t)b, hipMemcpyDeviceToDevice, st));
+  if (g_out)
+    HIP_TRY(hipMemcpy2DAsync(g_out, w, gg, (size_t)kPP * sizeof(double), w, (size_t)b, hipMemcpyDeviceToDevice, st));
+  HIP_TRY(hipStreamSynchronize(st));
+}
+
+struct BlockQrCall {
+  double* basis;
+  int64_t n, ld;
+  int j, b;
+  double *r, *g;
+  hipStream_t st;
+};
+
+constexpr size_t kQrGpartDoubles = (size_t)kGramPartials * kPP * kPP;
+constexpr size_t kQrSmallDoubles = (size_t)5 * kPP * kPP;
+
+}  // namespace
+
 extern "C" {
 
 int sc_version(void) { return 100; }
@@ -1551,6 +1585,8 @@ int eigsh_entry(const int64_t* csr_rowptr, const int32_t* csr_col, const double*
       &ctx);
   if (stats) *stats = sv.stats;
   if (rc < 0) (void)hipStreamSynchronize(sv.st);
+  if (use_workspace && debug_on())
+    std::fprintf(stderr, "[sceig] workspace: %zu bytes given, high-water mark %zu\n", workspace_bytes, arena.peak());
   return rc;
 }
 
@@ -1598,7 +1634,8 @@ int sc_workspace_bytes(int64_t n, int64_t nnz, int32_t k, const sc_options* opt,
   total += up((size_t)kMaxPartials * jmax * kPP * 8) + up((size_t)kGramPartials * kPP * kPP * 8) + 2 * up(jmax * kPP * 8);
   total += up((size_t)(m / b + 4) * kSlotDoubles * 8) + up(jmax * std::max<size_t>(rot_cols, (size_t)k) * 8);
   if (o.flags & SC_FLAG_COMPONENT_NULLSPACE) total += up(N * 8) + up(N * 4) + up(N * 8);
-  total += 16 * 256;                        // flags, small matrices, the output permutation
+  total += up((size_t)3 * kPP * kPP * 8) + up((size_t)k * 4);  // small matrices, the output permutation
+  total += 16 * 256;                        // flags and counters, alignment of the caller's workspace
   *bytes_out = total;
   return SC_OK;
 }
@@ -1816,35 +1853,15 @@ int sc_block_qr(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, doub
   if (!basis || n < 0) return SC_EINVAL;
   if (!supported_block(b) || j < 0 || ld < (int64_t)j + b) return SC_EDOMAIN;
   if (n == 0) return SC_OK;
-  struct Ctx {
-    double* basis;
-    int64_t n, ld;
-    int j, b;
-    double *r, *g;
-    hipStream_t st;
-  } ctx{basis, n, ld, j, b, r_out, g_out, reinterpret_cast<hipStream_t>(stream)};
+  BlockQrCall ctx{basis, n, ld, j, b, r_out, g_out, reinterpret_cast<hipStream_t>(stream)};
   return guarded(
       [](void* p) {
-        Ctx* c = static_cast<Ctx*>(p);
+        BlockQrCall* c = static_cast<BlockQrCall*>(p);
         DevBuf<double> part, small, gpart;
         part.alloc((size_t)kMaxPartials * c->b * kPP);
-        gpart.alloc((size_t)kGramPartials * kPP * kPP);
-        small.alloc(5 * kPP * kPP);
-        double* rinv = small.p;
-        double* r1 = small.p + kPP * kPP;
-        double* rr = small.p + 2 * kPP * kPP;
-        double* gg = small.p + 3 * kPP * kPP;
-        double* gram = small.p + 4 * kPP * kPP;
-        enqueue_block_qr(c->basis, c->n, c->ld, c->j, c->b, part.p, gpart.p, 0, gram, rinv, r1, rr, gg, nullptr, nullptr,
-                         c->st, nullptr);
-        const size_t w = (size_t)c->b * sizeof(double);
-        if (c->r)
-          HIP_TRY(hipMemcpy2DAsync(c->r, w, rr, (size_t)kPP * sizeof(double), w, (size_t)c->b, hipMemcpyDeviceToDevice,
-                                   c->st));
-        if (c->g)
-          HIP_TRY(hipMemcpy2DAsync(c->g, w, gg, (size_t)kPP * sizeof(double), w, (size_t)c->b, hipMemcpyDeviceToDevice,
-                                   c->st));
-        HIP_TRY(hipStreamSynchronize(c->st));
+        gpart.alloc(kQrGpartDoubles);
+        small.alloc(kQrSmallDoubles);
+        run_block_qr(c->basis, c->n, c->ld, c->j, c->b, c->r, c->g, part.p, gpart.p, small.p, c->st);
         return SC_OK;
       },
       &ctx);
