@@ -280,6 +280,22 @@ int sc_block_qr(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, doub
                 void* stream);
 
 /*
+ * sc_block_qr for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same arithmetic and same results as sc_block_qr, but the call allocates nothing
+ * (no hipMalloc / hipFree, no block cache): its partial Gram blocks and small matrices live in a fixed device array of
+ * 12.6 MB inside the library (about 1.58 million doubles), which every GPU the library runs on holds from the first such
+ * call on it until the process ends.
+ *   Limits: b in {1,2,4,8,16,32} (the array is sized for 32 columns; the number of partial blocks does not grow with
+ *   n), n <= 2^31 - 1; anything else is SC_EDOMAIN and nothing is written.
+ *   All calls on one GPU share that one array: calls that overlap in time on the same GPU (from several threads or
+ *   streams) race and give undefined results; serialise them.  Nothing in the array has to be cleared between calls
+ *   (every entry is written before it is read), and its contents after a call are unspecified.
+ * Returns after the work on `stream` is done, like sc_block_qr.
+ */
+int sc_block_qr_noalloc(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, double* r_out, double* g_out,
+                        void* stream);
+
+/*
  * Restart rotation / Ritz vectors (FindEigenvectors of Algorithm 3): out = basis[:, j0 : j0+ja] * Y.
  *   y       device fp64[ja*l], row-major ja x l
  *   out     device; if out_colmajor == 0 row-major n x l with leading dimension ldo >= l,

@@ -29,7 +29,8 @@ FAMILIES = ["spmm", "project", "update", "rotate", "qr", "other"]
 EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_validate_csr", "sc_reorder_csr", "sc_cgs2",
            "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version", "sc_release_cache",
            "sc_chebyshev_filter", "sc_kmeanspp", "sc_kmeans_lloyd", "sc_kmeans", "sc_edge_similarity", "sc_knn_search", "sc_knn_union_pairs",
-           "sc_coo_to_csr", "sc_workspace_bytes", "sc_scale_operator", "sc_laplacian_eigsh_ws"]
+           "sc_coo_to_csr", "sc_workspace_bytes", "sc_scale_operator", "sc_laplacian_eigsh_ws",
+           "sc_block_qr_noalloc"]
 
 
 class ScOptions(ctypes.Structure):
@@ -98,6 +99,7 @@ def lib() -> ctypes.CDLL:
         _lib.sc_reorder_csr.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp]
         _lib.sc_cgs2.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         _lib.sc_block_qr.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
+        _lib.sc_block_qr_noalloc.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         _lib.sc_rotate.argtypes = [vp, i64, i64, i32, i32, vp, i32, vp, i64, i32, vp]
         _lib.sc_chebyshev_filter.argtypes = [vp, vp, vp, i64, vp, i64, i32, dbl, i32, vp, i64, vp]
         u64 = ctypes.c_uint64
@@ -286,6 +288,15 @@ def sc_block_qr(basis, j: int, b: int):
         code = lib().sc_block_qr(_ptr(basis), n, basis.stride(0), j, b, _ptr(r), _ptr(g), _stream())
     _check(code)
     return r, g
+
+
+def sc_block_qr_noalloc(basis, j: int, b: int, r, g):
+    """sc_block_qr on the library's fixed device scratch: the call allocates nothing, so the outputs r and g ((b, b)
+    device tensors) are the caller's.  Returns the status code."""
+    n, ld = basis.shape
+    with __import__("torch").cuda.device(basis.device):
+        code = lib().sc_block_qr_noalloc(_ptr(basis), n, basis.stride(0), j, b, _ptr(r), _ptr(g), _stream())
+    return _check(code)
 
 
 def sc_rotate(basis, j0: int, ja: int, y, out_colmajor: bool = False):

@@ -1501,8 +1501,38 @@ struct BlockQrCall {
   hipStream_t st;
 };
 
+// Scratch of sc_block_qr_noalloc: device memory that lives in the library's code object, one copy per GPU, from the
+// moment the library is loaded on it until the process ends.  Sized for the largest block (32 columns): the partial
+// Gram blocks of the projection (512) and of the fused scaling pass (1024) and five small matrices.
+constexpr size_t kQrPartDoubles = (size_t)kMaxPartials * kMaxBlock * kPP;
 constexpr size_t kQrGpartDoubles = (size_t)kGramPartials * kPP * kPP;
 constexpr size_t kQrSmallDoubles = (size_t)5 * kPP * kPP;
+constexpr size_t kQrScratchDoubles = kQrPartDoubles + kQrGpartDoubles + kQrSmallDoubles;
+
+}  // namespace
+
+static __device__ __align__(256) double scratch[kQrScratchDoubles];
+
+namespace {
+
+// The array's name is only a handle in host code; its address on a device comes from the runtime, once per device.
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mu;
+double* scratch_ptr[kMaxDevices] = {};
+
+double* scratch_on_current_device() {
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) SC_THROW(SC_EDOMAIN);
+  std::lock_guard<std::mutex> lock(scratch_mu);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) SC_THROW(SC_EHIP);
+    scratch_ptr[dev] = static_cast<double*>(p);
+  }
+  return scratch_ptr[dev];
+}
 
 }  // namespace
 
@@ -1862,6 +1892,24 @@ int sc_block_qr(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, doub
         gpart.alloc(kQrGpartDoubles);
         small.alloc(kQrSmallDoubles);
         run_block_qr(c->basis, c->n, c->ld, c->j, c->b, c->r, c->g, part.p, gpart.p, small.p, c->st);
+        return SC_OK;
+      },
+      &ctx);
+}
+
+int sc_block_qr_noalloc(double* basis, int64_t n, int64_t ld, int32_t j, int32_t b, double* r_out, double* g_out,
+                        void* stream) {
+  if (!basis || n < 0) return SC_EINVAL;
+  // the scratch holds the partial blocks of a block of at most kMaxBlock columns, whatever n is
+  if (!supported_block(b) || b > kMaxBlock || j < 0 || ld < (int64_t)j + b || n > (int64_t)0x7fffffff) return SC_EDOMAIN;
+  if (n == 0) return SC_OK;
+  BlockQrCall ctx{basis, n, ld, j, b, r_out, g_out, reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        BlockQrCall* c = static_cast<BlockQrCall*>(p);
+        double* sp = scratch_on_current_device();
+        run_block_qr(c->basis, c->n, c->ld, c->j, c->b, c->r, c->g, sp, sp + kQrPartDoubles,
+                     sp + kQrPartDoubles + kQrGpartDoubles, c->st);
         return SC_OK;
       },
       &ctx);
