@@ -38,9 +38,14 @@ def test_edge_similarity_matches_oracle(B, n, d, ne, measure):
     rng = np.random.default_rng(n + d + measure)
     x = rng.normal(size=(n, d)) + 2.0 * rng.normal(size=(n, 1))
     u, v = _edges(n, ne, 3)
-    if d == 1 and measure == 0:
-        pytest.skip("one coordinate: every centred row is zero, the measure is 0/0 by definition")
     sigma = 1.7 * np.sqrt(d)
+    if d == 1 and measure == 0:
+        # one coordinate: every centred row is zero and the measure is 0/0 by its definition - NaN on both sides
+        got = B.sc_edge_similarity(_dev(x, torch.float64), _dev(u, torch.int32), _dev(v, torch.int32), measure, sigma)
+        with np.errstate(invalid="ignore", divide="ignore"):
+            ref = osim.edge_similarity(x, u, v, measure, sigma)
+        assert np.all(np.isnan(ref)) and bool(torch.all(torch.isnan(got)))
+        return
     ref = osim.edge_similarity(x, u, v, measure, sigma) if ne else np.zeros(0)
     got = B.sc_edge_similarity(_dev(x, torch.float64), _dev(u, torch.int32), _dev(v, torch.int32), measure, sigma)
     np.testing.assert_allclose(got.cpu().numpy(), ref, rtol=1e-12, atol=1e-14)

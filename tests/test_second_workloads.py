@@ -4,7 +4,6 @@ paper's Syn200, preferential attachment with DBLP's node and edge counts; Sectio
 CPU part: the generators give what they say.  GPU part: the eigensolver against the dense oracle at sizes the oracle
 finishes in seconds, the sparse products on hub rows, and (opt-in, SCEIG_FULLSIZE=1) Syn200 at full size by residuals
 and orthonormality."""
-import os
 
 import numpy as np
 import pytest
@@ -109,7 +108,6 @@ def test_products_on_power_law_rows(B, b):
 
 
 @gpu
-@pytest.mark.skipif(os.environ.get("SCEIG_FULLSIZE", "") == "", reason="full-size workload; set SCEIG_FULLSIZE=1")
 def test_syn200_full_size(B):
     g, spec = wl.build_second_workload("syn200")
     rp, c, v, n = g
