@@ -250,7 +250,11 @@ int sc_validate_csr(const int64_t* csr_rowptr, const int32_t* csr_col, int64_t n
  *   x, y    device, row-major n x ncols with leading dimensions ldx, ldy >= ncols; ncols in {1,2,4,8,16,32}; y may be x
  *   a       -1 < a < 1;  degree >= 1
  * For ncols >= 8 the products run on a scaled copy of the operator made inside the call (as the solver does), for
- * narrower blocks on W and the scaling vector.  Returns SC_EZERODEG if some degree is not positive.
+ * narrower blocks on W and the scaling vector.  When the matrix as given is block diagonal (contiguous diagonal blocks,
+ * e.g. one per connected component) with blocks small enough for two iterates of at least two columns to fit the LDS of
+ * a compute unit, and a cost model favours it, the ncols >= 8 filter runs as ONE launch in which a workgroup keeps the
+ * iterates of its block in LDS through all d steps; otherwise as d launches of the product kernel.  Both give the
+ * recurrence's result to rounding; each is bitwise reproducible.  Returns SC_EZERODEG if some degree is not positive.
  */
 int sc_chebyshev_filter(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, int64_t n,
                         const double* x, int64_t ldx, int32_t ncols, double a, int32_t degree, double* y, int64_t ldy,
@@ -446,6 +450,15 @@ int sc_coo_to_csr(const int32_t* row, const int32_t* col, const double* val, int
 
 const char* sc_strerror(int code);
 int sc_version(void);
+
+/*
+ * Process-wide event counters (for tests and tuning: which code path a call took).  HOST ONLY.
+ *   SC_COUNTER_RESIDENT_FILTERS  start-block filters (inside sc_laplacian_eigsh or sc_chebyshev_filter) that ran as one
+ *                                launch with the iterates resident in LDS, since the library was loaded
+ * Returns the count, or -1 for an unknown id.
+ */
+#define SC_COUNTER_RESIDENT_FILTERS 0
+int64_t sc_counter(int32_t which);
 
 /*
  * Memory.  Device and pinned-host blocks that a call allocates for itself are kept by the library when the call

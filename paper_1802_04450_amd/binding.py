@@ -30,7 +30,7 @@ EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_
            "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version", "sc_release_cache",
            "sc_chebyshev_filter", "sc_kmeanspp", "sc_kmeans_lloyd", "sc_kmeans", "sc_edge_similarity", "sc_knn_search", "sc_knn_union_pairs",
            "sc_coo_to_csr", "sc_workspace_bytes", "sc_scale_operator", "sc_laplacian_eigsh_ws",
-           "sc_block_qr_noalloc"]
+           "sc_block_qr_noalloc", "sc_counter"]
 
 
 class ScOptions(ctypes.Structure):
@@ -118,7 +118,17 @@ def lib() -> ctypes.CDLL:
         _lib.sc_strerror.argtypes = [ctypes.c_int]
         _lib.sc_version.argtypes = []
         _lib.sc_release_cache.argtypes = []
+        _lib.sc_counter.argtypes = [ctypes.c_int32]
+        _lib.sc_counter.restype = ctypes.c_int64
     return _lib
+
+
+SC_COUNTER_RESIDENT_FILTERS = 0
+
+
+def sc_counter(which: int) -> int:
+    """Process-wide event counter of the library (host only)."""
+    return int(lib().sc_counter(which))
 
 
 def sc_release_cache() -> int:

@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsceig.so")
-SOURCES = ["kernels.hip", "reorder.hip", "kmeans.hip", "similarity.hip", "knn.hip", "driver.hip", "sym_eig.cpp"]
+SOURCES = ["kernels.hip", "resident.hip", "reorder.hip", "kmeans.hip", "similarity.hip", "knn.hip", "driver.hip", "sym_eig.cpp"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fopenmp", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

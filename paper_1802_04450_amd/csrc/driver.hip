@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <cmath>
 #include <cstdint>
@@ -401,6 +402,90 @@ void enqueue_block_qr(double* basis, int64_t n, int64_t ld, int col, int b, doub
   tm->end(kFamQr, (ngram > 0 ? 4.0 : 5.0) * blk + (z ? blk : 0.0), 4.0 * (double)n * b * b);
 }
 
+std::atomic<int64_t> resident_launches{0};  // sc_counter(SC_COUNTER_RESIDENT_FILTERS)
+
+// Plan of the LDS-resident Chebyshev filter (resident.hip) for one matrix and block width: the diagonal blocks of the
+// matrix cut into work items (block rows x column slice) whose two iterates fit the LDS of a compute unit.
+struct ResidentPlan {
+  DevBuf<int32_t> items;
+  int nitems = 0;
+  size_t lds_bytes = 0;
+  bool usable = false;
+  double est_step_s = 0.0;  // modelled time of one recurrence step
+};
+
+int device_lds_limit() {
+  int dev = 0, lds = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+  return lds;
+}
+
+// Finds the diagonal blocks on the device, sizes the items on the host.  The plan is usable when every block fits LDS
+// with a slice of at least two columns and the modelled step time beats the general product's: an item costs its
+// entries times (12 bytes streamed + 8 bs bytes read from LDS) at about half a compute unit's LDS rate, the items
+// spread over the 256 compute units, largest first; the general product gathers 8 b bytes per entry from the L2 caches
+// at the 12.5 TB/s measured for it, and no launch is shorter than about 4 us.
+void plan_resident(const int64_t* rowptr, const int32_t* col, int64_t n, int64_t nnz, int b, hipStream_t st,
+                   ResidentPlan* plan) {
+  plan->usable = false;
+  plan->nitems = 0;
+  if (b < 8 || n <= 0 || nnz <= 0 || std::getenv("SCEIG_NO_RESIDENT")) return;
+  const int lds_limit = device_lds_limit() - 1024;
+  if (lds_limit < 32 * 1024) return;
+  DevBuf<char> work;
+  DevBuf<int32_t> starts, count;
+  const size_t wb = diagonal_blocks_workspace(n);
+  work.alloc(wb);
+  starts.alloc((size_t)n);
+  count.alloc(1);
+  HIP_TRY(diagonal_blocks(rowptr, col, n, work.p, wb, starts.p, count.p, st));
+  int32_t nblk = 0;
+  HIP_TRY(hipMemcpyAsync(&nblk, count.p, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (nblk <= 0 || (int64_t)nblk * 16 > (int64_t)1 << 24) return;
+  std::vector<int32_t> hs((size_t)nblk + 1);
+  HIP_TRY(hipMemcpyAsync(hs.data(), starts.p, (size_t)nblk * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  hs[nblk] = (int32_t)n;
+  struct Item {
+    int32_t row0, nrows, col0, bs;
+  };
+  std::vector<Item> items;
+  size_t lds_max = 0;
+  const double avg_deg = (double)nnz / (double)n;
+  double sum_cost = 0.0, max_cost = 0.0;
+  for (int t = 0; t < nblk; ++t) {
+    const int nr = hs[t + 1] - hs[t];
+    int bs = b;
+    while (bs >= 2 && resident_item_lds_bytes(nr, bs) > (size_t)lds_limit) bs /= 2;
+    if (bs < 2) return;  // a block too large for LDS: the general product does the whole filter
+    const double cost = (double)nr * avg_deg * (12.0 + 8.0 * bs);
+    for (int c0 = 0; c0 < b; c0 += bs) {
+      items.push_back(Item{hs[t], nr, c0, bs});
+      sum_cost += cost;
+    }
+    max_cost = std::max(max_cost, cost);
+    lds_max = std::max(lds_max, resident_item_lds_bytes(nr, bs));
+  }
+  const double cu_rate = 150e9;  // bytes per second through one compute unit's LDS and load path, about half of peak
+  plan->est_step_s = std::max(max_cost, sum_cost / 256.0) / cu_rate;
+  const double general_step_s = std::max(4e-6, (double)nnz * 8.0 * b / 12.5e12);
+  if (debug_on())
+    std::fprintf(stderr, "[sceig] resident filter plan: %d blocks, %zu items, LDS %zu, modelled step %.1f us against %.1f us\n",
+                 nblk, items.size(), lds_max, plan->est_step_s * 1e6, general_step_s * 1e6);
+  if (!(plan->est_step_s < general_step_s) && !std::getenv("SCEIG_FORCE_RESIDENT")) return;
+  std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& c) {
+    return (int64_t)a.nrows * a.bs > (int64_t)c.nrows * c.bs;
+  });
+  plan->items.alloc(items.size() * 4);
+  HIP_TRY(hipMemcpyAsync(plan->items.p, items.data(), items.size() * sizeof(Item), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipStreamSynchronize(st));  // `items` is pageable host memory
+  plan->nitems = (int)items.size();
+  plan->lds_bytes = lds_max;
+  plan->usable = true;
+}
+
 // Chebyshev filter of a packed block: result = T_d(g(S)) X, g the affine map taking [-1, a] to [-1, 1], by the
 // three-term recurrence Y_0 = X, Y_1 = g(S) X, Y_{i+1} = 2 g(S) Y_i - Y_{i-1}; one sparse product per step.
 //   wide blocks (val_scaled != null, b >= 8): z holds X packed; the recurrence is fused into the product kernel and
@@ -410,13 +495,23 @@ void enqueue_block_qr(double* basis, int64_t n, int64_t ld, int col, int b, doub
 double* enqueue_cheb_filter(const int64_t* rowptr, const int32_t* col, const double* val, const double* val_scaled,
                             const double* s, int64_t n, int64_t nnz, int b, int d, double a, double* z, double* buf1,
                             double* buf2, double* buf3, double avg_deg, const int32_t* longrows, int nlong,
-                            hipStream_t st, KTimer* tm) {
+                            const ResidentPlan* resident, hipStream_t st, KTimer* tm) {
   KTimer none;
   if (!tm) tm = &none;
   const double lo = -1.0;  // ||S||_2 = 1
   const double c = 0.5 * (a + lo), e = 0.5 * (a - lo);
   const double bytes = 12.0 * (double)nnz + 8.0 * (double)(n + 1) + (val_scaled ? 0.0 : 8.0 * (double)n) +
                        16.0 * (double)n * b;
+  if (val_scaled && resident && resident->usable) {
+    // all d steps in one launch, iterates in LDS: the matrix entries are streamed once per step and column slice, the
+    // block is read once and written once
+    resident_launches.fetch_add(1, std::memory_order_relaxed);
+    tm->begin(kFamSpmm);
+    HIP_TRY(launch_cheb_resident(rowptr, col, val_scaled, z, buf1, b, d, 1.0 / e, 2.0 / e, c, resident->items.p,
+                                 resident->nitems, resident->lds_bytes, st));
+    tm->end(kFamSpmm, d * bytes + (d - 1) * 8.0 * (double)n * b, d * 2.0 * (double)nnz * b, d);
+    return buf1;
+  }
   if (val_scaled) {
     double* cur = z;
     double* prev = buf1;
@@ -525,6 +620,7 @@ struct Solver {
   DevBuf<double> val_s;  // S_ij = s_i W_ij s_j multiplied out: the operator copy used when b >= 8
   DevBuf<int32_t> longrows;  // rows with more than kLongRow entries (wide products only), ascending
   int nlong = 0;
+  ResidentPlan resident;     // LDS-resident start-block filter (wide products on a block-diagonal operator)
   const int32_t* rowmap = nullptr;  // device: original row of each internal row, null if not reordered
   const int32_t* rowinv = nullptr;  // device: internal row of each original row, null if not reordered
   std::vector<int32_t> comp_host;   // component index of each internal row (only after reorder())
@@ -682,6 +778,7 @@ struct Solver {
       HIP_TRY(hipMemcpyAsync(&hcount, lcount.p, sizeof(int32_t), hipMemcpyDeviceToHost, st));
       HIP_TRY(hipStreamSynchronize(st));
       nlong = hcount;
+      if (!(flags & SC_FLAG_NO_START_FILTER)) plan_resident(rowptr, col, n, nnz, b, st, &resident);
     }
     const double t3 = now_s();
 
@@ -743,7 +840,7 @@ struct Solver {
     double* buf3 = rot.p + 2 * (size_t)n * b;
     if (!val_s.p) HIP_TRY(launch_copy_cols(basis.p, ld, nl, buf1, b, 0, b, n, st));
     const double* res = enqueue_cheb_filter(rowptr, col, val, val_s.p, s.p, n, nnz, b, d, a, z.p, buf1, buf2, buf3,
-                                            avg_deg, longrows.p, nlong, st, &timer);
+                                            avg_deg, longrows.p, nlong, &resident, st, &timer);
     stats.spmv_cols += (int64_t)d * b;
     stats.filter_steps += d;
     HIP_TRY(launch_copy_cols(res, b, 0, basis.p, ld, nl, b, n, st));
@@ -1540,6 +1637,13 @@ extern "C" {
 
 int sc_version(void) { return 100; }
 
+int64_t sc_counter(int32_t which) {
+  switch (which) {
+    case SC_COUNTER_RESIDENT_FILTERS: return resident_launches.load(std::memory_order_relaxed);
+    default: return -1;
+  }
+}
+
 int sc_release_cache(void) {
   device_cache().clear();
   pinned_cache().clear();
@@ -1660,6 +1764,8 @@ int sc_workspace_bytes(int64_t n, int64_t nnz, int32_t k, const sc_options* opt,
   }
   total += up(N * 8);                       // scaling vector
   if (b >= 8) total += up(Z * 8) + up(N * 4) + up(long_row_list_workspace(n)) + 256;  // scaled values, long-row list
+  if (b >= 8 && !(o.flags & SC_FLAG_NO_START_FILTER))  // diagonal-block search and the work items of the resident filter
+    total += up(diagonal_blocks_workspace(n)) + up(N * 4) + 256 + up(N * 18);
   total += up(N * ld * 8) + up(N * (size_t)b * 8) + up(N * rot_cols * 8);  // basis, packed block, rotation workspace
   total += up((size_t)kMaxPartials * jmax * kPP * 8) + up((size_t)kGramPartials * kPP * kPP * 8) + 2 * up(jmax * kPP * 8);
   total += up((size_t)(m / b + 4) * kSlotDoubles * 8) + up(jmax * std::max<size_t>(rot_cols, (size_t)k) * 8);
@@ -2009,9 +2115,11 @@ int sc_chebyshev_filter(const int64_t* csr_rowptr, const int32_t* csr_col, const
           HIP_TRY(hipStreamSynchronize(c->st));
           nlong = hcount;
         }
+        ResidentPlan resident;  // used when the matrix as given is block diagonal with blocks that fit LDS
+        if (wide) plan_resident(c->rp, c->c, c->n, nnz, c->b, c->st, &resident);
         const double* res = enqueue_cheb_filter(c->rp, c->c, c->v, wide ? vals.p : nullptr, s.p, c->n, nnz, c->b, c->d,
                                                 c->a, z.p, b1.p, b2.p, b3.p, (double)nnz / (double)c->n,
-                                                wide ? longrows.p : nullptr, nlong, c->st, nullptr);
+                                                wide ? longrows.p : nullptr, nlong, &resident, c->st, nullptr);
         HIP_TRY(launch_copy_cols(res, c->b, 0, c->y, c->ldy, 0, c->b, c->n, c->st));
         HIP_TRY(hipStreamSynchronize(c->st));
         return SC_OK;

@@ -83,6 +83,24 @@ int plan_update_gram(int64_t n);
 // acol0 = ccol0, kdim = b, bmat = R^-1)
 hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int b,
                               int ccol0, int overwrite, double* gpart, hipStream_t st);
+// ---- Chebyshev filter with the iterates resident in LDS (resident.hip) -------------------------------
+// LDS bytes of one work item: two iterates of nrows x bs doubles and the block's row pointers.
+size_t resident_item_lds_bytes(int nrows, int bs);
+// Diagonal blocks of a CSR matrix with a symmetric pattern: starts[0 .. *count) = the rows p (ascending) such that no
+// row before p has an entry in column p or beyond; starts has room for n entries, count is a device int32.
+// work: device scratch of diagonal_blocks_workspace(n) bytes.  n <= INT32_MAX.
+size_t diagonal_blocks_workspace(int64_t n);
+hipError_t diagonal_blocks(const int64_t* rowptr, const int32_t* col, int64_t n, void* work, size_t work_bytes,
+                           int32_t* starts, int32_t* count, hipStream_t st);
+// y = T_d-type recurrence applied to x, both packed n x b: u_0 = x, u_1 = alpha_first (A u_0 - shift u_0),
+// u_{i+1} = alpha_rest (A u_i - shift u_i) - u_{i-1}; y = u_d.  A = the CSR matrix, whose rows [row0, row0 + nrows) of
+// every item form a diagonal block.  items: device int32[4 * nitems] = (row0, nrows, col0, bs) per workgroup, bs in
+// {2, 4, 8, 16, 32} columns starting at col0; every (block, column) pair must be covered exactly once.  lds_bytes =
+// the largest resident_item_lds_bytes over the items.  y must not alias x.
+hipError_t launch_cheb_resident(const int64_t* rowptr, const int32_t* col, const double* val, const double* x, double* y,
+                                int b, int d, double alpha_first, double alpha_rest, double shift, const int32_t* items,
+                                int nitems, size_t lds_bytes, hipStream_t st);
+
 // ---- connected components and locality reordering (setup) --------------------------------------
 // Renumbering from the component labels (label[i] = smallest node index of i's component), on the device:
 //   old_of_new[p] = original index of new row p (components contiguous, ordered by their smallest node; inside a

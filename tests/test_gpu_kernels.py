@@ -311,6 +311,54 @@ def test_chebyshev_filter(B, ncols):
     assert np.max(np.abs(got1 - blockops.chebyshev_filter(rp, c, v, x, a, 1))) <= 1e-13 * max(1.0, np.max(np.abs(x)))
 
 
+def _block_diagonal_graph():
+    """Contiguous diagonal blocks of every kind the LDS-resident filter distinguishes: two rows; fewer rows than lane
+    groups; more than 256 rows (rows beyond the register-kept ones, one and several rounds of them); rows of 1, 33, 69,
+    299 and 500 entries (one batch, two, three, and more than one round of further batches); 1,500 rows (too many for
+    16 or 32 columns at once: column slices)."""
+    star = wl.symmetric_from_edges(np.zeros(500, dtype=np.int64), np.arange(1, 501), np.linspace(0.5, 1.5, 500), 501)
+    return wl.disjoint_union(wl.path(2), wl.random_weighted_connected(700, 9000, 5), wl.ring(257), wl.complete(70),
+                             wl.ring(7), wl.random_weighted_connected(333, 700, 6), wl.complete(300), star,
+                             wl.complete(34), wl.random_weighted_connected(1500, 9000, 7), wl.path(31))
+
+
+@pytest.mark.parametrize("ncols", [8, 16, 32])
+@pytest.mark.parametrize("degree", [1, 2, 12])
+def test_chebyshev_filter_resident_in_lds(B, ncols, degree, monkeypatch):
+    """The one-launch form of the start-block filter (a workgroup keeps the iterates of a diagonal block in LDS through
+    all steps) against the oracle's recurrence, element by element, on a block-diagonal graph as given; it must be the
+    path taken (event counter), be bitwise repeatable, and agree with the product-per-step path to rounding."""
+    from oracle import blockops
+    monkeypatch.setenv("SCEIG_FORCE_RESIDENT", "1")       # small graph: the cost model would pick the other path
+    g = _block_diagonal_graph()
+    rp, c, v, n = g
+    rng = np.random.default_rng(7 * ncols + degree)
+    x = rng.standard_normal((n, ncols))
+    a = 0.4
+    want = blockops.chebyshev_filter(rp, c, v, x, a, degree)
+    drp, dc, dv = B.csr_to_device(rp, c, v)
+    dx = torch.from_numpy(x).cuda()
+    before = B.sc_counter(B.SC_COUNTER_RESIDENT_FILTERS)
+    got = B.sc_chebyshev_filter(drp, dc, dv, dx, a, degree)
+    assert B.sc_counter(B.SC_COUNTER_RESIDENT_FILTERS) == before + 1
+    scale = max(1.0, np.max(np.abs(want)))
+    assert np.max(np.abs(got.cpu().numpy() - want)) <= 1e-11 * scale
+    again = B.sc_chebyshev_filter(drp, dc, dv, dx, a, degree)
+    assert torch.equal(got, again)
+    monkeypatch.delenv("SCEIG_FORCE_RESIDENT")
+    monkeypatch.setenv("SCEIG_NO_RESIDENT", "1")
+    other = B.sc_chebyshev_filter(drp, dc, dv, dx, a, degree)
+    assert B.sc_counter(B.SC_COUNTER_RESIDENT_FILTERS) == before + 2
+    assert np.max(np.abs(other.cpu().numpy() - got.cpu().numpy())) <= 1e-11 * scale
+    # the input block inside a wider buffer, the output into a wider buffer
+    monkeypatch.delenv("SCEIG_NO_RESIDENT")
+    monkeypatch.setenv("SCEIG_FORCE_RESIDENT", "1")
+    xb = torch.zeros((n, ncols + 3), dtype=torch.float64, device="cuda")
+    xb[:, :ncols] = dx
+    got2 = B.sc_chebyshev_filter(drp, dc, dv, xb[:, :ncols], a, degree)
+    assert torch.equal(got2, got)
+
+
 def test_chebyshev_filter_rejects_bad_arguments(B):
     rp, c, v, n = wl.ring(20)
     drp, dc, dv = B.csr_to_device(rp, c, v)
