@@ -6,7 +6,13 @@
 // host (a counter-based generator); a draw is one distance pass that also leaves block sums and one single-workgroup
 // kernel that walks the sums level by level to the drawn point.
 #include <hip/hip_runtime.h>
-#include <hipcub/hipcub.hpp>
+#include <cstring>
+
+#include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_scan.hpp>
+#include <rocprim/device/device_select.hpp>
+#include <rocprim/functional.hpp>
+#include <rocprim/iterator/counting_iterator.hpp>
 
 #include <cstdint>
 
@@ -356,8 +362,8 @@ hipError_t launch_fill_int32(int32_t* a, int64_t n, int32_t value, int use_iota,
 
 size_t kmeans_update_workspace(int64_t n) {
   size_t sort_bytes = 0;
-  (void)hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const int32_t*)nullptr, (int32_t*)nullptr,
-                                           (const int32_t*)nullptr, (int32_t*)nullptr, (int)n, 0, 32, nullptr);
+  (void)rocprim::radix_sort_pairs(nullptr, sort_bytes, (const int32_t*)nullptr, (int32_t*)nullptr,
+                                  (const int32_t*)nullptr, (int32_t*)nullptr, (size_t)n, 0u, 32u, (hipStream_t) nullptr);
   sort_bytes = (sort_bytes + 255) / 256 * 256;
   // temp | ident[n] | sorted_label[n] | member[n]
   return sort_bytes + (size_t)n * 12 + 1024;
@@ -367,8 +373,8 @@ hipError_t launch_centroid_update(const double* x, int64_t ldx, int d, int64_t n
                                   size_t work_bytes, int32_t* start, double* c, hipStream_t st) {
   if (n <= 0 || n > INT32_MAX) return hipErrorInvalidValue;
   size_t sort_bytes = 0;
-  hipError_t e = hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const int32_t*)nullptr, (int32_t*)nullptr,
-                                                    (const int32_t*)nullptr, (int32_t*)nullptr, (int)n, 0, 32, st);
+  hipError_t e = rocprim::radix_sort_pairs(nullptr, sort_bytes, (const int32_t*)nullptr, (int32_t*)nullptr,
+                                           (const int32_t*)nullptr, (int32_t*)nullptr, (size_t)n, 0u, 32u, st);
   if (e != hipSuccess) return e;
   const size_t tmp = (sort_bytes + 255) / 256 * 256;
   if (work_bytes < tmp + (size_t)n * 12) return hipErrorInvalidValue;
@@ -378,7 +384,7 @@ hipError_t launch_centroid_update(const double* x, int64_t ldx, int d, int64_t n
   int32_t* member = sorted_label + n;
   hipLaunchKernelGGL(iota_fill_kernel, dim3(blocks(n)), dim3(kT), 0, st, ident, n, 0, 1);
   size_t sb = sort_bytes;
-  e = hipcub::DeviceRadixSort::SortPairs(base, sb, label, sorted_label, ident, member, (int)n, 0, bits_for(k), st);
+  e = rocprim::radix_sort_pairs(base, sb, label, sorted_label, ident, member, (size_t)n, 0u, (unsigned)bits_for(k), st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(cluster_starts_kernel, dim3(blocks(k + 1)), dim3(kT), 0, st, sorted_label, n, k, start);
   hipLaunchKernelGGL(centroid_mean_kernel, dim3((unsigned)k, (unsigned)((d + 63) / 64)), dim3(kT), 0, st, x, ldx, d, member,

@@ -11,7 +11,13 @@
 // worst of them; a candidate that beats the worst replaces it and the worst is found again by a scan of the k slots,
 // which after the first few hundred candidates happens rarely.
 #include <hip/hip_runtime.h>
-#include <hipcub/hipcub.hpp>
+#include <cstring>
+
+#include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_scan.hpp>
+#include <rocprim/device/device_select.hpp>
+#include <rocprim/functional.hpp>
+#include <rocprim/iterator/counting_iterator.hpp>
 
 #include <cstdint>
 
@@ -457,8 +463,8 @@ hipError_t launch_knn_search(const double* x, int64_t ldx, int64_t n, int d, int
 
 size_t knn_pairs_workspace(int64_t n) {
   size_t scan_bytes = 0;
-  (void)hipcub::DeviceScan::ExclusiveSum(nullptr, scan_bytes, (const int32_t*)nullptr, (int32_t*)nullptr, (int)n,
-                                         nullptr);
+  (void)rocprim::exclusive_scan(nullptr, scan_bytes, (const int32_t*)nullptr, (int32_t*)nullptr, (int32_t)0, (size_t)n,
+                                rocprim::plus<int32_t>(), (hipStream_t) nullptr);
   return (scan_bytes + 255) / 256 * 256 + 2 * (size_t)n * sizeof(int32_t) + 256;
 }
 
@@ -467,8 +473,8 @@ hipError_t launch_knn_union_pairs(const int32_t* idx, const double* dist, int64_
                                   hipStream_t st) {
   if (n < 1 || k < 1 || n > INT32_MAX || n * k > INT32_MAX) return hipErrorInvalidValue;
   size_t scan_bytes = 0;
-  hipError_t e = hipcub::DeviceScan::ExclusiveSum(nullptr, scan_bytes, (const int32_t*)nullptr, (int32_t*)nullptr,
-                                                  (int)n, st);
+  hipError_t e = rocprim::exclusive_scan(nullptr, scan_bytes, (const int32_t*)nullptr, (int32_t*)nullptr, (int32_t)0,
+                                         (size_t)n, rocprim::plus<int32_t>(), st);
   if (e != hipSuccess) return e;
   const size_t tmp = (scan_bytes + 255) / 256 * 256;
   if (work_bytes < tmp + 2 * (size_t)n * sizeof(int32_t)) return hipErrorInvalidValue;
@@ -477,7 +483,7 @@ hipError_t launch_knn_union_pairs(const int32_t* idx, const double* dist, int64_
   int32_t* off = cnt + n;
   hipLaunchKernelGGL(pair_count_kernel, dim3(blocks(n)), dim3(kT), 0, st, idx, n, k, cnt);
   size_t sb = scan_bytes;
-  e = hipcub::DeviceScan::ExclusiveSum(base, sb, cnt, off, (int)n, st);
+  e = rocprim::exclusive_scan(base, sb, cnt, off, (int32_t)0, (size_t)n, rocprim::plus<int32_t>(), st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(pair_emit_kernel, dim3(blocks(n)), dim3(kT), 0, st, idx, dist, n, k, off,
                      sigma > 0.0 ? 1.0 / (2.0 * sigma * sigma) : 0.0, eu, ev, val);

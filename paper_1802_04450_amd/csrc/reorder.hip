@@ -28,7 +28,13 @@
 // The sort is a stable LSD radix sort on that key: ties keep the original node order, so the numbering is a
 // deterministic function of the graph.
 #include <hip/hip_runtime.h>
-#include <hipcub/hipcub.hpp>
+#include <cstring>
+
+#include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_scan.hpp>
+#include <rocprim/device/device_select.hpp>
+#include <rocprim/functional.hpp>
+#include <rocprim/iterator/counting_iterator.hpp>
 
 #include <cstdint>
 
@@ -156,28 +162,28 @@ struct IsLongRow {
 
 size_t long_row_list_workspace(int64_t n) {
   size_t bytes = 0;
-  hipcub::CountingInputIterator<int32_t> rows(0);
-  (void)hipcub::DeviceSelect::If(nullptr, bytes, rows, (int32_t*)nullptr, (int32_t*)nullptr, (int)n,
-                                 IsLongRow{nullptr}, nullptr);
+  rocprim::counting_iterator<int32_t> rows(0);
+  (void)rocprim::select(nullptr, bytes, rows, (int32_t*)nullptr, (int32_t*)nullptr, (size_t)n, IsLongRow{nullptr},
+                        (hipStream_t) nullptr);
   return bytes + 256;
 }
 
 hipError_t long_row_list(const int64_t* rowptr, int64_t n, void* work, size_t work_bytes, int32_t* list, int32_t* count,
                          hipStream_t st) {
   if (n <= 0 || n > INT32_MAX) return hipErrorInvalidValue;
-  hipcub::CountingInputIterator<int32_t> rows(0);
+  rocprim::counting_iterator<int32_t> rows(0);
   size_t bytes = work_bytes;
-  return hipcub::DeviceSelect::If(work, bytes, rows, list, count, (int)n, IsLongRow{rowptr}, st);
+  return rocprim::select(work, bytes, rows, list, count, (size_t)n, IsLongRow{rowptr}, st);
 }
 
 size_t order_by_component_workspace(int64_t n) {
   size_t sort_bytes = 0, scan64_bytes = 0, scan32_bytes = 0;
-  (void)hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const uint64_t*)nullptr, (uint64_t*)nullptr,
-                                           (const int32_t*)nullptr, (int32_t*)nullptr, (int)n, 0, 64, nullptr);
-  (void)hipcub::DeviceScan::ExclusiveSum(nullptr, scan64_bytes, (const int64_t*)nullptr, (int64_t*)nullptr, (int)n,
-                                         nullptr);
-  (void)hipcub::DeviceScan::InclusiveSum(nullptr, scan32_bytes, (const int32_t*)nullptr, (int32_t*)nullptr, (int)n,
-                                         nullptr);
+  (void)rocprim::radix_sort_pairs(nullptr, sort_bytes, (const uint64_t*)nullptr, (uint64_t*)nullptr,
+                                  (const int32_t*)nullptr, (int32_t*)nullptr, (size_t)n, 0u, 64u, (hipStream_t) nullptr);
+  (void)rocprim::exclusive_scan(nullptr, scan64_bytes, (const int64_t*)nullptr, (int64_t*)nullptr, (int64_t)0, (size_t)n,
+                                rocprim::plus<int64_t>(), (hipStream_t) nullptr);
+  (void)rocprim::inclusive_scan(nullptr, scan32_bytes, (const int32_t*)nullptr, (int32_t*)nullptr, (size_t)n,
+                                rocprim::plus<int32_t>(), (hipStream_t) nullptr);
   size_t tmp = sort_bytes > scan64_bytes ? sort_bytes : scan64_bytes;
   tmp = tmp > scan32_bytes ? tmp : scan32_bytes;
   tmp = (tmp + 255) / 256 * 256;
@@ -192,12 +198,14 @@ hipError_t order_by_component(const int64_t* rowptr, const int32_t* col, const i
   if (n <= 0) return hipSuccess;
   if (n > INT32_MAX || !comp_of_new) return hipErrorInvalidValue;
   size_t sort_bytes = 0, scan64_bytes = 0, scan32_bytes = 0;
-  hipError_t e = hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const uint64_t*)nullptr, (uint64_t*)nullptr,
-                                                    (const int32_t*)nullptr, (int32_t*)nullptr, (int)n, 0, 64, st);
+  hipError_t e = rocprim::radix_sort_pairs(nullptr, sort_bytes, (const uint64_t*)nullptr, (uint64_t*)nullptr,
+                                           (const int32_t*)nullptr, (int32_t*)nullptr, (size_t)n, 0u, 64u, st);
   if (e != hipSuccess) return e;
-  e = hipcub::DeviceScan::ExclusiveSum(nullptr, scan64_bytes, (const int64_t*)nullptr, (int64_t*)nullptr, (int)n, st);
+  e = rocprim::exclusive_scan(nullptr, scan64_bytes, (const int64_t*)nullptr, (int64_t*)nullptr, (int64_t)0, (size_t)n,
+                              rocprim::plus<int64_t>(), st);
   if (e != hipSuccess) return e;
-  e = hipcub::DeviceScan::InclusiveSum(nullptr, scan32_bytes, (const int32_t*)nullptr, (int32_t*)nullptr, (int)n, st);
+  e = rocprim::inclusive_scan(nullptr, scan32_bytes, (const int32_t*)nullptr, (int32_t*)nullptr, (size_t)n,
+                              rocprim::plus<int32_t>(), st);
   if (e != hipSuccess) return e;
   size_t tmp = sort_bytes > scan64_bytes ? sort_bytes : scan64_bytes;
   tmp = tmp > scan32_bytes ? tmp : scan32_bytes;
@@ -229,16 +237,16 @@ hipError_t order_by_component(const int64_t* rowptr, const int32_t* col, const i
   hipLaunchKernelGGL(pack_key_kernel, dim3(blocks(n)), dim3(kT), 0, st, label, h1, h2, h3, rowptr, maxlen, by_length,
                      w, n, key, ident);
   size_t sb = sort_bytes;
-  e = hipcub::DeviceRadixSort::SortPairs(temp, sb, key, key_sorted, ident, old_of_new, (int)n, 0, 3 * w + lb, st);
+  e = rocprim::radix_sort_pairs(temp, sb, key, key_sorted, ident, old_of_new, (size_t)n, 0u, (unsigned)(3 * w + lb), st);
   if (e != hipSuccess) return e;
   int32_t* starts = ident;  // the identity values are no longer needed: the buffer takes the component-start marks
   hipLaunchKernelGGL(after_sort_kernel, dim3(blocks(n)), dim3(kT), 0, st, rowptr, key_sorted, old_of_new, n, 3 * w,
                      new_of_old, len, starts);
   size_t s64 = scan64_bytes;
-  e = hipcub::DeviceScan::ExclusiveSum(temp, s64, len, len_scan, (int)n, st);
+  e = rocprim::exclusive_scan(temp, s64, len, len_scan, (int64_t)0, (size_t)n, rocprim::plus<int64_t>(), st);
   if (e != hipSuccess) return e;
   size_t s32 = scan32_bytes;
-  e = hipcub::DeviceScan::InclusiveSum(temp, s32, starts, comp_of_new, (int)n, st);
+  e = rocprim::inclusive_scan(temp, s32, starts, comp_of_new, (size_t)n, rocprim::plus<int32_t>(), st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(finish_kernel, dim3(blocks(n)), dim3(kT), 0, st, len_scan, len, n, rowptr_new, comp_of_new);
   return hipGetLastError();

@@ -4,10 +4,16 @@
 // Algorithm 1 centres the data in place and gives one thread a row / an edge.  Here the data are read only: a first
 // kernel stores the mean and the norm of every row (of the centred row for the cross correlation), and the edge
 // kernel forms sum_t (x_it - m_i)(x_jt - m_j) directly, 16 lanes per edge with 16-byte loads, so a row of the paper's
-// 90 doubles is read as a few full cache lines.  The conversion sorts (row, col) keys with hipCUB's radix sort (a
+// 90 doubles is read as a few full cache lines.  The conversion sorts (row, col) keys with rocPRIM's radix sort (a
 // library primitive, the counterpart of the paper's library call) and finds the row pointers by binary search.
 #include <hip/hip_runtime.h>
-#include <hipcub/hipcub.hpp>
+#include <cstring>
+
+#include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_scan.hpp>
+#include <rocprim/device/device_select.hpp>
+#include <rocprim/functional.hpp>
+#include <rocprim/iterator/counting_iterator.hpp>
 
 #include <cstdint>
 
@@ -193,8 +199,9 @@ hipError_t launch_edge_similarity(const double* x, int64_t ldx, int d, const int
 
 size_t coo_to_csr_workspace(int64_t total) {
   size_t sort_bytes = 0;
-  (void)hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const uint64_t*)nullptr, (uint64_t*)nullptr,
-                                           (const uint32_t*)nullptr, (uint32_t*)nullptr, (int)total, 0, 64, nullptr);
+  (void)rocprim::radix_sort_pairs(nullptr, sort_bytes, (const uint64_t*)nullptr, (uint64_t*)nullptr,
+                                  (const uint32_t*)nullptr, (uint32_t*)nullptr, (size_t)total, 0u, 64u,
+                                  (hipStream_t) nullptr);
   sort_bytes = (sort_bytes + 255) / 256 * 256;
   // temp | key[total] | key_sorted[total] | src[total] | src_sorted[total]
   return sort_bytes + (size_t)total * 24 + 1024;
@@ -209,8 +216,8 @@ hipError_t coo_to_csr(const int32_t* row, const int32_t* col, const double* val,
   const int64_t total = nnz_in * (symmetrize ? 2 : 1);
   if (total <= 0 || total > INT32_MAX) return hipErrorInvalidValue;
   size_t sort_bytes = 0;
-  hipError_t e = hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const uint64_t*)nullptr, (uint64_t*)nullptr,
-                                                    (const uint32_t*)nullptr, (uint32_t*)nullptr, (int)total, 0, 64, st);
+  hipError_t e = rocprim::radix_sort_pairs(nullptr, sort_bytes, (const uint64_t*)nullptr, (uint64_t*)nullptr,
+                                           (const uint32_t*)nullptr, (uint32_t*)nullptr, (size_t)total, 0u, 64u, st);
   if (e != hipSuccess) return e;
   const size_t tmp = (sort_bytes + 255) / 256 * 256;
   if (work_bytes < tmp + (size_t)total * 24) return hipErrorInvalidValue;
@@ -224,7 +231,7 @@ hipError_t coo_to_csr(const int32_t* row, const int32_t* col, const double* val,
   size_t sb = sort_bytes;
   // all 64 bits when dropped entries (keys of all ones) may be present, else only the bits that indices use
   const int end_bit = symmetrize ? 64 : 32 + key_bits(n);
-  e = hipcub::DeviceRadixSort::SortPairs(base, sb, key, key_sorted, src, src_sorted, (int)total, 0, end_bit, st);
+  e = rocprim::radix_sort_pairs(base, sb, key, key_sorted, src, src_sorted, (size_t)total, 0u, (unsigned)end_bit, st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(coo_rowptr_kernel, dim3(blocks(n + 1)), dim3(kT), 0, st, key_sorted, total, n, rowptr_out);
   // entries past rowptr[n] are the dropped ones; emitting them too is harmless (col = 2^32 - 1 truncated) but the
