@@ -177,15 +177,41 @@ def measure_spmv(B, torch, drp, dc, dv, n, nnz):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / reps
 
+    def time_spmv_chain(rp_d, c_d, v_d):
+        """The product as it occurs in a chain (sc_spmv_normalized_chain): the operand arrives scaled by the previous
+        product, which also leaves the next operand; one launch per product, both scalings fused, no scaling pass."""
+        _, s = B.sc_degree_scaling(rp_d, c_d, v_d, want_degrees=False)
+        x = torch.randn(n, dtype=torch.float64, device="cuda")
+        za, zb = s * x, torch.empty_like(x)
+        y = torch.empty_like(x)
+        for _ in range(5):
+            B.sc_spmv_normalized_chain(rp_d, c_d, v_d, s, nnz, za, y, zb)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 50
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps // 2):       # the two operand buffers alternate; the values stay bounded (|S| = 1)
+            B.sc_spmv_normalized_chain(rp_d, c_d, v_d, s, nnz, za, y, zb)
+            B.sc_spmv_normalized_chain(rp_d, c_d, v_d, s, nnz, zb, y, za)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / (2 * (reps // 2))
+
     rp2, c2, v2, _, ncomp = B.sc_reorder_csr(drp, dc, dv)
     spmv_s = time_spmv(rp2, c2, v2)
+    spmv_s_chain = time_spmv_chain(rp2, c2, v2)
     spmv_s_scaled = time_spmv_scaled(rp2, c2, v2)
     spmv_s_given = time_spmv(drp, dc, dv)
     spmv_bytes = 12 * nnz + 8 * (n + 1) + 8 * n + 8 * n + 8 * n
     scaled_bytes = 12 * nnz + 8 * (n + 1) + 8 * n + 8 * n
+    chain_bytes = spmv_bytes + 8 * n          # the next operand is written as well
     spmv_gbs = spmv_bytes / spmv_s / 1e9
     return {"gbps_algorithmic": spmv_gbs, "seconds": spmv_s, "bytes": spmv_bytes,
             "frac_of_hbm_peak": spmv_gbs / HBM_PEAK_GBS,
+            "chain": {"gbps_algorithmic": chain_bytes / spmv_s_chain / 1e9, "seconds": spmv_s_chain,
+                      "bytes": chain_bytes, "frac_of_hbm_peak": chain_bytes / spmv_s_chain / 1e9 / HBM_PEAK_GBS,
+                      "note": "y = s o (W (s o x)) inside a chain of products (sc_spmv_normalized_chain): one launch, the "
+                              "operand arrives scaled by the previous product, which also writes the next operand"},
             "scaled_operator": {"gbps_algorithmic": scaled_bytes / spmv_s_scaled / 1e9, "seconds": spmv_s_scaled,
                                 "bytes": scaled_bytes,
                                 "frac_of_hbm_peak": scaled_bytes / spmv_s_scaled / 1e9 / HBM_PEAK_GBS,

@@ -213,6 +213,20 @@ int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const 
                        void* stream);
 
 /*
+ * The single-vector product of Algorithm 3's loop body as it occurs in a chain of products (a Lanczos or power
+ * iteration), with the degree scaling fused on both sides and no pass of its own for it: the operand arrives scaled,
+ * z_in = s o x (elementwise), as the previous product left it, and the call produces in ONE launch
+ *   y = s o (W z_in)  ( = diag(s) W diag(s) x )   and   z_out = s o y, the operand of the next product.
+ * The first operand of a chain is formed by the caller (z = s o x, any elementwise multiply).
+ *   s, z_in   device fp64[n];  y, z_out  device fp64[n], neither may be z_in
+ *   nnz       csr_rowptr[n], passed by the caller (it only steers the choice of the tile shape)
+ * ENQUEUES on `stream` and returns without synchronising, so that products can be issued back to back.
+ * CSR columns are NOT range-checked here (sc_validate_csr does that).
+ */
+int sc_spmv_normalized_chain(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, const double* s,
+                             int64_t n, int64_t nnz, const double* z_in, double* y, double* z_out, void* stream);
+
+/*
  * Algorithm 2 step 3 (ScaleElements) in its symmetric form: val_out[e] = s_i * csr_val[e] * s_j for entry e = (i, j).
  * The two factors are applied in index order, so (i, j) and (j, i) get the same rounding and the copy is exactly
  * symmetric when W is.  val_out (device fp64[nnz]) may be csr_val itself.

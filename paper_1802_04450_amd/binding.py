@@ -30,7 +30,8 @@ EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_
            "sc_block_qr", "sc_rotate", "sc_sym_eig", "sc_sym_eig_top", "sc_strerror", "sc_version", "sc_release_cache",
            "sc_chebyshev_filter", "sc_kmeanspp", "sc_kmeans_lloyd", "sc_kmeans", "sc_edge_similarity", "sc_knn_search", "sc_knn_union_pairs",
            "sc_coo_to_csr", "sc_workspace_bytes", "sc_scale_operator", "sc_laplacian_eigsh_ws",
-           "sc_block_qr_noalloc", "sc_counter"]
+           "sc_block_qr_noalloc", "sc_counter",
+           "sc_spmv_normalized_chain"]
 
 
 class ScOptions(ctypes.Structure):
@@ -96,6 +97,7 @@ def lib() -> ctypes.CDLL:
         _lib.sc_scale_operator.argtypes = [vp, vp, vp, vp, i64, vp, vp]
         _lib.sc_spmm_normalized.argtypes = [vp, vp, vp, vp, i64, vp, i64, vp, i64, i32, vp, vp]
         _lib.sc_validate_csr.argtypes = [vp, vp, i64, vp]
+        _lib.sc_spmv_normalized_chain.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, vp, vp]
         _lib.sc_reorder_csr.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp]
         _lib.sc_cgs2.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         _lib.sc_block_qr.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
@@ -222,6 +224,20 @@ def sc_degree_scaling(rowptr, col, val, want_degrees: bool = True):
         code = lib().sc_degree_scaling(_ptr(rowptr), _ptr(col), _ptr(val), n, _ptr(d), _ptr(s), _stream())
     _check(code)
     return d, s
+
+
+def sc_spmv_normalized_chain(rowptr, col, val, s, nnz: int, z_in, y, z_out):
+    """One product of a chain: y = s o (W z_in), z_out = s o y, with z_in = s o x from the previous product.  Only
+    enqueues on the current stream; y and z_out are written in place.  Returns the status code."""
+    import torch
+    n = rowptr.numel() - 1
+    for t in (s, z_in, y, z_out):
+        _dev(t, torch.float64)
+        assert t.numel() == n
+    with torch.cuda.device(rowptr.device):
+        code = lib().sc_spmv_normalized_chain(_ptr(rowptr), _ptr(col), _ptr(val), _ptr(s), n, nnz, _ptr(z_in), _ptr(y),
+                                              _ptr(z_out), _stream())
+    return _check(code)
 
 
 def sc_scale_operator(rowptr, col, val, s):

@@ -421,20 +421,21 @@ int device_lds_limit() {
   return lds;
 }
 
-// Finds the diagonal blocks on the device, sizes the items on the host.  The plan is usable when every block fits LDS
-// with a slice of at least two columns and the modelled step time beats the general product's: an item costs its
-// entries times (12 bytes streamed + 8 bs bytes read from LDS) at about half a compute unit's LDS rate, the items
-// spread over the 256 compute units, largest first; the general product gathers 8 b bytes per entry from the L2 caches
-// at the 12.5 TB/s measured for it, and no launch is shorter than about 4 us.
+// Finds the diagonal blocks and their chunk counts on the device, sizes the items on the host.  The plan is usable
+// when b is 16 or 32, every block fits LDS as items of 32 or 16 columns with at most two chunks per lane group, and
+// the modelled step time beats the general product's: an item costs its entries times 8 bs bytes read from LDS at
+// about half a compute unit's LDS rate, the items spread over the 256 compute units, largest first; the general
+// product gathers 8 b bytes per entry from the L2 caches at the 12.5 TB/s measured for it, and no launch is shorter
+// than about 4 us.
 void plan_resident(const int64_t* rowptr, const int32_t* col, int64_t n, int64_t nnz, int b, hipStream_t st,
                    ResidentPlan* plan) {
   plan->usable = false;
   plan->nitems = 0;
-  if (b < 8 || n <= 0 || nnz <= 0 || std::getenv("SCEIG_NO_RESIDENT")) return;
+  if ((b != 16 && b != 32) || n <= 0 || nnz <= 0 || std::getenv("SCEIG_NO_RESIDENT")) return;
   const int lds_limit = device_lds_limit() - 1024;
   if (lds_limit < 32 * 1024) return;
   DevBuf<char> work;
-  DevBuf<int32_t> starts, count;
+  DevBuf<int32_t> starts, count, extra;
   const size_t wb = diagonal_blocks_workspace(n);
   work.alloc(wb);
   starts.alloc((size_t)n);
@@ -443,13 +444,17 @@ void plan_resident(const int64_t* rowptr, const int32_t* col, int64_t n, int64_t
   int32_t nblk = 0;
   HIP_TRY(hipMemcpyAsync(&nblk, count.p, sizeof(int32_t), hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
-  if (nblk <= 0 || (int64_t)nblk * 16 > (int64_t)1 << 24) return;
-  std::vector<int32_t> hs((size_t)nblk + 1);
+  // at most 640 rows fit an item, so a usable plan has at least n / 640 blocks; and its item table stays small
+  if (nblk <= 0 || (int64_t)nblk * 640 < n || (int64_t)nblk > (int64_t)1 << 22) return;
+  extra.alloc((size_t)2 * nblk);
+  HIP_TRY(launch_block_extra_chunks(rowptr, starts.p, nblk, n, extra.p, st));
+  std::vector<int32_t> hs((size_t)nblk + 1), hx((size_t)2 * nblk);
   HIP_TRY(hipMemcpyAsync(hs.data(), starts.p, (size_t)nblk * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync(hx.data(), extra.p, (size_t)2 * nblk * sizeof(int32_t), hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
   hs[nblk] = (int32_t)n;
   struct Item {
-    int32_t row0, nrows, col0, bs;
+    int32_t row0, nrows, col0, shape;
   };
   std::vector<Item> items;
   size_t lds_max = 0;
@@ -457,26 +462,34 @@ void plan_resident(const int64_t* rowptr, const int32_t* col, int64_t n, int64_t
   double sum_cost = 0.0, max_cost = 0.0;
   for (int t = 0; t < nblk; ++t) {
     const int nr = hs[t + 1] - hs[t];
-    int bs = b;
-    while (bs >= 2 && resident_item_lds_bytes(nr, bs) > (size_t)lds_limit) bs /= 2;
-    if (bs < 2) return;  // a block too large for LDS: the general product does the whole filter
-    const double cost = (double)nr * avg_deg * (12.0 + 8.0 * bs);
+    int cl = 0, nx = 0;
+    for (int c = b == 32 ? 4 : 2; c >= 2; c /= 2) {  // widest lane group first
+      const int x = c == 4 ? hx[2 * t] : hx[2 * t + 1];
+      if (x >= (1 << 26) || nr + x > resident_max_chunks(c)) continue;
+      if (resident_item_lds_bytes(nr, c, x) > (size_t)lds_limit) continue;
+      cl = c;
+      nx = x;
+      break;
+    }
+    if (cl == 0) return;  // a block too large for LDS or for the lane groups: the general product does the whole filter
+    const int bs = 8 * cl;
+    const double cost = (double)nr * avg_deg * 8.0 * bs;
     for (int c0 = 0; c0 < b; c0 += bs) {
-      items.push_back(Item{hs[t], nr, c0, bs});
+      items.push_back(Item{hs[t], nr, c0, (int32_t)(cl | (nx << 4))});
       sum_cost += cost;
     }
     max_cost = std::max(max_cost, cost);
-    lds_max = std::max(lds_max, resident_item_lds_bytes(nr, bs));
+    lds_max = std::max(lds_max, resident_item_lds_bytes(nr, cl, nx));
   }
-  const double cu_rate = 150e9;  // bytes per second through one compute unit's LDS and load path, about half of peak
-  plan->est_step_s = std::max(max_cost, sum_cost / 256.0) / cu_rate;
+  const double cu_rate = 150e9;  // bytes per second out of one compute unit's LDS, about half of its peak
+  plan->est_step_s = std::max(max_cost, sum_cost / 256.0) / cu_rate + 1e-6;
   const double general_step_s = std::max(4e-6, (double)nnz * 8.0 * b / 12.5e12);
   if (debug_on())
     std::fprintf(stderr, "[sceig] resident filter plan: %d blocks, %zu items, LDS %zu, modelled step %.1f us against %.1f us\n",
                  nblk, items.size(), lds_max, plan->est_step_s * 1e6, general_step_s * 1e6);
   if (!(plan->est_step_s < general_step_s) && !std::getenv("SCEIG_FORCE_RESIDENT")) return;
   std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& c) {
-    return (int64_t)a.nrows * a.bs > (int64_t)c.nrows * c.bs;
+    return (int64_t)a.nrows * (a.shape & 15) > (int64_t)c.nrows * (c.shape & 15);
   });
   plan->items.alloc(items.size() * 4);
   HIP_TRY(hipMemcpyAsync(plan->items.p, items.data(), items.size() * sizeof(Item), hipMemcpyHostToDevice, st));
@@ -1765,7 +1778,7 @@ int sc_workspace_bytes(int64_t n, int64_t nnz, int32_t k, const sc_options* opt,
   total += up(N * 8);                       // scaling vector
   if (b >= 8) total += up(Z * 8) + up(N * 4) + up(long_row_list_workspace(n)) + 256;  // scaled values, long-row list
   if (b >= 8 && !(o.flags & SC_FLAG_NO_START_FILTER))  // diagonal-block search and the work items of the resident filter
-    total += up(diagonal_blocks_workspace(n)) + up(N * 4) + 256 + up(N * 18);
+    total += up(diagonal_blocks_workspace(n)) + up(N * 4) + 256 + up(N * 8) + up(N * 18);
   total += up(N * ld * 8) + up(N * (size_t)b * 8) + up(N * rot_cols * 8);  // basis, packed block, rotation workspace
   total += up((size_t)kMaxPartials * jmax * kPP * 8) + up((size_t)kGramPartials * kPP * kPP * 8) + 2 * up(jmax * kPP * 8);
   total += up((size_t)(m / b + 4) * kSlotDoubles * 8) + up(jmax * std::max<size_t>(rot_cols, (size_t)k) * 8);
@@ -1920,6 +1933,29 @@ int sc_spmm_normalized(const int64_t* csr_rowptr, const int32_t* csr_col, const 
         HIP_TRY(launch_spmm(c->rp, c->c, c->v, c->s, c->n, in_place ? c->x : z, c->b, c->y, c->ldy,
                             (double)last_nnz / (double)c->n, c->st));
         if (own.p) HIP_TRY(hipStreamSynchronize(c->st));  // the internal scratch is freed on return
+        return SC_OK;
+      },
+      &ctx);
+}
+
+int sc_spmv_normalized_chain(const int64_t* csr_rowptr, const int32_t* csr_col, const double* csr_val, const double* s,
+                             int64_t n, int64_t nnz, const double* z_in, double* y, double* z_out, void* stream) {
+  if (!csr_rowptr || !csr_col || !csr_val || !s || !z_in || !y || !z_out || n < 0 || nnz < 0) return SC_EINVAL;
+  if (z_out == z_in || y == z_in) return SC_EINVAL;  // rows gather the operand of other rows
+  if (n == 0) return SC_OK;
+  struct Ctx {
+    const int64_t* rp;
+    const int32_t* c;
+    const double *v, *s;
+    int64_t n, nnz;
+    const double* z;
+    double *y, *zo;
+    hipStream_t st;
+  } ctx{csr_rowptr, csr_col, csr_val, s, n, nnz, z_in, y, z_out, reinterpret_cast<hipStream_t>(stream)};
+  return guarded(
+      [](void* p) {
+        Ctx* c = static_cast<Ctx*>(p);
+        HIP_TRY(launch_spmv_chain(c->rp, c->c, c->v, c->s, c->n, c->z, c->y, c->zo, (double)c->nnz / (double)c->n, c->st));
         return SC_OK;
       },
       &ctx);

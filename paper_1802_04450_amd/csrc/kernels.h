@@ -36,6 +36,11 @@ hipError_t launch_pack_scaled(const double* x, int64_t ldx, const double* s, int
 hipError_t launch_spmm(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
                        const double* z, int b, double* y, int64_t ldy, double avg_deg, hipStream_t st);
 
+// Single-vector product inside a chain of products: z = s o x (the operand, scaled by the call that produced x),
+// y = s o (W z), zout = s o y (the operand of the next product), one launch.
+hipError_t launch_spmv_chain(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
+                             const double* z, double* y, double* zout, double avg_deg, hipStream_t st);
+
 // ---- tall-skinny projections (fp64 MFMA) ---------------------------------------------------
 struct ProjectPlan {
   int rows_per_panel;  // multiple of 4
@@ -84,19 +89,26 @@ int plan_update_gram(int64_t n);
 hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int b,
                               int ccol0, int overwrite, double* gpart, hipStream_t st);
 // ---- Chebyshev filter with the iterates resident in LDS (resident.hip) -------------------------------
-// LDS bytes of one work item: two iterates of nrows x bs doubles and the block's row pointers.
-size_t resident_item_lds_bytes(int nrows, int bs);
+// A work item is a diagonal block (or a 16-column slice of it) worked on by lane groups of cl = 4 lanes (32 columns)
+// or cl = 2 lanes (16 columns).  Its rows are cut into chunks of 8 cl entries; `extra` = chunks beyond the first,
+// summed over its rows.  LDS bytes of an item, and the largest number of chunks (rows + extra) one may have:
+size_t resident_item_lds_bytes(int nrows, int cl, int extra);
+int resident_max_chunks(int cl);
 // Diagonal blocks of a CSR matrix with a symmetric pattern: starts[0 .. *count) = the rows p (ascending) such that no
 // row before p has an entry in column p or beyond; starts has room for n entries, count is a device int32.
 // work: device scratch of diagonal_blocks_workspace(n) bytes.  n <= INT32_MAX.
 size_t diagonal_blocks_workspace(int64_t n);
 hipError_t diagonal_blocks(const int64_t* rowptr, const int32_t* col, int64_t n, void* work, size_t work_bytes,
                            int32_t* starts, int32_t* count, hipStream_t st);
-// y = T_d-type recurrence applied to x, both packed n x b: u_0 = x, u_1 = alpha_first (A u_0 - shift u_0),
+// extra[2 t], extra[2 t + 1] (device int32) = extra chunks of block t for chunks of 32 and of 16 entries
+hipError_t launch_block_extra_chunks(const int64_t* rowptr, const int32_t* starts, int nblk, int64_t n, int32_t* extra,
+                                     hipStream_t st);
+// y = the recurrence applied to x, both packed n x b: u_0 = x, u_1 = alpha_first (A u_0 - shift u_0),
 // u_{i+1} = alpha_rest (A u_i - shift u_i) - u_{i-1}; y = u_d.  A = the CSR matrix, whose rows [row0, row0 + nrows) of
-// every item form a diagonal block.  items: device int32[4 * nitems] = (row0, nrows, col0, bs) per workgroup, bs in
-// {2, 4, 8, 16, 32} columns starting at col0; every (block, column) pair must be covered exactly once.  lds_bytes =
-// the largest resident_item_lds_bytes over the items.  y must not alias x.
+// every item form a diagonal block.  items: device int32[4 * nitems] = (row0, nrows, col0, cl | extra << 4) per
+// workgroup, covering columns [col0, col0 + 8 cl); every (block, column) pair must be covered exactly once, extra must
+// be the block's extra-chunk count for chunks of 8 cl entries and nrows + extra <= resident_max_chunks(cl).
+// lds_bytes = the largest resident_item_lds_bytes over the items.  y must not alias x.
 hipError_t launch_cheb_resident(const int64_t* rowptr, const int32_t* col, const double* val, const double* x, double* y,
                                 int b, int d, double alpha_first, double alpha_rest, double shift, const int32_t* items,
                                 int nitems, size_t lds_bytes, hipStream_t st);

@@ -400,7 +400,8 @@ __global__ __launch_bounds__(kThreads) void spmv_tile_kernel(const int64_t* __re
                                                              const double* __restrict__ val,
                                                              const double* __restrict__ s,
                                                              const double* __restrict__ z, double* __restrict__ y,
-                                                             int64_t ldy, int64_t n, int64_t ntiles) {
+                                                             int64_t ldy, int64_t n, int64_t ntiles,
+                                                             double* __restrict__ zout) {
   constexpr int LR = 64 / RW;  // lanes per row in the summation
   constexpr int CH = U * 64;   // entries per chunk
   __shared__ double prod_all[kThreads / 64][CH];
@@ -418,7 +419,10 @@ __global__ __launch_bounds__(kThreads) void spmv_tile_kernel(const int64_t* __re
   const int len = (int)(readlane64(rpv, RW) - e0);
   const bool mine = sl == 0 && row0 + g < n;
   if (len <= 0) {
-    if (mine) y[(row0 + g) * ldy] = 0.0;
+    if (mine) {
+      y[(row0 + g) * ldy] = 0.0;
+      if (zout) zout[row0 + g] = 0.0;
+    }
     return;
   }
   const int32_t* cp = col + e0;
@@ -472,18 +476,22 @@ __global__ __launch_bounds__(kThreads) void spmv_tile_kernel(const int64_t* __re
   acc += acc2;
 #pragma unroll
   for (int o = LR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, LR);
-  if (mine) y[(row0 + g) * ldy] = sg * acc;
+  if (mine) {
+    const double yv = sg * acc;
+    y[(row0 + g) * ldy] = yv;
+    if (zout) zout[row0 + g] = sg * yv;  // the next product's operand s o y, scaled here instead of in a pass of its own
+  }
 }
 
 // Tile shape by the average row length: the register buffer (U*64 entries) should hold an average tile with some room.
 static hipError_t launch_spmv_tile(const int64_t* rowptr, const int32_t* col, const double* val, const double* s,
                                    int64_t n, const double* z, double* y, int64_t ldy, double avg_deg,
-                                   hipStream_t st) {
+                                   hipStream_t st, double* zout = nullptr) {
 #define SC_LAUNCH_TILE(RW_, U_)                                                                                    \
   do {                                                                                                             \
     const int64_t ntiles = ceil_div64(n, RW_);                                                                     \
     hipLaunchKernelGGL((spmv_tile_kernel<RW_, U_>), dim3((unsigned)ceil_div64(ntiles, kThreads / 64)),              \
-                       dim3(kThreads), 0, st, rowptr, col, val, s, z, y, ldy, n, ntiles);                          \
+                       dim3(kThreads), 0, st, rowptr, col, val, s, z, y, ldy, n, ntiles, zout);                    \
   } while (0)
   const double need = avg_deg * 1.08 / 64.0;  // register slots per lane and row of the tile
   if (need * 32 <= 8) SC_LAUNCH_TILE(32, 8);
@@ -1512,6 +1520,15 @@ hipError_t launch_spmm(const int64_t* rowptr, const int32_t* col, const double* 
                                            nullptr, 0, st);
       return launch_spmm_cols_t<0>(rowptr, col, val, s, n, z, b, y, ldy, avg_deg, nullptr, 0.0, 0.0, 0.0, nullptr, 0, st);
   }
+}
+
+hipError_t launch_spmv_chain(const int64_t* rowptr, const int32_t* col, const double* val, const double* s, int64_t n,
+                             const double* z, double* y, double* zout, double avg_deg, hipStream_t st) {
+  if (avg_deg >= 6.0) return launch_spmv_tile(rowptr, col, val, s, n, z, y, 1, avg_deg, st, zout);
+  // very sparse rows: the lanes-per-row kernel, then the scaling as a pass of its own
+  hipError_t e = launch_spmm_nz<1>(rowptr, col, val, s, n, z, y, 1, avg_deg, st);
+  if (e != hipSuccess) return e;
+  return launch_pack_scaled(y, 1, s, n, 1, zout, st);
 }
 
 hipError_t launch_scale_values(const int64_t* rowptr, const int32_t* col, const double* val, const double* s,

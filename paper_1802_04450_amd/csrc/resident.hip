@@ -5,24 +5,27 @@
 // general product kernel per step gathers, for every matrix entry, a whole operand row from the L2 caches, and the
 // rate of those gathers - not HBM - bounds it.  But the similarity graphs here are block diagonal (one diagonal block
 // per connected component, contiguous rows after the solver's renumbering), and a step of the recurrence on one block
-// needs nothing from outside the block.  So one workgroup takes one diagonal block, or a slice of BS of its b
-// columns, keeps the two iterates u and u- of that slice in LDS for all d steps and streams only the block's
-// (col, val) entries; the per-entry gathers become LDS reads of 8 BS bytes, and nothing is written to memory until
-// the last step.
+// needs nothing from outside the block.  So one workgroup takes one diagonal block (or a 16-column slice of it), keeps
+// the two iterates u and u- in LDS for all d steps and the block's matrix entries in registers: after the first step
+// nothing is read from memory, and nothing is written until the last.
 //
-//   * Work items (row0, nrows, col0, BS), built by the host from the list of diagonal blocks: BS is the widest
-//     power of two <= b for which 2 * nrows * BS doubles (+ the block's row pointers) fit the LDS of a compute unit;
-//     a block narrower than b in LDS terms becomes b / BS items, each re-streaming the block's entries.
-//   * A workgroup has 32 lane groups of 32 lanes; group g owns the block's rows g, g + 32, g + 64, ...  Its lanes load
-//     32 consecutive entries of a row at once; BS / 2 lanes cover one entry with 16-byte LDS reads (a lane carries
-//     two adjacent columns) and the 64 / BS sub-groups of a lane group take the batch's entries round-robin; the
-//     sub-group sums are combined by a fixed shuffle tree, so the result does not depend on timing.
-//   * The entries never change between steps: the first batch of each group's first 8 rows stays in registers for
-//     the whole launch (a block of up to 256 rows with rows of up to 32 entries then reads the matrix exactly once);
-//     further rows are requested four at a time before any of them is used, and so are the further batches of a
-//     long row, so that a memory latency is paid per four batches, not per batch.
-//   * The new iterate of a row overwrites that row of u- in place (only the row's owner reads it), one workgroup
-//     barrier per step, then the two buffers swap roles.
+//   * A lane carries 8 adjacent columns; CL = 4 lanes (32 columns) or 2 lanes (16 columns) form a lane group that
+//     works on one piece of one row at a time, so a step needs no sum across lanes at all.
+//   * Rows are cut into chunks of at most 8 CL entries (32 or 16) and the chunks, numbered in row order, are dealt
+//     to the 1024 / CL lane groups; a group owns at most two chunks and keeps their entries - eight (column, value)
+//     pairs per lane - in registers for the whole launch.  A hub row of several hundred entries is thus spread over
+//     as many groups as it has chunks instead of being walked by one.  The kNN graphs' rows are ordered by length
+//     inside a component, so the chunks that share a wave are equally long.
+//   * One round: every lane group hands the round's entry from the lane that holds it to its other lanes with a DPP
+//     quad permute (an ALU move, no LDS traffic), reads the 64 bytes of its 8 columns of that operand row from LDS
+//     and does 8 multiply-adds.
+//   * The group that owns the first chunk of a row applies the recurrence with its own sum and stores the new row over
+//     u- in place (only the row's owner reads it); the other chunks of a row park their sums in LDS, and after a
+//     barrier the row's owner adds them in chunk order (fixed, so results are reproducible).  Blocks without hub rows
+//     skip that barrier.  One more barrier ends the step and the two buffers swap roles.
+//   * Work items (row0, rows, col0, CL, extra chunks) are built by the host from the diagonal blocks and their chunk
+//     counts; an item's LDS need is 2 rows x 8 CL doubles for the iterates, 8 CL doubles per extra chunk, and two
+//     int32 per row for the block's row pointers and chunk offsets.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -37,35 +40,51 @@
 namespace sceig {
 namespace {
 
-constexpr int kRT = 1024;           // threads per workgroup
-constexpr int kRL = 32;             // lanes per row
-constexpr int kRG = kRT / kRL;      // lane groups per workgroup
-constexpr int kRKeep = 8;           // rows per group whose first batch stays in registers
-constexpr int kRAhead = 4;          // batches requested together when streaming
+constexpr int kRT = 1024;  // threads per workgroup
+constexpr int kRK = 8;     // entries per lane and chunk
+constexpr int kRS = 2;     // chunks per lane group
 
-__host__ __device__ inline size_t resident_lds_bytes(int nrows, int bs) {
-  return ((size_t)2 * nrows * bs * sizeof(double) + (size_t)(nrows + 1) * sizeof(int32_t) + 15) / 16 * 16;
+__host__ __device__ inline size_t resident_lds_bytes(int nrows, int cl, int extra) {
+  const size_t bs = (size_t)8 * cl;
+  return ((size_t)2 * nrows * bs * sizeof(double) + (size_t)extra * bs * sizeof(double) +
+          (size_t)2 * (nrows + 1) * sizeof(int32_t) + 15) / 16 * 16;
 }
 
-template <int BS>
+template <int CTRL>
+__device__ __forceinline__ int dpp_int(int v) {
+  return __builtin_amdgcn_mov_dpp(v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_double(double v) {
+  return __hiloint2double(dpp_int<CTRL>(__double2hiint(v)), dpp_int<CTRL>(__double2loint(v)));
+}
+// quad permute that gives every lane of a CL-lane group the value held by the group's lane Q
+template <int CL, int Q>
+struct GroupBcast {
+  static constexpr int ctrl = CL == 4 ? Q * 0x55 : (Q == 0 ? 0xA0 : 0xF5);
+};
+
+template <int CL>
 __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr, const int32_t* __restrict__ col,
                                               const double* __restrict__ val, const double* __restrict__ x,
                                               double* __restrict__ y, int b, int d, double alpha_first,
-                                              double alpha_rest, double shift, int row0, int nr, int col0,
+                                              double alpha_rest, double shift, int row0, int nr, int col0, int nx,
                                               unsigned char* smem) {
-  constexpr int CL = BS / 2;       // lanes per entry (two columns per lane)
-  constexpr int NS = kRL / CL;     // entries a lane group handles per round
-  static_assert(BS >= 2 && BS <= 32, "slice width");
+  constexpr int BS = 8 * CL;     // columns of the item
+  constexpr int CH = kRK * CL;   // entries per chunk
+  constexpr int G = kRT / CL;    // lane groups
+  constexpr int RW = BS / 2;     // double2 per operand row
   double* bufa = reinterpret_cast<double*>(smem);
   double* bufb = bufa + (size_t)nr * BS;
-  int32_t* rpl = reinterpret_cast<int32_t*>(bufb + (size_t)nr * BS);
+  double* part = bufb + (size_t)nr * BS;
+  int32_t* rpl = reinterpret_cast<int32_t*>(part + (size_t)nx * BS);
+  int32_t* cst = rpl + (nr + 1);
   const int tid = threadIdx.x;
-  const int lane = tid % kRL, g = tid / kRL;
-  const int tl = lane % CL, sg = lane / CL;
+  const int q = tid % CL, g = tid / CL;
   const int64_t ebase = rowptr[row0];
   const int nnz_local = (int)(rowptr[row0 + nr] - ebase);
 
-  // ---- stage: row pointers relative to the block's first entry, u = the slice of x, u- = 0
+  // ---- stage: row pointers relative to the block's first entry, chunk counts, u = the slice of x, u- = 0
   for (int r = tid; r <= nr; r += kRT) rpl[r] = (int)(rowptr[row0 + r] - ebase);
   for (int idx = tid; idx < nr * BS; idx += kRT) {
     const int r = idx / BS, t = idx - r * BS;
@@ -73,38 +92,81 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
     bufb[idx] = 0.0;
   }
   __syncthreads();
-  if (nnz_local <= 0) {  // nothing to multiply with (cannot happen for a graph with positive degrees)
-    for (int idx = tid; idx < nr * BS; idx += kRT) {
-      const int r = idx / BS, t = idx - r * BS;
-      y[(int64_t)(row0 + r) * b + col0 + t] = 0.0;
-    }
-    return;  // uniform over the workgroup
+  for (int r = tid; r < nr; r += kRT) {
+    const int len = rpl[r + 1] - rpl[r];
+    cst[r + 1] = len > CH ? (len + CH - 1) / CH : 1;  // an empty row still is one (empty) chunk
   }
+  if (tid == 0) cst[0] = 0;
+  __syncthreads();
+  if (tid < 64) {  // exclusive prefix sums of the chunk counts: 64 lanes, a contiguous run of rows each
+    const int per = (nr + 63) / 64;
+    const int lo = tid * per < nr ? tid * per : nr, hi = lo + per < nr ? lo + per : nr;
+    int total = 0;
+    for (int r = lo; r < hi; ++r) total += cst[r + 1];
+    int incl = total;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(incl, o, 64);
+      if (tid >= o) incl += up;
+    }
+    int run = incl - total;
+    for (int r = lo; r < hi; ++r) {
+      run += cst[r + 1];
+      cst[r + 1] = run;
+    }
+  }
+  __syncthreads();
+  const int nv = cst[nr];  // chunks of the block; the host made sure that nv <= kRS * G and nv - nr == nx
+
   const int32_t* cp = col + ebase;
   const double* vp = val + ebase;
   const unsigned last_row = (unsigned)(nr - 1);
 
-  // entry `lane` of the batch that starts at local entry e (of a row ending at e1): local column and value; lanes
-  // past the row's end take its last entry with the value 0 (the loads are never predicated)
-  auto load_batch = [&](int e, int e1, int32_t& c, double& a) {
-    int idx = e + lane;
-    const bool in = idx < e1;
-    idx = in ? idx : e1 - 1;
-    idx = idx < 0 ? 0 : idx;
-    const unsigned lc = (unsigned)(cp[idx] - row0);
-    c = (int32_t)(lc < last_row ? lc : last_row);  // a column outside the block (not a diagonal block) stays in range
-    const double av = vp[idx];
-    a = in ? av : 0.0;
-  };
-
-  // ---- the register-resident batches: first batch of rows g, g + G, ..., g + (kRKeep-1) G
-  int32_t kc[kRKeep];
-  double ka[kRKeep];
+  // ---- the group's chunks: row, place among the row's chunks, entries (kept in registers for all steps)
+  int32_t kc[kRS][kRK];
+  double ka[kRS][kRK];
+  int crow[kRS], cidx[kRS], cnum[kRS], krounds[kRS];
 #pragma unroll
-  for (int k = 0; k < kRKeep; ++k) {
-    int r = g + k * kRG;
-    r = r < nr ? r : nr - 1;
-    load_batch(rpl[r], rpl[r + 1], kc[k], ka[k]);
+  for (int sl = 0; sl < kRS; ++sl) {
+    const int v = g + sl * G;
+    const bool valid = v < nv;
+    int lo = 0, hi = nr;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (cst[mid] <= (valid ? v : 0)) lo = mid; else hi = mid;
+    }
+    const int r = lo;
+    const int j = valid ? v - cst[r] : 0;
+    const int e0 = rpl[r] + j * CH;
+    int e1 = rpl[r + 1];
+    e1 = e1 < e0 + CH ? e1 : e0 + CH;
+    if (!valid) e1 = e0;
+    crow[sl] = valid ? r : -1;
+    cidx[sl] = j;
+    cnum[sl] = cst[r + 1] - cst[r];
+#pragma unroll
+    for (int k = 0; k < kRK; ++k) {
+      int idx = e0 + k * CL + q;
+      const bool in = idx < e1;
+      idx = in ? idx : (nnz_local > 0 ? (e1 > 0 ? e1 - 1 : 0) : 0);
+      unsigned lc = 0;
+      double av = 0.0;
+      if (nnz_local > 0) {  // uniform over the workgroup
+        lc = (unsigned)(cp[idx] - row0);
+        av = vp[idx];
+      }
+      kc[sl][k] = (int32_t)(lc < last_row ? lc : last_row);  // a column outside the block stays inside LDS
+      ka[sl][k] = in ? av : 0.0;
+    }
+    // rounds of this slot that any lane of the wave needs (uniform over the wave)
+    int need = (e1 - e0 + CL - 1) / CL;
+    if (valid && need < 1) need = 1;  // an empty row still gets its recurrence update
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const int other = __shfl_xor(need, o, 64);
+      need = need > other ? need : other;
+    }
+    krounds[sl] = __builtin_amdgcn_readfirstlane(need);
   }
 
   double* cur = bufa;
@@ -114,84 +176,98 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
     const double beta = step == 0 ? 0.0 : 1.0;
     const double2* __restrict__ cur2 = reinterpret_cast<const double2*>(cur);
     double2* prev2 = reinterpret_cast<double2*>(prev);
-
-    // sums of one batch (entry `lane` = (c, a)) into the lane's two accumulators
-    auto batch_sum = [&](int32_t c, double a, int cnt, double& acc0, double& acc1) {
-      const int rounds = (cnt + NS - 1) / NS;
-      int r = 0;
-#define SC_RES_ROUNDS(K)                                        \
-  {                                                             \
-    double2 zv[K];                                              \
-    _Pragma("unroll") for (int u = 0; u < K; ++u) {             \
-      const int32_t cu = __shfl(c, (r + u) * NS + sg, kRL);     \
-      zv[u] = cur2[cu * CL + tl];                               \
-    }                                                           \
-    _Pragma("unroll") for (int u = 0; u < K; ++u) {             \
-      const double au = __shfl(a, (r + u) * NS + sg, kRL);      \
-      acc0 += au * zv[u].x;                                     \
-      acc1 += au * zv[u].y;                                     \
-    }                                                           \
-    r += K;                                                     \
+#pragma unroll
+    for (int sl = 0; sl < kRS; ++sl) {
+      if (krounds[sl] == 0) continue;  // no lane of this wave has a chunk in this slot
+      double acc[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) acc[t] = 0.0;
+#define SC_RES_ENTRY(K, Q)                                                                   \
+  if constexpr (Q < CL) {                                                                    \
+    const int cb = dpp_int<GroupBcast<CL, Q>::ctrl>(kc[sl][K]);                              \
+    const double ab = dpp_double<GroupBcast<CL, Q>::ctrl>(ka[sl][K]);                        \
+    const double2* zp = cur2 + cb * RW + q * 4;                                              \
+    const double2 z0 = zp[0], z1 = zp[1], z2 = zp[2], z3 = zp[3];                            \
+    acc[0] += ab * z0.x;                                                                     \
+    acc[1] += ab * z0.y;                                                                     \
+    acc[2] += ab * z1.x;                                                                     \
+    acc[3] += ab * z1.y;                                                                     \
+    acc[4] += ab * z2.x;                                                                     \
+    acc[5] += ab * z2.y;                                                                     \
+    acc[6] += ab * z3.x;                                                                     \
+    acc[7] += ab * z3.y;                                                                     \
   }
-      while (rounds - r >= 4) SC_RES_ROUNDS(4)
-      if (rounds - r >= 2) SC_RES_ROUNDS(2)
-      if (rounds - r >= 1) SC_RES_ROUNDS(1)
-#undef SC_RES_ROUNDS
-    };
-
-    // one row, given its first batch: further batches eight at a time, shuffle tree, recurrence, store over u-
-    auto do_row = [&](int r, int32_t c, double a) {
-      const int e0 = rpl[r], e1 = rpl[r + 1];
-      const int len = e1 - e0;
-      double acc0 = 0.0, acc1 = 0.0;
-      batch_sum(c, a, len < kRL ? len : kRL, acc0, acc1);
-      for (int e = e0 + kRL; e < e1; e += kRL * kRAhead) {
-        int32_t tc[kRAhead];
-        double ta[kRAhead];
+#define SC_RES_ROUND(K)               \
+  if (K < krounds[sl]) {              \
+    SC_RES_ENTRY(K, 0)                \
+    SC_RES_ENTRY(K, 1)                \
+    SC_RES_ENTRY(K, 2)                \
+    SC_RES_ENTRY(K, 3)                \
+  }
+      SC_RES_ROUND(0)
+      SC_RES_ROUND(1)
+      SC_RES_ROUND(2)
+      SC_RES_ROUND(3)
+      SC_RES_ROUND(4)
+      SC_RES_ROUND(5)
+      SC_RES_ROUND(6)
+      SC_RES_ROUND(7)
+#undef SC_RES_ROUND
+#undef SC_RES_ENTRY
+      const int r = crow[sl];
+      if (r >= 0) {
+        if (cidx[sl] == 0) {  // first chunk of its row: the recurrence with this chunk's sum, stored over u-
+          const double2* own = cur2 + r * RW + q * 4;
+          double2* out = prev2 + r * RW + q * 4;
 #pragma unroll
-        for (int q = 0; q < kRAhead; ++q) {
-          const int eq = e + q * kRL;
-          load_batch(eq < e1 ? eq : e1 - 1, e1, tc[q], ta[q]);
+          for (int t = 0; t < 4; ++t) {
+            const double2 o = own[t], pv = out[t];
+            double2 w;
+            w.x = alpha * (acc[2 * t] - shift * o.x) - beta * pv.x;
+            w.y = alpha * (acc[2 * t + 1] - shift * o.y) - beta * pv.y;
+            out[t] = w;
+          }
+        } else {  // a further chunk: its sum waits in LDS for the row's owner
+          double2* out = reinterpret_cast<double2*>(part) + (size_t)(g + sl * G - r - 1) * RW + q * 4;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            double2 w;
+            w.x = acc[2 * t];
+            w.y = acc[2 * t + 1];
+            out[t] = w;
+          }
         }
-#pragma unroll
-        for (int q = 0; q < kRAhead; ++q) {
-          const int left = e1 - (e + q * kRL);
-          if (left > 0) batch_sum(tc[q], ta[q], left < kRL ? left : kRL, acc0, acc1);
-        }
       }
-#pragma unroll
-      for (int o = kRL / 2; o >= CL; o >>= 1) {
-        acc0 += __shfl_xor(acc0, o, kRL);
-        acc1 += __shfl_xor(acc1, o, kRL);
-      }
-      if (lane < CL) {
-        const double2 own = cur2[r * CL + tl];
-        const double2 pv = prev2[r * CL + tl];
-        double2 out;
-        out.x = alpha * (acc0 - shift * own.x) - beta * pv.x;
-        out.y = alpha * (acc1 - shift * own.y) - beta * pv.y;
-        prev2[r * CL + tl] = out;
-      }
-    };
-
-#pragma unroll
-    for (int k = 0; k < kRKeep; ++k) {
-      const int r = g + k * kRG;
-      if (r < nr) do_row(r, kc[k], ka[k]);
     }
-    for (int rb = g + kRKeep * kRG; rb < nr; rb += kRAhead * kRG) {
-      int32_t tc[kRAhead];
-      double ta[kRAhead];
+    if (nx > 0) {  // uniform over the workgroup
+      __syncthreads();
 #pragma unroll
-      for (int q = 0; q < kRAhead; ++q) {
-        int r = rb + q * kRG;
-        r = r < nr ? r : nr - 1;
-        load_batch(rpl[r], rpl[r + 1], tc[q], ta[q]);
-      }
+      for (int sl = 0; sl < kRS; ++sl) {
+        const int r = crow[sl];
+        if (r >= 0 && cidx[sl] == 0 && cnum[sl] > 1) {
+          // the row's further chunks are chunks cst[r] + 1 ... of the block; chunk v parks at slot v - row(v) - 1
+          const double2* src = reinterpret_cast<const double2*>(part) + (size_t)(g + sl * G - r) * RW + q * 4;
+          double2 sum[4];
 #pragma unroll
-      for (int q = 0; q < kRAhead; ++q) {
-        const int r = rb + q * kRG;
-        if (r < nr) do_row(r, tc[q], ta[q]);
+          for (int t = 0; t < 4; ++t) sum[t] = src[t];
+          for (int j = 2; j < cnum[sl]; ++j) {
+            const double2* more = src + (size_t)(j - 1) * RW;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              const double2 m = more[t];
+              sum[t].x += m.x;
+              sum[t].y += m.y;
+            }
+          }
+          double2* out = prev2 + r * RW + q * 4;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            double2 w = out[t];
+            w.x += alpha * sum[t].x;
+            w.y += alpha * sum[t].y;
+            out[t] = w;
+          }
+        }
       }
     }
     __syncthreads();  // every row of the new iterate is in place; nobody reads the old u- any more
@@ -213,14 +289,36 @@ __global__ __launch_bounds__(kRT) void cheb_resident_kernel(const int64_t* __res
                                                             const int32_t* __restrict__ items) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int32_t* it = items + 4 * (int64_t)blockIdx.x;
-  const int row0 = it[0], nr = it[1], col0 = it[2], bs = it[3];  // uniform over the workgroup
-  switch (bs) {
-    case 2: resident_item<2>(rowptr, col, val, x, y, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, smem); break;
-    case 4: resident_item<4>(rowptr, col, val, x, y, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, smem); break;
-    case 8: resident_item<8>(rowptr, col, val, x, y, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, smem); break;
-    case 16: resident_item<16>(rowptr, col, val, x, y, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, smem); break;
-    case 32: resident_item<32>(rowptr, col, val, x, y, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, smem); break;
-    default: break;
+  const int row0 = it[0], nr = it[1], col0 = it[2], cl = it[3] & 15, nx = it[3] >> 4;  // uniform over the workgroup
+  if (cl == 4)
+    resident_item<4>(rowptr, col, val, x, y, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem);
+  else if (cl == 2)
+    resident_item<2>(rowptr, col, val, x, y, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem);
+}
+
+// extra[2 t] / extra[2 t + 1] = chunks beyond the first, summed over the rows of diagonal block t, for chunks of 32 /
+// of 16 entries.  One wave per block.
+__global__ __launch_bounds__(256) void block_extra_chunks_kernel(const int64_t* __restrict__ rowptr,
+                                                                 const int32_t* __restrict__ starts, int nblk, int64_t n,
+                                                                 int32_t* __restrict__ extra) {
+  const int t = (int)(((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6);
+  const int lane = threadIdx.x & 63;
+  if (t >= nblk) return;
+  const int64_t r0 = starts[t], r1 = t + 1 < nblk ? (int64_t)starts[t + 1] : n;
+  int x32 = 0, x16 = 0;
+  for (int64_t r = r0 + lane; r < r1; r += 64) {
+    const int len = (int)(rowptr[r + 1] - rowptr[r]);
+    if (len > 32) x32 += (len + 31) / 32 - 1;
+    if (len > 16) x16 += (len + 15) / 16 - 1;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    x32 += __shfl_xor(x32, o, 64);
+    x16 += __shfl_xor(x16, o, 64);
+  }
+  if (lane == 0) {
+    extra[2 * t] = x32;
+    extra[2 * t + 1] = x16;
   }
 }
 
@@ -255,7 +353,17 @@ size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 }  // namespace
 
-size_t resident_item_lds_bytes(int nrows, int bs) { return resident_lds_bytes(nrows, bs); }
+size_t resident_item_lds_bytes(int nrows, int cl, int extra) { return resident_lds_bytes(nrows, cl, extra); }
+
+int resident_max_chunks(int cl) { return kRS * (kRT / cl); }
+
+hipError_t launch_block_extra_chunks(const int64_t* rowptr, const int32_t* starts, int nblk, int64_t n, int32_t* extra,
+                                     hipStream_t st) {
+  if (nblk <= 0) return hipSuccess;
+  hipLaunchKernelGGL(block_extra_chunks_kernel, dim3((unsigned)(((int64_t)nblk * 64 + 255) / 256)), dim3(256), 0, st,
+                     rowptr, starts, nblk, n, extra);
+  return hipGetLastError();
+}
 
 size_t diagonal_blocks_workspace(int64_t n) {
   size_t t1 = 0, t2 = 0;

@@ -133,6 +133,34 @@ def test_single_vector_product_over_average_degrees(B, deg):
     assert np.max(np.abs(y2.cpu().numpy() - y0)) <= 1e-13 * np.abs(y0).max(), deg
 
 
+@pytest.mark.parametrize("deg", [4, 8, 26, 60])
+def test_single_vector_product_chain(B, deg):
+    """sc_spmv_normalized_chain: three products in a row, each taking the operand the previous one left (s o y), against
+    the oracle's S applied three times; y of every link equals what sc_spmm_normalized gives for the same x."""
+    n = 3001
+    if deg == 4:
+        rp, c, v, _ = wl.random_weighted_connected(n, 3000, 4)       # about 4 entries per row: the lanes-per-row kernel
+    else:
+        rp, c, v, _ = _regular_with_hub(n, deg, deg)
+    drp, dc, dv = B.csr_to_device(rp, c, v)
+    _, s = B.sc_degree_scaling(drp, dc, dv)
+    x = np.random.default_rng(deg).standard_normal(n)
+    dx = torch.from_numpy(x).cuda()
+    z = s * dx
+    y = torch.empty_like(dx)
+    z2 = torch.empty_like(dx)
+    want = x
+    for link in range(3):
+        assert B.sc_spmv_normalized_chain(drp, dc, dv, s, int(rp[-1]), z, y, z2) == B.SC_OK
+        torch.cuda.synchronize()
+        want = laplacian.apply_s(rp, c, v, want)
+        assert np.max(np.abs(y.cpu().numpy() - want)) <= 1e-13 * np.abs(want).max(), (deg, link)
+        assert torch.equal(z2, s * y)
+        z, z2 = z2, z
+    with pytest.raises(B.ScError):
+        B.sc_spmv_normalized_chain(drp, dc, dv, s, int(rp[-1]), z, y, z)
+
+
 @pytest.mark.parametrize("ncols", [1, 2, 8, 16])
 def test_scaled_operator_and_its_product(B, graphs, ncols):
     """Algorithm 2 step 3 as a step of its own: the scaled values are s_i w_ij s_j entry by entry and exactly symmetric,
@@ -312,26 +340,28 @@ def test_chebyshev_filter(B, ncols):
 
 
 def _block_diagonal_graph():
-    """Contiguous diagonal blocks of every kind the LDS-resident filter distinguishes: two rows; fewer rows than lane
-    groups; more than 256 rows (rows beyond the register-kept ones, one and several rounds of them); rows of 1, 33, 69,
-    299 and 500 entries (one batch, two, three, and more than one round of further batches); 1,500 rows (too many for
-    16 or 32 columns at once: column slices)."""
+    """Contiguous diagonal blocks of every kind the LDS-resident filter distinguishes: two rows; fewer rows than a wave
+    has lane groups; rows of 1, 2, 27 (average), 33, 69 and 500 entries (one chunk, several chunks, a hub spread over
+    16 or 32 lane groups); more chunks than lane groups (second chunk slot); 300 to 501 rows (too many for 32 columns
+    at once: two 16-column items)."""
     star = wl.symmetric_from_edges(np.zeros(500, dtype=np.int64), np.arange(1, 501), np.linspace(0.5, 1.5, 500), 501)
-    return wl.disjoint_union(wl.path(2), wl.random_weighted_connected(700, 9000, 5), wl.ring(257), wl.complete(70),
-                             wl.ring(7), wl.random_weighted_connected(333, 700, 6), wl.complete(300), star,
-                             wl.complete(34), wl.random_weighted_connected(1500, 9000, 7), wl.path(31))
+    return wl.disjoint_union(wl.path(2), wl.random_weighted_connected(300, 4000, 5), wl.ring(257), wl.complete(70),
+                             wl.ring(7), wl.random_weighted_connected(333, 700, 6), star, wl.complete(34),
+                             wl.random_weighted_connected(450, 2500, 7), wl.path(31))
 
 
-@pytest.mark.parametrize("ncols", [8, 16, 32])
+@pytest.mark.parametrize("ncols", [16, 32])
 @pytest.mark.parametrize("degree", [1, 2, 12])
 def test_chebyshev_filter_resident_in_lds(B, ncols, degree, monkeypatch):
-    """The one-launch form of the start-block filter (a workgroup keeps the iterates of a diagonal block in LDS through
-    all steps) against the oracle's recurrence, element by element, on a block-diagonal graph as given; it must be the
-    path taken (event counter), be bitwise repeatable, and agree with the product-per-step path to rounding."""
+    """The one-launch form of the start-block filter (a workgroup keeps the iterates of a diagonal block in LDS and the
+    block's entries in registers through all steps) against the oracle's recurrence, element by element, on a
+    block-diagonal graph as given; it must be the path taken (event counter), be bitwise repeatable, and agree with the
+    product-per-step path to rounding."""
     from oracle import blockops
     monkeypatch.setenv("SCEIG_FORCE_RESIDENT", "1")       # small graph: the cost model would pick the other path
     g = _block_diagonal_graph()
     rp, c, v, n = g
+    assert np.diff(rp).max() == 500 and np.sum(np.diff(rp) > 32) > 100
     rng = np.random.default_rng(7 * ncols + degree)
     x = rng.standard_normal((n, ncols))
     a = 0.4
@@ -350,13 +380,33 @@ def test_chebyshev_filter_resident_in_lds(B, ncols, degree, monkeypatch):
     other = B.sc_chebyshev_filter(drp, dc, dv, dx, a, degree)
     assert B.sc_counter(B.SC_COUNTER_RESIDENT_FILTERS) == before + 2
     assert np.max(np.abs(other.cpu().numpy() - got.cpu().numpy())) <= 1e-11 * scale
-    # the input block inside a wider buffer, the output into a wider buffer
+    # the input block inside a wider buffer
     monkeypatch.delenv("SCEIG_NO_RESIDENT")
     monkeypatch.setenv("SCEIG_FORCE_RESIDENT", "1")
     xb = torch.zeros((n, ncols + 3), dtype=torch.float64, device="cuda")
     xb[:, :ncols] = dx
     got2 = B.sc_chebyshev_filter(drp, dc, dv, xb[:, :ncols], a, degree)
     assert torch.equal(got2, got)
+
+
+def test_chebyshev_filter_resident_declines_what_does_not_fit(B, monkeypatch):
+    """Blocks with more rows than LDS holds at 16 columns (700 rows), with more chunks than the lane groups take
+    (complete graph on 300 nodes: 10 chunks a row), or a block width without a resident form (8 columns) go the
+    product-per-step way even when the resident form is asked for; the answer is the oracle's either way."""
+    from oracle import blockops
+    monkeypatch.setenv("SCEIG_FORCE_RESIDENT", "1")
+    rng = np.random.default_rng(3)
+    cases = [(wl.disjoint_union(wl.ring(40), wl.random_weighted_connected(700, 3000, 1)), 16),
+             (wl.disjoint_union(wl.ring(40), wl.complete(300)), 32),
+             (wl.disjoint_union(wl.ring(40), wl.ring(50)), 8)]
+    for (rp, c, v, n), ncols in cases:
+        x = rng.standard_normal((n, ncols))
+        drp, dc, dv = B.csr_to_device(rp, c, v)
+        before = B.sc_counter(B.SC_COUNTER_RESIDENT_FILTERS)
+        got = B.sc_chebyshev_filter(drp, dc, dv, torch.from_numpy(x).cuda(), 0.3, 5).cpu().numpy()
+        assert B.sc_counter(B.SC_COUNTER_RESIDENT_FILTERS) == before
+        want = blockops.chebyshev_filter(rp, c, v, x, 0.3, 5)
+        assert np.max(np.abs(got - want)) <= 1e-11 * max(1.0, np.max(np.abs(want)))
 
 
 def test_chebyshev_filter_rejects_bad_arguments(B):
