@@ -18,7 +18,15 @@
 //     inside a component, so the chunks that share a wave are equally long.
 //   * One round: every lane group hands the round's entry from the lane that holds it to its other lanes with a DPP
 //     quad permute (an ALU move, no LDS traffic), reads the 64 bytes of its 8 columns of that operand row from LDS
-//     and does 8 multiply-adds.
+//     and does 8 multiply-adds.  A lane's 8 columns are four 16-byte pieces CL apart, so that one read instruction
+//     of a lane group covers 16 CL contiguous bytes (a "segment": a quarter of the row).  A row of 8 CL doubles is a
+//     whole number of LDS bank periods, so lane groups that read the same segment of different rows in the same
+//     instruction hit the same banks.  Neighbouring lane groups therefore take the four segments in rotated order
+//     (group w reads segment (t + w) mod 4 in its t-th read; its t-th pair of accumulators belongs to that segment
+//     throughout), and the four groups of a 16-lane pass always touch four different segments.  Measured per step
+//     on 2,000 blocks of 250 rows, 32 columns: 92 us with every group reading the segments in the same order, 59 us
+//     with a row-dependent xor placement of the pieces (bank-conflict cycles still 49 % of the LDS-active cycles),
+//     42 us with the rotation (conflict cycles below 0.2 %); the product-per-step kernel takes 166 us.
 //   * The group that owns the first chunk of a row applies the recurrence with its own sum and stores the new row over
 //     u- in place (only the row's owner reads it); the other chunks of a row park their sums in LDS, and after a
 //     barrier the row's owner adds them in chunk order (fixed, so results are reproducible).  Blocks without hub rows
@@ -81,6 +89,10 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
   int32_t* cst = rpl + (nr + 1);
   const int tid = threadIdx.x;
   const int q = tid % CL, g = tid / CL;
+  // this lane's t-th piece (double2 index inside a row): segment (t + g) mod 4, position q inside the segment
+  const int pc0 = ((g + 0) & 3) * CL + q, pc1 = ((g + 1) & 3) * CL + q, pc2 = ((g + 2) & 3) * CL + q,
+            pc3 = ((g + 3) & 3) * CL + q;
+  const int pcs[4] = {pc0, pc1, pc2, pc3};
   const int64_t ebase = rowptr[row0];
   const int nnz_local = (int)(rowptr[row0 + nr] - ebase);
 
@@ -186,8 +198,8 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
   if constexpr (Q < CL) {                                                                    \
     const int cb = dpp_int<GroupBcast<CL, Q>::ctrl>(kc[sl][K]);                              \
     const double ab = dpp_double<GroupBcast<CL, Q>::ctrl>(ka[sl][K]);                        \
-    const double2* zp = cur2 + cb * RW + q * 4;                                              \
-    const double2 z0 = zp[0], z1 = zp[1], z2 = zp[2], z3 = zp[3];                            \
+    const double2* zp = cur2 + cb * RW;                                                      \
+    const double2 z0 = zp[pc0], z1 = zp[pc1], z2 = zp[pc2], z3 = zp[pc3];                    \
     acc[0] += ab * z0.x;                                                                     \
     acc[1] += ab * z0.y;                                                                     \
     acc[2] += ab * z1.x;                                                                     \
@@ -217,24 +229,25 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
       const int r = crow[sl];
       if (r >= 0) {
         if (cidx[sl] == 0) {  // first chunk of its row: the recurrence with this chunk's sum, stored over u-
-          const double2* own = cur2 + r * RW + q * 4;
-          double2* out = prev2 + r * RW + q * 4;
+          const double2* own = cur2 + r * RW;
+          double2* out = prev2 + r * RW;
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
-            const double2 o = own[t], pv = out[t];
+            const int at = pcs[t];
+            const double2 o = own[at], pv = out[at];
             double2 w;
             w.x = alpha * (acc[2 * t] - shift * o.x) - beta * pv.x;
             w.y = alpha * (acc[2 * t + 1] - shift * o.y) - beta * pv.y;
-            out[t] = w;
+            out[at] = w;
           }
         } else {  // a further chunk: its sum waits in LDS for the row's owner
-          double2* out = reinterpret_cast<double2*>(part) + (size_t)(g + sl * G - r - 1) * RW + q * 4;
+          double2* out = reinterpret_cast<double2*>(part) + (size_t)(g + sl * G - r - 1) * RW;
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
             double2 w;
             w.x = acc[2 * t];
             w.y = acc[2 * t + 1];
-            out[t] = w;
+            out[pcs[t]] = w;
           }
         }
       }
@@ -246,26 +259,27 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
         const int r = crow[sl];
         if (r >= 0 && cidx[sl] == 0 && cnum[sl] > 1) {
           // the row's further chunks are chunks cst[r] + 1 ... of the block; chunk v parks at slot v - row(v) - 1
-          const double2* src = reinterpret_cast<const double2*>(part) + (size_t)(g + sl * G - r) * RW + q * 4;
+          const double2* src = reinterpret_cast<const double2*>(part) + (size_t)(g + sl * G - r) * RW;
           double2 sum[4];
 #pragma unroll
-          for (int t = 0; t < 4; ++t) sum[t] = src[t];
+          for (int t = 0; t < 4; ++t) sum[t] = src[pcs[t]];
           for (int j = 2; j < cnum[sl]; ++j) {
             const double2* more = src + (size_t)(j - 1) * RW;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-              const double2 m = more[t];
-              sum[t].x += m.x;
-              sum[t].y += m.y;
+              const double2 mo = more[pcs[t]];
+              sum[t].x += mo.x;
+              sum[t].y += mo.y;
             }
           }
-          double2* out = prev2 + r * RW + q * 4;
+          double2* out = prev2 + r * RW;
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
-            double2 w = out[t];
+            const int at = pcs[t];
+            double2 w = out[at];
             w.x += alpha * sum[t].x;
             w.y += alpha * sum[t].y;
-            out[t] = w;
+            out[at] = w;
           }
         }
       }
