@@ -375,6 +375,41 @@ int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, i
   return ngram;
 }
 
+// Gram-Schmidt of basis[:, wcol : wcol+b] against basis[:, 0 : j] with the second pass decided on the device ("twice
+// is enough", and once is when nothing is lost to cancellation): after the first pass a one-workgroup kernel compares,
+// per column, the squared norm the pass removed with the squared norm it kept; if no column lost more than a factor
+// 10^6 (orthogonality error after one pass about 1e-16 * 1e3), the three launches of the second pass find skip[0] set
+// and return at once.  No host round trip either way.  gpart receives the Gram partials of the final block (from the
+// first update, overwritten by the second when it runs); returns their count.  gram_tmp: kPP*kPP doubles of scratch.
+int enqueue_cgs_adaptive(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, double* part, double* h1,
+                         double* hsum, double* gpart, double* gram_tmp, int* skip, hipStream_t st, KTimer* tm) {
+  if (j <= 0) return 0;
+  KTimer none;
+  if (!tm) tm = &none;
+  const double rows = (double)n;
+  const ProjectPlan plan = plan_project(n, j, kMaxPartials);
+  const int ngram = plan_update_gram(n);
+  for (int pass = 0; pass < 2; ++pass) {
+    const int* sk = pass == 0 ? nullptr : skip;
+    // the second pass's traffic is not counted: whether it ran is known on the device only
+    const double counted = pass == 0 ? 1.0 : 0.0;
+    tm->begin(kFamProject);
+    HIP_TRY(launch_project(basis, n, ld, 0, j, wcol, b, plan, part, st, sk));
+    tm->end(kFamProject, counted * 8.0 * rows * (j + b), counted * 2.0 * rows * j * b);
+    tm->begin(kFamOther);
+    HIP_TRY(launch_reduce_partials(part, plan.npart, j, b, h1, hsum, pass, nullptr, 0, st, sk));
+    tm->end(kFamOther, counted * 8.0 * plan.npart * (double)j * b, 0.0);
+    tm->begin(kFamUpdate);
+    HIP_TRY(launch_update_gram(basis, n, ld, 0, j, h1, b, wcol, 0, gpart, st, sk));
+    tm->end(kFamUpdate, counted * 8.0 * rows * (j + 2 * b), counted * 2.0 * rows * j * b);
+    if (pass == 0) {
+      HIP_TRY(launch_reduce_partials(gpart, ngram, b, b, gram_tmp, nullptr, 0, nullptr, 0, st));
+      HIP_TRY(launch_second_pass_test(h1, j, b, gram_tmp, 1e6, skip, st));
+    }
+  }
+  return ngram;
+}
+
 // Cholesky QR twice on basis[:, col : col+b].  r_out / g_out: device b x b (stride kPP) or null;
 // gram, rinv, r1: device scratch of kPP*kPP doubles each; gpart: scratch for Gram partials (kGramPartials blocks).
 // ngram > 0: gpart already holds that many Gram partials of the block (left by enqueue_cgs2).
@@ -622,6 +657,7 @@ struct Solver {
   uint32_t flags;
   uint64_t seed;
   const double* v0 = nullptr;  // caller's start vector (caller's numbering), or null
+  bool no_late_projection = std::getenv("SCEIG_NO_LATE_PROJECTION") != nullptr;
   size_t ws_limit = 0;         // > 0: size of the caller's workspace, checked against the estimate once nnz is known
   hipStream_t st;
   // device
@@ -650,6 +686,7 @@ struct Solver {
   int filt_d = 0;
   double filt_a = 0.0;
   double filt_best = -2.0;  // best lower estimate so far of the largest eigenvalue below the locked cluster
+  double filt_ref = 2.0;    // the Ritz value the planned filter is made large at
   sc_stats stats{};
   KTimer timer;
 
@@ -906,6 +943,7 @@ struct Solver {
     const int d = (int)std::ceil(std::log(2.0 * amp) / rate);
     filt_d = std::min(std::max(d, 2), dmax);
     filt_a = a;
+    filt_ref = th_ref;
   }
 
   // out (n x l row-major in rot) = basis[:, nl : nl+ja] * Y[:, sel]; then copied to basis[:, dst : dst+l]
@@ -980,22 +1018,36 @@ struct Solver {
       if (v0 && stats.phases == 1)  // the caller's start vector leads the first block, the other columns stay random
         HIP_TRY(launch_set_column(basis.p, n, ld, nl, v0, rowmap, st));
       bool filtered = filt_d > 0;
+      // The locked vectors' eigenvalues lie above the damped interval too, so the filter amplifies what a block holds
+      // along them.  When none of them lies above the value the filter is aimed at (the usual case here: further
+      // copies of one multiple eigenvalue), they are amplified no more than the wanted directions, the filtered block
+      // keeps a fair share of its norm outside their span, and projecting them out AFTER the filter loses nothing to
+      // cancellation: the random block goes into the filter as it is, and one Gram-Schmidt pass afterwards - a second
+      // only if the device-side test asks for it - takes the place of a pass before and a pass after the filter.
+      // Otherwise (locked eigenvalues above the target: they would swamp the block) the block is projected first.
+      bool late_projection = false;
+      if (filtered && nl > 0 && !no_late_projection) {
+        const double top = *std::max_element(theta_locked.begin(), theta_locked.end());
+        late_projection = top <= filt_ref + 1e-6;
+      }
       if (filtered) {
-        // the filter is linear and takes the random block as it is, after one projection pass against the locked
-        // vectors: their eigenvalues lie above the damped interval too, so what the block holds along them is
-        // amplified like the wanted directions, and removing it afterwards is only as exact as the locked vectors
         if (debug_on())
-          std::fprintf(stderr, "[sceig] t=%.4fs phase %d start block filtered: degree %d, damped interval [-1, %.6f]\n",
-                       now_s() - t_begin, stats.phases, filt_d, filt_a);
-        (void)enqueue_cgs2(basis.p, n, ld, nl, nl, b, nl, part.p, h1.p, hsum.p, nullptr, 0, nullptr, st, &timer);
+          std::fprintf(stderr, "[sceig] t=%.4fs phase %d start block filtered: degree %d, damped interval [-1, %.6f]%s\n",
+                       now_s() - t_begin, stats.phases, filt_d, filt_a,
+                       late_projection ? ", locked vectors projected out afterwards" : "");
+        if (!late_projection)
+          (void)enqueue_cgs2(basis.p, n, ld, nl, nl, b, nl, part.p, h1.p, hsum.p, nullptr, 0, nullptr, st, &timer);
         HIP_TRY(launch_pack_scaled(basis.p + nl, ld, zs(), n, b, z.p, st));
         apply_start_filter(filt_d, filt_a);
         filt_d = 0;
       }
-      // a filtered block went into the filter orthogonal to the locked vectors; what it picked up along them since is
-      // of the order of their residuals relative to the block, so one projection removes it without cancellation
-      const int ngram0 = enqueue_cgs2(basis.p, n, ld, nl, nl, b, filtered ? nl : 0, part.p, h1.p, hsum.p, nullptr, 0,
-                                      gpart.p, st, &timer);
+      // a block that went into the filter orthogonal to the locked vectors picked up along them since only what is of
+      // the order of their residuals relative to the block, so one projection removes it without cancellation
+      const int ngram0 =
+          late_projection
+              ? enqueue_cgs_adaptive(basis.p, n, ld, nl, nl, b, part.p, h1.p, hsum.p, gpart.p, gram(), flag.p, st, &timer)
+              : enqueue_cgs2(basis.p, n, ld, nl, nl, b, filtered ? nl : 0, part.p, h1.p, hsum.p, nullptr, 0, gpart.p, st,
+                             &timer);
       enqueue_block_qr(basis.p, n, ld, nl, b, part.p, gpart.p, ngram0, gram(), rinv(), r1(), slot(0) + kPP * kPP,
                        slot(0) + 2 * kPP * kPP, z.p, zs(), st, &timer);
       int ja = b;            // active columns whose coupling is (or will be) assembled

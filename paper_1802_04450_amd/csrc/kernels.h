@@ -50,13 +50,20 @@ struct ProjectPlan {
 ProjectPlan plan_project(int64_t n, int ja, int max_partials);
 // part[p][c][t] (c < ja, t < kPartialPad) = sum over the rows of partial p of A[i, acol0 + c] * B[i, bcol0 + t]
 // with A and B both columns of `basis` (row-major n x ld); t >= b entries are written as 0.
+// skip (here and below; may be null): device int; if *skip != 0 when the kernel starts, the launch does nothing.
 hipError_t launch_project(const double* basis, int64_t n, int64_t ld, int acol0, int ja, int bcol0, int b,
-                          const ProjectPlan& plan, double* part, hipStream_t st);
+                          const ProjectPlan& plan, double* part, hipStream_t st, const int* skip = nullptr);
 // h[c*kPartialPad + t] = sum_p part[p][c][t] in the fixed order p = 0..npart-1 (t < b, else 0);
 // if hsum != null: hsum = (accumulate ? hsum : 0) + h.
 // if slot != null: rows [slot_row0, ja) of the resulting hsum (or h) are copied to slot[(c-slot_row0)*kPartialPad + t].
 hipError_t launch_reduce_partials(const double* part, int npart, int ja, int b, double* h, double* hsum,
-                                  int accumulate, double* slot, int slot_row0, hipStream_t st);
+                                  int accumulate, double* slot, int slot_row0, hipStream_t st,
+                                  const int* skip = nullptr);
+// skip[0] = 1 when no column of the block needs a second Gram-Schmidt pass: for every column t < b the squared norm
+// the first pass removed, sum_c h[c*kPartialPad + t]^2 over c < ja, is at most ratio2 times the squared norm it kept,
+// gram[t*kPartialPad + t]; else skip[0] = 0.
+hipError_t launch_second_pass_test(const double* h, int ja, int b, const double* gram, double ratio2, int* skip,
+                                   hipStream_t st);
 
 // C = A * B row GEMM:  A = basis[:, acol0 : acol0+kdim] (n x kdim), B = bmat (kdim x ncols, row-major, ldb).
 // mode 0: basis[:, ccol0 + t] -= C[:, t]          (in place update, ncols <= 32, out unused)
@@ -87,7 +94,7 @@ int plan_update_gram(int64_t n);
 // overwrite != 0: the block is replaced by the product instead of having it subtracted (W <- W R^-1 with
 // acol0 = ccol0, kdim = b, bmat = R^-1)
 hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int b,
-                              int ccol0, int overwrite, double* gpart, hipStream_t st);
+                              int ccol0, int overwrite, double* gpart, hipStream_t st, const int* skip = nullptr);
 // ---- Chebyshev filter with the iterates resident in LDS (resident.hip) -------------------------------
 // A work item is a diagonal block (or a 16-column slice of it) worked on by lane groups of cl = 4 lanes (32 columns)
 // or cl = 2 lanes (16 columns).  Its rows are cut into chunks of 8 cl entries; `extra` = chunks beyond the first,

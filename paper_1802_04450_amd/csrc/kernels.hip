@@ -546,7 +546,9 @@ hipError_t launch_spmm_nz(const int64_t* rowptr, const int32_t* col, const doubl
 template <int NT>
 __global__ __launch_bounds__(kThreads) void project_kernel(const double* __restrict__ basis, int64_t n, int64_t ld,
                                                            int acol0, int ja, int bcol0, int b, int rows_per_panel,
-                                                           int nwc, int vec_ok, double* __restrict__ part) {
+                                                           int nwc, int vec_ok, double* __restrict__ part,
+                                                           const int* __restrict__ skip) {
+  if (skip && *skip) return;  // uniform over the grid: a pass that a device-side test found unnecessary
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int i = lane & 15, g = lane >> 4;
   const int nwr = 4 / nwc;
@@ -664,8 +666,10 @@ constexpr int kRedElems = kThreads / kRedSplit;  // 32 output elements per workg
 __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double* __restrict__ part, int npart, int ja,
                                                                    int ncol, double* __restrict__ h,
                                                                    double* __restrict__ hsum, int accumulate,
-                                                                   double* __restrict__ slot, int slot_row0) {
+                                                                   double* __restrict__ slot, int slot_row0,
+                                                                   const int* __restrict__ skip) {
   __shared__ double sub[kRedSplit][kRedElems + 1];
+  if (skip && *skip) return;  // uniform over the grid
   const int el = threadIdx.x % kRedElems, r = threadIdx.x / kRedElems;
   const int e = blockIdx.x * kRedElems + el;  // element index over ja * ncol
   const int total = ja * ncol;
@@ -1076,7 +1080,9 @@ template <int NT, bool PIPE>
 __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
                                                                int acol0, int kdim, const double* __restrict__ bmat, int b,
                                                                int ccol0, int vec_ok, int overwrite,
-                                                               double* __restrict__ gpart) {
+                                                               double* __restrict__ gpart,
+                                                               const int* __restrict__ skip) {
+  if (skip && *skip) return;  // uniform over the grid
   constexpr int MT = 2;
   constexpr int BW = NT * 16;
   constexpr int KC = 4096 / BW;
@@ -1572,27 +1578,27 @@ ProjectPlan plan_project(int64_t n, int ja, int max_partials) {
 }
 
 hipError_t launch_project(const double* basis, int64_t n, int64_t ld, int acol0, int ja, int bcol0, int b,
-                          const ProjectPlan& plan, double* part, hipStream_t st) {
+                          const ProjectPlan& plan, double* part, hipStream_t st, const int* skip) {
   if (ja <= 0) return hipSuccess;
   const int panels = plan.npart / (4 / plan.nwc);
   const dim3 grid((unsigned)panels, (unsigned)((ja + 64 * plan.nwc - 1) / (64 * plan.nwc)));
   const int vec_ok = (ld % 4 == 0 && acol0 % 4 == 0 && (reinterpret_cast<uintptr_t>(basis) % 32 == 0)) ? 1 : 0;
   if (b <= 16) {
     hipLaunchKernelGGL((project_kernel<1>), grid, dim3(kThreads), 0, st, basis, n, ld, acol0, ja, bcol0, b,
-                       plan.rows_per_panel, plan.nwc, vec_ok, part);
+                       plan.rows_per_panel, plan.nwc, vec_ok, part, skip);
   } else {
     hipLaunchKernelGGL((project_kernel<2>), grid, dim3(kThreads), 0, st, basis, n, ld, acol0, ja, bcol0, b,
-                       plan.rows_per_panel, plan.nwc, vec_ok, part);
+                       plan.rows_per_panel, plan.nwc, vec_ok, part, skip);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_reduce_partials(const double* part, int npart, int ja, int b, double* h, double* hsum,
-                                  int accumulate, double* slot, int slot_row0, hipStream_t st) {
+                                  int accumulate, double* slot, int slot_row0, hipStream_t st, const int* skip) {
   if (ja <= 0) return hipSuccess;
   const int total = ja * b;
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((total + kRedElems - 1) / kRedElems)), dim3(kThreads), 0,
-                     st, part, npart, ja, b, h, hsum, accumulate, slot, slot_row0);
+                     st, part, npart, ja, b, h, hsum, accumulate, slot, slot_row0, skip);
   return hipGetLastError();
 }
 
@@ -1640,19 +1646,55 @@ hipError_t launch_gram_cholesky(const double* g_in, int b, double* g_out, double
   return hipGetLastError();
 }
 
+// skip[0] = 1 if a second Gram-Schmidt pass is unnecessary for every column of the block, else 0.  Column t lost
+// removed_t = sum_c h[c][t]^2 of its squared norm to the first pass and kept gram[t][t]; the first pass leaves an
+// orthogonality error of about eps * sqrt(1 + removed / kept), which a second pass is needed for only when
+// removed > ratio2 * kept.  One workgroup; fixed summation order.
+__global__ __launch_bounds__(kThreads) void second_pass_test_kernel(const double* __restrict__ h, int ja, int b,
+                                                                    const double* __restrict__ gram, double ratio2,
+                                                                    int* __restrict__ skip) {
+  __shared__ double sub[kThreads];
+  __shared__ int need;
+  if (threadIdx.x == 0) need = 0;
+  const int t = threadIdx.x % kPartialPad, r = threadIdx.x / kPartialPad;  // 8 row classes per column
+  double acc = 0.0;
+  if (t < b)
+    for (int c = r; c < ja; c += kThreads / kPartialPad) {
+      const double v = h[(int64_t)c * kPartialPad + t];
+      acc += v * v;
+    }
+  sub[threadIdx.x] = acc;
+  __syncthreads();
+  if (r == 0 && t < b) {
+    double removed = 0.0;
+#pragma unroll
+    for (int q = 0; q < kThreads / kPartialPad; ++q) removed += sub[q * kPartialPad + t];
+    const double kept = gram[t * kPartialPad + t];
+    if (removed > ratio2 * kept) atomicOr(&need, 1);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) skip[0] = need ? 0 : 1;
+}
+
+hipError_t launch_second_pass_test(const double* h, int ja, int b, const double* gram, double ratio2, int* skip,
+                                   hipStream_t st) {
+  hipLaunchKernelGGL(second_pass_test_kernel, dim3(1), dim3(kThreads), 0, st, h, ja, b, gram, ratio2, skip);
+  return hipGetLastError();
+}
+
 int plan_update_gram(int64_t n) {
   const int64_t ntiles = (n + 127) / 128;
   return (int)(ntiles < 1024 ? ntiles : 1024);
 }
 
 hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int b,
-                              int ccol0, int overwrite, double* gpart, hipStream_t st) {
+                              int ccol0, int overwrite, double* gpart, hipStream_t st, const int* skip) {
   const int vec_ok = (ld % 4 == 0 && acol0 % 4 == 0 && (reinterpret_cast<uintptr_t>(basis) % 32 == 0)) ? 1 : 0;
   const unsigned grid = (unsigned)plan_update_gram(n);
   const bool pipe = kdim >= 128;  // loads one trip ahead pay from a few trips on
 #define SC_LAUNCH_UG(NTV, PV)                                                                                     \
   hipLaunchKernelGGL((update_gram_kernel<NTV, PV>), dim3(grid), dim3(kThreads), 0, st, basis, n, ld, acol0, kdim, \
-                     bmat, b, ccol0, vec_ok, overwrite, gpart)
+                     bmat, b, ccol0, vec_ok, overwrite, gpart, skip)
   if (b <= 16) {
     if (pipe) SC_LAUNCH_UG(1, true); else SC_LAUNCH_UG(1, false);
   } else {
