@@ -27,9 +27,9 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 FP64_MFMA_PEAK_TFLOPS = 78.6
-KERNEL_OF_FAMILY = ["spmm_cols_kernel / spmm_nz_kernel (S X with fused D^-1/2 scaling)",
+KERNEL_OF_FAMILY = ["spmm_cols_kernel / cheb_resident_kernel (S X with fused D^-1/2 scaling; filter steps)",
                     "project_kernel (CGS2 block projection H = Q^T W, fp64 MFMA)",
-                    "row_gemm_kernel mode 0 (CGS2 block update W -= Q H, fp64 MFMA)",
+                    "row_gemm_kernel mode 0 / update_gram_kernel (CGS2 block update W -= Q H, fp64 MFMA)",
                     "row_gemm_kernel mode 1/2 (restart rotation V Y, fp64 MFMA)",
                     "block QR (Gram + Cholesky + scaling)", "reduce_partials_kernel"]
 
