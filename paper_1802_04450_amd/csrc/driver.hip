@@ -1338,9 +1338,11 @@ struct Solver {
       std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return theta_locked[x] > theta_locked[y]; });
       order.resize(nfound);
       for (int t = 0; t < nfound; ++t) evals_host[t] = 1.0 - theta_locked[order[t]];
-      HIP_TRY(hipMemcpyAsync(perm_d.p, order.data(), (size_t)nfound * sizeof(int32_t), hipMemcpyHostToDevice, st));
-      HIP_TRY(launch_gather_cols_colmajor(basis.p, n, ld, perm_d.p, nfound, evecs_out, rowinv, st));
-      HIP_TRY(hipStreamSynchronize(st));  // `order` is pageable host memory
+      std::vector<int32_t> outpos((size_t)nx, -1);  // output column of every locked basis column
+      for (int t = 0; t < nfound; ++t) outpos[order[t]] = t;
+      HIP_TRY(hipMemcpyAsync(perm_d.p, outpos.data(), (size_t)nx * sizeof(int32_t), hipMemcpyHostToDevice, st));
+      HIP_TRY(launch_gather_cols_colmajor(basis.p, n, ld, perm_d.p, nx, evecs_out, rowinv, st));
+      HIP_TRY(hipStreamSynchronize(st));  // `outpos` is pageable host memory
     } else if (nx > 0) {
       std::vector<double> G((size_t)nx * nx, 0.0), hbuf((size_t)nx * kPP);
       const ProjectPlan plan = plan_project(n, nx, kMaxPartials);

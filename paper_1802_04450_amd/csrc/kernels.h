@@ -162,10 +162,10 @@ hipError_t launch_set_column(double* basis, int64_t n, int64_t ld, int col, cons
 hipError_t launch_random_block(double* basis, int64_t n, int64_t ld, int col0, int b, uint64_t seed,
                                uint64_t stream_id, hipStream_t st);
 // dst[i*ldd + dcol0 + t] = src[i*lds + scol0 + t], t < w (regions must not overlap)
-// out[t*n + o] = basis[r(o)*ld + perm[t]], t < k (perm: device int32[k]; r(o) = inv[o], the internal row of original
-// row o, if inv is given, else o)
-hipError_t launch_gather_cols_colmajor(const double* basis, int64_t n, int64_t ld, const int32_t* perm, int k, double* out,
-                                       const int32_t* inv, hipStream_t st);
+// out[pos[c]*n + o] = basis[r(o)*ld + c] for c < ncols with pos[c] >= 0 (pos: device int32[ncols], the output column
+// of basis column c or -1; r(o) = inv[o], the internal row of original row o, if inv is given, else o)
+hipError_t launch_gather_cols_colmajor(const double* basis, int64_t n, int64_t ld, const int32_t* pos, int ncols,
+                                       double* out, const int32_t* inv, hipStream_t st);
 // The solver's own operator copy for wide blocks (b = 8, 16, 32) holds S_ij = s_i W_ij s_j multiplied out:
 // val_out[e] = s_i * val[e] * s_j (val_out may be val).
 hipError_t launch_scale_values(const int64_t* rowptr, const int32_t* col, const double* val, const double* s,

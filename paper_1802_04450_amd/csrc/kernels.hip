@@ -997,28 +997,32 @@ __global__ __launch_bounds__(kThreads) void copy_cols_kernel(const double* __res
   dst[i * ldd + dcol0 + t] = src[i * lds + scol0 + t];
 }
 
-// out[t * n + o] = basis[r(o) * ld + perm[t]] for t < k: selected columns of the row-major basis, written column-major
-// in the caller's row numbering (r(o) = inv[o], the internal row of original row o, if inv is given, else o).  A
-// workgroup moves a 64 x 64 tile through LDS: the reads run along basis rows (whole 512-byte pieces of the rows the
-// permutation points to), the writes along output columns over consecutive addresses.
+// out[pos[c] * n + o] = basis[r(o) * ld + c] for the basis columns c < ncols with pos[c] >= 0: selected columns of the
+// row-major basis, written column-major in the caller's row numbering (r(o) = inv[o], the internal row of original
+// row o, if inv is given, else o).  A workgroup moves a 64 x 64 tile through LDS: the reads take 512 contiguous bytes
+// of each basis row (consecutive basis columns), the writes 512 contiguous bytes of each output column (consecutive
+// original rows); only whole rows and whole columns are permuted, never single elements.
 __global__ __launch_bounds__(kThreads) void gather_cols_colmajor_kernel(const double* __restrict__ basis, int64_t n,
-                                                                        int64_t ld, const int32_t* __restrict__ perm,
-                                                                        int k, double* __restrict__ out,
+                                                                        int64_t ld, const int32_t* __restrict__ pos,
+                                                                        int ncols, double* __restrict__ out,
                                                                         const int32_t* __restrict__ inv) {
   __shared__ double tile[64][65];
   const int64_t i0 = (int64_t)blockIdx.x * 64;
   const int c0 = blockIdx.y * 64;
   for (int idx = threadIdx.x; idx < 64 * 64; idx += kThreads) {
     const int r = idx / 64, c = idx % 64;
-    if (i0 + r < n && c0 + c < k) {
+    if (i0 + r < n && c0 + c < ncols) {
       const int64_t src = inv ? (int64_t)inv[i0 + r] : i0 + r;
-      tile[c][r] = basis[src * ld + perm[c0 + c]];
+      tile[c][r] = basis[src * ld + c0 + c];
     }
   }
   __syncthreads();
   for (int idx = threadIdx.x; idx < 64 * 64; idx += kThreads) {
     const int c = idx / 64, r = idx % 64;
-    if (i0 + r < n && c0 + c < k) out[(int64_t)(c0 + c) * n + i0 + r] = tile[c][r];
+    if (i0 + r < n && c0 + c < ncols) {
+      const int p = pos[c0 + c];
+      if (p >= 0) out[(int64_t)p * n + i0 + r] = tile[c][r];
+    }
   }
 }
 
@@ -1742,11 +1746,11 @@ hipError_t launch_copy_cols(const double* src, int64_t lds, int scol0, double* d
   return hipGetLastError();
 }
 
-hipError_t launch_gather_cols_colmajor(const double* basis, int64_t n, int64_t ld, const int32_t* perm, int k, double* out,
-                                       const int32_t* inv, hipStream_t st) {
-  if (n <= 0 || k <= 0) return hipSuccess;
-  hipLaunchKernelGGL(gather_cols_colmajor_kernel, dim3((unsigned)ceil_div64(n, 64), (unsigned)((k + 63) / 64)),
-                     dim3(kThreads), 0, st, basis, n, ld, perm, k, out, inv);
+hipError_t launch_gather_cols_colmajor(const double* basis, int64_t n, int64_t ld, const int32_t* pos, int ncols,
+                                       double* out, const int32_t* inv, hipStream_t st) {
+  if (n <= 0 || ncols <= 0) return hipSuccess;
+  hipLaunchKernelGGL(gather_cols_colmajor_kernel, dim3((unsigned)ceil_div64(n, 64), (unsigned)((ncols + 63) / 64)),
+                     dim3(kThreads), 0, st, basis, n, ld, pos, ncols, out, inv);
   return hipGetLastError();
 }
 
