@@ -733,6 +733,7 @@ __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (d4){0.0, 0.0, 0.0, 0.0};
+  d4 a0[2][MT], a1[2][MT];  // operand registers of the pipelined path: a0 carries over from chunk to chunk
 
   for (int k0 = 0; k0 < kdim; k0 += KC) {
     const int kc = (kdim - k0) < KC ? (kdim - k0) : KC;
@@ -752,14 +753,14 @@ __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__
     // next trip are requested before the MFMAs of this one (the last request repeats the last trip's and is dropped);
     // columns past kdim are read from the last four instead: their B rows in LDS are zero (or skipped).
     if (PIPE && vec_ok && row0 + 16 * MT <= n && kdim % 4 == 0) {  // wave-uniform
-      const int klast = (kc16 - 1) / 32 * 32;  // start of the chunk's last trip
       const double* __restrict__ abase = basis + (row0 + i) * ld + acol0;
-      d4 a0[2][MT], a1[2][MT];
+      // The request that follows a chunk's last trip is the first trip of the NEXT chunk (columns are clamped to the
+      // contraction's end, not to the chunk's): it is in flight while the workgroup restages the coefficient chunk
+      // behind two barriers, so the stream of operand loads no longer drains at every chunk boundary.
       auto fetch = [&](d4 (&av)[2][MT], int kb) __attribute__((always_inline)) {
-        const int kq = kb < klast ? kb : klast;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-          int kcol = k0 + kq + 16 * h + 4 * g;
+          int kcol = k0 + kb + 16 * h + 4 * g;
           kcol = kcol + 3 < kdim ? kcol : kdim - 4;
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt)
@@ -782,7 +783,7 @@ __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__
           }
         }
       };
-      fetch(a0, 0);
+      if (k0 == 0) fetch(a0, 0);  // later chunks find their first trip requested by the chunk before
       for (int kb = 0; kb < kc16; kb += 64) {
         fetch(a1, kb + 32);
         mult(a0, kb);
