@@ -339,6 +339,8 @@ int pow2_floor(int x) {
 // most of the block's norm away, get the second pass.
 // slot_a (may be null) receives rows [slot_row0, j) of hsum.  If gpart != null the second update also leaves
 // the Gram partials of the updated block there; returns their count (0 if none were produced).
+constexpr int kWideUpdate = 256;  // contraction lengths from which update + separate Gram beats the fused kernel
+
 int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, int second_from, double* part,
                  double* h1, double* hsum, double* slot_a, int slot_row0, double* gpart, hipStream_t st, KTimer* tm) {
   if (j <= 0) return 0;
@@ -364,7 +366,14 @@ int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, i
     tm->end(kFamOther, 8.0 * plan.npart * (double)jc * b, 0.0);
     tm->begin(kFamUpdate);
     const bool last_pass = pass == 1 || j - second_from <= 0;  // the last update leaves the Gram partials
-    if (last_pass && gpart) {
+    if (last_pass && gpart && jc >= kWideUpdate) {
+      // against many columns the plain update is the faster kernel (more waves in flight: at n = 500,000 and 1,024
+      // columns 995 against 1,300 us), and the Gram partials of the updated block cost one pass over the block alone
+      HIP_TRY(launch_row_gemm(basis, n, ld, c0, jc, h1, kPP, b, 0, wcol, nullptr, 0, nullptr, st));
+      const ProjectPlan gplan = plan_project(n, b, kMaxPartials);
+      HIP_TRY(launch_project(basis, n, ld, wcol, b, wcol, b, gplan, gpart, st));
+      ngram = gplan.npart;
+    } else if (last_pass && gpart) {
       HIP_TRY(launch_update_gram(basis, n, ld, c0, jc, h1, b, wcol, 0, gpart, st));
       ngram = plan_update_gram(n);
     } else {
@@ -388,7 +397,9 @@ int enqueue_cgs_adaptive(double* basis, int64_t n, int64_t ld, int j, int wcol, 
   if (!tm) tm = &none;
   const double rows = (double)n;
   const ProjectPlan plan = plan_project(n, j, kMaxPartials);
-  const int ngram = plan_update_gram(n);
+  const ProjectPlan gplan = plan_project(n, b, kMaxPartials);
+  const bool wide = j >= kWideUpdate;
+  const int ngram = wide ? gplan.npart : plan_update_gram(n);
   for (int pass = 0; pass < 2; ++pass) {
     const int* sk = pass == 0 ? nullptr : skip;
     // the second pass's traffic is not counted: whether it ran is known on the device only
@@ -400,7 +411,12 @@ int enqueue_cgs_adaptive(double* basis, int64_t n, int64_t ld, int j, int wcol, 
     HIP_TRY(launch_reduce_partials(part, plan.npart, j, b, h1, hsum, pass, nullptr, 0, st, sk));
     tm->end(kFamOther, counted * 8.0 * plan.npart * (double)j * b, 0.0);
     tm->begin(kFamUpdate);
-    HIP_TRY(launch_update_gram(basis, n, ld, 0, j, h1, b, wcol, 0, gpart, st, sk));
+    if (wide) {  // see enqueue_cgs2
+      HIP_TRY(launch_row_gemm(basis, n, ld, 0, j, h1, kPP, b, 0, wcol, nullptr, 0, nullptr, st, sk));
+      HIP_TRY(launch_project(basis, n, ld, wcol, b, wcol, b, gplan, gpart, st, sk));
+    } else {
+      HIP_TRY(launch_update_gram(basis, n, ld, 0, j, h1, b, wcol, 0, gpart, st, sk));
+    }
     tm->end(kFamUpdate, counted * 8.0 * rows * (j + 2 * b), counted * 2.0 * rows * j * b);
     if (pass == 0) {
       HIP_TRY(launch_reduce_partials(gpart, ngram, b, b, gram_tmp, nullptr, 0, nullptr, 0, st));

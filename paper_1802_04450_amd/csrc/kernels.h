@@ -71,7 +71,7 @@ hipError_t launch_second_pass_test(const double* h, int ja, int b, const double*
 // mode 2: out[t*ldo + r(i)] = C[i, t]             (column-major; r(i) = rowmap[i] if rowmap != null, else i)
 hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int ldb,
                            int ncols, int mode, int ccol0, double* out, int64_t ldo, const int32_t* rowmap,
-                           hipStream_t st);
+                           hipStream_t st, const int* skip = nullptr);
 
 // ---- block orthonormalization --------------------------------------------------------------
 // One Cholesky-QR pass bookkeeping on the Gram matrix g_in (b x b, stride kPartialPad; single workgroup):

@@ -720,7 +720,9 @@ __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__
                                                             int acol0, int kdim, const double* __restrict__ bmat,
                                                             int ldb, int ncols, int mode, int ccol0,
                                                             double* __restrict__ out, int64_t ldo, int vec_ok,
-                                                            const int32_t* __restrict__ rowmap) {
+                                                            const int32_t* __restrict__ rowmap,
+                                                            const int* __restrict__ skip) {
+  if (skip && *skip) return;  // uniform over the grid
   constexpr int KC = 4096 / (NT * 16);  // contraction indices per LDS chunk (32 KB)
   __shared__ double lds[KC * NT * 16];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -1609,7 +1611,7 @@ hipError_t launch_reduce_partials(const double* part, int npart, int ja, int b, 
 
 hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int ldb,
                            int ncols, int mode, int ccol0, double* out, int64_t ldo, const int32_t* rowmap,
-                           hipStream_t st) {
+                           hipStream_t st, const int* skip) {
   if (kdim <= 0 || ncols <= 0) return hipSuccess;
   const int vec_ok = (ld % 4 == 0 && acol0 % 4 == 0 && (reinterpret_cast<uintptr_t>(basis) % 32 == 0)) ? 1 : 0;
   constexpr int MT = 2;
@@ -1617,7 +1619,7 @@ hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int 
   const bool pipe = kdim >= 128;  // loads one trip ahead pay from a few trips on
 #define SC_LAUNCH_RG(NTV, PV, GY)                                                                                  \
   hipLaunchKernelGGL((row_gemm_kernel<NTV, MT, PV>), dim3(gx, (GY)), dim3(kThreads), 0, st, basis, n, ld, acol0,   \
-                     kdim, bmat, ldb, ncols, mode, ccol0, out, ldo, vec_ok, rowmap)
+                     kdim, bmat, ldb, ncols, mode, ccol0, out, ldo, vec_ok, rowmap, skip)
   if (ncols <= 16) {
     if (pipe) SC_LAUNCH_RG(1, true, 1); else SC_LAUNCH_RG(1, false, 1);
   } else if (ncols <= 32) {
