@@ -414,10 +414,12 @@ __global__ __launch_bounds__(kThreads) void spmv_tile_kernel(const int64_t* __re
   int64_t r = row0 + lane;
   r = r < n ? r : n;  // rows past the end are empty: their pointers equal rowptr[n]
   const int64_t rpv = lane <= RW ? rowptr[r] : 0;
-  const double sv = (lane < RW && row0 + lane < n) ? (s ? s[row0 + lane] : 1.0) : 0.0;  // s == null: values are S
   const int64_t e0 = readlane64(rpv, 0);
   const int len = (int)(readlane64(rpv, RW) - e0);
   const bool mine = sl == 0 && row0 + g < n;
+  // the row's scaling factor, requested now by the lane that writes the row and needed only at the very end
+  // (s == null: the values are S already)
+  const double sg = (mine && s) ? s[row0 + g] : 1.0;
   if (len <= 0) {
     if (mine) {
       y[(row0 + g) * ldy] = 0.0;
@@ -438,7 +440,6 @@ __global__ __launch_bounds__(kThreads) void spmv_tile_kernel(const int64_t* __re
   }
   const int rel = (int)(rpv - e0);
   const int rlo = __shfl(rel, g), rhi = __shfl(rel, g + 1);
-  const double sg = __shfl(sv, g);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const double zz = *reinterpret_cast<const double*>(reinterpret_cast<const char*>(z) + ((uint64_t)(uint32_t)c[u] << 3));
@@ -929,6 +930,7 @@ __global__ __launch_bounds__(kCholThreads) void gram_cholesky_kernel(const doubl
   }
 }
 
+constexpr int kRinvTrips = 16;  // row groups per workgroup: the staging of R^-1 is paid once for all of them
 __global__ __launch_bounds__(kThreads) void apply_rinv_kernel(double* __restrict__ basis, int64_t n, int64_t ld,
                                                               int col0, int b, const double* __restrict__ rinv,
                                                               double* __restrict__ z, const double* __restrict__ s) {
@@ -937,14 +939,17 @@ __global__ __launch_bounds__(kThreads) void apply_rinv_kernel(double* __restrict
   for (int e = threadIdx.x; e < b * b; e += kThreads) Ri[e / b][e % b] = rinv[(e / b) * kPartialPad + (e % b)];
   const int rows_per_block = kThreads / b;
   const int t = threadIdx.x % b, rl = threadIdx.x / b;
-  const int64_t row = (int64_t)blockIdx.x * rows_per_block + rl;
-  Wt[rl * (b + 1) + t] = row < n ? basis[row * ld + col0 + t] : 0.0;
-  __syncthreads();
-  double acc = 0.0;
-  for (int q = 0; q <= t; ++q) acc += Wt[rl * (b + 1) + q] * Ri[q][t];
-  if (row < n) {
-    basis[row * ld + col0 + t] = acc;
-    if (z) z[row * b + t] = s ? s[row] * acc : acc;
+  for (int trip = 0; trip < kRinvTrips; ++trip) {
+    const int64_t row = ((int64_t)blockIdx.x * kRinvTrips + trip) * rows_per_block + rl;
+    __syncthreads();  // the tile of the trip before has been read (and, first time round, R^-1 is staged)
+    Wt[rl * (b + 1) + t] = row < n ? basis[row * ld + col0 + t] : 0.0;
+    __syncthreads();
+    double acc = 0.0;
+    for (int q = 0; q <= t; ++q) acc += Wt[rl * (b + 1) + q] * Ri[q][t];
+    if (row < n) {
+      basis[row * ld + col0 + t] = acc;
+      if (z) z[row * b + t] = s ? s[row] * acc : acc;
+    }
   }
 }
 
@@ -1657,16 +1662,17 @@ hipError_t launch_gram_cholesky(const double* g_in, int b, double* g_out, double
 // removed_t = sum_c h[c][t]^2 of its squared norm to the first pass and kept gram[t][t]; the first pass leaves an
 // orthogonality error of about eps * sqrt(1 + removed / kept), which a second pass is needed for only when
 // removed > ratio2 * kept.  One workgroup; fixed summation order.
-__global__ __launch_bounds__(kThreads) void second_pass_test_kernel(const double* __restrict__ h, int ja, int b,
-                                                                    const double* __restrict__ gram, double ratio2,
-                                                                    int* __restrict__ skip) {
-  __shared__ double sub[kThreads];
+constexpr int kTestThreads = 1024;  // 32 row classes per column: the coefficient block has up to m rows
+__global__ __launch_bounds__(kTestThreads) void second_pass_test_kernel(const double* __restrict__ h, int ja, int b,
+                                                                        const double* __restrict__ gram, double ratio2,
+                                                                        int* __restrict__ skip) {
+  __shared__ double sub[kTestThreads];
   __shared__ int need;
   if (threadIdx.x == 0) need = 0;
-  const int t = threadIdx.x % kPartialPad, r = threadIdx.x / kPartialPad;  // 8 row classes per column
+  const int t = threadIdx.x % kPartialPad, r = threadIdx.x / kPartialPad;
   double acc = 0.0;
   if (t < b)
-    for (int c = r; c < ja; c += kThreads / kPartialPad) {
+    for (int c = r; c < ja; c += kTestThreads / kPartialPad) {
       const double v = h[(int64_t)c * kPartialPad + t];
       acc += v * v;
     }
@@ -1675,7 +1681,7 @@ __global__ __launch_bounds__(kThreads) void second_pass_test_kernel(const double
   if (r == 0 && t < b) {
     double removed = 0.0;
 #pragma unroll
-    for (int q = 0; q < kThreads / kPartialPad; ++q) removed += sub[q * kPartialPad + t];
+    for (int q = 0; q < kTestThreads / kPartialPad; ++q) removed += sub[q * kPartialPad + t];
     const double kept = gram[t * kPartialPad + t];
     if (removed > ratio2 * kept) atomicOr(&need, 1);
   }
@@ -1685,7 +1691,7 @@ __global__ __launch_bounds__(kThreads) void second_pass_test_kernel(const double
 
 hipError_t launch_second_pass_test(const double* h, int ja, int b, const double* gram, double ratio2, int* skip,
                                    hipStream_t st) {
-  hipLaunchKernelGGL(second_pass_test_kernel, dim3(1), dim3(kThreads), 0, st, h, ja, b, gram, ratio2, skip);
+  hipLaunchKernelGGL(second_pass_test_kernel, dim3(1), dim3(kTestThreads), 0, st, h, ja, b, gram, ratio2, skip);
   return hipGetLastError();
 }
 
@@ -1713,8 +1719,8 @@ hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, i
 
 hipError_t launch_apply_rinv(double* basis, int64_t n, int64_t ld, int col0, int b, const double* rinv, double* z,
                              const double* s, hipStream_t st) {
-  hipLaunchKernelGGL(apply_rinv_kernel, dim3((unsigned)ceil_div64(n, kThreads / b)), dim3(kThreads), 0, st, basis, n,
-                     ld, col0, b, rinv, z, s);
+  hipLaunchKernelGGL(apply_rinv_kernel, dim3((unsigned)ceil_div64(n, (int64_t)(kThreads / b) * kRinvTrips)),
+                     dim3(kThreads), 0, st, basis, n, ld, col0, b, rinv, z, s);
   return hipGetLastError();
 }
 
