@@ -339,10 +339,12 @@ int pow2_floor(int x) {
 // most of the block's norm away, get the second pass.
 // slot_a (may be null) receives rows [slot_row0, j) of hsum.  If gpart != null the second update also leaves
 // the Gram partials of the updated block there; returns their count (0 if none were produced).
+// first_from > 0: the first pass too leaves the columns before it alone (the solver's tentative first step).
 constexpr int kWideUpdate = 256;  // contraction lengths from which update + separate Gram beats the fused kernel
 
 int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, int second_from, double* part,
-                 double* h1, double* hsum, double* slot_a, int slot_row0, double* gpart, hipStream_t st, KTimer* tm) {
+                 double* h1, double* hsum, double* slot_a, int slot_row0, double* gpart, hipStream_t st, KTimer* tm,
+                 int first_from = 0) {
   if (j <= 0) return 0;
   KTimer none;
   if (!tm) tm = &none;
@@ -351,7 +353,7 @@ int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, i
   const double rows = (double)n;
   int ngram = 0;
   for (int pass = 0; pass < 2; ++pass) {
-    const int c0 = pass == 0 ? 0 : second_from;  // first basis column of this pass
+    const int c0 = pass == 0 ? first_from : second_from;  // first basis column of this pass
     const int jc = j - c0;
     if (jc <= 0) {  // nothing to do in this pass: the Gram partials then come from the block QR itself
       continue;
@@ -674,6 +676,7 @@ struct Solver {
   uint64_t seed;
   const double* v0 = nullptr;  // caller's start vector (caller's numbering), or null
   bool no_late_projection = std::getenv("SCEIG_NO_LATE_PROJECTION") != nullptr;
+  bool no_tentative_step = std::getenv("SCEIG_NO_TENTATIVE_STEP") != nullptr;
   size_t ws_limit = 0;         // > 0: size of the caller's workspace, checked against the estimate once nnz is known
   hipStream_t st;
   // device
@@ -876,13 +879,21 @@ struct Solver {
   }
 
   // ---- one block step on the last active block (columns [nl+ja-b, nl+ja)), results into slot si
-  void enqueue_step(int ja, int si) {
+  // tentative: the new block is orthogonalized against the active Krylov columns only, not against the locked
+  // vectors.  Its residual estimates then still contain what the product holds along the locked vectors, so they
+  // are upper bounds of the proper ones: pairs that pass the test with them are converged, and the Ritz vectors
+  // (combinations of the active columns, which are orthogonal to the locked vectors) are unaffected.  The first
+  // step after a filtered start block is taken this way - most phases end with it, and the pass over all locked
+  // vectors, the most expensive thing a step does once many are locked, is never made for them; if the test fails
+  // the step is taken again in full.
+  void enqueue_step(int ja, int si, bool tentative = false) {
     const int jt = nl + ja;
     timer.begin(kFamSpmm);
     spmm_from_z(basis.p + jt, ld);
     timer.end(kFamSpmm, spmm_bytes(), 2.0 * (double)nnz * b);
     double* sl = slot(si);
-    const int ngram = enqueue_cgs2(basis.p, n, ld, jt, jt, b, nl, part.p, h1.p, hsum.p, sl, jt - b, gpart.p, st, &timer);
+    const int ngram = enqueue_cgs2(basis.p, n, ld, jt, jt, b, nl, part.p, h1.p, hsum.p, sl, jt - b, gpart.p, st, &timer,
+                                   tentative ? nl : 0);
     enqueue_block_qr(basis.p, n, ld, jt, b, part.p, gpart.p, ngram, gram(), rinv(), r1(), sl + kPP * kPP,
                      sl + 2 * kPP * kPP, z.p, zs(), st, &timer);
     stats.block_steps += 1;
@@ -1097,9 +1108,12 @@ struct Solver {
         return next;
       };
 
+      bool tentative_allowed = filtered && nl > 0 && !last_cycle_phase && !no_tentative_step;
       while (!phase_over) {
         if (next_slot >= max_slots) SC_THROW(SC_EDOMAIN);  // cannot happen: a cycle has at most m/b steps
-        enqueue_step(ja, next_slot);
+        // the phase's first step, inspected right after it, with room for its block in the basis
+        const bool tentative = tentative_allowed && steps_in_phase == 0 && ja == b && next_check <= 1 && ja + b <= cap;
+        enqueue_step(ja, next_slot, tentative);
         ++next_slot;
         ++pending;
         ++steps_in_phase;
@@ -1194,6 +1208,25 @@ struct Solver {
                        theta[ja - 1], rho[0], wi >= 0 ? theta[ja - 1 - wi] : 0.0, wi >= 0 ? rho[wi] : 0.0);
         }
 
+        if (tentative && !(lead >= want || exhausted)) {
+          // the upper bounds did not pass: the step again, this time with the projection against the locked vectors
+          if (debug_on())
+            std::fprintf(stderr, "[sceig] t=%.4fs phase %d first step repeated in full\n", now_s() - t_begin, stats.phases);
+          HIP_TRY(launch_pack_scaled(basis.p + nl, ld, zs(), n, b, z.p, st));  // the product's operand: the start block
+          tentative_allowed = false;
+          ja = b;
+          assembled = 0;
+          next_slot = 1;
+          fetched = 1;  // slot 0 (the start block's QR) is on the host already
+          pending = 0;
+          steps_in_phase = 0;
+          std::fill(T.begin(), T.end(), 0.0);
+          std::fill(ghost.begin() + b, ghost.end(), 0);
+          next_check = 1;
+          last_rho = -1.0;
+          last_rho_step = 0;
+          continue;
+        }
         if (nreal == 0) {  // the deflated space is empty: nothing more exists
           finished = true;
           if (nl < k) not_converged = true;
