@@ -677,6 +677,7 @@ struct Solver {
   const double* v0 = nullptr;  // caller's start vector (caller's numbering), or null
   bool no_late_projection = std::getenv("SCEIG_NO_LATE_PROJECTION") != nullptr;
   bool no_tentative_step = std::getenv("SCEIG_NO_TENTATIVE_STEP") != nullptr;
+  double tentative_min_work = std::getenv("SCEIG_TENTATIVE_MIN_WORK") ? std::atof(std::getenv("SCEIG_TENTATIVE_MIN_WORK")) : 2e7;
   size_t ws_limit = 0;         // > 0: size of the caller's workspace, checked against the estimate once nnz is known
   hipStream_t st;
   // device
@@ -894,8 +895,18 @@ struct Solver {
     double* sl = slot(si);
     const int ngram = enqueue_cgs2(basis.p, n, ld, jt, jt, b, nl, part.p, h1.p, hsum.p, sl, jt - b, gpart.p, st, &timer,
                                    tentative ? nl : 0);
-    enqueue_block_qr(basis.p, n, ld, jt, b, part.p, gpart.p, ngram, gram(), rinv(), r1(), sl + kPP * kPP,
-                     sl + 2 * kPP * kPP, z.p, zs(), st, &timer);
+    if (tentative && ngram > 0) {
+      // Only the Gram matrix of the residual block is looked at (residual estimates; a block that vanished): the
+      // block is not orthonormalized, since it either is dropped with the phase or built again.  The slot of the QR
+      // factor gets the Gram matrix too: its diagonal vanishes exactly when the factor's would.
+      timer.begin(kFamQr);
+      HIP_TRY(launch_reduce_partials(gpart.p, ngram, b, b, sl + 2 * kPP * kPP, nullptr, 0, nullptr, 0, st));
+      HIP_TRY(launch_reduce_partials(gpart.p, ngram, b, b, sl + kPP * kPP, nullptr, 0, nullptr, 0, st));
+      timer.end(kFamQr, 0.0, 0.0);
+    } else {
+      enqueue_block_qr(basis.p, n, ld, jt, b, part.p, gpart.p, ngram, gram(), rinv(), r1(), sl + kPP * kPP,
+                       sl + 2 * kPP * kPP, z.p, zs(), st, &timer);
+    }
     stats.block_steps += 1;
     stats.spmv_cols += b;
   }
@@ -930,7 +941,7 @@ struct Solver {
   // just locked and small below an estimate `a` of what follows: the largest unlocked Ritz value when a gap
   // separates it from the locked ones (it approaches the next distinct eigenvalue from below; the best such
   // estimate over the phases is kept, and reused when a phase has no unlocked Ritz value to offer), otherwise the
-  // (b+1)-th unlocked one, below the b values the next phase is after.
+  // larger of that kept estimate and the (b+1)-th unlocked one, below the b values the next phase is after.
   // locked = false: a phase that started unfiltered looks at its first Ritz values; nothing has converged, the
   // target is the largest Ritz value and `a` the kept estimate if there is one, else the (nlead+1)-th Ritz value.
   //
@@ -952,7 +963,7 @@ struct Solver {
         filt_best = std::max(filt_best, u1);
         a = filt_best;
       } else {
-        a = ub;
+        a = std::max(ub, filt_best);  // an estimate kept from a phase that did see a gap outranks a Ritz value far below it
       }
     } else if (!locked && filt_best <= -2.0 && nu >= 1) {
       a = theta[ja - 1 - nlead];
@@ -1108,7 +1119,10 @@ struct Solver {
         return next;
       };
 
-      bool tentative_allowed = filtered && nl > 0 && !last_cycle_phase && !no_tentative_step;
+      // worth it only where the pass over the locked vectors costs more than a repeated step does when the test
+      // fails (a product, two passes over the start block and its QR): from about 2e7 locked entries on
+      bool tentative_allowed = filtered && nl > 0 && !last_cycle_phase && !no_tentative_step &&
+                               (double)n * nl >= tentative_min_work;
       while (!phase_over) {
         if (next_slot >= max_slots) SC_THROW(SC_EDOMAIN);  // cannot happen: a cycle has at most m/b steps
         // the phase's first step, inspected right after it, with room for its block in the basis
