@@ -707,6 +707,9 @@ struct Solver {
   double filt_a = 0.0;
   double filt_best = -2.0;  // best lower estimate so far of the largest eigenvalue below the locked cluster
   double filt_ref = 2.0;    // the Ritz value the planned filter is made large at
+  double filt_rate = 0.0;   // growth exponent per degree of the planned filter at filt_ref
+  bool late_off = false;    // projecting the locked vectors out after the filter has stopped paying (see run())
+  int filt_extra = 0;       // degrees added to (or taken from) the planned degree: feedback from the phases' first steps
   sc_stats stats{};
   KTimer timer;
 
@@ -978,10 +981,11 @@ struct Solver {
     const double amp = std::min(1e12, std::max(1e6, 100.0 / std::max(tol, 1e-300)));
     const int dmax = 30;
     if (!(rate > 0.0) || std::cosh(dmax * rate) < 100.0) return;
-    const int d = (int)std::ceil(std::log(2.0 * amp) / rate);
+    const int d = (int)std::ceil(std::log(2.0 * amp) / rate) + filt_extra;
     filt_d = std::min(std::max(d, 2), dmax);
     filt_a = a;
     filt_ref = th_ref;
+    filt_rate = rate;
   }
 
   // out (n x l row-major in rot) = basis[:, nl : nl+ja] * Y[:, sel]; then copied to basis[:, dst : dst+l]
@@ -1056,6 +1060,8 @@ struct Solver {
       if (v0 && stats.phases == 1)  // the caller's start vector leads the first block, the other columns stay random
         HIP_TRY(launch_set_column(basis.p, n, ld, nl, v0, rowmap, st));
       bool filtered = filt_d > 0;
+      // exponent of the filter this phase starts from (0: none, or not a random block), for the degree feedback
+      double phase_rate = filtered ? filt_rate : 0.0;
       // The locked vectors' eigenvalues lie above the damped interval too, so the filter amplifies what a block holds
       // along them.  When none of them lies above the value the filter is aimed at (the usual case here: further
       // copies of one multiple eigenvalue), they are amplified no more than the wanted directions, the filtered block
@@ -1064,7 +1070,12 @@ struct Solver {
       // only if the device-side test asks for it - takes the place of a pass before and a pass after the filter.
       // Otherwise (locked eigenvalues above the target: they would swamp the block) the block is projected first.
       bool late_projection = false;
-      if (filtered && nl > 0 && !no_late_projection) {
+      // The price of projecting afterwards: the locked vectors x_i are eigenvectors only to within their residuals, so
+      // removing span(X) from the amplified block leaves, of what it held along the exact eigenvectors behind X, a
+      // part of relative size (angle between the two spans) * sqrt(locked / remaining directions), made of unwanted
+      // eigenvectors.  That floor under the first step's residuals grows as the wanted directions run out; once a
+      // phase sees it near tol (late_off) the later phases project before the filter again.
+      if (filtered && nl > 0 && !no_late_projection && !late_off) {
         const double top = *std::max_element(theta_locked.begin(), theta_locked.end());
         late_projection = top <= filt_ref + 1e-6;
       }
@@ -1123,6 +1134,13 @@ struct Solver {
       // fails (a product, two passes over the start block and its QR): from about 2e7 locked entries on
       bool tentative_allowed = filtered && nl > 0 && !last_cycle_phase && !no_tentative_step &&
                                (double)n * nl >= tentative_min_work;
+      // The floor under a late projection's residuals ends near sqrt(locked / remaining wanted directions) times the
+      // locked residuals.  The multiplicity of the eigenvalue 1 of S is the number of connected components, which the
+      // renumbering has counted: when k asks for (nearly) all of them the ratio gets large.  A hint for the degree
+      // feedback only.
+      const bool tight_target =
+          tentative_allowed && ncomp > 0 && (double)(k - b) > 4.0 * std::max(ncomp - (k - b), 1);
+      if (tentative_allowed) next_check = 1;  // a look after the cheap first step costs far less than a full second step
       while (!phase_over) {
         if (next_slot >= max_slots) SC_THROW(SC_EDOMAIN);  // cannot happen: a cycle has at most m/b steps
         // the phase's first step, inspected right after it, with room for its block in the basis
@@ -1213,6 +1231,28 @@ struct Solver {
         }
         int lead = 0;
         while (lead < nsel && rho[lead] <= tol) ++lead;
+        if (phase_rate > 0.0 && steps_in_phase == 1) {
+          // Degree feedback.  How much of a filtered random block lies along the wanted directions shrinks as fewer of
+          // them remain, so the same polynomial leaves relatively more of the rest: aim the first step's worst wanted
+          // residual estimate at a target by adding the degrees the miss is worth (or giving one back when the filter
+          // overshoots by more than a degree and a half).  The target is tol / 8, except where the floor described at
+          // the phase start would otherwise reach tol before the end: it is proportional to the residuals the vectors
+          // were locked with, so tol / 100 (two or three more degrees) keeps it down.  That is bought only where the
+          // passes over the locked vectors are what a phase costs (tight_target).
+          double rw = 0.0;
+          for (int t = 0; t < std::min(want, nsel); ++t) rw = std::max(rw, rho[t]);
+          if (rw > 0.0) {
+            const double target = (late_projection && tight_target ? 0.01 : 0.125) * tol;
+            const double need = std::log(rw / target) / phase_rate;
+            if (late_projection && rw > 0.5 * tol)
+              late_off = true;  // the floor, not the polynomial: more degrees would not help
+            else if (need > 1.0)
+              filt_extra = std::min(filt_extra + (int)std::ceil(need), 6);
+            else if (need < -1.5)
+              filt_extra = std::max(filt_extra - 1, -4);
+          }
+          phase_rate = 0.0;  // once per phase
+        }
         if (debug_on()) {
           const int wi = std::min(want, nsel) - 1;
           std::fprintf(stderr,
