@@ -465,6 +465,12 @@ struct ResidentPlan {
   size_t lds_bytes = 0;
   bool usable = false;
   double est_step_s = 0.0;  // modelled time of one recurrence step
+  int64_t rest_row0 = 0;    // rows [rest_row0, n): blocks that fit no item, left to the product-per-step kernel
+  // sliced copy of the blocks that are worked on in the sliced form (null if there are none)
+  DevBuf<uint16_t> scol;
+  DevBuf<double> sval;
+  DevBuf<int64_t> slice_base;
+  DevBuf<int32_t> slice_len;
 };
 
 int device_lds_limit() {
@@ -474,19 +480,22 @@ int device_lds_limit() {
   return lds;
 }
 
-// Finds the diagonal blocks and their chunk counts on the device, sizes the items on the host.  The plan is usable
-// when b is 16 or 32, every block fits LDS as items of 32 or 16 columns with at most two chunks per lane group, and
-// the modelled step time beats the general product's: an item costs its entries times 8 bs bytes read from LDS at
-// about half a compute unit's LDS rate, the items spread over the 256 compute units, largest first; the general
-// product gathers 8 b bytes per entry from the L2 caches at the 12.5 TB/s measured for it, and no launch is shorter
-// than about 4 us.
-void plan_resident(const int64_t* rowptr, const int32_t* col, int64_t n, int64_t nnz, int b, hipStream_t st,
-                   ResidentPlan* plan) {
+// Finds the diagonal blocks and their chunk counts on the device, sizes the items on the host.  A block goes, in this
+// order of preference, as items of 32 or 16 columns with its entries in registers (at most two chunks per lane
+// group), or as 8-column items in the sliced form (entries streamed from a sliced copy made here from `val`).  The
+// plan is usable when b is 16 or 32, every block fits LDS one way or the other, the sliced copy's padding stays below
+// a half, and the modelled step time beats the general product's: an item costs the LDS bytes its step reads (entries
+// times 8 bytes per column; the sliced form's streamed entries are charged as 48 more bytes each) at about half a
+// compute unit's LDS rate, the items spread over the 256 compute units, largest first; the general product gathers
+// 8 b bytes per entry from the L2 caches at the 12.5 TB/s measured for it, and no launch is shorter than about 4 us.
+void plan_resident(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n, int64_t nnz, int b,
+                   hipStream_t st, ResidentPlan* plan) {
   plan->usable = false;
   plan->nitems = 0;
   if ((b != 16 && b != 32) || n <= 0 || nnz <= 0 || std::getenv("SCEIG_NO_RESIDENT")) return;
   const int lds_limit = device_lds_limit() - 1024;
   if (lds_limit < 32 * 1024) return;
+  const bool no_sliced = std::getenv("SCEIG_NO_SLICED") != nullptr;
   DevBuf<char> work;
   DevBuf<int32_t> starts, count, extra;
   const size_t wb = diagonal_blocks_workspace(n);
@@ -497,8 +506,7 @@ void plan_resident(const int64_t* rowptr, const int32_t* col, int64_t n, int64_t
   int32_t nblk = 0;
   HIP_TRY(hipMemcpyAsync(&nblk, count.p, sizeof(int32_t), hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
-  // at most 640 rows fit an item, so a usable plan has at least n / 640 blocks; and its item table stays small
-  if (nblk <= 0 || (int64_t)nblk * 640 < n || (int64_t)nblk > (int64_t)1 << 22) return;
+  if (nblk <= 0 || (int64_t)nblk > (int64_t)1 << 22) return;  // the item table stays small
   extra.alloc((size_t)2 * nblk);
   HIP_TRY(launch_block_extra_chunks(rowptr, starts.p, nblk, n, extra.p, st));
   std::vector<int32_t> hs((size_t)nblk + 1), hx((size_t)2 * nblk);
@@ -510,9 +518,13 @@ void plan_resident(const int64_t* rowptr, const int32_t* col, int64_t n, int64_t
     int32_t row0, nrows, col0, shape;
   };
   std::vector<Item> items;
+  std::vector<int32_t> srow0, srows, sblk0, sblkrows;  // the slices of the blocks that go in the sliced form
+  std::vector<int> sliced_blocks;
+  const int srows_max = resident_slice_rows();
   size_t lds_max = 0;
   const double avg_deg = (double)nnz / (double)n;
   double sum_cost = 0.0, max_cost = 0.0;
+  int64_t rest_row0 = n;
   for (int t = 0; t < nblk; ++t) {
     const int nr = hs[t + 1] - hs[t];
     int cl = 0, nx = 0;
@@ -524,23 +536,92 @@ void plan_resident(const int64_t* rowptr, const int32_t* col, int64_t n, int64_t
       nx = x;
       break;
     }
-    if (cl == 0) return;  // a block too large for LDS or for the lane groups: the general product does the whole filter
+    if (cl == 0 && (no_sliced || nr > 65535 || resident_sliced_lds_bytes(nr) > (size_t)lds_limit)) {
+      // fits no item: acceptable only as part of a run of such blocks at the end of the matrix (the solver's
+      // renumbering puts the large components there), which the product-per-step kernel then takes
+      if (rest_row0 == n) rest_row0 = hs[t];
+      continue;
+    }
+    if (rest_row0 < n) return;  // an item after a block without one: the blocks without items are not a suffix
+    if (cl == 0) {
+      // the sliced form: column indices inside the block take 16 bits, the item's first slice 27
+      if (srow0.size() + (size_t)nr / srows_max + 1 >= ((size_t)1 << 27)) return;
+      cl = 1;
+      nx = (int)srow0.size();
+      for (int r = 0; r < nr; r += srows_max) {
+        srow0.push_back(hs[t] + r);
+        srows.push_back(std::min(srows_max, nr - r));
+        sblk0.push_back(hs[t]);
+        sblkrows.push_back(nr);
+      }
+      sliced_blocks.push_back(t);
+    }
     const int bs = 8 * cl;
-    const double cost = (double)nr * avg_deg * 8.0 * bs;
+    const double cost = (double)nr * avg_deg * (8.0 * bs + (cl == 1 ? 48.0 : 0.0));
     for (int c0 = 0; c0 < b; c0 += bs) {
       items.push_back(Item{hs[t], nr, c0, (int32_t)(cl | (nx << 4))});
       sum_cost += cost;
     }
     max_cost = std::max(max_cost, cost);
-    lds_max = std::max(lds_max, resident_item_lds_bytes(nr, cl, nx));
+    lds_max = std::max(lds_max, cl == 1 ? resident_sliced_lds_bytes(nr) : resident_item_lds_bytes(nr, cl, nx));
   }
   const double cu_rate = 150e9;  // bytes per second out of one compute unit's LDS, about half of its peak
-  plan->est_step_s = std::max(max_cost, sum_cost / 256.0) / cu_rate + 1e-6;
+  if (items.empty()) return;
   const double general_step_s = std::max(4e-6, (double)nnz * 8.0 * b / 12.5e12);
+  // the rows without items still take the general product, step by step, after the one launch of the items
+  const double rest_share = (double)(n - rest_row0) / (double)n;
+  plan->est_step_s = std::max(max_cost, sum_cost / 256.0) / cu_rate + 1e-6 +
+                     (rest_share > 0.0 ? std::max(4e-6, rest_share * general_step_s) : 0.0);
   if (debug_on())
-    std::fprintf(stderr, "[sceig] resident filter plan: %d blocks, %zu items, LDS %zu, modelled step %.1f us against %.1f us\n",
-                 nblk, items.size(), lds_max, plan->est_step_s * 1e6, general_step_s * 1e6);
+    std::fprintf(stderr, "[sceig] resident filter plan: %d blocks (%zu sliced), %zu items, LDS %zu, modelled step %.1f us "
+                 "against %.1f us\n", nblk, sliced_blocks.size(), items.size(), lds_max, plan->est_step_s * 1e6,
+                 general_step_s * 1e6);
   if (!(plan->est_step_s < general_step_s) && !std::getenv("SCEIG_FORCE_RESIDENT")) return;
+  const int nslices = (int)srow0.size();
+  if (nslices > 0) {
+    DevBuf<int32_t> d_row0, d_rows, d_blk0, d_blkrows;
+    DevBuf<int64_t> d_entries;
+    DevBuf<char> swork;
+    d_row0.alloc((size_t)nslices);
+    d_rows.alloc((size_t)nslices);
+    d_blk0.alloc((size_t)nslices);
+    d_blkrows.alloc((size_t)nslices);
+    d_entries.alloc((size_t)nslices + 1);
+    plan->slice_base.alloc((size_t)nslices + 1);
+    plan->slice_len.alloc((size_t)nslices);
+    const size_t sw = sliced_scan_workspace(nslices);
+    swork.alloc(sw);
+    const size_t ib = (size_t)nslices * sizeof(int32_t);
+    HIP_TRY(hipMemcpyAsync(d_row0.p, srow0.data(), ib, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(d_rows.p, srows.data(), ib, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(d_blk0.p, sblk0.data(), ib, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(d_blkrows.p, sblkrows.data(), ib, hipMemcpyHostToDevice, st));
+    HIP_TRY(sliced_copy_layout(rowptr, d_row0.p, d_rows.p, nslices, plan->slice_len.p, d_entries.p, plan->slice_base.p,
+                               swork.p, sw, st));
+    int64_t total = 0;
+    HIP_TRY(hipMemcpyAsync(&total, plan->slice_base.p + nslices, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));  // also: the host vectors above have been read
+    // padding: against the sliced blocks' share of the matrix entries, estimated by their share of the rows
+    int64_t sliced_rows = 0;
+    for (int t : sliced_blocks) sliced_rows += hs[t + 1] - hs[t];
+    const double basis_entries = (double)nnz * (double)sliced_rows / (double)n;
+    if (debug_on())
+      std::fprintf(stderr, "[sceig] sliced copy: %d slices, %lld entries for %.0f of the matrix\n", nslices,
+                   (long long)total, basis_entries);
+    if ((double)total > 1.5 * basis_entries && !std::getenv("SCEIG_FORCE_RESIDENT")) {
+      plan->slice_base.release();
+      plan->slice_len.release();
+      return;
+    }
+    const size_t tail = (size_t)sliced_copy_tail_entries();
+    plan->scol.alloc((size_t)total + tail);
+    plan->sval.alloc((size_t)total + tail);
+    HIP_TRY(hipMemsetAsync(plan->scol.p + total, 0, tail * sizeof(uint16_t), st));
+    HIP_TRY(hipMemsetAsync(plan->sval.p + total, 0, tail * sizeof(double), st));
+    HIP_TRY(sliced_copy_fill(rowptr, col, val, d_row0.p, d_rows.p, d_blk0.p, d_blkrows.p, nslices, plan->slice_base.p,
+                             d_entries.p, plan->scol.p, plan->sval.p, st));
+    HIP_TRY(hipStreamSynchronize(st));  // the temporaries above are released on return
+  }
   std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& c) {
     return (int64_t)a.nrows * (a.shape & 15) > (int64_t)c.nrows * (c.shape & 15);
   });
@@ -549,6 +630,7 @@ void plan_resident(const int64_t* rowptr, const int32_t* col, int64_t n, int64_t
   HIP_TRY(hipStreamSynchronize(st));  // `items` is pageable host memory
   plan->nitems = (int)items.size();
   plan->lds_bytes = lds_max;
+  plan->rest_row0 = rest_row0;
   plan->usable = true;
 }
 
@@ -574,7 +656,27 @@ double* enqueue_cheb_filter(const int64_t* rowptr, const int32_t* col, const dou
     resident_launches.fetch_add(1, std::memory_order_relaxed);
     tm->begin(kFamSpmm);
     HIP_TRY(launch_cheb_resident(rowptr, col, val_scaled, z, buf1, b, d, 1.0 / e, 2.0 / e, c, resident->items.p,
-                                 resident->nitems, resident->lds_bytes, st));
+                                 resident->nitems, resident->lds_bytes, resident->scol.p, resident->sval.p,
+                                 resident->slice_base.p, resident->slice_len.p, st));
+    const int64_t r0 = resident->rest_row0;
+    if (r0 < n) {
+      // the blocks without an item: the recurrence step by step on their rows alone (their iterates rotate through the
+      // same three buffers, in rows the items do not touch), then into the result buffer
+      double* cur = z;
+      double* prev = buf2;
+      double* next = buf1;
+      for (int i = 0; i < d; ++i) {
+        HIP_TRY(launch_spmm_vals_cheb(rowptr, col, val_scaled, n, cur, b, prev, next, i == 0 ? 1.0 / e : 2.0 / e, c,
+                                      i == 0 ? 0.0 : 1.0, avg_deg, longrows, nlong, st, r0));
+        double* t = prev;
+        prev = cur;
+        cur = next;
+        next = t;
+      }
+      if (cur != buf1)
+        HIP_TRY(hipMemcpyAsync(buf1 + r0 * b, cur + r0 * b, (size_t)(n - r0) * b * sizeof(double),
+                               hipMemcpyDeviceToDevice, st));
+    }
     tm->end(kFamSpmm, d * bytes + (d - 1) * 8.0 * (double)n * b, d * 2.0 * (double)nnz * b, d);
     return buf1;
   }
@@ -617,7 +719,8 @@ constexpr int kGramPartials = 1024;
 // new row (host).  Returns the component count.
 int reorder_csr(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n, int64_t nnz,
                 int64_t* rowptr_out, int32_t* col_out, double* val_out, int32_t* old_of_new_out,
-                int32_t* new_of_old_out, std::vector<int32_t>* comp_of_new, int by_length, hipStream_t st) {
+                int32_t* new_of_old_out, std::vector<int32_t>* comp_of_new, int by_length, hipStream_t st,
+                int big_rows = 0) {
   DevBuf<int32_t> label, new_of_old_own;
   DevBuf<int> flag;
   label.alloc((size_t)n);
@@ -645,7 +748,7 @@ int reorder_csr(const int64_t* rowptr, const int32_t* col, const double* val, in
   const size_t work_bytes = order_by_component_workspace(n);
   work.alloc(work_bytes);
   comp_dev.alloc((size_t)n);
-  HIP_TRY(order_by_component(rowptr, col, label.p, n, by_length, work.p, work_bytes, old_of_new_out, new_of_old_dev,
+  HIP_TRY(order_by_component(rowptr, col, label.p, n, by_length, big_rows, work.p, work_bytes, old_of_new_out, new_of_old_dev,
                              rowptr_out, comp_dev.p, st));
   HIP_TRY(launch_permute_csr(rowptr, col, val, old_of_new_out, new_of_old_dev, rowptr_out, col_out, val_out, n, st));
   int32_t last_comp = 0;
@@ -739,8 +842,12 @@ struct Solver {
     val_p.alloc((size_t)nnz);
     old_of_new_d.alloc((size_t)n);
     new_of_old_d.alloc((size_t)n);
+    // components too large for any item of the LDS-resident filter go last, as one run of rows that the filter leaves
+    // to the product-per-step kernel (8-column items with two iterates: 128 bytes of LDS per row)
+    int big_rows = 0;
+    if ((b == 16 || b == 32) && !(flags & SC_FLAG_NO_START_FILTER)) big_rows = (device_lds_limit() - 1024) / 128;
     ncomp = reorder_csr(rowptr, col, val, n, nnz, rowptr_p.p, col_p.p, val_p.p, old_of_new_d.p, new_of_old_d.p,
-                        (flags & SC_FLAG_COMPONENT_NULLSPACE) ? &comp_host : nullptr, b >= 8 ? 1 : 0, st);
+                        (flags & SC_FLAG_COMPONENT_NULLSPACE) ? &comp_host : nullptr, b >= 8 ? 1 : 0, st, big_rows);
     rowptr = rowptr_p.p;
     col = col_p.p;
     val = val_p.p;
@@ -851,7 +958,7 @@ struct Solver {
       HIP_TRY(hipMemcpyAsync(&hcount, lcount.p, sizeof(int32_t), hipMemcpyDeviceToHost, st));
       HIP_TRY(hipStreamSynchronize(st));
       nlong = hcount;
-      if (!(flags & SC_FLAG_NO_START_FILTER)) plan_resident(rowptr, col, n, nnz, b, st, &resident);
+      if (!(flags & SC_FLAG_NO_START_FILTER)) plan_resident(rowptr, col, val_s.p, n, nnz, b, st, &resident);
     }
     const double t3 = now_s();
 
@@ -1935,7 +2042,8 @@ int sc_workspace_bytes(int64_t n, int64_t nnz, int32_t k, const sc_options* opt,
   total += up(N * 8);                       // scaling vector
   if (b >= 8) total += up(Z * 8) + up(N * 4) + up(long_row_list_workspace(n)) + 256;  // scaled values, long-row list
   if (b >= 8 && !(o.flags & SC_FLAG_NO_START_FILTER))  // diagonal-block search and the work items of the resident filter
-    total += up(diagonal_blocks_workspace(n)) + up(N * 4) + 256 + up(N * 8) + up(N * 18);
+    total += up(diagonal_blocks_workspace(n)) + up(N * 4) + 256 + up(N * 8) + up(N * 18) +
+             up(Z * 15 + N * 2) + up(Z * 3 + N / 4) + 5 * up(N / 8 + 64) + up(sliced_scan_workspace((int)std::min<int64_t>(n, INT32_MAX)));  // + sliced copy (at most 1.5 x the entries plus look-ahead rounds) and its slice tables
   total += up(N * ld * 8) + up(N * (size_t)b * 8) + up(N * rot_cols * 8);  // basis, packed block, rotation workspace
   total += up((size_t)kMaxPartials * jmax * kPP * 8) + up((size_t)kGramPartials * kPP * kPP * 8) + 2 * up(jmax * kPP * 8);
   total += up((size_t)(m / b + 4) * kSlotDoubles * 8) + up(jmax * std::max<size_t>(rot_cols, (size_t)k) * 8);
@@ -2309,7 +2417,7 @@ int sc_chebyshev_filter(const int64_t* csr_rowptr, const int32_t* csr_col, const
           nlong = hcount;
         }
         ResidentPlan resident;  // used when the matrix as given is block diagonal with blocks that fit LDS
-        if (wide) plan_resident(c->rp, c->c, c->n, nnz, c->b, c->st, &resident);
+        if (wide) plan_resident(c->rp, c->c, vals.p, c->n, nnz, c->b, c->st, &resident);
         const double* res = enqueue_cheb_filter(c->rp, c->c, c->v, wide ? vals.p : nullptr, s.p, c->n, nnz, c->b, c->d,
                                                 c->a, z.p, b1.p, b2.p, b3.p, (double)nnz / (double)c->n,
                                                 wide ? longrows.p : nullptr, nlong, &resident, c->st, nullptr);

@@ -116,9 +116,30 @@ hipError_t launch_block_extra_chunks(const int64_t* rowptr, const int32_t* start
 // workgroup, covering columns [col0, col0 + 8 cl); every (block, column) pair must be covered exactly once, extra must
 // be the block's extra-chunk count for chunks of 8 cl entries and nrows + extra <= resident_max_chunks(cl).
 // lds_bytes = the largest resident_item_lds_bytes over the items.  y must not alias x.
+// A sliced item (cl = 1; the word's upper bits carry the item's first slice, not a chunk count) covers 8 columns of a
+// block of up to 65,535 rows and reads its entries from the sliced copy (scol, sval, slice_base, slice_len; null when
+// no item is sliced).
 hipError_t launch_cheb_resident(const int64_t* rowptr, const int32_t* col, const double* val, const double* x, double* y,
                                 int b, int d, double alpha_first, double alpha_rest, double shift, const int32_t* items,
-                                int nitems, size_t lds_bytes, hipStream_t st);
+                                int nitems, size_t lds_bytes, const uint16_t* scol, const double* sval,
+                                const int64_t* slice_base, const int32_t* slice_len, hipStream_t st);
+// Sliced copy of diagonal blocks for the sliced form.  A slice is up to resident_slice_rows() consecutive rows of one
+// block: slice_row0 / slice_rows (device int32[nslices]) name its rows, slice_blk0 / slice_blk_rows its block.
+// sliced_copy_layout fills slice_len (longest row), slice_entries (int64[nslices + 1]: entries the slice takes in the
+// copy, padding included; last slot 0) and slice_base (int64[nslices + 1]: exclusive prefix sums; the last one is the
+// size of the copy).  sliced_copy_fill writes the copy: scol / sval with room for slice_base[nslices] +
+// sliced_copy_tail_entries() entries (the kernel's requests run that far past the last slice; initialise the tail).
+int resident_slice_rows();
+int64_t sliced_copy_tail_entries();
+size_t resident_sliced_lds_bytes(int nrows);
+size_t sliced_scan_workspace(int nslices);
+hipError_t sliced_copy_layout(const int64_t* rowptr, const int32_t* slice_row0, const int32_t* slice_rows, int nslices,
+                              int32_t* slice_len, int64_t* slice_entries, int64_t* slice_base, void* work,
+                              size_t work_bytes, hipStream_t st);
+hipError_t sliced_copy_fill(const int64_t* rowptr, const int32_t* col, const double* val, const int32_t* slice_row0,
+                            const int32_t* slice_rows, const int32_t* slice_blk0, const int32_t* slice_blk_rows,
+                            int nslices, const int64_t* slice_base, const int64_t* slice_entries, uint16_t* scol,
+                            double* sval, hipStream_t st);
 
 // ---- connected components and locality reordering (setup) --------------------------------------
 // Renumbering from the component labels (label[i] = smallest node index of i's component), on the device:
@@ -128,9 +149,10 @@ hipError_t launch_cheb_resident(const int64_t* rowptr, const int32_t* col, const
 // work: device scratch of order_by_component_workspace(n) bytes.  All outputs are device arrays; n <= INT32_MAX.
 size_t order_by_component_workspace(int64_t n);
 // by_length != 0: on a graph with hubs (longest row > 3 average rows) the rows of a component are ordered by decreasing
-// length first (for the wide sparse products), then by the min-hash levels.
+// length first (for the wide sparse products), then by the min-hash levels.  big_rows > 0: the components with more
+// nodes than that come after all the others (in the order of their smallest node among themselves).
 hipError_t order_by_component(const int64_t* rowptr, const int32_t* col, const int32_t* label, int64_t n, int by_length,
-                              void* work,
+                              int big_rows, void* work,
                               size_t work_bytes, int32_t* old_of_new, int32_t* new_of_old, int64_t* rowptr_new,
                               int32_t* comp_of_new, hipStream_t st);
 // list[0 .. *count) = the rows with more than kLongRow entries, ascending; list has room for n entries; count: device
@@ -178,11 +200,12 @@ hipError_t launch_spmm_vals(const int64_t* rowptr, const int32_t* col, const dou
                             int b, double* y, int64_t ldy, double avg_deg, const int32_t* longrows, int nlong,
                             hipStream_t st);
 // One Chebyshev recurrence step on packed blocks:  unext = alpha * (A ucur - shift * ucur) - beta * uprev
-// (uprev is not read when beta == 0; unext must not be ucur)
+// (uprev is not read when beta == 0; unext must not be ucur).  row_begin > 0: only the rows [row_begin, n) are computed
+// and written (the rows before it belong to a caller that computes them another way).
 hipError_t launch_spmm_vals_cheb(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n,
                                  const double* ucur, int b, const double* uprev, double* unext, double alpha,
                                  double shift, double beta, double avg_deg, const int32_t* longrows, int nlong,
-                                 hipStream_t st);
+                                 hipStream_t st, int64_t row_begin = 0);
 // out[t*n + o] *= s[r(o)], t < k (column-major vectors in the caller's numbering; s in the internal numbering)
 hipError_t launch_scale_rows_colmajor(double* out, int64_t n, int k, const double* s, const int32_t* inv, hipStream_t st);
 // every row of the n x k column-major matrix scaled to unit 2-norm (zero rows stay zero)

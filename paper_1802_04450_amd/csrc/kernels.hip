@@ -140,7 +140,8 @@ __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __re
                                                              int64_t ldy, int64_t n, int vec_store,
                                                              const double* __restrict__ uprev, double alpha,
                                                              double shift, double beta, int64_t ntiles,
-                                                             const int32_t* __restrict__ longrows, int nlong) {
+                                                             const int32_t* __restrict__ longrows, int nlong,
+                                                             int64_t row_begin) {
   constexpr int G = kThreads / L;  // lane groups per workgroup
   constexpr int CL = B / 2;        // lanes per entry
   static_assert(L % CL == 0, "batch must split evenly");
@@ -155,7 +156,7 @@ __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __re
   if (main_part) {
     // row tiles, handed to the XCDs in contiguous eighths (ntiles is a multiple of kXcds)
     const int64_t tile = (int64_t)(blockIdx.x % kXcds) * (ntiles / kXcds) + blockIdx.x / kXcds;
-    row = tile * G + gi;
+    row = row_begin + tile * G + gi;  // rows before row_begin are somebody else's (see launch_spmm_vals_cheb)
     if (row >= n) return;  // uniform over the L-lane group; this part has no workgroup barrier
     e_first = 0;
     e_step = L;
@@ -165,6 +166,7 @@ __global__ __launch_bounds__(kThreads) void spmm_cols_kernel(const int64_t* __re
     const int64_t li = (bl % kXcds) * per + bl / kXcds;
     if (li >= nlong) return;  // uniform over the workgroup
     row = longrows[li];
+    if (row < row_begin) return;  // uniform over the workgroup
     e_first = (int64_t)gi * L;
     e_step = (int64_t)G * L;
   }
@@ -1494,17 +1496,17 @@ template <int MODE>
 static hipError_t launch_spmm_cols_t(const int64_t* rowptr, const int32_t* col, const double* val, const double* s,
                                      int64_t n, const double* z, int b, double* y, int64_t ldy, double avg_deg,
                                      const double* uprev, double alpha, double shift, double beta,
-                                     const int32_t* longrows, int nlong, hipStream_t st) {
+                                     const int32_t* longrows, int nlong, hipStream_t st, int64_t row_begin = 0) {
   const int vec_store = (ldy % 2 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0) ? 1 : 0;
   if (!longrows) nlong = 0;
   // grid: row tiles (a multiple of kXcds), then one workgroup per long row (rounded up to kXcds)
 #define SC_LAUNCH_COLS(BB, LL)                                                                                     \
   do {                                                                                                             \
-    const int64_t ntiles = ceil_div64(ceil_div64(n, kThreads / LL), kXcds) * kXcds;                                \
+    const int64_t ntiles = ceil_div64(ceil_div64(n - row_begin, kThreads / LL), kXcds) * kXcds;                    \
     const int64_t nextra = ceil_div64(nlong, kXcds) * kXcds;                                                       \
     hipLaunchKernelGGL((spmm_cols_kernel<BB, LL, MODE>), dim3((unsigned)(ntiles + nextra)), dim3(kThreads), 0, st, \
                        rowptr, col, val, s, z, y, ldy, n, vec_store, uprev, alpha, shift, beta, ntiles, longrows,  \
-                       nlong);                                                                                     \
+                       nlong, row_begin);                                                                          \
   } while (0)
   switch (b) {
     case 8:
@@ -1567,9 +1569,10 @@ hipError_t launch_spmm_vals(const int64_t* rowptr, const int32_t* col, const dou
 hipError_t launch_spmm_vals_cheb(const int64_t* rowptr, const int32_t* col, const double* val, int64_t n,
                                  const double* ucur, int b, const double* uprev, double* unext, double alpha,
                                  double shift, double beta, double avg_deg, const int32_t* longrows, int nlong,
-                                 hipStream_t st) {
+                                 hipStream_t st, int64_t row_begin) {
+  if (row_begin >= n) return hipSuccess;
   return launch_spmm_cols_t<2>(rowptr, col, val, nullptr, n, ucur, b, unext, b, avg_deg, uprev, alpha, shift, beta,
-                               longrows, nlong, st);
+                               longrows, nlong, st, row_begin);
 }
 
 ProjectPlan plan_project(int64_t n, int ja, int max_partials) {

@@ -96,26 +96,40 @@ __global__ __launch_bounds__(kT) void max_row_len_kernel(const int64_t* __restri
   if (threadIdx.x % 64 == 0 && m > 0) atomicMax(maxlen, m);
 }
 
-// key[i] = label << 3w | f << 2w | g(h2) << w | g(h1), g = the top w bits of a re-hash; ident[i] = i.
+// csize[l] += 1 for every node with label l (the slots must hold 0 on entry): the sizes of the components, at the
+// slots of their labels
+__global__ __launch_bounds__(kT) void component_size_kernel(const int32_t* __restrict__ label, int64_t n,
+                                                            int32_t* __restrict__ csize) {
+  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i < n) atomicAdd(&csize[label[i]], 1);
+}
+
+// key[i] = big << (3w + lb) | label << 3w | f << 2w | g(h2) << w | g(h1), g = the top w bits of a re-hash; ident[i] = i.
+// big = 1 for the nodes of components with more than big_rows nodes (csize != null): those components come last.
 // f = g(h3), or, if by_length is set and the graph has hubs (longest row > 3 average rows),
 // 2^w - 1 - min(row length, 2^w - 1): rows of a component then come in order of decreasing length.
 __global__ __launch_bounds__(kT) void pack_key_kernel(const int32_t* __restrict__ label, const uint32_t* __restrict__ h1,
                                                       const uint32_t* __restrict__ h2, const uint32_t* __restrict__ h3,
                                                       const int64_t* __restrict__ rowptr, const int* __restrict__ maxlen,
                                                       int by_length, int w, int64_t n, uint64_t* __restrict__ key,
-                                                      int32_t* __restrict__ ident) {
+                                                      int32_t* __restrict__ ident, const int32_t* __restrict__ csize,
+                                                      int big_rows, int lb) {
   const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (i >= n) return;
   const int sh = 32 - w;
   const bool hubs = by_length && (int64_t)(*maxlen) * n > 3 * rowptr[n];
   const uint64_t g1 = hash32(h1[i]) >> sh, g2 = hash32(h2[i]) >> sh;
   uint64_t f = hash32(h3[i]) >> sh;
-  if (hubs) {
+  // components small enough for the LDS-resident filter: their rows by decreasing length too (the filter's sliced copy
+  // pads the rows of a slice to its longest; locality inside such a component is of no consequence)
+  const bool small_comp = csize && csize[label[i]] <= big_rows;
+  if (hubs || small_comp) {
     const int64_t cap = ((int64_t)1 << w) - 1;
     const int64_t len = rowptr[i + 1] - rowptr[i];
     f = (uint64_t)(cap - (len < cap ? len : cap));
   }
-  key[i] = ((uint64_t)(uint32_t)label[i] << (3 * w)) | (f << (2 * w)) | (g2 << w) | g1;
+  const uint64_t big = (csize && !small_comp) ? 1 : 0;
+  key[i] = (big << (3 * w + lb)) | ((uint64_t)(uint32_t)label[i] << (3 * w)) | (f << (2 * w)) | (g2 << w) | g1;
   ident[i] = (int32_t)i;
 }
 
@@ -192,7 +206,7 @@ size_t order_by_component_workspace(int64_t n) {
 }
 
 hipError_t order_by_component(const int64_t* rowptr, const int32_t* col, const int32_t* label, int64_t n, int by_length,
-                              void* work,
+                              int big_rows, void* work,
                               size_t work_bytes, int32_t* old_of_new, int32_t* new_of_old, int64_t* rowptr_new,
                               int32_t* comp_of_new, hipStream_t st) {
   if (n <= 0) return hipSuccess;
@@ -228,16 +242,23 @@ hipError_t order_by_component(const int64_t* rowptr, const int32_t* col, const i
   hipLaunchKernelGGL(minhash_level_kernel, dim3(blocks(n * 16)), dim3(kT), 0, st, rowptr, col, h2, n, h3);
   // labels are node indices: bits_for(n) bits above three hash fields of w bits each
   const int lb = bits_for(n);
-  const int w = (64 - lb) / 3 < 16 ? (64 - lb) / 3 : 16;
+  const int w = (63 - lb) / 3 < 16 ? (63 - lb) / 3 : 16;  // one bit is kept for the large-component mark
+  int32_t* csize = nullptr;
+  if (big_rows > 0) {  // component sizes, in the buffer that takes the row lengths after the sort
+    csize = reinterpret_cast<int32_t*>(len);
+    hipError_t ec = hipMemsetAsync(csize, 0, (size_t)n * sizeof(int32_t), st);
+    if (ec != hipSuccess) return ec;
+    hipLaunchKernelGGL(component_size_kernel, dim3(blocks(n)), dim3(kT), 0, st, label, n, csize);
+  }
   int* maxlen = reinterpret_cast<int*>(h3 + n);  // in the spare bytes at the end of the workspace
   hipError_t em = hipMemsetAsync(maxlen, 0, sizeof(int), st);
   if (em != hipSuccess) return em;
   hipLaunchKernelGGL(max_row_len_kernel, dim3((unsigned)(blocks(n) < 1024 ? blocks(n) : 1024)), dim3(kT), 0, st, rowptr, n,
                      maxlen);
   hipLaunchKernelGGL(pack_key_kernel, dim3(blocks(n)), dim3(kT), 0, st, label, h1, h2, h3, rowptr, maxlen, by_length,
-                     w, n, key, ident);
+                     w, n, key, ident, csize, big_rows, lb);
   size_t sb = sort_bytes;
-  e = rocprim::radix_sort_pairs(temp, sb, key, key_sorted, ident, old_of_new, (size_t)n, 0u, (unsigned)(3 * w + lb), st);
+  e = rocprim::radix_sort_pairs(temp, sb, key, key_sorted, ident, old_of_new, (size_t)n, 0u, (unsigned)(3 * w + lb + 1), st);
   if (e != hipSuccess) return e;
   int32_t* starts = ident;  // the identity values are no longer needed: the buffer takes the component-start marks
   hipLaunchKernelGGL(after_sort_kernel, dim3(blocks(n)), dim3(kT), 0, st, rowptr, key_sorted, old_of_new, n, 3 * w,

@@ -40,6 +40,7 @@
 #include <cstring>
 
 #include <rocprim/device/device_scan.hpp>
+#include <rocprim/functional.hpp>
 #include <rocprim/device/device_select.hpp>
 #include <rocprim/iterator/counting_iterator.hpp>
 
@@ -295,12 +296,172 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
   }
 }
 
+// The sliced form, for diagonal blocks whose entries do not fit the registers (up to about 1,250 rows): items of 8
+// columns, the iterates in LDS as above, the entries read again in every step - from a copy of the block made for
+// that (build_sliced_copy below): the block's rows in slices of 64, the k-th entries of a slice's rows next to each
+// other, rows padded to the slice's longest with zero entries, columns as 16-bit indices inside the block.  A wave
+// takes a slice, a lane a row: a round is one coalesced read of 64 (column, value) pairs, a 64-byte read of an operand
+// row from LDS per lane (the four 16-byte pieces in an order rotated by the lane index, which spreads the banks) and 8
+// multiply-adds; the row's sum never leaves the lane, so there are no partial sums to exchange.  The solver's
+// renumbering orders the rows of a component by length, which keeps the padding of kNN graphs at a few per cent; a
+// matrix whose padding exceeds a half is left to the product-per-step kernel by the planner.
+constexpr int kSliceRows = 64;
+constexpr int kSliceGroup = 8;  // rounds per register buffer of entries
+constexpr int kSliceOwn = 2;    // slices a wave may own: items of up to 16 * 2 * 64 = 2,048 rows
+
+__device__ __forceinline__ void resident_item_sliced(const uint16_t* __restrict__ scol, const double* __restrict__ sval,
+                                                     const int64_t* __restrict__ slice_base,
+                                                     const int32_t* __restrict__ slice_len,
+                                                     const double* __restrict__ x, double* __restrict__ y, int b, int d,
+                                                     double alpha_first, double alpha_rest, double shift, int row0,
+                                                     int nr, int col0, int slice0, unsigned char* smem) {
+  constexpr int BS = 8;  // columns of the item
+  constexpr int RW = BS / 2;
+  double* bufa = reinterpret_cast<double*>(smem);
+  double* bufb = bufa + (size_t)nr * BS;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int pc0 = (lane + 0) & 3, pc1 = (lane + 1) & 3, pc2 = (lane + 2) & 3, pc3 = (lane + 3) & 3;
+  const int pcs[4] = {pc0, pc1, pc2, pc3};
+  for (int idx = tid; idx < nr * BS; idx += kRT) {
+    const int r = idx / BS, t = idx - r * BS;
+    bufa[idx] = x[(int64_t)(row0 + r) * b + col0 + t];
+    bufb[idx] = 0.0;
+  }
+  __syncthreads();
+  const int nsl = (nr + kSliceRows - 1) / kSliceRows;
+  // the wave's slices (wave, wave + 16, ...: at most kSliceOwn, which the planner guarantees): where their entries
+  // start and how many rounds they take, fetched once
+  const uint16_t* cps[kSliceOwn];
+  const double* vps[kSliceOwn];
+  int lens[kSliceOwn];
+  int nown = 0;
+#pragma unroll
+  for (int j = 0; j < kSliceOwn; ++j) {
+    const int sl = wave + j * (kRT / 64);
+    const bool have = sl < nsl;
+    const int64_t base = have ? slice_base[slice0 + sl] : 0;
+    lens[j] = have ? __builtin_amdgcn_readfirstlane(slice_len[slice0 + sl]) : 0;
+    cps[j] = scol + base + lane;
+    vps[j] = sval + base + lane;
+    nown += have ? 1 : 0;
+  }
+  // Rounds in groups of kSliceGroup, two register buffers: while one group is multiplied the entries of the next
+  // are on their way, and the first group of the slice the wave turns to next (in this step or the one after) is
+  // requested before the recurrence update and the step's barrier.  Whole groups run without a branch, so the LDS
+  // reads of a round are issued ahead of the multiply-adds of the round before.  Requests past a slice's end read
+  // the next slice's entries (the copy ends with room for the last slice's) and are not multiplied.
+  int ca[kSliceGroup], cb[kSliceGroup];
+  double aa[kSliceGroup], ab[kSliceGroup];
+  auto load_group = [&](int (&c)[kSliceGroup], double (&a)[kSliceGroup], const uint16_t* cp, const double* vp, int k0)
+                        __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < kSliceGroup; ++u) {
+      c[u] = cp[(int64_t)(k0 + u) * kSliceRows];
+      a[u] = vp[(int64_t)(k0 + u) * kSliceRows];
+    }
+  };
+  if (nown > 0) load_group(ca, aa, cps[0], vps[0], 0);
+  double* cur = bufa;
+  double* prev = bufb;
+  for (int step = 0; step < d; ++step) {
+    const double alpha = step == 0 ? alpha_first : alpha_rest;
+    const double beta = step == 0 ? 0.0 : 1.0;
+    const double2* __restrict__ cur2 = reinterpret_cast<const double2*>(cur);
+    double2* prev2 = reinterpret_cast<double2*>(prev);
+#pragma unroll
+    for (int j = 0; j < kSliceOwn; ++j) {
+      if (j >= nown) break;  // uniform over the wave
+      const int sl = wave + j * (kRT / 64);
+      const int len = lens[j];
+      const uint16_t* cp = cps[j];
+      const double* vp = vps[j];
+      double acc[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) acc[t] = 0.0;
+      auto round = [&](int c, double a) __attribute__((always_inline)) {
+        const double2* zp = cur2 + c * RW;
+        const double2 z0 = zp[pc0], z1 = zp[pc1], z2 = zp[pc2], z3 = zp[pc3];
+        acc[0] += a * z0.x;
+        acc[1] += a * z0.y;
+        acc[2] += a * z1.x;
+        acc[3] += a * z1.y;
+        acc[4] += a * z2.x;
+        acc[5] += a * z2.y;
+        acc[6] += a * z3.x;
+        acc[7] += a * z3.y;
+      };
+      auto mul_group = [&](const int (&c)[kSliceGroup], const double (&a)[kSliceGroup]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < kSliceGroup; ++u) round(c[u], a[u]);
+      };
+      auto mul_part = [&](const int (&c)[kSliceGroup], const double (&a)[kSliceGroup], int cnt)
+                          __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < kSliceGroup; ++u)
+          if (u < cnt) round(c[u], a[u]);  // uniform over the wave
+      };
+      // the slice the wave turns to after this one
+      const int jn = (j + 1 < kSliceOwn && j + 1 < nown) ? j + 1 : 0;
+      int k = 0;
+      while (k + 2 * kSliceGroup <= len) {
+        load_group(cb, ab, cp, vp, k + kSliceGroup);
+        mul_group(ca, aa);
+        load_group(ca, aa, cp, vp, k + 2 * kSliceGroup);
+        mul_group(cb, ab);
+        k += 2 * kSliceGroup;
+      }
+      if (len - k >= kSliceGroup) {
+        load_group(cb, ab, cp, vp, k + kSliceGroup);
+        mul_group(ca, aa);
+        load_group(ca, aa, cps[jn], vps[jn], 0);
+        mul_part(cb, ab, len - k - kSliceGroup);
+      } else {
+        int ct[kSliceGroup];
+        double at[kSliceGroup];
+#pragma unroll
+        for (int u = 0; u < kSliceGroup; ++u) {
+          ct[u] = ca[u];
+          at[u] = aa[u];
+        }
+        load_group(ca, aa, cps[jn], vps[jn], 0);
+        mul_part(ct, at, len - k);
+      }
+      const int r = sl * kSliceRows + lane;
+      if (r < nr) {  // the recurrence with the row's sum, stored over u- (only this lane reads or writes that row of it)
+        const double2* own = cur2 + r * RW;
+        double2* out = prev2 + r * RW;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int at = pcs[t];
+          const double2 o = own[at], pv = out[at];
+          double2 w;
+          w.x = alpha * (acc[2 * t] - shift * o.x) - beta * pv.x;
+          w.y = alpha * (acc[2 * t + 1] - shift * o.y) - beta * pv.y;
+          out[at] = w;
+        }
+      }
+    }
+    __syncthreads();  // every row of the new iterate is in place; nobody reads the old u- any more
+    double* t = cur;
+    cur = prev;
+    prev = t;
+  }
+  for (int idx = tid; idx < nr * BS; idx += kRT) {
+    const int r = idx / BS, t = idx - r * BS;
+    y[(int64_t)(row0 + r) * b + col0 + t] = cur[idx];
+  }
+}
+
 __global__ __launch_bounds__(kRT) void cheb_resident_kernel(const int64_t* __restrict__ rowptr,
                                                             const int32_t* __restrict__ col,
                                                             const double* __restrict__ val,
                                                             const double* __restrict__ x, double* __restrict__ y, int b,
                                                             int d, double alpha_first, double alpha_rest, double shift,
-                                                            const int32_t* __restrict__ items) {
+                                                            const int32_t* __restrict__ items,
+                                                            const uint16_t* __restrict__ scol,
+                                                            const double* __restrict__ sval,
+                                                            const int64_t* __restrict__ slice_base,
+                                                            const int32_t* __restrict__ slice_len) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int32_t* it = items + 4 * (int64_t)blockIdx.x;
   const int row0 = it[0], nr = it[1], col0 = it[2], cl = it[3] & 15, nx = it[3] >> 4;  // uniform over the workgroup
@@ -308,6 +469,98 @@ __global__ __launch_bounds__(kRT) void cheb_resident_kernel(const int64_t* __res
     resident_item<4>(rowptr, col, val, x, y, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem);
   else if (cl == 2)
     resident_item<2>(rowptr, col, val, x, y, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem);
+  else if (cl == 1)  // sliced form: the item's last word carries its first slice instead of a chunk count
+    resident_item_sliced(scol, sval, slice_base, slice_len, x, y, b, d, alpha_first, alpha_rest, shift, row0, nr, col0,
+                         nx, smem);
+}
+
+// ---- sliced copy of diagonal blocks ------------------------------------------------------------------------------------
+// One wave per slice (64 consecutive rows of one block, fewer at the block's end).  slice_len = the longest row;
+// slice_entries = 64 * slice_len: what the slice takes in the copy.
+__global__ __launch_bounds__(256) void slice_len_kernel(const int64_t* __restrict__ rowptr,
+                                                        const int32_t* __restrict__ slice_row0,
+                                                        const int32_t* __restrict__ slice_rows, int nslices,
+                                                        int32_t* __restrict__ slice_len,
+                                                        int64_t* __restrict__ slice_entries) {
+  const int sidx = (int)(((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6);
+  const int lane = threadIdx.x & 63;
+  if (sidx >= nslices) return;
+  const int64_t r = (int64_t)slice_row0[sidx] + lane;
+  int len = lane < slice_rows[sidx] ? (int)(rowptr[r + 1] - rowptr[r]) : 0;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const int other = __shfl_xor(len, o, 64);
+    len = len > other ? len : other;
+  }
+  if (lane == 0) {
+    slice_len[sidx] = len;
+    slice_entries[sidx] = (int64_t)kSliceRows * len;
+  }
+}
+
+// Fills slice sidx of the copy: round k of lane l sits at slice_base + 64 k + l.  Columns are stored relative to the
+// block's first row (slice_blk0); the padding (rounds past a row's end, lanes past the block's end) has value 0.
+//
+// The order of a row's entries is chosen for the LDS banks.  In a round the 16 lanes of a pass read 16 bytes each from
+// an operand row of 64 bytes: piece (t + lane) mod 4 of row c sits at bank quad 4 (c mod 4) + piece, so the four lanes
+// of a pass that share a piece number must read rows that differ mod 4, or the pass is served in several turns.
+// Lane l therefore puts into round k, while it has one, an entry whose column is ((l >> 2) + k) mod 4 modulo 4 (four
+// cursors walk the row, one per residue class, each in the row's own order), else an entry of the next class that has
+// any left; padding entries name a row of the wanted class.  The order depends on the matrix alone, so the sums stay
+// reproducible.
+__global__ __launch_bounds__(256) void slice_fill_kernel(const int64_t* __restrict__ rowptr,
+                                                         const int32_t* __restrict__ col,
+                                                         const double* __restrict__ val,
+                                                         const int32_t* __restrict__ slice_row0,
+                                                         const int32_t* __restrict__ slice_rows,
+                                                         const int32_t* __restrict__ slice_blk0,
+                                                         const int32_t* __restrict__ slice_blk_rows, int nslices,
+                                                         const int64_t* __restrict__ slice_base,
+                                                         const int64_t* __restrict__ slice_entries,
+                                                         uint16_t* __restrict__ scol, double* __restrict__ sval) {
+  const int sidx = (int)(((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6);
+  const int lane = threadIdx.x & 63;
+  if (sidx >= nslices) return;
+  const int rounds = (int)(slice_entries[sidx] / kSliceRows);
+  const int64_t base = slice_base[sidx];
+  const bool live = lane < slice_rows[sidx];
+  const int64_t r = (int64_t)slice_row0[sidx] + lane;
+  const int64_t e0 = live ? rowptr[r] : 0, e1 = live ? rowptr[r + 1] : 0;
+  const int blk0 = slice_blk0[sidx];
+  const unsigned last = (unsigned)(slice_blk_rows[sidx] - 1);
+  auto local = [&](int64_t e) -> unsigned {
+    const unsigned lc = (unsigned)(col[e] - blk0);
+    return lc < last ? lc : last;  // a column outside the block (there is none in a diagonal block) stays inside LDS
+  };
+  auto next_of_class = [&](int64_t from, unsigned cls) -> int64_t {
+    int64_t e = from;
+    while (e < e1 && (local(e) & 3u) != cls) ++e;
+    return e;
+  };
+  int64_t cur[4];
+#pragma unroll
+  for (unsigned cls = 0; cls < 4; ++cls) cur[cls] = next_of_class(e0, cls);
+  for (int k = 0; k < rounds; ++k) {
+    const unsigned want = (unsigned)((lane >> 2) + k) & 3u;
+    unsigned lc = want <= last ? want : 0;  // padding: a row of the wanted class
+    double av = 0.0;
+#pragma unroll
+    for (unsigned o = 0; o < 4; ++o) {
+      const unsigned cls = (want + o) & 3u;
+      bool took = false;
+#pragma unroll
+      for (unsigned q = 0; q < 4; ++q)  // cur[] is indexed with constants only (it lives in registers)
+        if (q == cls && cur[q] < e1 && !took) {
+          lc = local(cur[q]);
+          av = val[cur[q]];
+          cur[q] = next_of_class(cur[q] + 1, q);
+          took = true;
+        }
+      if (took) break;
+    }
+    scol[base + (int64_t)k * kSliceRows + lane] = (uint16_t)lc;
+    sval[base + (int64_t)k * kSliceRows + lane] = av;
+  }
 }
 
 // extra[2 t] / extra[2 t + 1] = chunks beyond the first, summed over the rows of diagonal block t, for chunks of 32 /
@@ -371,6 +624,48 @@ size_t resident_item_lds_bytes(int nrows, int cl, int extra) { return resident_l
 
 int resident_max_chunks(int cl) { return kRS * (kRT / cl); }
 
+int resident_slice_rows() { return kSliceRows; }
+
+int64_t sliced_copy_tail_entries() { return (int64_t)3 * kSliceGroup * kSliceRows; }
+
+size_t resident_sliced_lds_bytes(int nrows) {
+  if (nrows > kSliceOwn * (kRT / 64) * kSliceRows) return ~(size_t)0;  // more slices than the waves own: no item
+  return ((size_t)2 * nrows * 8 * sizeof(double) + 15) / 16 * 16;
+}
+
+size_t sliced_scan_workspace(int nslices) {
+  size_t t = 0;
+  (void)rocprim::exclusive_scan(nullptr, t, (int64_t*)nullptr, (int64_t*)nullptr, (int64_t)0, (size_t)nslices + 1,
+                                rocprim::plus<int64_t>());
+  return up256(t) + 256;
+}
+
+hipError_t sliced_copy_layout(const int64_t* rowptr, const int32_t* slice_row0, const int32_t* slice_rows, int nslices,
+                              int32_t* slice_len, int64_t* slice_entries, int64_t* slice_base, void* work,
+                              size_t work_bytes, hipStream_t st) {
+  if (nslices <= 0) return hipSuccess;
+  hipLaunchKernelGGL(slice_len_kernel, dim3((unsigned)(((int64_t)nslices * 64 + 255) / 256)), dim3(256), 0, st, rowptr,
+                     slice_row0, slice_rows, nslices, slice_len, slice_entries);
+  // slice_entries has nslices + 1 slots, the last one zero: the scan's last output is the copy's size
+  hipError_t e = hipMemsetAsync(slice_entries + nslices, 0, sizeof(int64_t), st);
+  if (e != hipSuccess) return e;
+  e = rocprim::exclusive_scan(work, work_bytes, slice_entries, slice_base, (int64_t)0, (size_t)nslices + 1,
+                              rocprim::plus<int64_t>(), st);
+  if (e != hipSuccess) return e;
+  return hipGetLastError();
+}
+
+hipError_t sliced_copy_fill(const int64_t* rowptr, const int32_t* col, const double* val, const int32_t* slice_row0,
+                            const int32_t* slice_rows, const int32_t* slice_blk0, const int32_t* slice_blk_rows,
+                            int nslices, const int64_t* slice_base, const int64_t* slice_entries, uint16_t* scol,
+                            double* sval, hipStream_t st) {
+  if (nslices <= 0) return hipSuccess;
+  hipLaunchKernelGGL(slice_fill_kernel, dim3((unsigned)(((int64_t)nslices * 64 + 255) / 256)), dim3(256), 0, st, rowptr,
+                     col, val, slice_row0, slice_rows, slice_blk0, slice_blk_rows, nslices, slice_base, slice_entries,
+                     scol, sval);
+  return hipGetLastError();
+}
+
 hipError_t launch_block_extra_chunks(const int64_t* rowptr, const int32_t* starts, int nblk, int64_t n, int32_t* extra,
                                      hipStream_t st) {
   if (nblk <= 0) return hipSuccess;
@@ -407,13 +702,14 @@ hipError_t diagonal_blocks(const int64_t* rowptr, const int32_t* col, int64_t n,
 
 hipError_t launch_cheb_resident(const int64_t* rowptr, const int32_t* col, const double* val, const double* x, double* y,
                                 int b, int d, double alpha_first, double alpha_rest, double shift, const int32_t* items,
-                                int nitems, size_t lds_bytes, hipStream_t st) {
+                                int nitems, size_t lds_bytes, const uint16_t* scol, const double* sval,
+                                const int64_t* slice_base, const int32_t* slice_len, hipStream_t st) {
   if (nitems <= 0 || d <= 0) return hipSuccess;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cheb_resident_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(cheb_resident_kernel, dim3((unsigned)nitems), dim3(kRT), lds_bytes, st, rowptr, col, val, x, y, b, d,
-                     alpha_first, alpha_rest, shift, items);
+                     alpha_first, alpha_rest, shift, items, scol, sval, slice_base, slice_len);
   return hipGetLastError();
 }
 

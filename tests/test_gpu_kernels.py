@@ -389,15 +389,71 @@ def test_chebyshev_filter_resident_in_lds(B, ncols, degree, monkeypatch):
     assert torch.equal(got2, got)
 
 
+@pytest.mark.parametrize("ncols", [16, 32])
+@pytest.mark.parametrize("degree", [2, 12])
+def test_chebyshev_filter_resident_sliced_form(B, ncols, degree, monkeypatch):
+    """Diagonal blocks of 700 to 1,150 rows: too many rows (or entries) for the form that keeps the entries in
+    registers, so they go as 8-column items that stream their entries from a sliced copy (slices of 64 rows, the last
+    one of a block shorter; rows of 2 to 50 entries, so slices with padding); small blocks in the same matrix keep the
+    register form.  Against the oracle's recurrence element by element, bitwise repeatable, and it must be the
+    one-launch path."""
+    from oracle import blockops
+    monkeypatch.setenv("SCEIG_FORCE_RESIDENT", "1")
+    rp, c, v, n = wl.disjoint_union(wl.random_weighted_connected(700, 9000, 1), wl.path(2), wl.ring(1150),
+                                    wl.random_weighted_connected(1000, 16000, 2), wl.complete(40), wl.path(65))
+    rng = np.random.default_rng(11 * ncols + degree)
+    x = rng.standard_normal((n, ncols))
+    a = 0.35
+    want = blockops.chebyshev_filter(rp, c, v, x, a, degree)
+    drp, dc, dv = B.csr_to_device(rp, c, v)
+    dx = torch.from_numpy(x).cuda()
+    before = B.sc_counter(B.SC_COUNTER_RESIDENT_FILTERS)
+    got = B.sc_chebyshev_filter(drp, dc, dv, dx, a, degree)
+    assert B.sc_counter(B.SC_COUNTER_RESIDENT_FILTERS) == before + 1
+    scale = max(1.0, np.max(np.abs(want)))
+    assert np.max(np.abs(got.cpu().numpy() - want)) <= 1e-11 * scale
+    assert torch.equal(got, B.sc_chebyshev_filter(drp, dc, dv, dx, a, degree))
+    # without the sliced form these blocks do not fit, and the product-per-step path gives the same to rounding
+    monkeypatch.setenv("SCEIG_NO_SLICED", "1")
+    other = B.sc_chebyshev_filter(drp, dc, dv, dx, a, degree)
+    assert B.sc_counter(B.SC_COUNTER_RESIDENT_FILTERS) == before + 2
+    assert np.max(np.abs(other.cpu().numpy() - want)) <= 1e-11 * scale
+
+
+@pytest.mark.parametrize("degree", [1, 2, 3, 8])
+def test_chebyshev_filter_resident_with_trailing_large_blocks(B, degree, monkeypatch):
+    """Blocks too large for any item (1,300 and 1,400 rows) at the END of the matrix: the items of the other blocks go
+    in one launch, the trailing rows step by step through the product kernel restricted to them (long rows among them
+    included), and both land in the same result; degrees 1, 2, 3 cover the three buffers the last step can end in."""
+    from oracle import blockops
+    monkeypatch.setenv("SCEIG_FORCE_RESIDENT", "1")
+    star = wl.symmetric_from_edges(np.zeros(500, dtype=np.int64), np.arange(1, 501), np.linspace(0.5, 1.5, 500), 501)
+    rp, c, v, n = wl.disjoint_union(wl.random_weighted_connected(700, 9000, 1), wl.ring(300), star,
+                                    wl.random_weighted_connected(1300, 5000, 3),
+                                    wl.disjoint_union(wl.random_weighted_connected(1400, 30000, 4)))
+    big_star = wl.symmetric_from_edges(np.zeros(1500, dtype=np.int64), np.arange(1, 1501), np.ones(1500), 1501)
+    rp, c, v, n = wl.disjoint_union((rp, c, v, n), big_star)      # a trailing block with a row of 1,500 entries
+    rng = np.random.default_rng(degree)
+    x = rng.standard_normal((n, 16))
+    a = 0.3
+    want = blockops.chebyshev_filter(rp, c, v, x, a, degree)
+    drp, dc, dv = B.csr_to_device(rp, c, v)
+    dx = torch.from_numpy(x).cuda()
+    before = B.sc_counter(B.SC_COUNTER_RESIDENT_FILTERS)
+    got = B.sc_chebyshev_filter(drp, dc, dv, dx, a, degree)
+    assert B.sc_counter(B.SC_COUNTER_RESIDENT_FILTERS) == before + 1
+    assert np.max(np.abs(got.cpu().numpy() - want)) <= 1e-11 * max(1.0, np.max(np.abs(want)))
+    assert torch.equal(got, B.sc_chebyshev_filter(drp, dc, dv, dx, a, degree))
+
+
 def test_chebyshev_filter_resident_declines_what_does_not_fit(B, monkeypatch):
-    """Blocks with more rows than LDS holds at 16 columns (700 rows), with more chunks than the lane groups take
-    (complete graph on 300 nodes: 10 chunks a row), or a block width without a resident form (8 columns) go the
-    product-per-step way even when the resident form is asked for; the answer is the oracle's either way."""
+    """A block with more rows than LDS holds even as 8-column items (1,300 rows) that is NOT at the end of the matrix,
+    or a block width without a resident form (8 columns): the product-per-step way, even when the resident form is
+    asked for; the answer is the oracle's either way."""
     from oracle import blockops
     monkeypatch.setenv("SCEIG_FORCE_RESIDENT", "1")
     rng = np.random.default_rng(3)
-    cases = [(wl.disjoint_union(wl.ring(40), wl.random_weighted_connected(700, 3000, 1)), 16),
-             (wl.disjoint_union(wl.ring(40), wl.complete(300)), 32),
+    cases = [(wl.disjoint_union(wl.random_weighted_connected(1300, 5000, 1), wl.ring(40)), 16),
              (wl.disjoint_union(wl.ring(40), wl.ring(50)), 8)]
     for (rp, c, v, n), ncols in cases:
         x = rng.standard_normal((n, ncols))
