@@ -639,11 +639,13 @@ void plan_resident(const int64_t* rowptr, const int32_t* col, const double* val,
 //   wide blocks (val_scaled != null, b >= 8): z holds X packed; the recurrence is fused into the product kernel and
 //     rotates through z, buf1 and buf2.
 //   narrow blocks: z holds s o X packed and buf1 holds X packed; buf2 and buf3 are scratch (product + combine kernel).
-// All buffers are packed n x b.  Returns the buffer that holds the result.
+// All buffers are packed n x b.  Returns the buffer that holds the result - or null when the one-launch form has
+// written it to `direct` (n x b with leading dimension direct_ld; optional), which saves the caller a copy.
 double* enqueue_cheb_filter(const int64_t* rowptr, const int32_t* col, const double* val, const double* val_scaled,
                             const double* s, int64_t n, int64_t nnz, int b, int d, double a, double* z, double* buf1,
                             double* buf2, double* buf3, double avg_deg, const int32_t* longrows, int nlong,
-                            const ResidentPlan* resident, hipStream_t st, KTimer* tm) {
+                            const ResidentPlan* resident, hipStream_t st, KTimer* tm, double* direct = nullptr,
+                            int64_t direct_ld = 0) {
   KTimer none;
   if (!tm) tm = &none;
   const double lo = -1.0;  // ||S||_2 = 1
@@ -654,14 +656,16 @@ double* enqueue_cheb_filter(const int64_t* rowptr, const int32_t* col, const dou
     // all d steps in one launch, iterates in LDS: the matrix entries are streamed once per step and column slice, the
     // block is read once and written once
     resident_launches.fetch_add(1, std::memory_order_relaxed);
+    double* out = direct ? direct : buf1;
+    const int64_t ldo = direct ? direct_ld : (int64_t)b;
     tm->begin(kFamSpmm);
-    HIP_TRY(launch_cheb_resident(rowptr, col, val_scaled, z, buf1, b, d, 1.0 / e, 2.0 / e, c, resident->items.p,
+    HIP_TRY(launch_cheb_resident(rowptr, col, val_scaled, z, out, ldo, b, d, 1.0 / e, 2.0 / e, c, resident->items.p,
                                  resident->nitems, resident->lds_bytes, resident->scol.p, resident->sval.p,
                                  resident->slice_base.p, resident->slice_len.p, st));
     const int64_t r0 = resident->rest_row0;
     if (r0 < n) {
       // the blocks without an item: the recurrence step by step on their rows alone (their iterates rotate through the
-      // same three buffers, in rows the items do not touch), then into the result buffer
+      // same three buffers, in rows the items do not touch), then into the result
       double* cur = z;
       double* prev = buf2;
       double* next = buf1;
@@ -673,12 +677,11 @@ double* enqueue_cheb_filter(const int64_t* rowptr, const int32_t* col, const dou
         cur = next;
         next = t;
       }
-      if (cur != buf1)
-        HIP_TRY(hipMemcpyAsync(buf1 + r0 * b, cur + r0 * b, (size_t)(n - r0) * b * sizeof(double),
-                               hipMemcpyDeviceToDevice, st));
+      if (cur != out)
+        HIP_TRY(launch_copy_cols(cur + r0 * b, b, 0, out + r0 * ldo, ldo, 0, b, n - r0, st));
     }
     tm->end(kFamSpmm, d * bytes + (d - 1) * 8.0 * (double)n * b, d * 2.0 * (double)nnz * b, d);
-    return buf1;
+    return direct ? nullptr : buf1;
   }
   if (val_scaled) {
     double* cur = z;
@@ -1038,10 +1041,10 @@ struct Solver {
     double* buf3 = rot.p + 2 * (size_t)n * b;
     if (!val_s.p) HIP_TRY(launch_copy_cols(basis.p, ld, nl, buf1, b, 0, b, n, st));
     const double* res = enqueue_cheb_filter(rowptr, col, val, val_s.p, s.p, n, nnz, b, d, a, z.p, buf1, buf2, buf3,
-                                            avg_deg, longrows.p, nlong, &resident, st, &timer);
+                                            avg_deg, longrows.p, nlong, &resident, st, &timer, basis.p + nl, ld);
     stats.spmv_cols += (int64_t)d * b;
     stats.filter_steps += d;
-    HIP_TRY(launch_copy_cols(res, b, 0, basis.p, ld, nl, b, n, st));
+    if (res) HIP_TRY(launch_copy_cols(res, b, 0, basis.p, ld, nl, b, n, st));
   }
 
   // Decide the filter of the next start block from the Ritz values theta (ascending, ghosts at the bottom).
@@ -1163,9 +1166,6 @@ struct Solver {
       stats.phases += 1;
 
       // ---- start block
-      HIP_TRY(launch_random_block(basis.p, n, ld, nl, b, seed, stream_id++, st));
-      if (v0 && stats.phases == 1)  // the caller's start vector leads the first block, the other columns stay random
-        HIP_TRY(launch_set_column(basis.p, n, ld, nl, v0, rowmap, st));
       bool filtered = filt_d > 0;
       // exponent of the filter this phase starts from (0: none, or not a random block), for the degree feedback
       double phase_rate = filtered ? filt_rate : 0.0;
@@ -1186,6 +1186,17 @@ struct Solver {
         const double top = *std::max_element(theta_locked.begin(), theta_locked.end());
         late_projection = top <= filt_ref + 1e-6;
       }
+      // the random block; when it goes into the filter as it is (the wide blocks' operand is a plain packed copy) it is
+      // drawn into the packed buffer directly: same numbers, one pass less
+      const bool use_v0 = v0 && stats.phases == 1;
+      const bool random_packed = filtered && late_projection && val_s.p && !use_v0;
+      if (random_packed) {
+        HIP_TRY(launch_random_block(z.p, n, b, 0, b, seed, stream_id++, st));
+      } else {
+        HIP_TRY(launch_random_block(basis.p, n, ld, nl, b, seed, stream_id++, st));
+        if (use_v0)  // the caller's start vector leads the first block, the other columns stay random
+          HIP_TRY(launch_set_column(basis.p, n, ld, nl, v0, rowmap, st));
+      }
       if (filtered) {
         if (debug_on())
           std::fprintf(stderr, "[sceig] t=%.4fs phase %d start block filtered: degree %d, damped interval [-1, %.6f]%s\n",
@@ -1193,7 +1204,7 @@ struct Solver {
                        late_projection ? ", locked vectors projected out afterwards" : "");
         if (!late_projection)
           (void)enqueue_cgs2(basis.p, n, ld, nl, nl, b, nl, part.p, h1.p, hsum.p, nullptr, 0, nullptr, st, &timer);
-        HIP_TRY(launch_pack_scaled(basis.p + nl, ld, zs(), n, b, z.p, st));
+        if (!random_packed) HIP_TRY(launch_pack_scaled(basis.p + nl, ld, zs(), n, b, z.p, st));
         apply_start_filter(filt_d, filt_a);
         filt_d = 0;
       }

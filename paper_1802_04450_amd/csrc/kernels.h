@@ -110,7 +110,7 @@ hipError_t diagonal_blocks(const int64_t* rowptr, const int32_t* col, int64_t n,
 // extra[2 t], extra[2 t + 1] (device int32) = extra chunks of block t for chunks of 32 and of 16 entries
 hipError_t launch_block_extra_chunks(const int64_t* rowptr, const int32_t* starts, int nblk, int64_t n, int32_t* extra,
                                      hipStream_t st);
-// y = the recurrence applied to x, both packed n x b: u_0 = x, u_1 = alpha_first (A u_0 - shift u_0),
+// y (n x b, leading dimension ldy >= b) = the recurrence applied to x (packed n x b): u_0 = x, u_1 = alpha_first (A u_0 - shift u_0),
 // u_{i+1} = alpha_rest (A u_i - shift u_i) - u_{i-1}; y = u_d.  A = the CSR matrix, whose rows [row0, row0 + nrows) of
 // every item form a diagonal block.  items: device int32[4 * nitems] = (row0, nrows, col0, cl | extra << 4) per
 // workgroup, covering columns [col0, col0 + 8 cl); every (block, column) pair must be covered exactly once, extra must
@@ -120,7 +120,7 @@ hipError_t launch_block_extra_chunks(const int64_t* rowptr, const int32_t* start
 // block of up to 65,535 rows and reads its entries from the sliced copy (scol, sval, slice_base, slice_len; null when
 // no item is sliced).
 hipError_t launch_cheb_resident(const int64_t* rowptr, const int32_t* col, const double* val, const double* x, double* y,
-                                int b, int d, double alpha_first, double alpha_rest, double shift, const int32_t* items,
+                                int64_t ldy, int b, int d, double alpha_first, double alpha_rest, double shift, const int32_t* items,
                                 int nitems, size_t lds_bytes, const uint16_t* scol, const double* sval,
                                 const int64_t* slice_base, const int32_t* slice_len, hipStream_t st);
 // Sliced copy of diagonal blocks for the sliced form.  A slice is up to resident_slice_rows() consecutive rows of one

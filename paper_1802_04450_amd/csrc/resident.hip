@@ -76,7 +76,7 @@ struct GroupBcast {
 template <int CL>
 __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr, const int32_t* __restrict__ col,
                                               const double* __restrict__ val, const double* __restrict__ x,
-                                              double* __restrict__ y, int b, int d, double alpha_first,
+                                              double* __restrict__ y, int64_t ldy, int b, int d, double alpha_first,
                                               double alpha_rest, double shift, int row0, int nr, int col0, int nx,
                                               unsigned char* smem) {
   constexpr int BS = 8 * CL;     // columns of the item
@@ -292,7 +292,7 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
   }
   for (int idx = tid; idx < nr * BS; idx += kRT) {
     const int r = idx / BS, t = idx - r * BS;
-    y[(int64_t)(row0 + r) * b + col0 + t] = cur[idx];
+    y[(int64_t)(row0 + r) * ldy + col0 + t] = cur[idx];
   }
 }
 
@@ -312,9 +312,9 @@ constexpr int kSliceOwn = 2;    // slices a wave may own: items of up to 16 * 2 
 __device__ __forceinline__ void resident_item_sliced(const uint16_t* __restrict__ scol, const double* __restrict__ sval,
                                                      const int64_t* __restrict__ slice_base,
                                                      const int32_t* __restrict__ slice_len,
-                                                     const double* __restrict__ x, double* __restrict__ y, int b, int d,
-                                                     double alpha_first, double alpha_rest, double shift, int row0,
-                                                     int nr, int col0, int slice0, unsigned char* smem) {
+                                                     const double* __restrict__ x, double* __restrict__ y, int64_t ldy, int b,
+                                                     int d, double alpha_first, double alpha_rest, double shift,
+                                                     int row0, int nr, int col0, int slice0, unsigned char* smem) {
   constexpr int BS = 8;  // columns of the item
   constexpr int RW = BS / 2;
   double* bufa = reinterpret_cast<double*>(smem);
@@ -448,15 +448,16 @@ __device__ __forceinline__ void resident_item_sliced(const uint16_t* __restrict_
   }
   for (int idx = tid; idx < nr * BS; idx += kRT) {
     const int r = idx / BS, t = idx - r * BS;
-    y[(int64_t)(row0 + r) * b + col0 + t] = cur[idx];
+    y[(int64_t)(row0 + r) * ldy + col0 + t] = cur[idx];
   }
 }
 
 __global__ __launch_bounds__(kRT) void cheb_resident_kernel(const int64_t* __restrict__ rowptr,
                                                             const int32_t* __restrict__ col,
                                                             const double* __restrict__ val,
-                                                            const double* __restrict__ x, double* __restrict__ y, int b,
-                                                            int d, double alpha_first, double alpha_rest, double shift,
+                                                            const double* __restrict__ x, double* __restrict__ y,
+                                                            int64_t ldy, int b, int d, double alpha_first,
+                                                            double alpha_rest, double shift,
                                                             const int32_t* __restrict__ items,
                                                             const uint16_t* __restrict__ scol,
                                                             const double* __restrict__ sval,
@@ -466,11 +467,11 @@ __global__ __launch_bounds__(kRT) void cheb_resident_kernel(const int64_t* __res
   const int32_t* it = items + 4 * (int64_t)blockIdx.x;
   const int row0 = it[0], nr = it[1], col0 = it[2], cl = it[3] & 15, nx = it[3] >> 4;  // uniform over the workgroup
   if (cl == 4)
-    resident_item<4>(rowptr, col, val, x, y, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem);
+    resident_item<4>(rowptr, col, val, x, y, ldy, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem);
   else if (cl == 2)
-    resident_item<2>(rowptr, col, val, x, y, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem);
+    resident_item<2>(rowptr, col, val, x, y, ldy, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem);
   else if (cl == 1)  // sliced form: the item's last word carries its first slice instead of a chunk count
-    resident_item_sliced(scol, sval, slice_base, slice_len, x, y, b, d, alpha_first, alpha_rest, shift, row0, nr, col0,
+    resident_item_sliced(scol, sval, slice_base, slice_len, x, y, ldy, b, d, alpha_first, alpha_rest, shift, row0, nr, col0,
                          nx, smem);
 }
 
@@ -701,14 +702,14 @@ hipError_t diagonal_blocks(const int64_t* rowptr, const int32_t* col, int64_t n,
 }
 
 hipError_t launch_cheb_resident(const int64_t* rowptr, const int32_t* col, const double* val, const double* x, double* y,
-                                int b, int d, double alpha_first, double alpha_rest, double shift, const int32_t* items,
+                                int64_t ldy, int b, int d, double alpha_first, double alpha_rest, double shift, const int32_t* items,
                                 int nitems, size_t lds_bytes, const uint16_t* scol, const double* sval,
                                 const int64_t* slice_base, const int32_t* slice_len, hipStream_t st) {
   if (nitems <= 0 || d <= 0) return hipSuccess;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cheb_resident_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(cheb_resident_kernel, dim3((unsigned)nitems), dim3(kRT), lds_bytes, st, rowptr, col, val, x, y, b, d,
+  hipLaunchKernelGGL(cheb_resident_kernel, dim3((unsigned)nitems), dim3(kRT), lds_bytes, st, rowptr, col, val, x, y, ldy, b, d,
                      alpha_first, alpha_rest, shift, items, scol, sval, slice_base, slice_len);
   return hipGetLastError();
 }
