@@ -52,19 +52,21 @@ def profiled_traffic(workload: str, family: int):
     from paper_1802_04450_amd.build import source_hash
     path = os.path.join(ROOT, "profiles", f"{workload}_eigensolve_traffic.txt")
     if not os.path.exists(path):
-        return None, None, "no counter summary for this workload"
+        return None, None, "no counter summary for this workload", None
     recorded, rows = None, []
     for line in open(path):
         if line.startswith("# csrc_sha256:"):
             recorded = line.split(":", 1)[1].strip()
         elif line.strip() and not line.startswith("#"):
-            rows.append(line.rsplit(None, 3))
+            rows.append(line.split())
     if recorded != source_hash():
-        return None, None, "counter summary was measured on other kernel sources"
-    for name, fetch, write, _avg in rows:
+        return None, None, "counter summary was measured on other kernel sources", None
+    for row in rows:
+        name, fetch, write, avg = row[0], row[1], row[2], row[3]
         if name.startswith(TRAFFIC_PREFIX[family]):
-            return float(fetch) + float(write), name, f"profiles/{workload}_eigensolve_traffic.txt"
-    return None, None, "kernel not in the counter summary"
+            extra = {"avg_launch_us_profiled": float(avg), "mfma_f64_flops_per_launch": float(row[4]) if len(row) > 4 else 0.0}
+            return float(fetch) + float(write), name, f"profiles/{workload}_eigensolve_traffic.txt", extra
+    return None, None, "kernel not in the counter summary", None
 
 
 def build_workload(name: str):
@@ -532,12 +534,24 @@ def main():
         launches = stats["fam_launches"][dom]
         ach = stats["fam_bytes"][dom] / kt / 1e9
         if args.block == 0 and args.m < 0:
-            traffic, traffic_kernel, traffic_source = profiled_traffic(args.workload, dom)
+            traffic, traffic_kernel, traffic_source, prof = profiled_traffic(args.workload, dom)
         else:
-            traffic, traffic_kernel, traffic_source = None, None, "non-default options"
+            traffic, traffic_kernel, traffic_source, prof = None, None, "non-default options", None
+        # The counters are per kernel, the family's byte model averages over all of its launches (the long contractions
+        # of traffic_kernel and many short ones of its sibling kernels), so the two per-launch figures are not of the same
+        # launches.  For the two reorthogonalization GEMMs the profiled kernel's own algorithmic bytes follow from its
+        # MFMA flop count: 2 n j b flops per launch give the contraction length j, the model 8 n (j + b) bytes for the
+        # projection and 8 n (j + 2 b) for the update.
+        traffic_alg = None
+        if prof and prof["mfma_f64_flops_per_launch"] > 0 and dom in (1, 2):
+            bb = stats["block"]
+            j_avg = prof["mfma_f64_flops_per_launch"] / (2.0 * n * bb)
+            traffic_alg = 8.0 * n * (j_avg + (1 if dom == 1 else 2) * bb)
         out["roofline"] = {"bound": "hbm", "kernel": KERNEL_OF_FAMILY[dom],
                            "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                            "traffic": traffic, "traffic_kernel": traffic_kernel, "traffic_source": traffic_source,
+                           "traffic_kernel_algorithmic_bytes": traffic_alg,
+                           "traffic_kernel_avg_us_profiled": prof["avg_launch_us_profiled"] if prof else None,
                            "launches_per_step": launches, "avg_launch_us": kt / max(1, launches) * 1e6,
                            "algorithmic_bytes_per_launch": stats["fam_bytes"][dom] / max(1, launches),
                            "fp64_tflops": stats["fam_flops"][dom] / kt / 1e12,

@@ -112,23 +112,26 @@ def main():
             fb = fetch.get((k, "FETCH_SIZE"), (0, 0.0))[1] * 1024 * ff
             wb = write.get((k, "WRITE_SIZE"), (0, 0.0))[1] * 1024 * wf
             line += " | %15.1f %15.1f" % (fb / 1e6, wb / 1e6)
-            traffic.append((k, fb, wb, avg))
+            traffic.append([k, fb, wb, avg, 0.0])
         if a.mfma:
             flops = mf.get((k, "SQ_INSTS_VALU_MFMA_MOPS_F64"), (0, 0.0))[1] * 512
             busy = mf.get((k, "SQ_VALU_MFMA_BUSY_CYCLES"), (0, 0.0))[1]
             # busy cycles are summed over the 1024 SIMDs of the chip; launch duration in cycles at 2.4 GHz
             util = busy / 1024.0 / (avg * 1e-6 * 2.4e9) * 100 if avg > 0 else 0.0
             line += " | %14.3e %10.1f" % (flops, util)
+            if traffic and traffic[-1][0] == k:
+                traffic[-1][4] = flops
         lines.append(line)
     with open(a.out, "w") as f:
         f.write("\n".join(lines) + "\n")
     if a.traffic_out and have_traffic:
         with open(a.traffic_out, "w") as f:
             f.write("# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the copy calibration), "
-                    f"bytes;\n# source and commands: {a.out}.  Columns: kernel fetch_bytes write_bytes avg_us\n"
+                    f"bytes;\n# source and commands: {a.out}.  Columns: kernel fetch_bytes write_bytes avg_us "
+                    f"mfma_f64_flops (per launch, SQ_INSTS_VALU_MFMA_MOPS_F64 * 512; 0 if not counted)\n"
                     f"# csrc_sha256: {source_hash()}\n")
-            for k, fb, wb, avg in traffic:
-                f.write("%s %.0f %.0f %.2f\n" % (k, fb, wb, avg))
+            for k, fb, wb, avg, fl in traffic:
+                f.write("%s %.0f %.0f %.2f %.4e\n" % (k, fb, wb, avg, fl))
     print("\n".join(lines))
 
 
