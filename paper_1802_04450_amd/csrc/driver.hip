@@ -645,10 +645,11 @@ double* enqueue_cheb_filter(const int64_t* rowptr, const int32_t* col, const dou
                             const double* s, int64_t n, int64_t nnz, int b, int d, double a, double* z, double* buf1,
                             double* buf2, double* buf3, double avg_deg, const int32_t* longrows, int nlong,
                             const ResidentPlan* resident, hipStream_t st, KTimer* tm, double* direct = nullptr,
-                            int64_t direct_ld = 0) {
+                            int64_t direct_ld = 0, double lo = -1.0) {
+  // lo: lower end of the damped interval; -1 always holds (||S||_2 = 1), the solver passes its estimate of the
+  // bottom of the spectrum when it has one
   KTimer none;
   if (!tm) tm = &none;
-  const double lo = -1.0;  // ||S||_2 = 1
   const double c = 0.5 * (a + lo), e = 0.5 * (a - lo);
   const double bytes = 12.0 * (double)nnz + 8.0 * (double)(n + 1) + (val_scaled ? 0.0 : 8.0 * (double)n) +
                        16.0 * (double)n * b;
@@ -782,6 +783,7 @@ struct Solver {
   uint64_t seed;
   const double* v0 = nullptr;  // caller's start vector (caller's numbering), or null
   bool no_late_projection = std::getenv("SCEIG_NO_LATE_PROJECTION") != nullptr;
+  bool no_spectrum_bottom = std::getenv("SCEIG_NO_SPECTRUM_BOTTOM") != nullptr;
   bool no_tentative_step = std::getenv("SCEIG_NO_TENTATIVE_STEP") != nullptr;
   double tentative_min_work = std::getenv("SCEIG_TENTATIVE_MIN_WORK") ? std::atof(std::getenv("SCEIG_TENTATIVE_MIN_WORK")) : 2e7;
   size_t ws_limit = 0;         // > 0: size of the caller's workspace, checked against the estimate once nnz is known
@@ -814,6 +816,16 @@ struct Solver {
   double filt_best = -2.0;  // best lower estimate so far of the largest eigenvalue below the locked cluster
   double filt_ref = 2.0;    // the Ritz value the planned filter is made large at
   double filt_rate = 0.0;   // growth exponent per degree of the planned filter at filt_ref
+  double filt_lo = -1.0;    // lower end of the planned filter's damped interval
+  // Estimate of the bottom of the spectrum of S, from below: the damped interval of the start-block filters is
+  // [spec_lo, a] instead of [-1, a], which shortens the polynomial by a seventh to a fifth on kNN graphs (their
+  // spectra end near -0.3 ... -0.5).  -1 until the first unfiltered steps have shown the smallest Ritz value (an upper
+  // bound of the true bottom; after four block steps it was found 0.11 to 0.17 above it, so 0.25 is taken off); a
+  // Ritz value seen near or below the estimate later lowers it.  An eigenvalue below the estimate is amplified instead
+  // of damped - at worst as much as the wanted ones (x(-1) = -x(1) when the interval is symmetric about 0) -, which
+  // costs block steps, never correctness: the phases converge by their own residual tests.
+  double spec_lo = -1.0;
+  bool spec_lo_set = false;
   bool late_off = false;    // projecting the locked vectors out after the filter has stopped paying (see run())
   int filt_extra = 0;       // degrees added to (or taken from) the planned degree: feedback from the phases' first steps
   sc_stats stats{};
@@ -1041,7 +1053,7 @@ struct Solver {
     double* buf3 = rot.p + 2 * (size_t)n * b;
     if (!val_s.p) HIP_TRY(launch_copy_cols(basis.p, ld, nl, buf1, b, 0, b, n, st));
     const double* res = enqueue_cheb_filter(rowptr, col, val, val_s.p, s.p, n, nnz, b, d, a, z.p, buf1, buf2, buf3,
-                                            avg_deg, longrows.p, nlong, &resident, st, &timer, basis.p + nl, ld);
+                                            avg_deg, longrows.p, nlong, &resident, st, &timer, basis.p + nl, ld, filt_lo);
     stats.spmv_cols += (int64_t)d * b;
     stats.filter_steps += d;
     if (res) HIP_TRY(launch_copy_cols(res, b, 0, basis.p, ld, nl, b, n, st));
@@ -1081,7 +1093,7 @@ struct Solver {
     } else if (!locked && filt_best <= -2.0 && nu >= 1) {
       a = theta[ja - 1 - nlead];
     }
-    const double lo = -1.0;
+    const double lo = spec_lo;
     if (!(a > lo + 0.05) || !(a < th_ref)) return;
     a += 0.03 * (th_ref - a);  // Ritz values approach the eigenvalue they estimate from below
     const double xt = (2.0 * th_ref - a - lo) / (a - lo);
@@ -1094,6 +1106,7 @@ struct Solver {
     const int d = (int)std::ceil(std::log(2.0 * amp) / rate) + filt_extra;
     filt_d = std::min(std::max(d, 2), dmax);
     filt_a = a;
+    filt_lo = lo;
     filt_ref = th_ref;
     filt_rate = rate;
   }
@@ -1199,8 +1212,8 @@ struct Solver {
       }
       if (filtered) {
         if (debug_on())
-          std::fprintf(stderr, "[sceig] t=%.4fs phase %d start block filtered: degree %d, damped interval [-1, %.6f]%s\n",
-                       now_s() - t_begin, stats.phases, filt_d, filt_a,
+          std::fprintf(stderr, "[sceig] t=%.4fs phase %d start block filtered: degree %d, damped interval [%.4f, %.6f]%s\n",
+                       now_s() - t_begin, stats.phases, filt_d, filt_lo, filt_a,
                        late_projection ? ", locked vectors projected out afterwards" : "");
         if (!late_projection)
           (void)enqueue_cgs2(basis.p, n, ld, nl, nl, b, nl, part.p, h1.p, hsum.p, nullptr, 0, nullptr, st, &timer);
@@ -1349,6 +1362,12 @@ struct Solver {
         }
         int lead = 0;
         while (lead < nsel && rho[lead] <= tol) ++lead;
+        if (nreal > 0 && spec_lo > -1.0 && theta[ja - nreal] < spec_lo + 0.02) {
+          // a Ritz value at or below the assumed bottom of the spectrum: the filters have been amplifying there
+          spec_lo = std::max(-1.0, theta[ja - nreal] - 0.1);
+          if (debug_on())
+            std::fprintf(stderr, "[sceig] t=%.4fs spectrum bottom estimate lowered to %.4f\n", now_s() - t_begin, spec_lo);
+        }
         if (phase_rate > 0.0 && steps_in_phase == 1) {
           // Degree feedback.  How much of a filtered random block lies along the wanted directions shrinks as fewer of
           // them remain, so the same polynomial leaves relatively more of the rest: aim the first step's worst wanted
@@ -1408,11 +1427,21 @@ struct Solver {
           // A phase that began from a plain random block (no spectrum estimate was available then): once its Ritz
           // values give one, filter the leading Ritz vectors - a far better start than a random block - and begin
           // the phase anew from the filtered block.
+          if (debug_on())
+            std::fprintf(stderr, "[sceig] smallest Ritz values after %d unfiltered steps: %.4f %.4f %.4f (ghosts %d)\n",
+                         steps_in_phase, theta[ja - nreal], theta[std::min(ja - 1, ja - nreal + 1)],
+                         theta[std::min(ja - 1, ja - nreal + 2)], ja - nreal);
+          if (nreal > 0 && !no_spectrum_bottom && !spec_lo_set) {  // once: later Ritz values can only lower it
+            spec_lo = std::max(-1.0, theta[ja - nreal] - 0.25);
+            if (const char* forced = std::getenv("SCEIG_SPECTRUM_BOTTOM"))  // for tests of a wrong estimate
+              spec_lo = std::min(0.9, std::max(-1.0, std::atof(forced)));
+            spec_lo_set = true;
+          }
           plan_start_filter(theta, ja, std::min(want, nreal), ja - nreal, false);
           if (filt_d > 0) {
             if (debug_on())
               std::fprintf(stderr, "[sceig] t=%.4fs phase %d restarts from its %d leading Ritz vectors filtered: degree %d, "
-                           "damped interval [-1, %.6f]\n", now_s() - t_begin, stats.phases, b, filt_d, filt_a);
+                           "damped interval [%.4f, %.6f]\n", now_s() - t_begin, stats.phases, b, filt_d, filt_lo, filt_a);
             std::vector<int> sel(b);
             for (int t = 0; t < b; ++t) sel[t] = t;
             rotate_into(ja, Y, ycols, sel, nl);

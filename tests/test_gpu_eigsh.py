@@ -287,6 +287,32 @@ def test_start_filter_is_used_on_clustered_workload(B):
     assert np.max(np.abs(lam)) <= 1e-8 and np.max(np.abs(lam2)) <= 1e-8
 
 
+def test_filter_interval_with_a_wrong_spectrum_bottom(B, monkeypatch):
+    """The start-block filters damp [estimate of the spectrum's bottom, a] instead of [-1, a].  Isolated eigenvalues at
+    the bottom (the -1 of a bipartite component, here K_{3,4}: 7 of 12,007 nodes) are found by the first unfiltered
+    steps; what those steps underestimate is the edge of a bulk, by a bounded amount that the margin covers.  This
+    test makes the estimate wrong on purpose (-0.05 and +0.2 where the spectrum ends at -0.3 and -1): the filters then
+    amplify what lies below it, the solver sees Ritz values below its estimate and lowers it, and all k null vectors
+    still come back within the parity bars - a wrong estimate costs block steps, never correctness."""
+    cfg = wl.reduced(wl.CONFIGS[2], n=12000, components=40)
+    g, label, sigma = wl.build_config_graph(cfg, device="cuda")
+    g = wl.disjoint_union(g, wl.complete_bipartite(3, 4))
+    rp, c, v, n = g
+    ncomp, _ = components.component_labels(rp, c, v)
+    assert ncomp == 41
+    basis = components.null_space(rp, c, v)
+    lam0, vec0, code0, stats0 = solve(B, g, 41, 1e-8, block=16)
+    assert code0 == B.SC_OK
+    for forced in ("-0.05", "0.2"):
+        monkeypatch.setenv("SCEIG_SPECTRUM_BOTTOM", forced)
+        lam, vec, code, stats = solve(B, g, 41, 1e-8, block=16)
+        assert code == B.SC_OK and stats["filter_steps"] > 0, stats
+        assert np.max(np.abs(lam)) <= 1e-8
+        assert compare.residual_norms(rp, c, v, lam, vec).max() <= 1e-7
+        assert np.max(compare.containment_defect(vec, basis)) <= 1e-6
+        assert compare.orthonormality_defect(vec) <= 1e-10
+
+
 def test_release_cache_between_calls(B):
     """Workspace blocks are kept between calls; giving them back must not change any later result."""
     g = wl.disjoint_union(*[wl.ring(20 + 3 * t) for t in range(6)])
