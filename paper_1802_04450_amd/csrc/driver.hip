@@ -625,6 +625,26 @@ void plan_resident(const int64_t* rowptr, const int32_t* col, const double* val,
   std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& c) {
     return (int64_t)a.nrows * (a.shape & 15) > (int64_t)c.nrows * (c.shape & 15);
   });
+  {
+    // Workgroups go to the eight XCDs in turn (workgroup i to XCD i mod 8), each XCD with an L2 of its own.  The items
+    // of one block (its column slices) read the same matrix entries, so they are placed eight apart: they run on the
+    // same XCD at about the same time, and what the first fetches the others find in that L2.
+    std::vector<std::vector<Item>> queue(8);
+    size_t q = 0;
+    for (size_t i = 0; i < items.size();) {
+      size_t j = i;
+      while (j < items.size() && items[j].row0 == items[i].row0) ++j;
+      for (size_t t = i; t < j; ++t) queue[q % 8].push_back(items[t]);
+      ++q;
+      i = j;
+    }
+    std::vector<Item> placed;
+    placed.reserve(items.size());
+    for (size_t r = 0; placed.size() < items.size(); ++r)
+      for (int x = 0; x < 8; ++x)
+        if (r < queue[x].size()) placed.push_back(queue[x][r]);
+    items.swap(placed);
+  }
   plan->items.alloc(items.size() * 4);
   HIP_TRY(hipMemcpyAsync(plan->items.p, items.data(), items.size() * sizeof(Item), hipMemcpyHostToDevice, st));
   HIP_TRY(hipStreamSynchronize(st));  // `items` is pageable host memory
