@@ -1788,24 +1788,29 @@ struct KMeans {
     struct EventPair {
       hipEvent_t a, b;
     };
-    std::vector<EventPair> events;
+    struct EventList {  // destroys what it still holds, also when an error unwinds the call
+      std::vector<EventPair> v;
+      ~EventList() {
+        for (EventPair& e : v) {
+          if (e.a) (void)hipEventDestroy(e.a);
+          if (e.b) (void)hipEventDestroy(e.b);
+        }
+      }
+    } events;
     double dist_bytes = 0.0, dist_flops = 0.0;
     for (int it = 0; it < max_iter; ++it) {
       HIP_TRY(launch_fill_int32(changes.p, 1, 0, 0, st));
       HIP_TRY(launch_centroid_operand(c, ldx, k, d, (int)ldx, ct.p, ldc, cnorm.p, st));
       for (int64_t r0 = 0; r0 < n; r0 += chunk) {
         const int64_t rows = std::min<int64_t>(chunk, n - r0);
-        EventPair ev{};
         if (timing) {
-          HIP_TRY(hipEventCreate(&ev.a));
-          HIP_TRY(hipEventCreate(&ev.b));
-          HIP_TRY(hipEventRecord(ev.a, st));
+          events.v.push_back(EventPair{nullptr, nullptr});
+          HIP_TRY(hipEventCreate(&events.v.back().a));
+          HIP_TRY(hipEventCreate(&events.v.back().b));
+          HIP_TRY(hipEventRecord(events.v.back().a, st));
         }
         HIP_TRY(launch_row_gemm(x.p + r0 * ldx, rows, ldx, 0, d, ct.p, (int)ldc, k, 1, 0, sblock.p, ldc, nullptr, st));
-        if (timing) {
-          HIP_TRY(hipEventRecord(ev.b, st));
-          events.push_back(ev);
-        }
+        if (timing) HIP_TRY(hipEventRecord(events.v.back().b, st));
         dist_bytes += 8.0 * ((double)rows * d + (double)rows * k + (double)k * d);
         dist_flops += 2.0 * (double)rows * k * d;
         HIP_TRY(launch_argmin(sblock.p, ldc, rows, k, cnorm.p, labels + r0, changes.p, st));
@@ -1839,15 +1844,13 @@ struct KMeans {
       stats->iterations = iters;
       stats->converged = converged;
       stats->last_changes = last_changes;
-      stats->distance_launches = (int64_t)(timing ? events.size() : 0);
+      stats->distance_launches = (int64_t)(timing ? events.v.size() : 0);
       stats->distance_bytes = dist_bytes;
       stats->distance_flops = dist_flops;
       double td = 0.0;
-      for (EventPair& ev : events) {  // every launch has completed: the stream was synchronized above
+      for (EventPair& ev : events.v) {  // every launch has completed: the stream was synchronized above
         float ms = 0.0f;
         if (hipEventElapsedTime(&ms, ev.a, ev.b) == hipSuccess) td += ms * 1e-3;
-        (void)hipEventDestroy(ev.a);
-        (void)hipEventDestroy(ev.b);
       }
       stats->t_distance = td;
     }
