@@ -711,6 +711,38 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double*
   }
 }
 
+// The coefficient chunk bmat[k0 : k0+kc, n0 : n0+NT*16] (row-major, leading dimension ldb; columns from ncols on
+// and rows from kc to kc16 count as zero) goes into LDS in the order the MFMA operand reads want: the 64 lanes of one
+// MFMA read 64 consecutive doubles.  Every thread first requests a batch of 16 of its elements, with clamped
+// addresses instead of tests round the loads, and only then parks them: one memory latency per batch of 4,096
+// elements.  (Written as a loop of load, test, store per element, the compiler waits for each load before the next
+// is requested: 16 latencies per chunk, more than the chunk's MFMAs take.)
+template <int NT>
+__device__ __forceinline__ void stage_coefficients(double* __restrict__ lds, const double* __restrict__ bmat,
+                                                   int64_t ldb, int k0, int kc, int kc16, int n0, int ncols) {
+  constexpr int BW = NT * 16;
+  constexpr int BATCH = 16;
+  for (int base = 0; base < kc16 * BW; base += kThreads * BATCH) {  // uniform; the LDS chunk holds whole batches
+    double v[BATCH];
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) {
+      const int e = base + u * kThreads + (int)threadIdx.x;
+      const int kk = e / BW, t = e % BW;
+      const int kr = kk < kc ? kk : kc - 1;
+      const int tc = n0 + t < ncols ? n0 + t : ncols - 1;
+      v[u] = bmat[(int64_t)(k0 + kr) * ldb + tc];
+    }
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) {
+      const int e = base + u * kThreads + (int)threadIdx.x;
+      const int kk = e / BW, t = e % BW;
+      const int kt = kk >> 4, rem = kk & 15, gg = rem >> 2, q = rem & 3;
+      const int nt = t >> 4, ii = t & 15;
+      lds[((((kt * 4 + q) * NT + nt) * 4 + gg) << 4) + ii] = (kk < kc && n0 + t < ncols) ? v[u] : 0.0;
+    }
+  }
+}
+
 // --------------------------------------------------------------------------------------------
 // row GEMM  C = A * Bm  (contraction over basis columns), fp64 MFMA, Bm staged through LDS
 // --------------------------------------------------------------------------------------------
@@ -744,14 +776,7 @@ __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__
     const int kc = (kdim - k0) < KC ? (kdim - k0) : KC;
     const int kc16 = (kc + 15) & ~15;
     __syncthreads();
-    for (int e = threadIdx.x; e < kc16 * NT * 16; e += kThreads) {
-      const int kk = e / (NT * 16), t = e % (NT * 16);
-      double v = 0.0;
-      if (kk < kc && n0 + t < ncols) v = bmat[(int64_t)(k0 + kk) * ldb + n0 + t];
-      const int kt = kk >> 4, rem = kk & 15, gg = rem >> 2, q = rem & 3;
-      const int nt = t >> 4, ii = t & 15;
-      lds[((((kt * 4 + q) * NT + nt) * 4 + gg) << 4) + ii] = v;
-    }
+    stage_coefficients<NT>(lds, bmat, ldb, k0, kc, kc16, n0, ncols);
     __syncthreads();
     int kk0 = 0;
     // A wave whose rows all exist runs the trips of the chunk without a branch round any load: the operands of the
@@ -1109,14 +1134,7 @@ __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restric
   const bool single = kdim <= KC;
 
   auto load_chunk = [&](int k0, int kc, int kc16) {
-    for (int e = threadIdx.x; e < kc16 * BW; e += kThreads) {
-      const int kk = e / BW, t = e % BW;
-      double v = 0.0;
-      if (kk < kc && t < b) v = bmat[(int64_t)(k0 + kk) * kPartialPad + t];
-      const int kt = kk >> 4, rem = kk & 15, gg = rem >> 2, q = rem & 3;
-      const int nt = t >> 4, ii = t & 15;
-      lds[((((kt * 4 + q) * NT + nt) * 4 + gg) << 4) + ii] = v;
-    }
+    stage_coefficients<NT>(lds, bmat, kPartialPad, k0, kc, kc16, 0, b);
   };
   if (single) {
     load_chunk(0, kdim, (kdim + 15) & ~15);

@@ -214,13 +214,16 @@ def test_single_vector_product_on_offset_arrays(B, graphs, shift):
         assert torch.all(cbuf[shift + nnz:] == 0) and torch.all(vbuf[:shift] == 0.0)
 
 
-@pytest.mark.parametrize("n,j,b", [(5000, 70, 16), (4099, 130, 8), (3001, 300, 32), (2500, 17, 1), (2000, 64, 4),
-                                   (777, 5, 2), (70000, 200, 16), (140000, 40, 32), (300, 280, 8)])
-def test_cgs2(B, n, j, b):
+@pytest.mark.parametrize("n,j,b,pad", [(5000, 70, 16, 5), (4099, 130, 8, 5), (3001, 300, 32, 5), (2500, 17, 1, 5),
+                                       (2000, 64, 4, 5), (777, 5, 2, 5), (70000, 200, 16, 5), (140000, 40, 32, 5),
+                                       (300, 280, 8, 5),
+                                       # rows of 32-byte multiples: the vector-load paths, as in the solver's basis
+                                       (5000, 72, 16, 8), (3001, 300, 32, 4), (9000, 520, 32, 8)])
+def test_cgs2(B, n, j, b, pad):
     rng = np.random.default_rng(n + j + b)
     q, _ = np.linalg.qr(rng.standard_normal((n, j)))
     w = rng.standard_normal((n, b)) + q @ rng.standard_normal((j, b)) * 3.0
-    ld = j + b + 5
+    ld = j + b + pad
     basis = np.zeros((n, ld))
     basis[:, :j] = q
     basis[:, j:j + b] = w
