@@ -442,6 +442,28 @@ def family_rates(B, survey):
     return out
 
 
+def measured_ceilings(B, torch):
+    """What the box itself reaches on the two resources the contraction kernels use, measured in this run: a plain
+    device copy of 1 GiB (bytes read + written per second) and a launch that issues only fp64 matrix-core instructions.
+    Context for the fractions of the published peaks, not a replacement for them."""
+    src = torch.ones(1 << 27, dtype=torch.float64, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * src.numel() * 8 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    torch.cuda.empty_cache()
+    tf = max(B.sc_probe_fp64_matrix_rate(2048, 4000) for _ in range(2))
+    return {"copy_gbps_read_plus_write": copy_gbps, "copy_frac_of_hbm_peak": copy_gbps / HBM_PEAK_GBS,
+            "fp64_mfma_only_tflops": tf, "fp64_mfma_only_frac_of_peak": tf / FP64_MFMA_PEAK_TFLOPS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -472,6 +494,9 @@ def main():
     ap.add_argument("--knn", action="store_true",
                     help="the k-nearest-neighbour graph construction (Section III-A) on the points of --workload "
                          "(default config 2: n = 100,000, d = 32, k_nn = 20); prints its own JSON line")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="only measure the practical ceilings the roofline fractions can be held against: a plain 1 GiB "
+                         "device copy and a launch of nothing but fp64 matrix-core instructions")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device copy 10 times (calibration of the HBM traffic counters)")
     args = ap.parse_args()
@@ -483,6 +508,11 @@ def main():
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         sys.exit(2)
+    if args.ceilings:
+        from paper_1802_04450_amd import binding as B
+        B.lib()
+        print(json.dumps({"measured_ceilings": measured_ceilings(B, torch)}))
+        return
     if args.copy_probe:
         src = torch.ones(1 << 27, dtype=torch.float64, device="cuda")      # 1 GiB
         dst = torch.empty_like(src)
@@ -556,7 +586,8 @@ def main():
                            "algorithmic_bytes_per_launch": stats["fam_bytes"][dom] / max(1, launches),
                            "fp64_tflops": stats["fam_flops"][dom] / kt / 1e12,
                            "fp64_mfma_frac": stats["fam_flops"][dom] / kt / 1e12 / FP64_MFMA_PEAK_TFLOPS,
-                           "family_seconds_per_step": {B.FAMILIES[f]: fam_t[f] for f in range(6)}}
+                           "family_seconds_per_step": {B.FAMILIES[f]: fam_t[f] for f in range(6)},
+                           "measured_ceilings": measured_ceilings(B, torch)}
     # every kernel family of the survey solve (all of them event-timed): achieved HBM rate by the byte model and fp64
     # rate against the matrix peak; "project" and "update" are the reorthogonalization GEMMs
     rates = family_rates(B, survey)

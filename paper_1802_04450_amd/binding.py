@@ -31,7 +31,7 @@ EXPORTS = ["sc_laplacian_eigsh", "sc_degree_scaling", "sc_spmm_normalized", "sc_
            "sc_chebyshev_filter", "sc_kmeanspp", "sc_kmeans_lloyd", "sc_kmeans", "sc_edge_similarity", "sc_knn_search", "sc_knn_union_pairs",
            "sc_coo_to_csr", "sc_workspace_bytes", "sc_scale_operator", "sc_laplacian_eigsh_ws",
            "sc_block_qr_noalloc", "sc_counter",
-           "sc_spmv_normalized_chain"]
+           "sc_spmv_normalized_chain", "sc_probe_fp64_matrix_rate"]
 
 
 class ScOptions(ctypes.Structure):
@@ -121,6 +121,7 @@ def lib() -> ctypes.CDLL:
         _lib.sc_version.argtypes = []
         _lib.sc_release_cache.argtypes = []
         _lib.sc_counter.argtypes = [ctypes.c_int32]
+        _lib.sc_probe_fp64_matrix_rate.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), vp]
         _lib.sc_counter.restype = ctypes.c_int64
     return _lib
 
@@ -131,6 +132,13 @@ SC_COUNTER_RESIDENT_FILTERS = 0
 def sc_counter(which: int) -> int:
     """Process-wide event counter of the library (host only)."""
     return int(lib().sc_counter(which))
+
+
+def sc_probe_fp64_matrix_rate(workgroups: int = 2048, iterations: int = 4000) -> float:
+    """TFLOP/s of a launch that issues only fp64 matrix-core instructions (the practical ceiling of that rate)."""
+    out = ctypes.c_double(0.0)
+    _check(lib().sc_probe_fp64_matrix_rate(workgroups, iterations, ctypes.byref(out), _stream()))
+    return float(out.value)
 
 
 def sc_release_cache() -> int:

@@ -1710,6 +1710,29 @@ __global__ __launch_bounds__(kTestThreads) void second_pass_test_kernel(const do
   if (threadIdx.x == 0) skip[0] = need ? 0 : 1;
 }
 
+// Measurement aid: nothing but fp64 matrix-core instructions, eight independent 16x16 accumulators per wave, no
+// memory traffic inside the loop.  What this reaches is the practical ceiling of the fp64 MFMA rate on the device the
+// contraction kernels above can be held against (the published peak assumes the highest clock).
+__global__ __launch_bounds__(kThreads) void mfma_rate_kernel(double* __restrict__ sink, int iters, double a0, double b0) {
+  d4 acc[8];
+#pragma unroll
+  for (int x = 0; x < 8; ++x) acc[x] = (d4){0.0, 0.0, 0.0, 0.0};
+  const double a = a0 + 1e-9 * (double)threadIdx.x, b = b0;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int x = 0; x < 8; ++x) acc[x] = MFMA_F64(a, b, acc[x]);
+  }
+  double sum = 0.0;
+#pragma unroll
+  for (int x = 0; x < 8; ++x) sum += acc[x][0] + acc[x][1] + acc[x][2] + acc[x][3];
+  sink[(int64_t)blockIdx.x * kThreads + threadIdx.x] = sum;
+}
+
+hipError_t launch_mfma_rate(double* sink, int workgroups, int iters, hipStream_t st) {
+  hipLaunchKernelGGL(mfma_rate_kernel, dim3((unsigned)workgroups), dim3(kThreads), 0, st, sink, iters, 1.0, 1e-3);
+  return hipGetLastError();
+}
+
 hipError_t launch_second_pass_test(const double* h, int ja, int b, const double* gram, double ratio2, int* skip,
                                    hipStream_t st) {
   hipLaunchKernelGGL(second_pass_test_kernel, dim3(1), dim3(kTestThreads), 0, st, h, ja, b, gram, ratio2, skip);

@@ -475,3 +475,14 @@ def test_chebyshev_filter_rejects_bad_arguments(B):
     for a, d in ((1.0, 3), (-1.0, 3), (0.3, 0)):
         with pytest.raises(B.ScError):
             B.sc_chebyshev_filter(drp, dc, dv, x, a, d)
+
+
+def test_fp64_matrix_rate_probe(B):
+    """The measurement aid runs, reports a rate that the published fp64 matrix peak bounds, and refuses bad arguments."""
+    import ctypes
+    rate = B.sc_probe_fp64_matrix_rate(512, 500)
+    assert 1.0 < rate <= 78.6 * 1.05, rate
+    out = ctypes.c_double(0.0)
+    assert B.lib().sc_probe_fp64_matrix_rate(0, 10, ctypes.byref(out), 0) == B.SC_EDOMAIN
+    assert B.lib().sc_probe_fp64_matrix_rate(8, 0, ctypes.byref(out), 0) == B.SC_EDOMAIN
+    assert B.lib().sc_probe_fp64_matrix_rate(8, 8, None, 0) == B.SC_EINVAL
