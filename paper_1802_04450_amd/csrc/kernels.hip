@@ -1044,19 +1044,29 @@ __global__ __launch_bounds__(kThreads) void gather_cols_colmajor_kernel(const do
   __shared__ double tile[64][65];
   const int64_t i0 = (int64_t)blockIdx.x * 64;
   const int c0 = blockIdx.y * 64;
-  for (int idx = threadIdx.x; idx < 64 * 64; idx += kThreads) {
-    const int r = idx / 64, c = idx % 64;
-    if (i0 + r < n && c0 + c < ncols) {
-      const int64_t src = inv ? (int64_t)inv[i0 + r] : i0 + r;
-      tile[c][r] = basis[src * ld + c0 + c];
-    }
+  // thread (c, rq) takes column c0 + c of the rows i0 + rq + 4u, u < 16.  All sixteen source rows are looked up, then
+  // all sixteen basis entries requested, with clamped addresses instead of tests round the loads, and only then
+  // parked: two memory latencies per tile (written as one loop of look-up, load and store the compiler waits for
+  // every load before it requests the next: thirty-two latencies).
+  const int c = threadIdx.x % 64, rq = threadIdx.x / 64;
+  const int cc = c0 + c < ncols ? c0 + c : ncols - 1;
+  int64_t src[16];
+#pragma unroll
+  for (int u = 0; u < 16; ++u) {
+    const int64_t row = i0 + rq + 4 * u < n ? i0 + rq + 4 * u : n - 1;
+    src[u] = inv ? (int64_t)inv[row] : row;
   }
+  double v[16];
+#pragma unroll
+  for (int u = 0; u < 16; ++u) v[u] = basis[src[u] * ld + cc];
+#pragma unroll
+  for (int u = 0; u < 16; ++u) tile[c][rq + 4 * u] = v[u];
   __syncthreads();
   for (int idx = threadIdx.x; idx < 64 * 64; idx += kThreads) {
-    const int c = idx / 64, r = idx % 64;
-    if (i0 + r < n && c0 + c < ncols) {
-      const int p = pos[c0 + c];
-      if (p >= 0) out[(int64_t)p * n + i0 + r] = tile[c][r];
+    const int oc = idx / 64, r = idx % 64;
+    if (i0 + r < n && c0 + oc < ncols) {
+      const int p = pos[c0 + oc];
+      if (p >= 0) out[(int64_t)p * n + i0 + r] = tile[oc][r];
     }
   }
 }
