@@ -823,6 +823,11 @@ struct Solver {
   std::vector<int32_t> comp_host;   // component index of each internal row (only after reorder())
   int ncomp = 0;
   PinnedBuf<double> slots_host;
+  // pinned staging for the small coefficient blocks of a rotation (locking b Ritz vectors): the upload then needs no
+  // wait on the host.  ystage_busy: an upload from it may still be in flight (cleared by the next wait on the stream).
+  PinnedBuf<double> ystage;
+  static constexpr size_t kYStageDoubles = 16384;
+  bool ystage_busy = false;
   int64_t ld = 0;
   int max_slots = 0;
   size_t yd_cap = 0, rot_cols = 0;
@@ -1009,6 +1014,7 @@ struct Solver {
     max_slots = m / b + 4;
     slots.alloc((size_t)max_slots * kSlotDoubles);
     slots_host.alloc((size_t)max_slots * kSlotDoubles);
+    ystage.alloc(kYStageDoubles);
     rot_cols = (size_t)std::min(m, std::max(m / 2 + b, 2 * b));
     rot.alloc((size_t)n * rot_cols);
     yd_cap = (size_t)(m + b) * std::max<size_t>(rot_cols, (size_t)k);
@@ -1061,6 +1067,7 @@ struct Solver {
     HIP_TRY(hipMemcpyAsync(slots_host.p + (size_t)first * kSlotDoubles, slots.p + (size_t)first * kSlotDoubles,
                            (size_t)count * kSlotDoubles * sizeof(double), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
+    ystage_busy = false;
   }
 
   // Start-block filter.  The block at columns [nl, nl+b) (orthonormal, its s-scaled packed copy in z) is replaced
@@ -1135,16 +1142,27 @@ struct Solver {
   void rotate_into(int ja, const std::vector<double>& ymat, int ycols, const std::vector<int>& sel, int dst) {
     const int l = (int)sel.size();
     if (l == 0) return;
-    std::vector<double> yl((size_t)ja * l);
+    if ((size_t)ja * l > yd_cap || (size_t)l > rot_cols) SC_THROW(SC_EDOMAIN);
+    const size_t count = (size_t)ja * l;
+    const bool staged = count <= kYStageDoubles;  // small blocks go through pinned memory: nothing to wait for
+    std::vector<double> ybig;
+    if (staged && ystage_busy) {
+      HIP_TRY(hipStreamSynchronize(st));
+      ystage_busy = false;
+    }
+    if (!staged) ybig.resize(count);
+    double* yl = staged ? ystage.p : ybig.data();
     for (int r = 0; r < ja; ++r)
       for (int t = 0; t < l; ++t) yl[(size_t)r * l + t] = ymat[(size_t)r * ycols + sel[t]];
-    if ((size_t)ja * l > yd_cap || (size_t)l > rot_cols) SC_THROW(SC_EDOMAIN);
-    HIP_TRY(hipMemcpyAsync(yd.p, yl.data(), yl.size() * sizeof(double), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(yd.p, yl, count * sizeof(double), hipMemcpyHostToDevice, st));
     timer.begin(kFamRotate);
     HIP_TRY(launch_row_gemm(basis.p, n, ld, nl, ja, yd.p, l, l, 1, 0, rot.p, l, nullptr, st));
     timer.end(kFamRotate, 8.0 * (double)n * (ja + l), 2.0 * (double)n * ja * l);
     HIP_TRY(launch_copy_cols(rot.p, l, 0, basis.p, ld, dst, l, n, st));
-    HIP_TRY(hipStreamSynchronize(st));  // yl (pageable host memory) must stay alive until the copy is done
+    if (staged)
+      ystage_busy = true;
+    else
+      HIP_TRY(hipStreamSynchronize(st));  // ybig (pageable host memory) must stay alive until the copy is done
   }
 
   // drop locked column `idx` by moving the last locked column into its place
