@@ -966,11 +966,16 @@ __global__ __launch_bounds__(kThreads) void apply_rinv_kernel(double* __restrict
   for (int e = threadIdx.x; e < b * b; e += kThreads) Ri[e / b][e % b] = rinv[(e / b) * kPartialPad + (e % b)];
   const int rows_per_block = kThreads / b;
   const int t = threadIdx.x % b, rl = threadIdx.x / b;
+  // the entry of the next trip is requested before this trip's sums, so its latency hides behind them
+  const int64_t first = (int64_t)blockIdx.x * kRinvTrips * rows_per_block + rl;
+  double ahead = first < n ? basis[first * ld + col0 + t] : 0.0;
   for (int trip = 0; trip < kRinvTrips; ++trip) {
     const int64_t row = ((int64_t)blockIdx.x * kRinvTrips + trip) * rows_per_block + rl;
     __syncthreads();  // the tile of the trip before has been read (and, first time round, R^-1 is staged)
-    Wt[rl * (b + 1) + t] = row < n ? basis[row * ld + col0 + t] : 0.0;
+    Wt[rl * (b + 1) + t] = ahead;
     __syncthreads();
+    const int64_t nrow = row + rows_per_block;
+    ahead = (trip + 1 < kRinvTrips && nrow < n) ? basis[nrow * ld + col0 + t] : 0.0;
     double acc = 0.0;
     for (int q = 0; q <= t; ++q) acc += Wt[rl * (b + 1) + q] * Ri[q][t];
     if (row < n) {
