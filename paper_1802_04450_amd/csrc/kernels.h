@@ -45,7 +45,8 @@ hipError_t launch_spmv_chain(const int64_t* rowptr, const int32_t* col, const do
 struct ProjectPlan {
   int rows_per_panel;  // multiple of 4
   int nwc;             // waves of a workgroup laid along the columns (1, 2 or 4)
-  int npart;           // number of partial blocks produced = panels * (4 / nwc)
+  int npart;           // number of partial blocks produced = row panels (one per workgroup: waves that share a
+                       // column tile add their sums inside the workgroup)
 };
 ProjectPlan plan_project(int64_t n, int ja, int max_partials);
 // part[p][c][t] (c < ja, t < kPartialPad) = sum over the rows of partial p of A[i, acol0 + c] * B[i, bcol0 + t]

@@ -557,8 +557,9 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const double* __restr
   const int nwr = 4 / nwc;
   const int wc = wave % nwc, wr = wave / nwc;
   const int c0 = ((int)blockIdx.y * nwc + wc) * 64;
-  if (c0 >= ja) return;  // wave-uniform; no barriers in this kernel
-  const int pidx = (int)blockIdx.x * nwr + wr;
+  // wave-uniform; happens only with four column tiles per workgroup (nwr = 1), where no barrier follows
+  if (c0 >= ja) return;
+  const int pidx = (int)blockIdx.x;  // one partial block per workgroup: waves that share a column tile are summed below
   const int sub = rows_per_panel / nwr;
   const int64_t r0 = (int64_t)blockIdx.x * rows_per_panel + (int64_t)wr * sub;
   int64_t r1 = r0 + sub;
@@ -649,6 +650,33 @@ __global__ __launch_bounds__(kThreads) void project_kernel(const double* __restr
         for (int q = 0; q < 4; ++q) acc[nt][q] = MFMA_F64(a[u][q], bv[u][nt], acc[nt][q]);
   }
 
+  if (nwr > 1) {
+    // Few basis columns: the workgroup's waves have taken row slices of the same column tile.  Their sums are added
+    // here, in wave order, instead of being written as partial blocks of their own: with one partial block per wave
+    // the limit on partial blocks left a short contraction with two waves per compute unit.
+    extern __shared__ double red[];  // (nwr - 1) * nwc slots of 16 * NT values per lane
+    constexpr int SLOT = 16 * NT * 64;
+    if (wr > 0) {
+      double* mine = red + (size_t)((wr - 1) * nwc + wc) * SLOT + lane;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) mine[((nt * 4 + q) * 4 + rr) * 64] = acc[nt][q][rr];
+    }
+    __syncthreads();
+    if (wr > 0) return;
+    for (int w = 1; w < nwr; ++w) {
+      const double* theirs = red + (size_t)((w - 1) * nwc + wc) * SLOT + lane;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) acc[nt][q][rr] += theirs[((nt * 4 + q) * 4 + rr) * 64];
+    }
+  }
   double* out = part + (int64_t)pidx * ja * kPartialPad;
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt)
@@ -1614,28 +1642,34 @@ ProjectPlan plan_project(int64_t n, int ja, int max_partials) {
   const int nwr = 4 / p.nwc;
   const int coltiles = (ja + 64 * p.nwc - 1) / (64 * p.nwc);
   // about 768 workgroups in total (three per compute unit), at least 16 rows per wave slice, and no
-  // more partial blocks than the reduction is meant to sum
+  // more partial blocks (one per workgroup and column tile group) than the reduction is meant to sum
   int64_t panels = 768 / coltiles;
   if (panels < 16) panels = 16;
-  if (panels * nwr > max_partials) panels = max_partials / nwr;
+  if (panels > max_partials) panels = max_partials;
   int64_t rows = ceil_div64(n, panels);
   rows = ceil_div64(rows, 16 * nwr) * 16 * nwr;
   p.rows_per_panel = (int)rows;
-  p.npart = (int)(ceil_div64(n, rows) * nwr);
+  p.npart = (int)ceil_div64(n, rows);
   return p;
 }
 
 hipError_t launch_project(const double* basis, int64_t n, int64_t ld, int acol0, int ja, int bcol0, int b,
                           const ProjectPlan& plan, double* part, hipStream_t st, const int* skip) {
   if (ja <= 0) return hipSuccess;
-  const int panels = plan.npart / (4 / plan.nwc);
+  const int panels = plan.npart;
   const dim3 grid((unsigned)panels, (unsigned)((ja + 64 * plan.nwc - 1) / (64 * plan.nwc)));
   const int vec_ok = (ld % 4 == 0 && acol0 % 4 == 0 && (reinterpret_cast<uintptr_t>(basis) % 32 == 0)) ? 1 : 0;
+  // waves that share a column tile (fewer than four tiles per workgroup) add their sums through LDS; the kernel's
+  // barrier needs every wave of such a workgroup to have a tile, which one tile group (ja <= 64 * nwc) guarantees
+  const int nwr = 4 / plan.nwc;
+  if (nwr > 1 && ja > 64 * plan.nwc) return hipErrorInvalidValue;
+  const int nt = b <= 16 ? 1 : 2;
+  const size_t lds = nwr > 1 ? (size_t)(nwr - 1) * plan.nwc * 16 * nt * 64 * sizeof(double) : 0;
   if (b <= 16) {
-    hipLaunchKernelGGL((project_kernel<1>), grid, dim3(kThreads), 0, st, basis, n, ld, acol0, ja, bcol0, b,
+    hipLaunchKernelGGL((project_kernel<1>), grid, dim3(kThreads), lds, st, basis, n, ld, acol0, ja, bcol0, b,
                        plan.rows_per_panel, plan.nwc, vec_ok, part, skip);
   } else {
-    hipLaunchKernelGGL((project_kernel<2>), grid, dim3(kThreads), 0, st, basis, n, ld, acol0, ja, bcol0, b,
+    hipLaunchKernelGGL((project_kernel<2>), grid, dim3(kThreads), lds, st, basis, n, ld, acol0, ja, bcol0, b,
                        plan.rows_per_panel, plan.nwc, vec_ok, part, skip);
   }
   return hipGetLastError();
