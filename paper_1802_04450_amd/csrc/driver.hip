@@ -1138,7 +1138,7 @@ struct Solver {
     filt_rate = rate;
   }
 
-  // out (n x l row-major in rot) = basis[:, nl : nl+ja] * Y[:, sel]; then copied to basis[:, dst : dst+l]
+  // basis[:, dst : dst+l] = basis[:, nl : nl+ja] * Y[:, sel] (through the rotation workspace when l > 64)
   void rotate_into(int ja, const std::vector<double>& ymat, int ycols, const std::vector<int>& sel, int dst) {
     const int l = (int)sel.size();
     if (l == 0) return;
@@ -1156,9 +1156,14 @@ struct Solver {
       for (int t = 0; t < l; ++t) yl[(size_t)r * l + t] = ymat[(size_t)r * ycols + sel[t]];
     HIP_TRY(hipMemcpyAsync(yd.p, yl, count * sizeof(double), hipMemcpyHostToDevice, st));
     timer.begin(kFamRotate);
-    HIP_TRY(launch_row_gemm(basis.p, n, ld, nl, ja, yd.p, l, l, 1, 0, rot.p, l, nullptr, st));
+    if (l <= 64) {
+      // one wave holds all l results of a row before it stores any: straight into the basis, also over its own inputs
+      HIP_TRY(launch_row_gemm(basis.p, n, ld, nl, ja, yd.p, l, l, 3, dst, nullptr, 0, nullptr, st));
+    } else {
+      HIP_TRY(launch_row_gemm(basis.p, n, ld, nl, ja, yd.p, l, l, 1, 0, rot.p, l, nullptr, st));
+    }
     timer.end(kFamRotate, 8.0 * (double)n * (ja + l), 2.0 * (double)n * ja * l);
-    HIP_TRY(launch_copy_cols(rot.p, l, 0, basis.p, ld, dst, l, n, st));
+    if (l > 64) HIP_TRY(launch_copy_cols(rot.p, l, 0, basis.p, ld, dst, l, n, st));
     if (staged)
       ystage_busy = true;
     else

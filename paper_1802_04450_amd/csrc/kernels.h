@@ -70,6 +70,8 @@ hipError_t launch_second_pass_test(const double* h, int ja, int b, const double*
 // mode 0: basis[:, ccol0 + t] -= C[:, t]          (in place update, ncols <= 32, out unused)
 // mode 1: out[i*ldo + t]  = C[i, t]                (row-major)
 // mode 2: out[t*ldo + r(i)] = C[i, t]             (column-major; r(i) = rowmap[i] if rowmap != null, else i)
+// mode 3: basis[:, ccol0 + t] = C[:, t]           (ncols <= 64, out unused; the columns written may be among the
+//         columns read: one wave owns all ncols entries of its rows and stores them after its last read of those rows)
 hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int ldb,
                            int ncols, int mode, int ccol0, double* out, int64_t ldo, const int32_t* rowmap,
                            hipStream_t st, const int* skip = nullptr);

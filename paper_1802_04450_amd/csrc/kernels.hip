@@ -904,6 +904,8 @@ __global__ __launch_bounds__(kThreads) void row_gemm_kernel(double* __restrict__
           const double v = acc[mt][nt][rr];
           if (mode == 0) {
             basis[row * ld + ccol0 + t] -= v;
+          } else if (mode == 3) {
+            basis[row * ld + ccol0 + t] = v;
           } else if (mode == 1) {
             out[row * ldo + t] = v;
           } else {
@@ -1700,7 +1702,7 @@ hipError_t launch_row_gemm(double* basis, int64_t n, int64_t ld, int acol0, int 
   } else if (ncols <= 32) {
     if (pipe) SC_LAUNCH_RG(2, true, 1); else SC_LAUNCH_RG(2, false, 1);
   } else {
-    if (mode == 0) return hipErrorInvalidValue;
+    if (mode == 0 || (mode == 3 && ncols > 64)) return hipErrorInvalidValue;
     const unsigned gy = (unsigned)((ncols + 63) / 64);
     if (pipe) SC_LAUNCH_RG(4, true, gy); else SC_LAUNCH_RG(4, false, gy);
   }
