@@ -805,6 +805,7 @@ struct Solver {
   bool no_late_projection = std::getenv("SCEIG_NO_LATE_PROJECTION") != nullptr;
   bool no_spectrum_bottom = std::getenv("SCEIG_NO_SPECTRUM_BOTTOM") != nullptr;
   bool no_tentative_step = std::getenv("SCEIG_NO_TENTATIVE_STEP") != nullptr;
+  bool no_resident_product = std::getenv("SCEIG_NO_RESIDENT_PRODUCT") != nullptr;
   double tentative_min_work = std::getenv("SCEIG_TENTATIVE_MIN_WORK") ? std::atof(std::getenv("SCEIG_TENTATIVE_MIN_WORK")) : 2e7;
   size_t ws_limit = 0;         // > 0: size of the caller's workspace, checked against the estimate once nnz is known
   hipStream_t st;
@@ -868,7 +869,13 @@ struct Solver {
   }
   // y (row-major, leading dimension ldy) = S x for the block whose packed operand is in z
   void spmm_from_z(double* y, int64_t ldy) {
-    if (val_s.p) {
+    if (val_s.p && resident.usable && resident.rest_row0 >= n && !no_resident_product) {
+      // every diagonal block has work items of the LDS-resident form: a single product is that form's recurrence
+      // with one step (u+ = 1 * (S u - 0 * u) - 0), read from LDS instead of gathered out of L2
+      HIP_TRY(launch_cheb_resident(rowptr, col, val_s.p, z.p, y, ldy, b, 1, 1.0, 1.0, 0.0, resident.items.p,
+                                   resident.nitems, resident.lds_bytes, resident.scol.p, resident.sval.p,
+                                   resident.slice_base.p, resident.slice_len.p, st));
+    } else if (val_s.p) {
       HIP_TRY(launch_spmm_vals(rowptr, col, val_s.p, n, z.p, b, y, ldy, avg_deg, longrows.p, nlong, st));
     } else {
       HIP_TRY(launch_spmm(rowptr, col, val, s.p, n, z.p, b, y, ldy, avg_deg, st));
