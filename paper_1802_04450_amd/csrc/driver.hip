@@ -787,6 +787,30 @@ int reorder_csr(const int64_t* rowptr, const int32_t* col, const double* val, in
   return ncomp;
 }
 
+// The projected matrix of a phase: m x m with a fixed leading dimension, zero pages from the system until touched.
+// Only the leading square that has been written since the last clear() is cleared again (a phase rarely assembles more
+// than a few blocks, while m x m can be 128 MB).
+struct ProjectedMatrix {
+  double* a = nullptr;
+  size_t ld = 0;
+  int hi = 0;  // rows and columns >= hi are zero
+  ProjectedMatrix() = default;
+  ProjectedMatrix(const ProjectedMatrix&) = delete;
+  ProjectedMatrix& operator=(const ProjectedMatrix&) = delete;
+  void init(int m) {
+    a = static_cast<double*>(std::calloc((size_t)m * m, sizeof(double)));
+    if (!a) throw std::bad_alloc();
+    ld = (size_t)m;
+  }
+  double& at(int x, int y) { return a[(size_t)x * ld + y]; }
+  void touch(int extent) { hi = std::max(hi, std::min(extent, (int)ld)); }
+  void clear() {
+    for (int x = 0; x < hi; ++x) std::memset(a + (size_t)x * ld, 0, sizeof(double) * hi);
+    hi = 0;
+  }
+  ~ProjectedMatrix() { std::free(a); }
+};
+
 struct Solver {
   // problem
   const int64_t* rowptr;
@@ -1207,7 +1231,9 @@ struct Solver {
     int prev_phase_steps = 0, prev_filtered_steps = 0;
     uint64_t stream_id = 0;
 
-    std::vector<double> T, Tsub, Y;
+    ProjectedMatrix T;
+    T.init(m);
+    std::vector<double> Tsub, Y;
     SelectedEig seig;
     int ycols = 0;
     std::vector<char> ghost;
@@ -1285,7 +1311,7 @@ struct Solver {
       int next_slot = 1;     // slot 0 = start block QR
       int fetched = 0;       // slots already on the host
       int steps_in_phase = 0;
-      T.assign((size_t)cap * cap, 0.0);
+      T.clear();
       ghost.assign((size_t)cap + b, 0);
       bool start_block_seen = false;
       int pending = 0;
@@ -1338,6 +1364,7 @@ struct Solver {
           continue;
         }
         // ---- inspect: bring the slots over and assemble T
+        T.touch(ja + b);
         fetch_slots(fetched, next_slot - fetched);
         fetched = next_slot;
         if (!start_block_seen) {
@@ -1353,11 +1380,11 @@ struct Solver {
           const double* A = hslot(q);
           for (int x = 0; x < b; ++x)
             for (int y = 0; y < b; ++y)
-              T[(size_t)(c0 + x) * cap + c0 + y] = 0.5 * (A[x * kPP + y] + A[y * kPP + x]);
+              T.at(c0 + x, c0 + y) = 0.5 * (A[x * kPP + y] + A[y * kPP + x]);
           for (int x = 0; x < b; ++x)
             if (ghost[c0 + x]) {
-              for (int y = 0; y < e; ++y) T[(size_t)(c0 + x) * cap + y] = T[(size_t)y * cap + c0 + x] = 0.0;
-              T[(size_t)(c0 + x) * cap + c0 + x] = -2.0;
+              for (int y = 0; y < e; ++y) T.at(c0 + x, y) = T.at(y, c0 + x) = 0.0;
+              T.at(c0 + x, c0 + x) = -2.0;
             }
           assembled = e;
           if (q + 1 < next_slot) {
@@ -1366,8 +1393,8 @@ struct Solver {
             for (int x = 0; x < b; ++x) {
               ghost[e + x] = (R[x * kPP + x] == 0.0);
               for (int y = 0; y < b; ++y) {
-                T[(size_t)(e + x) * cap + c0 + y] = R[x * kPP + y];
-                T[(size_t)(c0 + y) * cap + e + x] = R[x * kPP + y];
+                T.at(e + x, c0 + y) = R[x * kPP + y];
+                T.at(c0 + y, e + x) = R[x * kPP + y];
               }
             }
           }
@@ -1376,7 +1403,7 @@ struct Solver {
         // ---- Ritz pairs of T[0:ja, 0:ja]: all values, vectors only for the leading ones that may be used
         const double te0 = now_s();
         Tsub.resize((size_t)ja * ja);
-        for (int x = 0; x < ja; ++x) std::memcpy(&Tsub[(size_t)x * ja], &T[(size_t)x * cap], sizeof(double) * ja);
+        for (int x = 0; x < ja; ++x) std::memcpy(&Tsub[(size_t)x * ja], &T.at(x, 0), sizeof(double) * ja);
         if (seig.factor(Tsub.data(), ja) != 0) SC_THROW(SC_EHIP);
         const std::vector<double>& theta = seig.values();
         const double* Rl = hslot(next_slot - 1) + kPP * kPP;
@@ -1461,7 +1488,7 @@ struct Solver {
           fetched = 1;  // slot 0 (the start block's QR) is on the host already
           pending = 0;
           steps_in_phase = 0;
-          std::fill(T.begin(), T.end(), 0.0);
+          T.clear();
           std::fill(ghost.begin() + b, ghost.end(), 0);
           next_check = 1;
           last_rho = -1.0;
@@ -1507,7 +1534,7 @@ struct Solver {
             next_slot = 1;
             fetched = 0;
             steps_in_phase = 0;
-            std::fill(T.begin(), T.end(), 0.0);
+            T.clear();
             std::fill(ghost.begin(), ghost.end(), 0);
             start_block_seen = false;
             next_check = prev_filtered_steps > 1 ? prev_filtered_steps - 1 : 1;
@@ -1577,16 +1604,17 @@ struct Solver {
           rotate_into(ja, Y, ycols, sel, nl);
           HIP_TRY(launch_copy_cols(basis.p, ld, nl + ja, rot.p, b, 0, b, n, st));
           HIP_TRY(launch_copy_cols(rot.p, b, 0, basis.p, ld, nl + l, b, n, st));
-          std::fill(T.begin(), T.end(), 0.0);
+          T.clear();
+          T.touch(l + b);
           std::fill(ghost.begin(), ghost.end(), 0);
-          for (int t = 0; t < l; ++t) T[(size_t)t * cap + t] = theta[ja - 1 - t];
+          for (int t = 0; t < l; ++t) T.at(t, t) = theta[ja - 1 - t];
           for (int x = 0; x < b; ++x) {
             ghost[l + x] = (Rl[x * kPP + x] == 0.0);
             for (int t = 0; t < l; ++t) {
               double c = 0.0;
               for (int y = 0; y < b; ++y) c += Rl[x * kPP + y] * Y[(size_t)(ja - b + y) * ycols + t];
-              T[(size_t)(l + x) * cap + t] = c;
-              T[(size_t)t * cap + l + x] = c;
+              T.at(l + x, t) = c;
+              T.at(t, l + x) = c;
             }
           }
           ja = l + b;
@@ -1606,8 +1634,8 @@ struct Solver {
           for (int x = 0; x < b; ++x) {
             ghost[e + x] = (R[x * kPP + x] == 0.0);
             for (int y = 0; y < b; ++y) {
-              T[(size_t)(e + x) * cap + c0 + y] = R[x * kPP + y];
-              T[(size_t)(c0 + y) * cap + e + x] = R[x * kPP + y];
+              T.at(e + x, c0 + y) = R[x * kPP + y];
+              T.at(c0 + y, e + x) = R[x * kPP + y];
             }
           }
           ja += b;
