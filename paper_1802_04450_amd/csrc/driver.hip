@@ -1452,7 +1452,9 @@ struct Solver {
           // overshoots by more than a degree and a half).  The target is tol / 8, except where the floor described at
           // the phase start would otherwise reach tol before the end: it is proportional to the residuals the vectors
           // were locked with, so tol / 100 (two or three more degrees) keeps it down.  That is bought only where the
-          // passes over the locked vectors are what a phase costs (tight_target).
+          // passes over the locked vectors are what a phase costs (tight_target).  With the wider target a miss of half
+          // a degree already counts: tol / 8 less one degree (a factor 3 to 4) is within the spread between the columns
+          // of one block, and a pair that misses tol costs two further block steps, a degree one product.
           double rw = 0.0;
           for (int t = 0; t < std::min(want, nsel); ++t) rw = std::max(rw, rho[t]);
           if (rw > 0.0) {
@@ -1460,7 +1462,7 @@ struct Solver {
             const double need = std::log(rw / target) / phase_rate;
             if (late_projection && rw > 0.5 * tol)
               late_off = true;  // the floor, not the polynomial: more degrees would not help
-            else if (need > 1.0)
+            else if (need > (late_projection && tight_target ? 1.0 : 0.5))  // see above
               filt_extra = std::min(filt_extra + (int)std::ceil(need), 6);
             else if (need < -1.5)
               filt_extra = std::max(filt_extra - 1, -4);
