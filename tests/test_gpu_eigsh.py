@@ -287,6 +287,33 @@ def test_start_filter_is_used_on_clustered_workload(B):
     assert np.max(np.abs(lam)) <= 1e-8 and np.max(np.abs(lam2)) <= 1e-8
 
 
+def test_block_products_through_the_resident_form(B, monkeypatch):
+    """Where every diagonal block of the renumbered operator has work items of the LDS-resident filter, the single
+    products of the block steps run as a one-step recurrence of that form.  Both ways of multiplying must pass the
+    parity bars against the component oracle and agree with each other to the tolerance."""
+    cfg = wl.reduced(wl.CONFIGS[5], n=16000, components=64)
+    g, label, sigma = wl.build_config_graph(cfg, device="cuda")
+    rp, c, v, n = g
+    basis = components.null_space(rp, c, v)
+    k = basis.shape[1]
+    assert 64 <= k <= 80
+    monkeypatch.setenv("SCEIG_FORCE_RESIDENT", "1")   # small graph: the cost model would leave the form out
+    results = []
+    for off in (False, True):
+        if off:
+            monkeypatch.setenv("SCEIG_NO_RESIDENT_PRODUCT", "1")
+        before = B.sc_counter(B.SC_COUNTER_RESIDENT_FILTERS)
+        lam, vec, code, stats = solve(B, g, k, 1e-9, block=16)
+        assert code == B.SC_OK and stats["block_steps"] > 0, stats
+        assert B.sc_counter(B.SC_COUNTER_RESIDENT_FILTERS) > before       # the resident plan was in use
+        assert np.max(np.abs(lam)) <= 1e-9
+        assert compare.residual_norms(rp, c, v, lam, vec).max() <= 1e-8
+        assert np.max(compare.containment_defect(vec, basis)) <= 1e-7
+        assert compare.orthonormality_defect(vec) <= 1e-10
+        results.append(lam)
+    assert np.max(np.abs(results[0] - results[1])) <= 1e-9
+
+
 def test_filter_interval_with_a_wrong_spectrum_bottom(B, monkeypatch):
     """The start-block filters damp [estimate of the spectrum's bottom, a] instead of [-1, a].  Isolated eigenvalues at
     the bottom (the -1 of a bipartite component, here K_{3,4}: 7 of 12,007 nodes) are found by the first unfiltered
