@@ -337,7 +337,7 @@ int pow2_floor(int x) {
 // passes the number of locked vectors here: the block's components along locked eigenvectors are of the order of
 // their residuals, so removing them once involves no cancellation, whereas the active Krylov vectors, which take
 // most of the block's norm away, get the second pass.
-// slot_a (may be null) receives rows [slot_row0, j) of hsum.  If gpart != null the second update also leaves
+// slot_a (may be null) receives rows [slot_row0, j) of hsum after the last pass.  If gpart != null the last update also leaves
 // the Gram partials of the updated block there; returns their count (0 if none were produced).
 // first_from > 0: the first pass too leaves the columns before it alone (the solver's tentative first step).
 constexpr int kWideUpdate = 256;  // contraction lengths from which update + separate Gram beats the fused kernel
@@ -362,12 +362,12 @@ int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, i
     tm->begin(kFamProject);
     HIP_TRY(launch_project(basis, n, ld, c0, jc, wcol, b, plan, part, st));
     tm->end(kFamProject, 8.0 * rows * (jc + b), 2.0 * rows * jc * b);
+    const bool last_pass = pass == 1 || j - second_from <= 0;  // the last update leaves the Gram partials
     tm->begin(kFamOther);
     HIP_TRY(launch_reduce_partials(part, plan.npart, jc, b, h1, hsum + (size_t)c0 * kPP, pass,
-                                   pass == 1 ? slot_a : nullptr, slot_row0 - c0, st));
+                                   last_pass ? slot_a : nullptr, slot_row0 - c0, st));
     tm->end(kFamOther, 8.0 * plan.npart * (double)jc * b, 0.0);
     tm->begin(kFamUpdate);
-    const bool last_pass = pass == 1 || j - second_from <= 0;  // the last update leaves the Gram partials
     if (last_pass && gpart && jc >= kWideUpdate) {
       // against many columns the plain update is the faster kernel (more waves in flight: at n = 500,000 and 1,024
       // columns 995 against 1,300 us), and the Gram partials of the updated block cost one pass over the block alone
@@ -830,6 +830,7 @@ struct Solver {
   bool no_spectrum_bottom = std::getenv("SCEIG_NO_SPECTRUM_BOTTOM") != nullptr;
   bool no_tentative_step = std::getenv("SCEIG_NO_TENTATIVE_STEP") != nullptr;
   bool no_resident_product = std::getenv("SCEIG_NO_RESIDENT_PRODUCT") != nullptr;
+  bool tentative_two_passes = std::getenv("SCEIG_TENTATIVE_TWO_PASSES") != nullptr;
   double tentative_min_work = std::getenv("SCEIG_TENTATIVE_MIN_WORK") ? std::atof(std::getenv("SCEIG_TENTATIVE_MIN_WORK")) : 2e7;
   size_t ws_limit = 0;         // > 0: size of the caller's workspace, checked against the estimate once nnz is known
   hipStream_t st;
@@ -1075,8 +1076,11 @@ struct Solver {
     spmm_from_z(basis.p + jt, ld);
     timer.end(kFamSpmm, spmm_bytes(), 2.0 * (double)nnz * b);
     double* sl = slot(si);
-    const int ngram = enqueue_cgs2(basis.p, n, ld, jt, jt, b, nl, part.p, h1.p, hsum.p, sl, jt - b, gpart.p, st, &timer,
-                                   tentative ? nl : 0);
+    // A tentative step makes one Gram-Schmidt pass, not two: its block never joins the basis, so the orthogonality a
+    // second pass would restore is not needed, and the residual block W - V (V^T W) itself comes out of one pass to
+    // rounding relative to W (1e-16 of a block of norm one, against residuals of the size of tol).
+    const int ngram = enqueue_cgs2(basis.p, n, ld, jt, jt, b, tentative && !tentative_two_passes ? jt : nl, part.p, h1.p,
+                                   hsum.p, sl, jt - b, gpart.p, st, &timer, tentative ? nl : 0);
     if (tentative && ngram > 0) {
       // Only the Gram matrix of the residual block is looked at (residual estimates; a block that vanished): the
       // block is not orthonormalized, since it either is dropped with the phase or built again.  The slot of the QR
