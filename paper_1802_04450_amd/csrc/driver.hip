@@ -340,11 +340,13 @@ int pow2_floor(int x) {
 // slot_a (may be null) receives rows [slot_row0, j) of hsum after the last pass.  If gpart != null the last update also leaves
 // the Gram partials of the updated block there; returns their count (0 if none were produced).
 // first_from > 0: the first pass too leaves the columns before it alone (the solver's tentative first step).
+// gram_only: the last update (against fewer than kWideUpdate columns) is made for the Gram partials alone and the block
+// itself is not stored back (a block that will be dropped or built again).
 constexpr int kWideUpdate = 256;  // contraction lengths from which update + separate Gram beats the fused kernel
 
 int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, int second_from, double* part,
                  double* h1, double* hsum, double* slot_a, int slot_row0, double* gpart, hipStream_t st, KTimer* tm,
-                 int first_from = 0) {
+                 int first_from = 0, bool gram_only = false) {
   if (j <= 0) return 0;
   KTimer none;
   if (!tm) tm = &none;
@@ -376,7 +378,7 @@ int enqueue_cgs2(double* basis, int64_t n, int64_t ld, int j, int wcol, int b, i
       HIP_TRY(launch_project(basis, n, ld, wcol, b, wcol, b, gplan, gpart, st));
       ngram = gplan.npart;
     } else if (last_pass && gpart) {
-      HIP_TRY(launch_update_gram(basis, n, ld, c0, jc, h1, b, wcol, 0, gpart, st));
+      HIP_TRY(launch_update_gram(basis, n, ld, c0, jc, h1, b, wcol, gram_only ? 2 : 0, gpart, st));
       ngram = plan_update_gram(n);
     } else {
       HIP_TRY(launch_row_gemm(basis, n, ld, c0, jc, h1, kPP, b, 0, wcol, nullptr, 0, nullptr, st));
@@ -1079,8 +1081,9 @@ struct Solver {
     // A tentative step makes one Gram-Schmidt pass, not two: its block never joins the basis, so the orthogonality a
     // second pass would restore is not needed, and the residual block W - V (V^T W) itself comes out of one pass to
     // rounding relative to W (1e-16 of a block of norm one, against residuals of the size of tol).
-    const int ngram = enqueue_cgs2(basis.p, n, ld, jt, jt, b, tentative && !tentative_two_passes ? jt : nl, part.p, h1.p,
-                                   hsum.p, sl, jt - b, gpart.p, st, &timer, tentative ? nl : 0);
+    const bool one_pass = tentative && !tentative_two_passes;
+    const int ngram = enqueue_cgs2(basis.p, n, ld, jt, jt, b, one_pass ? jt : nl, part.p, h1.p, hsum.p, sl, jt - b, gpart.p,
+                                   st, &timer, tentative ? nl : 0, one_pass && b < kWideUpdate);
     if (tentative && ngram > 0) {
       // Only the Gram matrix of the residual block is looked at (residual estimates; a block that vanished): the
       // block is not orthonormalized, since it either is dropped with the phase or built again.  The slot of the QR

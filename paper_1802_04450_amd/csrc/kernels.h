@@ -94,8 +94,9 @@ hipError_t launch_apply_rinv(double* basis, int64_t n, int64_t ld, int col0, int
 //                gpart[p] (b x b, row stride kPartialPad, p < plan_update_gram(n)) = partial Gram matrices of the
 //                updated block, to be summed with launch_reduce_partials(gpart, npart, b, b, ...).
 int plan_update_gram(int64_t n);
-// overwrite != 0: the block is replaced by the product instead of having it subtracted (W <- W R^-1 with
-// acol0 = ccol0, kdim = b, bmat = R^-1)
+// overwrite = 1: the block is replaced by the product instead of having it subtracted (W <- W R^-1 with
+// acol0 = ccol0, kdim = b, bmat = R^-1); overwrite = 2: the product is subtracted for the Gram matrix only, the block
+// in memory stays as it is
 hipError_t launch_update_gram(double* basis, int64_t n, int64_t ld, int acol0, int kdim, const double* bmat, int b,
                               int ccol0, int overwrite, double* gpart, hipStream_t st, const int* skip = nullptr);
 // ---- Chebyshev filter with the iterates resident in LDS (resident.hip) -------------------------------

@@ -1307,8 +1307,8 @@ __global__ __launch_bounds__(kThreads) void update_gram_kernel(double* __restric
           double nv = 0.0;
           if (row < n && t < b) {
             double* p = basis + row * ld + ccol0 + t;
-            nv = overwrite ? acc[mt][nt][rr] : *p - acc[mt][nt][rr];
-            *p = nv;
+            nv = overwrite == 1 ? acc[mt][nt][rr] : *p - acc[mt][nt][rr];
+            if (overwrite != 2) *p = nv;  // 2: only the Gram matrix of the updated block is wanted
           }
           wt[lr * WP + t] = nv;
         }
