@@ -667,7 +667,7 @@ double* enqueue_cheb_filter(const int64_t* rowptr, const int32_t* col, const dou
                             const double* s, int64_t n, int64_t nnz, int b, int d, double a, double* z, double* buf1,
                             double* buf2, double* buf3, double avg_deg, const int32_t* longrows, int nlong,
                             const ResidentPlan* resident, hipStream_t st, KTimer* tm, double* direct = nullptr,
-                            int64_t direct_ld = 0, double lo = -1.0) {
+                            int64_t direct_ld = 0, double lo = -1.0, int d32 = 0) {
   // lo: lower end of the damped interval; -1 always holds (||S||_2 = 1), the solver passes its estimate of the
   // bottom of the spectrum when it has one
   KTimer none;
@@ -684,7 +684,7 @@ double* enqueue_cheb_filter(const int64_t* rowptr, const int32_t* col, const dou
     tm->begin(kFamSpmm);
     HIP_TRY(launch_cheb_resident(rowptr, col, val_scaled, z, out, ldo, b, d, 1.0 / e, 2.0 / e, c, resident->items.p,
                                  resident->nitems, resident->lds_bytes, resident->scol.p, resident->sval.p,
-                                 resident->slice_base.p, resident->slice_len.p, st));
+                                 resident->slice_base.p, resident->slice_len.p, st, d32));
     const int64_t r0 = resident->rest_row0;
     if (r0 < n) {
       // the blocks without an item: the recurrence step by step on their rows alone (their iterates rotate through the
@@ -832,6 +832,11 @@ struct Solver {
   bool no_spectrum_bottom = std::getenv("SCEIG_NO_SPECTRUM_BOTTOM") != nullptr;
   bool no_tentative_step = std::getenv("SCEIG_NO_TENTATIVE_STEP") != nullptr;
   bool no_resident_product = std::getenv("SCEIG_NO_RESIDENT_PRODUCT") != nullptr;
+  // A start-block filter only prepares a block whose Ritz pairs the Lanczos step then tests in double precision.  In
+  // its one-launch form all steps but the last filter_tail64 run in single precision (half the LDS traffic that bounds
+  // the form): the later steps damp what the rounding of the earlier ones adds along the unwanted directions.
+  // SCEIG_FILTER_FP64_TAIL = a number larger than any degree keeps every step in double precision.
+  int filter_tail64 = std::getenv("SCEIG_FILTER_FP64_TAIL") ? std::atoi(std::getenv("SCEIG_FILTER_FP64_TAIL")) : 6;
   bool tentative_two_passes = std::getenv("SCEIG_TENTATIVE_TWO_PASSES") != nullptr;
   double tentative_min_work = std::getenv("SCEIG_TENTATIVE_MIN_WORK") ? std::atof(std::getenv("SCEIG_TENTATIVE_MIN_WORK")) : 2e7;
   size_t ws_limit = 0;         // > 0: size of the caller's workspace, checked against the estimate once nnz is known
@@ -1117,8 +1122,14 @@ struct Solver {
     double* buf2 = rot.p + (size_t)n * b;
     double* buf3 = rot.p + 2 * (size_t)n * b;
     if (!val_s.p) HIP_TRY(launch_copy_cols(basis.p, ld, nl, buf1, b, 0, b, n, st));
+    // double-precision steps at the end: as many as damp the unwanted directions by 2,000 against the wanted ones at
+    // the planned growth per degree (single-precision rounding, 6e-8, then ends below 1e-10), and at least six
+    int tail = filter_tail64;
+    if (filt_rate > 0.0) tail = std::max(tail, (int)std::ceil(std::log(2000.0) / filt_rate));
+    const int d32 = d > tail + 1 ? d - tail : 0;
     const double* res = enqueue_cheb_filter(rowptr, col, val, val_s.p, s.p, n, nnz, b, d, a, z.p, buf1, buf2, buf3,
-                                            avg_deg, longrows.p, nlong, &resident, st, &timer, basis.p + nl, ld, filt_lo);
+                                            avg_deg, longrows.p, nlong, &resident, st, &timer, basis.p + nl, ld, filt_lo,
+                                            d32);
     stats.spmv_cols += (int64_t)d * b;
     stats.filter_steps += d;
     if (res) HIP_TRY(launch_copy_cols(res, b, 0, basis.p, ld, nl, b, n, st));

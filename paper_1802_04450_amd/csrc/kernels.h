@@ -123,10 +123,12 @@ hipError_t launch_block_extra_chunks(const int64_t* rowptr, const int32_t* start
 // A sliced item (cl = 1; the word's upper bits carry the item's first slice, not a chunk count) covers 8 columns of a
 // block of up to 65,535 rows and reads its entries from the sliced copy (scol, sval, slice_base, slice_len; null when
 // no item is sliced).
+// d32 (0 <= d32 < d): the first d32 steps of the items with cl = 2 or 4 run in single precision (iterates and entries
+// rounded to float), the rest in double; sliced items take all steps in double.  0 gives the recurrence in double.
 hipError_t launch_cheb_resident(const int64_t* rowptr, const int32_t* col, const double* val, const double* x, double* y,
                                 int64_t ldy, int b, int d, double alpha_first, double alpha_rest, double shift, const int32_t* items,
                                 int nitems, size_t lds_bytes, const uint16_t* scol, const double* sval,
-                                const int64_t* slice_base, const int32_t* slice_len, hipStream_t st);
+                                const int64_t* slice_base, const int32_t* slice_len, hipStream_t st, int d32 = 0);
 // Sliced copy of diagonal blocks for the sliced form.  A slice is up to resident_slice_rows() consecutive rows of one
 // block: slice_row0 / slice_rows (device int32[nslices]) name its rows, slice_blk0 / slice_blk_rows its block.
 // sliced_copy_layout fills slice_len (longest row), slice_entries (int64[nslices + 1]: entries the slice takes in the

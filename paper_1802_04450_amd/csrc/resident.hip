@@ -67,6 +67,18 @@ template <int CTRL>
 __device__ __forceinline__ double dpp_double(double v) {
   return __hiloint2double(dpp_int<CTRL>(__double2hiint(v)), dpp_int<CTRL>(__double2loint(v)));
 }
+template <int CTRL>
+__device__ __forceinline__ float dpp_float(float v) {
+  return __int_as_float(dpp_int<CTRL>(__float_as_int(v)));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_value(double v) { return dpp_double<CTRL>(v); }
+template <int CTRL>
+__device__ __forceinline__ float dpp_value(float v) { return dpp_float<CTRL>(v); }
+// two adjacent columns of an iterate, in the precision of the step
+template <typename T> struct Pair;
+template <> struct Pair<double> { using type = double2; };
+template <> struct Pair<float> { using type = float2; };
 // quad permute that gives every lane of a CL-lane group the value held by the group's lane Q
 template <int CL, int Q>
 struct GroupBcast {
@@ -78,7 +90,7 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
                                               const double* __restrict__ val, const double* __restrict__ x,
                                               double* __restrict__ y, int64_t ldy, int b, int d, double alpha_first,
                                               double alpha_rest, double shift, int row0, int nr, int col0, int nx,
-                                              unsigned char* smem) {
+                                              unsigned char* smem, int d32) {
   constexpr int BS = 8 * CL;     // columns of the item
   constexpr int CH = kRK * CL;   // entries per chunk
   constexpr int G = kRT / CL;    // lane groups
@@ -98,11 +110,18 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
   const int nnz_local = (int)(rowptr[row0 + nr] - ebase);
 
   // ---- stage: row pointers relative to the block's first entry, chunk counts, u = the slice of x, u- = 0
+  // (the first d32 steps run in single precision, on float iterates that take the first half of each buffer)
   for (int r = tid; r <= nr; r += kRT) rpl[r] = (int)(rowptr[row0 + r] - ebase);
   for (int idx = tid; idx < nr * BS; idx += kRT) {
     const int r = idx / BS, t = idx - r * BS;
-    bufa[idx] = x[(int64_t)(row0 + r) * b + col0 + t];
-    bufb[idx] = 0.0;
+    const double xv = x[(int64_t)(row0 + r) * b + col0 + t];
+    if (d32 > 0) {  // uniform
+      reinterpret_cast<float*>(bufa)[idx] = (float)xv;
+      reinterpret_cast<float*>(bufb)[idx] = 0.0f;
+    } else {
+      bufa[idx] = xv;
+      bufb[idx] = 0.0;
+    }
   }
   __syncthreads();
   for (int r = tid; r < nr; r += kRT) {
@@ -182,25 +201,39 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
     krounds[sl] = __builtin_amdgcn_readfirstlane(need);
   }
 
-  double* cur = bufa;
-  double* prev = bufb;
-  for (int step = 0; step < d; ++step) {
-    const double alpha = step == 0 ? alpha_first : alpha_rest;
-    const double beta = step == 0 ? 0.0 : 1.0;
-    const double2* __restrict__ cur2 = reinterpret_cast<const double2*>(cur);
-    double2* prev2 = reinterpret_cast<double2*>(prev);
+  // The steps [s0, s1) of the recurrence in the precision of `tag` (double or float), on iterates of that type in
+  // the two buffers (their first halves for float); returns the buffer that holds the last iterate.
+  float kaf[kRS][kRK];  // the entries once more in single precision
+#pragma unroll
+  for (int sl = 0; sl < kRS; ++sl)
+#pragma unroll
+    for (int k = 0; k < kRK; ++k) kaf[sl][k] = (float)ka[sl][k];
+  auto run_steps = [&](auto tag, int s0, int s1, void* bcur, void* bprev) __attribute__((always_inline)) -> void* {
+  using T = decltype(tag);
+  using T2 = typename Pair<T>::type;
+  T* cur = static_cast<T*>(bcur);
+  T* prev = static_cast<T*>(bprev);
+  T* partt = reinterpret_cast<T*>(part);
+  for (int step = s0; step < s1; ++step) {
+    const T alpha = (T)(step == 0 ? alpha_first : alpha_rest);
+    const T beta = step == 0 ? (T)0 : (T)1;
+    const T shiftt = (T)shift;
+    const T2* __restrict__ cur2 = reinterpret_cast<const T2*>(cur);
+    T2* prev2 = reinterpret_cast<T2*>(prev);
 #pragma unroll
     for (int sl = 0; sl < kRS; ++sl) {
       if (krounds[sl] == 0) continue;  // no lane of this wave has a chunk in this slot
-      double acc[8];
+      T acc[8];
 #pragma unroll
-      for (int t = 0; t < 8; ++t) acc[t] = 0.0;
+      for (int t = 0; t < 8; ++t) acc[t] = (T)0;
 #define SC_RES_ENTRY(K, Q)                                                                   \
   if constexpr (Q < CL) {                                                                    \
     const int cb = dpp_int<GroupBcast<CL, Q>::ctrl>(kc[sl][K]);                              \
-    const double ab = dpp_double<GroupBcast<CL, Q>::ctrl>(ka[sl][K]);                        \
-    const double2* zp = cur2 + cb * RW;                                                      \
-    const double2 z0 = zp[pc0], z1 = zp[pc1], z2 = zp[pc2], z3 = zp[pc3];                    \
+    T av_;                                                                                   \
+    if constexpr (sizeof(T) == 4) av_ = (T)kaf[sl][K]; else av_ = (T)ka[sl][K];              \
+    const T ab = dpp_value<GroupBcast<CL, Q>::ctrl>(av_);                                    \
+    const T2* zp = cur2 + cb * RW;                                                           \
+    const T2 z0 = zp[pc0], z1 = zp[pc1], z2 = zp[pc2], z3 = zp[pc3];                         \
     acc[0] += ab * z0.x;                                                                     \
     acc[1] += ab * z0.y;                                                                     \
     acc[2] += ab * z1.x;                                                                     \
@@ -230,22 +263,22 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
       const int r = crow[sl];
       if (r >= 0) {
         if (cidx[sl] == 0) {  // first chunk of its row: the recurrence with this chunk's sum, stored over u-
-          const double2* own = cur2 + r * RW;
-          double2* out = prev2 + r * RW;
+          const T2* own = cur2 + r * RW;
+          T2* out = prev2 + r * RW;
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
             const int at = pcs[t];
-            const double2 o = own[at], pv = out[at];
-            double2 w;
-            w.x = alpha * (acc[2 * t] - shift * o.x) - beta * pv.x;
-            w.y = alpha * (acc[2 * t + 1] - shift * o.y) - beta * pv.y;
+            const T2 o = own[at], pv = out[at];
+            T2 w;
+            w.x = alpha * (acc[2 * t] - shiftt * o.x) - beta * pv.x;
+            w.y = alpha * (acc[2 * t + 1] - shiftt * o.y) - beta * pv.y;
             out[at] = w;
           }
         } else {  // a further chunk: its sum waits in LDS for the row's owner
-          double2* out = reinterpret_cast<double2*>(part) + (size_t)(g + sl * G - r - 1) * RW;
+          T2* out = reinterpret_cast<T2*>(partt) + (size_t)(g + sl * G - r - 1) * RW;
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
-            double2 w;
+            T2 w;
             w.x = acc[2 * t];
             w.y = acc[2 * t + 1];
             out[pcs[t]] = w;
@@ -260,24 +293,24 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
         const int r = crow[sl];
         if (r >= 0 && cidx[sl] == 0 && cnum[sl] > 1) {
           // the row's further chunks are chunks cst[r] + 1 ... of the block; chunk v parks at slot v - row(v) - 1
-          const double2* src = reinterpret_cast<const double2*>(part) + (size_t)(g + sl * G - r) * RW;
-          double2 sum[4];
+          const T2* src = reinterpret_cast<const T2*>(partt) + (size_t)(g + sl * G - r) * RW;
+          T2 sum[4];
 #pragma unroll
           for (int t = 0; t < 4; ++t) sum[t] = src[pcs[t]];
           for (int j = 2; j < cnum[sl]; ++j) {
-            const double2* more = src + (size_t)(j - 1) * RW;
+            const T2* more = src + (size_t)(j - 1) * RW;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-              const double2 mo = more[pcs[t]];
+              const T2 mo = more[pcs[t]];
               sum[t].x += mo.x;
               sum[t].y += mo.y;
             }
           }
-          double2* out = prev2 + r * RW;
+          T2* out = prev2 + r * RW;
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
             const int at = pcs[t];
-            double2 w = out[at];
+            T2 w = out[at];
             w.x += alpha * sum[t].x;
             w.y += alpha * sum[t].y;
             out[at] = w;
@@ -286,9 +319,41 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
       }
     }
     __syncthreads();  // every row of the new iterate is in place; nobody reads the old u- any more
-    double* t = cur;
+    T* t = cur;
     cur = prev;
     prev = t;
+  }
+  return cur;
+  };
+  double* cur = bufa;
+  if (d32 > 0) {
+    // Single-precision steps first.  What their rounding adds to an iterate has components along every eigenvector,
+    // and the steps that follow damp the unwanted ones like everything else below the interval's end: by the last six
+    // double-precision steps they are back below what double precision leaves (measured on the first-step residuals:
+    // no difference from six such steps on, a factor 5 at four).
+    const bool in_b = run_steps(0.0f, 0, d32, bufa, bufb) == static_cast<void*>(bufb);
+    // both iterates from float to double, each inside its own buffer: everything is read before anything is written
+    constexpr int PER = 10;  // nr * BS <= 10,240 (two double iterates fit the LDS)
+    float ta[PER], tb[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int idx = tid + u * kRT;
+      ta[u] = idx < nr * BS ? reinterpret_cast<const float*>(bufa)[idx] : 0.0f;
+      tb[u] = idx < nr * BS ? reinterpret_cast<const float*>(bufb)[idx] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int idx = tid + u * kRT;
+      if (idx < nr * BS) {
+        bufa[idx] = (double)ta[u];
+        bufb[idx] = (double)tb[u];
+      }
+    }
+    __syncthreads();
+    cur = static_cast<double*>(run_steps(0.0, d32, d, in_b ? bufb : bufa, in_b ? bufa : bufb));
+  } else {
+    cur = static_cast<double*>(run_steps(0.0, 0, d, bufa, bufb));
   }
   for (int idx = tid; idx < nr * BS; idx += kRT) {
     const int r = idx / BS, t = idx - r * BS;
@@ -462,14 +527,14 @@ __global__ __launch_bounds__(kRT) void cheb_resident_kernel(const int64_t* __res
                                                             const uint16_t* __restrict__ scol,
                                                             const double* __restrict__ sval,
                                                             const int64_t* __restrict__ slice_base,
-                                                            const int32_t* __restrict__ slice_len) {
+                                                            const int32_t* __restrict__ slice_len, int d32) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int32_t* it = items + 4 * (int64_t)blockIdx.x;
   const int row0 = it[0], nr = it[1], col0 = it[2], cl = it[3] & 15, nx = it[3] >> 4;  // uniform over the workgroup
   if (cl == 4)
-    resident_item<4>(rowptr, col, val, x, y, ldy, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem);
+    resident_item<4>(rowptr, col, val, x, y, ldy, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem, d32);
   else if (cl == 2)
-    resident_item<2>(rowptr, col, val, x, y, ldy, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem);
+    resident_item<2>(rowptr, col, val, x, y, ldy, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem, d32);
   else if (cl == 1)  // sliced form: the item's last word carries its first slice instead of a chunk count
     resident_item_sliced(scol, sval, slice_base, slice_len, x, y, ldy, b, d, alpha_first, alpha_rest, shift, row0, nr, col0,
                          nx, smem);
@@ -704,13 +769,14 @@ hipError_t diagonal_blocks(const int64_t* rowptr, const int32_t* col, int64_t n,
 hipError_t launch_cheb_resident(const int64_t* rowptr, const int32_t* col, const double* val, const double* x, double* y,
                                 int64_t ldy, int b, int d, double alpha_first, double alpha_rest, double shift, const int32_t* items,
                                 int nitems, size_t lds_bytes, const uint16_t* scol, const double* sval,
-                                const int64_t* slice_base, const int32_t* slice_len, hipStream_t st) {
+                                const int64_t* slice_base, const int32_t* slice_len, hipStream_t st, int d32) {
   if (nitems <= 0 || d <= 0) return hipSuccess;
+  if (d32 < 0 || d32 >= d) return hipErrorInvalidValue;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cheb_resident_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(cheb_resident_kernel, dim3((unsigned)nitems), dim3(kRT), lds_bytes, st, rowptr, col, val, x, y, ldy, b, d,
-                     alpha_first, alpha_rest, shift, items, scol, sval, slice_base, slice_len);
+                     alpha_first, alpha_rest, shift, items, scol, sval, slice_base, slice_len, d32);
   return hipGetLastError();
 }
 
