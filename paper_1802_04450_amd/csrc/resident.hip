@@ -38,6 +38,7 @@
 
 #include <cstdint>
 #include <cstring>
+#include <type_traits>
 
 #include <rocprim/device/device_scan.hpp>
 #include <rocprim/functional.hpp>
@@ -208,18 +209,27 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
   for (int sl = 0; sl < kRS; ++sl)
 #pragma unroll
     for (int k = 0; k < kRK; ++k) kaf[sl][k] = (float)ka[sl][k];
-  auto run_steps = [&](auto tag, int s0, int s1, void* bcur, void* bprev) __attribute__((always_inline)) -> void* {
+  // NE = columns per LDS read of a lane (its 8 columns are 8 / NE pieces, CL pieces apart): 2 in double precision
+  // (16-byte reads, four pieces, as described at the top), 4 in single precision (16-byte reads again, two pieces).
+  auto run_steps = [&](auto tag, auto ne_tag, int s0, int s1, void* bcur, void* bprev) __attribute__((always_inline)) -> void* {
   using T = decltype(tag);
-  using T2 = typename Pair<T>::type;
+  constexpr int NE = decltype(ne_tag)::value;
+  constexpr int NP = 8 / NE;      // pieces per lane
+  constexpr int RWv = BS / NE;    // pieces per operand row
+  typedef T TV __attribute__((ext_vector_type(NE)));
   T* cur = static_cast<T*>(bcur);
   T* prev = static_cast<T*>(bprev);
   T* partt = reinterpret_cast<T*>(part);
+  // this lane's t-th piece: segment (t + g) mod NP, position q inside the segment
+  int pv[NP];
+#pragma unroll
+  for (int t = 0; t < NP; ++t) pv[t] = ((g + t) & (NP - 1)) * CL + q;
   for (int step = s0; step < s1; ++step) {
     const T alpha = (T)(step == 0 ? alpha_first : alpha_rest);
     const T beta = step == 0 ? (T)0 : (T)1;
     const T shiftt = (T)shift;
-    const T2* __restrict__ cur2 = reinterpret_cast<const T2*>(cur);
-    T2* prev2 = reinterpret_cast<T2*>(prev);
+    const TV* __restrict__ curv = reinterpret_cast<const TV*>(cur);
+    TV* prevv = reinterpret_cast<TV*>(prev);
 #pragma unroll
     for (int sl = 0; sl < kRS; ++sl) {
       if (krounds[sl] == 0) continue;  // no lane of this wave has a chunk in this slot
@@ -232,16 +242,11 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
     T av_;                                                                                   \
     if constexpr (sizeof(T) == 4) av_ = (T)kaf[sl][K]; else av_ = (T)ka[sl][K];              \
     const T ab = dpp_value<GroupBcast<CL, Q>::ctrl>(av_);                                    \
-    const T2* zp = cur2 + cb * RW;                                                           \
-    const T2 z0 = zp[pc0], z1 = zp[pc1], z2 = zp[pc2], z3 = zp[pc3];                         \
-    acc[0] += ab * z0.x;                                                                     \
-    acc[1] += ab * z0.y;                                                                     \
-    acc[2] += ab * z1.x;                                                                     \
-    acc[3] += ab * z1.y;                                                                     \
-    acc[4] += ab * z2.x;                                                                     \
-    acc[5] += ab * z2.y;                                                                     \
-    acc[6] += ab * z3.x;                                                                     \
-    acc[7] += ab * z3.y;                                                                     \
+    const TV* zp = curv + cb * RWv;                                                          \
+    TV z_[NP];                                                                               \
+    _Pragma("unroll") for (int t = 0; t < NP; ++t) z_[t] = zp[pv[t]];                        \
+    _Pragma("unroll") for (int t = 0; t < NP; ++t)                                           \
+      _Pragma("unroll") for (int e = 0; e < NE; ++e) acc[NE * t + e] += ab * z_[t][e];       \
   }
 #define SC_RES_ROUND(K)               \
   if (K < krounds[sl]) {              \
@@ -263,25 +268,25 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
       const int r = crow[sl];
       if (r >= 0) {
         if (cidx[sl] == 0) {  // first chunk of its row: the recurrence with this chunk's sum, stored over u-
-          const T2* own = cur2 + r * RW;
-          T2* out = prev2 + r * RW;
+          const TV* own = curv + r * RWv;
+          TV* out = prevv + r * RWv;
 #pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            const int at = pcs[t];
-            const T2 o = own[at], pv = out[at];
-            T2 w;
-            w.x = alpha * (acc[2 * t] - shiftt * o.x) - beta * pv.x;
-            w.y = alpha * (acc[2 * t + 1] - shiftt * o.y) - beta * pv.y;
+          for (int t = 0; t < NP; ++t) {
+            const int at = pv[t];
+            const TV o = own[at], pw = out[at];
+            TV w;
+#pragma unroll
+            for (int e = 0; e < NE; ++e) w[e] = alpha * (acc[NE * t + e] - shiftt * o[e]) - beta * pw[e];
             out[at] = w;
           }
         } else {  // a further chunk: its sum waits in LDS for the row's owner
-          T2* out = reinterpret_cast<T2*>(partt) + (size_t)(g + sl * G - r - 1) * RW;
+          TV* out = reinterpret_cast<TV*>(partt) + (size_t)(g + sl * G - r - 1) * RWv;
 #pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            T2 w;
-            w.x = acc[2 * t];
-            w.y = acc[2 * t + 1];
-            out[pcs[t]] = w;
+          for (int t = 0; t < NP; ++t) {
+            TV w;
+#pragma unroll
+            for (int e = 0; e < NE; ++e) w[e] = acc[NE * t + e];
+            out[pv[t]] = w;
           }
         }
       }
@@ -293,26 +298,21 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
         const int r = crow[sl];
         if (r >= 0 && cidx[sl] == 0 && cnum[sl] > 1) {
           // the row's further chunks are chunks cst[r] + 1 ... of the block; chunk v parks at slot v - row(v) - 1
-          const T2* src = reinterpret_cast<const T2*>(partt) + (size_t)(g + sl * G - r) * RW;
-          T2 sum[4];
+          const TV* src = reinterpret_cast<const TV*>(partt) + (size_t)(g + sl * G - r) * RWv;
+          TV sum[NP];
 #pragma unroll
-          for (int t = 0; t < 4; ++t) sum[t] = src[pcs[t]];
+          for (int t = 0; t < NP; ++t) sum[t] = src[pv[t]];
           for (int j = 2; j < cnum[sl]; ++j) {
-            const T2* more = src + (size_t)(j - 1) * RW;
+            const TV* more = src + (size_t)(j - 1) * RWv;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-              const T2 mo = more[pcs[t]];
-              sum[t].x += mo.x;
-              sum[t].y += mo.y;
-            }
+            for (int t = 0; t < NP; ++t) sum[t] += more[pv[t]];
           }
-          T2* out = prev2 + r * RW;
+          TV* out = prevv + r * RWv;
 #pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            const int at = pcs[t];
-            T2 w = out[at];
-            w.x += alpha * sum[t].x;
-            w.y += alpha * sum[t].y;
+          for (int t = 0; t < NP; ++t) {
+            const int at = pv[t];
+            TV w = out[at];
+            w += alpha * sum[t];
             out[at] = w;
           }
         }
@@ -325,13 +325,15 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
   }
   return cur;
   };
+  using Two = std::integral_constant<int, 2>;
+  using Four = std::integral_constant<int, 4>;
   double* cur = bufa;
   if (d32 > 0) {
     // Single-precision steps first.  What their rounding adds to an iterate has components along every eigenvector,
     // and the steps that follow damp the unwanted ones like everything else below the interval's end: by the last six
     // double-precision steps they are back below what double precision leaves (measured on the first-step residuals:
     // no difference from six such steps on, a factor 5 at four).
-    const bool in_b = run_steps(0.0f, 0, d32, bufa, bufb) == static_cast<void*>(bufb);
+    const bool in_b = run_steps(0.0f, Four{}, 0, d32, bufa, bufb) == static_cast<void*>(bufb);
     // both iterates from float to double, each inside its own buffer: everything is read before anything is written
     constexpr int PER = 10;  // nr * BS <= 10,240 (two double iterates fit the LDS)
     float ta[PER], tb[PER];
@@ -351,9 +353,9 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
       }
     }
     __syncthreads();
-    cur = static_cast<double*>(run_steps(0.0, d32, d, in_b ? bufb : bufa, in_b ? bufa : bufb));
+    cur = static_cast<double*>(run_steps(0.0, Two{}, d32, d, in_b ? bufb : bufa, in_b ? bufa : bufb));
   } else {
-    cur = static_cast<double*>(run_steps(0.0, 0, d, bufa, bufb));
+    cur = static_cast<double*>(run_steps(0.0, Two{}, 0, d, bufa, bufb));
   }
   for (int idx = tid; idx < nr * BS; idx += kRT) {
     const int r = idx / BS, t = idx - r * BS;
