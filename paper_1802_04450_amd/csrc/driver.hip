@@ -1126,7 +1126,16 @@ struct Solver {
     // the planned growth per degree (single-precision rounding, 6e-8, then ends below 1e-10), and at least six
     int tail = filter_tail64;
     if (filt_rate > 0.0) tail = std::max(tail, (int)std::ceil(std::log(2000.0) / filt_rate));
-    const int d32 = d > tail + 1 ? d - tail : 0;
+    int d32 = d > tail + 1 ? d - tail : 0;
+    {
+      // no single-precision step may overflow: the polynomial grows fastest at an end of the spectrum, +1 or (when
+      // the damped interval starts too high) -1; the start block's entries are at most 1, float reaches 3e38
+      const double lo = filt_lo;
+      const double xm = std::max(std::fabs((-2.0 - a - lo) / (a - lo)), std::fabs((2.0 - a - lo) / (a - lo)));
+      const double growth = xm > 1.0 ? std::acosh(xm) : 0.0;
+      if (growth > 0.0) d32 = std::min(d32, (int)std::floor(69.0 / growth));  // e^69 = 1e30
+      if (d32 < 1) d32 = 0;
+    }
     const double* res = enqueue_cheb_filter(rowptr, col, val, val_s.p, s.p, n, nnz, b, d, a, z.p, buf1, buf2, buf3,
                                             avg_deg, longrows.p, nlong, &resident, st, &timer, basis.p + nl, ld, filt_lo,
                                             d32);
