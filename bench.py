@@ -459,9 +459,13 @@ def measured_ceilings(B, torch):
     copy_gbps = 5 * 2 * src.numel() * 8 / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del src, dst
     torch.cuda.empty_cache()
-    tf = max(B.sc_probe_fp64_matrix_rate(2048, 4000) for _ in range(2))
+    tf = max(B.sc_probe_fp64_matrix_rate(2048, 4000, 16) for _ in range(2))
+    tf4 = max(B.sc_probe_fp64_matrix_rate(2048, 16000, 4) for _ in range(2))
     return {"copy_gbps_read_plus_write": copy_gbps, "copy_frac_of_hbm_peak": copy_gbps / HBM_PEAK_GBS,
-            "fp64_mfma_only_tflops": tf, "fp64_mfma_only_frac_of_peak": tf / FP64_MFMA_PEAK_TFLOPS}
+            "fp64_mfma_only_tflops": tf, "fp64_mfma_only_frac_of_peak": tf / FP64_MFMA_PEAK_TFLOPS,
+            "fp64_mfma_4x4x4_only_tflops": tf4, "fp64_mfma_4x4x4_only_frac_of_peak": tf4 / FP64_MFMA_PEAK_TFLOPS,
+            "note": "fp64_mfma_only: the 16x16x4 form, which the contraction kernels use; the 4x4x4 form issues faster "
+                    "but needs every operand value in the lanes of all blocks that use it"}
 
 
 def main():

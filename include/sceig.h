@@ -477,13 +477,14 @@ int64_t sc_counter(int32_t which);
 /*
  * Measurement aid (Section V reports rates against the hardware's peaks; this gives the practical one for the fp64
  * matrix cores, which the reorthogonalization, rotation, distance-product and neighbour-search kernels run on).
- * Launches `workgroups` workgroups of four waves that issue nothing but fp64 16x16x4 matrix instructions
- * (iterations * 8 per wave, eight independent accumulators, 2,048 flops per instruction) on `stream`, times the launch
- * with events and stores the rate in TFLOP/s.
+ * Launches `workgroups` workgroups of four waves that issue nothing but fp64 matrix instructions (iterations * 8 per
+ * wave, eight independent accumulators) on `stream`, times the launch with events and stores the rate in TFLOP/s.
+ *   shape       16: the 16x16x4 form (2,048 flops per instruction; the form the library's kernels use),
+ *               4: the 4x4x4 form (four independent 4x4 blocks, 512 flops per instruction); else SC_EDOMAIN
  *   tflops_out  HOST pointer
  *   1 <= workgroups <= 2^20, 1 <= iterations <= 2^24 (else SC_EDOMAIN); the call synchronizes the stream.
  */
-int sc_probe_fp64_matrix_rate(int32_t workgroups, int32_t iterations, double* tflops_out, void* stream);
+int sc_probe_fp64_matrix_rate(int32_t shape, int32_t workgroups, int32_t iterations, double* tflops_out, void* stream);
 
 /*
  * Memory.  Device and pinned-host blocks that a call allocates for itself are kept by the library when the call

@@ -121,7 +121,7 @@ def lib() -> ctypes.CDLL:
         _lib.sc_version.argtypes = []
         _lib.sc_release_cache.argtypes = []
         _lib.sc_counter.argtypes = [ctypes.c_int32]
-        _lib.sc_probe_fp64_matrix_rate.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), vp]
+        _lib.sc_probe_fp64_matrix_rate.argtypes = [i32, i32, i32, ctypes.POINTER(ctypes.c_double), vp]
         _lib.sc_counter.restype = ctypes.c_int64
     return _lib
 
@@ -134,10 +134,11 @@ def sc_counter(which: int) -> int:
     return int(lib().sc_counter(which))
 
 
-def sc_probe_fp64_matrix_rate(workgroups: int = 2048, iterations: int = 4000) -> float:
-    """TFLOP/s of a launch that issues only fp64 matrix-core instructions (the practical ceiling of that rate)."""
+def sc_probe_fp64_matrix_rate(workgroups: int = 2048, iterations: int = 4000, shape: int = 16) -> float:
+    """TFLOP/s of a launch that issues only fp64 matrix-core instructions (the practical ceiling of that rate);
+    shape 16 = the 16x16x4 form, 4 = the 4x4x4 form."""
     out = ctypes.c_double(0.0)
-    _check(lib().sc_probe_fp64_matrix_rate(workgroups, iterations, ctypes.byref(out), _stream()))
+    _check(lib().sc_probe_fp64_matrix_rate(shape, workgroups, iterations, ctypes.byref(out), _stream()))
     return float(out.value)
 
 

@@ -2071,25 +2071,26 @@ int64_t sc_counter(int32_t which) {
   }
 }
 
-int sc_probe_fp64_matrix_rate(int32_t workgroups, int32_t iterations, double* tflops_out, void* stream) {
+int sc_probe_fp64_matrix_rate(int32_t shape, int32_t workgroups, int32_t iterations, double* tflops_out, void* stream) {
   if (!tflops_out) return SC_EINVAL;
+  if (shape != 4 && shape != 16) return SC_EDOMAIN;
   if (workgroups < 1 || workgroups > (1 << 20) || iterations < 1 || iterations > (1 << 24)) return SC_EDOMAIN;
   struct Ctx {
-    int wgs, iters;
+    int shape, wgs, iters;
     double* out;
     hipStream_t st;
-  } ctx{workgroups, iterations, tflops_out, reinterpret_cast<hipStream_t>(stream)};
+  } ctx{shape, workgroups, iterations, tflops_out, reinterpret_cast<hipStream_t>(stream)};
   return guarded(
       [](void* p) {
         Ctx* c = static_cast<Ctx*>(p);
         DevBuf<double> sink;
         sink.alloc((size_t)c->wgs * 256);
         hipEvent_t e0 = nullptr, e1 = nullptr;
-        HIP_TRY(launch_mfma_rate(sink.p, c->wgs, 64, c->st));  // warm-up: code object loaded, clocks up
+        HIP_TRY(launch_mfma_rate(sink.p, c->shape, c->wgs, 64, c->st));  // warm-up: code object loaded, clocks up
         HIP_TRY(hipEventCreate(&e0));
         hipError_t err = hipEventCreate(&e1);
         if (err == hipSuccess) err = hipEventRecord(e0, c->st);
-        if (err == hipSuccess) err = launch_mfma_rate(sink.p, c->wgs, c->iters, c->st);
+        if (err == hipSuccess) err = launch_mfma_rate(sink.p, c->shape, c->wgs, c->iters, c->st);
         if (err == hipSuccess) err = hipEventRecord(e1, c->st);
         if (err == hipSuccess) err = hipEventSynchronize(e1);
         float ms = 0.0f;
@@ -2098,7 +2099,7 @@ int sc_probe_fp64_matrix_rate(int32_t workgroups, int32_t iterations, double* tf
         (void)hipEventDestroy(e0);
         if (e1) (void)hipEventDestroy(e1);
         HIP_TRY(err);
-        const double flops = (double)c->wgs * 4.0 * (double)c->iters * 8.0 * 2048.0;
+        const double flops = (double)c->wgs * 4.0 * (double)c->iters * 8.0 * (c->shape == 16 ? 2048.0 : 512.0);
         *c->out = ms > 0.0f ? flops / ((double)ms * 1e-3) / 1e12 : 0.0;
         return SC_OK;
       },

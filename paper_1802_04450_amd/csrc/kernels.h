@@ -280,8 +280,9 @@ hipError_t coo_to_csr(const int32_t* row, const int32_t* col, const double* val,
                       int symmetrize, void* work, size_t work_bytes, int64_t* rowptr_out, int32_t* col_out,
                       double* val_out, int* bad, hipStream_t st);
 
-// Measurement aid: `workgroups` workgroups of four waves, each wave issuing iters * 8 fp64 16x16x4 MFMAs (2,048 flops
-// each) and nothing else; sink: device, workgroups * 256 doubles.
-hipError_t launch_mfma_rate(double* sink, int workgroups, int iters, hipStream_t st);
+// Measurement aid: `workgroups` workgroups of four waves, each wave issuing iters * 8 fp64 matrix instructions and
+// nothing else; shape 16: 16x16x4 (2,048 flops each), shape 4: 4x4x4 (512 flops each); sink: device, workgroups * 256
+// doubles.
+hipError_t launch_mfma_rate(double* sink, int shape, int workgroups, int iters, hipStream_t st);
 
 }  // namespace sceig

@@ -1761,26 +1761,43 @@ __global__ __launch_bounds__(kTestThreads) void second_pass_test_kernel(const do
   if (threadIdx.x == 0) skip[0] = need ? 0 : 1;
 }
 
-// Measurement aid: nothing but fp64 matrix-core instructions, eight independent 16x16 accumulators per wave, no
-// memory traffic inside the loop.  What this reaches is the practical ceiling of the fp64 MFMA rate on the device the
-// contraction kernels above can be held against (the published peak assumes the highest clock).
+// Measurement aid: nothing but fp64 matrix-core instructions, eight independent accumulators per wave, no memory
+// traffic inside the loop, in either form of the instruction: 16x16x4 (2,048 flops, what the contraction kernels above
+// use: one operand value per lane feeds a 16 x 16 block) or 4x4x4 (four independent 4 x 4 blocks, 512 flops).  What
+// this reaches is the practical ceiling of the fp64 MFMA rate on the device (the published peak assumes the highest
+// clock and the better form).
+template <int SHAPE>
 __global__ __launch_bounds__(kThreads) void mfma_rate_kernel(double* __restrict__ sink, int iters, double a0, double b0) {
   d4 acc[8];
+  double acc1[8];
 #pragma unroll
-  for (int x = 0; x < 8; ++x) acc[x] = (d4){0.0, 0.0, 0.0, 0.0};
+  for (int x = 0; x < 8; ++x) {
+    acc[x] = (d4){0.0, 0.0, 0.0, 0.0};
+    acc1[x] = 0.0;
+  }
   const double a = a0 + 1e-9 * (double)threadIdx.x, b = b0;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int x = 0; x < 8; ++x) acc[x] = MFMA_F64(a, b, acc[x]);
+    for (int x = 0; x < 8; ++x) {
+      if constexpr (SHAPE == 16)
+        acc[x] = MFMA_F64(a, b, acc[x]);
+      else
+        acc1[x] = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, acc1[x], 0, 0, 0);
+    }
   }
   double sum = 0.0;
 #pragma unroll
-  for (int x = 0; x < 8; ++x) sum += acc[x][0] + acc[x][1] + acc[x][2] + acc[x][3];
+  for (int x = 0; x < 8; ++x) sum += acc[x][0] + acc[x][1] + acc[x][2] + acc[x][3] + acc1[x];
   sink[(int64_t)blockIdx.x * kThreads + threadIdx.x] = sum;
 }
 
-hipError_t launch_mfma_rate(double* sink, int workgroups, int iters, hipStream_t st) {
-  hipLaunchKernelGGL(mfma_rate_kernel, dim3((unsigned)workgroups), dim3(kThreads), 0, st, sink, iters, 1.0, 1e-3);
+hipError_t launch_mfma_rate(double* sink, int shape, int workgroups, int iters, hipStream_t st) {
+  if (shape == 16)
+    hipLaunchKernelGGL(mfma_rate_kernel<16>, dim3((unsigned)workgroups), dim3(kThreads), 0, st, sink, iters, 1.0, 1e-3);
+  else if (shape == 4)
+    hipLaunchKernelGGL(mfma_rate_kernel<4>, dim3((unsigned)workgroups), dim3(kThreads), 0, st, sink, iters, 1.0, 1e-3);
+  else
+    return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

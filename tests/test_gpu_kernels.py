@@ -478,11 +478,14 @@ def test_chebyshev_filter_rejects_bad_arguments(B):
 
 
 def test_fp64_matrix_rate_probe(B):
-    """The measurement aid runs, reports a rate that the published fp64 matrix peak bounds, and refuses bad arguments."""
+    """The measurement aid runs in both forms of the instruction, reports rates that the published fp64 matrix peak
+    bounds, and refuses bad arguments."""
     import ctypes
-    rate = B.sc_probe_fp64_matrix_rate(512, 500)
-    assert 1.0 < rate <= 78.6 * 1.05, rate
+    for shape in (16, 4):
+        rate = B.sc_probe_fp64_matrix_rate(512, 500, shape)
+        assert 1.0 < rate <= 78.6 * 1.05, (shape, rate)
     out = ctypes.c_double(0.0)
-    assert B.lib().sc_probe_fp64_matrix_rate(0, 10, ctypes.byref(out), 0) == B.SC_EDOMAIN
-    assert B.lib().sc_probe_fp64_matrix_rate(8, 0, ctypes.byref(out), 0) == B.SC_EDOMAIN
-    assert B.lib().sc_probe_fp64_matrix_rate(8, 8, None, 0) == B.SC_EINVAL
+    assert B.lib().sc_probe_fp64_matrix_rate(16, 0, 10, ctypes.byref(out), 0) == B.SC_EDOMAIN
+    assert B.lib().sc_probe_fp64_matrix_rate(16, 8, 0, ctypes.byref(out), 0) == B.SC_EDOMAIN
+    assert B.lib().sc_probe_fp64_matrix_rate(8, 8, 8, ctypes.byref(out), 0) == B.SC_EDOMAIN
+    assert B.lib().sc_probe_fp64_matrix_rate(16, 8, 8, None, 0) == B.SC_EINVAL
