@@ -314,6 +314,30 @@ def test_block_products_through_the_resident_form(B, monkeypatch):
     assert np.max(np.abs(results[0] - results[1])) <= 1e-9
 
 
+def test_single_precision_filter_steps_change_nothing_that_is_returned(B, monkeypatch):
+    """The one-launch start-block filter runs all steps but a double-precision tail in single precision.  The filter only
+    prepares a start block, so the returned pairs must meet the same bars with and without it, and the phases must
+    not need more block steps than a couple (the later steps damp what the rounding of the earlier ones adds)."""
+    cfg = wl.reduced(wl.CONFIGS[5], n=16000, components=64)
+    g, label, sigma = wl.build_config_graph(cfg, device="cuda")
+    rp, c, v, n = g
+    basis = components.null_space(rp, c, v)
+    k = basis.shape[1]
+    monkeypatch.setenv("SCEIG_FORCE_RESIDENT", "1")   # small graph: the cost model would leave the form out
+    runs = []
+    for tail in (None, "1000"):
+        if tail:
+            monkeypatch.setenv("SCEIG_FILTER_FP64_TAIL", tail)   # every step in double precision
+        lam, vec, code, stats = solve(B, g, k, 1e-9, block=32, m=k + 128)
+        assert code == B.SC_OK and stats["filter_steps"] > 0, stats
+        assert np.max(np.abs(lam)) <= 1e-9
+        assert compare.residual_norms(rp, c, v, lam, vec).max() <= 1e-8
+        assert np.max(compare.containment_defect(vec, basis)) <= 1e-7
+        assert compare.orthonormality_defect(vec) <= 1e-10
+        runs.append(stats)
+    assert runs[0]["block_steps"] <= runs[1]["block_steps"] + 2, (runs[0], runs[1])
+
+
 def test_filter_interval_with_a_wrong_spectrum_bottom(B, monkeypatch):
     """The start-block filters damp [estimate of the spectrum's bottom, a] instead of [-1, a].  Isolated eigenvalues at
     the bottom (the -1 of a bipartite component, here K_{3,4}: 7 of 12,007 nodes) are found by the first unfiltered
