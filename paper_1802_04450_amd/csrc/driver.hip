@@ -667,7 +667,7 @@ double* enqueue_cheb_filter(const int64_t* rowptr, const int32_t* col, const dou
                             const double* s, int64_t n, int64_t nnz, int b, int d, double a, double* z, double* buf1,
                             double* buf2, double* buf3, double avg_deg, const int32_t* longrows, int nlong,
                             const ResidentPlan* resident, hipStream_t st, KTimer* tm, double* direct = nullptr,
-                            int64_t direct_ld = 0, double lo = -1.0, int d32 = 0) {
+                            int64_t direct_ld = 0, double lo = -1.0, int d32 = 0, uint64_t rnd_key = 0, int use_rnd = 0) {
   // lo: lower end of the damped interval; -1 always holds (||S||_2 = 1), the solver passes its estimate of the
   // bottom of the spectrum when it has one
   KTimer none;
@@ -684,7 +684,7 @@ double* enqueue_cheb_filter(const int64_t* rowptr, const int32_t* col, const dou
     tm->begin(kFamSpmm);
     HIP_TRY(launch_cheb_resident(rowptr, col, val_scaled, z, out, ldo, b, d, 1.0 / e, 2.0 / e, c, resident->items.p,
                                  resident->nitems, resident->lds_bytes, resident->scol.p, resident->sval.p,
-                                 resident->slice_base.p, resident->slice_len.p, st, d32));
+                                 resident->slice_base.p, resident->slice_len.p, st, d32, rnd_key, use_rnd));
     const int64_t r0 = resident->rest_row0;
     if (r0 < n) {
       // the blocks without an item: the recurrence step by step on their rows alone (their iterates rotate through the
@@ -832,6 +832,7 @@ struct Solver {
   bool no_spectrum_bottom = std::getenv("SCEIG_NO_SPECTRUM_BOTTOM") != nullptr;
   bool no_tentative_step = std::getenv("SCEIG_NO_TENTATIVE_STEP") != nullptr;
   bool no_resident_product = std::getenv("SCEIG_NO_RESIDENT_PRODUCT") != nullptr;
+  bool no_random_inside = std::getenv("SCEIG_NO_RANDOM_INSIDE") != nullptr;
   // A start-block filter only prepares a block whose Ritz pairs the Lanczos step then tests in double precision.  In
   // its one-launch form all steps but the last filter_tail64 run in single precision (half the LDS traffic that bounds
   // the form): the later steps damp what the rounding of the earlier ones adds along the unwanted directions.
@@ -1117,7 +1118,9 @@ struct Solver {
   // by p(S) applied to it, p = Chebyshev polynomial of degree d of the interval [-1, a] mapped to [-1, 1]: what lies
   // in [-1, a] stays bounded by 1, what lies above a grows like cosh(d acosh(x)).  Only products and a three-term
   // recurrence: no reorthogonalization.  The caller orthogonalizes and orthonormalizes the result again.
-  void apply_start_filter(int d, double a) {
+  // rnd_key / use_rnd: the block to filter is random block rnd_key, which the one-launch form makes in its prologue
+  // (the caller has checked that this form takes every row); z is then not read
+  void apply_start_filter(int d, double a, uint64_t rnd_key = 0, int use_rnd = 0) {
     double* buf1 = rot.p;
     double* buf2 = rot.p + (size_t)n * b;
     double* buf3 = rot.p + 2 * (size_t)n * b;
@@ -1138,7 +1141,7 @@ struct Solver {
     }
     const double* res = enqueue_cheb_filter(rowptr, col, val, val_s.p, s.p, n, nnz, b, d, a, z.p, buf1, buf2, buf3,
                                             avg_deg, longrows.p, nlong, &resident, st, &timer, basis.p + nl, ld, filt_lo,
-                                            d32);
+                                            d32, rnd_key, use_rnd);
     stats.spmv_cols += (int64_t)d * b;
     stats.filter_steps += d;
     if (res) HIP_TRY(launch_copy_cols(res, b, 0, basis.p, ld, nl, b, n, st));
@@ -1306,7 +1309,12 @@ struct Solver {
       // drawn into the packed buffer directly: same numbers, one pass less
       const bool use_v0 = v0 && stats.phases == 1;
       const bool random_packed = filtered && late_projection && val_s.p && !use_v0;
-      if (random_packed) {
+      // ... and where the one-launch filter takes every row it makes those numbers itself: no pass to write them
+      const bool random_inside = random_packed && resident.usable && resident.rest_row0 >= n && !no_random_inside;
+      uint64_t rnd_key = 0;
+      if (random_inside) {
+        rnd_key = random_block_key(seed, stream_id++);
+      } else if (random_packed) {
         HIP_TRY(launch_random_block(z.p, n, b, 0, b, seed, stream_id++, st));
       } else {
         HIP_TRY(launch_random_block(basis.p, n, ld, nl, b, seed, stream_id++, st));
@@ -1321,7 +1329,7 @@ struct Solver {
         if (!late_projection)
           (void)enqueue_cgs2(basis.p, n, ld, nl, nl, b, nl, part.p, h1.p, hsum.p, nullptr, 0, nullptr, st, &timer);
         if (!random_packed) HIP_TRY(launch_pack_scaled(basis.p + nl, ld, zs(), n, b, z.p, st));
-        apply_start_filter(filt_d, filt_a);
+        apply_start_filter(filt_d, filt_a, rnd_key, random_inside ? 1 : 0);
         filt_d = 0;
       }
       // a block that went into the filter orthogonal to the locked vectors picked up along them since only what is of

@@ -125,10 +125,16 @@ hipError_t launch_block_extra_chunks(const int64_t* rowptr, const int32_t* start
 // no item is sliced).
 // d32 (0 <= d32 < d): the first d32 steps of the items with cl = 2 or 4 run in single precision (iterates and entries
 // rounded to float), the rest in double; sliced items take all steps in double.  0 gives the recurrence in double.
+// use_rnd != 0: x is not read; the operand is the random block of key rnd_key (random_block_key), entry by entry as
+// launch_random_block would have written it into a packed n x b buffer.
 hipError_t launch_cheb_resident(const int64_t* rowptr, const int32_t* col, const double* val, const double* x, double* y,
                                 int64_t ldy, int b, int d, double alpha_first, double alpha_rest, double shift, const int32_t* items,
                                 int nitems, size_t lds_bytes, const uint16_t* scol, const double* sval,
-                                const int64_t* slice_base, const int32_t* slice_len, hipStream_t st, int d32 = 0);
+                                const int64_t* slice_base, const int32_t* slice_len, hipStream_t st, int d32 = 0,
+                                uint64_t rnd_key = 0, int use_rnd = 0);
+// key of random block number `stream_id` under `seed`: entry i * b + t of the block launch_random_block writes is
+// 2 u - 1 with u the top 53 bits of mix(key + i * b + t)
+uint64_t random_block_key(uint64_t seed, uint64_t stream_id);
 // Sliced copy of diagonal blocks for the sliced form.  A slice is up to resident_slice_rows() consecutive rows of one
 // block: slice_row0 / slice_rows (device int32[nslices]) name its rows, slice_blk0 / slice_blk_rows its block.
 // sliced_copy_layout fills slice_len (longest row), slice_entries (int64[nslices + 1]: entries the slice takes in the

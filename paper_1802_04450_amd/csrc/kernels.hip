@@ -1836,6 +1836,14 @@ hipError_t launch_apply_rinv(double* basis, int64_t n, int64_t ld, int col0, int
   return hipGetLastError();
 }
 
+uint64_t random_block_key(uint64_t seed, uint64_t stream_id) {
+  uint64_t x = seed ^ (stream_id * 0xD1B54A32D192ED03ull);
+  x += 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+
 hipError_t launch_random_block(double* basis, int64_t n, int64_t ld, int col0, int b, uint64_t seed,
                                uint64_t stream_id, hipStream_t st) {
   hipLaunchKernelGGL(random_block_kernel, dim3((unsigned)ceil_div64(n * b, kThreads)), dim3(kThreads), 0, st, basis, n,

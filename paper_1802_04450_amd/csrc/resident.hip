@@ -60,6 +60,19 @@ __host__ __device__ inline size_t resident_lds_bytes(int nrows, int cl, int extr
           (size_t)2 * (nrows + 1) * sizeof(int32_t) + 15) / 16 * 16;
 }
 
+// Entry idx = i * b + t of a random start block (the same numbers as random_block_kernel writes: uniform in [-1, 1)
+// from the output function of splitmix64 applied to key + idx, key = mix of seed and block number made on the host).
+__device__ __forceinline__ uint64_t res_mix64(uint64_t x) {
+  x += 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+__device__ __forceinline__ double random_entry(uint64_t key, int64_t idx) {
+  const uint64_t h = res_mix64(key + (uint64_t)idx);
+  return 2.0 * ((double)(h >> 11) * (1.0 / 9007199254740992.0)) - 1.0;
+}
+
 template <int CTRL>
 __device__ __forceinline__ int dpp_int(int v) {
   return __builtin_amdgcn_mov_dpp(v, CTRL, 0xf, 0xf, true);
@@ -91,7 +104,7 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
                                               const double* __restrict__ val, const double* __restrict__ x,
                                               double* __restrict__ y, int64_t ldy, int b, int d, double alpha_first,
                                               double alpha_rest, double shift, int row0, int nr, int col0, int nx,
-                                              unsigned char* smem, int d32) {
+                                              unsigned char* smem, int d32, uint64_t rnd_key, int use_rnd) {
   constexpr int BS = 8 * CL;     // columns of the item
   constexpr int CH = kRK * CL;   // entries per chunk
   constexpr int G = kRT / CL;    // lane groups
@@ -115,7 +128,9 @@ __device__ __forceinline__ void resident_item(const int64_t* __restrict__ rowptr
   for (int r = tid; r <= nr; r += kRT) rpl[r] = (int)(rowptr[row0 + r] - ebase);
   for (int idx = tid; idx < nr * BS; idx += kRT) {
     const int r = idx / BS, t = idx - r * BS;
-    const double xv = x[(int64_t)(row0 + r) * b + col0 + t];
+    // the operand, or (use_rnd, uniform) the random start block's entry made on the spot instead of read
+    const int64_t gi = (int64_t)(row0 + r) * b + col0 + t;
+    const double xv = use_rnd ? random_entry(rnd_key, gi) : x[gi];
     if (d32 > 0) {  // uniform
       reinterpret_cast<float*>(bufa)[idx] = (float)xv;
       reinterpret_cast<float*>(bufb)[idx] = 0.0f;
@@ -381,7 +396,8 @@ __device__ __forceinline__ void resident_item_sliced(const uint16_t* __restrict_
                                                      const int32_t* __restrict__ slice_len,
                                                      const double* __restrict__ x, double* __restrict__ y, int64_t ldy, int b,
                                                      int d, double alpha_first, double alpha_rest, double shift,
-                                                     int row0, int nr, int col0, int slice0, unsigned char* smem) {
+                                                     int row0, int nr, int col0, int slice0, unsigned char* smem,
+                                                     uint64_t rnd_key, int use_rnd) {
   constexpr int BS = 8;  // columns of the item
   constexpr int RW = BS / 2;
   double* bufa = reinterpret_cast<double*>(smem);
@@ -391,7 +407,8 @@ __device__ __forceinline__ void resident_item_sliced(const uint16_t* __restrict_
   const int pcs[4] = {pc0, pc1, pc2, pc3};
   for (int idx = tid; idx < nr * BS; idx += kRT) {
     const int r = idx / BS, t = idx - r * BS;
-    bufa[idx] = x[(int64_t)(row0 + r) * b + col0 + t];
+    const int64_t gi = (int64_t)(row0 + r) * b + col0 + t;
+    bufa[idx] = use_rnd ? random_entry(rnd_key, gi) : x[gi];
     bufb[idx] = 0.0;
   }
   __syncthreads();
@@ -529,17 +546,18 @@ __global__ __launch_bounds__(kRT) void cheb_resident_kernel(const int64_t* __res
                                                             const uint16_t* __restrict__ scol,
                                                             const double* __restrict__ sval,
                                                             const int64_t* __restrict__ slice_base,
-                                                            const int32_t* __restrict__ slice_len, int d32) {
+                                                            const int32_t* __restrict__ slice_len, int d32,
+                                                            uint64_t rnd_key, int use_rnd) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int32_t* it = items + 4 * (int64_t)blockIdx.x;
   const int row0 = it[0], nr = it[1], col0 = it[2], cl = it[3] & 15, nx = it[3] >> 4;  // uniform over the workgroup
   if (cl == 4)
-    resident_item<4>(rowptr, col, val, x, y, ldy, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem, d32);
+    resident_item<4>(rowptr, col, val, x, y, ldy, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem, d32, rnd_key, use_rnd);
   else if (cl == 2)
-    resident_item<2>(rowptr, col, val, x, y, ldy, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem, d32);
+    resident_item<2>(rowptr, col, val, x, y, ldy, b, d, alpha_first, alpha_rest, shift, row0, nr, col0, nx, smem, d32, rnd_key, use_rnd);
   else if (cl == 1)  // sliced form: the item's last word carries its first slice instead of a chunk count
     resident_item_sliced(scol, sval, slice_base, slice_len, x, y, ldy, b, d, alpha_first, alpha_rest, shift, row0, nr, col0,
-                         nx, smem);
+                         nx, smem, rnd_key, use_rnd);
 }
 
 // ---- sliced copy of diagonal blocks ------------------------------------------------------------------------------------
@@ -771,14 +789,15 @@ hipError_t diagonal_blocks(const int64_t* rowptr, const int32_t* col, int64_t n,
 hipError_t launch_cheb_resident(const int64_t* rowptr, const int32_t* col, const double* val, const double* x, double* y,
                                 int64_t ldy, int b, int d, double alpha_first, double alpha_rest, double shift, const int32_t* items,
                                 int nitems, size_t lds_bytes, const uint16_t* scol, const double* sval,
-                                const int64_t* slice_base, const int32_t* slice_len, hipStream_t st, int d32) {
+                                const int64_t* slice_base, const int32_t* slice_len, hipStream_t st, int d32,
+                                uint64_t rnd_key, int use_rnd) {
   if (nitems <= 0 || d <= 0) return hipSuccess;
   if (d32 < 0 || d32 >= d) return hipErrorInvalidValue;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cheb_resident_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(cheb_resident_kernel, dim3((unsigned)nitems), dim3(kRT), lds_bytes, st, rowptr, col, val, x, y, ldy, b, d,
-                     alpha_first, alpha_rest, shift, items, scol, sval, slice_base, slice_len, d32);
+                     alpha_first, alpha_rest, shift, items, scol, sval, slice_base, slice_len, d32, rnd_key, use_rnd);
   return hipGetLastError();
 }
 
